@@ -1,0 +1,252 @@
+/*
+ * CPU oracle for the decentralized momentum updates -- TEST INFRASTRUCTURE.
+ *
+ * Plain, slow, fp64 loops that evaluate the paper's definitions one statement
+ * at a time.  Nothing here is shared with the GPU library: no header, no
+ * helper, no table.  Only tests, the smoke check and the benchmark's
+ * "cpu_baseline" leg may call it; the product path never does.
+ *
+ * Build with -ffp-contract=off so that every line below is evaluated as
+ * written (one rounding per operation, no fused multiply-add).
+ *
+ * Conventions: stacked arrays are row-major n x d (row i = node i, notation
+ * of the appendix "Preliminary"); a weight matrix W is a neighbour list in
+ * CSR form (row i lists the j with w_ij > 0, self included -- Sec.
+ * "Decentralized Momentum SGD", eq. (2) and the definition of N_i);
+ * a time-varying W is `period` such lists, iteration k using phase k mod period.
+ *
+ * Pins (tests marked "not gpu"): library momentum SGD for W = I, the DSGD
+ * compact form for beta = 0, the momentum-free second-order recursions of the
+ * appendix "Reformulation of DmSGD and DecentLaM", the alternative forms of
+ * the corrected gradient, node-average and zero-sum invariants, exact rational
+ * brute force on tiny cases, the fixed-point equations of the appendix
+ * "Limiting Bias of Decentralized Algorithms", automatic differentiation and
+ * finite differences for the least-squares gradient, hand-written neighbour
+ * tables for the topologies.
+ */
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_RING = 0, ORACLE_EXP_STATIC = 1, ORACLE_EXP_ONEPEER = 2 };
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Number of hop exponents of the exponential graphs: hops 2^0 .. 2^floor(log2(n-1))
+ * (appendix "Network topologies", exponential-graph item). */
+static int hop_count(int n)
+{
+    int tau = 0;
+    while (n > 1 && (1 << tau) <= n - 1) tau++;
+    return tau; /* 0 when n == 1 */
+}
+
+/* Append j to row (kept in first-occurrence order, no duplicates). */
+static int push_unique(int32_t* row, int len, int32_t j)
+{
+    for (int t = 0; t < len; ++t)
+        if (row[t] == j) return len;
+    row[len] = j;
+    return len + 1;
+}
+
+/* Neighbour set of node i in phase p, self first.
+ *   ring:              i, i-1, i+1 (mod n)               -- "Ring" item
+ *   static exponential: i, i+2^0, i+2^1, ... (mod n)     -- exponential-graph item
+ *   one-peer exponential: i, i+2^p (mod n)               -- one neighbour per iteration (Introduction)
+ * Reading: node i *receives from* the listed nodes. */
+static int neighbours(int kind, int n, int p, int i, int32_t* row)
+{
+    int len = 0;
+    len = push_unique(row, len, i);
+    if (kind == ORACLE_RING) {
+        len = push_unique(row, len, ((i - 1) % n + n) % n);
+        len = push_unique(row, len, (i + 1) % n);
+    } else if (kind == ORACLE_EXP_STATIC) {
+        int tau = hop_count(n);
+        for (int t = 0; t < tau; ++t) len = push_unique(row, len, (i + (1 << t)) % n);
+    } else if (kind == ORACLE_EXP_ONEPEER) {
+        if (n > 1) len = push_unique(row, len, (i + (1 << p)) % n);
+    }
+    return len;
+}
+
+/* Sizes first (row_ptr == NULL), then fill.  Weights are uniform over the
+ * neighbour set, 1/|N_i| evaluated in fp32: on a regular graph this is what the
+ * Metropolis-Hastings rule the paper cites gives.  row_ptr holds
+ * period*(n+1) absolute offsets into col_idx / w (phase-major). */
+int oracle_topology(int kind, int n, int32_t* period_out, int64_t* nnz_out,
+                    int32_t* row_ptr, int32_t* col_idx, float* w)
+{
+    if (n < 1 || kind < 0 || kind > 2) return -1;
+    int period = 1;
+    if (kind == ORACLE_EXP_ONEPEER && n > 1) period = hop_count(n);
+    int32_t* tmp = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n + 2));
+    if (!tmp) return -2;
+    int64_t nnz = 0;
+    for (int p = 0; p < period; ++p) {
+        for (int i = 0; i < n; ++i) {
+            int len = neighbours(kind, n, p, i, tmp);
+            if (row_ptr) {
+                row_ptr[p * (n + 1) + i] = (int32_t)nnz;
+                for (int t = 0; t < len; ++t) {
+                    col_idx[nnz + t] = tmp[t];
+                    w[nnz + t] = 1.0f / (float)len;
+                }
+            }
+            nnz += len;
+        }
+        if (row_ptr) row_ptr[p * (n + 1) + n] = (int32_t)nnz;
+    }
+    free(tmp);
+    *period_out = period;
+    *nnz_out = nnz;
+    return 0;
+}
+
+/* Partial averaging, eq. (3): out_i = sum_{j in N_i} w_ij in_j, terms added in
+ * list order.  `in` and `out` must not overlap. */
+static void partial_average(int n, int64_t d, const int32_t* row_ptr, const int32_t* col_idx,
+                            const float* w, const double* in, double* out)
+{
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < n; ++i) {
+        for (int64_t c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int32_t e = row_ptr[i]; e < row_ptr[i + 1]; ++e) {
+                double wij = (double)w[e];
+                acc = acc + wij * in[(int64_t)col_idx[e] * d + c];
+            }
+            out[(int64_t)i * d + c] = acc;
+        }
+    }
+}
+
+/* DSGD, eqs. (4)-(5): x^{k+1/2} = x - gamma g ; x^{k+1} = W x^{k+1/2}. */
+int oracle_dsgd_step(int n, int64_t d, int period, const int32_t* row_ptr, const int32_t* col_idx,
+                     const float* w, double gamma, int64_t k,
+                     const double* x, const double* g, double* x_out)
+{
+    const int32_t* rp = row_ptr + (k % period) * (n + 1);
+    double* half = (double*)malloc(sizeof(double) * (size_t)n * (size_t)(d > 0 ? d : 1));
+    if (!half) return -2;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < n; ++i)
+        for (int64_t c = 0; c < d; ++c) {
+            int64_t q = (int64_t)i * d + c;
+            half[q] = x[q] - gamma * g[q];
+        }
+    partial_average(n, d, rp, col_idx, w, half, x_out);
+    free(half);
+    return 0;
+}
+
+/* DmSGD, Algorithm 1:
+ *   m^{k+1} = beta m^k + g^k            (momentum update)
+ *   x^{k+1/2} = x^k - gamma m^{k+1}     (local model update)
+ *   x^{k+1} = sum_j w_ij x_j^{k+1/2}    (partial average)          */
+int oracle_dmsgd_step(int n, int64_t d, int period, const int32_t* row_ptr, const int32_t* col_idx,
+                      const float* w, double gamma, double beta, int64_t k,
+                      const double* x, const double* m, const double* g,
+                      double* x_out, double* m_out)
+{
+    const int32_t* rp = row_ptr + (k % period) * (n + 1);
+    double* half = (double*)malloc(sizeof(double) * (size_t)n * (size_t)(d > 0 ? d : 1));
+    if (!half) return -2;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < n; ++i)
+        for (int64_t c = 0; c < d; ++c) {
+            int64_t q = (int64_t)i * d + c;
+            double m_new = beta * m[q] + g[q];
+            m_out[q] = m_new;
+            half[q] = x[q] - gamma * m_new;
+        }
+    partial_average(n, d, rp, col_idx, w, half, x_out);
+    free(half);
+    return 0;
+}
+
+/* DecentLaM, Algorithm 2 with the corrected gradient of the equation that
+ * follows the "Efficient implementation" paragraph:
+ *   gt_i  = (1/gamma) x_i - (1/gamma) sum_j w_ij (x_j - gamma g_j)
+ *   m^{k+1} = beta m^k + gt            (momentum update)
+ *   x^{k+1} = x^k - gamma m^{k+1}      (local model update)
+ * Reading: the two 1/gamma terms are evaluated as one division of the
+ * difference, (x_i - z_i) / gamma. */
+int oracle_decentlam_step(int n, int64_t d, int period, const int32_t* row_ptr,
+                          const int32_t* col_idx, const float* w, double gamma, double beta,
+                          int64_t k, const double* x, const double* m, const double* g,
+                          double* x_out, double* m_out)
+{
+    const int32_t* rp = row_ptr + (k % period) * (n + 1);
+    size_t cnt = (size_t)n * (size_t)(d > 0 ? d : 1);
+    double* local = (double*)malloc(sizeof(double) * cnt);
+    double* z = (double*)malloc(sizeof(double) * cnt);
+    if (!local || !z) { free(local); free(z); return -2; }
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < n; ++i)
+        for (int64_t c = 0; c < d; ++c) {
+            int64_t q = (int64_t)i * d + c;
+            local[q] = x[q] - gamma * g[q];
+        }
+    partial_average(n, d, rp, col_idx, w, local, z);
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < n; ++i)
+        for (int64_t c = 0; c < d; ++c) {
+            int64_t q = (int64_t)i * d + c;
+            double gt = (x[q] - z[q]) / gamma;
+            double m_new = beta * m[q] + gt;
+            m_out[q] = m_new;
+            x_out[q] = x[q] - gamma * m_new;
+        }
+    free(local);
+    free(z);
+    return 0;
+}
+
+/* Least-squares gradient of f_i(x) = (scale/2) ||A_i x - y_i||^2 (appendix
+ * "Experimental setting for linear regression": grad f_i = A_i^T (A_i x - b_i),
+ * scale = 1 there):
+ *   res_i = A_i x_i - y_i ; g_i = scale A_i^T res_i ; loss_i = (scale/2) ||res_i||^2
+ * A is n x b x d, y is n x b (fp32 data), x is n x d. */
+int oracle_lsq_grad(int n, int b, int64_t d, const float* A, const float* y, const double* x,
+                    double scale, double* g_out, double* loss_out)
+{
+    double* res = (double*)malloc(sizeof(double) * (size_t)n * (size_t)b);
+    if (!res) return -2;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int i = 0; i < n; ++i)
+        for (int r = 0; r < b; ++r) {
+            const float* a = A + ((int64_t)i * b + r) * d;
+            double acc = 0.0;
+            for (int64_t c = 0; c < d; ++c) acc = acc + (double)a[c] * x[(int64_t)i * d + c];
+            res[(int64_t)i * b + r] = acc - (double)y[(int64_t)i * b + r];
+        }
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < n; ++i) {
+        double* gi = g_out + (int64_t)i * d;
+        for (int64_t c = 0; c < d; ++c) gi[c] = 0.0;
+        for (int r = 0; r < b; ++r) {
+            const float* a = A + ((int64_t)i * b + r) * d;
+            double rr = res[(int64_t)i * b + r];
+            for (int64_t c = 0; c < d; ++c) gi[c] = gi[c] + (double)a[c] * rr;
+        }
+        double sq = 0.0;
+        for (int r = 0; r < b; ++r) sq = sq + res[(int64_t)i * b + r] * res[(int64_t)i * b + r];
+        for (int64_t c = 0; c < d; ++c) gi[c] = scale * gi[c];
+        if (loss_out) loss_out[i] = 0.5 * scale * sq;
+    }
+    free(res);
+    return 0;
+}
