@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the DecentLaM hot path on one MI355X.
+
+A "step" is one pass of the fused decentralized update (`decentlam_step`:
+partial averaging + bias-corrected momentum + parameter step) over all n
+simulated nodes' stacked replicas, inputs resident in HBM.  The default
+workload is the headline one: n = 32 nodes, static exponential graph, d = 25.6 M
+fp32 parameters per node (synthetic N(0,1) replicas and gradients).
+
+Prints ONE JSON line.  `value` is the achieved algorithmic HBM rate of the step
+(20 bytes per node-element: read x, m, g; write x, m) over wall time of K steps;
+`steps_per_s` is the same measurement in steps.  `roofline` prices the step
+kernel against the 8 TB/s HBM peak from HIP-event time over the same K launches;
+`cpu_baseline` times the CPU oracle on a bounded column sample of the same
+workload (the work is exactly linear in d).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+BYTES_PER_ELEMENT = 20         # read x, m, g + write x, m, fp32
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), keyed by
+# (workload, algo); None until measured for that kernel.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def ensure_built():
+    from paper_2104_11981_amd import build as hip_build
+
+    if not os.path.exists(hip_build.LIB):
+        hip_build.build()
+
+
+def cpu_baseline(w, kind, algo, target_seconds=12.0):
+    """Time the oracle as it stands on a column sample of the same workload."""
+    import numpy as np
+
+    import oracle
+
+    oracle.build()
+    topo = oracle.topology(kind, w.n)
+    d_s = 1_280_000 if w.d >= 1_280_000 else w.d
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((w.n, d_s))
+    m = np.zeros_like(x)
+    g = rng.standard_normal((w.n, d_s))
+    gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
+    fn = oracle.STEP[algo]
+    fn(x, m, g, topo, gamma, beta, 0)                      # warm-up (page faults, thread pool)
+    t0 = time.perf_counter()
+    steps = 0
+    while True:
+        x, m = fn(x, m, g, topo, gamma, beta, steps)
+        steps += 1
+        el = time.perf_counter() - t0
+        if el >= target_seconds or steps >= 200:
+            break
+    per_step = el / steps
+    gbs = BYTES_PER_ELEMENT * w.n * d_s / per_step / 1e9
+    return {
+        "value": round(gbs, 3), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"{algo} oracle (fp64 C loops, OpenMP), n={w.n}, same topology, d={d_s} columns "
+                  f"({d_s / w.d:.3f} of the workload; cost is linear in d), {steps} steps, "
+                  f"{per_step * 1e3:.1f} ms/step; full-size equivalent "
+                  f"{1.0 / (per_step * w.d / d_s):.4f} steps/s",
+        "steps_per_s_full_size_equiv": 1.0 / (per_step * w.d / d_s),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3_exp32", choices=["c3_exp32", "c4_ring16_ragged"])
+    ap.add_argument("--algo", default="decentlam", choices=["decentlam", "dmsgd"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build simulates all n nodes on ONE GPU (columns of the update are "
+                 "independent, so sharding d over GPUs needs no exchange); run with --gpus 1")
+    if int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: single-process benchmark; do not launch it under torch.distributed.run")
+
+    ensure_built()
+    import numpy as np
+    import torch
+
+    import paper_2104_11981_amd as P
+    import workloads
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    torch.cuda.set_device(0)
+    w = workloads.get(args.workload)
+    d = workloads.generate.dim(w)
+    kind = w.topo
+    topo = P.topology_build(kind, w.n)
+    gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
+    step = getattr(P, args.algo + "_step")
+
+    x = workloads.device_x0(w, "cuda")
+    m = torch.zeros_like(x)
+    g = torch.empty_like(x)
+    workloads.device_grad(w, 0, g)
+    torch.cuda.synchronize()
+
+    for k in range(args.warmup):
+        step(x, m, g, topo, gamma, beta, k)
+    torch.cuda.synchronize()
+
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for k in range(args.steps):
+        step(x, m, g, topo, gamma, beta, args.warmup + k)
+    ev1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    wall_ms = (t1 - t0) * 1e3 / args.steps
+    kern_ms = ev0.elapsed_time(ev1) / args.steps
+    bytes_per_step = BYTES_PER_ELEMENT * w.n * d
+    value = bytes_per_step / (wall_ms * 1e-3) / 1e9
+    achieved = bytes_per_step / (kern_ms * 1e-3) / 1e9
+    assert bool(torch.isfinite(x[:, :1024]).all()), "state overflowed during the timed run"
+
+    out = {
+        "metric": "DecentLaM step: achieved HBM GB/s & steps/s at n=32 nodes x d=25.6M fp32"
+        if (args.workload, args.algo) == ("c3_exp32", "decentlam")
+        else f"{args.algo} step: achieved HBM GB/s & steps/s ({w.name})",
+        "value": round(value, 2), "unit": "GB/s",
+        "steps_per_s": round(1e3 / wall_ms, 2),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": w.name, "algo": args.algo, "n": w.n, "d": d,
+                   "topology": {0: "ring", 1: "exp_static", 2: "exp_onepeer"}[kind],
+                   "deg": int(topo.row_ptr[1] - topo.row_ptr[0]), "gamma": w.gamma, "beta": w.beta,
+                   "storage": "fp32", "bytes_per_node_element": BYTES_PER_ELEMENT},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.algo)),
+                     "kernel": "k_step", "kernel_ms": round(kern_ms, 4),
+                     "algorithmic_bytes_per_launch": bytes_per_step},
+    }
+    del x, m, g
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, kind, args.algo)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,142 @@
+/*
+ * decentlam.h -- C ABI of the MI355X (gfx950) library for the decentralized
+ * momentum updates of "DecentLaM: Decentralized Momentum SGD for Large-batch
+ * Deep Training" (arXiv 2104.11981).
+ *
+ * One GPU simulates all n nodes.  The stacked arrays of the paper's appendix
+ * "Preliminary" (x, m, gradient: n x d, row i = node i) live in device memory as
+ * row-major fp32 with a row stride `ld >= d` (in elements).  A weight matrix W
+ * (Sec. "Decentralized Momentum SGD", eq. (2)) is a neighbour list in CSR form
+ * held in HOST memory: row i lists the j with w_ij > 0, i itself included.  A
+ * time-varying W is `period` such lists stored phase after phase; iteration k
+ * uses phase k mod period.
+ *
+ * Common rules
+ *  - Every function returns DL_OK (0) or a negative dl_status; nothing aborts,
+ *    prints or throws.  dl_last_error() gives a thread-local description of the
+ *    last failure on the calling thread.
+ *  - The caller owns every buffer.  The library allocates no device memory and
+ *    keeps no state between calls.
+ *  - Device work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream) and the call returns without synchronising.  Host
+ *    arrays (the topology) are consumed before the call returns.
+ *  - Arithmetic: inputs are promoted to fp64 in registers, every statement of
+ *    the algorithm is evaluated in fp64, and each output element is rounded to
+ *    fp32 once when stored.
+ */
+#ifndef DECENTLAM_H
+#define DECENTLAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DL_OK = 0,
+    DL_EINVAL = -1, /* bad scalar/pointer argument                                  */
+    DL_ETOPO = -2,  /* neighbour list malformed or beyond DL_MAX_NODES / DL_MAX_NNZ */
+    DL_ECAP = -3,   /* an output or workspace capacity is too small                 */
+    DL_EHIP = -4,   /* a HIP runtime call failed (text in dl_last_error)            */
+    DL_EALIAS = -5  /* x, m, g (or A, y, x, g) overlap                              */
+} dl_status;
+
+typedef enum {
+    DL_TOPO_RING = 0,        /* N_i = {i, i-1, i+1}                    (appendix "Network topologies") */
+    DL_TOPO_EXP_STATIC = 1,  /* N_i = {i} U {i + 2^t}, t = 0..tau-1    (exponential graph, directed)   */
+    DL_TOPO_EXP_ONEPEER = 2  /* phase p: N_i = {i, i + 2^p}, period tau (one-peer exponential graph)   */
+} dl_topo_kind;             /* tau = floor(log2(n-1)) + 1; all indices mod n */
+
+/* properties reported by topology_build (every phase has the property) */
+#define DL_FLAG_ROW_STOCHASTIC 1u /* |sum_j w_ij - 1| <= 1e-6 for all i  (Assumption A.3: W 1 = 1) */
+#define DL_FLAG_COL_STOCHASTIC 2u /* |sum_i w_ij - 1| <= 1e-6 for all j                            */
+#define DL_FLAG_SYMMETRIC 4u      /* w_ij == w_ji                         (Assumption A.3)         */
+
+/* limits of the step kernels: the phase's neighbour list travels in the kernel arguments */
+#define DL_MAX_NODES 256
+#define DL_MAX_NNZ 512 /* entries per phase */
+
+/*
+ * topology_build -- neighbour lists and weights of the paper's topologies
+ * (appendix "Network topologies"; one-peer graph: Introduction).
+ *
+ * Host-only, integer work.  Row order: self first, then ring: i-1, i+1;
+ * exponential: ascending hop.  Duplicates (tiny n) are dropped keeping the first
+ * occurrence.  Weights are uniform, (float)1 / (float)|N_i| -- what the
+ * Metropolis-Hastings rule the paper cites yields on these regular graphs.
+ *
+ *   row_ptr  [out] period*(n+1) absolute offsets into col_idx / w, phase-major.
+ *                  Pass NULL (with col_idx = w = NULL) to query sizes only.
+ *   col_idx, w [out] nnz_out entries each.
+ *   row_ptr_cap, nnz_cap  capacities in elements.
+ *   period_out, nnz_out, flags_out [out] always written on DL_OK and DL_ECAP.
+ * Errors: DL_EINVAL (n < 1, unknown kind, NULL out pointers), DL_ECAP.
+ */
+int topology_build(int kind, int32_t n,
+                   int32_t* row_ptr, int64_t row_ptr_cap,
+                   int32_t* col_idx, float* w, int64_t nnz_cap,
+                   int32_t* period_out, int64_t* nnz_out, uint32_t* flags_out);
+
+/*
+ * decentlam_step -- one iteration of Algorithm 2 (DecentLaM) for all nodes:
+ *     z_i  = sum_{j in N_i} w_ij (x_j - gamma g_j)          partial averaging, eq. (3)
+ *     gt_i = (x_i - z_i) / gamma                             corrected gradient (equation after
+ *                                                            the "Efficient implementation" paragraph)
+ *     m_i <- beta m_i + gt_i ;  x_i <- x_i - gamma m_i       momentum and model update
+ * fused into one pass that reads x, m, g once and writes x, m once (20 bytes
+ * per node-element).
+ *
+ *   x, m   [in,out] device, n x d fp32, row stride ld; updated in place.
+ *   g      [in]     device, same shape and stride; the stochastic gradients.
+ *   row_ptr, col_idx, w, period  [in] host; W as described above.  Row sums must
+ *                   be 1 within 1e-6; weights finite and > 0; no duplicate j in a row.
+ *   gamma > 0 finite; 0 <= beta < 1; k >= 0 selects phase k mod period.
+ *   The caller zeroes m before iteration 0 (Algorithm 2, initialisation).
+ * d == 0 is a successful no-op.  Any alignment and any ld >= d are accepted
+ * (unaligned heads/tails fall back to narrower loads).
+ * Errors: DL_EINVAL, DL_ETOPO, DL_EALIAS, DL_EHIP.
+ */
+int decentlam_step(float* x, float* m, const float* g,
+                   int32_t n, int64_t d, int64_t ld,
+                   const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                   float gamma, float beta, int64_t k, void* stream);
+
+/*
+ * dmsgd_step -- one iteration of Algorithm 1 (DmSGD), same arguments:
+ *     m_i <- beta m_i + g_i ;  h_i = x_i - gamma m_i ;  x_i <- sum_{j in N_i} w_ij h_j
+ */
+int dmsgd_step(float* x, float* m, const float* g,
+               int32_t n, int64_t d, int64_t ld,
+               const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+               float gamma, float beta, int64_t k, void* stream);
+
+/*
+ * local_grad_lsq -- per-node least-squares gradient (appendix "Experimental
+ * setting for linear regression"): for f_i(x) = (scale/2) ||A_i x - y_i||^2,
+ *     res_i = A_i x_i - y_i ;  g_i = scale * A_i^T res_i ;  loss_i = (scale/2) ||res_i||^2
+ *
+ *   A  [in] device, n x b x d fp32: element (i, r, c) at A[(i*b + r)*ldA + c], ldA >= d.
+ *   y  [in] device, n x b fp32, contiguous.
+ *   x  [in] device, n x d fp32, row stride ld.     g [out] device, n x d fp32, row stride ld.
+ *   loss [out] device, n fp32, or NULL.
+ *   workspace [scratch] device, at least local_grad_lsq_workspace(n, b, d) bytes, 16-byte aligned;
+ *             contents are undefined before and after the call.
+ * Deterministic: partial sums are combined in a fixed order.
+ * Errors: DL_EINVAL (NULL, n < 1, b < 1, d < 0, ldA < d, ld < d, scale not finite),
+ *         DL_ECAP (workspace too small), DL_EALIAS (g overlaps an input), DL_EHIP.
+ */
+size_t local_grad_lsq_workspace(int32_t n, int32_t b, int64_t d);
+int local_grad_lsq(const float* A, const float* y, const float* x,
+                   float* g, float* loss,
+                   int32_t n, int32_t b, int64_t d, int64_t ldA, int64_t ld,
+                   float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Description of the last failure on the calling thread ("" if none). Never NULL. */
+const char* dl_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DECENTLAM_H */

@@ -1,0 +1,178 @@
+"""ctypes binding of libdecentlam.so: argument marshalling only.
+
+Every function has the name and meaning of its C entry point (see
+include/decentlam.h).  Device arrays are torch tensors used purely as handles to
+HBM (`data_ptr()`, strides) and the launch stream is torch's current stream.
+There is no fallback: if the shared library is missing the import of this
+module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+# torch first: it ships its own HIP runtime (same soname as the system one).  Loading the
+# library before torch would pull in a second runtime copy, and a process with two HIP
+# runtimes has no usable device in the second.  With torch loaded, the dynamic loader
+# resolves libdecentlam.so's dependency to the runtime torch already mapped.
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdecentlam.so")
+
+DL_OK, DL_EINVAL, DL_ETOPO, DL_ECAP, DL_EHIP, DL_EALIAS = 0, -1, -2, -3, -4, -5
+DL_TOPO_RING, DL_TOPO_EXP_STATIC, DL_TOPO_EXP_ONEPEER = 0, 1, 2
+DL_FLAG_ROW_STOCHASTIC, DL_FLAG_COL_STOCHASTIC, DL_FLAG_SYMMETRIC = 1, 2, 4
+DL_MAX_NODES, DL_MAX_NNZ = 256, 512
+
+EXPORTS = ("topology_build", "decentlam_step", "dmsgd_step", "local_grad_lsq",
+           "local_grad_lsq_workspace", "dl_last_error")
+
+
+class DecentLamError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"dl_status {status}: {message}")
+        self.status = status
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_2104_11981_amd.build). "
+            "This package has no CPU or PyTorch fallback.")
+    lib = ctypes.CDLL(LIB_PATH)
+    i32p, f32p = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)
+    vp = ctypes.c_void_p
+    lib.topology_build.restype = ctypes.c_int
+    lib.topology_build.argtypes = [ctypes.c_int, ctypes.c_int32, i32p, ctypes.c_int64, i32p, f32p,
+                                   ctypes.c_int64, i32p, ctypes.POINTER(ctypes.c_int64),
+                                   ctypes.POINTER(ctypes.c_uint32)]
+    step = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, i32p, f32p,
+            ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_int64, vp]
+    for name in ("decentlam_step", "dmsgd_step"):
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = step
+    lib.local_grad_lsq_workspace.restype = ctypes.c_size_t
+    lib.local_grad_lsq_workspace.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64]
+    lib.local_grad_lsq.restype = ctypes.c_int
+    lib.local_grad_lsq.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
+                                   ctypes.c_int64, ctypes.c_int64, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.dl_last_error.restype = ctypes.c_char_p
+    lib.dl_last_error.argtypes = []
+    return lib
+
+
+_lib = _load()
+
+
+def last_error() -> str:
+    return _lib.dl_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != DL_OK:
+        raise DecentLamError(rc, last_error())
+
+
+@dataclass
+class Topology:
+    """Host-side CSR neighbour lists, exactly the arrays the C ABI takes."""
+    n: int
+    period: int
+    row_ptr: np.ndarray   # int32 [period*(n+1)]
+    col_idx: np.ndarray   # int32 [nnz]
+    w: np.ndarray         # float32 [nnz]
+    flags: int = 0
+
+    def _args(self):
+        return (self.row_ptr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                self.col_idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                self.w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+                self.period)
+
+
+def topology_build(kind: int, n: int) -> Topology:
+    period, nnz, flags = ctypes.c_int32(0), ctypes.c_int64(0), ctypes.c_uint32(0)
+    _check(_lib.topology_build(kind, n, None, 0, None, None, 0, ctypes.byref(period),
+                               ctypes.byref(nnz), ctypes.byref(flags)))
+    row_ptr = np.zeros(period.value * (n + 1), dtype=np.int32)
+    col_idx = np.zeros(nnz.value, dtype=np.int32)
+    w = np.zeros(nnz.value, dtype=np.float32)
+    _check(_lib.topology_build(kind, n, row_ptr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                               row_ptr.size, col_idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                               w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), col_idx.size,
+                               ctypes.byref(period), ctypes.byref(nnz), ctypes.byref(flags)))
+    return Topology(n, period.value, row_ptr, col_idx, w, flags.value)
+
+
+def make_topology(n: int, row_ptr, col_idx, w, period: int = 1) -> Topology:
+    """Wrap caller-supplied CSR arrays (validated by the step functions)."""
+    return Topology(n, period, np.ascontiguousarray(row_ptr, np.int32),
+                    np.ascontiguousarray(col_idx, np.int32), np.ascontiguousarray(w, np.float32))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _matrix_args(t, name):
+    if t.dtype != torch.float32 or not t.is_cuda or t.dim() != 2:
+        raise TypeError(f"{name}: need a 2-D float32 device tensor")
+    if t.shape[1] > 0 and t.stride(1) != 1:
+        raise TypeError(f"{name}: columns must be contiguous")
+    return t.data_ptr(), t.shape[0], t.shape[1], (t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1]))
+
+
+def _step(fn, x, m, g, topo: Topology, gamma: float, beta: float, k: int, stream):
+    px, n, d, ld = _matrix_args(x, "x")
+    pm, nm, dm, ldm = _matrix_args(m, "m")
+    pg, ng, dg, ldg = _matrix_args(g, "g")
+    if (nm, dm, ldm) != (n, d, ld) or (ng, dg, ldg) != (n, d, ld):
+        raise TypeError("x, m and g must share shape and row stride")
+    if topo.n != n:
+        raise DecentLamError(DL_ETOPO, f"topology has {topo.n} nodes, arrays have {n} rows")
+    _check(fn(px, pm, pg, n, d, ld, *topo._args(), gamma, beta, k,
+              _stream() if stream is None else stream))
+
+
+def decentlam_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
+    """One DecentLaM iteration in place on device tensors x, m (n x d fp32), asynchronous."""
+    _step(_lib.decentlam_step, x, m, g, topo, gamma, beta, k, stream)
+
+
+def dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
+    """One DmSGD iteration in place on device tensors x, m (n x d fp32), asynchronous."""
+    _step(_lib.dmsgd_step, x, m, g, topo, gamma, beta, k, stream)
+
+
+def local_grad_lsq_workspace(n: int, b: int, d: int) -> int:
+    return int(_lib.local_grad_lsq_workspace(n, b, d))
+
+
+def local_grad_lsq(A, y, x, g, loss=None, scale: float = 1.0, workspace=None, stream=None):
+    """g_i = scale * A_i^T (A_i x_i - y_i) on device tensors; `workspace` is a uint8 device tensor
+    of at least local_grad_lsq_workspace(n, b, d) bytes."""
+    if A.dtype != torch.float32 or A.dim() != 3 or not A.is_cuda or A.stride(2) != 1:
+        raise TypeError("A: need a 3-D float32 device tensor with contiguous last axis")
+    n, b, d = A.shape
+    if b > 1 and n > 1 and A.stride(0) != b * A.stride(1):
+        raise TypeError("A: node stride must be b * row stride")
+    ldA = A.stride(1) if b > 1 else max(A.stride(1), d)
+    if y.dtype != torch.float32 or tuple(y.shape) != (n, b) or not y.is_contiguous() or not y.is_cuda:
+        raise TypeError("y: need a contiguous n x b float32 device tensor")
+    px, nx, dx, ld = _matrix_args(x, "x")
+    pg, ng, dg, ldg = _matrix_args(g, "g")
+    if (nx, dx) != (n, d) or (ng, dg, ldg) != (n, d, ld):
+        raise TypeError("x and g must be n x d with the same row stride")
+    pl = 0
+    if loss is not None:
+        if loss.dtype != torch.float32 or tuple(loss.shape) != (n,) or not loss.is_contiguous() or not loss.is_cuda:
+            raise TypeError("loss: need a contiguous float32 device tensor of n elements")
+        pl = loss.data_ptr()
+    if workspace is None:
+        raise TypeError("workspace: pass a uint8 device tensor (size from local_grad_lsq_workspace)")
+    _check(_lib.local_grad_lsq(A.data_ptr(), y.data_ptr(), px, pg, pl, n, b, d, ldA, ld, scale,
+                               workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                               _stream() if stream is None else stream))

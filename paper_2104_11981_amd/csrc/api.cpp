@@ -1,0 +1,201 @@
+// Host boundary: argument validation, error reporting, packing of one phase of W
+// into kernel arguments.  Every exported function returns a dl_status.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "internal.hpp"
+
+namespace dl {
+
+namespace {
+thread_local char g_error[512] = "";
+}
+
+void clear_error() { g_error[0] = '\0'; }
+
+int set_error(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_hip(hipError_t e, const char* what) {
+    if (e == hipSuccess) return DL_OK;
+    return set_error(DL_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+namespace {
+
+// Byte range [lo, hi) touched by an n x d array with row stride ld.
+struct Span {
+    uintptr_t lo, hi;
+};
+Span span_of(const void* p, int64_t rows, int64_t cols, int64_t ld) {
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(p);
+    if (rows <= 0 || cols <= 0) return {lo, lo};
+    return {lo, lo + static_cast<uintptr_t>(((rows - 1) * ld + cols) * 4)};
+}
+bool overlap(Span a, Span b) { return a.lo < b.hi && b.lo < a.hi; }
+
+// Validate phase `p` of the caller's CSR and copy it into kernel-argument form.
+int pack_phase(const char* fn, int32_t n, const int32_t* row_ptr, const int32_t* col_idx,
+               const float* w, int32_t p, PhaseArgs* out) {
+    if (n > DL_MAX_NODES)
+        return set_error(DL_ETOPO, "%s: n = %d exceeds DL_MAX_NODES = %d", fn, n, DL_MAX_NODES);
+    const int32_t* rp = row_ptr + static_cast<int64_t>(p) * (n + 1);
+    const int64_t base = rp[0];
+    const int64_t nnz = static_cast<int64_t>(rp[n]) - base;
+    if (base < 0 || nnz < n)
+        return set_error(DL_ETOPO, "%s: phase %d: row_ptr not monotone or a row is empty", fn, p);
+    if (nnz > DL_MAX_NNZ)
+        return set_error(DL_ETOPO, "%s: phase %d has %lld entries, limit DL_MAX_NNZ = %d", fn, p,
+                         static_cast<long long>(nnz), DL_MAX_NNZ);
+    out->n = n;
+    int32_t last_seen[DL_MAX_NODES];
+    for (int32_t j = 0; j < n; ++j) last_seen[j] = -1;
+    for (int32_t i = 0; i < n; ++i) {
+        const int64_t b = rp[i], e = rp[i + 1];
+        if (e <= b)
+            return set_error(DL_ETOPO, "%s: phase %d row %d is empty or row_ptr decreases", fn, p, i);
+        out->row_ptr[i] = static_cast<uint16_t>(b - base);
+        double sum = 0.0;
+        for (int64_t q = b; q < e; ++q) {
+            const int32_t j = col_idx[q];
+            const float wij = w[q];
+            if (j < 0 || j >= n)
+                return set_error(DL_ETOPO, "%s: phase %d row %d: neighbour index %d outside [0, %d)",
+                                 fn, p, i, j, n);
+            if (last_seen[j] == i)
+                return set_error(DL_ETOPO, "%s: phase %d row %d lists neighbour %d twice", fn, p, i, j);
+            last_seen[j] = i;
+            if (!std::isfinite(wij) || !(wij > 0.0f))
+                return set_error(DL_ETOPO, "%s: phase %d: w[%d,%d] = %g must be finite and > 0", fn,
+                                 p, i, j, static_cast<double>(wij));
+            sum += static_cast<double>(wij);
+            out->col[q - base] = static_cast<uint8_t>(j);
+            out->w[q - base] = wij;
+        }
+        if (std::fabs(sum - 1.0) > 1e-6)
+            return set_error(DL_ETOPO, "%s: phase %d row %d sums to %.9g, not 1", fn, p, i, sum);
+    }
+    out->row_ptr[n] = static_cast<uint16_t>(nnz);
+    return DL_OK;
+}
+
+int step_entry(const char* fn, Algo algo, float* x, float* m, const float* g, int32_t n, int64_t d,
+               int64_t ld, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
+               int32_t period, float gamma, float beta, int64_t k, void* stream) {
+    clear_error();
+    if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
+    if (d < 0) return set_error(DL_EINVAL, "%s: d = %lld, need d >= 0", fn, static_cast<long long>(d));
+    if (ld < d)
+        return set_error(DL_EINVAL, "%s: ld = %lld < d = %lld", fn, static_cast<long long>(ld),
+                         static_cast<long long>(d));
+    if (!std::isfinite(gamma) || !(gamma > 0.0f))
+        return set_error(DL_EINVAL, "%s: gamma = %g must be finite and > 0", fn, static_cast<double>(gamma));
+    if (!(beta >= 0.0f && beta < 1.0f))
+        return set_error(DL_EINVAL, "%s: beta = %g must lie in [0, 1)", fn, static_cast<double>(beta));
+    if (k < 0) return set_error(DL_EINVAL, "%s: k = %lld, need k >= 0", fn, static_cast<long long>(k));
+    if (period < 1) return set_error(DL_EINVAL, "%s: period = %d, need period >= 1", fn, period);
+    if (!row_ptr || !col_idx || !w)
+        return set_error(DL_EINVAL, "%s: row_ptr, col_idx and w must not be NULL", fn);
+
+    PhaseArgs topo;
+    std::memset(&topo, 0, sizeof(topo));
+    if (int rc = pack_phase(fn, n, row_ptr, col_idx, w, static_cast<int32_t>(k % period), &topo)) return rc;
+
+    if (d == 0) return DL_OK;
+    if (!x || !m || !g) return set_error(DL_EINVAL, "%s: x, m and g must not be NULL", fn);
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(g)) & 3u)
+        return set_error(DL_EINVAL, "%s: x, m and g must be 4-byte aligned", fn);
+    const Span sx = span_of(x, n, d, ld), sm = span_of(m, n, d, ld), sg = span_of(g, n, d, ld);
+    // Rows of different arrays may interleave when ld > d (views of one padded buffer); what
+    // must not happen is that the arrays share elements.  Whole-span overlap is only an error
+    // if the arrays are not column-disjoint views with the same stride.
+    auto shares = [&](const void* a, Span sa, const void* b2, Span sb) {
+        if (!overlap(sa, sb)) return false;
+        const intptr_t delta = (reinterpret_cast<intptr_t>(a) - reinterpret_cast<intptr_t>(b2)) / 4;
+        const int64_t off = ((delta % ld) + ld) % ld;  // column offset between the two views
+        return !(off >= d && ld - off >= d);
+    };
+    if (shares(x, sx, m, sm) || shares(x, sx, g, sg) || shares(m, sm, g, sg))
+        return set_error(DL_EALIAS, "%s: x, m and g must not overlap", fn);
+
+    return launch_step(algo, x, m, g, n, d, ld, topo, gamma, beta, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+}  // namespace dl
+
+extern "C" {
+
+int decentlam_step(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
+                   const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                   float gamma, float beta, int64_t k, void* stream) {
+    return dl::step_entry("decentlam_step", dl::ALGO_DECENTLAM, x, m, g, n, d, ld, row_ptr, col_idx, w,
+                          period, gamma, beta, k, stream);
+}
+
+int dmsgd_step(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
+               const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+               float gamma, float beta, int64_t k, void* stream) {
+    return dl::step_entry("dmsgd_step", dl::ALGO_DMSGD, x, m, g, n, d, ld, row_ptr, col_idx, w, period,
+                          gamma, beta, k, stream);
+}
+
+size_t local_grad_lsq_workspace(int32_t n, int32_t b, int64_t d) {
+    if (n < 1 || b < 1 || d < 0) return 0;
+    return dl::lsq_workspace_bytes(n, b, d);
+}
+
+int local_grad_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
+                   int32_t b, int64_t d, int64_t ldA, int64_t ld, float scale, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+    using namespace dl;
+    const char* fn = "local_grad_lsq";
+    clear_error();
+    if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
+    if (b < 1) return set_error(DL_EINVAL, "%s: b = %d, need b >= 1", fn, b);
+    if (d < 0) return set_error(DL_EINVAL, "%s: d = %lld, need d >= 0", fn, static_cast<long long>(d));
+    if (ldA < d || ld < d)
+        return set_error(DL_EINVAL, "%s: ldA = %lld and ld = %lld must be >= d = %lld", fn,
+                         static_cast<long long>(ldA), static_cast<long long>(ld), static_cast<long long>(d));
+    if (!std::isfinite(scale)) return set_error(DL_EINVAL, "%s: scale must be finite", fn);
+    if (!A || !y || !x || !g) return set_error(DL_EINVAL, "%s: A, y, x and g must not be NULL", fn);
+    if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(y) | reinterpret_cast<uintptr_t>(x) |
+         reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(loss)) & 3u)
+        return set_error(DL_EINVAL, "%s: arrays must be 4-byte aligned", fn);
+    const size_t need = lsq_workspace_bytes(n, b, d);
+    if (!workspace || workspace_bytes < need)
+        return set_error(DL_ECAP, "%s: workspace of %zu bytes needed, %zu given", fn, need,
+                         workspace ? workspace_bytes : size_t{0});
+    if (reinterpret_cast<uintptr_t>(workspace) & 15u)
+        return set_error(DL_EINVAL, "%s: workspace must be 16-byte aligned", fn);
+    const Span sg = span_of(g, n, d, ld);
+    const Span sA = span_of(A, static_cast<int64_t>(n) * b, d, ldA);
+    const Span sy = span_of(y, 1, static_cast<int64_t>(n) * b, static_cast<int64_t>(n) * b);
+    const Span sx = span_of(x, n, d, ld);
+    const Span sw = {reinterpret_cast<uintptr_t>(workspace), reinterpret_cast<uintptr_t>(workspace) + need};
+    if (overlap(sg, sA) || overlap(sg, sy) || overlap(sg, sw) || overlap(sw, sA) || overlap(sw, sy) ||
+        overlap(sw, sx))
+        return set_error(DL_EALIAS, "%s: g / workspace overlap an input", fn);
+    if (d > 0 && overlap(sg, sx)) {
+        const intptr_t delta = (reinterpret_cast<intptr_t>(g) - reinterpret_cast<intptr_t>(x)) / 4;
+        const int64_t off = ((delta % ld) + ld) % ld;
+        if (!(off >= d && ld - off >= d)) return set_error(DL_EALIAS, "%s: g overlaps x", fn);
+    }
+    if (loss) {
+        const Span sl = span_of(loss, 1, n, n);
+        if (overlap(sl, sA) || overlap(sl, sy) || overlap(sl, sx) || overlap(sl, sg) || overlap(sl, sw))
+            return set_error(DL_EALIAS, "%s: loss overlaps another array", fn);
+    }
+    return launch_lsq(A, y, x, g, loss, n, b, d, ldA, ld, scale, workspace, static_cast<hipStream_t>(stream));
+}
+
+const char* dl_last_error(void) { return dl::g_error; }
+
+}  // extern "C"

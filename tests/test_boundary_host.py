@@ -1,0 +1,161 @@
+"""Host-side tests of the C ABI (no GPU): the library loads and exports what
+include/decentlam.h declares, topology_build matches the oracle bit for bit,
+and argument validation returns the documented status codes before any device
+work is attempted."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2104_11981_amd as P
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+I32P = ctypes.POINTER(ctypes.c_int32)
+F32P = ctypes.POINTER(ctypes.c_float)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "decentlam.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b([a-z_][a-z0-9_]*)\s*\(", header)) - {"defined", "sizeof"}
+    assert declared == set(P.EXPORTS)
+    lib = ctypes.CDLL(P.LIB_PATH)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+@pytest.mark.parametrize("kind", [0, 1, 2])
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 6, 7, 8, 9, 15, 16, 17, 31, 32, 33, 64, 100, 128, 256])
+def test_topology_build_matches_oracle_bit_exactly(oracle, kind, n):
+    ours = P.topology_build(kind, n)
+    ref = oracle.topology(kind, n)
+    assert ours.period == ref.period
+    np.testing.assert_array_equal(ours.row_ptr, ref.row_ptr)
+    np.testing.assert_array_equal(ours.col_idx, ref.col_idx)
+    np.testing.assert_array_equal(ours.w.view(np.uint32), ref.w.view(np.uint32))  # fp32 bit patterns
+
+
+@pytest.mark.parametrize("kind,n", [(0, 1), (0, 2), (0, 5), (1, 8), (1, 12), (2, 8), (2, 6)])
+def test_topology_flags_describe_the_matrix(oracle, kind, n):
+    ours = P.topology_build(kind, n)
+    ref = oracle.topology(kind, n)
+    sym = all(np.array_equal(ref.dense(p), ref.dense(p).T) for p in range(ref.period))
+    assert bool(ours.flags & P.DL_FLAG_SYMMETRIC) == sym
+    for p in range(ref.period):
+        W = ref.dense(p)
+        assert bool(ours.flags & P.DL_FLAG_ROW_STOCHASTIC) and np.abs(W.sum(1) - 1).max() <= 1e-6
+        assert bool(ours.flags & P.DL_FLAG_COL_STOCHASTIC) and np.abs(W.sum(0) - 1).max() <= 1e-6
+
+
+def test_topology_build_size_query_and_capacity():
+    period, nnz, flags = ctypes.c_int32(), ctypes.c_int64(), ctypes.c_uint32()
+    rc = P.raw.topology_build(P.DL_TOPO_EXP_STATIC, 32, None, 0, None, None, 0, ctypes.byref(period),
+                              ctypes.byref(nnz), ctypes.byref(flags))
+    assert rc == P.DL_OK and period.value == 1 and nnz.value == 192
+    row_ptr = np.zeros(33, np.int32)
+    col = np.zeros(100, np.int32)
+    w = np.zeros(100, np.float32)
+    rc = P.raw.topology_build(P.DL_TOPO_EXP_STATIC, 32, row_ptr.ctypes.data_as(I32P), 33,
+                              col.ctypes.data_as(I32P), w.ctypes.data_as(F32P), 100,
+                              ctypes.byref(period), ctypes.byref(nnz), ctypes.byref(flags))
+    assert rc == P.DL_ECAP and nnz.value == 192 and "nnz_cap" in P.last_error()
+    assert not col.any()   # nothing written when the capacity is short
+    assert P.raw.topology_build(9, 4, None, 0, None, None, 0, ctypes.byref(period), ctypes.byref(nnz),
+                                None) == P.DL_EINVAL
+    assert P.raw.topology_build(0, 0, None, 0, None, None, 0, ctypes.byref(period), ctypes.byref(nnz),
+                                None) == P.DL_EINVAL
+    assert P.raw.topology_build(0, 4, None, 0, None, None, 0, None, None, None) == P.DL_EINVAL
+
+
+def _call(fn, n=4, d=0, ld=0, topo=None, gamma=0.1, beta=0.9, k=0, x=None, m=None, g=None):
+    topo = topo or P.topology_build(0, n)
+    return fn(x, m, g, n, d, ld, *topo._args(), gamma, beta, k, None)
+
+
+@pytest.mark.parametrize("fn", [P.raw.decentlam_step, P.raw.dmsgd_step])
+def test_step_argument_validation(fn):
+    assert _call(fn) == P.DL_OK                      # d == 0: successful no-op, no device needed
+    assert _call(fn, n=0, topo=P.topology_build(0, 1)) == P.DL_EINVAL
+    assert _call(fn, d=-1) == P.DL_EINVAL
+    assert _call(fn, d=8, ld=4) == P.DL_EINVAL
+    for bad in (0.0, -0.1, float("inf"), float("nan")):
+        assert _call(fn, gamma=bad) == P.DL_EINVAL
+    for bad in (-0.1, 1.0, float("nan")):
+        assert _call(fn, beta=bad) == P.DL_EINVAL
+    assert _call(fn, beta=0.0) == P.DL_OK            # beta = 0 is the DSGD case
+    assert _call(fn, k=-1) == P.DL_EINVAL
+    assert _call(fn, d=8, ld=8) == P.DL_EINVAL       # NULL arrays with d > 0
+    assert "NULL" in P.last_error()
+    assert _call(fn, d=8, ld=8, x=4096, m=4096 + 64, g=8192) == P.DL_EALIAS   # m starts inside x
+    assert _call(fn, d=8, ld=8, x=4096, m=8192, g=4096) == P.DL_EALIAS        # g is x
+    assert _call(fn, d=8, ld=8, x=1026, m=4096, g=8192) == P.DL_EINVAL        # misaligned pointer
+
+
+def _topo(n, rows):
+    row_ptr, col, w = [0], [], []
+    for r in rows:
+        for j, wij in r:
+            col.append(j)
+            w.append(wij)
+        row_ptr.append(len(col))
+    return P.make_topology(n, row_ptr, col, w)
+
+
+def test_step_topology_validation():
+    fn = P.raw.decentlam_step
+    good = [[(0, 0.5), (1, 0.5)], [(1, 0.5), (0, 0.5)]]
+    assert _call(fn, n=2, topo=_topo(2, good)) == P.DL_OK
+    cases = {
+        "outside": [[(0, 0.5), (2, 0.5)], [(1, 1.0)]],
+        "twice": [[(0, 0.5), (0, 0.5)], [(1, 1.0)]],
+        "must be finite": [[(0, 1.5), (1, -0.5)], [(1, 1.0)]],
+        "sums to": [[(0, 0.5), (1, 0.4)], [(1, 1.0)]],
+        "empty": [[(0, 1.0)], []],
+    }
+    for needle, rows in cases.items():
+        assert _call(fn, n=2, topo=_topo(2, rows)) == P.DL_ETOPO
+        assert needle in P.last_error(), (needle, P.last_error())
+    nan_w = _topo(2, [[(0, float("nan"))], [(1, 1.0)]])
+    assert _call(fn, n=2, topo=nan_w) == P.DL_ETOPO
+    # limits: more nodes / entries than travel in the kernel arguments
+    big = P.topology_build(0, 300)
+    assert _call(fn, n=300, topo=big) == P.DL_ETOPO and "DL_MAX_NODES" in P.last_error()
+    dense = _topo(32, [[(j, 1.0 / 32) for j in range(32)] for _ in range(32)])
+    assert _call(fn, n=32, topo=dense) == P.DL_ETOPO and "DL_MAX_NNZ" in P.last_error()
+    # time-varying W: the phase used is k mod period, and only that phase is inspected
+    t = P.topology_build(2, 8)
+    t.w[2 * 16 + 3] = -1.0                            # corrupt phase 2 only
+    assert _call(fn, n=8, topo=t, k=0) == P.DL_OK
+    assert _call(fn, n=8, topo=t, k=1) == P.DL_OK
+    assert _call(fn, n=8, topo=t, k=2) == P.DL_ETOPO
+    assert _call(fn, n=8, topo=t, k=5) == P.DL_ETOPO
+    assert _call(fn, n=8, topo=t, k=6) == P.DL_OK
+
+
+def test_lsq_argument_validation():
+    f = P.raw.local_grad_lsq
+    ws = P.local_grad_lsq_workspace(2, 3, 8)
+    assert ws > 0 and P.local_grad_lsq_workspace(0, 3, 8) == 0
+    ok = dict(A=0x10000, y=0x20000, x=0x30000, g=0x40000, loss=0, n=2, b=3, d=8, ldA=8, ld=8,
+              scale=1.0, wsp=0x50000, wsb=ws)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["A"], a["y"], a["x"], a["g"], a["loss"], a["n"], a["b"], a["d"], a["ldA"], a["ld"],
+                 a["scale"], a["wsp"], a["wsb"], None)
+
+    assert call(n=0) == P.DL_EINVAL
+    assert call(b=0) == P.DL_EINVAL
+    assert call(d=-1) == P.DL_EINVAL
+    assert call(ldA=4) == P.DL_EINVAL
+    assert call(ld=4) == P.DL_EINVAL
+    assert call(scale=float("nan")) == P.DL_EINVAL
+    assert call(A=0) == P.DL_EINVAL
+    assert call(wsb=ws - 1) == P.DL_ECAP and str(ws) in P.last_error()
+    assert call(wsp=0) == P.DL_ECAP
+    assert call(wsp=0x50008) == P.DL_EINVAL          # workspace not 16-byte aligned
+    assert call(g=0x10010) == P.DL_EALIAS            # g inside A
+    assert call(g=0x30000) == P.DL_EALIAS            # g == x
+    assert call(loss=0x40000) == P.DL_EALIAS         # loss inside g

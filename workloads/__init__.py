@@ -26,4 +26,5 @@ from .generate import (  # noqa: F401
     ragged_layout,
     device_x0,
     device_grad,
+    device_lsq_problem,
 )
