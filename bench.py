@@ -29,9 +29,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 BYTES_PER_ELEMENT = 20         # read x, m, g + write x, m, fp32
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), keyed by
-# (workload, algo); None until measured for that kernel.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by what
+# the same counter reads for a plain device copy of known size; profiles/*_hbm_traffic_pmc.txt),
+# keyed by (workload, algo); None where not measured.
+MEASURED_TRAFFIC_BYTES = {("c3_exp32", "decentlam"): 16_383_747_763}
 
 
 def ensure_built():
@@ -85,6 +86,10 @@ def main():
     ap.add_argument("--workload", default="c3_exp32", choices=["c3_exp32", "c4_ring16_ragged"])
     ap.add_argument("--algo", default="decentlam", choices=["decentlam", "dmsgd"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed region, run one plain device copy of one n x d array "
+                         "(known size: reads and writes 4*n*d bytes) so that a rocprofv3 --pmc run "
+                         "of this command can scale FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build simulates all n nodes on ONE GPU (columns of the update are "
@@ -154,6 +159,11 @@ def main():
                      "kernel": "k_step", "kernel_ms": round(kern_ms, 4),
                      "algorithmic_bytes_per_launch": bytes_per_step},
     }
+    if args.calibration_copy:
+        scratch = torch.empty_like(g)
+        scratch.copy_(g)
+        torch.cuda.synchronize()
+        del scratch
     del x, m, g
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
