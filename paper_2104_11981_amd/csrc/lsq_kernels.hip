@@ -5,6 +5,14 @@
 // The bound is HBM, and the kernels are organised around streaming A with wide
 // coalesced loads; products are exact in fp64 (two fp32 factors) and sums are fp64.
 //
+// Single sweep (rows 16-byte aligned, d <= 8192): k_fused keeps a tile of R rows of A_i in
+// registers, split by columns over the 256 threads of a workgroup; the R residuals are reduced
+// with wavefront shuffles plus one LDS hop, then the same registers feed the transposed
+// product, so A is read from HBM exactly once (4*b*d bytes per node).  The next tile's loads are
+// issued before the current tile's reduction.  Each workgroup owns a block of rows of one node
+// and leaves a partial gradient; k_finish_fused adds the partials in fixed order.
+//
+// Two sweeps (any shape and alignment):
 //   k_residual   one wave per row r of A_i: res[i][r] = A_i[r,:] . x_i - y_i[r]
 //                (lane-strided 16-byte loads, fp64 accumulators, wavefront-shuffle reduction)
 //   k_transpose  one thread per 4 columns, one workgroup per (column block, row split, node):
@@ -128,12 +136,184 @@ __global__ __launch_bounds__(kThreads) void k_finish(const double* __restrict__ 
     }
 }
 
+
+// ---------------------------------------------------------------- single sweep
+// CPT  16-byte column chunks per thread (thread t owns columns 4t + 1024q .. +3, q < CPT)
+// R    rows of A per register tile
+template <int CPT, int R>
+struct Tile {
+    vf4 a[R][CPT];
+};
+
+// Loads never need a predicate: rows past the block's end are clamped to its last row (their
+// residual is forced to zero below) and column chunks past d are clamped to the last chunk
+// (their x is zero and their accumulators are never stored).
+template <int CPT, int R>
+__device__ __forceinline__ void load_tile(Tile<CPT, R>& t, const float* __restrict__ a_node, int64_t ldA,
+                                          int r, int r_last, const int (&col)[CPT]) {
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        const int row = (r + rr < r_last) ? r + rr : r_last;
+        const float* __restrict__ a_row = a_node + static_cast<int64_t>(row) * ldA;
+#pragma unroll
+        for (int q = 0; q < CPT; ++q)
+            t.a[rr][q] = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(a_row + col[q]));
+    }
+}
+
+template <int CPT, int R>
+__device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float (&xs)[CPT][4],
+                                             double (&acc)[CPT][4], double& sq, double (*red)[R],
+                                             const float* __restrict__ yi, int r, int r1, int lane, int wave) {
+    double p[R];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+        for (int q = 0; q < CPT; ++q) {
+            s0 = __builtin_fma(static_cast<double>(t.a[rr][q].x), static_cast<double>(xs[q][0]), s0);
+            s1 = __builtin_fma(static_cast<double>(t.a[rr][q].y), static_cast<double>(xs[q][1]), s1);
+            s0 = __builtin_fma(static_cast<double>(t.a[rr][q].z), static_cast<double>(xs[q][2]), s0);
+            s1 = __builtin_fma(static_cast<double>(t.a[rr][q].w), static_cast<double>(xs[q][3]), s1);
+        }
+        p[rr] = wave_sum(s0 + s1);
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) red[wave][rr] = p[rr];
+    }
+    __syncthreads();
+    // The transposed product re-converts the tile from fp32: keeping the forward pass's fp64
+    // copies alive across the barrier would double the register footprint of the tile.
+    Tile<CPT, R> u = t;
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+#pragma unroll
+        for (int q = 0; q < CPT; ++q) asm volatile("" : "+v"(u.a[rr][q]));
+    }
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        double res = 0.0;
+        if (r + rr < r1)  // uniform over the workgroup
+            res = ((red[0][rr] + red[1][rr]) + (red[2][rr] + red[3][rr])) - static_cast<double>(yi[r + rr]);
+        sq = __builtin_fma(res, res, sq);
+#pragma unroll
+        for (int q = 0; q < CPT; ++q) {
+            acc[q][0] = __builtin_fma(static_cast<double>(u.a[rr][q].x), res, acc[q][0]);
+            acc[q][1] = __builtin_fma(static_cast<double>(u.a[rr][q].y), res, acc[q][1]);
+            acc[q][2] = __builtin_fma(static_cast<double>(u.a[rr][q].z), res, acc[q][2]);
+            acc[q][3] = __builtin_fma(static_cast<double>(u.a[rr][q].w), res, acc[q][3]);
+        }
+    }
+}
+
+template <int CPT, int R, bool PF>
+__global__ __launch_bounds__(kThreads, (PF || CPT >= 8) ? 2 : 4) void k_fused(const float* __restrict__ A, const float* __restrict__ y,
+                                                     const float* __restrict__ x, double* __restrict__ partial,
+                                                     double* __restrict__ sq_partial, int b, int64_t d,
+                                                     int64_t ldA, int64_t ld, int splits) {
+    __shared__ double red[2][kThreads / 64][R];  // two buffers: one barrier per tile is enough
+    const int i = blockIdx.y, s = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r0 = static_cast<int>(static_cast<int64_t>(b) * s / splits);
+    const int r1 = static_cast<int>(static_cast<int64_t>(b) * (s + 1) / splits);  // r1 > r0: splits <= b
+
+    int col[CPT];
+    float xs[CPT][4];
+    double acc[CPT][4];
+#pragma unroll
+    for (int q = 0; q < CPT; ++q) {
+        const int c = 4 * static_cast<int>(threadIdx.x) + 1024 * q;
+        const bool inside = c < d;
+        col[q] = inside ? c : static_cast<int>(d) - 4;
+        const vf4 xv = *reinterpret_cast<const vf4*>(x + static_cast<int64_t>(i) * ld + col[q]);
+        xs[q][0] = inside ? xv.x : 0.f; xs[q][1] = inside ? xv.y : 0.f;
+        xs[q][2] = inside ? xv.z : 0.f; xs[q][3] = inside ? xv.w : 0.f;
+        acc[q][0] = acc[q][1] = acc[q][2] = acc[q][3] = 0.0;
+    }
+    double sq = 0.0;
+    const float* __restrict__ a_node = A + static_cast<int64_t>(i) * b * ldA;
+    const float* __restrict__ yi = y + static_cast<int64_t>(i) * b;
+
+    if constexpr (PF) {
+        Tile<CPT, R> t0, t1;
+        load_tile<CPT, R>(t0, a_node, ldA, r0, r1 - 1, col);
+        for (int r = r0; r < r1; r += 2 * R) {
+            load_tile<CPT, R>(t1, a_node, ldA, r + R, r1 - 1, col);
+            consume_tile<CPT, R>(t0, xs, acc, sq, red[0], yi, r, r1, lane, wave);
+            load_tile<CPT, R>(t0, a_node, ldA, r + 2 * R, r1 - 1, col);
+            consume_tile<CPT, R>(t1, xs, acc, sq, red[1], yi, r + R, r1, lane, wave);
+        }
+    } else {
+        Tile<CPT, R> t0;
+        int buf = 0;
+        for (int r = r0; r < r1; r += R, buf ^= 1) {
+            load_tile<CPT, R>(t0, a_node, ldA, r, r1 - 1, col);
+            consume_tile<CPT, R>(t0, xs, acc, sq, red[buf], yi, r, r1, lane, wave);
+        }
+    }
+
+    double* out = partial + (static_cast<int64_t>(i) * splits + s) * d;
+#pragma unroll
+    for (int q = 0; q < CPT; ++q) {
+        const int c = 4 * static_cast<int>(threadIdx.x) + 1024 * q;
+        if (c < d) {
+            out[c + 0] = acc[q][0]; out[c + 1] = acc[q][1]; out[c + 2] = acc[q][2]; out[c + 3] = acc[q][3];
+        }
+    }
+    if (threadIdx.x == 0) sq_partial[static_cast<int64_t>(i) * splits + s] = sq;
+}
+
+__global__ __launch_bounds__(kThreads) void k_finish_fused(const double* __restrict__ partial,
+                                                            const double* __restrict__ sq_partial,
+                                                            float* __restrict__ g, float* __restrict__ loss,
+                                                            int64_t d, int64_t ld, int splits, double scale) {
+    const int i = blockIdx.y;
+    const int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (c < d) {
+        const double* p = partial + static_cast<int64_t>(i) * splits * d + c;
+        double acc = 0.0;
+        for (int s = 0; s < splits; ++s) acc += p[static_cast<int64_t>(s) * d];
+        g[static_cast<int64_t>(i) * ld + c] = static_cast<float>(scale * acc);
+    }
+    if (loss != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
+        double sq = 0.0;
+        for (int s = 0; s < splits; ++s) sq += sq_partial[static_cast<int64_t>(i) * splits + s];
+        loss[i] = static_cast<float>(0.5 * scale * sq);
+    }
+}
+
+// Row blocks per node for the single sweep: about two workgroups per CU in total, all resident
+// at once (measured best on 256 CUs: 512 workgroups; more, shorter ones lose up to 15 %), but at
+// least one double tile of rows each.
+int fused_splits(int32_t n, int32_t b, int rows_per_iteration) {
+    int64_t s = (512 + n / 2) / n;
+    const int64_t most = (b + rows_per_iteration - 1) / rows_per_iteration;
+    if (s > most) s = most;
+    if (s > 256) s = 256;
+    if (s < 1) s = 1;
+    return static_cast<int>(s);
+}
+
+// rows consumed per loop iteration (two register tiles of R rows, or one without prefetch)
+int fused_rows(int cpt) { return cpt == 1 ? 8 : cpt == 2 ? 4 : cpt == 4 ? 2 : 1; }
+int fused_cpt(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : 8; }
+constexpr int kMaxFusedD = 8192;
+
 }  // namespace
 
 size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d) {
+    // two-sweep layout: res[n*b], partial[n*splits*d]; single-sweep layout: sq[n*splits], partial[n*splits*d]
     const size_t res = static_cast<size_t>(n) * static_cast<size_t>(b);
     const size_t partial = static_cast<size_t>(n) * static_cast<size_t>(row_splits(n, b, d)) * static_cast<size_t>(d);
-    return (res + partial) * sizeof(double) + 16;
+    size_t need = (res + partial) * sizeof(double) + 16;
+    if (d > 0 && d <= kMaxFusedD) {
+        const size_t fs = static_cast<size_t>(fused_splits(n, b, fused_rows(fused_cpt(d))));
+        const size_t fused = (static_cast<size_t>(n) * fs * (static_cast<size_t>(d) + 1)) * sizeof(double) + 16;
+        if (fused > need) need = fused;
+    }
+    return need;
 }
 
 int launch_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
@@ -147,6 +327,25 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
     if (n > 65535 || splits > 65535) return set_error(DL_EINVAL, "local_grad_lsq: n too large for the launch grid");
 
     const dim3 block(kThreads);
+    if (vec4 && d > 0 && d <= kMaxFusedD) {
+        const int cpt = fused_cpt(d);
+        const int fs = fused_splits(n, b, fused_rows(cpt));
+        double* sq_partial = static_cast<double*>(workspace);
+        double* fpartial = sq_partial + ((static_cast<size_t>(n) * fs + 1) & ~size_t{1});
+        const dim3 grid(static_cast<unsigned>(fs), static_cast<unsigned>(n));
+        switch (cpt) {
+            case 1: hipLaunchKernelGGL((k_fused<1, 4, true>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs); break;
+            case 2: hipLaunchKernelGGL((k_fused<2, 2, true>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs); break;
+            case 4: hipLaunchKernelGGL((k_fused<4, 1, true>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs); break;
+            default: hipLaunchKernelGGL((k_fused<8, 1, false>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs); break;
+        }
+        if (int rc = check_hip(hipGetLastError(), "fused gradient kernel launch")) return rc;
+        const dim3 grid_ff(static_cast<unsigned>((d + kThreads - 1) / kThreads), static_cast<unsigned>(n));
+        hipLaunchKernelGGL(k_finish_fused, grid_ff, block, 0, stream, fpartial, sq_partial, g, loss, d, ld, fs,
+                           static_cast<double>(scale));
+        return check_hip(hipGetLastError(), "finish kernel launch");
+    }
+
     const dim3 grid_r(static_cast<unsigned>((b + 3) / 4), static_cast<unsigned>(n));
     if (vec4)
         hipLaunchKernelGGL(k_residual<true>, grid_r, block, 0, stream, A, y, x, res, b, d, ldA, ld);

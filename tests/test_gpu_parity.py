@@ -179,7 +179,12 @@ LSQ_CASES = [
     (2, 5, 33, 1, 3, 0.5),               # odd strides: scalar path
     (1, 1, 1, 0, 0, 1.0),
     (4, 300, 7, 0, 0, 1.0),              # tall and thin
-    (4, 3, 2500, 0, 0, 1.0),             # short and wide
+    (4, 3, 2500, 0, 0, 1.0),             # short and wide; single sweep, 4 chunks per thread
+    (2, 77, 132, 0, 4, 1.0),             # single sweep with most threads idle (d < 1024)
+    (3, 1000, 1500, 4, 0, 0.001),        # single sweep, 2 chunks per thread, ragged row blocks
+    (2, 45, 5000, 0, 0, 1.0),            # single sweep, 8 chunks per thread
+    (1, 9, 8200, 0, 0, 1.0),             # d > 8192: two sweeps with 16-byte loads
+    (70, 2, 64, 0, 0, 1.0),              # more nodes than rows
 ]
 
 
