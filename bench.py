@@ -78,6 +78,88 @@ def cpu_baseline(w, kind, algo, target_seconds=12.0):
     }
 
 
+def time_launches(fn, steps, warmup):
+    """W untimed calls, then K calls between two synchronisations; returns (wall ms, HIP-event ms) per call."""
+    import torch
+
+    for k in range(warmup):
+        fn(k)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for k in range(steps):
+        fn(warmup + k)
+    ev1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, ev0.elapsed_time(ev1) / steps
+
+
+def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False):
+    import numpy as np
+    import torch
+
+    w = workloads.get(name)
+    d = workloads.generate.dim(w)
+    topo = P.topology_build(w.topo, w.n)
+    gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
+    step = getattr(P, algo + "_step")
+    # Row stride: rows start on 256-byte boundaries (ld = d rounded up to 64 elements).  With rows
+    # that are only 16-byte aligned every 1 KiB wave access straddles an extra cache line and the
+    # ragged workload loses about 17 % (measured 4.65 vs 5.60 TB/s).
+    ld = (d + 63) // 64 * 64
+    xb = workloads.device_x0(w, "cuda", ld=ld)
+    mb = torch.zeros_like(xb)
+    gb = torch.zeros_like(xb)
+    workloads.device_grad(w, 0, gb)
+    x, m, g = xb[:, :d], mb[:, :d], gb[:, :d]
+    torch.cuda.synchronize()
+    wall_ms, kern_ms = time_launches(lambda k: step(x, m, g, topo, gamma, beta, k), steps, warmup)
+    assert bool(torch.isfinite(x[:, :1024]).all()), "state overflowed during the timed run"
+    if calibration_copy:
+        scratch = torch.empty_like(gb)
+        scratch.copy_(gb)
+        torch.cuda.synchronize()
+        del scratch
+    del x, m, g, xb, mb, gb
+    torch.cuda.empty_cache()
+    return w, d, ld, topo, wall_ms, kern_ms
+
+
+def bench_lsq(P, workloads, name, steps, warmup):
+    """Workload 5: local_grad_lsq then decentlam_step per iteration; times the gradient alone too."""
+    import numpy as np
+    import torch
+
+    w = workloads.get(name)
+    A, y, _ = workloads.device_lsq_problem(w, "cuda")
+    topo = P.topology_build(w.topo, w.n)
+    gamma, beta, scale = (float(np.float32(v)) for v in (w.gamma, w.beta, w.lsq_scale))
+    x = torch.zeros((w.n, w.d), dtype=torch.float32, device="cuda")
+    m = torch.zeros_like(x)
+    g = torch.empty_like(x)
+    loss = torch.empty(w.n, dtype=torch.float32, device="cuda")
+    ws = torch.empty(P.local_grad_lsq_workspace(w.n, w.b, w.d), dtype=torch.uint8, device="cuda")
+
+    def iteration(k):
+        P.local_grad_lsq(A, y, x, g, loss, scale, ws)
+        P.decentlam_step(x, m, g, topo, gamma, beta, k)
+
+    wall_ms, both_ms = time_launches(iteration, steps, warmup)
+    _, grad_ms = time_launches(lambda k: P.local_grad_lsq(A, y, x, g, loss, scale, ws), steps, 1)
+    a_bytes = 4 * w.n * w.b * w.d
+    del A, y, x, m, g, ws
+    torch.cuda.empty_cache()
+    return {
+        "workload": w.name, "n": w.n, "b": w.b, "d": w.d,
+        "ms_per_iteration_grad_plus_step": round(wall_ms, 4), "grad_kernel_ms": round(grad_ms, 4),
+        "grad_algorithmic_bytes": a_bytes, "grad_GBps": round(a_bytes / (grad_ms * 1e-3) / 1e9, 1),
+        "grad_frac_of_hbm_peak": round(a_bytes / (grad_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "grad_GFLOPps_fp64": round(4.0 * w.n * w.b * w.d / (grad_ms * 1e-3) / 1e9, 1),
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -86,6 +168,8 @@ def main():
     ap.add_argument("--workload", default="c3_exp32", choices=["c3_exp32", "c4_ring16_ragged"])
     ap.add_argument("--algo", default="decentlam", choices=["decentlam", "dmsgd"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the side measurements (DmSGD, ragged workload, least-squares gradient)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed region, run one plain device copy of one n x d array "
                          "(known size: reads and writes 4*n*d bytes) so that a rocprofv3 --pmc run "
@@ -98,7 +182,6 @@ def main():
         sys.exit("bench.py: single-process benchmark; do not launch it under torch.distributed.run")
 
     ensure_built()
-    import numpy as np
     import torch
 
     import paper_2104_11981_amd as P
@@ -107,38 +190,13 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     torch.cuda.set_device(0)
-    w = workloads.get(args.workload)
-    d = workloads.generate.dim(w)
+
+    w, d, ld, topo, wall_ms, kern_ms = bench_step(P, workloads, args.workload, args.algo, args.steps,
+                                                  args.warmup, args.calibration_copy)
     kind = w.topo
-    topo = P.topology_build(kind, w.n)
-    gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
-    step = getattr(P, args.algo + "_step")
-
-    x = workloads.device_x0(w, "cuda")
-    m = torch.zeros_like(x)
-    g = torch.empty_like(x)
-    workloads.device_grad(w, 0, g)
-    torch.cuda.synchronize()
-
-    for k in range(args.warmup):
-        step(x, m, g, topo, gamma, beta, k)
-    torch.cuda.synchronize()
-
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for k in range(args.steps):
-        step(x, m, g, topo, gamma, beta, args.warmup + k)
-    ev1.record()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-
-    wall_ms = (t1 - t0) * 1e3 / args.steps
-    kern_ms = ev0.elapsed_time(ev1) / args.steps
     bytes_per_step = BYTES_PER_ELEMENT * w.n * d
     value = bytes_per_step / (wall_ms * 1e-3) / 1e9
     achieved = bytes_per_step / (kern_ms * 1e-3) / 1e9
-    assert bool(torch.isfinite(x[:, :1024]).all()), "state overflowed during the timed run"
 
     out = {
         "metric": "DecentLaM step: achieved HBM GB/s & steps/s at n=32 nodes x d=25.6M fp32"
@@ -149,7 +207,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(wall_ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-        "config": {"workload": w.name, "algo": args.algo, "n": w.n, "d": d,
+        "config": {"workload": w.name, "algo": args.algo, "n": w.n, "d": d, "ld": ld,
                    "topology": {0: "ring", 1: "exp_static", 2: "exp_onepeer"}[kind],
                    "deg": int(topo.row_ptr[1] - topo.row_ptr[0]), "gamma": w.gamma, "beta": w.beta,
                    "storage": "fp32", "bytes_per_node_element": BYTES_PER_ELEMENT},
@@ -159,13 +217,17 @@ def main():
                      "kernel": "k_step", "kernel_ms": round(kern_ms, 4),
                      "algorithmic_bytes_per_launch": bytes_per_step},
     }
-    if args.calibration_copy:
-        scratch = torch.empty_like(g)
-        scratch.copy_(g)
-        torch.cuda.synchronize()
-        del scratch
-    del x, m, g
-    torch.cuda.empty_cache()
+    if not args.no_extras:
+        extras = {}
+        for name, algo in (("c3_exp32", "dmsgd"), ("c4_ring16_ragged", "decentlam")):
+            if (name, algo) == (args.workload, args.algo):
+                continue
+            w2, d2, _, _, _, k2 = bench_step(P, workloads, name, algo, args.steps, args.warmup)
+            b2 = BYTES_PER_ELEMENT * w2.n * d2
+            extras[f"{algo}_step_{name}"] = {"kernel_ms": round(k2, 4), "GBps": round(b2 / (k2 * 1e-3) / 1e9, 1),
+                                             "frac_of_hbm_peak": round(b2 / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        extras["local_grad_lsq_c5"] = bench_lsq(P, workloads, "c5_onepeer64_lsq", args.steps, args.warmup)
+        out["extras"] = extras
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, kind, args.algo)
     print(json.dumps(out), flush=True)

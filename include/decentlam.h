@@ -95,7 +95,8 @@ int topology_build(int kind, int32_t n,
  *   gamma > 0 finite; 0 <= beta < 1; k >= 0 selects phase k mod period.
  *   The caller zeroes m before iteration 0 (Algorithm 2, initialisation).
  * d == 0 is a successful no-op.  Any alignment and any ld >= d are accepted
- * (unaligned heads/tails fall back to narrower loads).
+ * (unaligned heads/tails fall back to narrower loads); for full speed let rows start on
+ * 128-byte boundaries (16-byte aligned bases, ld a multiple of 32).
  * Errors: DL_EINVAL, DL_ETOPO, DL_EALIAS, DL_EHIP.
  */
 int decentlam_step(float* x, float* m, const float* g,
@@ -132,6 +133,26 @@ int local_grad_lsq(const float* A, const float* y, const float* x,
                    float* g, float* loss,
                    int32_t n, int32_t b, int64_t d, int64_t ldA, int64_t ld,
                    float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * decentlam_stats -- diagnostics of the stacked state, one pass over x (and m):
+ *     out[0] = sum_i ||x_i - xbar||^2,  xbar = (1/n) sum_i x_i   (consensus distance; xbar as in
+ *                                                                 the appendix "Preliminary")
+ *     out[1] = ||xbar||^2
+ *     out[2] = sum_i ||x_i - ref||^2,  out[3] = ||ref||^2         (0 if ref == NULL); the relative
+ *              error of the appendix "Experimental setting for linear regression",
+ *              (1/n) sum_i ||x_i - x*||^2 / ||x*||^2, is out[2] / (n * out[3]) with ref = x*
+ *     out[4] = ||m||_F^2                                          (0 if m == NULL)
+ *
+ *   x [in] device n x d fp32 (row stride ld); m [in] same shape or NULL; ref [in] device, d fp32, or NULL.
+ *   out [out] device, 5 doubles.  workspace [scratch] device, decentlam_stats_workspace(n, d) bytes.
+ * fp64 sums combined in a fixed order (bit-reproducible).  d == 0 yields zeros.
+ * Errors: DL_EINVAL, DL_ECAP, DL_EHIP.
+ */
+size_t decentlam_stats_workspace(int32_t n, int64_t d);
+int decentlam_stats(const float* x, const float* m, const float* ref,
+                    int32_t n, int64_t d, int64_t ld,
+                    double* out, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Description of the last failure on the calling thread ("" if none). Never NULL. */
 const char* dl_last_error(void);

@@ -56,6 +56,7 @@ def _load():
                 ctypes.c_double, ctypes.c_int64, f64p, f64p, f64p, f64p, f64p]
         _lib.oracle_dmsgd_step.argtypes = step
         _lib.oracle_decentlam_step.argtypes = step
+        _lib.oracle_stats.argtypes = [ctypes.c_int, ctypes.c_int64, f64p, f64p, f64p, f64p]
         _lib.oracle_lsq_grad.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, f32p, f32p, f64p,
                                          ctypes.c_double, f64p, f64p]
     return _lib
@@ -178,6 +179,22 @@ def lsq_grad(A, y, x, scale: float = 1.0):
                                  _p(loss, ctypes.c_double))
     assert rc == 0
     return g, loss
+
+
+def stats(x, m=None, ref=None):
+    """[sum_i ||x_i - xbar||^2, ||xbar||^2, sum_i ||x_i - ref||^2, ||ref||^2, ||m||_F^2] (float64[5])."""
+    x = _f64(x)
+    n, d = x.shape
+    m = None if m is None else _f64(m)
+    ref = None if ref is None else _f64(ref)
+    assert m is None or m.shape == x.shape
+    assert ref is None or ref.shape == (d,)
+    out = np.zeros(5)
+    null = ctypes.POINTER(ctypes.c_double)()
+    rc = _load().oracle_stats(n, d, _p(x, ctypes.c_double), null if m is None else _p(m, ctypes.c_double),
+                              null if ref is None else _p(ref, ctypes.c_double), _p(out, ctypes.c_double))
+    assert rc == 0
+    return out
 
 
 STEP = {"decentlam": decentlam_step, "dmsgd": dmsgd_step}

@@ -250,3 +250,34 @@ int oracle_lsq_grad(int n, int b, int64_t d, const float* A, const float* y, con
     free(res);
     return 0;
 }
+
+/* Diagnostics on the stacked state (notation of the appendix "Preliminary"; the relative error
+ * is the y-axis of the linear-regression experiment):
+ *   out[0] = sum_i ||x_i - xbar||^2  with xbar = (1/n) sum_i x_i     (consensus distance)
+ *   out[1] = ||xbar||^2
+ *   out[2] = sum_i ||x_i - ref||^2   (0 if ref == NULL)
+ *   out[3] = ||ref||^2               (0 if ref == NULL)
+ *   out[4] = ||m||_F^2               (0 if m == NULL)
+ * Two passes per column: mean first, deviations second. */
+int oracle_stats(int n, int64_t d, const double* x, const double* m, const double* ref, double* out)
+{
+    double cons = 0.0, xbar2 = 0.0, err = 0.0, ref2 = 0.0, m2 = 0.0;
+    for (int64_t c = 0; c < d; ++c) {
+        double mean = 0.0;
+        for (int i = 0; i < n; ++i) mean = mean + x[(int64_t)i * d + c];
+        mean = mean / (double)n;
+        for (int i = 0; i < n; ++i) {
+            double dev = x[(int64_t)i * d + c] - mean;
+            cons = cons + dev * dev;
+            if (ref) {
+                double e = x[(int64_t)i * d + c] - ref[c];
+                err = err + e * e;
+            }
+            if (m) m2 = m2 + m[(int64_t)i * d + c] * m[(int64_t)i * d + c];
+        }
+        xbar2 = xbar2 + mean * mean;
+        if (ref) ref2 = ref2 + ref[c] * ref[c];
+    }
+    out[0] = cons; out[1] = xbar2; out[2] = err; out[3] = ref2; out[4] = m2;
+    return 0;
+}

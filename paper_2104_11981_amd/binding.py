@@ -28,7 +28,7 @@ DL_FLAG_ROW_STOCHASTIC, DL_FLAG_COL_STOCHASTIC, DL_FLAG_SYMMETRIC = 1, 2, 4
 DL_MAX_NODES, DL_MAX_NNZ = 256, 512
 
 EXPORTS = ("topology_build", "decentlam_step", "dmsgd_step", "local_grad_lsq",
-           "local_grad_lsq_workspace", "dl_last_error")
+           "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
 
 class DecentLamError(RuntimeError):
@@ -59,6 +59,11 @@ def _load() -> ctypes.CDLL:
     lib.local_grad_lsq.restype = ctypes.c_int
     lib.local_grad_lsq.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.decentlam_stats_workspace.restype = ctypes.c_size_t
+    lib.decentlam_stats_workspace.argtypes = [ctypes.c_int32, ctypes.c_int64]
+    lib.decentlam_stats.restype = ctypes.c_int
+    lib.decentlam_stats.argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, vp, vp,
+                                    ctypes.c_size_t, vp]
     lib.dl_last_error.restype = ctypes.c_char_p
     lib.dl_last_error.argtypes = []
     return lib
@@ -176,3 +181,30 @@ def local_grad_lsq(A, y, x, g, loss=None, scale: float = 1.0, workspace=None, st
     _check(_lib.local_grad_lsq(A.data_ptr(), y.data_ptr(), px, pg, pl, n, b, d, ldA, ld, scale,
                                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                _stream() if stream is None else stream))
+
+
+def decentlam_stats_workspace(n: int, d: int) -> int:
+    return int(_lib.decentlam_stats_workspace(n, d))
+
+
+def decentlam_stats(x, m=None, ref=None, out=None, workspace=None, stream=None):
+    """Fill `out` (device float64[5]) with [consensus distance, ||xbar||^2, sum_i ||x_i - ref||^2,
+    ||ref||^2, ||m||_F^2]; `workspace` is a uint8 device tensor of decentlam_stats_workspace(n, d) bytes."""
+    px, n, d, ld = _matrix_args(x, "x")
+    pm = 0
+    if m is not None:
+        pm, nm, dm, ldm = _matrix_args(m, "m")
+        if (nm, dm, ldm) != (n, d, ld):
+            raise TypeError("m must share x's shape and row stride")
+    pr = 0
+    if ref is not None:
+        if ref.dtype != torch.float32 or tuple(ref.shape) != (d,) or not ref.is_cuda or not ref.is_contiguous():
+            raise TypeError("ref: need a contiguous float32 device tensor of d elements")
+        pr = ref.data_ptr()
+    if out is None or out.dtype != torch.float64 or out.numel() < 5 or not out.is_cuda or not out.is_contiguous():
+        raise TypeError("out: need a contiguous float64 device tensor of 5 elements")
+    if workspace is None:
+        raise TypeError("workspace: pass a uint8 device tensor (size from decentlam_stats_workspace)")
+    _check(_lib.decentlam_stats(px, pm, pr, n, d, ld, out.data_ptr(), workspace.data_ptr(),
+                                workspace.numel() * workspace.element_size(),
+                                _stream() if stream is None else stream))

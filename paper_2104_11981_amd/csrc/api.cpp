@@ -196,6 +196,35 @@ int local_grad_lsq(const float* A, const float* y, const float* x, float* g, flo
     return launch_lsq(A, y, x, g, loss, n, b, d, ldA, ld, scale, workspace, static_cast<hipStream_t>(stream));
 }
 
+size_t decentlam_stats_workspace(int32_t n, int64_t d) {
+    if (n < 1 || d < 0) return 0;
+    return dl::stats_workspace_bytes(d);
+}
+
+int decentlam_stats(const float* x, const float* m, const float* ref, int32_t n, int64_t d, int64_t ld,
+                    double* out, void* workspace, size_t workspace_bytes, void* stream) {
+    using namespace dl;
+    const char* fn = "decentlam_stats";
+    clear_error();
+    if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
+    if (d < 0) return set_error(DL_EINVAL, "%s: d = %lld, need d >= 0", fn, static_cast<long long>(d));
+    if (ld < d)
+        return set_error(DL_EINVAL, "%s: ld = %lld < d = %lld", fn, static_cast<long long>(ld),
+                         static_cast<long long>(d));
+    if (!out) return set_error(DL_EINVAL, "%s: out must not be NULL", fn);
+    if (d > 0 && !x) return set_error(DL_EINVAL, "%s: x must not be NULL", fn);
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(ref)) & 3u)
+        return set_error(DL_EINVAL, "%s: x, m and ref must be 4-byte aligned", fn);
+    if (reinterpret_cast<uintptr_t>(out) & 7u) return set_error(DL_EINVAL, "%s: out must be 8-byte aligned", fn);
+    const size_t need = stats_workspace_bytes(d);
+    if (!workspace || workspace_bytes < need)
+        return set_error(DL_ECAP, "%s: workspace of %zu bytes needed, %zu given", fn, need,
+                         workspace ? workspace_bytes : size_t{0});
+    if (reinterpret_cast<uintptr_t>(workspace) & 7u)
+        return set_error(DL_EINVAL, "%s: workspace must be 8-byte aligned", fn);
+    return launch_stats(x, m, ref, n, d, ld, out, workspace, static_cast<hipStream_t>(stream));
+}
+
 const char* dl_last_error(void) { return dl::g_error; }
 
 }  // extern "C"

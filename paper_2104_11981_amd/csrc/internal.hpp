@@ -35,4 +35,9 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
                int32_t b, int64_t d, int64_t ldA, int64_t ld, float scale, void* workspace,
                hipStream_t stream);
 
+// Diagnostics (already validated).
+size_t stats_workspace_bytes(int64_t d);
+int launch_stats(const float* x, const float* m, const float* ref, int32_t n, int64_t d, int64_t ld,
+                 double* out, void* workspace, hipStream_t stream);
+
 }  // namespace dl

@@ -1,0 +1,150 @@
+// Diagnostics of the stacked state: consensus distance sum_i ||x_i - xbar||^2, ||xbar||^2,
+// error against a reference vector (the relative-error metric of the appendix "Experimental
+// setting for linear regression" is out[2] / (n * out[3])), and ||m||_F^2.
+//
+// HBM-bound, one pass: a thread owns VEC columns and walks down the n rows (a wave reads
+// 64*VEC contiguous columns of one row per access).  Per column it keeps shifted sums around
+// the first row's value p: s1 = sum_i (x_i - p), s2 = sum_i (x_i - p)^2, so that
+// sum_i (x_i - xbar)^2 = s2 - s1^2 / n without the cancellation of the raw-moment formula.
+// Partial sums go wave shuffle -> LDS -> one slot per workgroup; k_stats_finish adds the
+// slots in a fixed order, so results are reproducible bit for bit.
+#include "internal.hpp"
+
+namespace dl {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kOut = 5;
+typedef float vf4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+template <int VEC>
+__device__ __forceinline__ void load_cols(const float* __restrict__ p, float (&v)[VEC]) {
+    if constexpr (VEC == 4) {
+        const vf4 t = *reinterpret_cast<const vf4*>(p);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else {
+        v[0] = *p;
+    }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void k_stats(const float* __restrict__ x, const float* __restrict__ m,
+                                                     const float* __restrict__ ref, int n, int64_t d,
+                                                     int64_t ld, double* __restrict__ slots) {
+    __shared__ double red[kThreads / 64][kOut];
+    const int64_t c = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * VEC;
+    double acc[kOut] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    if (c < d) {  // d is a multiple of VEC for this launch
+        float pv[VEC], rv[VEC];
+        load_cols<VEC>(x + c, pv);
+        if (ref != nullptr) load_cols<VEC>(ref + c, rv);
+        double s1[VEC], s2[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) s1[v] = s2[v] = 0.0;
+#pragma unroll 4
+        for (int i = 0; i < n; ++i) {
+            float xv[VEC];
+            load_cols<VEC>(x + static_cast<int64_t>(i) * ld + c, xv);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                const double dev = static_cast<double>(xv[v]) - static_cast<double>(pv[v]);
+                s1[v] += dev;
+                s2[v] = __builtin_fma(dev, dev, s2[v]);
+                if (ref != nullptr) {
+                    const double e = static_cast<double>(xv[v]) - static_cast<double>(rv[v]);
+                    acc[2] = __builtin_fma(e, e, acc[2]);
+                }
+            }
+            if (m != nullptr) {
+                float mv[VEC];
+                load_cols<VEC>(m + static_cast<int64_t>(i) * ld + c, mv);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+                    acc[4] = __builtin_fma(static_cast<double>(mv[v]), static_cast<double>(mv[v]), acc[4]);
+            }
+        }
+        const double inv_n = 1.0 / static_cast<double>(n);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            acc[0] += s2[v] - s1[v] * s1[v] * inv_n;
+            const double mean = static_cast<double>(pv[v]) + s1[v] * inv_n;
+            acc[1] = __builtin_fma(mean, mean, acc[1]);
+            if (ref != nullptr) acc[3] = __builtin_fma(static_cast<double>(rv[v]), static_cast<double>(rv[v]), acc[3]);
+        }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int q = 0; q < kOut; ++q) {
+        const double s = wave_sum(acc[q]);
+        if (lane == 0) red[wave][q] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x < kOut) {
+        const int q = threadIdx.x;
+        slots[static_cast<int64_t>(blockIdx.x) * kOut + q] = (red[0][q] + red[1][q]) + (red[2][q] + red[3][q]);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_stats_finish(const double* __restrict__ slots, int64_t count,
+                                                            double* __restrict__ out) {
+    __shared__ double red[kThreads][kOut];
+    double acc[kOut] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int64_t s = threadIdx.x; s < count; s += kThreads) {
+#pragma unroll
+        for (int q = 0; q < kOut; ++q) acc[q] += slots[s * kOut + q];
+    }
+#pragma unroll
+    for (int q = 0; q < kOut; ++q) red[threadIdx.x][q] = acc[q];
+    __syncthreads();
+    for (int half = kThreads / 2; half > 0; half >>= 1) {
+        if (static_cast<int>(threadIdx.x) < half) {
+#pragma unroll
+            for (int q = 0; q < kOut; ++q) red[threadIdx.x][q] += red[threadIdx.x + half][q];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x < kOut) out[threadIdx.x] = red[0][threadIdx.x];
+}
+
+int64_t blocks_for(int64_t cols, int vec) {
+    return (cols + static_cast<int64_t>(kThreads) * vec - 1) / (static_cast<int64_t>(kThreads) * vec);
+}
+
+}  // namespace
+
+size_t stats_workspace_bytes(int64_t d) {
+    // worst case: every column through the 4-byte path, plus one tail block
+    return static_cast<size_t>(blocks_for(d, 1) + 2) * kOut * sizeof(double);
+}
+
+int launch_stats(const float* x, const float* m, const float* ref, int32_t n, int64_t d, int64_t ld,
+                 double* out, void* workspace, hipStream_t stream) {
+    double* slots = static_cast<double*>(workspace);
+    const bool vec4 = (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m) |
+                                          reinterpret_cast<uintptr_t>(ref)) & 15u) == 0;
+    const int64_t body = vec4 ? (d / 4) * 4 : 0;
+    const int64_t tail = d - body;
+    const int64_t nb_body = blocks_for(body, 4), nb_tail = blocks_for(tail, 1);
+    if (nb_body > 0x7fffffffLL || nb_tail > 0x7fffffffLL) return set_error(DL_EINVAL, "stats: d too large");
+    if (nb_body > 0) {
+        hipLaunchKernelGGL(k_stats<4>, dim3(static_cast<unsigned>(nb_body)), dim3(kThreads), 0, stream, x, m, ref,
+                           n, body, ld, slots);
+        if (int rc = check_hip(hipGetLastError(), "stats kernel launch")) return rc;
+    }
+    if (nb_tail > 0) {
+        hipLaunchKernelGGL(k_stats<1>, dim3(static_cast<unsigned>(nb_tail)), dim3(kThreads), 0, stream, x + body,
+                           m ? m + body : nullptr, ref ? ref + body : nullptr, n, tail, ld,
+                           slots + nb_body * kOut);
+        if (int rc = check_hip(hipGetLastError(), "stats kernel launch")) return rc;
+    }
+    hipLaunchKernelGGL(k_stats_finish, dim3(1), dim3(kThreads), 0, stream, slots, nb_body + nb_tail, out);
+    return check_hip(hipGetLastError(), "stats finish kernel launch");
+}
+
+}  // namespace dl

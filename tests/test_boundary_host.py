@@ -159,3 +159,24 @@ def test_lsq_argument_validation():
     assert call(g=0x10010) == P.DL_EALIAS            # g inside A
     assert call(g=0x30000) == P.DL_EALIAS            # g == x
     assert call(loss=0x40000) == P.DL_EALIAS         # loss inside g
+
+
+def test_stats_argument_validation():
+    f = P.raw.decentlam_stats
+    ws = P.decentlam_stats_workspace(4, 100)
+    assert ws > 0 and P.decentlam_stats_workspace(0, 100) == 0
+    ok = dict(x=0x10000, m=0, ref=0, n=4, d=100, ld=100, out=0x20000, wsp=0x30000, wsb=ws)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["x"], a["m"], a["ref"], a["n"], a["d"], a["ld"], a["out"], a["wsp"], a["wsb"], None)
+
+    assert call(n=0) == P.DL_EINVAL
+    assert call(d=-1) == P.DL_EINVAL
+    assert call(ld=99) == P.DL_EINVAL
+    assert call(out=0) == P.DL_EINVAL
+    assert call(x=0) == P.DL_EINVAL
+    assert call(x=0x10002) == P.DL_EINVAL
+    assert call(out=0x20004) == P.DL_EINVAL
+    assert call(wsb=ws - 1) == P.DL_ECAP
+    assert call(wsp=0) == P.DL_ECAP

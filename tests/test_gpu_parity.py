@@ -277,3 +277,53 @@ def test_workload2_trajectory_200_steps(P, oracle, name, ring, algo):
     assert rel <= 1e-4, rel
     rel32 = np.linalg.norm(xg - states[-1][0]) / np.linalg.norm(states[-1][0])
     assert rel32 <= 1e-4, rel32
+
+
+# ---------------------------------------------------------------- diagnostics
+@pytest.mark.parametrize("n,d,pad,off", [(8, 1000, 0, 0), (32, 4099, 1, 0), (5, 7, 0, 0), (16, 2048, 4, 1),
+                                         (1, 300, 0, 0), (64, 513, 3, 0)])
+def test_stats_match_oracle(P, oracle, n, d, pad, off):
+    rng = np.random.default_rng(n + d)
+    x0 = (rng.standard_normal((n, d)) * 0.01 + rng.standard_normal(d) * 5.0).astype(np.float32)  # near consensus
+    m0 = rng.standard_normal((n, d)).astype(np.float32)
+    r0 = rng.standard_normal(d).astype(np.float32)
+    ld = d + pad + off
+    xb = torch.full((n, ld), 9.0, dtype=torch.float32, device="cuda")
+    mb = torch.full((n, ld), 9.0, dtype=torch.float32, device="cuda")
+    x, m = xb[:, off:off + d], mb[:, off:off + d]
+    x.copy_(dev(x0))
+    m.copy_(dev(m0))
+    out = torch.full((5,), -1.0, dtype=torch.float64, device="cuda")
+    ws = torch.empty(P.decentlam_stats_workspace(n, d), dtype=torch.uint8, device="cuda")
+    P.decentlam_stats(x, m, dev(r0), out, ws)
+    ref = oracle.stats(x0, m0, r0)
+    np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-10, atol=1e-18)
+    P.decentlam_stats(x, None, None, out, ws)
+    got = out.cpu().numpy()
+    np.testing.assert_allclose(got[:2], ref[:2], rtol=1e-10, atol=1e-18)
+    assert np.all(got[2:] == 0.0)
+    out2 = torch.empty_like(out)
+    P.decentlam_stats(x, None, None, out2, ws)
+    assert torch.equal(out, out2)                      # fixed summation order
+
+
+def test_stats_track_consensus_during_a_run(P, oracle):
+    """Diagnostics on the device state of a DmSGD run on the ring: the consensus distance the
+    library reports equals the oracle's on the downloaded state."""
+    n, d = 16, 5000
+    topo = P.topology_build(0, n)
+    gen = torch.Generator(device="cuda").manual_seed(3)
+    x = torch.randn((n, d), device="cuda", generator=gen)
+    m = torch.zeros_like(x)
+    out = torch.empty(5, dtype=torch.float64, device="cuda")
+    ws = torch.empty(P.decentlam_stats_workspace(n, d), dtype=torch.uint8, device="cuda")
+    seen = []
+    for k in range(5):
+        g = torch.randn((n, d), device="cuda", generator=gen) * 0.1
+        P.dmsgd_step(x, m, g, topo, 0.05, 0.9, k)
+        P.decentlam_stats(x, m, None, out, ws)
+        got = out.cpu().numpy()
+        ref = oracle.stats(x.cpu().numpy(), m.cpu().numpy())
+        np.testing.assert_allclose(got[[0, 1, 4]], ref[[0, 1, 4]], rtol=1e-10)
+        seen.append(got[0])
+    assert seen[-1] < seen[0]                          # averaging contracts the disagreement

@@ -369,3 +369,26 @@ def test_long_run_limits_match_fixed_point_equations(oracle):
     err = lambda X: np.mean(np.sum((X - xstar) ** 2, axis=1)) / np.sum(xstar ** 2)
     assert abs(err(x_lam) - err(x_ds)) < 1e-12
     assert err(x_dm) > 3 * err(x_lam)          # bias amplified by up to 1/(1-beta)^2
+
+
+# ---------------------------------------------------------------- diagnostics
+def test_stats_against_library_moments(oracle):
+    """Consensus distance is n times the population variance over nodes summed over columns;
+    the other entries are plain squared norms (numpy)."""
+    n, d = 7, 23
+    r = rng(30)
+    x = r.standard_normal((n, d)) * 3 + 100.0      # large common offset: a one-pass formula would cancel
+    m = r.standard_normal((n, d))
+    ref = r.standard_normal(d)
+    out = oracle.stats(x, m, ref)
+    np.testing.assert_allclose(out[0], n * np.var(x, axis=0).sum(), rtol=1e-12)
+    np.testing.assert_allclose(out[1], (x.mean(axis=0) ** 2).sum(), rtol=1e-13)
+    np.testing.assert_allclose(out[2], ((x - ref) ** 2).sum(), rtol=1e-13)
+    np.testing.assert_allclose(out[3], (ref ** 2).sum(), rtol=1e-13)
+    np.testing.assert_allclose(out[4], np.linalg.norm(m, "fro") ** 2, rtol=1e-13)
+    # Pythagoras over nodes: sum_i ||x_i||^2 = consensus + n ||xbar||^2
+    np.testing.assert_allclose((x ** 2).sum(), out[0] + n * out[1], rtol=1e-13)
+    # identical rows: zero consensus distance exactly
+    same = np.tile(r.standard_normal(d), (n, 1))
+    assert oracle.stats(same)[0] < 1e-25          # identical rows: no consensus distance beyond rounding of the mean
+    assert np.all(oracle.stats(x)[2:] == 0.0)
