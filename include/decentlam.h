@@ -114,6 +114,16 @@ int dmsgd_step(float* x, float* m, const float* g,
                float gamma, float beta, int64_t k, void* stream);
 
 /*
+ * dsgd_step -- one iteration of DSGD (eqs. (4)-(5), compact form x <- W (x - gamma g)), the
+ * momentum-free method both algorithms reduce to at beta = 0 and the baseline of the paper's
+ * linear-regression study.  Same conventions; there is no momentum array.  12 bytes per node-element.
+ */
+int dsgd_step(float* x, const float* g,
+              int32_t n, int64_t d, int64_t ld,
+              const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+              float gamma, int64_t k, void* stream);
+
+/*
  * local_grad_lsq -- per-node least-squares gradient (appendix "Experimental
  * setting for linear regression"): for f_i(x) = (scale/2) ||A_i x - y_i||^2,
  *     res_i = A_i x_i - y_i ;  g_i = scale * A_i^T res_i ;  loss_i = (scale/2) ||res_i||^2

@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     DL_MAX_NNZ, DL_MAX_NODES,
     DL_TOPO_EXP_ONEPEER, DL_TOPO_EXP_STATIC, DL_TOPO_RING,
     EXPORTS, LIB_PATH, DecentLamError, Topology,
-    decentlam_stats, decentlam_stats_workspace, decentlam_step, dmsgd_step, last_error, local_grad_lsq, local_grad_lsq_workspace,
+    decentlam_stats, decentlam_stats_workspace, decentlam_step, dmsgd_step, dsgd_step, last_error, local_grad_lsq, local_grad_lsq_workspace,
     make_topology, topology_build,
 )
 from .binding import _lib as raw  # noqa: F401  (the ctypes handle, for tests of the C ABI itself)

@@ -27,7 +27,7 @@ DL_TOPO_RING, DL_TOPO_EXP_STATIC, DL_TOPO_EXP_ONEPEER = 0, 1, 2
 DL_FLAG_ROW_STOCHASTIC, DL_FLAG_COL_STOCHASTIC, DL_FLAG_SYMMETRIC = 1, 2, 4
 DL_MAX_NODES, DL_MAX_NNZ = 256, 512
 
-EXPORTS = ("topology_build", "decentlam_step", "dmsgd_step", "local_grad_lsq",
+EXPORTS = ("topology_build", "decentlam_step", "dmsgd_step", "dsgd_step", "local_grad_lsq",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
 
@@ -54,6 +54,9 @@ def _load() -> ctypes.CDLL:
     for name in ("decentlam_step", "dmsgd_step"):
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = step
+    lib.dsgd_step.restype = ctypes.c_int
+    lib.dsgd_step.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, i32p, f32p,
+                              ctypes.c_int32, ctypes.c_float, ctypes.c_int64, vp]
     lib.local_grad_lsq_workspace.restype = ctypes.c_size_t
     lib.local_grad_lsq_workspace.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64]
     lib.local_grad_lsq.restype = ctypes.c_int
@@ -150,6 +153,17 @@ def decentlam_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 
 def dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
     """One DmSGD iteration in place on device tensors x, m (n x d fp32), asynchronous."""
     _step(_lib.dmsgd_step, x, m, g, topo, gamma, beta, k, stream)
+
+
+def dsgd_step(x, g, topo: Topology, gamma: float, k: int = 0, stream=None):
+    """One DSGD iteration x <- W (x - gamma g) in place on the device tensor x, asynchronous."""
+    px, n, d, ld = _matrix_args(x, "x")
+    pg, ng, dg, ldg = _matrix_args(g, "g")
+    if (ng, dg, ldg) != (n, d, ld):
+        raise TypeError("x and g must share shape and row stride")
+    if topo.n != n:
+        raise DecentLamError(DL_ETOPO, f"topology has {topo.n} nodes, arrays have {n} rows")
+    _check(_lib.dsgd_step(px, pg, n, d, ld, *topo._args(), gamma, k, _stream() if stream is None else stream))
 
 
 def local_grad_lsq_workspace(n: int, b: int, d: int) -> int:

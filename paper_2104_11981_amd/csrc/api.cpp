@@ -109,7 +109,8 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const float* g, in
     if (int rc = pack_phase(fn, n, row_ptr, col_idx, w, static_cast<int32_t>(k % period), &topo)) return rc;
 
     if (d == 0) return DL_OK;
-    if (!x || !m || !g) return set_error(DL_EINVAL, "%s: x, m and g must not be NULL", fn);
+    const bool uses_m = algo != ALGO_DSGD;
+    if (!x || !g || (uses_m && !m)) return set_error(DL_EINVAL, "%s: x, m and g must not be NULL", fn);
     if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(g)) & 3u)
         return set_error(DL_EINVAL, "%s: x, m and g must be 4-byte aligned", fn);
     const Span sx = span_of(x, n, d, ld), sm = span_of(m, n, d, ld), sg = span_of(g, n, d, ld);
@@ -122,7 +123,7 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const float* g, in
         const int64_t off = ((delta % ld) + ld) % ld;  // column offset between the two views
         return !(off >= d && ld - off >= d);
     };
-    if (shares(x, sx, m, sm) || shares(x, sx, g, sg) || shares(m, sm, g, sg))
+    if ((uses_m && (shares(x, sx, m, sm) || shares(m, sm, g, sg))) || shares(x, sx, g, sg))
         return set_error(DL_EALIAS, "%s: x, m and g must not overlap", fn);
 
     return launch_step(algo, x, m, g, n, d, ld, topo, gamma, beta, static_cast<hipStream_t>(stream));
@@ -145,6 +146,12 @@ int dmsgd_step(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t
                float gamma, float beta, int64_t k, void* stream) {
     return dl::step_entry("dmsgd_step", dl::ALGO_DMSGD, x, m, g, n, d, ld, row_ptr, col_idx, w, period,
                           gamma, beta, k, stream);
+}
+
+int dsgd_step(float* x, const float* g, int32_t n, int64_t d, int64_t ld, const int32_t* row_ptr,
+              const int32_t* col_idx, const float* w, int32_t period, float gamma, int64_t k, void* stream) {
+    return dl::step_entry("dsgd_step", dl::ALGO_DSGD, x, nullptr, g, n, d, ld, row_ptr, col_idx, w, period,
+                          gamma, 0.0f, k, stream);
 }
 
 size_t local_grad_lsq_workspace(int32_t n, int32_t b, int64_t d) {

@@ -19,7 +19,7 @@ struct PhaseArgs {
 };
 static_assert(sizeof(PhaseArgs) <= 3200, "kernel-argument segment is 4 KiB");
 
-enum Algo { ALGO_DECENTLAM = 0, ALGO_DMSGD = 1 };
+enum Algo { ALGO_DECENTLAM = 0, ALGO_DMSGD = 1, ALGO_DSGD = 2 };
 
 int set_error(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 int check_hip(hipError_t e, const char* what);

@@ -86,7 +86,7 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
 
 // VEC    columns per lane (width of the global accesses: 4, 8 or 16 bytes)
 // RPT    rows per thread; WAVES wavefronts per workgroup: the kernel covers n <= WAVES * RPT nodes
-// ALGO   ALGO_DECENTLAM or ALGO_DMSGD
+// ALGO   ALGO_DECENTLAM, ALGO_DMSGD or ALGO_DSGD (x <- W (x - gamma g); m is not touched)
 template <int VEC, int RPT, int WAVES, int ALGO>
 __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, float* __restrict__ m,
                                                       const float* __restrict__ g, int64_t d, int64_t ld,
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
             const int64_t at = static_cast<int64_t>(i) * ld + c;
             load_vec<VEC>(x + at, xr[r]);
             load_vec<VEC>(g + at, gr[r]);
-            load_vec<VEC>(m + at, mr[r]);
+            if constexpr (ALGO != ALGO_DSGD) load_vec<VEC>(m + at, mr[r]);
         }
     }
     // neighbour list: kernel arguments -> LDS table (one entry per thread and round)
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
         const int i = wave + WAVES * r;
         if (i < n && live) {
             double* slot = lds + i * TC + lane * VEC;
-            if constexpr (ALGO == ALGO_DECENTLAM) {
+            if constexpr (ALGO == ALGO_DECENTLAM || ALGO == ALGO_DSGD) {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v)
                     slot[v] = static_cast<double>(xr[r][v]) - gamma * static_cast<double>(gr[r][v]);
@@ -262,7 +262,7 @@ int launch_step(Algo algo, float* x, float* m, const float* g, int32_t n, int64_
     for (; vec > 1; vec >>= 1) {
         const uintptr_t mask = static_cast<uintptr_t>(vec) - 1;
         const uintptr_t ax = (reinterpret_cast<uintptr_t>(x) >> 2) & mask;
-        const uintptr_t am = (reinterpret_cast<uintptr_t>(m) >> 2) & mask;
+        const uintptr_t am = m ? (reinterpret_cast<uintptr_t>(m) >> 2) & mask : ax;
         const uintptr_t ag = (reinterpret_cast<uintptr_t>(g) >> 2) & mask;
         if (ax == am && ax == ag && (ld & static_cast<int64_t>(mask)) == 0) {
             head = static_cast<int64_t>((vec - ax) & mask);
@@ -277,6 +277,8 @@ int launch_step(Algo algo, float* x, float* m, const float* g, int32_t n, int64_
     auto run = [&](int v, int64_t c0, int64_t cols) {
         if (algo == ALGO_DECENTLAM)
             return launch_cols<ALGO_DECENTLAM>(v, x + c0, m + c0, g + c0, n, cols, ld, topo, gamma, beta, stream);
+        if (algo == ALGO_DSGD)
+            return launch_cols<ALGO_DSGD>(v, x + c0, nullptr, g + c0, n, cols, ld, topo, gamma, beta, stream);
         return launch_cols<ALGO_DMSGD>(v, x + c0, m + c0, g + c0, n, cols, ld, topo, gamma, beta, stream);
     };
     if (int rc = run(vec, head, body)) return rc;   // aligned body first: it is the bulk

@@ -180,3 +180,14 @@ def test_stats_argument_validation():
     assert call(out=0x20004) == P.DL_EINVAL
     assert call(wsb=ws - 1) == P.DL_ECAP
     assert call(wsp=0) == P.DL_ECAP
+
+
+def test_dsgd_argument_validation():
+    t = P.topology_build(0, 4)
+    f = lambda **kw: P.raw.dsgd_step(kw.get("x"), kw.get("g"), kw.get("n", 4), kw.get("d", 0), kw.get("ld", 0),
+                                     *t._args(), kw.get("gamma", 0.1), kw.get("k", 0), None)
+    assert f() == P.DL_OK
+    assert f(gamma=0.0) == P.DL_EINVAL
+    assert f(k=-1) == P.DL_EINVAL
+    assert f(d=8, ld=8) == P.DL_EINVAL
+    assert f(d=8, ld=8, x=4096, g=4096 + 32) == P.DL_EALIAS

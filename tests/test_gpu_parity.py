@@ -327,3 +327,33 @@ def test_stats_track_consensus_during_a_run(P, oracle):
         np.testing.assert_allclose(got[[0, 1, 4]], ref[[0, 1, 4]], rtol=1e-10)
         seen.append(got[0])
     assert seen[-1] < seen[0]                          # averaging contracts the disagreement
+
+
+# ---------------------------------------------------------------- DSGD
+@pytest.mark.parametrize("kind,n,d,pad,off", [(0, 8, 1000, 0, 0), (1, 32, 1030, 2, 0), (2, 64, 517, 3, 0),
+                                              (0, 16, 2051, 1, 3), (0, 100, 333, 0, 0), (0, 1, 70, 0, 0)])
+def test_dsgd_step_matches_oracle(P, oracle, kind, n, d, pad, off):
+    gamma = float(np.float32(0.05))
+    topo, otopo = topo_pair(P, oracle, kind, n)
+    rng = np.random.default_rng(77 + n + d)
+    x0 = rng.standard_normal((n, d)).astype(np.float32)
+    ld = d + pad + off
+    xb = torch.full((n, ld), 5.0, dtype=torch.float32, device="cuda")
+    gb = torch.full((n, ld), 5.0, dtype=torch.float32, device="cuda")
+    x, g = xb[:, off:off + d], gb[:, off:off + d]
+    x.copy_(dev(x0))
+    xs = x0.astype(np.float64)
+    for k in range(4):
+        gk = rng.standard_normal((n, d)).astype(np.float32)
+        g.copy_(dev(gk))
+        P.dsgd_step(x, g, topo, gamma, k)
+        xs = oracle.dsgd_step(xs, gk, otopo, gamma, k).astype(np.float32).astype(np.float64)
+        check_elementwise(x.cpu().numpy(), xs, f"x after iteration {k}")
+    full = xb.cpu().numpy()
+    assert np.all(full[:, :off] == 5.0) and np.all(full[:, off + d:] == 5.0)
+    # beta = 0 in the momentum kernels is the same map
+    xa, ma = dev(x0), torch.zeros((n, d), dtype=torch.float32, device="cuda")
+    xd = dev(x0)
+    P.decentlam_step(xa, ma, g.contiguous(), topo, gamma, 0.0, 0)
+    P.dsgd_step(xd, g.contiguous(), topo, gamma, 0)
+    check_elementwise(xa.cpu().numpy(), xd.cpu().numpy().astype(np.float64), "DecentLaM(beta=0) vs DSGD")
