@@ -46,7 +46,11 @@ typedef enum {
 typedef enum {
     DL_TOPO_RING = 0,        /* N_i = {i, i-1, i+1}                    (appendix "Network topologies") */
     DL_TOPO_EXP_STATIC = 1,  /* N_i = {i} U {i + 2^t}, t = 0..tau-1    (exponential graph, directed)   */
-    DL_TOPO_EXP_ONEPEER = 2  /* phase p: N_i = {i, i + 2^p}, period tau (one-peer exponential graph)   */
+    DL_TOPO_EXP_ONEPEER = 2, /* phase p: N_i = {i, i + 2^p}, period tau (one-peer exponential graph)   */
+    DL_TOPO_EXP_SYM = 3,     /* N_i = {i} U {i + 2^t, i - 2^t}          (symmetric exponential graph)   */
+    DL_TOPO_MESH = 4,        /* R x C grid, 4-neighbourhood, no wrap-around; R = largest divisor of n
+                                not above sqrt(n), node i at (i / C, i % C)                             */
+    DL_TOPO_BIPARTITE_MATCH = 5 /* per phase a seeded random perfect matching (topology_build_ex)      */
 } dl_topo_kind;             /* tau = floor(log2(n-1)) + 1; all indices mod n */
 
 /* properties reported by topology_build (every phase has the property) */
@@ -63,9 +67,12 @@ typedef enum {
  * (appendix "Network topologies"; one-peer graph: Introduction).
  *
  * Host-only, integer work.  Row order: self first, then ring: i-1, i+1;
- * exponential: ascending hop.  Duplicates (tiny n) are dropped keeping the first
- * occurrence.  Weights are uniform, (float)1 / (float)|N_i| -- what the
- * Metropolis-Hastings rule the paper cites yields on these regular graphs.
+ * exponential: ascending hop (symmetric: +2^t before -2^t); mesh: up, down, left, right;
+ * match: the partner.  Duplicates (tiny n) are dropped keeping the first occurrence.
+ * Weights: the undirected kinds follow the Metropolis-Hastings rule the paper cites,
+ * w_ij = 1 / (1 + max(deg_i, deg_j)), w_ii = 1 - sum_j w_ij (deg counts neighbours other than
+ * i); where all neighbours of i share its degree this is (float)1 / (float)|N_i| and is
+ * evaluated as such.  The two directed exponential kinds carry the uniform 1 / |N_i|.
  *
  *   row_ptr  [out] period*(n+1) absolute offsets into col_idx / w, phase-major.
  *                  Pass NULL (with col_idx = w = NULL) to query sizes only.
@@ -78,6 +85,30 @@ int topology_build(int kind, int32_t n,
                    int32_t* row_ptr, int64_t row_ptr_cap,
                    int32_t* col_idx, float* w, int64_t nnz_cap,
                    int32_t* period_out, int64_t* nnz_out, uint32_t* flags_out);
+
+/*
+ * topology_build_ex -- the same with the parameters of the randomised kind.
+ * DL_TOPO_BIPARTITE_MATCH (appendix "Network topologies", last item): `phases` matchings,
+ * iteration k uses matching k mod phases.  Matching p comes from a Fisher-Yates shuffle of
+ * 0..n-1 driven by splitmix64 seeded with seed ^ (0xD1B54A32D192ED03 * (p + 1)) (from the
+ * top index t = n-1 down to 1, swap with index next() % (t + 1)); shuffled position q is
+ * paired with position q + n/2; with odd n the last position stays alone.  Every node derives
+ * the same matching from the same seed, which is what the paper asks for.  Weights 1/2, 1/2.
+ * Other kinds ignore seed and phases.  Additional error: DL_EINVAL if phases < 1 for the match.
+ */
+int topology_build_ex(int kind, int32_t n, uint64_t seed, int32_t phases,
+                      int32_t* row_ptr, int64_t row_ptr_cap,
+                      int32_t* col_idx, float* w, int64_t nnz_cap,
+                      int32_t* period_out, int64_t* nnz_out, uint32_t* flags_out);
+
+/*
+ * topology_metropolis -- Metropolis-Hastings weights (the rule above) for a caller-supplied
+ * undirected graph: one phase in CSR form, every row containing i itself, j in N_i iff i in N_j.
+ *   w [out] one weight per entry of col_idx, in the caller's order.   flags_out may be NULL.
+ * Errors: DL_EINVAL, DL_ETOPO (empty row, index out of range, duplicate, missing self, not undirected).
+ */
+int topology_metropolis(int32_t n, const int32_t* row_ptr, const int32_t* col_idx,
+                        float* w, uint32_t* flags_out);
 
 /*
  * decentlam_step -- one iteration of Algorithm 2 (DecentLaM) for all nodes:

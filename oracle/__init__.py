@@ -23,7 +23,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "decentlam_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
-RING, EXP_STATIC, EXP_ONEPEER = 0, 1, 2
+RING, EXP_STATIC, EXP_ONEPEER, EXP_SYM, MESH, BIPARTITE_MATCH = 0, 1, 2, 3, 4, 5
 
 
 def build(force: bool = False) -> str:
@@ -49,7 +49,8 @@ def _load():
         f32p = ctypes.POINTER(ctypes.c_float)
         f64p = ctypes.POINTER(ctypes.c_double)
         _lib.oracle_num_threads.restype = ctypes.c_int
-        _lib.oracle_topology.argtypes = [ctypes.c_int, ctypes.c_int, i32p, i64p, i32p, i32p, f32p]
+        _lib.oracle_topology.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_uint64, ctypes.c_int, i32p, i64p,
+                                         i32p, i32p, f32p]
         _lib.oracle_dsgd_step.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, i32p, i32p, f32p,
                                           ctypes.c_double, ctypes.c_int64, f64p, f64p, f64p]
         step = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, i32p, i32p, f32p, ctypes.c_double,
@@ -89,17 +90,18 @@ class Topology:
         return W
 
 
-def topology(kind: int, n: int) -> Topology:
+def topology(kind: int, n: int, seed: int = 0, phases: int = 1) -> Topology:
+    """Neighbour lists and weights of one of the paper's topologies (seed, phases: random match only)."""
     lib = _load()
     period = ctypes.c_int32(0)
     nnz = ctypes.c_int64(0)
-    rc = lib.oracle_topology(kind, n, ctypes.byref(period), ctypes.byref(nnz), None, None, None)
+    rc = lib.oracle_topology(kind, n, seed, phases, ctypes.byref(period), ctypes.byref(nnz), None, None, None)
     if rc:
         raise ValueError(f"oracle_topology({kind}, {n}) -> {rc}")
     row_ptr = np.zeros(period.value * (n + 1), dtype=np.int32)
     col_idx = np.zeros(nnz.value, dtype=np.int32)
     w = np.zeros(nnz.value, dtype=np.float32)
-    rc = lib.oracle_topology(kind, n, ctypes.byref(period), ctypes.byref(nnz),
+    rc = lib.oracle_topology(kind, n, seed, phases, ctypes.byref(period), ctypes.byref(nnz),
                              _p(row_ptr, ctypes.c_int32), _p(col_idx, ctypes.c_int32),
                              _p(w, ctypes.c_float))
     assert rc == 0

@@ -32,7 +32,8 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_RING = 0, ORACLE_EXP_STATIC = 1, ORACLE_EXP_ONEPEER = 2 };
+enum { ORACLE_RING = 0, ORACLE_EXP_STATIC = 1, ORACLE_EXP_ONEPEER = 2, ORACLE_EXP_SYM = 3,
+       ORACLE_MESH = 4, ORACLE_BIPARTITE_MATCH = 5 };
 
 int oracle_num_threads(void)
 {
@@ -61,55 +62,135 @@ static int push_unique(int32_t* row, int len, int32_t j)
     return len + 1;
 }
 
+static int wrap(int j, int n) { return ((j % n) + n) % n; }
+
+/* splitmix64, the published 64-bit mixing generator; drives the random matching. */
+static uint64_t splitmix64(uint64_t* state)
+{
+    uint64_t z = (*state += 0x9E3779B97F4A7C15ULL);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+/* Partner of every node in the bipartite random match of phase p ("all nodes are evenly divided
+ * into two groups randomly per iteration; communication only within each pair"; same seed on all
+ * nodes).  Recipe (an interface both sides must share, like a file format): Fisher-Yates shuffle
+ * of 0..n-1 from the top with index splitmix64() % (t+1), generator seeded with
+ * seed ^ (0xD1B54A32D192ED03 * (p+1)); shuffled position q pairs with position q + n/2; an odd
+ * node out stays alone (partner = itself). */
+static void match_partners(int n, uint64_t seed, int p, int32_t* partner)
+{
+    int32_t* perm = (int32_t*)malloc(sizeof(int32_t) * (size_t)n);
+    for (int i = 0; i < n; ++i) perm[i] = i;
+    uint64_t state = seed ^ (0xD1B54A32D192ED03ULL * ((uint64_t)p + 1));
+    for (int t = n - 1; t > 0; --t) {
+        int q = (int)(splitmix64(&state) % (uint64_t)(t + 1));
+        int32_t tmp = perm[t]; perm[t] = perm[q]; perm[q] = tmp;
+    }
+    for (int i = 0; i < n; ++i) partner[i] = i;
+    for (int q = 0; q < n / 2; ++q) {
+        partner[perm[q]] = perm[q + n / 2];
+        partner[perm[q + n / 2]] = perm[q];
+    }
+    free(perm);
+}
+
 /* Neighbour set of node i in phase p, self first.
- *   ring:              i, i-1, i+1 (mod n)               -- "Ring" item
- *   static exponential: i, i+2^0, i+2^1, ... (mod n)     -- exponential-graph item
- *   one-peer exponential: i, i+2^p (mod n)               -- one neighbour per iteration (Introduction)
+ *   ring:                 i, i-1, i+1 (mod n)                          -- "Ring" item
+ *   static exponential:   i, i+2^0, i+2^1, ... (mod n)                 -- exponential-graph item, directed reading
+ *   one-peer exponential: i, i+2^p (mod n)                             -- one neighbour per iteration (Introduction)
+ *   symmetric exponential: i, i+2^0, i-2^0, i+2^1, i-2^1, ... (mod n)  -- "Symmetric Exponential Graph" item
+ *   mesh:                 R x C grid (R the largest divisor of n with R*R <= n, node i at row i/C,
+ *                         column i%C), neighbours up, down, left, right, no wrap-around -- "Mesh" item;
+ *                         the paper's drawing of it is lost, this is the reading taken
+ *   bipartite match:      i and its partner of this phase                -- "Bipartite Random Match" item
  * Reading: node i *receives from* the listed nodes. */
-static int neighbours(int kind, int n, int p, int i, int32_t* row)
+static int neighbours(int kind, int n, int p, int i, const int32_t* partner, int32_t* row)
 {
     int len = 0;
     len = push_unique(row, len, i);
     if (kind == ORACLE_RING) {
-        len = push_unique(row, len, ((i - 1) % n + n) % n);
-        len = push_unique(row, len, (i + 1) % n);
+        len = push_unique(row, len, wrap(i - 1, n));
+        len = push_unique(row, len, wrap(i + 1, n));
     } else if (kind == ORACLE_EXP_STATIC) {
         int tau = hop_count(n);
-        for (int t = 0; t < tau; ++t) len = push_unique(row, len, (i + (1 << t)) % n);
+        for (int t = 0; t < tau; ++t) len = push_unique(row, len, wrap(i + (1 << t), n));
     } else if (kind == ORACLE_EXP_ONEPEER) {
-        if (n > 1) len = push_unique(row, len, (i + (1 << p)) % n);
+        if (n > 1) len = push_unique(row, len, wrap(i + (1 << p), n));
+    } else if (kind == ORACLE_EXP_SYM) {
+        int tau = hop_count(n);
+        for (int t = 0; t < tau; ++t) {
+            len = push_unique(row, len, wrap(i + (1 << t), n));
+            len = push_unique(row, len, wrap(i - (1 << t), n));
+        }
+    } else if (kind == ORACLE_MESH) {
+        int R = 1;
+        for (int r = 1; r * r <= n; ++r)
+            if (n % r == 0) R = r;
+        int C = n / R, a = i / C, b = i % C;
+        if (a > 0) len = push_unique(row, len, i - C);
+        if (a + 1 < R) len = push_unique(row, len, i + C);
+        if (b > 0) len = push_unique(row, len, i - 1);
+        if (b + 1 < C) len = push_unique(row, len, i + 1);
+    } else if (kind == ORACLE_BIPARTITE_MATCH) {
+        len = push_unique(row, len, partner[i]);
     }
     return len;
 }
 
-/* Sizes first (row_ptr == NULL), then fill.  Weights are uniform over the
- * neighbour set, 1/|N_i| evaluated in fp32: on a regular graph this is what the
- * Metropolis-Hastings rule the paper cites gives.  row_ptr holds
- * period*(n+1) absolute offsets into col_idx / w (phase-major). */
-int oracle_topology(int kind, int n, int32_t* period_out, int64_t* nnz_out,
+/* Sizes first (row_ptr == NULL), then fill.  row_ptr holds period*(n+1) absolute offsets into
+ * col_idx / w (phase-major).
+ * Weights: Metropolis-Hastings rule (the paper cites it for all its topologies without printing
+ * it; reading taken: w_ij = 1/(1 + max(deg_i, deg_j)) for j != i, w_ii = 1 - sum_j w_ij, deg =
+ * neighbours other than the node itself).  Where every neighbour of i has i's degree the rule
+ * gives 1/|N_i| for all entries and is evaluated as (float)1/(float)|N_i|.  The two directed
+ * exponential graphs are not undirected graphs, so the rule does not apply; they carry the
+ * uniform 1/|N_i|. */
+int oracle_topology(int kind, int n, uint64_t seed, int phases, int32_t* period_out, int64_t* nnz_out,
                     int32_t* row_ptr, int32_t* col_idx, float* w)
 {
-    if (n < 1 || kind < 0 || kind > 2) return -1;
+    if (n < 1 || kind < 0 || kind > 5) return -1;
     int period = 1;
     if (kind == ORACLE_EXP_ONEPEER && n > 1) period = hop_count(n);
+    if (kind == ORACLE_BIPARTITE_MATCH) {
+        if (phases < 1) return -1;
+        period = phases;
+    }
+    int undirected = (kind != ORACLE_EXP_STATIC && kind != ORACLE_EXP_ONEPEER);
     int32_t* tmp = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n + 2));
-    if (!tmp) return -2;
+    int32_t* other = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n + 2));
+    int32_t* partner = (int32_t*)malloc(sizeof(int32_t) * (size_t)n);
+    int32_t* deg = (int32_t*)malloc(sizeof(int32_t) * (size_t)n);
+    if (!tmp || !other || !partner || !deg) { free(tmp); free(other); free(partner); free(deg); return -2; }
     int64_t nnz = 0;
     for (int p = 0; p < period; ++p) {
+        if (kind == ORACLE_BIPARTITE_MATCH) match_partners(n, seed, p, partner);
+        for (int i = 0; i < n; ++i) deg[i] = neighbours(kind, n, p, i, partner, tmp) - 1;
         for (int i = 0; i < n; ++i) {
-            int len = neighbours(kind, n, p, i, tmp);
+            int len = neighbours(kind, n, p, i, partner, tmp);
             if (row_ptr) {
                 row_ptr[p * (n + 1) + i] = (int32_t)nnz;
+                int same_degree = 1;
+                for (int t = 1; t < len; ++t) same_degree = same_degree && (deg[tmp[t]] == deg[i]);
+                double rest = 0.0;
                 for (int t = 0; t < len; ++t) {
                     col_idx[nnz + t] = tmp[t];
-                    w[nnz + t] = 1.0f / (float)len;
+                    if (!undirected || same_degree) {
+                        w[nnz + t] = 1.0f / (float)len;
+                    } else if (t > 0) {
+                        int big = deg[i] > deg[tmp[t]] ? deg[i] : deg[tmp[t]];
+                        w[nnz + t] = 1.0f / (float)(1 + big);
+                        rest = rest + (double)w[nnz + t];
+                    }
                 }
+                if (undirected && !same_degree) w[nnz] = (float)(1.0 - rest);
             }
             nnz += len;
         }
         if (row_ptr) row_ptr[p * (n + 1) + n] = (int32_t)nnz;
     }
-    free(tmp);
+    free(tmp); free(other); free(partner); free(deg);
     *period_out = period;
     *nnz_out = nnz;
     return 0;

@@ -24,10 +24,11 @@ LIB_PATH = os.path.join(_HERE, "libdecentlam.so")
 
 DL_OK, DL_EINVAL, DL_ETOPO, DL_ECAP, DL_EHIP, DL_EALIAS = 0, -1, -2, -3, -4, -5
 DL_TOPO_RING, DL_TOPO_EXP_STATIC, DL_TOPO_EXP_ONEPEER = 0, 1, 2
+DL_TOPO_EXP_SYM, DL_TOPO_MESH, DL_TOPO_BIPARTITE_MATCH = 3, 4, 5
 DL_FLAG_ROW_STOCHASTIC, DL_FLAG_COL_STOCHASTIC, DL_FLAG_SYMMETRIC = 1, 2, 4
 DL_MAX_NODES, DL_MAX_NNZ = 256, 512
 
-EXPORTS = ("topology_build", "decentlam_step", "dmsgd_step", "dsgd_step", "local_grad_lsq",
+EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decentlam_step", "dmsgd_step", "dsgd_step", "local_grad_lsq",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
 
@@ -49,6 +50,12 @@ def _load() -> ctypes.CDLL:
     lib.topology_build.argtypes = [ctypes.c_int, ctypes.c_int32, i32p, ctypes.c_int64, i32p, f32p,
                                    ctypes.c_int64, i32p, ctypes.POINTER(ctypes.c_int64),
                                    ctypes.POINTER(ctypes.c_uint32)]
+    lib.topology_build_ex.restype = ctypes.c_int
+    lib.topology_build_ex.argtypes = [ctypes.c_int, ctypes.c_int32, ctypes.c_uint64, ctypes.c_int32, i32p,
+                                      ctypes.c_int64, i32p, f32p, ctypes.c_int64, i32p,
+                                      ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_uint32)]
+    lib.topology_metropolis.restype = ctypes.c_int
+    lib.topology_metropolis.argtypes = [ctypes.c_int32, i32p, i32p, f32p, ctypes.POINTER(ctypes.c_uint32)]
     step = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, i32p, f32p,
             ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_int64, vp]
     for name in ("decentlam_step", "dmsgd_step"):
@@ -101,18 +108,34 @@ class Topology:
                 self.period)
 
 
-def topology_build(kind: int, n: int) -> Topology:
+def topology_build(kind: int, n: int, seed: int = 0, phases: int = 1) -> Topology:
+    """topology_build (or topology_build_ex for the seeded bipartite random match)."""
     period, nnz, flags = ctypes.c_int32(0), ctypes.c_int64(0), ctypes.c_uint32(0)
-    _check(_lib.topology_build(kind, n, None, 0, None, None, 0, ctypes.byref(period),
-                               ctypes.byref(nnz), ctypes.byref(flags)))
+    if kind == DL_TOPO_BIPARTITE_MATCH:
+        call = lambda *a: _lib.topology_build_ex(kind, n, seed, phases, *a)
+    else:
+        call = lambda *a: _lib.topology_build(kind, n, *a)
+    _check(call(None, 0, None, None, 0, ctypes.byref(period), ctypes.byref(nnz), ctypes.byref(flags)))
     row_ptr = np.zeros(period.value * (n + 1), dtype=np.int32)
     col_idx = np.zeros(nnz.value, dtype=np.int32)
     w = np.zeros(nnz.value, dtype=np.float32)
-    _check(_lib.topology_build(kind, n, row_ptr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
-                               row_ptr.size, col_idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
-                               w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), col_idx.size,
-                               ctypes.byref(period), ctypes.byref(nnz), ctypes.byref(flags)))
+    _check(call(row_ptr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), row_ptr.size,
+                col_idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), col_idx.size,
+                ctypes.byref(period), ctypes.byref(nnz), ctypes.byref(flags)))
     return Topology(n, period.value, row_ptr, col_idx, w, flags.value)
+
+
+def topology_metropolis(n: int, row_ptr, col_idx) -> Topology:
+    """Metropolis-Hastings weights for a caller-supplied undirected one-phase graph."""
+    row_ptr = np.ascontiguousarray(row_ptr, np.int32)
+    col_idx = np.ascontiguousarray(col_idx, np.int32)
+    w = np.zeros(col_idx.size, dtype=np.float32)
+    flags = ctypes.c_uint32(0)
+    _check(_lib.topology_metropolis(n, row_ptr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                    col_idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                    w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), ctypes.byref(flags)))
+    return Topology(n, 1, row_ptr, col_idx, w, flags.value)
 
 
 def make_topology(n: int, row_ptr, col_idx, w, period: int = 1) -> Topology:

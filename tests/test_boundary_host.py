@@ -26,21 +26,22 @@ def test_library_exports_every_declared_symbol():
         assert getattr(lib, name) is not None
 
 
-@pytest.mark.parametrize("kind", [0, 1, 2])
+@pytest.mark.parametrize("kind", [0, 1, 2, 3, 4, 5])
 @pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 6, 7, 8, 9, 15, 16, 17, 31, 32, 33, 64, 100, 128, 256])
 def test_topology_build_matches_oracle_bit_exactly(oracle, kind, n):
-    ours = P.topology_build(kind, n)
-    ref = oracle.topology(kind, n)
+    ours = P.topology_build(kind, n, seed=2104 + n, phases=5)
+    ref = oracle.topology(kind, n, seed=2104 + n, phases=5)
     assert ours.period == ref.period
     np.testing.assert_array_equal(ours.row_ptr, ref.row_ptr)
     np.testing.assert_array_equal(ours.col_idx, ref.col_idx)
     np.testing.assert_array_equal(ours.w.view(np.uint32), ref.w.view(np.uint32))  # fp32 bit patterns
 
 
-@pytest.mark.parametrize("kind,n", [(0, 1), (0, 2), (0, 5), (1, 8), (1, 12), (2, 8), (2, 6)])
+@pytest.mark.parametrize("kind,n", [(0, 1), (0, 2), (0, 5), (1, 8), (1, 12), (2, 8), (2, 6), (3, 8), (3, 12),
+                                    (4, 6), (4, 12), (4, 7), (5, 8), (5, 9)])
 def test_topology_flags_describe_the_matrix(oracle, kind, n):
-    ours = P.topology_build(kind, n)
-    ref = oracle.topology(kind, n)
+    ours = P.topology_build(kind, n, seed=3, phases=4)
+    ref = oracle.topology(kind, n, seed=3, phases=4)
     sym = all(np.array_equal(ref.dense(p), ref.dense(p).T) for p in range(ref.period))
     assert bool(ours.flags & P.DL_FLAG_SYMMETRIC) == sym
     for p in range(ref.period):
@@ -191,3 +192,27 @@ def test_dsgd_argument_validation():
     assert f(k=-1) == P.DL_EINVAL
     assert f(d=8, ld=8) == P.DL_EINVAL
     assert f(d=8, ld=8, x=4096, g=4096 + 32) == P.DL_EALIAS
+
+
+def test_topology_build_ex_and_metropolis_errors(oracle):
+    period, nnz = ctypes.c_int32(), ctypes.c_int64()
+    assert P.raw.topology_build(P.DL_TOPO_BIPARTITE_MATCH, 8, None, 0, None, None, 0, ctypes.byref(period),
+                                ctypes.byref(nnz), None) == P.DL_EINVAL       # needs seed and phases
+    assert P.raw.topology_build_ex(P.DL_TOPO_BIPARTITE_MATCH, 8, 1, 0, None, 0, None, None, 0,
+                                   ctypes.byref(period), ctypes.byref(nnz), None) == P.DL_EINVAL
+    assert P.raw.topology_build_ex(6, 8, 1, 1, None, 0, None, None, 0, ctypes.byref(period),
+                                   ctypes.byref(nnz), None) == P.DL_EINVAL
+    # Metropolis weights for a caller's graph: a path 0 - 1 - 2 (degrees 1, 2, 1)
+    t = P.topology_metropolis(3, [0, 2, 5, 7], [0, 1, 0, 1, 2, 2, 1])
+    np.testing.assert_allclose(t.w, [2 / 3, 1 / 3, 1 / 3, 1 / 3, 1 / 3, 2 / 3, 1 / 3], atol=6e-8)
+    assert t.flags == P.DL_FLAG_ROW_STOCHASTIC | P.DL_FLAG_COL_STOCHASTIC | P.DL_FLAG_SYMMETRIC
+    # on the mesh it reproduces topology_build, whatever the order inside the rows
+    mesh = P.topology_build(P.DL_TOPO_MESH, 12)
+    again = P.topology_metropolis(12, mesh.row_ptr, mesh.col_idx)
+    np.testing.assert_array_equal(again.w.view(np.uint32), mesh.w.view(np.uint32))
+    for bad_rows, needle in (([0, 1, 3, 4], [0, 1, 2, 2]), "reverse"), (([0, 2, 4, 5], [1, 2, 1, 0, 2]), "itself"), \
+            (([0, 2, 2, 3], [0, 1, 2]), "empty"), (([0, 3, 5, 6], [0, 1, 1, 1, 0, 2]), "twice"), \
+            (([0, 2, 4, 5], [0, 5, 1, 0, 2]), "outside"):
+        with pytest.raises(P.DecentLamError) as e:
+            P.topology_metropolis(3, *bad_rows)
+        assert e.value.status == P.DL_ETOPO and needle in str(e.value), (needle, str(e.value))

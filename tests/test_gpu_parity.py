@@ -40,8 +40,8 @@ def check_elementwise(gpu, ref, what):
 
 
 def topo_pair(P, oracle, kind, n):
-    t = P.topology_build(kind, n)
-    r = oracle.topology(kind, n)
+    t = P.topology_build(kind, n, seed=11, phases=5)     # seed and phases only matter to the random match
+    r = oracle.topology(kind, n, seed=11, phases=5)
     assert t.period == r.period
     np.testing.assert_array_equal(t.row_ptr, r.row_ptr)
     np.testing.assert_array_equal(t.col_idx, r.col_idx)
@@ -69,6 +69,13 @@ STEP_CASES = [
     (2, 8, 4, 0, 0, 4, 0.1),
     (2, 8, 255, 1, 0, 4, 0.1),
     (2, 8, 257, 3, 0, 4, 0.1),
+    (3, 32, 1030, 2, 0, 4, 0.1),      # symmetric exponential graph, 10 entries per row
+    (3, 12, 260, 0, 0, 3, 0.1),       # n not a power of two: hops collide and are dropped
+    (4, 12, 515, 1, 0, 4, 0.05),      # 3 x 4 mesh: degrees 2-4, Metropolis-Hastings weights
+    (4, 32, 700, 0, 0, 3, 0.05),      # 4 x 8 mesh
+    (4, 7, 100, 0, 0, 3, 0.05),       # prime n: the mesh is a path
+    (5, 16, 300, 0, 0, 8, 0.1),       # bipartite random match, a new matching every iteration (period 5)
+    (5, 9, 64, 0, 0, 6, 0.1),         # odd n: one node sits out each iteration
 ]
 
 
@@ -357,3 +364,26 @@ def test_dsgd_step_matches_oracle(P, oracle, kind, n, d, pad, off):
     P.decentlam_step(xa, ma, g.contiguous(), topo, gamma, 0.0, 0)
     P.dsgd_step(xd, g.contiguous(), topo, gamma, 0)
     check_elementwise(xa.cpu().numpy(), xd.cpu().numpy().astype(np.float64), "DecentLaM(beta=0) vs DSGD")
+
+
+def test_decentlam_stays_bounded_on_symmetric_graphs(P):
+    """The paper's requirement (Sec. "Experiments"): DecentLaM needs a symmetric weight matrix.  On the
+    symmetric exponential graph and the mesh a long run with zero-mean gradients keeps the state
+    bounded, while the directed static exponential graph of the same size lets it grow geometrically."""
+    n, d, T = 32, 2048, 300
+    gen = torch.Generator(device="cuda").manual_seed(21)
+    x0 = torch.randn((n, d), device="cuda", generator=gen)
+    gs = [torch.randn((n, d), device="cuda", generator=gen) for _ in range(8)]
+
+    def final_norm(kind):
+        topo = P.topology_build(kind, n)
+        x, m = x0.clone(), torch.zeros_like(x0)
+        for k in range(T):
+            P.decentlam_step(x, m, gs[k % 8], topo, 0.01, 0.9, k)
+        return float(x.norm())
+
+    base = float(x0.norm())
+    assert final_norm(P.DL_TOPO_EXP_SYM) < 10 * base
+    assert final_norm(P.DL_TOPO_MESH) < 10 * base
+    assert final_norm(P.DL_TOPO_RING) < 10 * base
+    assert not final_norm(P.DL_TOPO_EXP_STATIC) < 1e6 * base      # inf or astronomically large

@@ -41,6 +41,7 @@ def table_of(topo):
     (0, 4, "topology_ring_n4.txt"),
     (1, 8, "topology_exp_static_n8.txt"),
     (2, 8, "topology_exp_onepeer_n8.txt"),
+    (3, 8, "topology_exp_sym_n8.txt"),
 ])
 def test_matches_hand_written_table(oracle, kind, n, fname):
     topo = oracle.topology(kind, n)
@@ -51,25 +52,46 @@ def test_matches_hand_written_table(oracle, kind, n, fname):
         assert np.all(topo.w[rp[i]:rp[i + 1]] == np.float32(1.0) / np.float32(len(nb)))
 
 
-def dense_from_text(kind, n, phase):
-    """W built straight from the wording, with sets instead of ordered lists."""
-    W = np.zeros((n, n))
+def neighbour_sets(kind, n, phase):
+    """N_i straight from the wording, as sets."""
+    hops = [h for h in (2 ** t for t in range(64)) if h <= n - 1]
+    out = []
     for i in range(n):
         nb = {i}
         if kind == 0:
             nb |= {(i + 1) % n, (i - 1) % n}
+        elif kind == 1:
+            nb |= {(i + h) % n for h in hops}
+        elif kind == 2 and hops:
+            nb |= {(i + hops[phase]) % n}
+        elif kind == 3:
+            nb |= {(i + h) % n for h in hops} | {(i - h) % n for h in hops}
+        elif kind == 4:
+            R = max(r for r in range(1, n + 1) if n % r == 0 and r * r <= n)
+            C = n // R
+            a, b = divmod(i, C)
+            nb |= {(a + da) * C + (b + db) for da, db in ((-1, 0), (1, 0), (0, -1), (0, 1))
+                   if 0 <= a + da < R and 0 <= b + db < C}
+        out.append(nb)
+    return out
+
+
+def dense_from_text(kind, n, phase):
+    """W from the sets: uniform 1/|N_i| on the directed graphs, Metropolis-Hastings otherwise."""
+    nbs = neighbour_sets(kind, n, phase)
+    W = np.zeros((n, n))
+    for i, nb in enumerate(nbs):
+        if kind in (1, 2):
+            for j in nb:
+                W[i, j] = 1.0 / len(nb)
         else:
-            hops = [h for h in (2 ** t for t in range(64)) if h <= n - 1]
-            if kind == 1:
-                nb |= {(i + h) % n for h in hops}
-            elif hops:
-                nb |= {(i + hops[phase]) % n}
-        for j in nb:
-            W[i, j] = 1.0 / len(nb)
+            for j in nb - {i}:
+                W[i, j] = 1.0 / (1 + max(len(nb) - 1, len(nbs[j]) - 1))
+            W[i, i] = 1.0 - W[i].sum()
     return W
 
 
-@pytest.mark.parametrize("kind", [0, 1, 2])
+@pytest.mark.parametrize("kind", [0, 1, 2, 3, 4])
 @pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 7, 8, 16, 17, 32, 64])
 def test_dense_matrix_and_stochasticity(oracle, kind, n):
     topo = oracle.topology(kind, n)
@@ -88,8 +110,8 @@ def test_dense_matrix_and_stochasticity(oracle, kind, n):
         for i in range(n):
             nb = topo.col_idx[rp[i]:rp[i + 1]]
             assert nb[0] == i and len(set(nb.tolist())) == len(nb)
-        if kind == 0:
-            np.testing.assert_array_equal(W, W.T)                   # undirected ring
+        if kind in (0, 3, 4):
+            np.testing.assert_array_equal(W, W.T)                   # undirected: Assumption A.3 asks for symmetry
 
 
 def test_config_sizes(oracle):
@@ -118,3 +140,65 @@ def test_rejects_bad_arguments(oracle):
         oracle.topology(0, 0)
     with pytest.raises(ValueError):
         oracle.topology(7, 4)
+
+
+def test_mesh_weights_match_hand_computed_fractions(oracle):
+    from fractions import Fraction
+
+    topo = oracle.topology(oracle.MESH, 6)
+    rp = topo.row_ptr
+    with open(os.path.join(GOLDEN, "topology_mesh_n6_weights.txt")) as f:
+        lines = [l.strip() for l in f if l.strip() and not l.startswith("#")]
+    assert len(lines) == 6
+    for line in lines:
+        head, tail = line.split(":")
+        _, i = (int(t) for t in head.split())
+        want = [(int(e.split("=")[0]), Fraction(e.split("=")[1])) for e in tail.split()]
+        got_j = [int(j) for j in topo.col_idx[rp[i]:rp[i + 1]]]
+        got_w = topo.w[rp[i]:rp[i + 1]]
+        assert got_j == [j for j, _ in want]
+        for (j, frac), wij in zip(want, got_w):
+            assert abs(float(wij) - float(frac)) <= 6e-8, (i, j)
+            if j != i:
+                assert wij == np.float32(1.0) / np.float32(frac.denominator)   # 1/(1+max deg) evaluated in fp32
+
+
+@pytest.mark.parametrize("n", [2, 6, 8, 9, 32, 64])
+def test_bipartite_random_match_is_a_seeded_perfect_matching(oracle, n):
+    phases = 7
+    topo = oracle.topology(oracle.BIPARTITE_MATCH, n, seed=12345, phases=phases)
+    again = oracle.topology(oracle.BIPARTITE_MATCH, n, seed=12345, phases=phases)
+    other = oracle.topology(oracle.BIPARTITE_MATCH, n, seed=12346, phases=phases)
+    assert topo.period == phases
+    np.testing.assert_array_equal(topo.col_idx, again.col_idx)     # same seed on all nodes => same matching
+    if n > 2:
+        assert not np.array_equal(topo.col_idx, other.col_idx)
+    distinct = set()
+    for p in range(phases):
+        W = topo.dense(p)
+        np.testing.assert_array_equal(W, W.T)
+        np.testing.assert_array_equal(W.sum(axis=0), 1.0)
+        np.testing.assert_array_equal(W.sum(axis=1), 1.0)
+        partner = W.argmax(axis=1) if n == 1 else [int(np.flatnonzero((W[i] > 0) & (np.arange(n) != i))[0])
+                                                  if (W[i] > 0).sum() == 2 else i for i in range(n)]
+        singles = [i for i in range(n) if partner[i] == i]
+        assert len(singles) == n % 2                                # everyone paired (one left over if n is odd)
+        for i in range(n):
+            assert partner[partner[i]] == i
+            if partner[i] != i:
+                assert W[i, i] == 0.5 and W[i, partner[i]] == 0.5
+        distinct.add(tuple(partner))
+    if n >= 8:
+        assert len(distinct) > 1                                    # the matching changes from iteration to iteration
+
+
+def test_bipartite_groups_are_a_uniform_shuffle(oracle):
+    """Over many phases every other node shows up as node 0's partner about equally often."""
+    n, phases = 8, 7000
+    topo = oracle.topology(oracle.BIPARTITE_MATCH, n, seed=99, phases=phases)
+    counts = np.zeros(n)
+    for p in range(phases):
+        rp = topo.row_ptr[p * (n + 1):(p + 1) * (n + 1)]
+        counts[topo.col_idx[rp[0] + 1]] += 1
+    assert counts[0] == 0
+    np.testing.assert_allclose(counts[1:], phases / (n - 1), rtol=0.12)   # 1000 +- 4 sigma
