@@ -32,7 +32,8 @@ BYTES_PER_ELEMENT = 20         # read x, m, g + write x, m, fp32
 # HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by what
 # the same counter reads for a plain device copy of known size; profiles/*_hbm_traffic_pmc.txt),
 # keyed by (workload, algo); None where not measured.
-MEASURED_TRAFFIC_BYTES = {("c3_exp32", "decentlam"): 16_383_747_763}
+MEASURED_TRAFFIC_BYTES = {("c3_exp32", "decentlam"): 16_383_747_763,
+                          ("c5_onepeer64_lsq", "local_grad_lsq"): 4_342_500_000}
 
 
 def ensure_built():
@@ -127,7 +128,7 @@ def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False):
     return w, d, ld, topo, wall_ms, kern_ms
 
 
-def bench_lsq(P, workloads, name, steps, warmup):
+def bench_lsq(P, workloads, name, steps, warmup, calibration_copy=False):
     """Workload 5: local_grad_lsq then decentlam_step per iteration; times the gradient alone too."""
     import numpy as np
     import torch
@@ -149,6 +150,11 @@ def bench_lsq(P, workloads, name, steps, warmup):
     wall_ms, both_ms = time_launches(iteration, steps, warmup)
     _, grad_ms = time_launches(lambda k: P.local_grad_lsq(A, y, x, g, loss, scale, ws), steps, 1)
     a_bytes = 4 * w.n * w.b * w.d
+    if calibration_copy:
+        scratch = torch.empty_like(A)
+        scratch.copy_(A)
+        torch.cuda.synchronize()
+        del scratch
     del A, y, x, m, g, ws
     torch.cuda.empty_cache()
     return {
@@ -165,7 +171,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c3_exp32", choices=["c3_exp32", "c4_ring16_ragged"])
+    ap.add_argument("--workload", default="c3_exp32",
+                    choices=["c3_exp32", "c4_ring16_ragged", "c5_onepeer64_lsq"])
     ap.add_argument("--algo", default="decentlam", choices=["decentlam", "dmsgd"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
@@ -191,6 +198,23 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     torch.cuda.set_device(0)
 
+    if args.workload == "c5_onepeer64_lsq":
+        # side workload: one iteration = local_grad_lsq + decentlam_step; the gradient kernel dominates
+        r = bench_lsq(P, workloads, args.workload, args.steps, args.warmup, args.calibration_copy)
+        print(json.dumps({
+            "metric": "least-squares workload: local_grad_lsq + decentlam_step per iteration (n=64, A_i 4096x4096)",
+            "value": round(r["grad_algorithmic_bytes"] / (r["ms_per_iteration_grad_plus_step"] * 1e-3) / 1e9, 2),
+            "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": r["ms_per_iteration_grad_plus_step"], "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+            "config": {"workload": args.workload, "n": r["n"], "b": r["b"], "d": r["d"]},
+            "roofline": {"bound": "hbm", "achieved": r["grad_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": r["grad_frac_of_hbm_peak"],
+                         "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "local_grad_lsq")),
+                         "kernel": "k_fused", "kernel_ms": r["grad_kernel_ms"],
+                         "algorithmic_bytes_per_launch": r["grad_algorithmic_bytes"]},
+        }), flush=True)
+        return
     w, d, ld, topo, wall_ms, kern_ms = bench_step(P, workloads, args.workload, args.algo, args.steps,
                                                   args.warmup, args.calibration_copy)
     kind = w.topo
