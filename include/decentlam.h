@@ -176,6 +176,22 @@ int local_grad_lsq(const float* A, const float* y, const float* x,
                    float scale, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * local_grad_lsq_rows -- the stochastic (mini-batch) version: node i's sample xi_i (Algorithms 1
+ * and 2, "Sample xi_i") is a list of bs row indices into its local data, drawn by the caller:
+ *     g_i = scale * sum_{t < bs} a_t (a_t . x_i - y_i[r_t]),  r_t = rows[i*bs + t],  a_t = A_i[r_t, :]
+ *     loss_i = (scale/2) * sum_t (a_t . x_i - y_i[r_t])^2
+ * Repeated indices are allowed (sampling with replacement) and count as often as they appear.
+ *   rows [in] device, n x bs int32 with values in [0, b); values outside are clamped into the range.
+ *   workspace: at least local_grad_lsq_workspace(n, bs, d) bytes.
+ * Everything else as local_grad_lsq.  Additional errors: DL_EINVAL (rows NULL, bs < 1).
+ */
+int local_grad_lsq_rows(const float* A, const float* y, const float* x,
+                        float* g, float* loss,
+                        int32_t n, int32_t b, int64_t d, int64_t ldA, int64_t ld,
+                        const int32_t* rows, int32_t bs,
+                        float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * decentlam_stats -- diagnostics of the stacked state, one pass over x (and m):
  *     out[0] = sum_i ||x_i - xbar||^2,  xbar = (1/n) sum_i x_i   (consensus distance; xbar as in
  *                                                                 the appendix "Preliminary")

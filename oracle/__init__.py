@@ -57,6 +57,8 @@ def _load():
                 ctypes.c_double, ctypes.c_int64, f64p, f64p, f64p, f64p, f64p]
         _lib.oracle_dmsgd_step.argtypes = step
         _lib.oracle_decentlam_step.argtypes = step
+        _lib.oracle_lsq_grad_rows.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, f32p, f32p, f64p, i32p,
+                                              ctypes.c_int, ctypes.c_double, f64p, f64p]
         _lib.oracle_stats.argtypes = [ctypes.c_int, ctypes.c_int64, f64p, f64p, f64p, f64p]
         _lib.oracle_lsq_grad.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, f32p, f32p, f64p,
                                          ctypes.c_double, f64p, f64p]
@@ -180,6 +182,24 @@ def lsq_grad(A, y, x, scale: float = 1.0):
                                  _p(x, ctypes.c_double), float(scale), _p(g, ctypes.c_double),
                                  _p(loss, ctypes.c_double))
     assert rc == 0
+    return g, loss
+
+
+def lsq_grad_rows(A, y, x, rows, scale: float = 1.0):
+    """Mini-batch gradient over the sampled rows `rows` (n x bs int32, values in [0, b)) -> (g, loss)."""
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    y = np.ascontiguousarray(y, dtype=np.float32)
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    x = _f64(x)
+    n, b, d = A.shape
+    assert y.shape == (n, b) and x.shape == (n, d) and rows.ndim == 2 and rows.shape[0] == n
+    g = np.empty((n, d), dtype=np.float64)
+    loss = np.empty(n, dtype=np.float64)
+    rc = _load().oracle_lsq_grad_rows(n, b, d, _p(A, ctypes.c_float), _p(y, ctypes.c_float),
+                                      _p(x, ctypes.c_double), _p(rows, ctypes.c_int32), rows.shape[1],
+                                      float(scale), _p(g, ctypes.c_double), _p(loss, ctypes.c_double))
+    if rc:
+        raise ValueError("row index outside [0, b)")
     return g, loss
 
 

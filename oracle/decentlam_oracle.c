@@ -362,3 +362,30 @@ int oracle_stats(int n, int64_t d, const double* x, const double* m, const doubl
     out[0] = cons; out[1] = xbar2; out[2] = err; out[3] = ref2; out[4] = m2;
     return 0;
 }
+
+/* Stochastic version of the least-squares gradient: the sample xi_i of Algorithms 1 and 2 is a
+ * list of bs row indices rows[i*bs + t] into node i's local data (repeats allowed):
+ *   res_t = a_t . x_i - y_i[r_t] ;  g_i = scale sum_t a_t res_t ;  loss_i = (scale/2) sum_t res_t^2
+ * with a_t the r_t-th row of A_i. */
+int oracle_lsq_grad_rows(int n, int b, int64_t d, const float* A, const float* y, const double* x,
+                         const int32_t* rows, int bs, double scale, double* g_out, double* loss_out)
+{
+    for (int i = 0; i < n; ++i) {
+        double* gi = g_out + (int64_t)i * d;
+        for (int64_t c = 0; c < d; ++c) gi[c] = 0.0;
+        double sq = 0.0;
+        for (int t = 0; t < bs; ++t) {
+            int r = rows[(int64_t)i * bs + t];
+            if (r < 0 || r >= b) return -1;
+            const float* a = A + ((int64_t)i * b + r) * d;
+            double res = 0.0;
+            for (int64_t c = 0; c < d; ++c) res = res + (double)a[c] * x[(int64_t)i * d + c];
+            res = res - (double)y[(int64_t)i * b + r];
+            for (int64_t c = 0; c < d; ++c) gi[c] = gi[c] + (double)a[c] * res;
+            sq = sq + res * res;
+        }
+        for (int64_t c = 0; c < d; ++c) gi[c] = scale * gi[c];
+        if (loss_out) loss_out[i] = 0.5 * scale * sq;
+    }
+    return 0;
+}

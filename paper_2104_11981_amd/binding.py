@@ -28,7 +28,7 @@ DL_TOPO_EXP_SYM, DL_TOPO_MESH, DL_TOPO_BIPARTITE_MATCH = 3, 4, 5
 DL_FLAG_ROW_STOCHASTIC, DL_FLAG_COL_STOCHASTIC, DL_FLAG_SYMMETRIC = 1, 2, 4
 DL_MAX_NODES, DL_MAX_NNZ = 256, 512
 
-EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decentlam_step", "dmsgd_step", "dsgd_step", "local_grad_lsq",
+EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decentlam_step", "dmsgd_step", "dsgd_step", "local_grad_lsq", "local_grad_lsq_rows",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
 
@@ -69,6 +69,10 @@ def _load() -> ctypes.CDLL:
     lib.local_grad_lsq.restype = ctypes.c_int
     lib.local_grad_lsq.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.local_grad_lsq_rows.restype = ctypes.c_int
+    lib.local_grad_lsq_rows.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
+                                        ctypes.c_int64, ctypes.c_int64, vp, ctypes.c_int32, ctypes.c_float, vp,
+                                        ctypes.c_size_t, vp]
     lib.decentlam_stats_workspace.restype = ctypes.c_size_t
     lib.decentlam_stats_workspace.argtypes = [ctypes.c_int32, ctypes.c_int64]
     lib.decentlam_stats.restype = ctypes.c_int
@@ -193,9 +197,10 @@ def local_grad_lsq_workspace(n: int, b: int, d: int) -> int:
     return int(_lib.local_grad_lsq_workspace(n, b, d))
 
 
-def local_grad_lsq(A, y, x, g, loss=None, scale: float = 1.0, workspace=None, stream=None):
+def local_grad_lsq(A, y, x, g, loss=None, scale: float = 1.0, workspace=None, stream=None, rows=None):
     """g_i = scale * A_i^T (A_i x_i - y_i) on device tensors; `workspace` is a uint8 device tensor
-    of at least local_grad_lsq_workspace(n, b, d) bytes."""
+    of at least local_grad_lsq_workspace(n, b, d) bytes.  With `rows` (n x bs int32 device tensor)
+    the sums run over the listed rows only (local_grad_lsq_rows)."""
     if A.dtype != torch.float32 or A.dim() != 3 or not A.is_cuda or A.stride(2) != 1:
         raise TypeError("A: need a 3-D float32 device tensor with contiguous last axis")
     n, b, d = A.shape
@@ -215,9 +220,16 @@ def local_grad_lsq(A, y, x, g, loss=None, scale: float = 1.0, workspace=None, st
         pl = loss.data_ptr()
     if workspace is None:
         raise TypeError("workspace: pass a uint8 device tensor (size from local_grad_lsq_workspace)")
-    _check(_lib.local_grad_lsq(A.data_ptr(), y.data_ptr(), px, pg, pl, n, b, d, ldA, ld, scale,
-                               workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                               _stream() if stream is None else stream))
+    st = _stream() if stream is None else stream
+    ws_bytes = workspace.numel() * workspace.element_size()
+    if rows is None:
+        _check(_lib.local_grad_lsq(A.data_ptr(), y.data_ptr(), px, pg, pl, n, b, d, ldA, ld, scale,
+                                   workspace.data_ptr(), ws_bytes, st))
+        return
+    if rows.dtype != torch.int32 or rows.dim() != 2 or rows.shape[0] != n or not rows.is_cuda or not rows.is_contiguous():
+        raise TypeError("rows: need a contiguous n x bs int32 device tensor")
+    _check(_lib.local_grad_lsq_rows(A.data_ptr(), y.data_ptr(), px, pg, pl, n, b, d, ldA, ld, rows.data_ptr(),
+                                    rows.shape[1], scale, workspace.data_ptr(), ws_bytes, st))
 
 
 def decentlam_stats_workspace(n: int, d: int) -> int:

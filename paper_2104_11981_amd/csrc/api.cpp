@@ -159,11 +159,11 @@ size_t local_grad_lsq_workspace(int32_t n, int32_t b, int64_t d) {
     return dl::lsq_workspace_bytes(n, b, d);
 }
 
-int local_grad_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
-                   int32_t b, int64_t d, int64_t ldA, int64_t ld, float scale, void* workspace,
-                   size_t workspace_bytes, void* stream) {
-    using namespace dl;
-    const char* fn = "local_grad_lsq";
+namespace dl {
+namespace {
+int lsq_entry(const char* fn, const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
+              int32_t b, int64_t d, int64_t ldA, int64_t ld, const int32_t* rows, int32_t bs, bool sampled,
+              float scale, void* workspace, size_t workspace_bytes, void* stream) {
     clear_error();
     if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
     if (b < 1) return set_error(DL_EINVAL, "%s: b = %d, need b >= 1", fn, b);
@@ -173,10 +173,16 @@ int local_grad_lsq(const float* A, const float* y, const float* x, float* g, flo
                          static_cast<long long>(ldA), static_cast<long long>(ld), static_cast<long long>(d));
     if (!std::isfinite(scale)) return set_error(DL_EINVAL, "%s: scale must be finite", fn);
     if (!A || !y || !x || !g) return set_error(DL_EINVAL, "%s: A, y, x and g must not be NULL", fn);
+    if (sampled) {
+        if (!rows) return set_error(DL_EINVAL, "%s: rows must not be NULL", fn);
+        if (bs < 1) return set_error(DL_EINVAL, "%s: bs = %d, need bs >= 1", fn, bs);
+    } else {
+        bs = b;
+    }
     if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(y) | reinterpret_cast<uintptr_t>(x) |
-         reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(loss)) & 3u)
+         reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(loss) | reinterpret_cast<uintptr_t>(rows)) & 3u)
         return set_error(DL_EINVAL, "%s: arrays must be 4-byte aligned", fn);
-    const size_t need = lsq_workspace_bytes(n, b, d);
+    const size_t need = lsq_workspace_bytes(n, bs, d);
     if (!workspace || workspace_bytes < need)
         return set_error(DL_ECAP, "%s: workspace of %zu bytes needed, %zu given", fn, need,
                          workspace ? workspace_bytes : size_t{0});
@@ -200,7 +206,29 @@ int local_grad_lsq(const float* A, const float* y, const float* x, float* g, flo
         if (overlap(sl, sA) || overlap(sl, sy) || overlap(sl, sx) || overlap(sl, sg) || overlap(sl, sw))
             return set_error(DL_EALIAS, "%s: loss overlaps another array", fn);
     }
-    return launch_lsq(A, y, x, g, loss, n, b, d, ldA, ld, scale, workspace, static_cast<hipStream_t>(stream));
+    if (sampled) {
+        const Span sr = span_of(rows, 1, static_cast<int64_t>(n) * bs, static_cast<int64_t>(n) * bs);
+        if (overlap(sr, sg) || overlap(sr, sw) || (loss && overlap(sr, span_of(loss, 1, n, n))))
+            return set_error(DL_EALIAS, "%s: rows overlaps an output", fn);
+    }
+    return launch_lsq(A, y, x, g, loss, n, b, d, ldA, ld, sampled ? rows : nullptr, bs, scale, workspace,
+                      static_cast<hipStream_t>(stream));
+}
+}  // namespace
+}  // namespace dl
+
+int local_grad_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
+                   int32_t b, int64_t d, int64_t ldA, int64_t ld, float scale, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+    return dl::lsq_entry("local_grad_lsq", A, y, x, g, loss, n, b, d, ldA, ld, nullptr, b, false, scale,
+                         workspace, workspace_bytes, stream);
+}
+
+int local_grad_lsq_rows(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
+                        int32_t b, int64_t d, int64_t ldA, int64_t ld, const int32_t* rows, int32_t bs,
+                        float scale, void* workspace, size_t workspace_bytes, void* stream) {
+    return dl::lsq_entry("local_grad_lsq_rows", A, y, x, g, loss, n, b, d, ldA, ld, rows, bs, true, scale,
+                         workspace, workspace_bytes, stream);
 }
 
 size_t decentlam_stats_workspace(int32_t n, int64_t d) {

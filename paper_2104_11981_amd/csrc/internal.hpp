@@ -31,9 +31,10 @@ int launch_step(Algo algo, float* x, float* m, const float* g, int32_t n, int64_
 
 // Least-squares gradient (already validated).
 size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d);
+// rows == nullptr: full-batch gradient over all b rows; otherwise bs sampled rows per node.
 int launch_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
-               int32_t b, int64_t d, int64_t ldA, int64_t ld, float scale, void* workspace,
-               hipStream_t stream);
+               int32_t b, int64_t d, int64_t ldA, int64_t ld, const int32_t* rows, int32_t bs, float scale,
+               void* workspace, hipStream_t stream);
 
 // Diagnostics (already validated).
 size_t stats_workspace_bytes(int64_t d);

@@ -33,6 +33,13 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
+// Mini-batch gradients: logical row r of node i is physical row rows[i*bs + r] of A_i and y_i
+// (clamped into [0, b) so that a bad index can never leave the arrays).
+__device__ __forceinline__ int physical_row(const int32_t* __restrict__ rows_i, int r, int b) {
+    const int p = rows_i[r];
+    return p < 0 ? 0 : (p >= b ? b - 1 : p);
+}
+
 // Row splits of the transposed product: enough workgroups to fill 256 CUs several times over.
 int row_splits(int32_t n, int32_t b, int64_t d) {
     const int64_t col_blocks = (d + 4 * kThreads - 1) / (4 * kThreads);
@@ -43,18 +50,21 @@ int row_splits(int32_t n, int32_t b, int64_t d) {
     return static_cast<int>(s);
 }
 
+// rows == nullptr: all b rows (bs == b); otherwise bs sampled rows per node
 template <bool VEC4>
 __global__ __launch_bounds__(kThreads) void k_residual(const float* __restrict__ A,
                                                         const float* __restrict__ y,
                                                         const float* __restrict__ x,
                                                         double* __restrict__ res, int b, int64_t d,
-                                                        int64_t ldA, int64_t ld) {
+                                                        int64_t ldA, int64_t ld,
+                                                        const int32_t* __restrict__ rows, int bs) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i = blockIdx.y;
     const int r = blockIdx.x * (kThreads / 64) + wave;
-    if (r >= b) return;
-    const float* __restrict__ a = A + (static_cast<int64_t>(i) * b + r) * ldA;
+    if (r >= bs) return;
+    const int pr = rows ? physical_row(rows + static_cast<int64_t>(i) * bs, r, b) : r;
+    const float* __restrict__ a = A + (static_cast<int64_t>(i) * b + pr) * ldA;
     const float* __restrict__ xi = x + static_cast<int64_t>(i) * ld;
     double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
     if constexpr (VEC4) {
@@ -71,36 +81,39 @@ __global__ __launch_bounds__(kThreads) void k_residual(const float* __restrict__
             acc0 = __builtin_fma(static_cast<double>(a[c]), static_cast<double>(xi[c]), acc0);
     }
     const double dot = wave_sum((acc0 + acc1) + (acc2 + acc3));
-    if (lane == 0) res[static_cast<int64_t>(i) * b + r] = dot - static_cast<double>(y[static_cast<int64_t>(i) * b + r]);
+    if (lane == 0) res[static_cast<int64_t>(i) * bs + r] = dot - static_cast<double>(y[static_cast<int64_t>(i) * b + pr]);
 }
 
 template <bool VEC4>
 __global__ __launch_bounds__(kThreads) void k_transpose(const float* __restrict__ A,
                                                          const double* __restrict__ res,
                                                          double* __restrict__ partial, int b, int64_t d,
-                                                         int64_t ldA, int splits) {
+                                                         int64_t ldA, int splits,
+                                                         const int32_t* __restrict__ rows, int bs) {
     constexpr int V = VEC4 ? 4 : 1;
     const int i = blockIdx.z, s = blockIdx.y;
     const int64_t c = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * V;
     if (c >= d) return;
-    const int r0 = static_cast<int>(static_cast<int64_t>(b) * s / splits);
-    const int r1 = static_cast<int>(static_cast<int64_t>(b) * (s + 1) / splits);
+    const int r0 = static_cast<int>(static_cast<int64_t>(bs) * s / splits);
+    const int r1 = static_cast<int>(static_cast<int64_t>(bs) * (s + 1) / splits);
     const float* __restrict__ a = A + static_cast<int64_t>(i) * b * ldA + c;
-    const double* __restrict__ ri = res + static_cast<int64_t>(i) * b;
+    const double* __restrict__ ri = res + static_cast<int64_t>(i) * bs;
+    const int32_t* __restrict__ rows_i = rows ? rows + static_cast<int64_t>(i) * bs : nullptr;
     double acc[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) acc[v] = 0.0;
 #pragma unroll 8
     for (int r = r0; r < r1; ++r) {
         const double rr = ri[r];
+        const int pr = rows_i ? physical_row(rows_i, r, b) : r;
         if constexpr (VEC4) {
-            const vf4 av = *reinterpret_cast<const vf4*>(a + static_cast<int64_t>(r) * ldA);
+            const vf4 av = *reinterpret_cast<const vf4*>(a + static_cast<int64_t>(pr) * ldA);
             acc[0] = __builtin_fma(static_cast<double>(av.x), rr, acc[0]);
             acc[1] = __builtin_fma(static_cast<double>(av.y), rr, acc[1]);
             acc[2] = __builtin_fma(static_cast<double>(av.z), rr, acc[2]);
             acc[3] = __builtin_fma(static_cast<double>(av.w), rr, acc[3]);
         } else {
-            acc[0] = __builtin_fma(static_cast<double>(a[static_cast<int64_t>(r) * ldA]), rr, acc[0]);
+            acc[0] = __builtin_fma(static_cast<double>(a[static_cast<int64_t>(pr) * ldA]), rr, acc[0]);
         }
     }
     double* out = partial + (static_cast<int64_t>(i) * splits + s) * d + c;
@@ -150,10 +163,12 @@ struct Tile {
 // (their x is zero and their accumulators are never stored).
 template <int CPT, int R>
 __device__ __forceinline__ void load_tile(Tile<CPT, R>& t, const float* __restrict__ a_node, int64_t ldA,
-                                          int r, int r_last, const int (&col)[CPT]) {
+                                          int r, int r_last, const int (&col)[CPT],
+                                          const int32_t* __restrict__ rows_i, int b) {
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
-        const int row = (r + rr < r_last) ? r + rr : r_last;
+        int row = (r + rr < r_last) ? r + rr : r_last;
+        if (rows_i) row = physical_row(rows_i, row, b);
         const float* __restrict__ a_row = a_node + static_cast<int64_t>(row) * ldA;
 #pragma unroll
         for (int q = 0; q < CPT; ++q)
@@ -164,7 +179,8 @@ __device__ __forceinline__ void load_tile(Tile<CPT, R>& t, const float* __restri
 template <int CPT, int R>
 __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float (&xs)[CPT][4],
                                              double (&acc)[CPT][4], double& sq, double (*red)[R],
-                                             const float* __restrict__ yi, int r, int r1, int lane, int wave) {
+                                             const float* __restrict__ yi, int r, int r1, int lane, int wave,
+                                             const int32_t* __restrict__ rows_i, int b) {
     double p[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
@@ -194,8 +210,10 @@ __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float 
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
         double res = 0.0;
-        if (r + rr < r1)  // uniform over the workgroup
-            res = ((red[0][rr] + red[1][rr]) + (red[2][rr] + red[3][rr])) - static_cast<double>(yi[r + rr]);
+        if (r + rr < r1) {  // uniform over the workgroup
+            const int pr = rows_i ? physical_row(rows_i, r + rr, b) : r + rr;
+            res = ((red[0][rr] + red[1][rr]) + (red[2][rr] + red[3][rr])) - static_cast<double>(yi[pr]);
+        }
         sq = __builtin_fma(res, res, sq);
 #pragma unroll
         for (int q = 0; q < CPT; ++q) {
@@ -211,13 +229,15 @@ template <int CPT, int R, bool PF>
 __global__ __launch_bounds__(kThreads, (PF || CPT >= 8) ? 2 : 4) void k_fused(const float* __restrict__ A, const float* __restrict__ y,
                                                      const float* __restrict__ x, double* __restrict__ partial,
                                                      double* __restrict__ sq_partial, int b, int64_t d,
-                                                     int64_t ldA, int64_t ld, int splits) {
+                                                     int64_t ldA, int64_t ld, int splits,
+                                                     const int32_t* __restrict__ rows, int bs) {
     __shared__ double red[2][kThreads / 64][R];  // two buffers: one barrier per tile is enough
     const int i = blockIdx.y, s = blockIdx.x;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int r0 = static_cast<int>(static_cast<int64_t>(b) * s / splits);
-    const int r1 = static_cast<int>(static_cast<int64_t>(b) * (s + 1) / splits);  // r1 > r0: splits <= b
+    const int r0 = static_cast<int>(static_cast<int64_t>(bs) * s / splits);
+    const int r1 = static_cast<int>(static_cast<int64_t>(bs) * (s + 1) / splits);  // r1 > r0: splits <= bs
+    const int32_t* __restrict__ rows_i = rows ? rows + static_cast<int64_t>(i) * bs : nullptr;
 
     int col[CPT];
     float xs[CPT][4];
@@ -238,19 +258,19 @@ __global__ __launch_bounds__(kThreads, (PF || CPT >= 8) ? 2 : 4) void k_fused(co
 
     if constexpr (PF) {
         Tile<CPT, R> t0, t1;
-        load_tile<CPT, R>(t0, a_node, ldA, r0, r1 - 1, col);
+        load_tile<CPT, R>(t0, a_node, ldA, r0, r1 - 1, col, rows_i, b);
         for (int r = r0; r < r1; r += 2 * R) {
-            load_tile<CPT, R>(t1, a_node, ldA, r + R, r1 - 1, col);
-            consume_tile<CPT, R>(t0, xs, acc, sq, red[0], yi, r, r1, lane, wave);
-            load_tile<CPT, R>(t0, a_node, ldA, r + 2 * R, r1 - 1, col);
-            consume_tile<CPT, R>(t1, xs, acc, sq, red[1], yi, r + R, r1, lane, wave);
+            load_tile<CPT, R>(t1, a_node, ldA, r + R, r1 - 1, col, rows_i, b);
+            consume_tile<CPT, R>(t0, xs, acc, sq, red[0], yi, r, r1, lane, wave, rows_i, b);
+            load_tile<CPT, R>(t0, a_node, ldA, r + 2 * R, r1 - 1, col, rows_i, b);
+            consume_tile<CPT, R>(t1, xs, acc, sq, red[1], yi, r + R, r1, lane, wave, rows_i, b);
         }
     } else {
         Tile<CPT, R> t0;
         int buf = 0;
         for (int r = r0; r < r1; r += R, buf ^= 1) {
-            load_tile<CPT, R>(t0, a_node, ldA, r, r1 - 1, col);
-            consume_tile<CPT, R>(t0, xs, acc, sq, red[buf], yi, r, r1, lane, wave);
+            load_tile<CPT, R>(t0, a_node, ldA, r, r1 - 1, col, rows_i, b);
+            consume_tile<CPT, R>(t0, xs, acc, sq, red[buf], yi, r, r1, lane, wave, rows_i, b);
         }
     }
 
@@ -303,7 +323,7 @@ constexpr int kMaxFusedD = 8192;
 
 }  // namespace
 
-size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d) {
+size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d) {  // b = rows actually used per node
     // two-sweep layout: res[n*b], partial[n*splits*d]; single-sweep layout: sq[n*splits], partial[n*splits*d]
     const size_t res = static_cast<size_t>(n) * static_cast<size_t>(b);
     const size_t partial = static_cast<size_t>(n) * static_cast<size_t>(row_splits(n, b, d)) * static_cast<size_t>(d);
@@ -317,11 +337,12 @@ size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d) {
 }
 
 int launch_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
-               int32_t b, int64_t d, int64_t ldA, int64_t ld, float scale, void* workspace,
-               hipStream_t stream) {
+               int32_t b, int64_t d, int64_t ldA, int64_t ld, const int32_t* rows, int32_t bs, float scale,
+               void* workspace, hipStream_t stream) {
+    if (rows == nullptr) bs = b;
     double* res = static_cast<double*>(workspace);
-    double* partial = res + ((static_cast<size_t>(n) * b + 1) & ~size_t{1});  // keep 16-byte alignment
-    const int splits = row_splits(n, b, d);
+    double* partial = res + ((static_cast<size_t>(n) * bs + 1) & ~size_t{1});  // keep 16-byte alignment
+    const int splits = row_splits(n, bs, d);
     const bool vec4 = d % 4 == 0 && ldA % 4 == 0 && ld % 4 == 0 &&
                       ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(x)) & 15u) == 0;
     if (n > 65535 || splits > 65535) return set_error(DL_EINVAL, "local_grad_lsq: n too large for the launch grid");
@@ -329,15 +350,15 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
     const dim3 block(kThreads);
     if (vec4 && d > 0 && d <= kMaxFusedD) {
         const int cpt = fused_cpt(d);
-        const int fs = fused_splits(n, b, fused_rows(cpt));
+        const int fs = fused_splits(n, bs, fused_rows(cpt));
         double* sq_partial = static_cast<double*>(workspace);
         double* fpartial = sq_partial + ((static_cast<size_t>(n) * fs + 1) & ~size_t{1});
         const dim3 grid(static_cast<unsigned>(fs), static_cast<unsigned>(n));
         switch (cpt) {
-            case 1: hipLaunchKernelGGL((k_fused<1, 4, true>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs); break;
-            case 2: hipLaunchKernelGGL((k_fused<2, 2, true>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs); break;
-            case 4: hipLaunchKernelGGL((k_fused<4, 1, true>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs); break;
-            default: hipLaunchKernelGGL((k_fused<8, 1, false>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs); break;
+            case 1: hipLaunchKernelGGL((k_fused<1, 4, true>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
+            case 2: hipLaunchKernelGGL((k_fused<2, 2, true>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
+            case 4: hipLaunchKernelGGL((k_fused<4, 1, true>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
+            default: hipLaunchKernelGGL((k_fused<8, 1, false>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
         }
         if (int rc = check_hip(hipGetLastError(), "fused gradient kernel launch")) return rc;
         const dim3 grid_ff(static_cast<unsigned>((d + kThreads - 1) / kThreads), static_cast<unsigned>(n));
@@ -346,11 +367,11 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
         return check_hip(hipGetLastError(), "finish kernel launch");
     }
 
-    const dim3 grid_r(static_cast<unsigned>((b + 3) / 4), static_cast<unsigned>(n));
+    const dim3 grid_r(static_cast<unsigned>((bs + 3) / 4), static_cast<unsigned>(n));
     if (vec4)
-        hipLaunchKernelGGL(k_residual<true>, grid_r, block, 0, stream, A, y, x, res, b, d, ldA, ld);
+        hipLaunchKernelGGL(k_residual<true>, grid_r, block, 0, stream, A, y, x, res, b, d, ldA, ld, rows, bs);
     else
-        hipLaunchKernelGGL(k_residual<false>, grid_r, block, 0, stream, A, y, x, res, b, d, ldA, ld);
+        hipLaunchKernelGGL(k_residual<false>, grid_r, block, 0, stream, A, y, x, res, b, d, ldA, ld, rows, bs);
     if (int rc = check_hip(hipGetLastError(), "residual kernel launch")) return rc;
 
     if (d > 0) {
@@ -358,14 +379,14 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
         const dim3 grid_t(static_cast<unsigned>((d + static_cast<int64_t>(V) * kThreads - 1) / (static_cast<int64_t>(V) * kThreads)),
                           static_cast<unsigned>(splits), static_cast<unsigned>(n));
         if (vec4)
-            hipLaunchKernelGGL(k_transpose<true>, grid_t, block, 0, stream, A, res, partial, b, d, ldA, splits);
+            hipLaunchKernelGGL(k_transpose<true>, grid_t, block, 0, stream, A, res, partial, b, d, ldA, splits, rows, bs);
         else
-            hipLaunchKernelGGL(k_transpose<false>, grid_t, block, 0, stream, A, res, partial, b, d, ldA, splits);
+            hipLaunchKernelGGL(k_transpose<false>, grid_t, block, 0, stream, A, res, partial, b, d, ldA, splits, rows, bs);
         if (int rc = check_hip(hipGetLastError(), "transpose kernel launch")) return rc;
     }
 
     const dim3 grid_f(static_cast<unsigned>(d > 0 ? (d + kThreads - 1) / kThreads : 1), static_cast<unsigned>(n));
-    hipLaunchKernelGGL(k_finish, grid_f, block, 0, stream, partial, res, g, loss, b, d, ld, splits,
+    hipLaunchKernelGGL(k_finish, grid_f, block, 0, stream, partial, res, g, loss, bs, d, ld, splits,
                        static_cast<double>(scale));
     return check_hip(hipGetLastError(), "finish kernel launch");
 }

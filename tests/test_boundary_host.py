@@ -216,3 +216,21 @@ def test_topology_build_ex_and_metropolis_errors(oracle):
         with pytest.raises(P.DecentLamError) as e:
             P.topology_metropolis(3, *bad_rows)
         assert e.value.status == P.DL_ETOPO and needle in str(e.value), (needle, str(e.value))
+
+
+def test_lsq_rows_argument_validation():
+    f = P.raw.local_grad_lsq_rows
+    ws = P.local_grad_lsq_workspace(2, 4, 8)
+    base = dict(A=0x10000, y=0x20000, x=0x30000, g=0x40000, loss=0, n=2, b=10, d=8, ldA=8, ld=8,
+                rows=0x60000, bs=4, scale=1.0, wsp=0x50000, wsb=ws)
+
+    def call(**kw):
+        a = dict(base, **kw)
+        return f(a["A"], a["y"], a["x"], a["g"], a["loss"], a["n"], a["b"], a["d"], a["ldA"], a["ld"],
+                 a["rows"], a["bs"], a["scale"], a["wsp"], a["wsb"], None)
+
+    assert call(rows=0) == P.DL_EINVAL and "rows" in P.last_error()
+    assert call(bs=0) == P.DL_EINVAL
+    assert call(wsb=ws - 1) == P.DL_ECAP
+    assert call(rows=0x40000) == P.DL_EALIAS
+    assert call(rows=0x60002) == P.DL_EINVAL

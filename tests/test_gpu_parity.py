@@ -387,3 +387,26 @@ def test_decentlam_stays_bounded_on_symmetric_graphs(P):
     assert final_norm(P.DL_TOPO_MESH) < 10 * base
     assert final_norm(P.DL_TOPO_RING) < 10 * base
     assert not final_norm(P.DL_TOPO_EXP_STATIC) < 1e6 * base      # inf or astronomically large
+
+
+# ---------------------------------------------------------------- mini-batch gradient
+@pytest.mark.parametrize("n,b,d,bs,pad", [(8, 1024, 1024, 64, 0), (3, 40, 132, 7, 0), (2, 50, 33, 20, 1),
+                                          (4, 300, 2500, 33, 0), (2, 100, 5000, 9, 0), (1, 5, 8200, 5, 0),
+                                          (5, 64, 1500, 200, 0)])
+def test_local_grad_lsq_rows_matches_oracle(P, oracle, n, b, d, bs, pad):
+    rng = np.random.default_rng(n * 1000 + bs)
+    A0 = rng.standard_normal((n, b, d)).astype(np.float32)
+    y0 = rng.standard_normal((n, b)).astype(np.float32)
+    x0 = rng.standard_normal((n, d)).astype(np.float32)
+    rows0 = rng.integers(0, b, size=(n, bs)).astype(np.int32)       # with replacement
+    Ab = torch.zeros((n, b, d + pad), dtype=torch.float32, device="cuda")
+    A = Ab[:, :, :d]
+    A.copy_(dev(A0))
+    x, g = dev(x0), torch.empty((n, d), dtype=torch.float32, device="cuda")
+    loss = torch.empty(n, dtype=torch.float32, device="cuda")
+    ws = torch.empty(P.local_grad_lsq_workspace(n, bs, d), dtype=torch.uint8, device="cuda")
+    scale = float(np.float32(1.0 / bs))
+    P.local_grad_lsq(A, dev(y0), x, g, loss, scale, ws, rows=dev(rows0))
+    gr, lr = oracle.lsq_grad_rows(A0, y0, x0, rows0, scale)
+    check_elementwise(g.cpu().numpy(), gr, "g")
+    check_elementwise(loss.cpu().numpy(), lr, "loss")

@@ -70,3 +70,35 @@ def test_nodes_use_their_own_data(oracle):
     g2, _ = oracle.lsq_grad(A2, y, x, 1.0)
     changed = [i for i in range(5) if not np.array_equal(g[i], g2[i])]
     assert changed == [3]
+
+
+def test_sampled_rows_gradient(oracle):
+    """The mini-batch gradient is the full-batch gradient of the gathered sub-problem (checked through
+    automatic differentiation of the sampled loss), repeated rows count as often as they are drawn,
+    and its mean over uniform samples is the full gradient scaled by bs/b (unbiasedness, Assumption A.2)."""
+    n, b, d, bs = 3, 9, 5, 4
+    A, y, x = problem(7, n, b, d)
+    rows = np.array([[0, 3, 3, 8], [1, 2, 4, 6], [8, 8, 8, 0]], dtype=np.int32)
+    g, loss = oracle.lsq_grad_rows(A, y, x, rows, 0.5)
+    xt = torch.tensor(x, requires_grad=True)
+    total = 0.0
+    for i in range(n):
+        Ai = torch.tensor(A[i][rows[i]], dtype=torch.float64)
+        yi = torch.tensor(y[i][rows[i]], dtype=torch.float64)
+        fi = 0.25 * ((Ai @ xt[i] - yi) ** 2).sum()
+        np.testing.assert_allclose(loss[i], fi.item(), rtol=1e-13)
+        total = total + fi
+    total.backward()
+    np.testing.assert_allclose(g, xt.grad.numpy(), rtol=1e-13, atol=1e-13)
+    # all rows once = the full-batch gradient
+    full, full_loss = oracle.lsq_grad(A, y, x, 0.5)
+    g_all, loss_all = oracle.lsq_grad_rows(A, y, x, np.tile(np.arange(b, dtype=np.int32), (n, 1)), 0.5)
+    np.testing.assert_allclose(g_all, full, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(loss_all, full_loss, rtol=1e-13)
+    # unbiased: average over every single-row sample equals full / b
+    acc = np.zeros_like(full)
+    for r in range(b):
+        acc += oracle.lsq_grad_rows(A, y, x, np.full((n, 1), r, dtype=np.int32), 0.5)[0]
+    np.testing.assert_allclose(acc / b, full / b, rtol=1e-12, atol=1e-13)
+    with pytest.raises(ValueError):
+        oracle.lsq_grad_rows(A, y, x, np.full((n, 1), b, dtype=np.int32), 1.0)
