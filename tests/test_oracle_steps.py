@@ -392,3 +392,28 @@ def test_stats_against_library_moments(oracle):
     same = np.tile(r.standard_normal(d), (n, 1))
     assert oracle.stats(same)[0] < 1e-25          # identical rows: no consensus distance beyond rounding of the mean
     assert np.all(oracle.stats(x)[2:] == 0.0)
+
+
+def test_oracle_reproduces_its_frozen_trajectory():
+    """tests/golden/oracle_traj_c1.txt was written by make_golden.py from the oracle alone; the oracle
+    must still produce it bit for bit (guards against silent changes of its arithmetic)."""
+    import importlib.util
+    import os
+
+    here = os.path.join(os.path.dirname(__file__), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now = mod.trajectories()
+    seen = 0
+    with open(os.path.join(here, "oracle_traj_c1.txt")) as f:
+        for line in f:
+            if line.startswith("#"):
+                continue
+            head, tail = line.split(":")
+            algo, name, i = head.split()
+            want = np.array([float.fromhex(t) for t in tail.split()], dtype=np.float32)
+            got = now[algo][0 if name == "x" else 1][int(i)]
+            np.testing.assert_array_equal(got, want)
+            seen += 1
+    assert seen == 16
