@@ -251,6 +251,10 @@ def main():
             extras[f"{algo}_step_{name}"] = {"kernel_ms": round(k2, 4), "GBps": round(b2 / (k2 * 1e-3) / 1e9, 1),
                                              "frac_of_hbm_peak": round(b2 / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         extras["local_grad_lsq_c5"] = bench_lsq(P, workloads, "c5_onepeer64_lsq", args.steps, args.warmup)
+        # the small workloads are launch-latency bound: report microseconds per call
+        w1 = workloads.get("c1_ring4")
+        _, _, _, _, _, k1 = bench_step(P, workloads, "c1_ring4", "decentlam", 200, 20)
+        extras["decentlam_step_c1_ring4_us"] = round(k1 * 1e3, 2)
         out["extras"] = extras
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, kind, args.algo)

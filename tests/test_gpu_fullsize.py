@@ -36,7 +36,7 @@ def sample_columns(d, seed, block=64, blocks=48, edge=1024):
     return np.unique(np.concatenate(cols))
 
 
-def run_sampled_trajectory(P, oracle, w, algo, kind, stepper=None):
+def run_sampled_trajectory(P, oracle, w, algo, kind, stepper=None, ld=None):
     import workloads
 
     d = workloads.generate.dim(w)
@@ -45,14 +45,15 @@ def run_sampled_trajectory(P, oracle, w, algo, kind, stepper=None):
     gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
     cols = sample_columns(d, seed=w.cfg)
     cols_t = torch.from_numpy(cols).cuda()
-    x = workloads.device_x0(w, "cuda")
-    m = torch.zeros_like(x)
-    g = torch.empty_like(x)
+    xb = workloads.device_x0(w, "cuda", ld=ld)
+    mb = torch.zeros_like(xb)
+    gb = torch.zeros_like(xb)
+    x, m, g = xb[:, :d], mb[:, :d], gb[:, :d]
     xs = x.index_select(1, cols_t).cpu().numpy().astype(np.float64)
     ms = np.zeros_like(xs)
     fn = getattr(P, algo + "_step")
     for k in range(w.steps):
-        workloads.device_grad(w, k, g)
+        workloads.device_grad(w, k, gb)
         gs = g.index_select(1, cols_t).cpu().numpy().astype(np.float64)
         if stepper is None:
             fn(x, m, g, topo, gamma, beta, k)
@@ -93,6 +94,10 @@ def test_workload4_ragged_flat_and_ranged_calls(P, oracle):
 
     x_rng, m_rng = run_sampled_trajectory(P, oracle, w, "decentlam", 0, stepper=ranged)
     assert torch.equal(x_flat, x_rng) and torch.equal(m_flat, m_rng)
+    # the benchmark's layout: rows padded to a multiple of 64 elements (256-byte aligned rows)
+    d = int(offsets[-1])
+    x_pad, m_pad = run_sampled_trajectory(P, oracle, w, "decentlam", 0, ld=(d + 63) // 64 * 64)
+    assert torch.equal(x_flat, x_pad) and torch.equal(m_flat, m_pad)
 
 
 def test_workload5_lsq_gradient_then_step(P, oracle):
@@ -137,3 +142,33 @@ def test_workload5_lsq_gradient_then_step(P, oracle):
         P.decentlam_step(x, m, g, topo, gamma, beta, k)
         losses.append(float(loss.sum()))
     assert np.isfinite(losses).all() and bool(torch.isfinite(x).all())
+
+
+def test_more_than_2_pow_31_elements_per_array(P, oracle):
+    """64-bit indexing: n x d = 3 x 800 000 003 (2.4 G elements, 9.6 GB per array, odd d so that the
+    body / tail split is exercised far from the origin).  Sampled columns against the oracle,
+    including the very last ones."""
+    n, d = 3, 800_000_003
+    topo = P.topology_build(P.DL_TOPO_RING, n)
+    otopo = oracle.topology(oracle.RING, n)
+    gamma, beta = float(np.float32(0.05)), float(np.float32(0.9))
+    gen = torch.Generator(device="cuda").manual_seed(31)
+    x = torch.empty((n, d), dtype=torch.float32, device="cuda").normal_(generator=gen)
+    m = torch.empty((n, d), dtype=torch.float32, device="cuda").normal_(generator=gen)
+    g = torch.empty((n, d), dtype=torch.float32, device="cuda").normal_(generator=gen)
+    cols = np.unique(np.concatenate([np.arange(0, 512), np.arange(d - 515, d),
+                                     np.arange(715_827_880, 715_827_890),      # around 2^31 / 3
+                                     np.arange(2**29 - 4, 2**29 + 4)]))
+    ct = torch.from_numpy(cols).cuda()
+    for algo in ("decentlam", "dmsgd"):
+        xs, ms, gs = (t.index_select(1, ct).cpu().numpy().astype(np.float64) for t in (x, m, g))
+        getattr(P, algo + "_step")(x, m, g, topo, gamma, beta, 0)
+        xr, mr = oracle.STEP[algo](xs, ms, gs, otopo, gamma, beta, 0)
+        check_elementwise(x.index_select(1, ct).cpu().numpy(), xr, algo + " x")
+        check_elementwise(m.index_select(1, ct).cpu().numpy(), mr, algo + " m")
+    out = torch.empty(5, dtype=torch.float64, device="cuda")
+    ws = torch.empty(P.decentlam_stats_workspace(n, d), dtype=torch.uint8, device="cuda")
+    P.decentlam_stats(x, m, None, out, ws)
+    got = out.cpu().numpy()
+    m2 = float((m.double() ** 2).sum())
+    assert abs(got[4] - m2) <= 1e-9 * m2
