@@ -106,10 +106,17 @@ class Topology:
     flags: int = 0
 
     def _args(self):
-        return (self.row_ptr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
-                self.col_idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
-                self.w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
-                self.period)
+        # the ctypes pointers are built once per (array identity) -- the step functions are called
+        # every iteration and the small workloads are launch-latency bound
+        key = (id(self.row_ptr), id(self.col_idx), id(self.w), self.period)
+        cached = self.__dict__.get("_cached_args")
+        if cached is None or cached[0] != key:
+            cached = (key, (self.row_ptr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                            self.col_idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                            self.w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+                            self.period))
+            self.__dict__["_cached_args"] = cached
+        return cached[1]
 
 
 def topology_build(kind: int, n: int, seed: int = 0, phases: int = 1) -> Topology:

@@ -410,3 +410,55 @@ def test_local_grad_lsq_rows_matches_oracle(P, oracle, n, b, d, bs, pad):
     gr, lr = oracle.lsq_grad_rows(A0, y0, x0, rows0, scale)
     check_elementwise(g.cpu().numpy(), gr, "g")
     check_elementwise(loss.cpu().numpy(), lr, "loss")
+
+
+# ---------------------------------------------------------------- HIP graph capture
+def test_iteration_is_capturable_in_a_hip_graph(P):
+    """The small least-squares workload is launch-latency bound.  All entry points only enqueue
+    kernels on the caller's stream (no allocation, no synchronisation, no memset), so one period of
+    the time-varying topology (gradient + step for k = 0, 1, 2) can be captured once and replayed.
+    Every replay is checked against eager execution, with eager work and synchronisations in between."""
+    import workloads
+
+    w = workloads.get("c2_onepeer8_b32")
+    A0, y0, _ = workloads.lsq_problem(w)
+    topo = P.topology_build(w.topo, w.n)
+    assert topo.period == 3
+    gamma, beta, scale = (float(np.float32(v)) for v in (w.gamma, w.beta, w.lsq_scale))
+    A, y = dev(A0), dev(y0)
+    ws = torch.empty(P.local_grad_lsq_workspace(w.n, w.b, w.d), dtype=torch.uint8, device="cuda")
+
+    def period(x, m, g):
+        for k in range(3):
+            P.local_grad_lsq(A, y, x, g, None, scale, ws)
+            P.dmsgd_step(x, m, g, topo, gamma, beta, k)
+
+    # eager reference: 5 periods, state recorded after each
+    xe = torch.zeros((w.n, w.d), dtype=torch.float32, device="cuda")
+    me, ge = torch.zeros_like(xe), torch.zeros_like(xe)
+    eager = []
+    for _ in range(5):
+        period(xe, me, ge)
+        eager.append((xe.clone(), me.clone()))
+
+    xg = torch.zeros((w.n, w.d), dtype=torch.float32, device="cuda")
+    mg, gg = torch.zeros_like(xg), torch.zeros_like(xg)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):          # warm-up on the capture stream, then restore the state
+        period(xg, mg, gg)
+    torch.cuda.current_stream().wait_stream(side)
+    xg.zero_()
+    mg.zero_()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        period(xg, mg, gg)
+    xg.zero_()
+    mg.zero_()
+    scratch = torch.zeros(1000, device="cuda")
+    for r in range(5):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(xg, eager[r][0]) and torch.equal(mg, eager[r][1]), f"replay {r} differs from eager"
+        scratch.add_(1.0)                  # unrelated eager work between replays
+        torch.cuda.synchronize()
