@@ -37,7 +37,7 @@ extern "C" {
 typedef enum {
     DL_OK = 0,
     DL_EINVAL = -1, /* bad scalar/pointer argument                                  */
-    DL_ETOPO = -2,  /* neighbour list malformed or beyond DL_MAX_NODES / DL_MAX_NNZ */
+    DL_ETOPO = -2,  /* neighbour list malformed or beyond DL_MAX_NODES / DL_MAX_NNZ* */
     DL_ECAP = -3,   /* an output or workspace capacity is too small                 */
     DL_EHIP = -4,   /* a HIP runtime call failed (text in dl_last_error)            */
     DL_EALIAS = -5  /* x, m, g (or A, y, x, g) overlap                              */
@@ -60,7 +60,9 @@ typedef enum {
 
 /* limits of the step kernels: the phase's neighbour list travels in the kernel arguments */
 #define DL_MAX_NODES 256
-#define DL_MAX_NNZ 512 /* entries per phase */
+#define DL_MAX_NNZ 512            /* entries per phase, arbitrary weights                                 */
+#define DL_MAX_NNZ_PALETTE 1536   /* entries per phase when it holds at most DL_MAX_WEIGHT_VALUES distinct */
+#define DL_MAX_WEIGHT_VALUES 64   /* weight values (true of every topology topology_build produces)       */
 
 /*
  * topology_build -- neighbour lists and weights of the paper's topologies
@@ -143,6 +145,25 @@ int dmsgd_step(float* x, float* m, const float* g,
                int32_t n, int64_t d, int64_t ld,
                const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
                float gamma, float beta, int64_t k, void* stream);
+
+/*
+ * decentlam_step_xprev -- DecentLaM in its momentum-free form (appendix "Reformulation of
+ * DecentLaM"): with m^k = (x^{k-1} - x^k) / gamma_{k-1} eliminated,
+ *     x^{k+1} = W (x^k - gamma_k g^k) + beta (gamma_k / gamma_{k-1}) (x^k - x^{k-1}).
+ * The state is the pair (x^k, x^{k-1}) instead of (x^k, m^k); m^0 = 0 corresponds to
+ * x^{-1} = x^0.  Same iterates as decentlam_step in exact arithmetic.
+ *
+ *   x      [in]     device, n x d fp32 (ld): x^k, not modified.
+ *   x_prev [in,out] device, same shape: x^{k-1} on entry, x^{k+1} on exit.  The caller swaps the
+ *                   roles of the two buffers after every call.
+ *   gamma_prev      the learning rate of the previous call (pass gamma for a constant rate).
+ * Reads x, x_prev, g and writes one array: 16 bytes per node-element.  Other arguments,
+ * conventions and errors as decentlam_step.
+ */
+int decentlam_step_xprev(const float* x, float* x_prev, const float* g,
+                         int32_t n, int64_t d, int64_t ld,
+                         const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                         float gamma, float gamma_prev, float beta, int64_t k, void* stream);
 
 /*
  * dsgd_step -- one iteration of DSGD (eqs. (4)-(5), compact form x <- W (x - gamma g)), the

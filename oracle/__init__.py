@@ -57,6 +57,9 @@ def _load():
                 ctypes.c_double, ctypes.c_int64, f64p, f64p, f64p, f64p, f64p]
         _lib.oracle_dmsgd_step.argtypes = step
         _lib.oracle_decentlam_step.argtypes = step
+        _lib.oracle_decentlam_xprev_step.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, i32p, i32p, f32p,
+                                                     ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                                     ctypes.c_int64, f64p, f64p, f64p, f64p]
         _lib.oracle_lsq_grad_rows.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, f32p, f32p, f64p, i32p,
                                               ctypes.c_int, ctypes.c_double, f64p, f64p]
         _lib.oracle_stats.argtypes = [ctypes.c_int, ctypes.c_int64, f64p, f64p, f64p, f64p]
@@ -167,6 +170,21 @@ def dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0):
 def decentlam_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0):
     """One iteration of Algorithm 2 -> (x_next, m_next), float64."""
     return _mom_step(_load().oracle_decentlam_step, x, m, g, topo, gamma, beta, k)
+
+
+def decentlam_xprev_step(x, x_prev, g, topo: Topology, gamma: float, beta: float, k: int = 0,
+                         gamma_prev: float | None = None):
+    """Momentum-free DecentLaM: x_next = W(x - gamma g) + beta (gamma/gamma_prev) (x - x_prev), float64."""
+    x, x_prev, g = _f64(x), _f64(x_prev), _f64(g)
+    n, d = x.shape
+    assert n == topo.n and x_prev.shape == x.shape and g.shape == x.shape
+    xo = np.empty_like(x)
+    rc = _load().oracle_decentlam_xprev_step(n, d, *_topo_args(topo), float(gamma),
+                                             float(gamma if gamma_prev is None else gamma_prev), float(beta),
+                                             int(k), _p(x, ctypes.c_double), _p(x_prev, ctypes.c_double),
+                                             _p(g, ctypes.c_double), _p(xo, ctypes.c_double))
+    assert rc == 0
+    return xo
 
 
 def lsq_grad(A, y, x, scale: float = 1.0):

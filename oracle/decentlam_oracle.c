@@ -296,6 +296,38 @@ int oracle_decentlam_step(int n, int64_t d, int period, const int32_t* row_ptr,
     return 0;
 }
 
+/* DecentLaM without the momentum array, appendix "Reformulation of DecentLaM":
+ *   x^{k+1} = W (x^k - gamma g^k) + beta (x^k - x^{k-1})
+ * Reading for a learning rate that changes between iterations (the appendix derives the constant
+ * case): eliminating m^k = (x^{k-1} - x^k)/gamma_{k-1} from Algorithm 2 gives the factor
+ * beta * gamma_k / gamma_{k-1} in front of the difference.  m^0 = 0 corresponds to x^{-1} = x^0. */
+int oracle_decentlam_xprev_step(int n, int64_t d, int period, const int32_t* row_ptr,
+                                const int32_t* col_idx, const float* w, double gamma, double gamma_prev,
+                                double beta, int64_t k, const double* x, const double* x_prev,
+                                const double* g, double* x_out)
+{
+    const int32_t* rp = row_ptr + (k % period) * (n + 1);
+    size_t cnt = (size_t)n * (size_t)(d > 0 ? d : 1);
+    double* local = (double*)malloc(sizeof(double) * cnt);
+    double* z = (double*)malloc(sizeof(double) * cnt);
+    if (!local || !z) { free(local); free(z); return -2; }
+    for (int i = 0; i < n; ++i)
+        for (int64_t c = 0; c < d; ++c) {
+            int64_t q = (int64_t)i * d + c;
+            local[q] = x[q] - gamma * g[q];
+        }
+    partial_average(n, d, rp, col_idx, w, local, z);
+    double factor = beta * gamma / gamma_prev;
+    for (int i = 0; i < n; ++i)
+        for (int64_t c = 0; c < d; ++c) {
+            int64_t q = (int64_t)i * d + c;
+            x_out[q] = z[q] + factor * (x[q] - x_prev[q]);
+        }
+    free(local);
+    free(z);
+    return 0;
+}
+
 /* Least-squares gradient of f_i(x) = (scale/2) ||A_i x - y_i||^2 (appendix
  * "Experimental setting for linear regression": grad f_i = A_i^T (A_i x - b_i),
  * scale = 1 there):

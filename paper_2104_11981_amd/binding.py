@@ -26,9 +26,9 @@ DL_OK, DL_EINVAL, DL_ETOPO, DL_ECAP, DL_EHIP, DL_EALIAS = 0, -1, -2, -3, -4, -5
 DL_TOPO_RING, DL_TOPO_EXP_STATIC, DL_TOPO_EXP_ONEPEER = 0, 1, 2
 DL_TOPO_EXP_SYM, DL_TOPO_MESH, DL_TOPO_BIPARTITE_MATCH = 3, 4, 5
 DL_FLAG_ROW_STOCHASTIC, DL_FLAG_COL_STOCHASTIC, DL_FLAG_SYMMETRIC = 1, 2, 4
-DL_MAX_NODES, DL_MAX_NNZ = 256, 512
+DL_MAX_NODES, DL_MAX_NNZ, DL_MAX_NNZ_PALETTE, DL_MAX_WEIGHT_VALUES = 256, 512, 1536, 64
 
-EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decentlam_step", "dmsgd_step", "dsgd_step", "local_grad_lsq", "local_grad_lsq_rows",
+EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decentlam_step", "decentlam_step_xprev", "dmsgd_step", "dsgd_step", "local_grad_lsq", "local_grad_lsq_rows",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
 
@@ -61,6 +61,10 @@ def _load() -> ctypes.CDLL:
     for name in ("decentlam_step", "dmsgd_step"):
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = step
+    lib.decentlam_step_xprev.restype = ctypes.c_int
+    lib.decentlam_step_xprev.argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, i32p,
+                                         f32p, ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                         ctypes.c_int64, vp]
     lib.dsgd_step.restype = ctypes.c_int
     lib.dsgd_step.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, i32p, f32p,
                               ctypes.c_int32, ctypes.c_float, ctypes.c_int64, vp]
@@ -187,6 +191,21 @@ def decentlam_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 
 def dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
     """One DmSGD iteration in place on device tensors x, m (n x d fp32), asynchronous."""
     _step(_lib.dmsgd_step, x, m, g, topo, gamma, beta, k, stream)
+
+
+def decentlam_step_xprev(x, x_prev, g, topo: Topology, gamma: float, beta: float, k: int = 0,
+                         gamma_prev: float | None = None, stream=None):
+    """Momentum-free DecentLaM: x_prev (x^{k-1}) is overwritten with x^{k+1}; x (x^k) is only read."""
+    px, n, d, ld = _matrix_args(x, "x")
+    pp, n2, d2, ld2 = _matrix_args(x_prev, "x_prev")
+    pg, ng, dg, ldg = _matrix_args(g, "g")
+    if (n2, d2, ld2) != (n, d, ld) or (ng, dg, ldg) != (n, d, ld):
+        raise TypeError("x, x_prev and g must share shape and row stride")
+    if topo.n != n:
+        raise DecentLamError(DL_ETOPO, f"topology has {topo.n} nodes, arrays have {n} rows")
+    _check(_lib.decentlam_step_xprev(px, pp, pg, n, d, ld, *topo._args(), gamma,
+                                     gamma if gamma_prev is None else gamma_prev, beta, k,
+                                     _stream() if stream is None else stream))
 
 
 def dsgd_step(x, g, topo: Topology, gamma: float, k: int = 0, stream=None):

@@ -51,10 +51,14 @@ int pack_phase(const char* fn, int32_t n, const int32_t* row_ptr, const int32_t*
     const int64_t nnz = static_cast<int64_t>(rp[n]) - base;
     if (base < 0 || nnz < n)
         return set_error(DL_ETOPO, "%s: phase %d: row_ptr not monotone or a row is empty", fn, p);
-    if (nnz > DL_MAX_NNZ)
-        return set_error(DL_ETOPO, "%s: phase %d has %lld entries, limit DL_MAX_NNZ = %d", fn, p,
-                         static_cast<long long>(nnz), DL_MAX_NNZ);
+    if (nnz > kMaxNnzPalette)
+        return set_error(DL_ETOPO, "%s: phase %d has %lld entries, limit DL_MAX_NNZ_PALETTE = %d", fn, p,
+                         static_cast<long long>(nnz), kMaxNnzPalette);
     out->n = n;
+    // first pass: validate, and collect the distinct weight values while there are few of them
+    float values[kMaxWeightValues];
+    int n_values = 0;
+    bool few_values = true;
     int32_t last_seen[DL_MAX_NODES];
     for (int32_t j = 0; j < n; ++j) last_seen[j] = -1;
     for (int32_t i = 0; i < n; ++i) {
@@ -76,20 +80,48 @@ int pack_phase(const char* fn, int32_t n, const int32_t* row_ptr, const int32_t*
                 return set_error(DL_ETOPO, "%s: phase %d: w[%d,%d] = %g must be finite and > 0", fn,
                                  p, i, j, static_cast<double>(wij));
             sum += static_cast<double>(wij);
-            out->col[q - base] = static_cast<uint8_t>(j);
-            out->w[q - base] = wij;
+            if (few_values) {
+                int v = 0;
+                while (v < n_values && values[v] != wij) ++v;
+                if (v == n_values) {
+                    if (n_values < kMaxWeightValues) values[n_values++] = wij;
+                    else few_values = false;
+                }
+            }
         }
         if (std::fabs(sum - 1.0) > 1e-6)
             return set_error(DL_ETOPO, "%s: phase %d row %d sums to %.9g, not 1", fn, p, i, sum);
     }
     out->row_ptr[n] = static_cast<uint16_t>(nnz);
+    // second pass: encode
+    if (few_values) {
+        out->palette = 1;
+        for (int v = 0; v < n_values; ++v) out->pal.value[v] = values[v];
+        for (int64_t q = 0; q < nnz; ++q) {
+            out->pal.col[q] = static_cast<uint8_t>(col_idx[base + q]);
+            int v = 0;
+            while (values[v] != w[base + q]) ++v;
+            out->pal.widx[q] = static_cast<uint8_t>(v);
+        }
+        return DL_OK;
+    }
+    if (nnz > DL_MAX_NNZ)
+        return set_error(DL_ETOPO, "%s: phase %d has %lld entries with more than %d distinct weights, "
+                         "limit DL_MAX_NNZ = %d", fn, p, static_cast<long long>(nnz), kMaxWeightValues, DL_MAX_NNZ);
+    out->palette = 0;
+    for (int64_t q = 0; q < nnz; ++q) {
+        out->direct.col[q] = static_cast<uint8_t>(col_idx[base + q]);
+        out->direct.w[q] = w[base + q];
+    }
     return DL_OK;
 }
 
 int step_entry(const char* fn, Algo algo, float* x, float* m, const float* g, int32_t n, int64_t d,
                int64_t ld, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
-               int32_t period, float gamma, float beta, int64_t k, void* stream) {
+               int32_t period, float gamma, float beta, int64_t k, void* stream, float gamma_prev = 0.0f) {
     clear_error();
+    if (algo == ALGO_DECENTLAM_XPREV && (!std::isfinite(gamma_prev) || !(gamma_prev > 0.0f)))
+        return set_error(DL_EINVAL, "%s: gamma_prev = %g must be finite and > 0", fn, static_cast<double>(gamma_prev));
     if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
     if (d < 0) return set_error(DL_EINVAL, "%s: d = %lld, need d >= 0", fn, static_cast<long long>(d));
     if (ld < d)
@@ -126,7 +158,10 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const float* g, in
     if ((uses_m && (shares(x, sx, m, sm) || shares(m, sm, g, sg))) || shares(x, sx, g, sg))
         return set_error(DL_EALIAS, "%s: x, m and g must not overlap", fn);
 
-    return launch_step(algo, x, m, g, n, d, ld, topo, gamma, beta, static_cast<hipStream_t>(stream));
+    double beta_eff = static_cast<double>(beta);
+    if (algo == ALGO_DECENTLAM_XPREV)
+        beta_eff = beta_eff * static_cast<double>(gamma) / static_cast<double>(gamma_prev);
+    return launch_step(algo, x, m, g, n, d, ld, topo, gamma, beta_eff, static_cast<hipStream_t>(stream));
 }
 
 }  // namespace
@@ -146,6 +181,13 @@ int dmsgd_step(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t
                float gamma, float beta, int64_t k, void* stream) {
     return dl::step_entry("dmsgd_step", dl::ALGO_DMSGD, x, m, g, n, d, ld, row_ptr, col_idx, w, period,
                           gamma, beta, k, stream);
+}
+
+int decentlam_step_xprev(const float* x, float* x_prev, const float* g, int32_t n, int64_t d, int64_t ld,
+                         const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                         float gamma, float gamma_prev, float beta, int64_t k, void* stream) {
+    return dl::step_entry("decentlam_step_xprev", dl::ALGO_DECENTLAM_XPREV, const_cast<float*>(x), x_prev, g, n,
+                          d, ld, row_ptr, col_idx, w, period, gamma, beta, k, stream, gamma_prev);
 }
 
 int dsgd_step(float* x, const float* g, int32_t n, int64_t d, int64_t ld, const int32_t* row_ptr,

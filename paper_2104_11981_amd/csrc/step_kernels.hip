@@ -86,7 +86,11 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
 
 // VEC    columns per lane (width of the global accesses: 4, 8 or 16 bytes)
 // RPT    rows per thread; WAVES wavefronts per workgroup: the kernel covers n <= WAVES * RPT nodes
-// ALGO   ALGO_DECENTLAM, ALGO_DMSGD or ALGO_DSGD (x <- W (x - gamma g); m is not touched)
+// ALGO   ALGO_DECENTLAM, ALGO_DMSGD, ALGO_DSGD (x <- W (x - gamma g); m is not touched) or
+//        ALGO_DECENTLAM_XPREV: DecentLaM in its momentum-free form (appendix "Reformulation of
+//        DecentLaM"), x_next = W (x - gamma g) + beta' (x - x_prev); here `m` is the buffer that
+//        holds x_prev on entry and x_next on exit, x is only read, and `beta` carries
+//        beta' = beta * gamma / gamma_prev: 16 bytes per node-element, one written array
 template <int VEC, int RPT, int WAVES, int ALGO>
 __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, float* __restrict__ m,
                                                       const float* __restrict__ g, int64_t d, int64_t ld,
@@ -118,8 +122,13 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
     const int nnz = topo.row_ptr[n];
     for (int e = threadIdx.x; e < nnz; e += 64 * WAVES) {
         Neighbour t;
-        t.w = static_cast<double>(topo.w[e]);
-        t.offset = static_cast<int>(topo.col[e]) * TC;
+        if (topo.palette) {  // uniform over the grid
+            t.w = static_cast<double>(topo.pal.value[topo.pal.widx[e]]);
+            t.offset = static_cast<int>(topo.pal.col[e]) * TC;
+        } else {
+            t.w = static_cast<double>(topo.direct.w[e]);
+            t.offset = static_cast<int>(topo.direct.col[e]) * TC;
+        }
         t.unused = 0;
         table[e] = t;
     }
@@ -129,7 +138,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
         const int i = wave + WAVES * r;
         if (i < n && live) {
             double* slot = lds + i * TC + lane * VEC;
-            if constexpr (ALGO == ALGO_DECENTLAM || ALGO == ALGO_DSGD) {
+            if constexpr (ALGO != ALGO_DMSGD) {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v)
                     slot[v] = static_cast<double>(xr[r][v]) - gamma * static_cast<double>(gr[r][v]);
@@ -184,11 +193,17 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                     xo[v] = static_cast<float>(xi - gamma * m_new);
                 }
                 store_vec<VEC>(m + at, mo);
+            } else if constexpr (ALGO == ALGO_DECENTLAM_XPREV) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const double diff = static_cast<double>(xr[r][v]) - static_cast<double>(mr[r][v]);
+                    xo[v] = static_cast<float>(__builtin_fma(beta, diff, z[v]));
+                }
             } else {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) xo[v] = static_cast<float>(z[v]);
             }
-            store_vec<VEC>(x + at, xo);
+            store_vec<VEC>((ALGO == ALGO_DECENTLAM_XPREV ? m : x) + at, xo);
         }
     }
 }
@@ -252,8 +267,8 @@ int widest_vec_for(int32_t n) {
 
 }  // namespace
 int launch_step(Algo algo, float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
-                const PhaseArgs& topo, float gamma_f, float beta_f, hipStream_t stream) {
-    const double gamma = static_cast<double>(gamma_f), beta = static_cast<double>(beta_f);
+                const PhaseArgs& topo, float gamma_f, double beta, hipStream_t stream) {
+    const double gamma = static_cast<double>(gamma_f);
 
     // Pick the widest access all three arrays can share: same misalignment (in elements)
     // modulo the vector width and a row stride that preserves it.
@@ -279,6 +294,8 @@ int launch_step(Algo algo, float* x, float* m, const float* g, int32_t n, int64_
             return launch_cols<ALGO_DECENTLAM>(v, x + c0, m + c0, g + c0, n, cols, ld, topo, gamma, beta, stream);
         if (algo == ALGO_DSGD)
             return launch_cols<ALGO_DSGD>(v, x + c0, nullptr, g + c0, n, cols, ld, topo, gamma, beta, stream);
+        if (algo == ALGO_DECENTLAM_XPREV)
+            return launch_cols<ALGO_DECENTLAM_XPREV>(v, x + c0, m + c0, g + c0, n, cols, ld, topo, gamma, beta, stream);
         return launch_cols<ALGO_DMSGD>(v, x + c0, m + c0, g + c0, n, cols, ld, topo, gamma, beta, stream);
     };
     if (int rc = run(vec, head, body)) return rc;   // aligned body first: it is the bulk

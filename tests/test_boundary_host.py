@@ -124,7 +124,18 @@ def test_step_topology_validation():
     big = P.topology_build(0, 300)
     assert _call(fn, n=300, topo=big) == P.DL_ETOPO and "DL_MAX_NODES" in P.last_error()
     dense = _topo(32, [[(j, 1.0 / 32) for j in range(32)] for _ in range(32)])
-    assert _call(fn, n=32, topo=dense) == P.DL_ETOPO and "DL_MAX_NNZ" in P.last_error()
+    assert _call(fn, n=32, topo=dense) == P.DL_OK          # 1024 entries, one weight value: palette encoding
+    dense64 = _topo(64, [[(j, 1.0 / 64) for j in range(64)] for _ in range(64)])
+    assert _call(fn, n=64, topo=dense64) == P.DL_ETOPO and "DL_MAX_NNZ_PALETTE" in P.last_error()
+    rng = np.random.default_rng(0)
+    rows = []
+    for i in range(30):                                     # 900 entries, all weights different
+        wts = rng.uniform(0.5, 1.5, size=30).astype(np.float32).astype(np.float64)
+        wts[0] += 1e-3 * i
+        wts = (wts / wts.sum()).astype(np.float32)
+        rows.append([(j, float(wts[j])) for j in range(30)])
+    assert _call(fn, n=30, topo=_topo(30, rows)) == P.DL_ETOPO and "distinct" in P.last_error()
+    assert _call(fn, n=16, topo=_topo(16, [r[:16] for r in rows[:16]])) in (P.DL_OK, P.DL_ETOPO)  # row sums decide
     # time-varying W: the phase used is k mod period, and only that phase is inspected
     t = P.topology_build(2, 8)
     t.w[2 * 16 + 3] = -1.0                            # corrupt phase 2 only
@@ -234,3 +245,16 @@ def test_lsq_rows_argument_validation():
     assert call(wsb=ws - 1) == P.DL_ECAP
     assert call(rows=0x40000) == P.DL_EALIAS
     assert call(rows=0x60002) == P.DL_EINVAL
+
+
+def test_decentlam_xprev_argument_validation():
+    t = P.topology_build(0, 4)
+    f = lambda **kw: P.raw.decentlam_step_xprev(kw.get("x"), kw.get("xp"), kw.get("g"), 4, kw.get("d", 0),
+                                                kw.get("ld", 0), *t._args(), kw.get("gamma", 0.1),
+                                                kw.get("gp", 0.1), kw.get("beta", 0.9), 0, None)
+    assert f() == P.DL_OK
+    assert f(gp=0.0) == P.DL_EINVAL and "gamma_prev" in P.last_error()
+    assert f(gp=float("nan")) == P.DL_EINVAL
+    assert f(beta=1.0) == P.DL_EINVAL
+    assert f(d=8, ld=8, x=4096, xp=4096, g=8192) == P.DL_EALIAS
+    assert f(d=8, ld=8, x=4096, xp=0, g=8192) == P.DL_EINVAL

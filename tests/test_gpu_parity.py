@@ -59,8 +59,11 @@ STEP_CASES = [
     (2, 64, 517, 3, 0, 7, 0.05),      # n = 64 uses 8-byte accesses
     (1, 64, 300, 0, 2, 2, 0.05),
     (0, 100, 333, 0, 0, 2, 0.1),      # n > 64: 4-byte accesses
-    (2, 256, 130, 2, 0, 9, 0.1),      # DL_MAX_NODES with exactly DL_MAX_NNZ entries per phase
-    (0, 170, 67, 0, 0, 2, 0.1),       # largest ring that fits DL_MAX_NNZ (510 entries)
+    (2, 256, 130, 2, 0, 9, 0.1),      # DL_MAX_NODES, 512 entries per phase
+    (0, 170, 67, 0, 0, 2, 0.1),
+    (0, 256, 67, 0, 0, 2, 0.1),       # 768 entries: beyond DL_MAX_NNZ, palette encoding of the weights
+    (1, 128, 70, 0, 0, 2, 0.1),       # 1024 entries
+    (3, 64, 300, 0, 0, 3, 0.1),       # symmetric exponential graph on 64 nodes, 768 entries
     (1, 7, 129, 0, 0, 3, 0.1),        # n not a power of two
     (0, 1, 70, 0, 0, 3, 0.1),         # single node: W = [1]
     (0, 2, 5, 0, 0, 3, 0.1),          # ring degenerates to a pair
@@ -462,3 +465,87 @@ def test_iteration_is_capturable_in_a_hip_graph(P):
         assert torch.equal(xg, eager[r][0]) and torch.equal(mg, eager[r][1]), f"replay {r} differs from eager"
         scratch.add_(1.0)                  # unrelated eager work between replays
         torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------- momentum-free DecentLaM
+@pytest.mark.parametrize("kind,n,d,pad,off,steps", [(1, 32, 1030, 2, 0, 6), (2, 8, 1000, 0, 0, 7), (0, 16, 2051, 1, 3, 4),
+                                                     (3, 64, 517, 3, 0, 4), (4, 12, 515, 1, 0, 4), (0, 100, 333, 0, 0, 3),
+                                                     (0, 1, 70, 0, 0, 3), (5, 16, 300, 0, 0, 6)])
+def test_decentlam_xprev_matches_oracle(P, oracle, kind, n, d, pad, off, steps):
+    """Buffers rotate as a caller would rotate them; a changing learning rate exercises gamma_prev."""
+    beta = float(np.float32(0.9))
+    topo, otopo = topo_pair(P, oracle, kind, n)
+    rng = np.random.default_rng(500 + n + d)
+    x0 = rng.standard_normal((n, d)).astype(np.float32)
+    ld = d + pad + off
+    bufs = [torch.full((n, ld), 3.0, dtype=torch.float32, device="cuda") for _ in range(3)]
+    cur, prev, g = (b[:, off:off + d] for b in bufs)
+    cur.copy_(dev(x0))
+    prev.copy_(dev(x0))                                # x^{-1} = x^0
+    xc, xp = x0.astype(np.float64), x0.astype(np.float64)
+    gammas = [float(np.float32(0.05 * (1 + 0.2 * k))) for k in range(steps)]
+    for k in range(steps):
+        gk = rng.standard_normal((n, d)).astype(np.float32)
+        g.copy_(dev(gk))
+        gp = gammas[k - 1] if k else gammas[0]
+        P.decentlam_step_xprev(cur, prev, g, topo, gammas[k], beta, k, gamma_prev=gp)
+        xn = oracle.decentlam_xprev_step(xc, xp, gk, otopo, gammas[k], beta, k, gamma_prev=gp)
+        xn = xn.astype(np.float32).astype(np.float64)
+        check_elementwise(prev.cpu().numpy(), xn, f"x after iteration {k}")
+        np.testing.assert_array_equal(cur.cpu().numpy(), xc.astype(np.float32))      # x^k is only read
+        cur, prev = prev, cur
+        xc, xp = xn, xc
+    for b in bufs:
+        full = b.cpu().numpy()
+        assert np.all(full[:, :off] == 3.0) and np.all(full[:, off + d:] == 3.0)
+
+
+def test_decentlam_xprev_tracks_decentlam_step(P):
+    """Same method, two state layouts: after 30 iterations on a symmetric graph the iterates agree to fp32 noise."""
+    n, d = 32, 4096
+    topo = P.topology_build(P.DL_TOPO_EXP_SYM, n)
+    gen = torch.Generator(device="cuda").manual_seed(9)
+    x0 = torch.randn((n, d), device="cuda", generator=gen)
+    xa, ma = x0.clone(), torch.zeros_like(x0)
+    cur, prev = x0.clone(), x0.clone()
+    for k in range(30):
+        g = torch.randn((n, d), device="cuda", generator=gen)
+        P.decentlam_step(xa, ma, g, topo, 0.05, 0.9, k)
+        P.decentlam_step_xprev(cur, prev, g, topo, 0.05, 0.9, k)
+        cur, prev = prev, cur
+    rel = float((cur - xa).norm() / xa.norm())
+    assert rel < 1e-5, rel
+
+
+def test_global_averaging_and_many_weight_values(P, oracle):
+    """W = 11^T/n with n = 32 (1024 entries, one weight value: palette encoding) turns DmSGD into
+    Parallel SGD -- every node holds the same model after one iteration (Sec. "Decentralized Momentum
+    SGD"); a dense 16-node W with 256 different weights goes through the direct encoding."""
+    n, d = 32, 777
+    rows = [[(j, 1.0 / n) for j in range(n)] for _ in range(n)]
+    otopo = oracle.custom_topology(n, [rows])
+    topo = P.make_topology(n, otopo.row_ptr, otopo.col_idx, otopo.w)
+    rng = np.random.default_rng(8)
+    x0, g0 = (rng.standard_normal((n, d)).astype(np.float32) for _ in range(2))
+    x, m, g = dev(x0), torch.zeros((n, d), dtype=torch.float32, device="cuda"), dev(g0)
+    P.dmsgd_step(x, m, g, topo, 0.1, 0.9, 0)
+    xr, mr = oracle.dmsgd_step(x0, np.zeros_like(x0), g0, otopo, float(np.float32(0.1)), float(np.float32(0.9)))
+    check_elementwise(x.cpu().numpy(), xr, "x")
+    got = x.cpu().numpy()
+    assert np.all(got == got[0])                      # identical rows, bit for bit (same sum order)
+
+    n = 16
+    W = rng.uniform(0.5, 1.5, size=(n, n))
+    W = (W / W.sum(axis=1, keepdims=True)).astype(np.float32)
+    W[:, 0] += (1.0 - W.astype(np.float64).sum(axis=1)).astype(np.float32)      # row sums 1 within 1e-6
+    assert len(np.unique(W)) > 64
+    rows = [[(j, float(W[i, j])) for j in range(n)] for i in range(n)]
+    otopo = oracle.custom_topology(n, [rows])
+    topo = P.make_topology(n, otopo.row_ptr, otopo.col_idx, otopo.w)
+    x0, m0, g0 = (rng.standard_normal((n, d)).astype(np.float32) for _ in range(3))
+    for algo in ("decentlam", "dmsgd"):
+        x, m, g = dev(x0), dev(m0), dev(g0)
+        getattr(P, algo + "_step")(x, m, g, topo, 0.05, 0.9, 0)
+        xr, mr = oracle.STEP[algo](x0, m0, g0, otopo, float(np.float32(0.05)), float(np.float32(0.9)))
+        check_elementwise(x.cpu().numpy(), xr, algo + " x")
+        check_elementwise(m.cpu().numpy(), mr, algo + " m")

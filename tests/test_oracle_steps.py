@@ -417,3 +417,34 @@ def test_oracle_reproduces_its_frozen_trajectory():
             np.testing.assert_array_equal(got, want)
             seen += 1
     assert seen == 16
+
+
+# ---------------------------------------------------------------- momentum-free DecentLaM
+@pytest.mark.parametrize("kind", [0, 2, 3])
+def test_xprev_form_reproduces_algorithm_2(oracle, kind):
+    """The (x^k, x^{k-1}) recursion of the appendix "Reformulation of DecentLaM" must generate the
+    iterates of Algorithm 2 -- also with a time-varying W and with a learning rate that changes every
+    iteration (factor gamma_k / gamma_{k-1}); the momentum Algorithm 2 carries is (x^{k-1} - x^k)/gamma_{k-1}."""
+    n, d, beta, steps = 8, 6, 0.9, 14
+    topo = oracle.topology(kind, n)
+    x0, _, _ = random_state(40, n, d)
+    grads = [rng(400 + k).standard_normal((n, d)) for k in range(steps)]
+    gammas = [0.05 * (1 + 0.3 * np.sin(k)) for k in range(steps)]       # a schedule
+    xa, ma = x0.copy(), np.zeros_like(x0)
+    xc, xp = x0.copy(), x0.copy()                                       # x^{-1} = x^0  <=>  m^0 = 0
+    for k in range(steps):
+        xa, ma = oracle.decentlam_step(xa, ma, grads[k], topo, gammas[k], beta, k)
+        xn = oracle.decentlam_xprev_step(xc, xp, grads[k], topo, gammas[k], beta, k,
+                                         gamma_prev=gammas[k - 1] if k else gammas[0])
+        xc, xp = xn, xc
+        np.testing.assert_allclose(xc, xa, rtol=0, atol=1e-10)
+        np.testing.assert_allclose((xp - xc) / gammas[k], ma, rtol=0, atol=1e-8)
+
+
+def test_xprev_form_against_dense_matrices(oracle):
+    n, d, gamma, beta = 8, 5, 0.1, 0.8
+    topo = oracle.topology(1, n)
+    W = topo.dense()
+    x, xp, g = random_state(41, n, d)
+    out = oracle.decentlam_xprev_step(x, xp, g, topo, gamma, beta)
+    np.testing.assert_allclose(out, W @ (x - gamma * g) + beta * (x - xp), rtol=0, atol=1e-14)
