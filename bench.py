@@ -128,6 +128,34 @@ def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False):
     return w, d, ld, topo, wall_ms, kern_ms
 
 
+def bench_xprev(P, workloads, name, steps, warmup):
+    """Momentum-free DecentLaM (state x^k, x^{k-1}; 16 bytes per node-element), buffers rotated per step."""
+    import numpy as np
+    import torch
+
+    w = workloads.get(name)
+    d = workloads.generate.dim(w)
+    topo = P.topology_build(w.topo, w.n)
+    gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
+    bufs = [workloads.device_x0(w, "cuda")]
+    bufs.append(bufs[0].clone())
+    g = torch.empty_like(bufs[0])
+    workloads.device_grad(w, 0, g)
+    torch.cuda.synchronize()
+
+    def step(k):
+        P.decentlam_step_xprev(bufs[k % 2], bufs[(k + 1) % 2], g, topo, gamma, beta, k)
+
+    _, kern_ms = time_launches(step, steps, warmup)
+    nbytes = 16 * w.n * d
+    del bufs, g
+    torch.cuda.empty_cache()
+    return {"kernel_ms": round(kern_ms, 4), "bytes_per_node_element": 16,
+            "GBps": round(nbytes / (kern_ms * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(nbytes / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "steps_per_s": round(1e3 / kern_ms, 1)}
+
+
 def bench_lsq(P, workloads, name, steps, warmup, calibration_copy=False):
     """Workload 5: local_grad_lsq then decentlam_step per iteration; times the gradient alone too."""
     import numpy as np
@@ -250,6 +278,7 @@ def main():
             b2 = BYTES_PER_ELEMENT * w2.n * d2
             extras[f"{algo}_step_{name}"] = {"kernel_ms": round(k2, 4), "GBps": round(b2 / (k2 * 1e-3) / 1e9, 1),
                                              "frac_of_hbm_peak": round(b2 / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        extras["decentlam_step_xprev_c3_exp32"] = bench_xprev(P, workloads, "c3_exp32", args.steps, args.warmup)
         extras["local_grad_lsq_c5"] = bench_lsq(P, workloads, "c5_onepeer64_lsq", args.steps, args.warmup)
         # the small workloads are launch-latency bound: report microseconds per call
         w1 = workloads.get("c1_ring4")

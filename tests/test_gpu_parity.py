@@ -72,6 +72,8 @@ STEP_CASES = [
     (2, 8, 4, 0, 0, 4, 0.1),
     (2, 8, 255, 1, 0, 4, 0.1),
     (2, 8, 257, 3, 0, 4, 0.1),
+    (0, 4, 4095, 1, 0, 2, 0.1),       # one short of / one past a whole number of tiles
+    (0, 4, 4097, 3, 0, 2, 0.1),
     (3, 32, 1030, 2, 0, 4, 0.1),      # symmetric exponential graph, 10 entries per row
     (3, 12, 260, 0, 0, 3, 0.1),       # n not a power of two: hops collide and are dropped
     (4, 12, 515, 1, 0, 4, 0.05),      # 3 x 4 mesh: degrees 2-4, Metropolis-Hastings weights
@@ -549,3 +551,37 @@ def test_global_averaging_and_many_weight_values(P, oracle):
         xr, mr = oracle.STEP[algo](x0, m0, g0, otopo, float(np.float32(0.05)), float(np.float32(0.9)))
         check_elementwise(x.cpu().numpy(), xr, algo + " x")
         check_elementwise(m.cpu().numpy(), mr, algo + " m")
+
+
+def test_per_tensor_steps_overlap_with_gradient_production(P):
+    """The paper's workflow (Sec. "Improving Inconsistency Bias", "Efficient implementation": per-layer
+    communication overlapped with back-propagation): gradients of the tensors of a ragged layout become
+    available one tensor at a time, last layer first, on one stream; a second stream runs the ranged
+    DecentLaM step of each tensor as soon as its gradient is there.  The result equals one flat call."""
+    n, T = 8, 12
+    rng = np.random.default_rng(17)
+    sizes = rng.integers(50, 4000, size=T)
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    d = int(off[-1])
+    topo = P.topology_build(P.DL_TOPO_EXP_SYM, n)
+    gen = torch.Generator(device="cuda").manual_seed(4)
+    x0 = torch.randn((n, d), device="cuda", generator=gen)
+    m0 = torch.randn((n, d), device="cuda", generator=gen)
+    g_src = torch.randn((n, d), device="cuda", generator=gen)
+
+    x_flat, m_flat = x0.clone(), m0.clone()
+    P.decentlam_step(x_flat, m_flat, g_src, topo, 0.05, 0.9, 3)
+
+    x, m, g = x0.clone(), m0.clone(), torch.zeros_like(g_src)
+    producer, consumer = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for t in reversed(range(T)):
+        a, b = int(off[t]), int(off[t + 1])
+        with torch.cuda.stream(producer):
+            g[:, a:b].copy_(g_src[:, a:b])              # "back-propagation" delivers this tensor's gradient
+            ready = torch.cuda.Event()
+            ready.record(producer)
+        consumer.wait_event(ready)
+        P.decentlam_step(x[:, a:b], m[:, a:b], g[:, a:b], topo, 0.05, 0.9, 3, stream=consumer.cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(x, x_flat) and torch.equal(m, m_flat)
