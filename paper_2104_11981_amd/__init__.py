@@ -1,16 +1,30 @@
 """MI355X-native decentralized momentum updates (DecentLaM / DmSGD), arXiv 2104.11981.
 
-The product is `libdecentlam.so` (hand-written HIP kernels for gfx950 behind a C
-ABI, see include/decentlam.h); this package is its thin ctypes binding.  Importing
-it requires the built library -- there is no CPU or PyTorch fallback.
+The product is `libdecentlam.so` (hand-written HIP kernels for gfx950 behind a C ABI, see
+include/decentlam.h); this package is its thin ctypes binding.  There is no CPU or PyTorch
+fallback: the first use of any name below loads the shared library and raises ImportError if it
+has not been built (`python -m paper_2104_11981_amd.build`).  The binding is loaded on first use
+rather than on import so that `paper_2104_11981_amd.build` itself can be imported in a fresh tree.
 """
-from .binding import (  # noqa: F401
-    DL_EALIAS, DL_ECAP, DL_EHIP, DL_EINVAL, DL_ETOPO, DL_OK,
-    DL_FLAG_COL_STOCHASTIC, DL_FLAG_ROW_STOCHASTIC, DL_FLAG_SYMMETRIC,
-    DL_MAX_NNZ, DL_MAX_NNZ_PALETTE, DL_MAX_NODES, DL_MAX_WEIGHT_VALUES,
-    DL_TOPO_BIPARTITE_MATCH, DL_TOPO_EXP_ONEPEER, DL_TOPO_EXP_STATIC, DL_TOPO_EXP_SYM, DL_TOPO_MESH, DL_TOPO_RING,
-    EXPORTS, LIB_PATH, DecentLamError, Topology,
-    decentlam_stats, decentlam_stats_workspace, decentlam_step, decentlam_step_xprev, dmsgd_step, dsgd_step, last_error, local_grad_lsq, local_grad_lsq_workspace,
-    make_topology, topology_build, topology_metropolis,
+_BINDING_NAMES = (
+    "DL_EALIAS", "DL_ECAP", "DL_EHIP", "DL_EINVAL", "DL_ETOPO", "DL_OK",
+    "DL_FLAG_COL_STOCHASTIC", "DL_FLAG_ROW_STOCHASTIC", "DL_FLAG_SYMMETRIC",
+    "DL_MAX_NNZ", "DL_MAX_NNZ_PALETTE", "DL_MAX_NODES", "DL_MAX_WEIGHT_VALUES",
+    "DL_TOPO_BIPARTITE_MATCH", "DL_TOPO_EXP_ONEPEER", "DL_TOPO_EXP_STATIC", "DL_TOPO_EXP_SYM",
+    "DL_TOPO_MESH", "DL_TOPO_RING",
+    "EXPORTS", "LIB_PATH", "DecentLamError", "Topology",
+    "decentlam_stats", "decentlam_stats_workspace", "decentlam_step", "decentlam_step_xprev",
+    "dmsgd_step", "dsgd_step", "last_error", "local_grad_lsq", "local_grad_lsq_workspace",
+    "make_topology", "topology_build", "topology_metropolis",
 )
-from .binding import _lib as raw  # noqa: F401  (the ctypes handle, for tests of the C ABI itself)
+__all__ = list(_BINDING_NAMES) + ["raw"]
+
+
+def __getattr__(name):
+    if name in _BINDING_NAMES or name == "raw":
+        from . import binding   # raises ImportError if libdecentlam.so is missing
+
+        value = binding._lib if name == "raw" else getattr(binding, name)   # raw: the ctypes handle
+        globals()[name] = value
+        return value
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")
