@@ -156,6 +156,63 @@ def bench_xprev(P, workloads, name, steps, warmup):
             "steps_per_s": round(1e3 / kern_ms, 1)}
 
 
+def bench_g16(P, workloads, name, steps, warmup, dtype_name="bfloat16"):
+    """DecentLaM step with 16-bit gradients (x, m fp32): 18 bytes per node-element."""
+    import numpy as np
+    import torch
+
+    w = workloads.get(name)
+    d = workloads.generate.dim(w)
+    topo = P.topology_build(w.topo, w.n)
+    gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
+    ld = (d + 63) // 64 * 64
+    xb = workloads.device_x0(w, "cuda", ld=ld)
+    mb = torch.zeros_like(xb)
+    g32 = torch.zeros_like(xb)
+    workloads.device_grad(w, 0, g32)
+    gb = g32.to(getattr(torch, dtype_name))
+    del g32
+    x, m, g = xb[:, :d], mb[:, :d], gb[:, :d]
+    _, kern_ms = time_launches(lambda k: P.decentlam_step_g16(x, m, g, topo, gamma, beta, k), steps, warmup)
+    nbytes = 18 * w.n * d
+    del x, m, g, xb, mb, gb
+    torch.cuda.empty_cache()
+    return {"kernel_ms": round(kern_ms, 4), "bytes_per_node_element": 18, "g_format": dtype_name,
+            "GBps": round(nbytes / (kern_ms * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(nbytes / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "steps_per_s": round(1e3 / kern_ms, 1)}
+
+
+def bench_multi(P, workloads, name, steps, warmup):
+    """Ragged workload as one multi-tensor call with per-tensor sums of squares of g, m, x
+    (table upload + fused step + final per-tensor pass), timed as a whole."""
+    import numpy as np
+    import torch
+
+    w = workloads.get(name)
+    d = workloads.generate.dim(w)
+    _, offsets, _ = workloads.ragged_layout(w)
+    offsets = np.asarray(offsets, dtype=np.int64)
+    topo = P.topology_build(w.topo, w.n)
+    gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
+    ld = (d + 63) // 64 * 64
+    x = workloads.device_x0(w, "cuda", ld=ld)
+    m = torch.zeros_like(x)
+    g = torch.zeros_like(x)
+    workloads.device_grad(w, 0, g)
+    T = offsets.size - 1
+    norms = torch.empty((T, w.n, 3), dtype=torch.float64, device="cuda")
+    ws = torch.empty(P.decentlam_step_multi_workspace(w.n, d, T) + 256, dtype=torch.uint8, device="cuda")
+    ws = ws[(-ws.data_ptr()) % 256:]
+    _, ms = time_launches(lambda k: P.decentlam_step_multi(x, m, g, offsets, topo, gamma, beta, k,
+                                                           norms=norms, workspace=ws), steps, warmup)
+    nbytes = BYTES_PER_ELEMENT * w.n * d
+    del x, m, g, ws, norms
+    torch.cuda.empty_cache()
+    return {"ms_per_call": round(ms, 4), "tensors": int(T), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
 def bench_lsq(P, workloads, name, steps, warmup, calibration_copy=False):
     """Workload 5: local_grad_lsq then decentlam_step per iteration; times the gradient alone too."""
     import numpy as np
@@ -279,6 +336,9 @@ def main():
             extras[f"{algo}_step_{name}"] = {"kernel_ms": round(k2, 4), "GBps": round(b2 / (k2 * 1e-3) / 1e9, 1),
                                              "frac_of_hbm_peak": round(b2 / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         extras["decentlam_step_xprev_c3_exp32"] = bench_xprev(P, workloads, "c3_exp32", args.steps, args.warmup)
+        extras["decentlam_step_g16_bf16_c3_exp32"] = bench_g16(P, workloads, "c3_exp32", args.steps, args.warmup)
+        extras["decentlam_step_multi_norms_c4_ring16_ragged"] = bench_multi(P, workloads, "c4_ring16_ragged",
+                                                                             args.steps, args.warmup)
         extras["local_grad_lsq_c5"] = bench_lsq(P, workloads, "c5_onepeer64_lsq", args.steps, args.warmup)
         # the small workloads are launch-latency bound: report microseconds per call
         w1 = workloads.get("c1_ring4")

@@ -165,6 +165,73 @@ int decentlam_step_xprev(const float* x, float* x_prev, const float* g,
                          const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
                          float gamma, float gamma_prev, float beta, int64_t k, void* stream);
 
+/* Storage format of the gradient operand of the *_g16 and *_multi calls. */
+typedef enum {
+    DL_GRAD_F32 = 0,
+    DL_GRAD_BF16 = 1,   /* upper 16 bits of the fp32 pattern */
+    DL_GRAD_F16 = 2     /* IEEE binary16                      */
+} dl_grad_format;
+
+/*
+ * decentlam_step_g16, dmsgd_step_g16 -- Algorithm 2 / Algorithm 1 with the gradients held in a
+ * 16-bit format, as they come out of a mixed-precision backward pass (the paper trains in mixed
+ * precision, Sec. "Experiments", implementation details); x and m stay fp32.  Each g value is
+ * widened exactly to fp32 on load, so the call computes what decentlam_step / dmsgd_step compute on
+ * the widened array: 18 bytes per node-element instead of 20.
+ *
+ *   g         [in] device, n x d elements of `g_format` (a dl_grad_format), row stride ldg elements,
+ *                  aligned to its element size.  DL_GRAD_F32 is accepted too (g with its own stride).
+ *   ldg >= d.  For 8-byte accesses to g let rows of g start on 8-byte boundaries (ldg % 4 == 0).
+ * Everything else as decentlam_step.
+ */
+int decentlam_step_g16(float* x, float* m, const void* g, int32_t g_format,
+                       int32_t n, int64_t d, int64_t ld, int64_t ldg,
+                       const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                       float gamma, float beta, int64_t k, void* stream);
+int dmsgd_step_g16(float* x, float* m, const void* g, int32_t g_format,
+                   int32_t n, int64_t d, int64_t ld, int64_t ldg,
+                   const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                   float gamma, float beta, int64_t k, void* stream);
+
+/*
+ * decentlam_step_multi, dmsgd_step_multi -- one iteration over a table of tensors (the layers of a
+ * model, flattened and packed along the columns), optionally with per-tensor, per-node sums of
+ * squares taken from the registers of the same pass.  Such layer-wise norms are what layer-wise
+ * adaptive rate scaling, the companion of large-batch momentum SGD in the paper's comparison
+ * (Sec. "Experiments"), consumes.  The update itself is the one of decentlam_step / dmsgd_step
+ * applied to the columns [offsets[0], offsets[num_tensors]).
+ *
+ *   x, m      [in,out] device, n x ld fp32 arrays; column c of the table is x[i * ld + c].
+ *   g         [in]     device, gradient in `g_format`, row stride ldg, same column numbering.
+ *   offsets   [in]     host, num_tensors + 1 non-decreasing column offsets, 0 <= offsets[0],
+ *                      offsets[num_tensors] <= min(ld, ldg); tensor t is [offsets[t], offsets[t+1])
+ *                      (empty tensors allowed; sizes need not be multiples of anything).
+ *   norms     [out]    device, num_tensors x n x 3 doubles, or NULL for none:
+ *                      norms[(t*n + i)*3 + 0] = sum of g_i^2 over tensor t (the values as loaded),
+ *                      ... + 1 = sum of the new m_i^2, ... + 2 = sum of the new x_i^2 (the stored
+ *                      fp32 values, squared and added in fp64).  Deterministic: same inputs, same bits.
+ *   workspace [scratch] device, 8-byte aligned, at least
+ *                      decentlam_step_multi_workspace(n, offsets[num_tensors] - offsets[0], num_tensors)
+ *                      bytes; needed only when norms != NULL (per-tile partial sums).
+ * With norms == NULL this is a single fused launch like the flat call; with norms the step launch
+ * also writes one small record per tile and a final per-tensor pass follows (one launch per 440
+ * tensors; the table travels as kernel arguments: no host-to-device copy, capturable).
+ * Errors: as decentlam_step; DL_ECAP if the workspace is too small; DL_EINVAL for a bad table.
+ */
+size_t decentlam_step_multi_workspace(int32_t n, int64_t d, int32_t num_tensors);
+int decentlam_step_multi(float* x, float* m, const void* g, int32_t g_format,
+                         int32_t n, int64_t ld, int64_t ldg,
+                         int32_t num_tensors, const int64_t* offsets,
+                         double* norms, void* workspace, size_t workspace_bytes,
+                         const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                         float gamma, float beta, int64_t k, void* stream);
+int dmsgd_step_multi(float* x, float* m, const void* g, int32_t g_format,
+                     int32_t n, int64_t ld, int64_t ldg,
+                     int32_t num_tensors, const int64_t* offsets,
+                     double* norms, void* workspace, size_t workspace_bytes,
+                     const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                     float gamma, float beta, int64_t k, void* stream);
+
 /*
  * dsgd_step -- one iteration of DSGD (eqs. (4)-(5), compact form x <- W (x - gamma g)), the
  * momentum-free method both algorithms reduce to at beta = 0 and the baseline of the paper's

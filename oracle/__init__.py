@@ -237,6 +237,41 @@ def stats(x, m=None, ref=None):
     return out
 
 
+def tensor_sumsq(g, m, x, offsets):
+    """Layer-wise squared 2-norms: out[t, i] = (||g_i||^2, ||m_i||^2, ||x_i||^2) restricted to the
+    columns [offsets[t], offsets[t+1]) of tensor t, for every node i; float64[T, n, 3].
+    Plain definition, one element at a time in index order."""
+    arrays = [_f64(a) for a in (g, m, x)]
+    n = arrays[0].shape[0]
+    offsets = [int(o) for o in offsets]
+    out = np.zeros((len(offsets) - 1, n, 3))
+    for t in range(len(offsets) - 1):
+        for i in range(n):
+            for q, a in enumerate(arrays):
+                acc = 0.0
+                for v in a[i, offsets[t]:offsets[t + 1]].tolist():
+                    acc += v * v
+                out[t, i, q] = acc
+    return out
+
+
+def widen16(bits, fmt: str):
+    """Value of each 16-bit pattern (uint16 array) as float64: "bf16" = sign, 8 exponent bits
+    (bias 127), 7 fraction bits; "f16" = IEEE binary16: sign, 5 exponent bits (bias 15), 10
+    fraction bits.  Evaluated from the field definitions, no reinterpretation of bits."""
+    bits = np.asarray(bits, dtype=np.uint16).astype(np.int64)
+    ebits, fbits = (8, 7) if fmt == "bf16" else (5, 10)
+    bias = (1 << (ebits - 1)) - 1
+    sign = np.where(bits >> 15, -1.0, 1.0)
+    e = (bits >> fbits) & ((1 << ebits) - 1)
+    f = (bits & ((1 << fbits) - 1)).astype(np.float64) / (1 << fbits)
+    normal = np.ldexp(1.0 + f, (e - bias).astype(np.int64))
+    subnormal = np.ldexp(f, 1 - bias)
+    val = np.where(e == 0, subnormal, normal)
+    val = np.where(e == (1 << ebits) - 1, np.where(f == 0, np.inf, np.nan), val)
+    return sign * val
+
+
 STEP = {"decentlam": decentlam_step, "dmsgd": dmsgd_step}
 
 

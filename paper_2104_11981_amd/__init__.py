@@ -11,10 +11,11 @@ _BINDING_NAMES = (
     "DL_FLAG_COL_STOCHASTIC", "DL_FLAG_ROW_STOCHASTIC", "DL_FLAG_SYMMETRIC",
     "DL_MAX_NNZ", "DL_MAX_NNZ_PALETTE", "DL_MAX_NODES", "DL_MAX_WEIGHT_VALUES",
     "DL_TOPO_BIPARTITE_MATCH", "DL_TOPO_EXP_ONEPEER", "DL_TOPO_EXP_STATIC", "DL_TOPO_EXP_SYM",
-    "DL_TOPO_MESH", "DL_TOPO_RING",
+    "DL_TOPO_MESH", "DL_TOPO_RING", "DL_GRAD_F32", "DL_GRAD_BF16", "DL_GRAD_F16",
     "EXPORTS", "LIB_PATH", "DecentLamError", "Topology",
     "decentlam_stats", "decentlam_stats_workspace", "decentlam_step", "decentlam_step_xprev",
-    "dmsgd_step", "dsgd_step", "last_error", "local_grad_lsq", "local_grad_lsq_workspace",
+    "dmsgd_step", "dsgd_step", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
+    "dmsgd_step_multi", "decentlam_step_multi_workspace", "last_error", "local_grad_lsq", "local_grad_lsq_workspace",
     "make_topology", "topology_build", "topology_metropolis",
 )
 __all__ = list(_BINDING_NAMES) + ["raw"]

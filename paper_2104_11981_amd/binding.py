@@ -28,7 +28,11 @@ DL_TOPO_EXP_SYM, DL_TOPO_MESH, DL_TOPO_BIPARTITE_MATCH = 3, 4, 5
 DL_FLAG_ROW_STOCHASTIC, DL_FLAG_COL_STOCHASTIC, DL_FLAG_SYMMETRIC = 1, 2, 4
 DL_MAX_NODES, DL_MAX_NNZ, DL_MAX_NNZ_PALETTE, DL_MAX_WEIGHT_VALUES = 256, 512, 1536, 64
 
-EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decentlam_step", "decentlam_step_xprev", "dmsgd_step", "dsgd_step", "local_grad_lsq", "local_grad_lsq_rows",
+DL_GRAD_F32, DL_GRAD_BF16, DL_GRAD_F16 = 0, 1, 2
+
+EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decentlam_step", "decentlam_step_xprev",
+           "dmsgd_step", "dsgd_step", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
+           "dmsgd_step_multi", "decentlam_step_multi_workspace", "local_grad_lsq", "local_grad_lsq_rows",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
 
@@ -61,6 +65,19 @@ def _load() -> ctypes.CDLL:
     for name in ("decentlam_step", "dmsgd_step"):
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = step
+    for name in ("decentlam_step_g16", "dmsgd_step_g16"):
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64,
+                                       ctypes.c_int64, i32p, i32p, f32p, ctypes.c_int32, ctypes.c_float,
+                                       ctypes.c_float, ctypes.c_int64, vp]
+    for name in ("decentlam_step_multi", "dmsgd_step_multi"):
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64,
+                                       ctypes.c_int32, ctypes.POINTER(ctypes.c_int64), vp, vp, ctypes.c_size_t,
+                                       i32p, i32p, f32p, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
+                                       ctypes.c_int64, vp]
+    lib.decentlam_step_multi_workspace.restype = ctypes.c_size_t
+    lib.decentlam_step_multi_workspace.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32]
     lib.decentlam_step_xprev.restype = ctypes.c_int
     lib.decentlam_step_xprev.argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, i32p,
                                          f32p, ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_float,
@@ -191,6 +208,85 @@ def decentlam_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 
 def dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
     """One DmSGD iteration in place on device tensors x, m (n x d fp32), asynchronous."""
     _step(_lib.dmsgd_step, x, m, g, topo, gamma, beta, k, stream)
+
+
+_GRAD_FORMAT = {torch.float32: DL_GRAD_F32, torch.bfloat16: DL_GRAD_BF16, torch.float16: DL_GRAD_F16}
+
+
+def _grad_args(g, n, d):
+    if g.dtype not in _GRAD_FORMAT or not g.is_cuda or g.dim() != 2:
+        raise TypeError("g: need a 2-D float32, bfloat16 or float16 device tensor")
+    if tuple(g.shape) != (n, d):
+        raise TypeError("g must have x's shape")
+    if d > 0 and g.stride(1) != 1:
+        raise TypeError("g: columns must be contiguous")
+    return g.data_ptr(), _GRAD_FORMAT[g.dtype], (g.stride(0) if n > 1 else max(g.stride(0), d))
+
+
+def _step_g16(fn, x, m, g, topo, gamma, beta, k, stream):
+    px, n, d, ld = _matrix_args(x, "x")
+    pm, nm, dm, ldm = _matrix_args(m, "m")
+    if (nm, dm, ldm) != (n, d, ld):
+        raise TypeError("x and m must share shape and row stride")
+    pg, fmt, ldg = _grad_args(g, n, d)
+    if topo.n != n:
+        raise DecentLamError(DL_ETOPO, f"topology has {topo.n} nodes, arrays have {n} rows")
+    _check(fn(px, pm, pg, fmt, n, d, ld, ldg, *topo._args(), gamma, beta, k,
+              _stream() if stream is None else stream))
+
+
+def decentlam_step_g16(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
+    """decentlam_step with g stored as bfloat16 / float16 (its dtype selects the format)."""
+    _step_g16(_lib.decentlam_step_g16, x, m, g, topo, gamma, beta, k, stream)
+
+
+def dmsgd_step_g16(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
+    """dmsgd_step with g stored as bfloat16 / float16 (its dtype selects the format)."""
+    _step_g16(_lib.dmsgd_step_g16, x, m, g, topo, gamma, beta, k, stream)
+
+
+def decentlam_step_multi_workspace(n: int, d: int, num_tensors: int) -> int:
+    return int(_lib.decentlam_step_multi_workspace(n, d, num_tensors))
+
+
+def _step_multi(fn, x, m, g, offsets, topo, gamma, beta, k, norms, workspace, stream):
+    px, n, cols, ld = _matrix_args(x, "x")
+    pm, nm, dm, ldm = _matrix_args(m, "m")
+    if (nm, dm, ldm) != (n, cols, ld):
+        raise TypeError("x and m must share shape and row stride")
+    pg, fmt, ldg = _grad_args(g, n, cols)
+    if topo.n != n:
+        raise DecentLamError(DL_ETOPO, f"topology has {topo.n} nodes, arrays have {n} rows")
+    offsets = np.ascontiguousarray(offsets, np.int64)
+    if offsets.ndim != 1 or offsets.size < 2:
+        raise TypeError("offsets: need num_tensors + 1 column offsets")
+    num = offsets.size - 1
+    if offsets[-1] > cols:
+        raise DecentLamError(DL_EINVAL, f"offsets end at {offsets[-1]}, arrays have {cols} columns")
+    pn = pw = wb = 0
+    if norms is not None:
+        if norms.dtype != torch.float64 or not norms.is_cuda or not norms.is_contiguous() or norms.numel() != num * n * 3:
+            raise TypeError("norms: need a contiguous float64 device tensor of num_tensors x n x 3 elements")
+        if workspace is None:
+            raise TypeError("workspace: pass a uint8 device tensor (size from decentlam_step_multi_workspace)")
+        pn, pw, wb = norms.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    _check(fn(px, pm, pg, fmt, n, max(ld, cols), max(ldg, cols), num,
+              offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), pn, pw, wb, *topo._args(), gamma, beta, k,
+              _stream() if stream is None else stream))
+
+
+def decentlam_step_multi(x, m, g, offsets, topo: Topology, gamma: float, beta: float, k: int = 0,
+                         norms=None, workspace=None, stream=None):
+    """decentlam_step over the tensors [offsets[t], offsets[t+1]) of x, m, g (full-width tensors whose
+    column 0 is column 0 of the table); `norms` (float64 device tensor, num_tensors x n x 3) receives
+    the per-tensor, per-node sums of squares of g, the new m and the new x."""
+    _step_multi(_lib.decentlam_step_multi, x, m, g, offsets, topo, gamma, beta, k, norms, workspace, stream)
+
+
+def dmsgd_step_multi(x, m, g, offsets, topo: Topology, gamma: float, beta: float, k: int = 0,
+                     norms=None, workspace=None, stream=None):
+    """dmsgd_step over a table of tensors, see decentlam_step_multi."""
+    _step_multi(_lib.dmsgd_step_multi, x, m, g, offsets, topo, gamma, beta, k, norms, workspace, stream)
 
 
 def decentlam_step_xprev(x, x_prev, g, topo: Topology, gamma: float, beta: float, k: int = 0,

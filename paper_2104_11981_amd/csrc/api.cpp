@@ -34,10 +34,10 @@ namespace {
 struct Span {
     uintptr_t lo, hi;
 };
-Span span_of(const void* p, int64_t rows, int64_t cols, int64_t ld) {
+Span span_of(const void* p, int64_t rows, int64_t cols, int64_t ld, int64_t elem_bytes = 4) {
     const uintptr_t lo = reinterpret_cast<uintptr_t>(p);
     if (rows <= 0 || cols <= 0) return {lo, lo};
-    return {lo, lo + static_cast<uintptr_t>(((rows - 1) * ld + cols) * 4)};
+    return {lo, lo + static_cast<uintptr_t>(((rows - 1) * ld + cols) * elem_bytes)};
 }
 bool overlap(Span a, Span b) { return a.lo < b.hi && b.lo < a.hi; }
 
@@ -116,17 +116,55 @@ int pack_phase(const char* fn, int32_t n, const int32_t* row_ptr, const int32_t*
     return DL_OK;
 }
 
-int step_entry(const char* fn, Algo algo, float* x, float* m, const float* g, int32_t n, int64_t d,
+// Optional extras of a step call: a gradient format other than fp32 with its own row stride, and
+// the tensor table with its outputs.
+struct StepExtras {
+    int g_format = DL_GRAD_F32;
+    int64_t ldg = -1;               // -1: same as ld
+    bool multi = false;
+    int32_t num_tensors = 0;
+    const int64_t* offsets = nullptr;   // host
+    double* norms = nullptr;            // device or NULL
+    void* workspace = nullptr;
+    size_t workspace_bytes = 0;
+};
+
+size_t multi_workspace_bytes(int32_t n, int64_t d) {
+    return static_cast<size_t>(norm_tiles_bound(d)) * static_cast<size_t>(n) * 3 * sizeof(double);
+}
+
+int step_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int32_t n, int64_t d,
                int64_t ld, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
-               int32_t period, float gamma, float beta, int64_t k, void* stream, float gamma_prev = 0.0f) {
+               int32_t period, float gamma, float beta, int64_t k, void* stream, float gamma_prev = 0.0f,
+               const StepExtras& ex = StepExtras()) {
     clear_error();
     if (algo == ALGO_DECENTLAM_XPREV && (!std::isfinite(gamma_prev) || !(gamma_prev > 0.0f)))
         return set_error(DL_EINVAL, "%s: gamma_prev = %g must be finite and > 0", fn, static_cast<double>(gamma_prev));
     if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
+    if (ex.g_format != DL_GRAD_F32 && ex.g_format != DL_GRAD_BF16 && ex.g_format != DL_GRAD_F16)
+        return set_error(DL_EINVAL, "%s: g_format = %d is not a dl_grad_format", fn, ex.g_format);
+    int64_t col0 = 0;
+    if (ex.multi) {   // the tensor table fixes the column range
+        if (ex.num_tensors < 1) return set_error(DL_EINVAL, "%s: num_tensors = %d, need >= 1", fn, ex.num_tensors);
+        if (!ex.offsets) return set_error(DL_EINVAL, "%s: offsets must not be NULL", fn);
+        if (ex.offsets[0] < 0) return set_error(DL_EINVAL, "%s: offsets[0] = %lld < 0", fn,
+                                                static_cast<long long>(ex.offsets[0]));
+        for (int32_t t = 0; t < ex.num_tensors; ++t)
+            if (ex.offsets[t + 1] < ex.offsets[t])
+                return set_error(DL_EINVAL, "%s: offsets decrease at tensor %d", fn, t);
+        col0 = ex.offsets[0];
+        d = ex.offsets[ex.num_tensors] - col0;
+        if (ex.offsets[ex.num_tensors] > ld)
+            return set_error(DL_EINVAL, "%s: offsets end at %lld > ld = %lld", fn,
+                             static_cast<long long>(ex.offsets[ex.num_tensors]), static_cast<long long>(ld));
+    }
     if (d < 0) return set_error(DL_EINVAL, "%s: d = %lld, need d >= 0", fn, static_cast<long long>(d));
     if (ld < d)
         return set_error(DL_EINVAL, "%s: ld = %lld < d = %lld", fn, static_cast<long long>(ld),
                          static_cast<long long>(d));
+    const int64_t ldg = ex.ldg < 0 ? ld : ex.ldg;
+    if (ldg < col0 + d)
+        return set_error(DL_EINVAL, "%s: ldg = %lld does not cover the columns", fn, static_cast<long long>(ldg));
     if (!std::isfinite(gamma) || !(gamma > 0.0f))
         return set_error(DL_EINVAL, "%s: gamma = %g must be finite and > 0", fn, static_cast<double>(gamma));
     if (!(beta >= 0.0f && beta < 1.0f))
@@ -140,12 +178,26 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const float* g, in
     std::memset(&topo, 0, sizeof(topo));
     if (int rc = pack_phase(fn, n, row_ptr, col_idx, w, static_cast<int32_t>(k % period), &topo)) return rc;
 
-    if (d == 0) return DL_OK;
+    const bool want_norms = ex.multi && ex.norms != nullptr;
+    if (want_norms) {
+        const size_t need = multi_workspace_bytes(n, d);
+        if (!ex.workspace || ex.workspace_bytes < need)
+            return set_error(DL_ECAP, "%s: workspace of %zu bytes needed, %zu given", fn, need,
+                             ex.workspace ? ex.workspace_bytes : size_t{0});
+        if ((reinterpret_cast<uintptr_t>(ex.workspace) | reinterpret_cast<uintptr_t>(ex.norms)) & 7u)
+            return set_error(DL_EINVAL, "%s: workspace and norms must be 8-byte aligned", fn);
+    }
+    if (d == 0 && !want_norms) return DL_OK;
     const bool uses_m = algo != ALGO_DSGD;
     if (!x || !g || (uses_m && !m)) return set_error(DL_EINVAL, "%s: x, m and g must not be NULL", fn);
-    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(g)) & 3u)
-        return set_error(DL_EINVAL, "%s: x, m and g must be 4-byte aligned", fn);
-    const Span sx = span_of(x, n, d, ld), sm = span_of(m, n, d, ld), sg = span_of(g, n, d, ld);
+    const uintptr_t gbytes = grad_elem_bytes(ex.g_format);
+    if (((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m)) & 3u) ||
+        (reinterpret_cast<uintptr_t>(g) & (gbytes - 1)))
+        return set_error(DL_EINVAL, "%s: x, m and g must be aligned to their element size", fn);
+    x += col0;
+    if (m) m += col0;
+    g = static_cast<const char*>(g) + static_cast<size_t>(col0) * gbytes;
+    const Span sx = span_of(x, n, d, ld), sm = span_of(m, n, d, ld), sg = span_of(g, n, d, ldg, gbytes);
     // Rows of different arrays may interleave when ld > d (views of one padded buffer); what
     // must not happen is that the arrays share elements.  Whole-span overlap is only an error
     // if the arrays are not column-disjoint views with the same stride.
@@ -155,13 +207,33 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const float* g, in
         const int64_t off = ((delta % ld) + ld) % ld;  // column offset between the two views
         return !(off >= d && ld - off >= d);
     };
-    if ((uses_m && (shares(x, sx, m, sm) || shares(m, sm, g, sg))) || shares(x, sx, g, sg))
+    const bool g_like_x = ex.g_format == DL_GRAD_F32 && ldg == ld;
+    auto g_shares = [&](const void* a, Span sa) { return g_like_x ? shares(a, sa, g, sg) : overlap(sa, sg); };
+    if ((uses_m && (shares(x, sx, m, sm) || g_shares(m, sm))) || g_shares(x, sx))
         return set_error(DL_EALIAS, "%s: x, m and g must not overlap", fn);
 
     double beta_eff = static_cast<double>(beta);
     if (algo == ALGO_DECENTLAM_XPREV)
         beta_eff = beta_eff * static_cast<double>(gamma) / static_cast<double>(gamma_prev);
-    return launch_step(algo, x, m, g, n, d, ld, topo, gamma, beta_eff, static_cast<hipStream_t>(stream));
+    const GradArg ga{g, ex.g_format, ldg};
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!want_norms) return launch_step(algo, x, m, ga, n, d, ld, topo, gamma, beta_eff, s);
+
+    const size_t need = multi_workspace_bytes(n, d);
+    const Span sw = {reinterpret_cast<uintptr_t>(ex.workspace), reinterpret_cast<uintptr_t>(ex.workspace) + need};
+    const Span sn = span_of(ex.norms, 1, static_cast<int64_t>(ex.num_tensors) * n * 3,
+                            static_cast<int64_t>(ex.num_tensors) * n * 3, 8);
+    if (overlap(sw, sn) || overlap(sw, sx) || overlap(sw, sm) || overlap(sw, sg) || overlap(sn, sx) ||
+        overlap(sn, sm) || overlap(sn, sg))
+        return set_error(DL_EALIAS, "%s: norms / workspace overlap another array", fn);
+    NormPlan plan;
+    std::memset(&plan, 0, sizeof(plan));
+    plan.offsets = ex.offsets;
+    plan.num_tensors = ex.num_tensors;
+    plan.partial = static_cast<double*>(ex.workspace);
+    plan.norms = ex.norms;
+    if (int rc = launch_step(algo, x, m, ga, n, d, ld, topo, gamma, beta_eff, s, &plan)) return rc;
+    return launch_norms_finish(plan, x, m, ga, ld, n, s);
 }
 
 }  // namespace
@@ -181,6 +253,68 @@ int dmsgd_step(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t
                float gamma, float beta, int64_t k, void* stream) {
     return dl::step_entry("dmsgd_step", dl::ALGO_DMSGD, x, m, g, n, d, ld, row_ptr, col_idx, w, period,
                           gamma, beta, k, stream);
+}
+
+int decentlam_step_g16(float* x, float* m, const void* g, int32_t g_format, int32_t n, int64_t d, int64_t ld,
+                       int64_t ldg, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
+                       int32_t period, float gamma, float beta, int64_t k, void* stream) {
+    dl::StepExtras ex;
+    ex.g_format = g_format;
+    ex.ldg = ldg;
+    return dl::step_entry("decentlam_step_g16", dl::ALGO_DECENTLAM, x, m, g, n, d, ld, row_ptr, col_idx, w,
+                          period, gamma, beta, k, stream, 0.0f, ex);
+}
+
+int dmsgd_step_g16(float* x, float* m, const void* g, int32_t g_format, int32_t n, int64_t d, int64_t ld,
+                   int64_t ldg, const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                   float gamma, float beta, int64_t k, void* stream) {
+    dl::StepExtras ex;
+    ex.g_format = g_format;
+    ex.ldg = ldg;
+    return dl::step_entry("dmsgd_step_g16", dl::ALGO_DMSGD, x, m, g, n, d, ld, row_ptr, col_idx, w, period,
+                          gamma, beta, k, stream, 0.0f, ex);
+}
+
+size_t decentlam_step_multi_workspace(int32_t n, int64_t d, int32_t num_tensors) {
+    if (n < 1 || d < 0 || num_tensors < 1) return 0;
+    return dl::multi_workspace_bytes(n, d);
+}
+
+namespace dl {
+namespace {
+int multi_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int32_t g_format, int32_t n,
+                int64_t ld, int64_t ldg, int32_t num_tensors, const int64_t* offsets, double* norms,
+                void* workspace, size_t workspace_bytes, const int32_t* row_ptr, const int32_t* col_idx,
+                const float* w, int32_t period, float gamma, float beta, int64_t k, void* stream) {
+    StepExtras ex;
+    ex.g_format = g_format;
+    ex.ldg = ldg;
+    ex.multi = true;
+    ex.num_tensors = num_tensors;
+    ex.offsets = offsets;
+    ex.norms = norms;
+    ex.workspace = workspace;
+    ex.workspace_bytes = workspace_bytes;
+    return step_entry(fn, algo, x, m, g, n, 0, ld, row_ptr, col_idx, w, period, gamma, beta, k, stream, 0.0f, ex);
+}
+}  // namespace
+}  // namespace dl
+
+int decentlam_step_multi(float* x, float* m, const void* g, int32_t g_format, int32_t n, int64_t ld, int64_t ldg,
+                         int32_t num_tensors, const int64_t* offsets, double* norms, void* workspace,
+                         size_t workspace_bytes, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
+                         int32_t period, float gamma, float beta, int64_t k, void* stream) {
+    return dl::multi_entry("decentlam_step_multi", dl::ALGO_DECENTLAM, x, m, g, g_format, n, ld, ldg, num_tensors,
+                           offsets, norms, workspace, workspace_bytes, row_ptr, col_idx, w, period, gamma, beta,
+                           k, stream);
+}
+
+int dmsgd_step_multi(float* x, float* m, const void* g, int32_t g_format, int32_t n, int64_t ld, int64_t ldg,
+                     int32_t num_tensors, const int64_t* offsets, double* norms, void* workspace,
+                     size_t workspace_bytes, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
+                     int32_t period, float gamma, float beta, int64_t k, void* stream) {
+    return dl::multi_entry("dmsgd_step_multi", dl::ALGO_DMSGD, x, m, g, g_format, n, ld, ldg, num_tensors, offsets,
+                           norms, workspace, workspace_bytes, row_ptr, col_idx, w, period, gamma, beta, k, stream);
 }
 
 int decentlam_step_xprev(const float* x, float* x_prev, const float* g, int32_t n, int64_t d, int64_t ld,

@@ -40,10 +40,46 @@ int set_error(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3
 int check_hip(hipError_t e, const char* what);
 void clear_error();
 
+// The gradient operand of a step: fp32, or a 16-bit format that is widened exactly on load.
+struct GradArg {
+    const void* p;
+    int format;   // dl_grad_format
+    int64_t ld;   // row stride in elements of that format
+};
+inline size_t grad_elem_bytes(int format) { return format == DL_GRAD_F32 ? 4 : 2; }
+
+// Per-tensor sums of squares fused into a step.  Tensor t is the column range
+// [offsets[t], offsets[t + 1]) of the caller's arrays.  Every workgroup of a step launch owns one
+// tile of columns and writes one record of n x 3 doubles (sums of squares of g, new m, new x over
+// the tile) with plain stores.  A final pass adds, for every tensor, the records of the tiles that
+// lie wholly inside it and sums the remaining edge columns directly from the arrays.
+constexpr int kMaxNormGrids = 3;   // aligned body, peeled head, peeled tail
+struct NormGrid {
+    int64_t col0;    // first column of the launch, relative to the first column of the step
+    int64_t cols;    // columns covered by the launch
+    int64_t tile0;   // index of the launch's first record in `partial`
+    int32_t tc;      // columns per tile
+};
+struct NormPlan {
+    const int64_t* offsets;   // host, num_tensors + 1; offsets[0] is the first column of the step
+    int32_t num_tensors;
+    double* partial;          // device, room for norm_tiles_bound(d) records of n x 3 doubles
+    double* norms;            // device, [num_tensors][n][3]
+    NormGrid grid[kMaxNormGrids];
+    int grids;
+};
+// Upper bound on the number of tile records a step over d columns writes, at any alignment.
+inline int64_t norm_tiles_bound(int64_t d) { return (d + 63) / 64 + 3; }
+
 // Enqueue one fused iteration over columns [0, d) of x, m, g (already validated).
 // `beta` is a double so that the momentum-free form can pass beta * gamma / gamma_prev unrounded.
-int launch_step(Algo algo, float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
-                const PhaseArgs& topo, float gamma, double beta, hipStream_t stream);
+// With `norms` the launches also write their tile records and note their grids in it.
+int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, int64_t ld,
+                const PhaseArgs& topo, float gamma, double beta, hipStream_t stream,
+                NormPlan* norms = nullptr);
+// After launch_step with `norms`: x, m, g as passed there.
+int launch_norms_finish(const NormPlan& plan, const float* x, const float* m, GradArg g, int64_t ld, int32_t n,
+                        hipStream_t stream);
 
 // Least-squares gradient (already validated).
 size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d);

@@ -21,6 +21,10 @@
 // other workgroup touches these columns.  The gather costs no time next to the
 // streaming (measured: replacing it by a copy of the own row does not speed the
 // kernel up), and the non-temporal accesses are worth about 5 %.
+//
+// Two optional extras share the kernel: the gradient may be stored as bf16 or fp16 (widened exactly
+// on load: 18 bytes per node-element), and a launch may accumulate per-tensor sums of squares of
+// g, the new m and the new x for a table of tensors packed along the columns.
 #include "internal.hpp"
 
 namespace dl {
@@ -54,6 +58,85 @@ __device__ __forceinline__ void store_vec(float* __restrict__ p, const float (&v
     } else {
         __builtin_nontemporal_store(v[0], p);
     }
+}
+
+// Gradient element types by dl_grad_format; 16-bit values widen to fp32 exactly.
+template <int GF> struct GradElem { using type = float; };
+template <> struct GradElem<DL_GRAD_BF16> { using type = uint16_t; };
+template <> struct GradElem<DL_GRAD_F16> { using type = _Float16; };
+
+template <int VEC, int GF>
+__device__ __forceinline__ void load_grad(const typename GradElem<GF>::type* __restrict__ p, float (&v)[VEC]) {
+    if constexpr (GF == DL_GRAD_F32) {
+        load_vec<VEC>(p, v);
+    } else {
+        using E = typename GradElem<GF>::type;
+        E raw[VEC];
+        if constexpr (VEC == 1) {
+            raw[0] = __builtin_nontemporal_load(p);
+        } else {
+            typedef E vec_t __attribute__((ext_vector_type(VEC)));
+            const vec_t t = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(p));
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) raw[k] = t[k];
+        }
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            if constexpr (GF == DL_GRAD_BF16)   // bf16 is the upper half of the fp32 pattern
+                v[k] = __builtin_bit_cast(float, static_cast<uint32_t>(raw[k]) << 16);
+            else
+                v[k] = static_cast<float>(raw[k]);
+        }
+    }
+}
+
+// Per-launch arguments of the per-tensor sums (see NormPlan): where the tile records go.
+struct NormArgs {
+    double* partial;
+    int64_t tile0;   // record index of this launch's tile 0
+};
+
+// Cross-lane exchange of a double on the data-parallel-primitive network (no LDS traffic).
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    const int lo = __builtin_amdgcn_update_dpp(0, static_cast<int>(b), CTRL, 0xF, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, static_cast<int>(b >> 32), CTRL, 0xF, 0xF, true);
+    return __builtin_bit_cast(double, (static_cast<uint64_t>(static_cast<uint32_t>(hi)) << 32) |
+                                          static_cast<uint32_t>(lo));
+}
+
+// Sums over the 64 lanes in a fixed order, the result in every lane: butterfly steps inside each
+// row of 16 lanes on the primitive network (swap inside pairs, swap pairs inside quads, mirror
+// inside 8, mirror inside 16), then two exchanges between the four rows.
+__device__ __forceinline__ double wave_sum(double v) {
+    v += dpp_f64<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_f64<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_f64<0x141>(v);   // row_half_mirror
+    v += dpp_f64<0x140>(v);   // row_mirror
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    return v;
+}
+// Two sums for little more than the price of one: after the first step even lanes carry on with a,
+// odd lanes with b, and every later step (swap pairs inside quads, rotate a row by 4 and by 8,
+// exchange rows) keeps the parity of the lane.  Even lanes return sum(a), odd lanes sum(b).
+__device__ __forceinline__ double wave_sum2(double a, double b, int lane) {
+    a += dpp_f64<0xB1>(a);
+    b += dpp_f64<0xB1>(b);
+    double v = (lane & 1) ? b : a;
+    v += dpp_f64<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_f64<0x124>(v);   // row_ror:4
+    v += dpp_f64<0x128>(v);   // row_ror:8
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    return v;
+}
+__device__ __forceinline__ double uniform_f64(double v) {   // lane 0's value as a scalar
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<int>(b));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<int>(b >> 32));
+    return __builtin_bit_cast(double, (static_cast<uint64_t>(hi) << 32) | lo);
 }
 
 // One neighbour in the LDS table.
@@ -91,11 +174,13 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
 //        DecentLaM"), x_next = W (x - gamma g) + beta' (x - x_prev); here `m` is the buffer that
 //        holds x_prev on entry and x_next on exit, x is only read, and `beta` carries
 //        beta' = beta * gamma / gamma_prev: 16 bytes per node-element, one written array
-template <int VEC, int RPT, int WAVES, int ALGO>
-__global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, float* __restrict__ m,
-                                                      const float* __restrict__ g, int64_t d, int64_t ld,
+// GF     dl_grad_format of g;  NORMS: accumulate the per-tensor sums of squares
+template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
+__global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8) ? 8 : 1) void k_step(float* __restrict__ x, float* __restrict__ m,
+                                                      const typename GradElem<GF>::type* __restrict__ g,
+                                                      int64_t d, int64_t ld, int64_t ldg,
                                                       double gamma, double inv_gamma, double beta,
-                                                      const PhaseArgs topo) {
+                                                      const NormArgs na, const PhaseArgs topo) {
     constexpr int TC = 64 * VEC;
     extern __shared__ double lds[];  // tile [n][TC] of u_j (DecentLaM) or h_j (DmSGD), then the table
     const int n = topo.n;
@@ -108,13 +193,16 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
 
     // ---- phase 1: stream rows in
     float xr[RPT][VEC], mr[RPT][VEC], gr[RPT][VEC];
+    // NORMS: sums of squares that are complete before the barrier (g; the new m of DmSGD), reduced
+    // over the wave right away and kept as scalars so that they cost no vector registers later
+    double early[RPT][2];
 #pragma unroll
     for (int r = 0; r < RPT; ++r) {
         const int i = wave + WAVES * r;
         if (i < n && live) {
             const int64_t at = static_cast<int64_t>(i) * ld + c;
             load_vec<VEC>(x + at, xr[r]);
-            load_vec<VEC>(g + at, gr[r]);
+            load_grad<VEC, GF>(g + static_cast<int64_t>(i) * ldg + c, gr[r]);
             if constexpr (ALGO != ALGO_DSGD) load_vec<VEC>(m + at, mr[r]);
         }
     }
@@ -136,8 +224,16 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
 #pragma unroll
     for (int r = 0; r < RPT; ++r) {
         const int i = wave + WAVES * r;
+        double sq_g = 0.0, sq_m = 0.0;   // this lane's share (NORMS)
         if (i < n && live) {
             double* slot = lds + i * TC + lane * VEC;
+            if constexpr (NORMS) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const double gv = static_cast<double>(gr[r][v]);
+                    sq_g = __builtin_fma(gv, gv, sq_g);
+                }
+            }
             if constexpr (ALGO != ALGO_DMSGD) {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v)
@@ -149,8 +245,23 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                     const double m_new = beta * static_cast<double>(mr[r][v]) + static_cast<double>(gr[r][v]);
                     mn[v] = static_cast<float>(m_new);
                     slot[v] = static_cast<double>(xr[r][v]) - gamma * m_new;
+                    if constexpr (NORMS) {
+                        const double mv = static_cast<double>(mn[v]);
+                        sq_m = __builtin_fma(mv, mv, sq_m);
+                    }
                 }
                 store_vec<VEC>(m + static_cast<int64_t>(i) * ld + c, mn);
+            }
+        }
+        if constexpr (NORMS) {
+            if (i < n) {   // wave-uniform: all 64 lanes take part
+                if constexpr (ALGO == ALGO_DMSGD) {
+                    const double both = wave_sum2(sq_g, sq_m, lane);   // lane 0: g, lane 1: m
+                    early[r][0] = uniform_f64(both);
+                    early[r][1] = uniform_f64(dpp_f64<0xB1>(both));
+                } else {
+                    early[r][0] = uniform_f64(wave_sum(sq_g));
+                }
             }
         }
     }
@@ -161,6 +272,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
 #pragma unroll
     for (int r = 0; r < RPT; ++r) {
         const int i = wave + WAVES * r;
+        double sq_m = 0.0, sq_x = 0.0;   // this lane's share (NORMS)
         if (i < n && live) {
             double z[VEC];
 #pragma unroll
@@ -175,10 +287,10 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                     gather<VEC, 2>(table + e, tile_at_lane, z);
                     e += 2;
                 }
-            } else {
+            } else if constexpr (!(NORMS && RPT >= 2)) {   // (with the sums: one at a time, to fit 64 VGPRs)
                 for (; e + 2 <= e1; e += 2) gather<VEC, 2>(table + e, tile_at_lane, z);
             }
-            if (e < e1) gather<VEC, 1>(table + e, tile_at_lane, z);
+            for (; e < e1; ++e) gather<VEC, 1>(table + e, tile_at_lane, z);
 
             const int64_t at = static_cast<int64_t>(i) * ld + c;
             float xo[VEC];
@@ -191,6 +303,10 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                     const double m_new = __builtin_fma(beta, static_cast<double>(mr[r][v]), gt);
                     mo[v] = static_cast<float>(m_new);
                     xo[v] = static_cast<float>(xi - gamma * m_new);
+                    if constexpr (NORMS) {
+                        const double mv = static_cast<double>(mo[v]);
+                        sq_m = __builtin_fma(mv, mv, sq_m);
+                    }
                 }
                 store_vec<VEC>(m + at, mo);
             } else if constexpr (ALGO == ALGO_DECENTLAM_XPREV) {
@@ -204,6 +320,27 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                 for (int v = 0; v < VEC; ++v) xo[v] = static_cast<float>(z[v]);
             }
             store_vec<VEC>((ALGO == ALGO_DECENTLAM_XPREV ? m : x) + at, xo);
+            if constexpr (NORMS) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const double xv = static_cast<double>(xo[v]);
+                    sq_x = __builtin_fma(xv, xv, sq_x);
+                }
+            }
+        }
+        // per-tile sums of squares: one record of 3 doubles (g, new m, new x) per row and tile;
+        // lanes beyond the launch contributed zeros
+        if constexpr (NORMS) {
+            if (i < n) {
+                double* rec = na.partial + ((na.tile0 + blockIdx.x) * n + i) * 3;
+                if constexpr (ALGO == ALGO_DMSGD) {
+                    const double sx = wave_sum(sq_x);
+                    if (lane < 3) rec[lane] = lane == 0 ? early[r][0] : (lane == 1 ? early[r][1] : sx);
+                } else {
+                    const double mx = wave_sum2(sq_m, sq_x, lane);   // lane 0: m, lane 1: x
+                    if (lane < 3) rec[(lane + 1) % 3] = lane == 2 ? early[r][0] : mx;
+                }
+            }
         }
     }
 }
@@ -212,12 +349,24 @@ size_t lds_bytes_for(int32_t n, int vec, int nnz) {
     return static_cast<size_t>(n) * 64 * vec * sizeof(double) + static_cast<size_t>(nnz) * sizeof(Neighbour);
 }
 
-template <int VEC, int RPT, int WAVES, int ALGO>
-int launch_variant(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
-                   const PhaseArgs& topo, double gamma, double beta, hipStream_t stream) {
+// Everything a launch needs besides its template parameters.
+struct StepCall {
+    float* x;
+    float* m;
+    const void* g;
+    int32_t n;
+    int64_t d, ld, ldg;
+    double gamma, beta;
+    const PhaseArgs* topo;
+    hipStream_t stream;
+    NormArgs na;
+};
+
+template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
+int launch_variant(const StepCall& s) {
     constexpr int TC = 64 * VEC;
-    const size_t lds_bytes = lds_bytes_for(n, VEC, topo.row_ptr[n]);
-    auto kernel = k_step<VEC, RPT, WAVES, ALGO>;
+    const size_t lds_bytes = lds_bytes_for(s.n, VEC, s.topo->row_ptr[s.n]);
+    auto kernel = k_step<VEC, RPT, WAVES, ALGO, GF, NORMS>;
     if (lds_bytes > 48 * 1024) {
         if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -225,36 +374,53 @@ int launch_variant(float* x, float* m, const float* g, int32_t n, int64_t d, int
                                "hipFuncSetAttribute(max dynamic LDS)"))
             return rc;
     }
-    const int64_t blocks = (d + TC - 1) / TC;
+    const int64_t blocks = (s.d + TC - 1) / TC;
     if (blocks > 0x7fffffffLL) return set_error(DL_EINVAL, "step: d too large for one launch");
-    hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(blocks)), dim3(64 * WAVES), lds_bytes, stream,
-                       x, m, g, d, ld, gamma, 1.0 / gamma, beta, topo);
+    hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(blocks)), dim3(64 * WAVES), lds_bytes, s.stream,
+                       s.x, s.m, static_cast<const typename GradElem<GF>::type*>(s.g), s.d, s.ld, s.ldg,
+                       s.gamma, 1.0 / s.gamma, s.beta, s.na, *s.topo);
     return check_hip(hipGetLastError(), "step kernel launch");
 }
 
 // Workgroup shape by node count: as many waves as rows up to 16, then more rows per thread.
-template <int VEC, int ALGO>
-int launch_rows(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
-                const PhaseArgs& topo, double gamma, double beta, hipStream_t stream) {
-#define DL_SHAPE(MAXN, W, R)                                                                        \
-    if constexpr (VEC == 1 || VEC * (MAXN) <= 128) {                                                \
-        if (n <= (MAXN)) return launch_variant<VEC, R, W, ALGO>(x, m, g, n, d, ld, topo, gamma, beta, stream); \
+template <int VEC, int ALGO, int GF, bool NORMS>
+int launch_rows(const StepCall& s) {
+#define DL_SHAPE(MAXN, W, R)                                                             \
+    if constexpr (VEC == 1 || VEC * (MAXN) <= 128) {                                     \
+        if (s.n <= (MAXN)) return launch_variant<VEC, R, W, ALGO, GF, NORMS>(s);         \
     }
     DL_SHAPE(4, 4, 1) DL_SHAPE(8, 8, 1) DL_SHAPE(16, 16, 1) DL_SHAPE(32, 16, 2)
     DL_SHAPE(64, 16, 4) DL_SHAPE(128, 16, 8) DL_SHAPE(256, 16, 16)
 #undef DL_SHAPE
-    return set_error(DL_ETOPO, "step: n = %d has no kernel variant at vector width %d", n, VEC);
+    return set_error(DL_ETOPO, "step: n = %d has no kernel variant at vector width %d", s.n, VEC);
 }
 
-template <int ALGO>
-int launch_cols(int vec, float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
-                const PhaseArgs& topo, double gamma, double beta, hipStream_t stream) {
-    if (d <= 0) return DL_OK;
+template <int ALGO, int GF, bool NORMS>
+int launch_cols(int vec, const StepCall& s) {
+    if (s.d <= 0) return DL_OK;
     switch (vec) {
-        case 4: return launch_rows<4, ALGO>(x, m, g, n, d, ld, topo, gamma, beta, stream);
-        case 2: return launch_rows<2, ALGO>(x, m, g, n, d, ld, topo, gamma, beta, stream);
-        default: return launch_rows<1, ALGO>(x, m, g, n, d, ld, topo, gamma, beta, stream);
+        case 4: return launch_rows<4, ALGO, GF, NORMS>(s);
+        case 2: return launch_rows<2, ALGO, GF, NORMS>(s);
+        default: return launch_rows<1, ALGO, GF, NORMS>(s);
     }
+}
+
+// 16-bit gradients and per-tensor sums exist for the two momentum methods only.
+template <int ALGO>
+int launch_extras(int vec, int format, bool norms, const StepCall& s) {
+    if constexpr (ALGO == ALGO_DECENTLAM || ALGO == ALGO_DMSGD) {
+        if (norms) {
+            if (format == DL_GRAD_BF16) return launch_cols<ALGO, DL_GRAD_BF16, true>(vec, s);
+            if (format == DL_GRAD_F16) return launch_cols<ALGO, DL_GRAD_F16, true>(vec, s);
+            return launch_cols<ALGO, DL_GRAD_F32, true>(vec, s);
+        }
+        if (format == DL_GRAD_BF16) return launch_cols<ALGO, DL_GRAD_BF16, false>(vec, s);
+        if (format == DL_GRAD_F16) return launch_cols<ALGO, DL_GRAD_F16, false>(vec, s);
+    } else {
+        if (norms || format != DL_GRAD_F32)
+            return set_error(DL_EINVAL, "step: 16-bit gradients and per-tensor sums need decentlam or dmsgd");
+    }
+    return launch_cols<ALGO, DL_GRAD_F32, false>(vec, s);
 }
 
 // Widest access for which the fp64 tile of n rows takes 64 KiB of LDS, so that two workgroups
@@ -266,20 +432,22 @@ int widest_vec_for(int32_t n) {
 }
 
 }  // namespace
-int launch_step(Algo algo, float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
-                const PhaseArgs& topo, float gamma_f, double beta, hipStream_t stream) {
+int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, int64_t ld,
+                const PhaseArgs& topo, float gamma_f, double beta, hipStream_t stream, NormPlan* norms) {
     const double gamma = static_cast<double>(gamma_f);
+    const size_t gbytes = grad_elem_bytes(g.format);
+    const unsigned gshift = gbytes == 4 ? 2 : 1;
 
     // Pick the widest access all three arrays can share: same misalignment (in elements)
-    // modulo the vector width and a row stride that preserves it.
+    // modulo the vector width and row strides that preserve it.
     int vec = widest_vec_for(n);
     int64_t head = 0;
     for (; vec > 1; vec >>= 1) {
         const uintptr_t mask = static_cast<uintptr_t>(vec) - 1;
         const uintptr_t ax = (reinterpret_cast<uintptr_t>(x) >> 2) & mask;
         const uintptr_t am = m ? (reinterpret_cast<uintptr_t>(m) >> 2) & mask : ax;
-        const uintptr_t ag = (reinterpret_cast<uintptr_t>(g) >> 2) & mask;
-        if (ax == am && ax == ag && (ld & static_cast<int64_t>(mask)) == 0) {
+        const uintptr_t ag = (reinterpret_cast<uintptr_t>(g.p) >> gshift) & mask;
+        if (ax == am && ax == ag && ((ld | g.ld) & static_cast<int64_t>(mask)) == 0) {
             head = static_cast<int64_t>((vec - ax) & mask);
             break;
         }
@@ -289,19 +457,135 @@ int launch_step(Algo algo, float* x, float* m, const float* g, int32_t n, int64_
     const int64_t body = ((d - head) / vec) * vec;
     const int64_t tail = d - head - body;
 
+    if (norms) norms->grids = 0;
+    int64_t tiles_used = 0;
     auto run = [&](int v, int64_t c0, int64_t cols) {
-        if (algo == ALGO_DECENTLAM)
-            return launch_cols<ALGO_DECENTLAM>(v, x + c0, m + c0, g + c0, n, cols, ld, topo, gamma, beta, stream);
-        if (algo == ALGO_DSGD)
-            return launch_cols<ALGO_DSGD>(v, x + c0, nullptr, g + c0, n, cols, ld, topo, gamma, beta, stream);
-        if (algo == ALGO_DECENTLAM_XPREV)
-            return launch_cols<ALGO_DECENTLAM_XPREV>(v, x + c0, m + c0, g + c0, n, cols, ld, topo, gamma, beta, stream);
-        return launch_cols<ALGO_DMSGD>(v, x + c0, m + c0, g + c0, n, cols, ld, topo, gamma, beta, stream);
+        if (cols <= 0) return static_cast<int>(DL_OK);
+        StepCall s;
+        s.x = x + c0;
+        s.m = m ? m + c0 : nullptr;
+        s.g = static_cast<const char*>(g.p) + static_cast<size_t>(c0) * gbytes;
+        s.n = n; s.d = cols; s.ld = ld; s.ldg = g.ld;
+        s.gamma = gamma; s.beta = beta; s.topo = &topo; s.stream = stream;
+        s.na = NormArgs{nullptr, 0};
+        if (norms) {
+            const int tc = 64 * v;
+            NormGrid& gr = norms->grid[norms->grids++];
+            gr.col0 = c0; gr.cols = cols; gr.tile0 = tiles_used; gr.tc = tc;
+            s.na = NormArgs{norms->partial, gr.tile0};
+            tiles_used += (cols + tc - 1) / tc;
+        }
+        switch (algo) {
+            case ALGO_DECENTLAM: return launch_extras<ALGO_DECENTLAM>(v, g.format, norms != nullptr, s);
+            case ALGO_DMSGD: return launch_extras<ALGO_DMSGD>(v, g.format, norms != nullptr, s);
+            case ALGO_DSGD: return launch_extras<ALGO_DSGD>(v, g.format, norms != nullptr, s);
+            default: return launch_extras<ALGO_DECENTLAM_XPREV>(v, g.format, norms != nullptr, s);
+        }
     };
     if (int rc = run(vec, head, body)) return rc;   // aligned body first: it is the bulk
     if (int rc = run(1, 0, head)) return rc;        // columns are independent, so the peeled
     if (int rc = run(1, head + body, tail)) return rc;  // head and tail are separate launches
     return DL_OK;
+}
+
+// ---- per-tensor sums: final pass ---------------------------------------------------------------
+namespace {
+
+constexpr int kChunk = 440;   // tensors per final-pass launch (their offsets travel as kernel arguments)
+struct OffsetChunk {
+    int64_t v[kChunk + 1];    // column offsets relative to the first column of the step
+};
+struct FinishArgs {
+    NormGrid grid[kMaxNormGrids];
+    int grids;
+};
+
+// One workgroup per (tensor, node).  For every step launch ("grid" of tiles) the tensor's columns
+// split into whole tiles, whose records the step launches wrote, and at most two edge pieces that
+// share a tile with other tensors; the edge pieces are summed from g and from the m and x the step
+// stored.  Fixed order of additions: same inputs, same bits.
+template <int GF>
+__global__ __launch_bounds__(256) void k_norms_finish(const float* __restrict__ x, const float* __restrict__ m,
+                                                      const typename GradElem<GF>::type* __restrict__ g,
+                                                      int64_t ld, int64_t ldg, int n,
+                                                      const double* __restrict__ partial,
+                                                      double* __restrict__ norms, const FinishArgs fa,
+                                                      const OffsetChunk chunk) {
+    const int t = blockIdx.x, i = blockIdx.y;
+    const int64_t lo = chunk.v[t], hi = chunk.v[t + 1];
+    double s[3] = {0.0, 0.0, 0.0};
+    auto columns = [&](int64_t a, int64_t b) {   // element-wise over [a, b)
+        for (int64_t c = a + threadIdx.x; c < b; c += 256) {
+            float gv[1];
+            load_grad<1, GF>(g + static_cast<int64_t>(i) * ldg + c, gv);
+            const double g1 = static_cast<double>(gv[0]);
+            const double m1 = static_cast<double>(m[static_cast<int64_t>(i) * ld + c]);
+            const double x1 = static_cast<double>(x[static_cast<int64_t>(i) * ld + c]);
+            s[0] = __builtin_fma(g1, g1, s[0]);
+            s[1] = __builtin_fma(m1, m1, s[1]);
+            s[2] = __builtin_fma(x1, x1, s[2]);
+        }
+    };
+    for (int k = 0; k < fa.grids; ++k) {
+        const NormGrid gd = fa.grid[k];
+        const int64_t a = lo > gd.col0 ? lo : gd.col0;                          // the tensor inside this grid
+        const int64_t b = hi < gd.col0 + gd.cols ? hi : gd.col0 + gd.cols;
+        if (a >= b) continue;
+        const int64_t tiles = (gd.cols + gd.tc - 1) / gd.tc;
+        const int64_t b0 = (a - gd.col0 + gd.tc - 1) / gd.tc;                   // first tile that starts at or after a
+        const int64_t b1 = b == gd.col0 + gd.cols ? tiles : (b - gd.col0) / gd.tc;  // tiles [b0, b1) lie inside [a, b)
+        if (b0 >= b1) {
+            columns(a, b);
+            continue;
+        }
+        columns(a, gd.col0 + b0 * gd.tc);
+        const int64_t tail = gd.col0 + b1 * gd.tc;
+        if (tail < b) columns(tail, b);
+        for (int64_t q = b0 + threadIdx.x; q < b1; q += 256) {
+            const double* rec = partial + ((gd.tile0 + q) * n + i) * 3;
+            s[0] += rec[0]; s[1] += rec[1]; s[2] += rec[2];
+        }
+    }
+    __shared__ double red[3][256];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) red[q][threadIdx.x] = s[q];
+    __syncthreads();
+    for (int half = 128; half >= 1; half >>= 1) {
+        if (static_cast<int>(threadIdx.x) < half) {
+#pragma unroll
+            for (int q = 0; q < 3; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + half];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x < 3) norms[(static_cast<int64_t>(t) * n + i) * 3 + threadIdx.x] = red[threadIdx.x][0];
+}
+
+template <int GF>
+int finish_chunks(const NormPlan& plan, const float* x, const float* m, const void* g, int64_t ld, int64_t ldg,
+                  int32_t n, hipStream_t stream) {
+    FinishArgs fa;
+    fa.grids = plan.grids;
+    for (int k = 0; k < kMaxNormGrids; ++k) fa.grid[k] = k < plan.grids ? plan.grid[k] : NormGrid{0, 0, 0, 64};
+    for (int32_t t0 = 0; t0 < plan.num_tensors; t0 += kChunk) {
+        const int32_t count = plan.num_tensors - t0 < kChunk ? plan.num_tensors - t0 : kChunk;
+        OffsetChunk chunk;
+        for (int j = 0; j <= kChunk; ++j)
+            chunk.v[j] = plan.offsets[t0 + (j <= count ? j : count)] - plan.offsets[0];
+        hipLaunchKernelGGL(k_norms_finish<GF>, dim3(static_cast<unsigned>(count), static_cast<unsigned>(n)),
+                           dim3(256), 0, stream, x, m, static_cast<const typename GradElem<GF>::type*>(g), ld, ldg,
+                           n, plan.partial, plan.norms + static_cast<int64_t>(t0) * n * 3, fa, chunk);
+        if (int rc = check_hip(hipGetLastError(), "per-tensor sums, final pass")) return rc;
+    }
+    return DL_OK;
+}
+
+}  // namespace
+
+int launch_norms_finish(const NormPlan& plan, const float* x, const float* m, GradArg g, int64_t ld, int32_t n,
+                        hipStream_t stream) {
+    if (g.format == DL_GRAD_BF16) return finish_chunks<DL_GRAD_BF16>(plan, x, m, g.p, ld, g.ld, n, stream);
+    if (g.format == DL_GRAD_F16) return finish_chunks<DL_GRAD_F16>(plan, x, m, g.p, ld, g.ld, n, stream);
+    return finish_chunks<DL_GRAD_F32>(plan, x, m, g.p, ld, g.ld, n, stream);
 }
 
 }  // namespace dl

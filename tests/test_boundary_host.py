@@ -258,3 +258,48 @@ def test_decentlam_xprev_argument_validation():
     assert f(beta=1.0) == P.DL_EINVAL
     assert f(d=8, ld=8, x=4096, xp=4096, g=8192) == P.DL_EALIAS
     assert f(d=8, ld=8, x=4096, xp=0, g=8192) == P.DL_EINVAL
+
+
+def test_g16_argument_validation():
+    t = P.topology_build(0, 4)
+    f = lambda **kw: P.raw.decentlam_step_g16(kw.get("x"), kw.get("m"), kw.get("g"), kw.get("fmt", P.DL_GRAD_BF16),
+                                              4, kw.get("d", 0), kw.get("ld", 0), kw.get("ldg", 0), *t._args(),
+                                              kw.get("gamma", 0.1), 0.9, 0, None)
+    assert f() == P.DL_OK
+    assert f(fmt=3) == P.DL_EINVAL and "g_format" in P.last_error()
+    assert f(d=8, ld=8, ldg=7) == P.DL_EINVAL and "ldg" in P.last_error()
+    assert f(d=8, ld=8, ldg=8, x=0x1000, m=0x2000, g=0) == P.DL_EINVAL
+    assert f(d=8, ld=8, ldg=8, x=0x1000, m=0x2000, g=0x3001) == P.DL_EINVAL        # g not 2-byte aligned
+    assert f(d=8, ld=8, ldg=8, x=0x1000, m=0x2000, g=0x1000 + 64) == P.DL_EALIAS   # g inside x
+    assert f(d=8, ld=8, ldg=8, x=0x1000, m=0x1000 + 16, g=0x3000) == P.DL_EALIAS
+    assert P.raw.dmsgd_step_g16(None, None, None, P.DL_GRAD_F16, 4, 0, 0, 0, *t._args(), 0.1, 0.9, 0, None) == P.DL_OK
+
+
+def test_multi_tensor_argument_validation():
+    t = P.topology_build(0, 4)
+    I64 = ctypes.c_int64
+
+    def call(offsets, **kw):
+        arr = (I64 * len(offsets))(*offsets) if offsets is not None else None
+        return P.raw.decentlam_step_multi(kw.get("x", 0x10000), kw.get("m", 0x20000), kw.get("g", 0x30000),
+                                          kw.get("fmt", P.DL_GRAD_F32), 4, kw.get("ld", 64), kw.get("ldg", 64),
+                                          kw.get("T", len(offsets) - 1 if offsets else 1), arr,
+                                          kw.get("norms", 0), kw.get("ws", 0), kw.get("wsb", 0), *t._args(),
+                                          0.1, 0.9, 0, None)
+
+    assert call([0, 0, 0]) == P.DL_OK                                   # nothing to do, nothing touched
+    assert call(None) == P.DL_EINVAL and "offsets" in P.last_error()
+    assert call([0, 10], T=0) == P.DL_EINVAL
+    assert call([-1, 10]) == P.DL_EINVAL
+    assert call([0, 20, 10]) == P.DL_EINVAL and "decrease" in P.last_error()
+    assert call([0, 10, 65]) == P.DL_EINVAL                             # beyond ld
+    assert call([0, 10, 64], ldg=63) == P.DL_EINVAL
+    need = P.decentlam_step_multi_workspace(4, 64, 2)
+    assert need >= (64 // 64 + 3) * 4 * 3 * 8
+    assert call([0, 10, 64], norms=0x40000, ws=0, wsb=need) == P.DL_ECAP
+    assert call([0, 10, 64], norms=0x40000, ws=0x50000, wsb=need - 1) == P.DL_ECAP
+    assert call([0, 10, 64], norms=0x40000, ws=0x50004, wsb=need) == P.DL_EINVAL          # workspace alignment
+    assert call([0, 10, 64], norms=0x40004, ws=0x50000, wsb=need) == P.DL_EINVAL          # norms alignment
+    assert call([0, 10, 64], norms=0x50000 + 8, ws=0x50000, wsb=need) == P.DL_EALIAS      # norms inside the workspace
+    assert call([0, 10, 64], norms=0x10000, ws=0x50000, wsb=need) == P.DL_EALIAS          # norms inside x
+    assert P.decentlam_step_multi_workspace(0, 64, 2) == 0

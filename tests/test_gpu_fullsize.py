@@ -172,3 +172,83 @@ def test_more_than_2_pow_31_elements_per_array(P, oracle):
     got = out.cpu().numpy()
     m2 = float((m.double() ** 2).sum())
     assert abs(got[4] - m2) <= 1e-9 * m2
+
+
+def test_workload3_bf16_gradients_sampled_columns(P, oracle):
+    """n = 32, d = 25.6 M with the gradients stored as bfloat16 (decentlam_step_g16), in the
+    benchmark's layout.  The oracle gets the values of the same 16-bit patterns on sampled columns."""
+    import workloads
+
+    w = workloads.get("c3_exp32")
+    d = w.d
+    topo, otopo = P.topology_build(1, w.n), oracle.topology(1, w.n)
+    gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
+    cols = sample_columns(d, seed=77)
+    ct = torch.from_numpy(cols).cuda()
+    x = workloads.device_x0(w, "cuda")
+    m = torch.zeros_like(x)
+    g32 = torch.empty_like(x)
+    g = torch.empty((w.n, d), dtype=torch.bfloat16, device="cuda")
+    xs = x.index_select(1, ct).cpu().numpy().astype(np.float64)
+    ms = np.zeros_like(xs)
+    for k in range(6):
+        workloads.device_grad(w, k, g32)
+        g.copy_(g32)                                                    # the tensor library rounds to bf16
+        bits = g.index_select(1, ct).cpu().view(torch.int16).numpy().view(np.uint16)
+        P.decentlam_step_g16(x, m, g, topo, gamma, beta, k)
+        xs, ms = oracle.decentlam_step(xs, ms, oracle.widen16(bits, "bf16"), otopo, gamma, beta, k)
+        xs, ms = xs.astype(np.float32).astype(np.float64), ms.astype(np.float32).astype(np.float64)
+        check_elementwise(x.index_select(1, ct).cpu().numpy(), xs, f"x, iteration {k}")
+        check_elementwise(m.index_select(1, ct).cpu().numpy(), ms, f"m, iteration {k}")
+
+
+def test_workload4_multi_tensor_call_with_norms(P, oracle):
+    """The ragged workload as ONE multi-tensor call per iteration with the per-tensor sums of
+    squares: the state must equal the flat call's bit for bit; the sums are checked for every
+    tensor against fp64 sums of what the call stored, and for a sample of tensors (the smallest
+    ones and two that straddle many tiles' worth of columns) against the oracle, which runs its own
+    trajectory on exactly those tensors' columns."""
+    import workloads
+
+    w = workloads.get("c4_ring16_ragged")
+    sizes, offsets, _ = workloads.ragged_layout(w)
+    d, T, n = int(offsets[-1]), len(sizes), w.n
+    ld = (d + 63) // 64 * 64
+    topo, otopo = P.topology_build(0, n), oracle.topology(0, n)
+    gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
+    order = np.argsort(sizes)
+    sample = sorted(int(t) for t in np.concatenate([order[:10], order[T // 2:T // 2 + 2]]))
+    assert sum(int(sizes[t]) for t in sample) < 400_000
+    cols = np.concatenate([np.arange(offsets[t], offsets[t + 1]) for t in sample])
+    rel = np.concatenate([[0], np.cumsum([sizes[t] for t in sample])])
+    ct = torch.from_numpy(cols).cuda()
+    x = workloads.device_x0(w, "cuda", ld=ld)
+    xf = x.clone()
+    m, mf = torch.zeros_like(x), torch.zeros_like(x)
+    g = torch.zeros_like(x)
+    norms = torch.empty((T, n, 3), dtype=torch.float64, device="cuda")
+    ws = torch.empty(P.decentlam_step_multi_workspace(n, d, T) + 256, dtype=torch.uint8, device="cuda")
+    ws = ws[(-ws.data_ptr()) % 256:]
+    xs = x.index_select(1, ct).cpu().numpy().astype(np.float64)
+    ms = np.zeros_like(xs)
+    steps = 5
+    for k in range(steps):
+        workloads.device_grad(w, k, g)
+        gs = g.index_select(1, ct).cpu().numpy().astype(np.float64)
+        P.decentlam_step_multi(x, m, g, offsets, topo, gamma, beta, k, norms=norms, workspace=ws)
+        P.decentlam_step(xf[:, :d], mf[:, :d], g[:, :d], topo, gamma, beta, k)
+        xs, ms = oracle.decentlam_step(xs, ms, gs, otopo, gamma, beta, k)
+        xs, ms = xs.astype(np.float32).astype(np.float64), ms.astype(np.float32).astype(np.float64)
+    assert torch.equal(x, xf) and torch.equal(m, mf)
+    got = norms.cpu().numpy()
+    want = oracle.tensor_sumsq(gs, ms, xs, rel)
+    np.testing.assert_allclose(got[sample], want, rtol=2e-6)
+    np.testing.assert_allclose(got[sample][:, :, 0], want[:, :, 0], rtol=1e-13)
+    csum = lambda a: torch.cat([torch.zeros((n, 1), dtype=torch.float64, device="cuda"),
+                                torch.cumsum(a[:, :d].double() ** 2, dim=1)], dim=1)
+    idx = torch.from_numpy(offsets).cuda()
+    for q, a in enumerate((g, m, x)):
+        c = csum(a)
+        own = (c[:, idx[1:]] - c[:, idx[:-1]]).T.cpu().numpy()          # [T, n], differences of a running sum
+        np.testing.assert_allclose(got[:, :, q], own, rtol=1e-7, atol=1e-6)
+        del c
