@@ -79,6 +79,65 @@ def cpu_baseline(w, kind, algo, target_seconds=12.0):
     }
 
 
+def oracle_table_child():
+    """Times the oracle as it stands with the OpenMP thread count this process was started with:
+    every workload's step (column samples for the two large ones: the cost is linear in d) and the
+    least-squares gradient of the two regression workloads.  One JSON line per row."""
+    import numpy as np
+
+    import oracle
+    import workloads
+
+    oracle.build()
+    threads = oracle.num_threads()
+
+    def timed(fn, budget=4.0, max_reps=50):
+        fn()
+        t0, reps = time.perf_counter(), 0
+        while True:
+            fn()
+            reps += 1
+            el = time.perf_counter() - t0
+            if el >= budget or reps >= max_reps:
+                return el / reps
+
+    rng = np.random.default_rng(0)
+    for name in ("c1_ring4", "c2_onepeer8_b1024", "c3_exp32", "c4_ring16_ragged", "c5_onepeer64_lsq"):
+        w = workloads.get(name)
+        d = workloads.generate.dim(w)
+        d_s = min(d, 1_280_000)
+        topo = oracle.topology(w.topo, w.n)
+        x, g = rng.standard_normal((w.n, d_s)), rng.standard_normal((w.n, d_s))
+        m = np.zeros_like(x)
+        for algo in ("decentlam", "dmsgd"):
+            sec = timed(lambda: oracle.STEP[algo](x, m, g, topo, 0.05, 0.9, 0))
+            print(json.dumps({"oracle": algo + "_step", "workload": name, "threads": threads, "n": w.n, "d": d,
+                              "columns_timed": d_s, "ns_per_node_element": round(sec / (w.n * d_s) * 1e9, 3),
+                              "steps_per_s_full_size": round(d_s / d / sec, 4)}), flush=True)
+        if w.b:
+            nodes = min(w.n, 8)                     # cost is linear in the number of nodes
+            A = rng.standard_normal((nodes, w.b, w.d)).astype(np.float32)
+            y = rng.standard_normal((nodes, w.b)).astype(np.float32)
+            xs = rng.standard_normal((nodes, w.d))
+            sec = timed(lambda: oracle.lsq_grad(A, y, xs, 1.0), max_reps=10) * w.n / nodes
+            print(json.dumps({"oracle": "lsq_grad", "workload": name, "threads": threads, "n": w.n, "b": w.b,
+                              "d": w.d, "nodes_timed": nodes,
+                              "ns_per_matrix_element": round(sec / (w.n * w.b * w.d) * 1e9, 3),
+                              "calls_per_s_full_size": round(1.0 / sec, 4)}), flush=True)
+
+
+def oracle_table():
+    """Runs oracle_table_child with 1 thread and with all host cores (child processes: the thread
+    count of an OpenMP runtime is fixed by its environment); nothing here touches the GPU."""
+    import subprocess
+
+    cores = os.cpu_count() or 1
+    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+    for threads in (1, cores):
+        env = dict(os.environ, OMP_NUM_THREADS=str(threads))
+        subprocess.run([sys.executable, os.path.abspath(__file__), "--oracle-table-child"], env=env, check=True)
+
+
 def time_launches(fn, steps, warmup):
     """W untimed calls, then K calls between two synchronisations; returns (wall ms, HIP-event ms) per call."""
     import torch
@@ -97,7 +156,7 @@ def time_launches(fn, steps, warmup):
     return (t1 - t0) * 1e3 / steps, ev0.elapsed_time(ev1) / steps
 
 
-def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False):
+def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False, detail=None):
     import numpy as np
     import torch
 
@@ -118,6 +177,28 @@ def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False):
     torch.cuda.synchronize()
     wall_ms, kern_ms = time_launches(lambda k: step(x, m, g, topo, gamma, beta, k), steps, warmup)
     assert bool(torch.isfinite(x[:, :1024]).all()), "state overflowed during the timed run"
+    if detail is not None:
+        # four more repetitions of the same K-launch loop (median of five), then K launches each
+        # bracketed by its own event pair with a fresh gradient generated in between
+        reps = [kern_ms]
+        for _ in range(4):
+            xb[:, :d].normal_()
+            mb.zero_()
+            reps.append(time_launches(lambda k: step(x, m, g, topo, gamma, beta, k), steps, 0)[1])
+        xb[:, :d].normal_()
+        mb.zero_()
+        fresh = []
+        for k in range(steps):
+            workloads.device_grad(w, k, gb)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            step(x, m, g, topo, gamma, beta, k)
+            e1.record()
+            torch.cuda.synchronize()
+            fresh.append(e0.elapsed_time(e1))
+        detail.update({"kernel_ms_repetitions": [round(v, 4) for v in reps],
+                       "kernel_ms_median_of_5": round(sorted(reps)[2], 4),
+                       "kernel_ms_fresh_gradient_each_launch": round(sum(fresh) / len(fresh), 4)})
     if calibration_copy:
         scratch = torch.empty_like(gb)
         scratch.copy_(gb)
@@ -266,7 +347,16 @@ def main():
                     help="after the timed region, run one plain device copy of one n x d array "
                          "(known size: reads and writes 4*n*d bytes) so that a rocprofv3 --pmc run "
                          "of this command can scale FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--oracle-table", action="store_true",
+                    help="CPU only: time the oracle on every workload at 1 thread and at all host cores")
+    ap.add_argument("--oracle-table-child", action="store_true", help=argparse.SUPPRESS)
     args = ap.parse_args()
+    if args.oracle_table_child:
+        oracle_table_child()
+        return
+    if args.oracle_table:
+        oracle_table()
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this build simulates all n nodes on ONE GPU (columns of the update are "
                  "independent, so sharding d over GPUs needs no exchange); run with --gpus 1")
@@ -300,8 +390,9 @@ def main():
                          "algorithmic_bytes_per_launch": r["grad_algorithmic_bytes"]},
         }), flush=True)
         return
+    detail = None if args.no_extras else {}
     w, d, ld, topo, wall_ms, kern_ms = bench_step(P, workloads, args.workload, args.algo, args.steps,
-                                                  args.warmup, args.calibration_copy)
+                                                  args.warmup, args.calibration_copy, detail)
     kind = w.topo
     bytes_per_step = BYTES_PER_ELEMENT * w.n * d
     value = bytes_per_step / (wall_ms * 1e-3) / 1e9
@@ -327,7 +418,7 @@ def main():
                      "algorithmic_bytes_per_launch": bytes_per_step},
     }
     if not args.no_extras:
-        extras = {}
+        extras = dict(detail)
         for name, algo in (("c3_exp32", "dmsgd"), ("c4_ring16_ragged", "decentlam")):
             if (name, algo) == (args.workload, args.algo):
                 continue
