@@ -57,6 +57,8 @@ def _load():
                 ctypes.c_double, ctypes.c_int64, f64p, f64p, f64p, f64p, f64p]
         _lib.oracle_dmsgd_step.argtypes = step
         _lib.oracle_decentlam_step.argtypes = step
+        _lib.oracle_awc_dmsgd_step.argtypes = step
+        _lib.oracle_da_dmsgd_step.argtypes = step
         _lib.oracle_decentlam_xprev_step.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, i32p, i32p, f32p,
                                                      ctypes.c_double, ctypes.c_double, ctypes.c_double,
                                                      ctypes.c_int64, f64p, f64p, f64p, f64p]
@@ -172,6 +174,18 @@ def decentlam_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 
     return _mom_step(_load().oracle_decentlam_step, x, m, g, topo, gamma, beta, k)
 
 
+def awc_dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0):
+    """AWC-DmSGD as read here (m <- beta m + g; x <- W x - gamma m) -> (x_next, m_next), float64.
+    Parity weakly pinned: the paper prints no recursion for it."""
+    return _mom_step(_load().oracle_awc_dmsgd_step, x, m, g, topo, gamma, beta, k)
+
+
+def da_dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0):
+    """DA-DmSGD as read here (mh = beta m + g; x <- W (x - gamma mh); m <- W mh) -> (x_next, m_next).
+    Parity weakly pinned: the paper prints no recursion for it."""
+    return _mom_step(_load().oracle_da_dmsgd_step, x, m, g, topo, gamma, beta, k)
+
+
 def decentlam_xprev_step(x, x_prev, g, topo: Topology, gamma: float, beta: float, k: int = 0,
                          gamma_prev: float | None = None):
     """Momentum-free DecentLaM: x_next = W(x - gamma g) + beta (gamma/gamma_prev) (x - x_prev), float64."""
@@ -272,7 +286,7 @@ def widen16(bits, fmt: str):
     return sign * val
 
 
-STEP = {"decentlam": decentlam_step, "dmsgd": dmsgd_step}
+STEP = {"decentlam": decentlam_step, "dmsgd": dmsgd_step, "awc_dmsgd": awc_dmsgd_step, "da_dmsgd": da_dmsgd_step}
 
 
 def run(algo: str, x0, grad_fn, topo: Topology, gamma: float, beta: float, steps: int,

@@ -22,7 +22,11 @@
  * brute force on tiny cases, the fixed-point equations of the appendix
  * "Limiting Bias of Decentralized Algorithms", automatic differentiation and
  * finite differences for the least-squares gradient, hand-written neighbour
- * tables for the topologies.
+ * tables for the topologies.  The two sibling methods AWC-DmSGD and DA-DmSGD
+ * are this file's reading of one-sentence descriptions ("parity weakly
+ * pinned"): their pins (W = I, beta = 0, node average, dense-matrix brute force,
+ * directly solved fixed points) fix the arithmetic of the reading, not the
+ * reading itself.
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -254,6 +258,63 @@ int oracle_dmsgd_step(int n, int64_t d, int period, const int32_t* row_ptr, cons
             half[q] = x[q] - gamma * m_new;
         }
     partial_average(n, d, rp, col_idx, w, half, x_out);
+    free(half);
+    return 0;
+}
+
+/* AWC-DmSGD (Sec. "Experiments", list of compared algorithms: the
+ * adaptation-with-combination form of DSGD, whose recursion x <- W x - gamma grad
+ * is printed in the discussion that follows the DSGD-as-SGD proposition,
+ * accelerated with momentum).  PARITY WEAKLY PINNED: the paper prints no recursion
+ * for the momentum version; reading taken: the gradient in that recursion is
+ * replaced by the momentum buffer of Algorithm 1,
+ *   m^{k+1} = beta m^k + g^k
+ *   x^{k+1} = sum_j w_ij x_j^k - gamma m_i^{k+1}                           */
+int oracle_awc_dmsgd_step(int n, int64_t d, int period, const int32_t* row_ptr, const int32_t* col_idx,
+                          const float* w, double gamma, double beta, int64_t k,
+                          const double* x, const double* m, const double* g,
+                          double* x_out, double* m_out)
+{
+    const int32_t* rp = row_ptr + (k % period) * (n + 1);
+    partial_average(n, d, rp, col_idx, w, x, x_out);
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < n; ++i)
+        for (int64_t c = 0; c < d; ++c) {
+            int64_t q = (int64_t)i * d + c;
+            double m_new = beta * m[q] + g[q];
+            m_out[q] = m_new;
+            x_out[q] = x_out[q] - gamma * m_new;
+        }
+    return 0;
+}
+
+/* DA-DmSGD (Sec. "Related work" and "Experiments": DmSGD with an additional
+ * partial averaging over the momentum, two partial averages per iteration).
+ * PARITY WEAKLY PINNED: no recursion is printed; reading taken: Algorithm 1
+ * with its momentum buffer averaged as well,
+ *   mh_i    = beta m_i^k + g_i^k
+ *   x^{k+1} = sum_j w_ij (x_j^k - gamma mh_j)
+ *   m^{k+1} = sum_j w_ij mh_j                                              */
+int oracle_da_dmsgd_step(int n, int64_t d, int period, const int32_t* row_ptr, const int32_t* col_idx,
+                         const float* w, double gamma, double beta, int64_t k,
+                         const double* x, const double* m, const double* g,
+                         double* x_out, double* m_out)
+{
+    const int32_t* rp = row_ptr + (k % period) * (n + 1);
+    size_t cnt = (size_t)n * (size_t)(d > 0 ? d : 1);
+    double* mh = (double*)malloc(sizeof(double) * cnt);
+    double* half = (double*)malloc(sizeof(double) * cnt);
+    if (!mh || !half) { free(mh); free(half); return -2; }
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < n; ++i)
+        for (int64_t c = 0; c < d; ++c) {
+            int64_t q = (int64_t)i * d + c;
+            mh[q] = beta * m[q] + g[q];
+            half[q] = x[q] - gamma * mh[q];
+        }
+    partial_average(n, d, rp, col_idx, w, half, x_out);
+    partial_average(n, d, rp, col_idx, w, mh, m_out);
+    free(mh);
     free(half);
     return 0;
 }
