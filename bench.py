@@ -419,7 +419,8 @@ def main():
     }
     if not args.no_extras:
         extras = dict(detail)
-        for name, algo in (("c3_exp32", "dmsgd"), ("c4_ring16_ragged", "decentlam")):
+        for name, algo in (("c3_exp32", "dmsgd"), ("c4_ring16_ragged", "decentlam"), ("c3_exp32", "awc_dmsgd"),
+                           ("c3_exp32", "da_dmsgd")):
             if (name, algo) == (args.workload, args.algo):
                 continue
             w2, d2, _, _, _, k2 = bench_step(P, workloads, name, algo, args.steps, args.warmup)

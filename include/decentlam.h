@@ -165,6 +165,27 @@ int decentlam_step_xprev(const float* x, float* x_prev, const float* g,
                          const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
                          float gamma, float gamma_prev, float beta, int64_t k, void* stream);
 
+/*
+ * awc_dmsgd_step, da_dmsgd_step -- two sibling methods of the paper's comparison that reuse the
+ * same fused gather-mix pass (Sec. "Experiments", list of compared algorithms).  The paper
+ * describes them in a sentence each and prints no recursion; the library implements this reading:
+ *   AWC-DmSGD  (momentum on the adaptation-with-combination form x <- W x - gamma grad, the
+ *              recursion printed after the DSGD-as-SGD proposition):
+ *                  m_i <- beta m_i + g_i ;  x_i <- sum_{j in N_i} w_ij x_j - gamma m_i
+ *   DA-DmSGD   (Algorithm 1 with an additional partial average over the momentum):
+ *                  mh_i = beta m_i + g_i ;  x_i <- sum_j w_ij (x_j - gamma mh_j) ;  m_i <- sum_j w_ij mh_j
+ * Arguments, conventions and errors as dmsgd_step; 20 bytes per node-element.  da_dmsgd_step keeps
+ * two n-row tiles on chip and therefore takes n <= 128 (DL_ETOPO beyond what fits).
+ */
+int awc_dmsgd_step(float* x, float* m, const float* g,
+                   int32_t n, int64_t d, int64_t ld,
+                   const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                   float gamma, float beta, int64_t k, void* stream);
+int da_dmsgd_step(float* x, float* m, const float* g,
+                  int32_t n, int64_t d, int64_t ld,
+                  const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                  float gamma, float beta, int64_t k, void* stream);
+
 /* Storage format of the gradient operand of the *_g16 and *_multi calls. */
 typedef enum {
     DL_GRAD_F32 = 0,

@@ -31,7 +31,7 @@ DL_MAX_NODES, DL_MAX_NNZ, DL_MAX_NNZ_PALETTE, DL_MAX_WEIGHT_VALUES = 256, 512, 1
 DL_GRAD_F32, DL_GRAD_BF16, DL_GRAD_F16 = 0, 1, 2
 
 EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decentlam_step", "decentlam_step_xprev",
-           "dmsgd_step", "dsgd_step", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
+           "dmsgd_step", "dsgd_step", "awc_dmsgd_step", "da_dmsgd_step", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
            "dmsgd_step_multi", "decentlam_step_multi_workspace", "local_grad_lsq", "local_grad_lsq_rows",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
@@ -62,7 +62,7 @@ def _load() -> ctypes.CDLL:
     lib.topology_metropolis.argtypes = [ctypes.c_int32, i32p, i32p, f32p, ctypes.POINTER(ctypes.c_uint32)]
     step = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, i32p, f32p,
             ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_int64, vp]
-    for name in ("decentlam_step", "dmsgd_step"):
+    for name in ("decentlam_step", "dmsgd_step", "awc_dmsgd_step", "da_dmsgd_step"):
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = step
     for name in ("decentlam_step_g16", "dmsgd_step_g16"):
@@ -208,6 +208,16 @@ def decentlam_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 
 def dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
     """One DmSGD iteration in place on device tensors x, m (n x d fp32), asynchronous."""
     _step(_lib.dmsgd_step, x, m, g, topo, gamma, beta, k, stream)
+
+
+def awc_dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
+    """One AWC-DmSGD iteration (m <- beta m + g; x <- W x - gamma m) in place, asynchronous."""
+    _step(_lib.awc_dmsgd_step, x, m, g, topo, gamma, beta, k, stream)
+
+
+def da_dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
+    """One DA-DmSGD iteration (mh = beta m + g; x <- W (x - gamma mh); m <- W mh) in place, asynchronous."""
+    _step(_lib.da_dmsgd_step, x, m, g, topo, gamma, beta, k, stream)
 
 
 _GRAD_FORMAT = {torch.float32: DL_GRAD_F32, torch.bfloat16: DL_GRAD_BF16, torch.float16: DL_GRAD_F16}

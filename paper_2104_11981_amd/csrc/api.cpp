@@ -255,6 +255,20 @@ int dmsgd_step(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t
                           gamma, beta, k, stream);
 }
 
+int awc_dmsgd_step(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
+                   const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                   float gamma, float beta, int64_t k, void* stream) {
+    return dl::step_entry("awc_dmsgd_step", dl::ALGO_AWC_DMSGD, x, m, g, n, d, ld, row_ptr, col_idx, w, period,
+                          gamma, beta, k, stream);
+}
+
+int da_dmsgd_step(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
+                  const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                  float gamma, float beta, int64_t k, void* stream) {
+    return dl::step_entry("da_dmsgd_step", dl::ALGO_DA_DMSGD, x, m, g, n, d, ld, row_ptr, col_idx, w, period,
+                          gamma, beta, k, stream);
+}
+
 int decentlam_step_g16(float* x, float* m, const void* g, int32_t g_format, int32_t n, int64_t d, int64_t ld,
                        int64_t ldg, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
                        int32_t period, float gamma, float beta, int64_t k, void* stream) {

@@ -34,7 +34,8 @@ struct PhaseArgs {
 };
 static_assert(sizeof(PhaseArgs) <= 4096 - 128, "kernel-argument segment is 4 KiB");
 
-enum Algo { ALGO_DECENTLAM = 0, ALGO_DMSGD = 1, ALGO_DSGD = 2, ALGO_DECENTLAM_XPREV = 3 };
+enum Algo { ALGO_DECENTLAM = 0, ALGO_DMSGD = 1, ALGO_DSGD = 2, ALGO_DECENTLAM_XPREV = 3, ALGO_AWC_DMSGD = 4,
+            ALGO_DA_DMSGD = 5 };
 
 int set_error(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 int check_hip(hipError_t e, const char* what);

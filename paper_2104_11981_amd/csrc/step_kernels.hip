@@ -173,7 +173,9 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
 //        ALGO_DECENTLAM_XPREV: DecentLaM in its momentum-free form (appendix "Reformulation of
 //        DecentLaM"), x_next = W (x - gamma g) + beta' (x - x_prev); here `m` is the buffer that
 //        holds x_prev on entry and x_next on exit, x is only read, and `beta` carries
-//        beta' = beta * gamma / gamma_prev: 16 bytes per node-element, one written array
+//        beta' = beta * gamma / gamma_prev: 16 bytes per node-element, one written array;
+//        ALGO_AWC_DMSGD (m <- beta m + g; x <- W x - gamma m: the tile holds x) and ALGO_DA_DMSGD
+//        (mh = beta m + g; x <- W (x - gamma mh); m <- W mh: two tiles, h and mh, both gathered)
 // GF     dl_grad_format of g;  NORMS: accumulate the per-tensor sums of squares
 template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
 __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8) ? 8 : 1) void k_step(float* __restrict__ x, float* __restrict__ m,
@@ -184,7 +186,8 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
     constexpr int TC = 64 * VEC;
     extern __shared__ double lds[];  // tile [n][TC] of u_j (DecentLaM) or h_j (DmSGD), then the table
     const int n = topo.n;
-    Neighbour* table = reinterpret_cast<Neighbour*>(lds + n * TC);
+    constexpr int TILES = ALGO == ALGO_DA_DMSGD ? 2 : 1;   // DA-DmSGD parks mh_j in a second tile
+    Neighbour* table = reinterpret_cast<Neighbour*>(lds + TILES * n * TC);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -234,7 +237,17 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
                     sq_g = __builtin_fma(gv, gv, sq_g);
                 }
             }
-            if constexpr (ALGO != ALGO_DMSGD) {
+            if constexpr (ALGO == ALGO_AWC_DMSGD) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) slot[v] = static_cast<double>(xr[r][v]);
+            } else if constexpr (ALGO == ALGO_DA_DMSGD) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const double mh = beta * static_cast<double>(mr[r][v]) + static_cast<double>(gr[r][v]);
+                    slot[v] = static_cast<double>(xr[r][v]) - gamma * mh;
+                    slot[n * TC + v] = mh;
+                }
+            } else if constexpr (ALGO != ALGO_DMSGD) {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v)
                     slot[v] = static_cast<double>(xr[r][v]) - gamma * static_cast<double>(gr[r][v]);
@@ -315,6 +328,28 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
                     const double diff = static_cast<double>(xr[r][v]) - static_cast<double>(mr[r][v]);
                     xo[v] = static_cast<float>(__builtin_fma(beta, diff, z[v]));
                 }
+            } else if constexpr (ALGO == ALGO_AWC_DMSGD) {
+                float mo[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const double m_new = beta * static_cast<double>(mr[r][v]) + static_cast<double>(gr[r][v]);
+                    mo[v] = static_cast<float>(m_new);
+                    xo[v] = static_cast<float>(z[v] - gamma * m_new);
+                }
+                store_vec<VEC>(m + at, mo);
+            } else if constexpr (ALGO == ALGO_DA_DMSGD) {
+                double zm[VEC];   // second partial average, over the momentum tile
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) zm[v] = 0.0;
+                const double* m_tile_at_lane = tile_at_lane + n * TC;
+                for (int q = topo.row_ptr[i]; q < e1; ++q) gather<VEC, 1>(table + q, m_tile_at_lane, zm);
+                float mo[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    mo[v] = static_cast<float>(zm[v]);
+                    xo[v] = static_cast<float>(z[v]);
+                }
+                store_vec<VEC>(m + at, mo);
             } else {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) xo[v] = static_cast<float>(z[v]);
@@ -345,8 +380,8 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
     }
 }
 
-size_t lds_bytes_for(int32_t n, int vec, int nnz) {
-    return static_cast<size_t>(n) * 64 * vec * sizeof(double) + static_cast<size_t>(nnz) * sizeof(Neighbour);
+size_t lds_bytes_for(int32_t n, int vec, int nnz, int tiles) {
+    return static_cast<size_t>(tiles) * n * 64 * vec * sizeof(double) + static_cast<size_t>(nnz) * sizeof(Neighbour);
 }
 
 // Everything a launch needs besides its template parameters.
@@ -365,8 +400,11 @@ struct StepCall {
 template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
 int launch_variant(const StepCall& s) {
     constexpr int TC = 64 * VEC;
-    const size_t lds_bytes = lds_bytes_for(s.n, VEC, s.topo->row_ptr[s.n]);
+    const size_t lds_bytes = lds_bytes_for(s.n, VEC, s.topo->row_ptr[s.n], ALGO == ALGO_DA_DMSGD ? 2 : 1);
     auto kernel = k_step<VEC, RPT, WAVES, ALGO, GF, NORMS>;
+    if (lds_bytes > 160 * 1024)
+        return set_error(DL_ETOPO, "step: n = %d with %d entries needs %zu bytes of LDS, a CU has 163840", s.n,
+                         static_cast<int>(s.topo->row_ptr[s.n]), lds_bytes);
     if (lds_bytes > 48 * 1024) {
         if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -386,7 +424,7 @@ int launch_variant(const StepCall& s) {
 template <int VEC, int ALGO, int GF, bool NORMS>
 int launch_rows(const StepCall& s) {
 #define DL_SHAPE(MAXN, W, R)                                                             \
-    if constexpr (VEC == 1 || VEC * (MAXN) <= 128) {                                     \
+    if constexpr (VEC == 1 || VEC * (MAXN) <= (ALGO == ALGO_DA_DMSGD ? 64 : 128)) {        \
         if (s.n <= (MAXN)) return launch_variant<VEC, R, W, ALGO, GF, NORMS>(s);         \
     }
     DL_SHAPE(4, 4, 1) DL_SHAPE(8, 8, 1) DL_SHAPE(16, 16, 1) DL_SHAPE(32, 16, 2)
@@ -425,7 +463,8 @@ int launch_extras(int vec, int format, bool norms, const StepCall& s) {
 
 // Widest access for which the fp64 tile of n rows takes 64 KiB of LDS, so that two workgroups
 // share a CU (VEC * n <= 128); beyond n = 128 the 4-byte variant uses up to 128 KiB.
-int widest_vec_for(int32_t n) {
+int widest_vec_for(int32_t n, Algo algo) {
+    if (algo == ALGO_DA_DMSGD) n *= 2;   // two tiles
     if (n <= 32) return 4;
     if (n <= 64) return 2;
     return 1;
@@ -440,7 +479,7 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
 
     // Pick the widest access all three arrays can share: same misalignment (in elements)
     // modulo the vector width and row strides that preserve it.
-    int vec = widest_vec_for(n);
+    int vec = widest_vec_for(n, algo);
     int64_t head = 0;
     for (; vec > 1; vec >>= 1) {
         const uintptr_t mask = static_cast<uintptr_t>(vec) - 1;
@@ -479,6 +518,8 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
             case ALGO_DECENTLAM: return launch_extras<ALGO_DECENTLAM>(v, g.format, norms != nullptr, s);
             case ALGO_DMSGD: return launch_extras<ALGO_DMSGD>(v, g.format, norms != nullptr, s);
             case ALGO_DSGD: return launch_extras<ALGO_DSGD>(v, g.format, norms != nullptr, s);
+            case ALGO_AWC_DMSGD: return launch_extras<ALGO_AWC_DMSGD>(v, g.format, norms != nullptr, s);
+            case ALGO_DA_DMSGD: return launch_extras<ALGO_DA_DMSGD>(v, g.format, norms != nullptr, s);
             default: return launch_extras<ALGO_DECENTLAM_XPREV>(v, g.format, norms != nullptr, s);
         }
     };

@@ -303,3 +303,18 @@ def test_multi_tensor_argument_validation():
     assert call([0, 10, 64], norms=0x50000 + 8, ws=0x50000, wsb=need) == P.DL_EALIAS      # norms inside the workspace
     assert call([0, 10, 64], norms=0x10000, ws=0x50000, wsb=need) == P.DL_EALIAS          # norms inside x
     assert P.decentlam_step_multi_workspace(0, 64, 2) == 0
+
+
+@pytest.mark.parametrize("name", ["awc_dmsgd_step", "da_dmsgd_step"])
+def test_sibling_step_argument_validation(name):
+    t = P.topology_build(0, 4)
+    fn = getattr(P.raw, name)
+    f = lambda **kw: fn(kw.get("x"), kw.get("m"), kw.get("g"), 4, kw.get("d", 0), kw.get("ld", 0), *t._args(),
+                        kw.get("gamma", 0.1), kw.get("beta", 0.9), kw.get("k", 0), None)
+    assert f() == P.DL_OK
+    assert f(gamma=-1.0) == P.DL_EINVAL
+    assert f(beta=1.0) == P.DL_EINVAL
+    assert f(k=-1) == P.DL_EINVAL
+    assert f(d=8, ld=4) == P.DL_EINVAL
+    assert f(d=8, ld=8) == P.DL_EINVAL and "NULL" in P.last_error()
+    assert f(d=8, ld=8, x=4096, m=4096 + 16, g=8192) == P.DL_EALIAS
