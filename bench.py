@@ -237,6 +237,34 @@ def bench_xprev(P, workloads, name, steps, warmup):
             "steps_per_s": round(1e3 / kern_ms, 1)}
 
 
+def bench_blocked(P, workloads, name, algo, steps, warmup, bw=8192):
+    """The same n x d step on arrays in the blocked layout (blocks of bw columns, each a row-major
+    n x bw matrix): the n rows a workgroup touches lie within n*bw*4 bytes and share address
+    translations, instead of being d*4 bytes apart."""
+    import numpy as np
+    import torch
+
+    w = workloads.get(name)
+    d = workloads.generate.dim(w)
+    nb = (d + bw - 1) // bw
+    topo = P.topology_build(w.topo, w.n)
+    gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
+    gen = torch.Generator(device="cuda").manual_seed(workloads.BASE_SEED % (2 ** 31))
+    x = torch.empty((nb, w.n, bw), dtype=torch.float32, device="cuda").normal_(generator=gen)
+    m = torch.zeros_like(x)
+    g = torch.empty_like(x).normal_(generator=gen)
+    step = getattr(P, algo + "_step_blocked")
+    wall_ms, kern_ms = time_launches(lambda k: step(x, m, g, d, topo, gamma, beta, k), steps, warmup)
+    assert bool(torch.isfinite(x[0, :, :1024]).all()), "state overflowed during the timed run"
+    nbytes = BYTES_PER_ELEMENT * w.n * d
+    del x, m, g
+    torch.cuda.empty_cache()
+    return {"kernel_ms": round(kern_ms, 4), "wall_ms": round(wall_ms, 4), "block_columns": bw,
+            "GBps": round(nbytes / (kern_ms * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(nbytes / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "steps_per_s": round(1e3 / wall_ms, 1)}
+
+
 def bench_g16(P, workloads, name, steps, warmup, dtype_name="bfloat16"):
     """DecentLaM step with 16-bit gradients (x, m fp32): 18 bytes per node-element."""
     import numpy as np
@@ -428,6 +456,10 @@ def main():
             extras[f"{algo}_step_{name}"] = {"kernel_ms": round(k2, 4), "GBps": round(b2 / (k2 * 1e-3) / 1e9, 1),
                                              "frac_of_hbm_peak": round(b2 / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         extras["decentlam_step_xprev_c3_exp32"] = bench_xprev(P, workloads, "c3_exp32", args.steps, args.warmup)
+        extras["decentlam_step_blocked_c3_exp32"] = bench_blocked(P, workloads, "c3_exp32", "decentlam", args.steps,
+                                                                  args.warmup)
+        extras["dmsgd_step_blocked_c3_exp32"] = bench_blocked(P, workloads, "c3_exp32", "dmsgd", args.steps,
+                                                              args.warmup)
         extras["decentlam_step_g16_bf16_c3_exp32"] = bench_g16(P, workloads, "c3_exp32", args.steps, args.warmup)
         extras["decentlam_step_multi_norms_c4_ring16_ragged"] = bench_multi(P, workloads, "c4_ring16_ragged",
                                                                              args.steps, args.warmup)

@@ -31,7 +31,8 @@ DL_MAX_NODES, DL_MAX_NNZ, DL_MAX_NNZ_PALETTE, DL_MAX_WEIGHT_VALUES = 256, 512, 1
 DL_GRAD_F32, DL_GRAD_BF16, DL_GRAD_F16 = 0, 1, 2
 
 EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decentlam_step", "decentlam_step_xprev",
-           "dmsgd_step", "dsgd_step", "awc_dmsgd_step", "da_dmsgd_step", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
+           "dmsgd_step", "dsgd_step", "awc_dmsgd_step", "da_dmsgd_step", "decentlam_step_blocked",
+           "dmsgd_step_blocked", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
            "dmsgd_step_multi", "decentlam_step_multi_workspace", "local_grad_lsq", "local_grad_lsq_rows",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
@@ -62,7 +63,8 @@ def _load() -> ctypes.CDLL:
     lib.topology_metropolis.argtypes = [ctypes.c_int32, i32p, i32p, f32p, ctypes.POINTER(ctypes.c_uint32)]
     step = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, i32p, i32p, f32p,
             ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_int64, vp]
-    for name in ("decentlam_step", "dmsgd_step", "awc_dmsgd_step", "da_dmsgd_step"):
+    for name in ("decentlam_step", "dmsgd_step", "awc_dmsgd_step", "da_dmsgd_step", "decentlam_step_blocked",
+                 "dmsgd_step_blocked"):   # the blocked calls take bw where the others take ld
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = step
     for name in ("decentlam_step_g16", "dmsgd_step_g16"):
@@ -208,6 +210,46 @@ def decentlam_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 
 def dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
     """One DmSGD iteration in place on device tensors x, m (n x d fp32), asynchronous."""
     _step(_lib.dmsgd_step, x, m, g, topo, gamma, beta, k, stream)
+
+
+def to_blocked(a, bw: int, fill: float = 0.0):
+    """Logical n x d tensor -> blocked layout tensor of shape (ceil(d / bw), n, bw) (a copy; padding = fill)."""
+    n, d = a.shape
+    nb = (d + bw - 1) // bw
+    out = torch.full((n, nb * bw), fill, dtype=a.dtype, device=a.device)
+    out[:, :d] = a
+    return out.view(n, nb, bw).permute(1, 0, 2).contiguous()
+
+
+def from_blocked(b, d: int):
+    """Blocked layout tensor (nb, n, bw) -> logical n x d tensor (a copy)."""
+    nb, n, bw = b.shape
+    return b.permute(1, 0, 2).reshape(n, nb * bw)[:, :d].contiguous()
+
+
+def _step_blocked(fn, x, m, g, d, topo, gamma, beta, k, stream):
+    for name, t in (("x", x), ("m", m), ("g", g)):
+        if t.dtype != torch.float32 or not t.is_cuda or t.dim() != 3 or not t.is_contiguous():
+            raise TypeError(f"{name}: need a contiguous 3-D (blocks, n, bw) float32 device tensor")
+    if x.shape != m.shape or x.shape != g.shape:
+        raise TypeError("x, m and g must share their shape")
+    nb, n, bw = x.shape
+    if not (0 <= d <= nb * bw) or (nb > 0 and d <= (nb - 1) * bw):
+        raise DecentLamError(DL_EINVAL, f"d = {d} does not end in the last of {nb} blocks of {bw} columns")
+    if topo.n != n:
+        raise DecentLamError(DL_ETOPO, f"topology has {topo.n} nodes, arrays have {n} rows")
+    _check(fn(x.data_ptr(), m.data_ptr(), g.data_ptr(), n, d, bw, *topo._args(), gamma, beta, k,
+              _stream() if stream is None else stream))
+
+
+def decentlam_step_blocked(x, m, g, d: int, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
+    """decentlam_step on arrays in the blocked layout: tensors of shape (ceil(d / bw), n, bw)."""
+    _step_blocked(_lib.decentlam_step_blocked, x, m, g, d, topo, gamma, beta, k, stream)
+
+
+def dmsgd_step_blocked(x, m, g, d: int, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
+    """dmsgd_step on arrays in the blocked layout: tensors of shape (ceil(d / bw), n, bw)."""
+    _step_blocked(_lib.dmsgd_step_blocked, x, m, g, d, topo, gamma, beta, k, stream)
 
 
 def awc_dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):

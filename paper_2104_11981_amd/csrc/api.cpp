@@ -236,6 +236,53 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int
     return launch_norms_finish(plan, x, m, ga, ld, n, s);
 }
 
+// Blocked layout: the n x d problem is stored as ceil(d / bw) blocks of bw columns, each block a
+// row-major n x bw matrix (row stride bw), blocks back to back: element (i, c) lives at
+// ((c / bw) * n + i) * bw + c % bw.  The full blocks are one batched launch, a narrower last block
+// is an ordinary row-major problem with ld = bw.
+int blocked_entry(const char* fn, Algo algo, float* x, float* m, const float* g, int32_t n, int64_t d,
+                  int64_t bw, const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                  float gamma, float beta, int64_t k, void* stream) {
+    clear_error();
+    if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
+    if (d < 0) return set_error(DL_EINVAL, "%s: d = %lld, need d >= 0", fn, static_cast<long long>(d));
+    if (bw < 1) return set_error(DL_EINVAL, "%s: bw = %lld, need bw >= 1", fn, static_cast<long long>(bw));
+    if (!std::isfinite(gamma) || !(gamma > 0.0f))
+        return set_error(DL_EINVAL, "%s: gamma = %g must be finite and > 0", fn, static_cast<double>(gamma));
+    if (!(beta >= 0.0f && beta < 1.0f))
+        return set_error(DL_EINVAL, "%s: beta = %g must lie in [0, 1)", fn, static_cast<double>(beta));
+    if (k < 0) return set_error(DL_EINVAL, "%s: k = %lld, need k >= 0", fn, static_cast<long long>(k));
+    if (period < 1) return set_error(DL_EINVAL, "%s: period = %d, need period >= 1", fn, period);
+    if (!row_ptr || !col_idx || !w)
+        return set_error(DL_EINVAL, "%s: row_ptr, col_idx and w must not be NULL", fn);
+    PhaseArgs topo;
+    std::memset(&topo, 0, sizeof(topo));
+    if (int rc = pack_phase(fn, n, row_ptr, col_idx, w, static_cast<int32_t>(k % period), &topo)) return rc;
+    if (d == 0) return DL_OK;
+    if (!x || !m || !g) return set_error(DL_EINVAL, "%s: x, m and g must not be NULL", fn);
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(g)) & 3u)
+        return set_error(DL_EINVAL, "%s: x, m and g must be 4-byte aligned", fn);
+    const int64_t full = d / bw, rest = d % bw;
+    const int64_t block = static_cast<int64_t>(n) * bw;
+    const int64_t elements = full * block + (rest ? (static_cast<int64_t>(n) - 1) * bw + rest : 0);
+    const Span sx = span_of(x, 1, elements, elements), sm = span_of(m, 1, elements, elements),
+               sg = span_of(g, 1, elements, elements);
+    if (overlap(sx, sm) || overlap(sx, sg) || overlap(sm, sg))
+        return set_error(DL_EALIAS, "%s: x, m and g must not overlap", fn);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (full > 0) {
+        if (int rc = launch_step(algo, x, m, GradArg{g, DL_GRAD_F32, bw}, n, bw, bw, topo, gamma,
+                                 static_cast<double>(beta), s, nullptr, full, block, block))
+            return rc;
+    }
+    if (rest > 0) {
+        const int64_t at = full * block;
+        return launch_step(algo, x + at, m + at, GradArg{g + at, DL_GRAD_F32, bw}, n, rest, bw, topo, gamma,
+                           static_cast<double>(beta), s);
+    }
+    return DL_OK;
+}
+
 }  // namespace
 }  // namespace dl
 
@@ -253,6 +300,20 @@ int dmsgd_step(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t
                float gamma, float beta, int64_t k, void* stream) {
     return dl::step_entry("dmsgd_step", dl::ALGO_DMSGD, x, m, g, n, d, ld, row_ptr, col_idx, w, period,
                           gamma, beta, k, stream);
+}
+
+int decentlam_step_blocked(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t bw,
+                           const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                           float gamma, float beta, int64_t k, void* stream) {
+    return dl::blocked_entry("decentlam_step_blocked", dl::ALGO_DECENTLAM, x, m, g, n, d, bw, row_ptr, col_idx, w,
+                             period, gamma, beta, k, stream);
+}
+
+int dmsgd_step_blocked(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t bw,
+                       const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                       float gamma, float beta, int64_t k, void* stream) {
+    return dl::blocked_entry("dmsgd_step_blocked", dl::ALGO_DMSGD, x, m, g, n, d, bw, row_ptr, col_idx, w, period,
+                             gamma, beta, k, stream);
 }
 
 int awc_dmsgd_step(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,

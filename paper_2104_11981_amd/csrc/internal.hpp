@@ -75,9 +75,12 @@ inline int64_t norm_tiles_bound(int64_t d) { return (d + 63) / 64 + 3; }
 // Enqueue one fused iteration over columns [0, d) of x, m, g (already validated).
 // `beta` is a double so that the momentum-free form can pass beta * gamma / gamma_prev unrounded.
 // With `norms` the launches also write their tile records and note their grids in it.
+// With batches > 1 the launches cover `batches` equally shaped problems whose arrays start
+// batch_stride (x, m) and batch_stride_g (g) elements apart -- the full blocks of the blocked layout.
 int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, int64_t ld,
                 const PhaseArgs& topo, float gamma, double beta, hipStream_t stream,
-                NormPlan* norms = nullptr);
+                NormPlan* norms = nullptr, int64_t batches = 1, int64_t batch_stride = 0,
+                int64_t batch_stride_g = 0);
 // After launch_step with `norms`: x, m, g as passed there.
 int launch_norms_finish(const NormPlan& plan, const float* x, const float* m, GradArg g, int64_t ld, int32_t n,
                         hipStream_t stream);

@@ -90,6 +90,14 @@ __device__ __forceinline__ void load_grad(const typename GradElem<GF>::type* __r
     }
 }
 
+// A launch may cover `count` equally shaped sub-problems ("batches": the blocks of the blocked
+// layout): consecutive workgroups walk the tiles of batch 0, then batch 1, ...
+struct BatchArgs {
+    int64_t stride;        // elements between consecutive batches of x and m
+    int64_t stride_g;      // the same for g, in its elements
+    uint32_t tiles;        // tiles per batch; 0: the launch is a single problem
+};
+
 // Per-launch arguments of the per-tensor sums (see NormPlan): where the tile records go.
 struct NormArgs {
     double* partial;
@@ -182,7 +190,8 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
                                                       const typename GradElem<GF>::type* __restrict__ g,
                                                       int64_t d, int64_t ld, int64_t ldg,
                                                       double gamma, double inv_gamma, double beta,
-                                                      const NormArgs na, const PhaseArgs topo) {
+                                                      const BatchArgs batch, const NormArgs na,
+                                                      const PhaseArgs topo) {
     constexpr int TC = 64 * VEC;
     extern __shared__ double lds[];  // tile [n][TC] of u_j (DecentLaM) or h_j (DmSGD), then the table
     const int n = topo.n;
@@ -191,7 +200,15 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t c = static_cast<int64_t>(blockIdx.x) * TC + lane * VEC;
+    uint32_t tile = blockIdx.x;
+    if (batch.tiles) {   // uniform: which sub-problem, which of its tiles
+        const uint32_t b = tile / batch.tiles;
+        tile -= b * batch.tiles;
+        x += b * batch.stride;
+        if constexpr (ALGO != ALGO_DSGD) m += b * batch.stride;
+        g += b * batch.stride_g;
+    }
+    const int64_t c = static_cast<int64_t>(tile) * TC + lane * VEC;
     const bool live = c < d;  // d is a multiple of VEC for this launch
 
     // ---- phase 1: stream rows in
@@ -395,6 +412,7 @@ struct StepCall {
     const PhaseArgs* topo;
     hipStream_t stream;
     NormArgs na;
+    int64_t batches, batch_stride, batch_stride_g;   // batches == 1: a single problem
 };
 
 template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
@@ -412,11 +430,13 @@ int launch_variant(const StepCall& s) {
                                "hipFuncSetAttribute(max dynamic LDS)"))
             return rc;
     }
-    const int64_t blocks = (s.d + TC - 1) / TC;
+    const int64_t tiles = (s.d + TC - 1) / TC;
+    const int64_t blocks = tiles * s.batches;
     if (blocks > 0x7fffffffLL) return set_error(DL_EINVAL, "step: d too large for one launch");
+    const BatchArgs batch{s.batch_stride, s.batch_stride_g, s.batches > 1 ? static_cast<uint32_t>(tiles) : 0u};
     hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(blocks)), dim3(64 * WAVES), lds_bytes, s.stream,
                        s.x, s.m, static_cast<const typename GradElem<GF>::type*>(s.g), s.d, s.ld, s.ldg,
-                       s.gamma, 1.0 / s.gamma, s.beta, s.na, *s.topo);
+                       s.gamma, 1.0 / s.gamma, s.beta, batch, s.na, *s.topo);
     return check_hip(hipGetLastError(), "step kernel launch");
 }
 
@@ -472,7 +492,8 @@ int widest_vec_for(int32_t n, Algo algo) {
 
 }  // namespace
 int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, int64_t ld,
-                const PhaseArgs& topo, float gamma_f, double beta, hipStream_t stream, NormPlan* norms) {
+                const PhaseArgs& topo, float gamma_f, double beta, hipStream_t stream, NormPlan* norms,
+                int64_t batches, int64_t batch_stride, int64_t batch_stride_g) {
     const double gamma = static_cast<double>(gamma_f);
     const size_t gbytes = grad_elem_bytes(g.format);
     const unsigned gshift = gbytes == 4 ? 2 : 1;
@@ -486,7 +507,8 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
         const uintptr_t ax = (reinterpret_cast<uintptr_t>(x) >> 2) & mask;
         const uintptr_t am = m ? (reinterpret_cast<uintptr_t>(m) >> 2) & mask : ax;
         const uintptr_t ag = (reinterpret_cast<uintptr_t>(g.p) >> gshift) & mask;
-        if (ax == am && ax == ag && ((ld | g.ld) & static_cast<int64_t>(mask)) == 0) {
+        const int64_t strides = ld | g.ld | (batches > 1 ? (batch_stride | batch_stride_g) : 0);
+        if (ax == am && ax == ag && (strides & static_cast<int64_t>(mask)) == 0) {
             head = static_cast<int64_t>((vec - ax) & mask);
             break;
         }
@@ -507,6 +529,7 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
         s.n = n; s.d = cols; s.ld = ld; s.ldg = g.ld;
         s.gamma = gamma; s.beta = beta; s.topo = &topo; s.stream = stream;
         s.na = NormArgs{nullptr, 0};
+        s.batches = batches; s.batch_stride = batch_stride; s.batch_stride_g = batch_stride_g;
         if (norms) {
             const int tc = 64 * v;
             NormGrid& gr = norms->grid[norms->grids++];

@@ -318,3 +318,17 @@ def test_sibling_step_argument_validation(name):
     assert f(d=8, ld=4) == P.DL_EINVAL
     assert f(d=8, ld=8) == P.DL_EINVAL and "NULL" in P.last_error()
     assert f(d=8, ld=8, x=4096, m=4096 + 16, g=8192) == P.DL_EALIAS
+
+
+def test_blocked_argument_validation():
+    t = P.topology_build(0, 4)
+    f = lambda **kw: P.raw.decentlam_step_blocked(kw.get("x"), kw.get("m"), kw.get("g"), 4, kw.get("d", 0),
+                                                  kw.get("bw", 64), *t._args(), kw.get("gamma", 0.1), 0.9,
+                                                  kw.get("k", 0), None)
+    assert f() == P.DL_OK
+    assert f(bw=0) == P.DL_EINVAL and "bw" in P.last_error()
+    assert f(d=-1) == P.DL_EINVAL
+    assert f(gamma=float("inf")) == P.DL_EINVAL
+    assert f(d=100) == P.DL_EINVAL and "NULL" in P.last_error()
+    assert f(d=100, x=0x10000, m=0x10000 + 4 * 200, g=0x80000) == P.DL_EALIAS     # m inside x's second block
+    assert f(d=100, x=0x10002, m=0x40000, g=0x80000) == P.DL_EINVAL
