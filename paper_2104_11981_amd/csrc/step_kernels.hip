@@ -280,7 +280,10 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
                         sq_m = __builtin_fma(mv, mv, sq_m);
                     }
                 }
-                store_vec<VEC>(m + static_cast<int64_t>(i) * ld + c, mn);
+                // the new m waits in the registers of the old one and is stored together with x
+                // after the barrier: one burst of stores per row measures faster than two
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) mr[r][v] = mn[v];
             }
         }
         if constexpr (NORMS) {
@@ -370,6 +373,7 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
             } else {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) xo[v] = static_cast<float>(z[v]);
+                if constexpr (ALGO == ALGO_DMSGD) store_vec<VEC>(m + at, mr[r]);
             }
             store_vec<VEC>((ALGO == ALGO_DECENTLAM_XPREV ? m : x) + at, xo);
             if constexpr (NORMS) {
