@@ -33,6 +33,7 @@ BYTES_PER_ELEMENT = 20         # read x, m, g + write x, m, fp32
 # the same counter reads for a plain device copy of known size; profiles/*_hbm_traffic_pmc.txt),
 # keyed by (workload, algo); None where not measured.
 MEASURED_TRAFFIC_BYTES = {("c3_exp32", "decentlam"): 16_383_747_763,
+                          ("c3_exp32", "decentlam_blocked"): 16_383_700_000,
                           ("c5_onepeer64_lsq", "local_grad_lsq"): 4_342_500_000}
 
 
@@ -237,7 +238,7 @@ def bench_xprev(P, workloads, name, steps, warmup):
             "steps_per_s": round(1e3 / kern_ms, 1)}
 
 
-def bench_blocked(P, workloads, name, algo, steps, warmup, bw=8192):
+def bench_blocked(P, workloads, name, algo, steps, warmup, bw=8192, calibration_copy=False):
     """The same n x d step on arrays in the blocked layout (blocks of bw columns, each a row-major
     n x bw matrix): the n rows a workgroup touches lie within n*bw*4 bytes and share address
     translations, instead of being d*4 bytes apart."""
@@ -257,6 +258,11 @@ def bench_blocked(P, workloads, name, algo, steps, warmup, bw=8192):
     wall_ms, kern_ms = time_launches(lambda k: step(x, m, g, d, topo, gamma, beta, k), steps, warmup)
     assert bool(torch.isfinite(x[0, :, :1024]).all()), "state overflowed during the timed run"
     nbytes = BYTES_PER_ELEMENT * w.n * d
+    if calibration_copy:
+        scratch = torch.empty_like(g)
+        scratch.copy_(g)
+        torch.cuda.synchronize()
+        del scratch
     del x, m, g
     torch.cuda.empty_cache()
     return {"kernel_ms": round(kern_ms, 4), "wall_ms": round(wall_ms, 4), "block_columns": bw,
@@ -368,6 +374,11 @@ def main():
     ap.add_argument("--workload", default="c3_exp32",
                     choices=["c3_exp32", "c4_ring16_ragged", "c5_onepeer64_lsq"])
     ap.add_argument("--algo", default="decentlam", choices=["decentlam", "dmsgd"])
+    ap.add_argument("--layout", default="rowmajor", choices=["rowmajor", "blocked"],
+                    help="rowmajor: decentlam_step / dmsgd_step on n x d arrays with row stride ld (the default); "
+                         "blocked: the *_step_blocked calls on the same problem stored in blocks of "
+                         "--block-columns columns")
+    ap.add_argument("--block-columns", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the side measurements (DmSGD, ragged workload, least-squares gradient)")
@@ -416,6 +427,26 @@ def main():
                          "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "local_grad_lsq")),
                          "kernel": "k_fused", "kernel_ms": r["grad_kernel_ms"],
                          "algorithmic_bytes_per_launch": r["grad_algorithmic_bytes"]},
+        }), flush=True)
+        return
+    if args.layout == "blocked":
+        # the same problem in the blocked layout, as a line of its own (used for the profiles)
+        w = workloads.get(args.workload)
+        d = workloads.generate.dim(w)
+        r = bench_blocked(P, workloads, args.workload, args.algo, args.steps, args.warmup, args.block_columns,
+                          args.calibration_copy)
+        nbytes = BYTES_PER_ELEMENT * w.n * d
+        print(json.dumps({
+            "metric": f"{args.algo} step, blocked layout: achieved HBM GB/s & steps/s ({w.name})",
+            "value": round(nbytes / (r["wall_ms"] * 1e-3) / 1e9, 2), "unit": "GB/s", "steps_per_s": r["steps_per_s"],
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["wall_ms"],
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+            "config": {"workload": w.name, "algo": args.algo, "n": w.n, "d": d, "layout": "blocked",
+                       "block_columns": args.block_columns, "bytes_per_node_element": BYTES_PER_ELEMENT},
+            "roofline": {"bound": "hbm", "achieved": r["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": r["frac_of_hbm_peak"],
+                         "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.algo + "_blocked")),
+                         "kernel": "k_step", "kernel_ms": r["kernel_ms"], "algorithmic_bytes_per_launch": nbytes},
         }), flush=True)
         return
     detail = None if args.no_extras else {}
