@@ -33,7 +33,7 @@ BYTES_PER_ELEMENT = 20         # read x, m, g + write x, m, fp32
 # the same counter reads for a plain device copy of known size; profiles/*_hbm_traffic_pmc.txt),
 # keyed by (workload, algo); None where not measured.
 MEASURED_TRAFFIC_BYTES = {("c3_exp32", "decentlam"): 16_383_747_763,
-                          ("c3_exp32", "decentlam_blocked"): 16_383_700_000,
+                          ("c3_exp32", "decentlam_blocked"): 16_383_742_345,
                           ("c5_onepeer64_lsq", "local_grad_lsq"): 4_342_500_000}
 
 
