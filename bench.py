@@ -271,6 +271,35 @@ def bench_blocked(P, workloads, name, algo, steps, warmup, bw=8192, calibration_
             "steps_per_s": round(1e3 / wall_ms, 1)}
 
 
+def bench_lean(P, workloads, name, steps, warmup, bw=8192):
+    """The leanest iteration on offer: momentum-free DecentLaM (state x^k, x^{k-1}), bf16 gradients,
+    blocked layout: 14 bytes per node-element."""
+    import numpy as np
+    import torch
+
+    w = workloads.get(name)
+    d = workloads.generate.dim(w)
+    nb = (d + bw - 1) // bw
+    topo = P.topology_build(w.topo, w.n)
+    gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
+    gen = torch.Generator(device="cuda").manual_seed(workloads.BASE_SEED % (2 ** 31))
+    bufs = [torch.empty((nb, w.n, bw), dtype=torch.float32, device="cuda").normal_(generator=gen)]
+    bufs.append(bufs[0].clone())
+    g = torch.empty((nb, w.n, bw), dtype=torch.float32, device="cuda").normal_(generator=gen).to(torch.bfloat16)
+
+    def step(k):
+        P.decentlam_step_xprev_ex(bufs[k % 2], bufs[(k + 1) % 2], g, topo, gamma, beta, k, d=d)
+
+    _, kern_ms = time_launches(step, steps, warmup)
+    nbytes = 14 * w.n * d
+    del bufs, g
+    torch.cuda.empty_cache()
+    return {"kernel_ms": round(kern_ms, 4), "bytes_per_node_element": 14, "block_columns": bw,
+            "GBps": round(nbytes / (kern_ms * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(nbytes / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "steps_per_s": round(1e3 / kern_ms, 1)}
+
+
 def bench_g16(P, workloads, name, steps, warmup, dtype_name="bfloat16"):
     """DecentLaM step with 16-bit gradients (x, m fp32): 18 bytes per node-element."""
     import numpy as np
@@ -491,6 +520,8 @@ def main():
                                                                   args.warmup)
         extras["dmsgd_step_blocked_c3_exp32"] = bench_blocked(P, workloads, "c3_exp32", "dmsgd", args.steps,
                                                               args.warmup)
+        extras["decentlam_step_xprev_bf16_blocked_c3_exp32"] = bench_lean(P, workloads, "c3_exp32", args.steps,
+                                                                          args.warmup)
         extras["decentlam_step_g16_bf16_c3_exp32"] = bench_g16(P, workloads, "c3_exp32", args.steps, args.warmup)
         extras["decentlam_step_multi_norms_c4_ring16_ragged"] = bench_multi(P, workloads, "c4_ring16_ragged",
                                                                              args.steps, args.warmup)

@@ -53,6 +53,13 @@ typedef enum {
     DL_TOPO_BIPARTITE_MATCH = 5 /* per phase a seeded random perfect matching (topology_build_ex)      */
 } dl_topo_kind;             /* tau = floor(log2(n-1)) + 1; all indices mod n */
 
+/* Storage format of the gradient operand of the *_g16, *_multi and *_ex calls. */
+typedef enum {
+    DL_GRAD_F32 = 0,
+    DL_GRAD_BF16 = 1,   /* upper 16 bits of the fp32 pattern */
+    DL_GRAD_F16 = 2     /* IEEE binary16                      */
+} dl_grad_format;
+
 /* properties reported by topology_build (every phase has the property) */
 #define DL_FLAG_ROW_STOCHASTIC 1u /* |sum_j w_ij - 1| <= 1e-6 for all i  (Assumption A.3: W 1 = 1) */
 #define DL_FLAG_COL_STOCHASTIC 2u /* |sum_i w_ij - 1| <= 1e-6 for all j                            */
@@ -189,6 +196,37 @@ int dmsgd_step_blocked(float* x, float* m, const float* g,
                        float gamma, float beta, int64_t k, void* stream);
 
 /*
+ * decentlam_step_ex, dmsgd_step_ex, decentlam_step_xprev_ex -- the general forms: any combination of
+ * layout (row-major or blocked) and gradient format.  The simpler calls above are special cases.
+ *
+ *   layout->bw == 0   row-major arrays: x, m with row stride layout->ld, g with row stride
+ *                     layout->ldg (elements of its format; < 0 means "same as ld").
+ *   layout->bw  > 0   blocked layout with blocks of bw columns for all three arrays (ld, ldg ignored).
+ *   layout->g_format  a dl_grad_format; g points to elements of that format.
+ * decentlam_step_xprev_ex with 16-bit gradients in the blocked layout is the leanest iteration the
+ * library offers: 14 bytes per node-element (read x^k, x^{k-1} fp32 and g 16-bit, write x^{k+1}).
+ * Errors as the special cases; a NULL layout or bw < 0 is DL_EINVAL.
+ */
+typedef struct {
+    int32_t g_format;
+    int64_t ld;
+    int64_t ldg;
+    int64_t bw;
+} dl_layout;
+int decentlam_step_ex(float* x, float* m, const void* g,
+                      int32_t n, int64_t d, const dl_layout* layout,
+                      const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                      float gamma, float beta, int64_t k, void* stream);
+int dmsgd_step_ex(float* x, float* m, const void* g,
+                  int32_t n, int64_t d, const dl_layout* layout,
+                  const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                  float gamma, float beta, int64_t k, void* stream);
+int decentlam_step_xprev_ex(const float* x, float* x_prev, const void* g,
+                            int32_t n, int64_t d, const dl_layout* layout,
+                            const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                            float gamma, float gamma_prev, float beta, int64_t k, void* stream);
+
+/*
  * awc_dmsgd_step, da_dmsgd_step -- two sibling methods of the paper's comparison that reuse the
  * same fused gather-mix pass (Sec. "Experiments", list of compared algorithms).  The paper
  * describes them in a sentence each and prints no recursion; the library implements this reading:
@@ -208,13 +246,6 @@ int da_dmsgd_step(float* x, float* m, const float* g,
                   int32_t n, int64_t d, int64_t ld,
                   const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
                   float gamma, float beta, int64_t k, void* stream);
-
-/* Storage format of the gradient operand of the *_g16 and *_multi calls. */
-typedef enum {
-    DL_GRAD_F32 = 0,
-    DL_GRAD_BF16 = 1,   /* upper 16 bits of the fp32 pattern */
-    DL_GRAD_F16 = 2     /* IEEE binary16                      */
-} dl_grad_format;
 
 /*
  * decentlam_step_g16, dmsgd_step_g16 -- Algorithm 2 / Algorithm 1 with the gradients held in a

@@ -32,9 +32,14 @@ DL_GRAD_F32, DL_GRAD_BF16, DL_GRAD_F16 = 0, 1, 2
 
 EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decentlam_step", "decentlam_step_xprev",
            "dmsgd_step", "dsgd_step", "awc_dmsgd_step", "da_dmsgd_step", "decentlam_step_blocked",
-           "dmsgd_step_blocked", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
+           "dmsgd_step_blocked", "decentlam_step_ex", "dmsgd_step_ex", "decentlam_step_xprev_ex", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
            "dmsgd_step_multi", "decentlam_step_multi_workspace", "local_grad_lsq", "local_grad_lsq_rows",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
+
+
+class Layout(ctypes.Structure):
+    """dl_layout of include/decentlam.h."""
+    _fields_ = [("g_format", ctypes.c_int32), ("ld", ctypes.c_int64), ("ldg", ctypes.c_int64), ("bw", ctypes.c_int64)]
 
 
 class DecentLamError(RuntimeError):
@@ -78,6 +83,15 @@ def _load() -> ctypes.CDLL:
                                        ctypes.c_int32, ctypes.POINTER(ctypes.c_int64), vp, vp, ctypes.c_size_t,
                                        i32p, i32p, f32p, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
                                        ctypes.c_int64, vp]
+    layp = ctypes.POINTER(Layout)
+    for name in ("decentlam_step_ex", "dmsgd_step_ex"):
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, layp, i32p, i32p, f32p,
+                                       ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_int64, vp]
+    lib.decentlam_step_xprev_ex.restype = ctypes.c_int
+    lib.decentlam_step_xprev_ex.argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, layp, i32p, i32p, f32p,
+                                            ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                            ctypes.c_int64, vp]
     lib.decentlam_step_multi_workspace.restype = ctypes.c_size_t
     lib.decentlam_step_multi_workspace.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32]
     lib.decentlam_step_xprev.restype = ctypes.c_int
@@ -250,6 +264,56 @@ def decentlam_step_blocked(x, m, g, d: int, topo: Topology, gamma: float, beta: 
 def dmsgd_step_blocked(x, m, g, d: int, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):
     """dmsgd_step on arrays in the blocked layout: tensors of shape (ceil(d / bw), n, bw)."""
     _step_blocked(_lib.dmsgd_step_blocked, x, m, g, d, topo, gamma, beta, k, stream)
+
+
+def _step_ex(fn, x, m, g, d, topo, gamma, beta, k, stream, gamma_prev=None):
+    """Marshal the general forms: 2-D tensors (n, d) are row-major arrays, 3-D tensors (blocks, n, bw)
+    are arrays in the blocked layout (then `d` says where the last block ends); g may be 16-bit."""
+    if g.dtype not in _GRAD_FORMAT:
+        raise TypeError("g: need a float32, bfloat16 or float16 tensor")
+    for name, t in (("x", x), ("m", m)):
+        if t.dtype != torch.float32 or not t.is_cuda:
+            raise TypeError(f"{name}: need a float32 device tensor")
+    if x.dim() == 3:
+        if not (x.is_contiguous() and m.is_contiguous() and g.is_contiguous()) or x.shape != m.shape or x.shape != g.shape:
+            raise TypeError("blocked layout: x, m and g must be contiguous (blocks, n, bw) tensors of one shape")
+        nb, n, bw = x.shape
+        if d is None or not ((nb - 1) * bw < d <= nb * bw):
+            raise DecentLamError(DL_EINVAL, f"d = {d} does not end in the last of {nb} blocks of {bw} columns")
+        lay = Layout(_GRAD_FORMAT[g.dtype], 0, 0, bw)
+    else:
+        px, n, cols, ld = _matrix_args(x, "x")
+        pm, nm, dm, ldm = _matrix_args(m, "m")
+        if (nm, dm, ldm) != (n, cols, ld):
+            raise TypeError("x and m must share shape and row stride")
+        _, fmt, ldg = _grad_args(g, n, cols)
+        d = cols
+        lay = Layout(fmt, ld, ldg, 0)
+    if topo.n != n:
+        raise DecentLamError(DL_ETOPO, f"topology has {topo.n} nodes, arrays have {n} rows")
+    st = _stream() if stream is None else stream
+    if gamma_prev is None:
+        _check(fn(x.data_ptr(), m.data_ptr(), g.data_ptr(), n, d, ctypes.byref(lay), *topo._args(), gamma, beta, k, st))
+    else:
+        _check(fn(x.data_ptr(), m.data_ptr(), g.data_ptr(), n, d, ctypes.byref(lay), *topo._args(), gamma,
+                  gamma_prev, beta, k, st))
+
+
+def decentlam_step_ex(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, d=None, stream=None):
+    """General DecentLaM step: row-major (2-D tensors) or blocked (3-D tensors, pass d), fp32 or 16-bit g."""
+    _step_ex(_lib.decentlam_step_ex, x, m, g, d, topo, gamma, beta, k, stream)
+
+
+def dmsgd_step_ex(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, d=None, stream=None):
+    """General DmSGD step, see decentlam_step_ex."""
+    _step_ex(_lib.dmsgd_step_ex, x, m, g, d, topo, gamma, beta, k, stream)
+
+
+def decentlam_step_xprev_ex(x, x_prev, g, topo: Topology, gamma: float, beta: float, k: int = 0,
+                            gamma_prev: float | None = None, d=None, stream=None):
+    """General momentum-free DecentLaM step (x_prev is overwritten with x^{k+1}), see decentlam_step_ex."""
+    _step_ex(_lib.decentlam_step_xprev_ex, x, x_prev, g, d, topo, gamma, beta, k, stream,
+             gamma if gamma_prev is None else gamma_prev)
 
 
 def awc_dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):

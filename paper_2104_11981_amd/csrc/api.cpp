@@ -240,10 +240,15 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int
 // row-major n x bw matrix (row stride bw), blocks back to back: element (i, c) lives at
 // ((c / bw) * n + i) * bw + c % bw.  The full blocks are one batched launch, a narrower last block
 // is an ordinary row-major problem with ld = bw.
-int blocked_entry(const char* fn, Algo algo, float* x, float* m, const float* g, int32_t n, int64_t d,
+int blocked_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int32_t n, int64_t d,
                   int64_t bw, const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
-                  float gamma, float beta, int64_t k, void* stream) {
+                  float gamma, float beta, int64_t k, void* stream, int g_format = DL_GRAD_F32,
+                  float gamma_prev = 0.0f) {
     clear_error();
+    if (g_format != DL_GRAD_F32 && g_format != DL_GRAD_BF16 && g_format != DL_GRAD_F16)
+        return set_error(DL_EINVAL, "%s: g_format = %d is not a dl_grad_format", fn, g_format);
+    if (algo == ALGO_DECENTLAM_XPREV && (!std::isfinite(gamma_prev) || !(gamma_prev > 0.0f)))
+        return set_error(DL_EINVAL, "%s: gamma_prev = %g must be finite and > 0", fn, static_cast<double>(gamma_prev));
     if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
     if (d < 0) return set_error(DL_EINVAL, "%s: d = %lld, need d >= 0", fn, static_cast<long long>(d));
     if (bw < 1) return set_error(DL_EINVAL, "%s: bw = %lld, need bw >= 1", fn, static_cast<long long>(bw));
@@ -260,25 +265,31 @@ int blocked_entry(const char* fn, Algo algo, float* x, float* m, const float* g,
     if (int rc = pack_phase(fn, n, row_ptr, col_idx, w, static_cast<int32_t>(k % period), &topo)) return rc;
     if (d == 0) return DL_OK;
     if (!x || !m || !g) return set_error(DL_EINVAL, "%s: x, m and g must not be NULL", fn);
-    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(g)) & 3u)
-        return set_error(DL_EINVAL, "%s: x, m and g must be 4-byte aligned", fn);
+    const uintptr_t gbytes = grad_elem_bytes(g_format);
+    if (((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m)) & 3u) ||
+        (reinterpret_cast<uintptr_t>(g) & (gbytes - 1)))
+        return set_error(DL_EINVAL, "%s: x, m and g must be aligned to their element size", fn);
     const int64_t full = d / bw, rest = d % bw;
     const int64_t block = static_cast<int64_t>(n) * bw;
     const int64_t elements = full * block + (rest ? (static_cast<int64_t>(n) - 1) * bw + rest : 0);
     const Span sx = span_of(x, 1, elements, elements), sm = span_of(m, 1, elements, elements),
-               sg = span_of(g, 1, elements, elements);
+               sg = span_of(g, 1, elements, elements, static_cast<int64_t>(gbytes));
     if (overlap(sx, sm) || overlap(sx, sg) || overlap(sm, sg))
         return set_error(DL_EALIAS, "%s: x, m and g must not overlap", fn);
+    double beta_eff = static_cast<double>(beta);
+    if (algo == ALGO_DECENTLAM_XPREV)
+        beta_eff = beta_eff * static_cast<double>(gamma) / static_cast<double>(gamma_prev);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (full > 0) {
-        if (int rc = launch_step(algo, x, m, GradArg{g, DL_GRAD_F32, bw}, n, bw, bw, topo, gamma,
-                                 static_cast<double>(beta), s, nullptr, full, block, block))
+        if (int rc = launch_step(algo, x, m, GradArg{g, g_format, bw}, n, bw, bw, topo, gamma, beta_eff, s,
+                                 nullptr, full, block, block))
             return rc;
     }
     if (rest > 0) {
         const int64_t at = full * block;
-        return launch_step(algo, x + at, m + at, GradArg{g + at, DL_GRAD_F32, bw}, n, rest, bw, topo, gamma,
-                           static_cast<double>(beta), s);
+        const void* g_rest = static_cast<const char*>(g) + static_cast<size_t>(at) * gbytes;
+        return launch_step(algo, x + at, m + at, GradArg{g_rest, g_format, bw}, n, rest, bw, topo, gamma, beta_eff,
+                           s);
     }
     return DL_OK;
 }
@@ -314,6 +325,54 @@ int dmsgd_step_blocked(float* x, float* m, const float* g, int32_t n, int64_t d,
                        float gamma, float beta, int64_t k, void* stream) {
     return dl::blocked_entry("dmsgd_step_blocked", dl::ALGO_DMSGD, x, m, g, n, d, bw, row_ptr, col_idx, w, period,
                              gamma, beta, k, stream);
+}
+
+namespace dl {
+namespace {
+// The general form: layout and gradient format from a dl_layout.
+int ex_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int32_t n, int64_t d,
+             const dl_layout* layout, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
+             int32_t period, float gamma, float gamma_prev, float beta, int64_t k, void* stream) {
+    if (!layout) {
+        clear_error();
+        return set_error(DL_EINVAL, "%s: layout must not be NULL", fn);
+    }
+    if (layout->bw > 0)
+        return blocked_entry(fn, algo, x, m, g, n, d, layout->bw, row_ptr, col_idx, w, period, gamma, beta, k,
+                             stream, layout->g_format, gamma_prev);
+    if (layout->bw < 0) {
+        clear_error();
+        return set_error(DL_EINVAL, "%s: layout.bw = %lld, need >= 0", fn, static_cast<long long>(layout->bw));
+    }
+    StepExtras ex;
+    ex.g_format = layout->g_format;
+    ex.ldg = layout->ldg;
+    return step_entry(fn, algo, x, m, g, n, d, layout->ld, row_ptr, col_idx, w, period, gamma, beta, k, stream,
+                      gamma_prev, ex);
+}
+}  // namespace
+}  // namespace dl
+
+int decentlam_step_ex(float* x, float* m, const void* g, int32_t n, int64_t d, const dl_layout* layout,
+                      const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                      float gamma, float beta, int64_t k, void* stream) {
+    return dl::ex_entry("decentlam_step_ex", dl::ALGO_DECENTLAM, x, m, g, n, d, layout, row_ptr, col_idx, w, period,
+                        gamma, 0.0f, beta, k, stream);
+}
+
+int dmsgd_step_ex(float* x, float* m, const void* g, int32_t n, int64_t d, const dl_layout* layout,
+                  const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                  float gamma, float beta, int64_t k, void* stream) {
+    return dl::ex_entry("dmsgd_step_ex", dl::ALGO_DMSGD, x, m, g, n, d, layout, row_ptr, col_idx, w, period, gamma,
+                        0.0f, beta, k, stream);
+}
+
+int decentlam_step_xprev_ex(const float* x, float* x_prev, const void* g, int32_t n, int64_t d,
+                            const dl_layout* layout, const int32_t* row_ptr, const int32_t* col_idx,
+                            const float* w, int32_t period, float gamma, float gamma_prev, float beta, int64_t k,
+                            void* stream) {
+    return dl::ex_entry("decentlam_step_xprev_ex", dl::ALGO_DECENTLAM_XPREV, const_cast<float*>(x), x_prev, g, n, d,
+                        layout, row_ptr, col_idx, w, period, gamma, gamma_prev, beta, k, stream);
 }
 
 int awc_dmsgd_step(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,

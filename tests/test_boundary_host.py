@@ -332,3 +332,29 @@ def test_blocked_argument_validation():
     assert f(d=100) == P.DL_EINVAL and "NULL" in P.last_error()
     assert f(d=100, x=0x10000, m=0x10000 + 4 * 200, g=0x80000) == P.DL_EALIAS     # m inside x's second block
     assert f(d=100, x=0x10002, m=0x40000, g=0x80000) == P.DL_EINVAL
+
+
+def test_general_step_argument_validation():
+    t = P.topology_build(0, 4)
+
+    def call(fn=P.raw.decentlam_step_ex, lay=None, **kw):
+        layout = P.Layout(*(lay or (P.DL_GRAD_F32, 8, 8, 0)))
+        return fn(kw.get("x"), kw.get("m"), kw.get("g"), 4, kw.get("d", 0), ctypes.byref(layout), *t._args(),
+                  kw.get("gamma", 0.1), 0.9, 0, None)
+
+    assert call() == P.DL_OK
+    assert P.raw.decentlam_step_ex(None, None, None, 4, 0, None, *t._args(), 0.1, 0.9, 0, None) == P.DL_EINVAL
+    assert "layout" in P.last_error()
+    assert call(lay=(P.DL_GRAD_F32, 8, 8, -1)) == P.DL_EINVAL
+    assert call(lay=(7, 8, 8, 0)) == P.DL_EINVAL and "g_format" in P.last_error()
+    assert call(lay=(7, 8, 8, 64)) == P.DL_EINVAL and "g_format" in P.last_error()
+    assert call(d=9) == P.DL_EINVAL                                     # ld < d
+    assert call(d=8, lay=(P.DL_GRAD_BF16, 8, 4, 0)) == P.DL_EINVAL      # ldg < d
+    assert call(d=8, x=0x1000, m=0x2000, g=0x3001, lay=(P.DL_GRAD_BF16, 8, 8, 0)) == P.DL_EINVAL
+    assert call(d=8, x=0x1000, m=0x2000, g=0x1010, lay=(P.DL_GRAD_F16, 8, 8, 64)) == P.DL_EALIAS
+    layout = P.Layout(P.DL_GRAD_F32, 8, 8, 0)
+    f = lambda gp: P.raw.decentlam_step_xprev_ex(None, None, None, 4, 0, ctypes.byref(layout), *t._args(), 0.1, gp,
+                                                 0.9, 0, None)
+    assert f(0.1) == P.DL_OK and f(0.0) == P.DL_EINVAL
+    layout.bw = 64
+    assert f(0.1) == P.DL_OK and f(-1.0) == P.DL_EINVAL and "gamma_prev" in P.last_error()

@@ -1,0 +1,131 @@
+"""GPU parity of the general step calls (`*_step_ex`): every combination of layout (row-major,
+blocked) and gradient format (fp32, bf16, fp16) for DecentLaM, DmSGD and the momentum-free DecentLaM,
+against the oracle; and bit for bit against the special-case calls where one exists."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from test_gpu_parity import P, check_elementwise, dev, topo_pair  # noqa: E402,F401
+
+DT = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+
+
+def make_grad(oracle, rng, n, d, fmt):
+    """(device tensor in the given format, float64 values the oracle uses)."""
+    g32 = rng.standard_normal((n, d)).astype(np.float32)
+    if fmt == "f32":
+        return torch.from_numpy(g32).cuda(), g32.astype(np.float64)
+    t = torch.from_numpy(g32).to(DT[fmt])
+    bits = t.view(torch.int16).numpy().view(np.uint16)
+    return t.cuda(), oracle.widen16(bits, fmt)
+
+
+CASES = [
+    # kind, n, d, bw (0 = row-major), steps
+    (1, 32, 5000, 0, 3),
+    (1, 32, 20000, 8192, 3),
+    (0, 16, 2051, 256, 3),
+    (2, 8, 1000, 64, 6),
+    (3, 64, 700, 512, 2),
+    (0, 100, 333, 128, 2),
+    (4, 12, 515, 0, 3),
+]
+
+
+@pytest.mark.parametrize("fmt", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("algo", ["decentlam", "dmsgd", "decentlam_xprev"])
+@pytest.mark.parametrize("kind,n,d,bw,steps", CASES)
+def test_general_step_matches_oracle(P, oracle, fmt, algo, kind, n, d, bw, steps):
+    gamma, beta = float(np.float32(0.05)), float(np.float32(0.9))
+    topo, otopo = topo_pair(P, oracle, kind, n)
+    rng = np.random.default_rng(17 * n + d + bw)
+    x0 = rng.standard_normal((n, d)).astype(np.float32)
+    lay = (lambda t: P.to_blocked(t, bw)) if bw else (lambda t: t.clone())
+    unlay = (lambda t: P.from_blocked(t, d)) if bw else (lambda t: t)
+    x = lay(dev(x0))
+    second = lay(dev(x0)) if algo == "decentlam_xprev" else torch.zeros_like(x)       # x^{-1} = x^0, or m^0 = 0
+    xs, ss = x0.astype(np.float64), (x0.astype(np.float64) if algo == "decentlam_xprev" else np.zeros((n, d)))
+    r32 = lambda a: a.astype(np.float32).astype(np.float64)
+    for k in range(steps):
+        gd, gv = make_grad(oracle, rng, n, d, fmt)
+        g = lay(gd)
+        kw = dict(d=d) if bw else {}
+        if algo == "decentlam_xprev":
+            P.decentlam_step_xprev_ex(x, second, g, topo, gamma, beta, k, **kw)
+            xn = r32(oracle.decentlam_xprev_step(xs, ss, gv, otopo, gamma, beta, k))
+            check_elementwise(unlay(second).cpu().numpy(), xn, f"x after iteration {k}")
+            x, second = second, x
+            xs, ss = xn, xs
+        else:
+            getattr(P, algo + "_step_ex")(x, second, g, topo, gamma, beta, k, **kw)
+            xs, ss = (r32(a) for a in oracle.STEP[algo](xs, ss, gv, otopo, gamma, beta, k))
+            check_elementwise(unlay(x).cpu().numpy(), xs, f"x after iteration {k}")
+            check_elementwise(unlay(second).cpu().numpy(), ss, f"m after iteration {k}")
+
+
+def test_general_forms_reproduce_the_special_cases(P):
+    n, d, bw = 32, 20000, 8192
+    topo = P.topology_build(P.DL_TOPO_EXP_STATIC, n)
+    gen = torch.Generator(device="cuda").manual_seed(4)
+    x0 = torch.randn((n, d), device="cuda", generator=gen)
+    g = torch.randn((n, d), device="cuda", generator=gen)
+    g16 = g.to(torch.bfloat16)
+    # row-major fp32
+    xa, ma, xb, mb = x0.clone(), torch.zeros_like(x0), x0.clone(), torch.zeros_like(x0)
+    P.decentlam_step(xa, ma, g, topo, 0.1, 0.9, 0)
+    P.decentlam_step_ex(xb, mb, g, topo, 0.1, 0.9, 0)
+    assert torch.equal(xa, xb) and torch.equal(ma, mb)
+    # row-major bf16
+    xa, ma, xb, mb = x0.clone(), torch.zeros_like(x0), x0.clone(), torch.zeros_like(x0)
+    P.dmsgd_step_g16(xa, ma, g16, topo, 0.1, 0.9, 0)
+    P.dmsgd_step_ex(xb, mb, g16, topo, 0.1, 0.9, 0)
+    assert torch.equal(xa, xb) and torch.equal(ma, mb)
+    # blocked fp32
+    xa, ma = P.to_blocked(x0, bw), P.to_blocked(torch.zeros_like(x0), bw)
+    xb, mb = xa.clone(), ma.clone()
+    gb = P.to_blocked(g, bw)
+    P.decentlam_step_blocked(xa, ma, gb, d, topo, 0.1, 0.9, 0)
+    P.decentlam_step_ex(xb, mb, gb, topo, 0.1, 0.9, 0, d=d)
+    assert torch.equal(xa, xb) and torch.equal(ma, mb)
+    # momentum-free, row-major fp32
+    ca, pa, cb, pb = x0.clone(), x0.clone(), x0.clone(), x0.clone()
+    P.decentlam_step_xprev(ca, pa, g, topo, 0.1, 0.9, 0, gamma_prev=0.05)
+    P.decentlam_step_xprev_ex(cb, pb, g, topo, 0.1, 0.9, 0, gamma_prev=0.05)
+    assert torch.equal(pa, pb)
+    torch.cuda.synchronize()
+
+
+def test_leanest_iteration_at_the_headline_size(P, oracle):
+    """n = 32, d = 25.6 M, blocked layout, bf16 gradients, momentum-free form (14 B per node-element):
+    sampled columns against the oracle over several iterations."""
+    import workloads
+    from test_gpu_fullsize import sample_columns
+
+    w = workloads.get("c3_exp32")
+    d, n, bw = w.d, w.n, 8192
+    nb = d // bw
+    topo, otopo = P.topology_build(1, n), oracle.topology(1, n)
+    gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
+    cols = sample_columns(d, seed=3, blocks=24)
+    flat = (torch.from_numpy((cols // bw) * (n * bw) + cols % bw).cuda().view(1, -1)
+            + torch.arange(n, device="cuda").view(n, 1) * bw)
+    gen = torch.Generator(device="cuda").manual_seed(14)
+    cur = torch.empty((nb, n, bw), dtype=torch.float32, device="cuda").normal_(generator=gen)
+    prev = cur.clone()
+    g32 = torch.empty_like(cur)
+    g = torch.empty((nb, n, bw), dtype=torch.bfloat16, device="cuda")
+    xc = cur.view(-1)[flat].cpu().numpy().astype(np.float64)
+    xp = xc.copy()
+    for k in range(5):
+        g32.normal_(generator=gen)
+        g.copy_(g32)
+        bits = g.view(-1)[flat].cpu().view(torch.int16).numpy().view(np.uint16)
+        P.decentlam_step_xprev_ex(cur, prev, g, topo, gamma, beta, k, d=d)
+        xn = oracle.decentlam_xprev_step(xc, xp, oracle.widen16(bits, "bf16"), otopo, gamma, beta, k)
+        xn = xn.astype(np.float32).astype(np.float64)
+        check_elementwise(prev.view(-1)[flat].cpu().numpy(), xn, f"x, iteration {k}")
+        cur, prev = prev, cur
+        xc, xp = xn, xc
