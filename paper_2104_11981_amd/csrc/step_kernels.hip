@@ -182,6 +182,24 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
     }
 }
 
+// After the barrier all waves of a workgroup gather, compute and store at the same moment, and the
+// memory system sees the workgroup's 64 KiB of stores as one burst.  Letting the odd-numbered waves
+// (SIMDs 1 and 3) begin that phase 32-48 x 64 cycles later measured 4-8 % faster wherever the kernel
+// is bound by the mix of reads and writes: 16-byte lanes up to 32 nodes, every form that moves 14 B
+// per node-element or more.  Measured neutral or harmful, hence off: DSGD (12 B), 64 nodes and
+// more, the 16-wave single-row shape with less than 20 B, the variants with per-tensor sums.
+// A hand-over through a second barrier (odd waves wait for the even ones) was tried instead of the
+// fixed pause: better for DecentLaM at 32 nodes, worse everywhere else.
+template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
+constexpr int stagger_units() {
+    if (NORMS || VEC != 4 || ALGO == ALGO_DSGD || ALGO == ALGO_DA_DMSGD) return 0;
+    const bool twenty_bytes = ALGO != ALGO_DECENTLAM_XPREV && GF == DL_GRAD_F32;
+    if (RPT == 2 && WAVES == 16) return twenty_bytes ? 48 : 32;
+    if (RPT == 1 && WAVES == 16) return twenty_bytes ? 32 : 0;
+    if (RPT == 1 && WAVES <= 8) return 32;
+    return 0;
+}
+
 // VEC    columns per lane (width of the global accesses: 4, 8 or 16 bytes)
 // RPT    rows per thread; WAVES wavefronts per workgroup: the kernel covers n <= WAVES * RPT nodes
 // ALGO   ALGO_DECENTLAM, ALGO_DMSGD, ALGO_DSGD (x <- W (x - gamma g); m is not touched) or
@@ -306,6 +324,11 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
         }
     }
     __syncthreads();
+    // Odd waves start their second phase a little later (see stagger_units).
+    constexpr int kStagger = stagger_units<VEC, RPT, WAVES, ALGO, GF, NORMS>();
+    if constexpr (kStagger > 0) {
+        if (wave & 1) __builtin_amdgcn_s_sleep(kStagger);
+    }
 
     // ---- phase 2: gather-mix from LDS, finish the update, store in place
     const double* tile_at_lane = lds + lane;
