@@ -516,8 +516,17 @@ def main():
             extras[f"{algo}_step_{name}"] = {"kernel_ms": round(k2, 4), "GBps": round(b2 / (k2 * 1e-3) / 1e9, 1),
                                              "frac_of_hbm_peak": round(b2 / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         extras["decentlam_step_xprev_c3_exp32"] = bench_xprev(P, workloads, "c3_exp32", args.steps, args.warmup)
-        extras["decentlam_step_blocked_c3_exp32"] = bench_blocked(P, workloads, "c3_exp32", "decentlam", args.steps,
-                                                                  args.warmup)
+        blk = bench_blocked(P, workloads, "c3_exp32", "decentlam", args.steps, args.warmup)
+        extras["decentlam_step_blocked_c3_exp32"] = blk
+        if (args.workload, args.algo) == ("c3_exp32", "decentlam"):
+            # the same workload through decentlam_step_blocked (arrays stored in blocks of 8192 columns):
+            # same arithmetic, same bytes, no address-translation misses
+            out["roofline_blocked_layout"] = {
+                "bound": "hbm", "achieved": blk["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": blk["frac_of_hbm_peak"], "traffic": MEASURED_TRAFFIC_BYTES.get(("c3_exp32", "decentlam_blocked")),
+                "kernel": "k_step", "kernel_ms": blk["kernel_ms"], "steps_per_s": blk["steps_per_s"],
+                "algorithmic_bytes_per_launch": bytes_per_step, "entry_point": "decentlam_step_blocked",
+                "block_columns": blk["block_columns"]}
         extras["dmsgd_step_blocked_c3_exp32"] = bench_blocked(P, workloads, "c3_exp32", "dmsgd", args.steps,
                                                               args.warmup)
         extras["decentlam_step_xprev_bf16_blocked_c3_exp32"] = bench_lean(P, workloads, "c3_exp32", args.steps,
