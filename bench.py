@@ -535,6 +535,11 @@ def main():
         extras["decentlam_step_multi_norms_c4_ring16_ragged"] = bench_multi(P, workloads, "c4_ring16_ragged",
                                                                              args.steps, args.warmup)
         extras["local_grad_lsq_c5"] = bench_lsq(P, workloads, "c5_onepeer64_lsq", args.steps, args.warmup)
+        # the small least-squares workloads are cache-resident and latency-bound: microseconds only
+        for small in ("c2_onepeer8_b32", "c2_onepeer8_b1024"):
+            r2 = bench_lsq(P, workloads, small, 200, 20)
+            extras[f"{small}_us"] = {"grad_plus_step": round(r2["ms_per_iteration_grad_plus_step"] * 1e3, 2),
+                                     "grad": round(r2["grad_kernel_ms"] * 1e3, 2)}
         # the small workloads are launch-latency bound: report microseconds per call
         w1 = workloads.get("c1_ring4")
         _, _, _, _, _, k1 = bench_step(P, workloads, "c1_ring4", "decentlam", 200, 20)

@@ -129,3 +129,58 @@ def test_leanest_iteration_at_the_headline_size(P, oracle):
         check_elementwise(prev.view(-1)[flat].cpu().numpy(), xn, f"x, iteration {k}")
         cur, prev = prev, cur
         xc, xp = xn, xc
+
+
+def test_multi_tensor_and_general_calls_are_capturable_in_a_hip_graph(P):
+    """decentlam_step_multi with per-tensor sums (tile records + final pass, the tensor table passed
+    as kernel arguments) and the general call in the blocked layout with bf16 gradients only enqueue
+    kernels: captured once, replayed five times, each replay compared with eager execution.  n = 32
+    uses more than 48 KiB of LDS per workgroup, so the capture also covers the launch path that raises
+    the kernel's dynamic LDS limit."""
+    n, bw = 32, 256
+    topo = P.topology_build(P.DL_TOPO_RING, n)
+    sizes = [300, 1, 0, 63, 64, 65, 2000, 2, 700]
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    d, T = int(offsets[-1]), len(sizes)
+    gen = torch.Generator(device="cuda").manual_seed(8)
+    x0 = torch.randn((n, d), device="cuda", generator=gen)
+    g = torch.randn((n, d), device="cuda", generator=gen)
+    xb0, gb = P.to_blocked(x0, bw), P.to_blocked(g, bw).to(torch.bfloat16)
+    ws = torch.empty(P.decentlam_step_multi_workspace(n, d, T), dtype=torch.uint8, device="cuda")
+
+    def work(x, m, norms, cur, prev):
+        for k in range(2):
+            P.decentlam_step_multi(x, m, g, offsets, topo, 0.05, 0.9, k, norms=norms, workspace=ws)
+        P.decentlam_step_xprev_ex(cur, prev, gb, topo, 0.05, 0.9, 0, d=d)
+        P.decentlam_step_xprev_ex(prev, cur, gb, topo, 0.05, 0.9, 1, d=d)
+
+    def fresh():
+        return (x0.clone(), torch.zeros_like(x0), torch.zeros((T, n, 3), dtype=torch.float64, device="cuda"),
+                xb0.clone(), xb0.clone())
+
+    eager_state = fresh()
+    eager = []
+    for _ in range(5):
+        work(*eager_state)
+        eager.append([t.clone() for t in eager_state])
+    state = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        work(*state)                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    for t, f in zip(state, fresh()):
+        t.copy_(f)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        work(*state)
+    for t, f in zip(state, fresh()):
+        t.copy_(f)
+    scratch = torch.zeros(1000, device="cuda")
+    for r in range(5):
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip(state, eager[r]):
+            assert torch.equal(got, want), f"replay {r} differs from eager"
+        scratch.add_(1.0)
+        torch.cuda.synchronize()
