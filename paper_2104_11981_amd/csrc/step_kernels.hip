@@ -8,87 +8,30 @@
 //   phase 1  every wave streams whole rows of the tile (row index is wave-uniform):
 //            x_j, g_j, m_j come in with VEC*4-byte non-temporal loads, the local
 //            pre-step (u_j = x_j - gamma g_j for DecentLaM, h_j = x_j - gamma (beta m_j + g_j)
-//            for DmSGD) is evaluated in fp64 and parked in LDS as fp64; meanwhile the
-//            neighbour list of W is unpacked from the kernel arguments into an LDS
-//            table of (fp64 weight, LDS row offset) pairs;
-//   phase 2  after one barrier, row i gathers its |N_i| neighbour rows from LDS in
-//            list order, a few neighbours at a time so that the table and tile reads of
-//            a group are in flight together, finishes the update in
-//            fp64 and stores fp32 in place with non-temporal stores.
+//            for DmSGD) is evaluated in fp64 and parked in LDS as fp64 (each tile row as VEC
+//            planes of 64 doubles: bank-conflict free); meanwhile the neighbour list of W is
+//            unpacked from the kernel arguments into an LDS table of (fp64 weight, LDS row
+//            offset) pairs;
+//   phase 2  after one barrier (and, for some shapes, a short pause of the odd-numbered waves
+//            that spreads the workgroup's stores), row i gathers its |N_i| neighbour rows from
+//            LDS in list order, finishes the update in fp64 and stores fp32 in place with
+//            non-temporal stores.
 //
 // HBM traffic is exactly read x, m, g + write x, m = 20 bytes per node-element,
 // independent of the node degree; updating in place is race-free because no
-// other workgroup touches these columns.  The gather costs no time next to the
-// streaming (measured: replacing it by a copy of the own row does not speed the
-// kernel up), and the non-temporal accesses are worth about 5 %.
+// other workgroup touches these columns.
 //
-// Two optional extras share the kernel: the gradient may be stored as bf16 or fp16 (widened exactly
-// on load: 18 bytes per node-element), and a launch may accumulate per-tensor sums of squares of
-// g, the new m and the new x for a table of tensors packed along the columns.
+// The same template serves DSGD, the momentum-free form of DecentLaM, AWC-DmSGD and DA-DmSGD, bf16 or
+// fp16 gradients (widened exactly on load), per-tile sums of squares of g, the new m and the new x
+// (per-tensor norms are finished in norms_kernels.hip), and launches over "batches" (the blocks of the
+// blocked layout).
+#include "device_util.hpp"
 #include "internal.hpp"
 
 namespace dl {
 namespace {
 
-typedef float vf2 __attribute__((ext_vector_type(2)));
-typedef float vf4 __attribute__((ext_vector_type(4)));
-
-// Streaming accesses: every byte is touched once per launch, so mark them non-temporal.
-template <int VEC>
-__device__ __forceinline__ void load_vec(const float* __restrict__ p, float (&v)[VEC]) {
-    if constexpr (VEC == 4) {
-        const vf4 t = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(p));
-        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-    } else if constexpr (VEC == 2) {
-        const vf2 t = __builtin_nontemporal_load(reinterpret_cast<const vf2*>(p));
-        v[0] = t.x; v[1] = t.y;
-    } else {
-        v[0] = __builtin_nontemporal_load(p);
-    }
-}
-
-template <int VEC>
-__device__ __forceinline__ void store_vec(float* __restrict__ p, const float (&v)[VEC]) {
-    if constexpr (VEC == 4) {
-        vf4 t; t.x = v[0]; t.y = v[1]; t.z = v[2]; t.w = v[3];
-        __builtin_nontemporal_store(t, reinterpret_cast<vf4*>(p));
-    } else if constexpr (VEC == 2) {
-        vf2 t; t.x = v[0]; t.y = v[1];
-        __builtin_nontemporal_store(t, reinterpret_cast<vf2*>(p));
-    } else {
-        __builtin_nontemporal_store(v[0], p);
-    }
-}
-
-// Gradient element types by dl_grad_format; 16-bit values widen to fp32 exactly.
-template <int GF> struct GradElem { using type = float; };
-template <> struct GradElem<DL_GRAD_BF16> { using type = uint16_t; };
-template <> struct GradElem<DL_GRAD_F16> { using type = _Float16; };
-
-template <int VEC, int GF>
-__device__ __forceinline__ void load_grad(const typename GradElem<GF>::type* __restrict__ p, float (&v)[VEC]) {
-    if constexpr (GF == DL_GRAD_F32) {
-        load_vec<VEC>(p, v);
-    } else {
-        using E = typename GradElem<GF>::type;
-        E raw[VEC];
-        if constexpr (VEC == 1) {
-            raw[0] = __builtin_nontemporal_load(p);
-        } else {
-            typedef E vec_t __attribute__((ext_vector_type(VEC)));
-            const vec_t t = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(p));
-#pragma unroll
-            for (int k = 0; k < VEC; ++k) raw[k] = t[k];
-        }
-#pragma unroll
-        for (int k = 0; k < VEC; ++k) {
-            if constexpr (GF == DL_GRAD_BF16)   // bf16 is the upper half of the fp32 pattern
-                v[k] = __builtin_bit_cast(float, static_cast<uint32_t>(raw[k]) << 16);
-            else
-                v[k] = static_cast<float>(raw[k]);
-        }
-    }
-}
+using namespace dev;
 
 // A launch may cover `count` equally shaped sub-problems ("batches": the blocks of the blocked
 // layout): consecutive workgroups walk the tiles of batch 0, then batch 1, ...
@@ -103,49 +46,6 @@ struct NormArgs {
     double* partial;
     int64_t tile0;   // record index of this launch's tile 0
 };
-
-// Cross-lane exchange of a double on the data-parallel-primitive network (no LDS traffic).
-template <int CTRL>
-__device__ __forceinline__ double dpp_f64(double v) {
-    const uint64_t b = __builtin_bit_cast(uint64_t, v);
-    const int lo = __builtin_amdgcn_update_dpp(0, static_cast<int>(b), CTRL, 0xF, 0xF, true);
-    const int hi = __builtin_amdgcn_update_dpp(0, static_cast<int>(b >> 32), CTRL, 0xF, 0xF, true);
-    return __builtin_bit_cast(double, (static_cast<uint64_t>(static_cast<uint32_t>(hi)) << 32) |
-                                          static_cast<uint32_t>(lo));
-}
-
-// Sums over the 64 lanes in a fixed order, the result in every lane: butterfly steps inside each
-// row of 16 lanes on the primitive network (swap inside pairs, swap pairs inside quads, mirror
-// inside 8, mirror inside 16), then two exchanges between the four rows.
-__device__ __forceinline__ double wave_sum(double v) {
-    v += dpp_f64<0xB1>(v);    // quad_perm [1,0,3,2]
-    v += dpp_f64<0x4E>(v);    // quad_perm [2,3,0,1]
-    v += dpp_f64<0x141>(v);   // row_half_mirror
-    v += dpp_f64<0x140>(v);   // row_mirror
-    v += __shfl_xor(v, 16, 64);
-    v += __shfl_xor(v, 32, 64);
-    return v;
-}
-// Two sums for little more than the price of one: after the first step even lanes carry on with a,
-// odd lanes with b, and every later step (swap pairs inside quads, rotate a row by 4 and by 8,
-// exchange rows) keeps the parity of the lane.  Even lanes return sum(a), odd lanes sum(b).
-__device__ __forceinline__ double wave_sum2(double a, double b, int lane) {
-    a += dpp_f64<0xB1>(a);
-    b += dpp_f64<0xB1>(b);
-    double v = (lane & 1) ? b : a;
-    v += dpp_f64<0x4E>(v);    // quad_perm [2,3,0,1]
-    v += dpp_f64<0x124>(v);   // row_ror:4
-    v += dpp_f64<0x128>(v);   // row_ror:8
-    v += __shfl_xor(v, 16, 64);
-    v += __shfl_xor(v, 32, 64);
-    return v;
-}
-__device__ __forceinline__ double uniform_f64(double v) {   // lane 0's value as a scalar
-    const uint64_t b = __builtin_bit_cast(uint64_t, v);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<int>(b));
-    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<int>(b >> 32));
-    return __builtin_bit_cast(double, (static_cast<uint64_t>(hi) << 32) | lo);
-}
 
 // Position of a lane's v-th column inside a row of the LDS tile, in doubles: a row is kept as VEC
 // planes of 64 doubles (column v of every lane), so that every LDS access of a wave touches 64
@@ -587,106 +487,6 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
     if (int rc = run(1, 0, head)) return rc;        // columns are independent, so the peeled
     if (int rc = run(1, head + body, tail)) return rc;  // head and tail are separate launches
     return DL_OK;
-}
-
-// ---- per-tensor sums: final pass ---------------------------------------------------------------
-namespace {
-
-constexpr int kChunk = 440;   // tensors per final-pass launch (their offsets travel as kernel arguments)
-struct OffsetChunk {
-    int64_t v[kChunk + 1];    // column offsets relative to the first column of the step
-};
-struct FinishArgs {
-    NormGrid grid[kMaxNormGrids];
-    int grids;
-};
-
-// One workgroup per (tensor, node).  For every step launch ("grid" of tiles) the tensor's columns
-// split into whole tiles, whose records the step launches wrote, and at most two edge pieces that
-// share a tile with other tensors; the edge pieces are summed from g and from the m and x the step
-// stored.  Fixed order of additions: same inputs, same bits.
-template <int GF>
-__global__ __launch_bounds__(256) void k_norms_finish(const float* __restrict__ x, const float* __restrict__ m,
-                                                      const typename GradElem<GF>::type* __restrict__ g,
-                                                      int64_t ld, int64_t ldg, int n,
-                                                      const double* __restrict__ partial,
-                                                      double* __restrict__ norms, const FinishArgs fa,
-                                                      const OffsetChunk chunk) {
-    const int t = blockIdx.x, i = blockIdx.y;
-    const int64_t lo = chunk.v[t], hi = chunk.v[t + 1];
-    double s[3] = {0.0, 0.0, 0.0};
-    auto columns = [&](int64_t a, int64_t b) {   // element-wise over [a, b)
-        for (int64_t c = a + threadIdx.x; c < b; c += 256) {
-            float gv[1];
-            load_grad<1, GF>(g + static_cast<int64_t>(i) * ldg + c, gv);
-            const double g1 = static_cast<double>(gv[0]);
-            const double m1 = static_cast<double>(m[static_cast<int64_t>(i) * ld + c]);
-            const double x1 = static_cast<double>(x[static_cast<int64_t>(i) * ld + c]);
-            s[0] = __builtin_fma(g1, g1, s[0]);
-            s[1] = __builtin_fma(m1, m1, s[1]);
-            s[2] = __builtin_fma(x1, x1, s[2]);
-        }
-    };
-    for (int k = 0; k < fa.grids; ++k) {
-        const NormGrid gd = fa.grid[k];
-        const int64_t a = lo > gd.col0 ? lo : gd.col0;                          // the tensor inside this grid
-        const int64_t b = hi < gd.col0 + gd.cols ? hi : gd.col0 + gd.cols;
-        if (a >= b) continue;
-        const int64_t tiles = (gd.cols + gd.tc - 1) / gd.tc;
-        const int64_t b0 = (a - gd.col0 + gd.tc - 1) / gd.tc;                   // first tile that starts at or after a
-        const int64_t b1 = b == gd.col0 + gd.cols ? tiles : (b - gd.col0) / gd.tc;  // tiles [b0, b1) lie inside [a, b)
-        if (b0 >= b1) {
-            columns(a, b);
-            continue;
-        }
-        columns(a, gd.col0 + b0 * gd.tc);
-        const int64_t tail = gd.col0 + b1 * gd.tc;
-        if (tail < b) columns(tail, b);
-        for (int64_t q = b0 + threadIdx.x; q < b1; q += 256) {
-            const double* rec = partial + ((gd.tile0 + q) * n + i) * 3;
-            s[0] += rec[0]; s[1] += rec[1]; s[2] += rec[2];
-        }
-    }
-    __shared__ double red[3][256];
-#pragma unroll
-    for (int q = 0; q < 3; ++q) red[q][threadIdx.x] = s[q];
-    __syncthreads();
-    for (int half = 128; half >= 1; half >>= 1) {
-        if (static_cast<int>(threadIdx.x) < half) {
-#pragma unroll
-            for (int q = 0; q < 3; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + half];
-        }
-        __syncthreads();
-    }
-    if (threadIdx.x < 3) norms[(static_cast<int64_t>(t) * n + i) * 3 + threadIdx.x] = red[threadIdx.x][0];
-}
-
-template <int GF>
-int finish_chunks(const NormPlan& plan, const float* x, const float* m, const void* g, int64_t ld, int64_t ldg,
-                  int32_t n, hipStream_t stream) {
-    FinishArgs fa;
-    fa.grids = plan.grids;
-    for (int k = 0; k < kMaxNormGrids; ++k) fa.grid[k] = k < plan.grids ? plan.grid[k] : NormGrid{0, 0, 0, 64};
-    for (int32_t t0 = 0; t0 < plan.num_tensors; t0 += kChunk) {
-        const int32_t count = plan.num_tensors - t0 < kChunk ? plan.num_tensors - t0 : kChunk;
-        OffsetChunk chunk;
-        for (int j = 0; j <= kChunk; ++j)
-            chunk.v[j] = plan.offsets[t0 + (j <= count ? j : count)] - plan.offsets[0];
-        hipLaunchKernelGGL(k_norms_finish<GF>, dim3(static_cast<unsigned>(count), static_cast<unsigned>(n)),
-                           dim3(256), 0, stream, x, m, static_cast<const typename GradElem<GF>::type*>(g), ld, ldg,
-                           n, plan.partial, plan.norms + static_cast<int64_t>(t0) * n * 3, fa, chunk);
-        if (int rc = check_hip(hipGetLastError(), "per-tensor sums, final pass")) return rc;
-    }
-    return DL_OK;
-}
-
-}  // namespace
-
-int launch_norms_finish(const NormPlan& plan, const float* x, const float* m, GradArg g, int64_t ld, int32_t n,
-                        hipStream_t stream) {
-    if (g.format == DL_GRAD_BF16) return finish_chunks<DL_GRAD_BF16>(plan, x, m, g.p, ld, g.ld, n, stream);
-    if (g.format == DL_GRAD_F16) return finish_chunks<DL_GRAD_F16>(plan, x, m, g.p, ld, g.ld, n, stream);
-    return finish_chunks<DL_GRAD_F32>(plan, x, m, g.p, ld, g.ld, n, stream);
 }
 
 }  // namespace dl
