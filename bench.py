@@ -357,6 +357,43 @@ def bench_multi(P, workloads, name, steps, warmup):
             "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
 
+def bench_graph(P, workloads, name, replays=200):
+    """Launch-bound small workload: one period of the time-varying topology (gradient + DecentLaM step
+    per iteration) captured once in a HIP graph and replayed; microseconds per iteration, eager beside it."""
+    import numpy as np
+    import torch
+
+    w = workloads.get(name)
+    A, y, _ = workloads.device_lsq_problem(w, "cuda")
+    topo = P.topology_build(w.topo, w.n)
+    gamma, beta, scale = (float(np.float32(v)) for v in (w.gamma, w.beta, w.lsq_scale))
+    x = torch.zeros((w.n, w.d), dtype=torch.float32, device="cuda")
+    m, g = torch.zeros_like(x), torch.zeros_like(x)
+    ws = torch.empty(P.local_grad_lsq_workspace(w.n, w.b, w.d), dtype=torch.uint8, device="cuda")
+
+    def period():
+        for k in range(topo.period):
+            P.local_grad_lsq(A, y, x, g, None, scale, ws)
+            P.decentlam_step(x, m, g, topo, gamma, beta, k)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        period()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        period()
+    x.zero_()
+    m.zero_()
+    _, graph_ms = time_launches(lambda k: graph.replay(), replays, 5)
+    x.zero_()
+    m.zero_()
+    _, eager_ms = time_launches(lambda k: period(), replays, 5)
+    return {"iterations_per_graph": topo.period, "graph_us_per_iteration": round(graph_ms * 1e3 / topo.period, 2),
+            "eager_us_per_iteration": round(eager_ms * 1e3 / topo.period, 2)}
+
+
 def bench_lsq(P, workloads, name, steps, warmup, calibration_copy=False):
     """Workload 5: local_grad_lsq then decentlam_step per iteration; times the gradient alone too."""
     import numpy as np
@@ -540,6 +577,7 @@ def main():
             r2 = bench_lsq(P, workloads, small, 200, 20)
             extras[f"{small}_us"] = {"grad_plus_step": round(r2["ms_per_iteration_grad_plus_step"] * 1e3, 2),
                                      "grad": round(r2["grad_kernel_ms"] * 1e3, 2)}
+        extras["c2_onepeer8_b32_hip_graph"] = bench_graph(P, workloads, "c2_onepeer8_b32")
         # the small workloads are launch-latency bound: report microseconds per call
         w1 = workloads.get("c1_ring4")
         _, _, _, _, _, k1 = bench_step(P, workloads, "c1_ring4", "decentlam", 200, 20)
