@@ -157,7 +157,7 @@ def time_launches(fn, steps, warmup):
     return (t1 - t0) * 1e3 / steps, ev0.elapsed_time(ev1) / steps
 
 
-def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False, detail=None):
+def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False, detail=None, ld=None):
     import numpy as np
     import torch
 
@@ -169,7 +169,8 @@ def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False, 
     # Row stride: rows start on 256-byte boundaries (ld = d rounded up to 64 elements).  With rows
     # that are only 16-byte aligned every 1 KiB wave access straddles an extra cache line and the
     # ragged workload loses about 17 % (measured 4.65 vs 5.60 TB/s).
-    ld = (d + 63) // 64 * 64
+    if ld is None:
+        ld = (d + 63) // 64 * 64
     xb = workloads.device_x0(w, "cuda", ld=ld)
     mb = torch.zeros_like(xb)
     gb = torch.zeros_like(xb)
@@ -552,6 +553,12 @@ def main():
             b2 = BYTES_PER_ELEMENT * w2.n * d2
             extras[f"{algo}_step_{name}"] = {"kernel_ms": round(k2, 4), "GBps": round(b2 / (k2 * 1e-3) / 1e9, 1),
                                              "frac_of_hbm_peak": round(b2 / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        # row-major with the rows padded to 128 MiB (ld = 2^25 elements): the row stride alone moves the
+        # row-major figure between 2.8 and 3.5 ms (address hashing); 2^25 was the best of a dozen tried
+        _, _, _, _, _, k3 = bench_step(P, workloads, "c3_exp32", "decentlam", args.steps, args.warmup, ld=1 << 25)
+        extras["decentlam_step_c3_exp32_ld_2pow25"] = {
+            "kernel_ms": round(k3, 4), "GBps": round(bytes_per_step / (k3 * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(bytes_per_step / (k3 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         extras["decentlam_step_xprev_c3_exp32"] = bench_xprev(P, workloads, "c3_exp32", args.steps, args.warmup)
         blk = bench_blocked(P, workloads, "c3_exp32", "decentlam", args.steps, args.warmup)
         extras["decentlam_step_blocked_c3_exp32"] = blk
