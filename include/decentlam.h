@@ -227,6 +227,26 @@ int decentlam_step_xprev_ex(const float* x, float* x_prev, const void* g,
                             float gamma, float gamma_prev, float beta, int64_t k, void* stream);
 
 /*
+ * decentlam_step_multi_ex, dmsgd_step_multi_ex -- the multi-tensor calls in their general form: tensor
+ * table and per-tensor sums as decentlam_step_multi, layout and gradient format from a dl_layout.
+ * In the blocked layout (layout->bw > 0) the table starts at column 0 (offsets[0] == 0), and with
+ * norms != NULL the block width must be a multiple of 256 and x, m 16-byte aligned (g: 4 elements),
+ * so that whole tiles line up with the columns (DL_EINVAL otherwise).
+ */
+int decentlam_step_multi_ex(float* x, float* m, const void* g,
+                            int32_t n, const dl_layout* layout,
+                            int32_t num_tensors, const int64_t* offsets,
+                            double* norms, void* workspace, size_t workspace_bytes,
+                            const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                            float gamma, float beta, int64_t k, void* stream);
+int dmsgd_step_multi_ex(float* x, float* m, const void* g,
+                        int32_t n, const dl_layout* layout,
+                        int32_t num_tensors, const int64_t* offsets,
+                        double* norms, void* workspace, size_t workspace_bytes,
+                        const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                        float gamma, float beta, int64_t k, void* stream);
+
+/*
  * awc_dmsgd_step, da_dmsgd_step -- two sibling methods of the paper's comparison that reuse the
  * same fused gather-mix pass (Sec. "Experiments", list of compared algorithms).  The paper
  * describes them in a sentence each and prints no recursion; the library implements this reading:

@@ -32,7 +32,7 @@ DL_GRAD_F32, DL_GRAD_BF16, DL_GRAD_F16 = 0, 1, 2
 
 EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decentlam_step", "decentlam_step_xprev",
            "dmsgd_step", "dsgd_step", "awc_dmsgd_step", "da_dmsgd_step", "decentlam_step_blocked",
-           "dmsgd_step_blocked", "decentlam_step_ex", "dmsgd_step_ex", "decentlam_step_xprev_ex", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
+           "dmsgd_step_blocked", "decentlam_step_ex", "dmsgd_step_ex", "decentlam_step_xprev_ex", "decentlam_step_multi_ex", "dmsgd_step_multi_ex", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
            "dmsgd_step_multi", "decentlam_step_multi_workspace", "local_grad_lsq", "local_grad_lsq_rows",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
@@ -87,6 +87,11 @@ def _load() -> ctypes.CDLL:
     for name in ("decentlam_step_ex", "dmsgd_step_ex"):
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, layp, i32p, i32p, f32p,
+                                       ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_int64, vp]
+    for name in ("decentlam_step_multi_ex", "dmsgd_step_multi_ex"):
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = [vp, vp, vp, ctypes.c_int32, layp, ctypes.c_int32,
+                                       ctypes.POINTER(ctypes.c_int64), vp, vp, ctypes.c_size_t, i32p, i32p, f32p,
                                        ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_int64, vp]
     lib.decentlam_step_xprev_ex.restype = ctypes.c_int
     lib.decentlam_step_xprev_ex.argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, layp, i32p, i32p, f32p,
@@ -314,6 +319,59 @@ def decentlam_step_xprev_ex(x, x_prev, g, topo: Topology, gamma: float, beta: fl
     """General momentum-free DecentLaM step (x_prev is overwritten with x^{k+1}), see decentlam_step_ex."""
     _step_ex(_lib.decentlam_step_xprev_ex, x, x_prev, g, d, topo, gamma, beta, k, stream,
              gamma if gamma_prev is None else gamma_prev)
+
+
+def _step_multi_ex(fn, x, m, g, offsets, topo, gamma, beta, k, norms, workspace, stream):
+    if g.dtype not in _GRAD_FORMAT:
+        raise TypeError("g: need a float32, bfloat16 or float16 tensor")
+    for name, t in (("x", x), ("m", m)):
+        if t.dtype != torch.float32 or not t.is_cuda:
+            raise TypeError(f"{name}: need a float32 device tensor")
+    offsets = np.ascontiguousarray(offsets, np.int64)
+    if offsets.ndim != 1 or offsets.size < 2:
+        raise TypeError("offsets: need num_tensors + 1 column offsets")
+    num = offsets.size - 1
+    if x.dim() == 3:
+        if not (x.is_contiguous() and m.is_contiguous() and g.is_contiguous()) or x.shape != m.shape or x.shape != g.shape:
+            raise TypeError("blocked layout: x, m and g must be contiguous (blocks, n, bw) tensors of one shape")
+        nb, n, bw = x.shape
+        if offsets[-1] > nb * bw:
+            raise DecentLamError(DL_EINVAL, f"offsets end at {offsets[-1]}, arrays hold {nb * bw} columns")
+        lay = Layout(_GRAD_FORMAT[g.dtype], 0, 0, bw)
+    else:
+        px, n, cols, ld = _matrix_args(x, "x")
+        pm, nm, dm, ldm = _matrix_args(m, "m")
+        if (nm, dm, ldm) != (n, cols, ld):
+            raise TypeError("x and m must share shape and row stride")
+        _, fmt, ldg = _grad_args(g, n, cols)
+        if offsets[-1] > cols:
+            raise DecentLamError(DL_EINVAL, f"offsets end at {offsets[-1]}, arrays have {cols} columns")
+        lay = Layout(fmt, max(ld, cols), max(ldg, cols), 0)
+    if topo.n != n:
+        raise DecentLamError(DL_ETOPO, f"topology has {topo.n} nodes, arrays have {n} rows")
+    pn = pw = wb = 0
+    if norms is not None:
+        if norms.dtype != torch.float64 or not norms.is_cuda or not norms.is_contiguous() or norms.numel() != num * n * 3:
+            raise TypeError("norms: need a contiguous float64 device tensor of num_tensors x n x 3 elements")
+        if workspace is None:
+            raise TypeError("workspace: pass a uint8 device tensor (size from decentlam_step_multi_workspace)")
+        pn, pw, wb = norms.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    _check(fn(x.data_ptr(), m.data_ptr(), g.data_ptr(), n, ctypes.byref(lay), num,
+              offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), pn, pw, wb, *topo._args(), gamma, beta, k,
+              _stream() if stream is None else stream))
+
+
+def decentlam_step_multi_ex(x, m, g, offsets, topo: Topology, gamma: float, beta: float, k: int = 0,
+                            norms=None, workspace=None, stream=None):
+    """General multi-tensor DecentLaM step: 2-D tensors are row-major arrays, 3-D (blocks, n, bw) tensors
+    the blocked layout (the table then starts at column 0); g may be 16-bit."""
+    _step_multi_ex(_lib.decentlam_step_multi_ex, x, m, g, offsets, topo, gamma, beta, k, norms, workspace, stream)
+
+
+def dmsgd_step_multi_ex(x, m, g, offsets, topo: Topology, gamma: float, beta: float, k: int = 0,
+                        norms=None, workspace=None, stream=None):
+    """General multi-tensor DmSGD step, see decentlam_step_multi_ex."""
+    _step_multi_ex(_lib.dmsgd_step_multi_ex, x, m, g, offsets, topo, gamma, beta, k, norms, workspace, stream)
 
 
 def awc_dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):

@@ -243,8 +243,20 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int
 int blocked_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int32_t n, int64_t d,
                   int64_t bw, const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
                   float gamma, float beta, int64_t k, void* stream, int g_format = DL_GRAD_F32,
-                  float gamma_prev = 0.0f) {
+                  float gamma_prev = 0.0f, const StepExtras* multi = nullptr) {
     clear_error();
+    if (multi) {   // the tensor table fixes d
+        if (multi->num_tensors < 1)
+            return set_error(DL_EINVAL, "%s: num_tensors = %d, need >= 1", fn, multi->num_tensors);
+        if (!multi->offsets) return set_error(DL_EINVAL, "%s: offsets must not be NULL", fn);
+        if (multi->offsets[0] != 0)
+            return set_error(DL_EINVAL, "%s: offsets[0] = %lld; in the blocked layout the table starts at column 0",
+                             fn, static_cast<long long>(multi->offsets[0]));
+        for (int32_t t = 0; t < multi->num_tensors; ++t)
+            if (multi->offsets[t + 1] < multi->offsets[t])
+                return set_error(DL_EINVAL, "%s: offsets decrease at tensor %d", fn, t);
+        d = multi->offsets[multi->num_tensors];
+    }
     if (g_format != DL_GRAD_F32 && g_format != DL_GRAD_BF16 && g_format != DL_GRAD_F16)
         return set_error(DL_EINVAL, "%s: g_format = %d is not a dl_grad_format", fn, g_format);
     if (algo == ALGO_DECENTLAM_XPREV && (!std::isfinite(gamma_prev) || !(gamma_prev > 0.0f)))
@@ -263,7 +275,21 @@ int blocked_entry(const char* fn, Algo algo, float* x, float* m, const void* g, 
     PhaseArgs topo;
     std::memset(&topo, 0, sizeof(topo));
     if (int rc = pack_phase(fn, n, row_ptr, col_idx, w, static_cast<int32_t>(k % period), &topo)) return rc;
-    if (d == 0) return DL_OK;
+    const bool want_norms = multi && multi->norms != nullptr;
+    if (want_norms) {
+        const size_t need = multi_workspace_bytes(n, d);
+        if (!multi->workspace || multi->workspace_bytes < need)
+            return set_error(DL_ECAP, "%s: workspace of %zu bytes needed, %zu given", fn, need,
+                             multi->workspace ? multi->workspace_bytes : size_t{0});
+        if ((reinterpret_cast<uintptr_t>(multi->workspace) | reinterpret_cast<uintptr_t>(multi->norms)) & 7u)
+            return set_error(DL_EINVAL, "%s: workspace and norms must be 8-byte aligned", fn);
+        // whole tiles per block and no peeled columns: the tile records then line up with the columns
+        if (bw % 256 != 0 || ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m)) & 15u) ||
+            (reinterpret_cast<uintptr_t>(g) & (4 * grad_elem_bytes(g_format) - 1)))
+            return set_error(DL_EINVAL, "%s: per-tensor sums in the blocked layout need bw %% 256 == 0 and "
+                             "16-byte aligned x, m (g: 4 elements)", fn);
+    }
+    if (d == 0 && !want_norms) return DL_OK;
     if (!x || !m || !g) return set_error(DL_EINVAL, "%s: x, m and g must not be NULL", fn);
     const uintptr_t gbytes = grad_elem_bytes(g_format);
     if (((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m)) & 3u) ||
@@ -280,17 +306,39 @@ int blocked_entry(const char* fn, Algo algo, float* x, float* m, const void* g, 
     if (algo == ALGO_DECENTLAM_XPREV)
         beta_eff = beta_eff * static_cast<double>(gamma) / static_cast<double>(gamma_prev);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    NormPlan plan;
+    std::memset(&plan, 0, sizeof(plan));
+    NormPlan* np = nullptr;
+    if (want_norms) {
+        const size_t need = multi_workspace_bytes(n, d);
+        const Span sw = {reinterpret_cast<uintptr_t>(multi->workspace),
+                         reinterpret_cast<uintptr_t>(multi->workspace) + need};
+        const int64_t count = static_cast<int64_t>(multi->num_tensors) * n * 3;
+        const Span sn = span_of(multi->norms, 1, count, count, 8);
+        if (overlap(sw, sn) || overlap(sw, sx) || overlap(sw, sm) || overlap(sw, sg) || overlap(sn, sx) ||
+            overlap(sn, sm) || overlap(sn, sg))
+            return set_error(DL_EALIAS, "%s: norms / workspace overlap another array", fn);
+        plan.offsets = multi->offsets;
+        plan.num_tensors = multi->num_tensors;
+        plan.partial = static_cast<double*>(multi->workspace);
+        plan.norms = multi->norms;
+        plan.bw = bw;
+        np = &plan;
+    }
     if (full > 0) {
-        if (int rc = launch_step(algo, x, m, GradArg{g, g_format, bw}, n, bw, bw, topo, gamma, beta_eff, s,
-                                 nullptr, full, block, block))
+        if (int rc = launch_step(algo, x, m, GradArg{g, g_format, bw}, n, bw, bw, topo, gamma, beta_eff, s, np,
+                                 full, block, block))
             return rc;
     }
     if (rest > 0) {
         const int64_t at = full * block;
         const void* g_rest = static_cast<const char*>(g) + static_cast<size_t>(at) * gbytes;
-        return launch_step(algo, x + at, m + at, GradArg{g_rest, g_format, bw}, n, rest, bw, topo, gamma, beta_eff,
-                           s);
+        plan.col_base = full * bw;
+        if (int rc = launch_step(algo, x + at, m + at, GradArg{g_rest, g_format, bw}, n, rest, bw, topo, gamma,
+                                 beta_eff, s, np))
+            return rc;
     }
+    if (np) return launch_norms_finish(plan, x, m, GradArg{g, g_format, bw}, bw, n, s);
     return DL_OK;
 }
 
@@ -373,6 +421,54 @@ int decentlam_step_xprev_ex(const float* x, float* x_prev, const void* g, int32_
                             void* stream) {
     return dl::ex_entry("decentlam_step_xprev_ex", dl::ALGO_DECENTLAM_XPREV, const_cast<float*>(x), x_prev, g, n, d,
                         layout, row_ptr, col_idx, w, period, gamma, gamma_prev, beta, k, stream);
+}
+
+namespace dl {
+namespace {
+int multi_ex_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int32_t n,
+                   const dl_layout* layout, int32_t num_tensors, const int64_t* offsets, double* norms,
+                   void* workspace, size_t workspace_bytes, const int32_t* row_ptr, const int32_t* col_idx,
+                   const float* w, int32_t period, float gamma, float beta, int64_t k, void* stream) {
+    if (!layout) {
+        clear_error();
+        return set_error(DL_EINVAL, "%s: layout must not be NULL", fn);
+    }
+    if (layout->bw < 0) {
+        clear_error();
+        return set_error(DL_EINVAL, "%s: layout.bw = %lld, need >= 0", fn, static_cast<long long>(layout->bw));
+    }
+    StepExtras ex;
+    ex.g_format = layout->g_format;
+    ex.ldg = layout->ldg;
+    ex.multi = true;
+    ex.num_tensors = num_tensors;
+    ex.offsets = offsets;
+    ex.norms = norms;
+    ex.workspace = workspace;
+    ex.workspace_bytes = workspace_bytes;
+    if (layout->bw > 0)
+        return blocked_entry(fn, algo, x, m, g, n, 0, layout->bw, row_ptr, col_idx, w, period, gamma, beta, k, stream,
+                             layout->g_format, 0.0f, &ex);
+    return step_entry(fn, algo, x, m, g, n, 0, layout->ld, row_ptr, col_idx, w, period, gamma, beta, k, stream, 0.0f,
+                      ex);
+}
+}  // namespace
+}  // namespace dl
+
+int decentlam_step_multi_ex(float* x, float* m, const void* g, int32_t n, const dl_layout* layout,
+                            int32_t num_tensors, const int64_t* offsets, double* norms, void* workspace,
+                            size_t workspace_bytes, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
+                            int32_t period, float gamma, float beta, int64_t k, void* stream) {
+    return dl::multi_ex_entry("decentlam_step_multi_ex", dl::ALGO_DECENTLAM, x, m, g, n, layout, num_tensors, offsets,
+                              norms, workspace, workspace_bytes, row_ptr, col_idx, w, period, gamma, beta, k, stream);
+}
+
+int dmsgd_step_multi_ex(float* x, float* m, const void* g, int32_t n, const dl_layout* layout,
+                        int32_t num_tensors, const int64_t* offsets, double* norms, void* workspace,
+                        size_t workspace_bytes, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
+                        int32_t period, float gamma, float beta, int64_t k, void* stream) {
+    return dl::multi_ex_entry("dmsgd_step_multi_ex", dl::ALGO_DMSGD, x, m, g, n, layout, num_tensors, offsets, norms,
+                              workspace, workspace_bytes, row_ptr, col_idx, w, period, gamma, beta, k, stream);
 }
 
 int awc_dmsgd_step(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,

@@ -66,15 +66,19 @@ struct NormPlan {
     int32_t num_tensors;
     double* partial;          // device, room for norm_tiles_bound(d) records of n x 3 doubles
     double* norms;            // device, [num_tensors][n][3]
-    NormGrid grid[kMaxNormGrids];
+    NormGrid grid[kMaxNormGrids];   // appended to by every launch_step call of one iteration
     int grids;
+    int64_t tiles_used;       // records written so far
+    int64_t col_base;         // logical column of the next launch_step call's column 0
+    int64_t bw;               // 0: row-major arrays; > 0: blocked layout with this block width
 };
 // Upper bound on the number of tile records a step over d columns writes, at any alignment.
 inline int64_t norm_tiles_bound(int64_t d) { return (d + 63) / 64 + 3; }
 
 // Enqueue one fused iteration over columns [0, d) of x, m, g (already validated).
 // `beta` is a double so that the momentum-free form can pass beta * gamma / gamma_prev unrounded.
-// With `norms` the launches also write their tile records and note their grids in it.
+// With `norms` the launches also write their tile records and append their grids to it (a batched
+// launch must then cover whole blocks: it is recorded as one grid over batches * d logical columns).
 // With batches > 1 the launches cover `batches` equally shaped problems whose arrays start
 // batch_stride (x, m) and batch_stride_g (g) elements apart -- the full blocks of the blocked layout.
 int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, int64_t ld,

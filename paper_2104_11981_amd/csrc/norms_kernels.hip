@@ -25,7 +25,7 @@ struct FinishArgs {
 template <int GF>
 __global__ __launch_bounds__(256) void k_norms_finish(const float* __restrict__ x, const float* __restrict__ m,
                                                       const typename GradElem<GF>::type* __restrict__ g,
-                                                      int64_t ld, int64_t ldg, int n,
+                                                      int64_t ld, int64_t ldg, int64_t bw, int n,
                                                       const double* __restrict__ partial,
                                                       double* __restrict__ norms, const FinishArgs fa,
                                                       const OffsetChunk chunk) {
@@ -34,11 +34,15 @@ __global__ __launch_bounds__(256) void k_norms_finish(const float* __restrict__ 
     double s[3] = {0.0, 0.0, 0.0};
     auto columns = [&](int64_t a, int64_t b) {   // element-wise over [a, b)
         for (int64_t c = a + threadIdx.x; c < b; c += 256) {
+            // element (i, c): row-major i * ld + c, blocked ((c / bw) * n + i) * bw + c % bw
+            const int64_t blk = bw > 0 ? c / bw : 0;
+            const int64_t at = bw > 0 ? (blk * n + i) * bw + (c - blk * bw) : static_cast<int64_t>(i) * ld + c;
+            const int64_t at_g = bw > 0 ? at : static_cast<int64_t>(i) * ldg + c;
             float gv[1];
-            load_grad<1, GF>(g + static_cast<int64_t>(i) * ldg + c, gv);
+            load_grad<1, GF>(g + at_g, gv);
             const double g1 = static_cast<double>(gv[0]);
-            const double m1 = static_cast<double>(m[static_cast<int64_t>(i) * ld + c]);
-            const double x1 = static_cast<double>(x[static_cast<int64_t>(i) * ld + c]);
+            const double m1 = static_cast<double>(m[at]);
+            const double x1 = static_cast<double>(x[at]);
             s[0] = __builtin_fma(g1, g1, s[0]);
             s[1] = __builtin_fma(m1, m1, s[1]);
             s[2] = __builtin_fma(x1, x1, s[2]);
@@ -91,7 +95,7 @@ int finish_chunks(const NormPlan& plan, const float* x, const float* m, const vo
             chunk.v[j] = plan.offsets[t0 + (j <= count ? j : count)] - plan.offsets[0];
         hipLaunchKernelGGL(k_norms_finish<GF>, dim3(static_cast<unsigned>(count), static_cast<unsigned>(n)),
                            dim3(256), 0, stream, x, m, static_cast<const typename GradElem<GF>::type*>(g), ld, ldg,
-                           n, plan.partial, plan.norms + static_cast<int64_t>(t0) * n * 3, fa, chunk);
+                           plan.bw, n, plan.partial, plan.norms + static_cast<int64_t>(t0) * n * 3, fa, chunk);
         if (int rc = check_hip(hipGetLastError(), "per-tensor sums, final pass")) return rc;
     }
     return DL_OK;

@@ -455,8 +455,6 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
     const int64_t body = ((d - head) / vec) * vec;
     const int64_t tail = d - head - body;
 
-    if (norms) norms->grids = 0;
-    int64_t tiles_used = 0;
     auto run = [&](int v, int64_t c0, int64_t cols) {
         if (cols <= 0) return static_cast<int>(DL_OK);
         StepCall s;
@@ -469,10 +467,11 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
         s.batches = batches; s.batch_stride = batch_stride; s.batch_stride_g = batch_stride_g;
         if (norms) {
             const int tc = 64 * v;
+            if (norms->grids >= kMaxNormGrids) return set_error(DL_EINVAL, "step: too many launches for the per-tensor sums");
             NormGrid& gr = norms->grid[norms->grids++];
-            gr.col0 = c0; gr.cols = cols; gr.tile0 = tiles_used; gr.tc = tc;
+            gr.col0 = norms->col_base + c0; gr.cols = cols * batches; gr.tile0 = norms->tiles_used; gr.tc = tc;
             s.na = NormArgs{norms->partial, gr.tile0};
-            tiles_used += (cols + tc - 1) / tc;
+            norms->tiles_used += (cols + tc - 1) / tc * batches;
         }
         switch (algo) {
             case ALGO_DECENTLAM: return launch_extras<ALGO_DECENTLAM>(v, g.format, norms != nullptr, s);

@@ -184,3 +184,63 @@ def test_multi_tensor_and_general_calls_are_capturable_in_a_hip_graph(P):
             assert torch.equal(got, want), f"replay {r} differs from eager"
         scratch.add_(1.0)
         torch.cuda.synchronize()
+
+
+MULTI_EX_CASES = [
+    # n, bw (0 = row-major), tensor sizes
+    (16, 256, [300, 1, 0, 63, 64, 65, 700, 2, 2, 2, 500, 0, 1097]),     # ends inside a block
+    (32, 512, [1] * 40 + [600] + [5] * 30 + [1024 - 790]),              # exactly two blocks
+    (64, 256, [517, 100, 100, 51]),                                     # 128-column tiles
+    (100, 256, [64, 64, 1, 200, 500]),                                  # 64-column tiles
+    (16, 8192, [3000, 5000, 10000, 7]),                                 # two full blocks + a rest with a tail
+    (16, 0, [300, 1, 0, 63, 64, 65, 700]),                              # row-major through the general call
+]
+
+
+@pytest.mark.parametrize("fmt", ["f32", "bf16"])
+@pytest.mark.parametrize("algo", ["decentlam", "dmsgd"])
+@pytest.mark.parametrize("n,bw,sizes", MULTI_EX_CASES)
+def test_general_multi_tensor_call_matches_oracle(P, oracle, fmt, algo, n, bw, sizes):
+    gamma, beta = float(np.float32(0.05)), float(np.float32(0.9))
+    topo, otopo = topo_pair(P, oracle, 0, n)
+    rng = np.random.default_rng(7 * n + bw + len(sizes))
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    d, T = int(offsets[-1]), len(sizes)
+    x0 = rng.standard_normal((n, d)).astype(np.float32)
+    lay = (lambda t: P.to_blocked(t, bw)) if bw else (lambda t: t.clone())
+    unlay = (lambda t: P.from_blocked(t, d)) if bw else (lambda t: t)
+    x, m = lay(dev(x0)), lay(torch.zeros((n, d), dtype=torch.float32, device="cuda"))
+    norms = torch.full((T, n, 3), -1.0, dtype=torch.float64, device="cuda")
+    ws = torch.empty(P.decentlam_step_multi_workspace(n, d, T), dtype=torch.uint8, device="cuda")
+    xs, ms = x0.astype(np.float64), np.zeros((n, d))
+    r32 = lambda a: a.astype(np.float32).astype(np.float64)
+    for k in range(3):
+        gd, gv = make_grad(oracle, rng, n, d, fmt)
+        getattr(P, algo + "_step_multi_ex")(x, m, lay(gd), offsets, topo, gamma, beta, k, norms=norms, workspace=ws)
+        xs, ms = (r32(a) for a in oracle.STEP[algo](xs, ms, gv, otopo, gamma, beta, k))
+        xg, mg = unlay(x).cpu().numpy(), unlay(m).cpu().numpy()
+        check_elementwise(xg, xs, f"x after iteration {k}")
+        check_elementwise(mg, ms, f"m after iteration {k}")
+        got = norms.cpu().numpy()
+        want = oracle.tensor_sumsq(gv, ms, xs, offsets)
+        np.testing.assert_allclose(got, want, rtol=2e-6, atol=1e-30)
+        np.testing.assert_allclose(got[:, :, 0], want[:, :, 0], rtol=1e-13, atol=0)
+        own = oracle.tensor_sumsq(gv, mg, xg, offsets)              # plain sums of what the call stored
+        np.testing.assert_allclose(got, own, rtol=1e-13, atol=0)
+
+
+def test_blocked_multi_tensor_requirements(P):
+    n = 4
+    topo = P.topology_build(P.DL_TOPO_RING, n)
+    x = torch.zeros((2, n, 100), device="cuda")                         # bw not a multiple of 256
+    m, g = torch.zeros_like(x), torch.zeros_like(x)
+    norms = torch.zeros((1, n, 3), dtype=torch.float64, device="cuda")
+    ws = torch.empty(P.decentlam_step_multi_workspace(n, 200, 1), dtype=torch.uint8, device="cuda")
+    with pytest.raises(P.DecentLamError) as e:
+        P.decentlam_step_multi_ex(x, m, g, [0, 200], topo, 0.1, 0.9, 0, norms=norms, workspace=ws)
+    assert e.value.status == P.DL_EINVAL and "256" in str(e.value)
+    P.decentlam_step_multi_ex(x, m, g, [0, 200], topo, 0.1, 0.9, 0)     # without sums any width works
+    with pytest.raises(P.DecentLamError) as e:
+        P.decentlam_step_multi_ex(x, m, g, [5, 200], topo, 0.1, 0.9, 0)
+    assert e.value.status == P.DL_EINVAL
+    torch.cuda.synchronize()
