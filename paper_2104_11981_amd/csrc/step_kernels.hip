@@ -381,7 +381,7 @@ int launch_rows(const StepCall& s) {
     if constexpr (VEC == 1 || VEC * (MAXN) <= (ALGO == ALGO_DA_DMSGD ? 64 : 128)) {        \
         if (s.n <= (MAXN)) return launch_variant<VEC, R, W, ALGO, GF, NORMS>(s);         \
     }
-    DL_SHAPE(4, 4, 1) DL_SHAPE(8, 8, 1) DL_SHAPE(16, 16, 1) DL_SHAPE(32, 16, 2)
+    DL_SHAPE(1, 1, 1) DL_SHAPE(2, 2, 1) DL_SHAPE(4, 4, 1) DL_SHAPE(8, 8, 1) DL_SHAPE(16, 16, 1) DL_SHAPE(32, 16, 2)
     DL_SHAPE(64, 16, 4) DL_SHAPE(128, 16, 8) DL_SHAPE(256, 16, 16)
 #undef DL_SHAPE
     return set_error(DL_ETOPO, "step: n = %d has no kernel variant at vector width %d", s.n, VEC);
