@@ -1,0 +1,412 @@
+// Implementation shared by the translation units that instantiate the step kernel, one per method
+// (the instantiations are split over several files only so that they compile in parallel).
+#pragma once
+
+#include "device_util.hpp"
+#include "internal.hpp"
+
+namespace dl {
+namespace step {
+
+using namespace dev;
+
+// A launch may cover `count` equally shaped sub-problems ("batches": the blocks of the blocked
+// layout): consecutive workgroups walk the tiles of batch 0, then batch 1, ...
+struct BatchArgs {
+    int64_t stride;        // elements between consecutive batches of x and m
+    int64_t stride_g;      // the same for g, in its elements
+    uint32_t tiles;        // tiles per batch; 0: the launch is a single problem
+};
+
+// Per-launch arguments of the per-tensor sums (see NormPlan): where the tile records go.
+struct NormArgs {
+    double* partial;
+    int64_t tile0;   // record index of this launch's tile 0
+};
+
+// Everything a launch needs besides its template parameters.
+struct StepCall {
+    float* x;
+    float* m;
+    const void* g;
+    int32_t n;
+    int64_t d, ld, ldg;
+    double gamma, beta;
+    const PhaseArgs* topo;
+    hipStream_t stream;
+    NormArgs na;
+    int64_t batches, batch_stride, batch_stride_g;   // batches == 1: a single problem
+};
+
+
+// Launch the kernel of one method for the given vector width, gradient format and sums option
+// (defined in step_<method>.hip).
+template <int ALGO>
+int launch_method(int vec, int format, bool norms, const StepCall& s);
+
+#ifdef DL_STEP_KERNEL_IMPL
+namespace {
+
+// Position of a lane's v-th column inside a row of the LDS tile, in doubles: a row is kept as VEC
+// planes of 64 doubles (column v of every lane), so that every LDS access of a wave touches 64
+// consecutive doubles and is free of bank conflicts.  With the lane's VEC columns side by side
+// (32-byte groups per lane) 71 % of the LDS cycles were bank conflicts (measured) and the kernel was
+// LDS-bound at 2.6 ms on the headline workload whatever the traffic.
+__device__ __forceinline__ constexpr int lds_col(int v) { return v * 64; }
+
+// One neighbour in the LDS table.
+struct alignas(16) Neighbour {
+    double w;     // w_ij, promoted exactly from fp32
+    int offset;   // j * TC: start of row j in the LDS tile, in doubles
+    int unused;
+};
+
+// z += sum over K consecutive table entries; all K table reads, then all K tile reads, are
+// issued before the first multiply-add so their latencies overlap.
+template <int VEC, int K>
+__device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, const double* __restrict__ tile_at_lane,
+                                       double (&z)[VEC]) {
+    Neighbour nb[K];
+#pragma unroll
+    for (int t = 0; t < K; ++t) nb[t] = entry[t];
+    double u[K][VEC];
+#pragma unroll
+    for (int t = 0; t < K; ++t) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) u[t][v] = tile_at_lane[nb[t].offset + lds_col(v)];
+    }
+#pragma unroll
+    for (int t = 0; t < K; ++t) {   // list order, one fused multiply-add per term
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) z[v] = __builtin_fma(nb[t].w, u[t][v], z[v]);
+    }
+}
+
+// After the barrier all waves of a workgroup gather, compute and store at the same moment, and the
+// memory system sees the workgroup's 64 KiB of stores as one burst.  Letting the odd-numbered waves
+// (SIMDs 1 and 3) begin that phase 32-48 x 64 cycles later measured 4-8 % faster wherever the kernel
+// is bound by the mix of reads and writes: 16-byte lanes up to 32 nodes, every form that moves 14 B
+// per node-element or more.  Measured neutral or harmful, hence off: DSGD (12 B), 64 nodes and
+// more, the 16-wave single-row shape with less than 20 B, the variants with per-tensor sums.
+// A hand-over through a second barrier (odd waves wait for the even ones) was tried instead of the
+// fixed pause: better for DecentLaM at 32 nodes, worse everywhere else.
+template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
+constexpr int stagger_units() {
+    if (NORMS || VEC != 4 || ALGO == ALGO_DSGD || ALGO == ALGO_DA_DMSGD) return 0;
+    const bool twenty_bytes = ALGO != ALGO_DECENTLAM_XPREV && GF == DL_GRAD_F32;
+    if (RPT == 2 && WAVES == 16) return twenty_bytes ? 48 : 32;
+    if (RPT == 1 && WAVES == 16) return twenty_bytes ? 32 : 0;
+    if (RPT == 1 && WAVES <= 8) return 32;
+    return 0;
+}
+
+// VEC    columns per lane (width of the global accesses: 4, 8 or 16 bytes)
+// RPT    rows per thread; WAVES wavefronts per workgroup: the kernel covers n <= WAVES * RPT nodes
+// ALGO   ALGO_DECENTLAM, ALGO_DMSGD, ALGO_DSGD (x <- W (x - gamma g); m is not touched) or
+//        ALGO_DECENTLAM_XPREV: DecentLaM in its momentum-free form (appendix "Reformulation of
+//        DecentLaM"), x_next = W (x - gamma g) + beta' (x - x_prev); here `m` is the buffer that
+//        holds x_prev on entry and x_next on exit, x is only read, and `beta` carries
+//        beta' = beta * gamma / gamma_prev: 16 bytes per node-element, one written array;
+//        ALGO_AWC_DMSGD (m <- beta m + g; x <- W x - gamma m: the tile holds x) and ALGO_DA_DMSGD
+//        (mh = beta m + g; x <- W (x - gamma mh); m <- W mh: two tiles, h and mh, both gathered)
+// GF     dl_grad_format of g;  NORMS: accumulate the per-tensor sums of squares
+template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
+__global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8) ? 8 : 1) void k_step(float* __restrict__ x, float* __restrict__ m,
+                                                      const typename GradElem<GF>::type* __restrict__ g,
+                                                      int64_t d, int64_t ld, int64_t ldg,
+                                                      double gamma, double inv_gamma, double beta,
+                                                      const BatchArgs batch, const NormArgs na,
+                                                      const PhaseArgs topo) {
+    constexpr int TC = 64 * VEC;
+    extern __shared__ double lds[];  // tile [n][TC] of u_j (DecentLaM) or h_j (DmSGD), then the table
+    const int n = topo.n;
+    constexpr int TILES = ALGO == ALGO_DA_DMSGD ? 2 : 1;   // DA-DmSGD parks mh_j in a second tile
+    Neighbour* table = reinterpret_cast<Neighbour*>(lds + TILES * n * TC);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint32_t tile = blockIdx.x;
+    if (batch.tiles) {   // uniform: which sub-problem, which of its tiles
+        const uint32_t b = tile / batch.tiles;
+        tile -= b * batch.tiles;
+        x += b * batch.stride;
+        if constexpr (ALGO != ALGO_DSGD) m += b * batch.stride;
+        g += b * batch.stride_g;
+    }
+    const int64_t c = static_cast<int64_t>(tile) * TC + lane * VEC;
+    const bool live = c < d;  // d is a multiple of VEC for this launch
+
+    // ---- phase 1: stream rows in
+    float xr[RPT][VEC], mr[RPT][VEC], gr[RPT][VEC];
+    // NORMS: sums of squares that are complete before the barrier (g; the new m of DmSGD), reduced
+    // over the wave right away and kept as scalars so that they cost no vector registers later
+    double early[RPT][2];
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) {
+        const int i = wave + WAVES * r;
+        if (i < n && live) {
+            const int64_t at = static_cast<int64_t>(i) * ld + c;
+            load_vec<VEC>(x + at, xr[r]);
+            load_grad<VEC, GF>(g + static_cast<int64_t>(i) * ldg + c, gr[r]);
+            if constexpr (ALGO != ALGO_DSGD) load_vec<VEC>(m + at, mr[r]);
+        }
+    }
+    // neighbour list: kernel arguments -> LDS table (one entry per thread and round)
+    const int nnz = topo.row_ptr[n];
+    for (int e = threadIdx.x; e < nnz; e += 64 * WAVES) {
+        Neighbour t;
+        if (topo.palette) {  // uniform over the grid
+            t.w = static_cast<double>(topo.pal.value[topo.pal.widx[e]]);
+            t.offset = static_cast<int>(topo.pal.col[e]) * TC;
+        } else {
+            t.w = static_cast<double>(topo.direct.w[e]);
+            t.offset = static_cast<int>(topo.direct.col[e]) * TC;
+        }
+        t.unused = 0;
+        table[e] = t;
+    }
+    // local pre-step, parked in LDS
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) {
+        const int i = wave + WAVES * r;
+        double sq_g = 0.0, sq_m = 0.0;   // this lane's share (NORMS)
+        if (i < n && live) {
+            double* slot = lds + i * TC + lane;
+            if constexpr (NORMS) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const double gv = static_cast<double>(gr[r][v]);
+                    sq_g = __builtin_fma(gv, gv, sq_g);
+                }
+            }
+            if constexpr (ALGO == ALGO_AWC_DMSGD) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) slot[lds_col(v)] = static_cast<double>(xr[r][v]);
+            } else if constexpr (ALGO == ALGO_DA_DMSGD) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const double mh = beta * static_cast<double>(mr[r][v]) + static_cast<double>(gr[r][v]);
+                    slot[lds_col(v)] = static_cast<double>(xr[r][v]) - gamma * mh;
+                    slot[n * TC + lds_col(v)] = mh;
+                }
+            } else if constexpr (ALGO != ALGO_DMSGD) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+                    slot[lds_col(v)] = static_cast<double>(xr[r][v]) - gamma * static_cast<double>(gr[r][v]);
+            } else {
+                float mn[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const double m_new = beta * static_cast<double>(mr[r][v]) + static_cast<double>(gr[r][v]);
+                    mn[v] = static_cast<float>(m_new);
+                    slot[lds_col(v)] = static_cast<double>(xr[r][v]) - gamma * m_new;
+                    if constexpr (NORMS) {
+                        const double mv = static_cast<double>(mn[v]);
+                        sq_m = __builtin_fma(mv, mv, sq_m);
+                    }
+                }
+                // the new m waits in the registers of the old one and is stored together with x
+                // after the barrier: one burst of stores per row measures faster than two
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) mr[r][v] = mn[v];
+            }
+        }
+        if constexpr (NORMS) {
+            if (i < n) {   // wave-uniform: all 64 lanes take part
+                if constexpr (ALGO == ALGO_DMSGD) {
+                    const double both = wave_sum2(sq_g, sq_m, lane);   // lane 0: g, lane 1: m
+                    early[r][0] = uniform_f64(both);
+                    early[r][1] = uniform_f64(dpp_f64<0xB1>(both));
+                } else {
+                    early[r][0] = uniform_f64(wave_sum(sq_g));
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // Odd waves start their second phase a little later (see stagger_units).
+    constexpr int kStagger = stagger_units<VEC, RPT, WAVES, ALGO, GF, NORMS>();
+    if constexpr (kStagger > 0) {
+        if (wave & 1) __builtin_amdgcn_s_sleep(kStagger);
+    }
+
+    // ---- phase 2: gather-mix from LDS, finish the update, store in place
+    const double* tile_at_lane = lds + lane;
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) {
+        const int i = wave + WAVES * r;
+        double sq_m = 0.0, sq_x = 0.0;   // this lane's share (NORMS)
+        if (i < n && live) {
+            double z[VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) z[v] = 0.0;
+            int e = topo.row_ptr[i];
+            const int e1 = topo.row_ptr[i + 1];
+            // groups of 4 (2 for 16-byte lanes: eight fp64 values in flight keep the kernel at
+            // 64 VGPRs, i.e. two 1024-thread workgroups per CU), then 2, then 1
+            if constexpr (VEC < 4) {
+                for (; e + 4 <= e1; e += 4) gather<VEC, 4>(table + e, tile_at_lane, z);
+                if (e + 2 <= e1) {
+                    gather<VEC, 2>(table + e, tile_at_lane, z);
+                    e += 2;
+                }
+            } else if constexpr (!(NORMS && RPT >= 2)) {   // (with the sums: one at a time, to fit 64 VGPRs)
+                for (; e + 2 <= e1; e += 2) gather<VEC, 2>(table + e, tile_at_lane, z);
+            }
+            for (; e < e1; ++e) gather<VEC, 1>(table + e, tile_at_lane, z);
+
+            const int64_t at = static_cast<int64_t>(i) * ld + c;
+            float xo[VEC];
+            if constexpr (ALGO == ALGO_DECENTLAM) {
+                float mo[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const double xi = static_cast<double>(xr[r][v]);
+                    const double gt = (xi - z[v]) * inv_gamma;
+                    const double m_new = __builtin_fma(beta, static_cast<double>(mr[r][v]), gt);
+                    mo[v] = static_cast<float>(m_new);
+                    xo[v] = static_cast<float>(xi - gamma * m_new);
+                    if constexpr (NORMS) {
+                        const double mv = static_cast<double>(mo[v]);
+                        sq_m = __builtin_fma(mv, mv, sq_m);
+                    }
+                }
+                store_vec<VEC>(m + at, mo);
+            } else if constexpr (ALGO == ALGO_DECENTLAM_XPREV) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const double diff = static_cast<double>(xr[r][v]) - static_cast<double>(mr[r][v]);
+                    xo[v] = static_cast<float>(__builtin_fma(beta, diff, z[v]));
+                }
+            } else if constexpr (ALGO == ALGO_AWC_DMSGD) {
+                float mo[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const double m_new = beta * static_cast<double>(mr[r][v]) + static_cast<double>(gr[r][v]);
+                    mo[v] = static_cast<float>(m_new);
+                    xo[v] = static_cast<float>(z[v] - gamma * m_new);
+                }
+                store_vec<VEC>(m + at, mo);
+            } else if constexpr (ALGO == ALGO_DA_DMSGD) {
+                double zm[VEC];   // second partial average, over the momentum tile
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) zm[v] = 0.0;
+                const double* m_tile_at_lane = tile_at_lane + n * TC;
+                for (int q = topo.row_ptr[i]; q < e1; ++q) gather<VEC, 1>(table + q, m_tile_at_lane, zm);
+                float mo[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    mo[v] = static_cast<float>(zm[v]);
+                    xo[v] = static_cast<float>(z[v]);
+                }
+                store_vec<VEC>(m + at, mo);
+            } else {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) xo[v] = static_cast<float>(z[v]);
+                if constexpr (ALGO == ALGO_DMSGD) store_vec<VEC>(m + at, mr[r]);
+            }
+            store_vec<VEC>((ALGO == ALGO_DECENTLAM_XPREV ? m : x) + at, xo);
+            if constexpr (NORMS) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const double xv = static_cast<double>(xo[v]);
+                    sq_x = __builtin_fma(xv, xv, sq_x);
+                }
+            }
+        }
+        // per-tile sums of squares: one record of 3 doubles (g, new m, new x) per row and tile;
+        // lanes beyond the launch contributed zeros
+        if constexpr (NORMS) {
+            if (i < n) {
+                double* rec = na.partial + ((na.tile0 + blockIdx.x) * n + i) * 3;
+                if constexpr (ALGO == ALGO_DMSGD) {
+                    const double sx = wave_sum(sq_x);
+                    if (lane < 3) rec[lane] = lane == 0 ? early[r][0] : (lane == 1 ? early[r][1] : sx);
+                } else {
+                    const double mx = wave_sum2(sq_m, sq_x, lane);   // lane 0: m, lane 1: x
+                    if (lane < 3) rec[(lane + 1) % 3] = lane == 2 ? early[r][0] : mx;
+                }
+            }
+        }
+    }
+}
+
+size_t lds_bytes_for(int32_t n, int vec, int nnz, int tiles) {
+    return static_cast<size_t>(tiles) * n * 64 * vec * sizeof(double) + static_cast<size_t>(nnz) * sizeof(Neighbour);
+}
+
+template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
+int launch_variant(const StepCall& s) {
+    constexpr int TC = 64 * VEC;
+    const size_t lds_bytes = lds_bytes_for(s.n, VEC, s.topo->row_ptr[s.n], ALGO == ALGO_DA_DMSGD ? 2 : 1);
+    auto kernel = k_step<VEC, RPT, WAVES, ALGO, GF, NORMS>;
+    if (lds_bytes > 160 * 1024)
+        return set_error(DL_ETOPO, "step: n = %d with %d entries needs %zu bytes of LDS, a CU has 163840", s.n,
+                         static_cast<int>(s.topo->row_ptr[s.n]), lds_bytes);
+    if (lds_bytes > 48 * 1024) {
+        if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                   static_cast<int>(lds_bytes)),
+                               "hipFuncSetAttribute(max dynamic LDS)"))
+            return rc;
+    }
+    const int64_t tiles = (s.d + TC - 1) / TC;
+    const int64_t blocks = tiles * s.batches;
+    if (blocks > 0x7fffffffLL) return set_error(DL_EINVAL, "step: d too large for one launch");
+    const BatchArgs batch{s.batch_stride, s.batch_stride_g, s.batches > 1 ? static_cast<uint32_t>(tiles) : 0u};
+    hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(blocks)), dim3(64 * WAVES), lds_bytes, s.stream,
+                       s.x, s.m, static_cast<const typename GradElem<GF>::type*>(s.g), s.d, s.ld, s.ldg,
+                       s.gamma, 1.0 / s.gamma, s.beta, batch, s.na, *s.topo);
+    return check_hip(hipGetLastError(), "step kernel launch");
+}
+
+// Workgroup shape by node count: as many waves as rows up to 16, then more rows per thread.
+template <int VEC, int ALGO, int GF, bool NORMS>
+int launch_rows(const StepCall& s) {
+#define DL_SHAPE(MAXN, W, R)                                                             \
+    if constexpr (VEC == 1 || VEC * (MAXN) <= (ALGO == ALGO_DA_DMSGD ? 64 : 128)) {        \
+        if (s.n <= (MAXN)) return launch_variant<VEC, R, W, ALGO, GF, NORMS>(s);         \
+    }
+    DL_SHAPE(1, 1, 1) DL_SHAPE(2, 2, 1) DL_SHAPE(4, 4, 1) DL_SHAPE(8, 8, 1) DL_SHAPE(16, 16, 1) DL_SHAPE(32, 16, 2)
+    DL_SHAPE(64, 16, 4) DL_SHAPE(128, 16, 8) DL_SHAPE(256, 16, 16)
+#undef DL_SHAPE
+    return set_error(DL_ETOPO, "step: n = %d has no kernel variant at vector width %d", s.n, VEC);
+}
+
+template <int ALGO, int GF, bool NORMS>
+int launch_cols(int vec, const StepCall& s) {
+    if (s.d <= 0) return DL_OK;
+    switch (vec) {
+        case 4: return launch_rows<4, ALGO, GF, NORMS>(s);
+        case 2: return launch_rows<2, ALGO, GF, NORMS>(s);
+        default: return launch_rows<1, ALGO, GF, NORMS>(s);
+    }
+}
+
+// 16-bit gradients exist for DecentLaM (both forms) and DmSGD, per-tensor sums for the (x, m) forms.
+template <int ALGO>
+int launch_extras(int vec, int format, bool norms, const StepCall& s) {
+    if constexpr (ALGO == ALGO_DECENTLAM || ALGO == ALGO_DMSGD) {
+        if (norms) {
+            if (format == DL_GRAD_BF16) return launch_cols<ALGO, DL_GRAD_BF16, true>(vec, s);
+            if (format == DL_GRAD_F16) return launch_cols<ALGO, DL_GRAD_F16, true>(vec, s);
+            return launch_cols<ALGO, DL_GRAD_F32, true>(vec, s);
+        }
+    }
+    if constexpr (ALGO == ALGO_DECENTLAM || ALGO == ALGO_DMSGD || ALGO == ALGO_DECENTLAM_XPREV) {
+        if (!norms) {
+            if (format == DL_GRAD_BF16) return launch_cols<ALGO, DL_GRAD_BF16, false>(vec, s);
+            if (format == DL_GRAD_F16) return launch_cols<ALGO, DL_GRAD_F16, false>(vec, s);
+        }
+    }
+    if (norms || format != DL_GRAD_F32)
+        return set_error(DL_EINVAL, "step: this method has no variant with 16-bit gradients / per-tensor sums");
+    return launch_cols<ALGO, DL_GRAD_F32, false>(vec, s);
+}
+
+
+}  // namespace
+#endif  // DL_STEP_KERNEL_IMPL
+
+}  // namespace step
+}  // namespace dl
