@@ -32,7 +32,7 @@ BYTES_PER_ELEMENT = 20         # read x, m, g + write x, m, fp32
 # HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by what
 # the same counter reads for a plain device copy of known size; profiles/*_hbm_traffic_pmc.txt),
 # keyed by (workload, algo); None where not measured.
-MEASURED_TRAFFIC_BYTES = {("c3_exp32", "decentlam"): 16_383_747_763,
+MEASURED_TRAFFIC_BYTES = {("c3_exp32", "decentlam"): 16_383_753_870,
                           ("c3_exp32", "decentlam_blocked"): 16_383_742_345,
                           ("c5_onepeer64_lsq", "local_grad_lsq"): 4_342_500_000}
 
@@ -157,6 +157,14 @@ def time_launches(fn, steps, warmup):
     return (t1 - t0) * 1e3 / steps, ev0.elapsed_time(ev1) / steps
 
 
+def padded_ld(d):
+    """Row stride the library's header recommends: rows start on 64 KiB boundaries when the arrays are
+    large (the step then writes whole 64 KiB-aligned address pairs, see split tiles in step_impl.hpp;
+    c3: 25 608 192 instead of 25 600 000 elements, +0.03 %), on 256-byte boundaries otherwise."""
+    unit = 16384 if d >= (1 << 20) else 64
+    return (d + unit - 1) // unit * unit
+
+
 def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False, detail=None, ld=None):
     import numpy as np
     import torch
@@ -166,11 +174,10 @@ def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False, 
     topo = P.topology_build(w.topo, w.n)
     gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
     step = getattr(P, algo + "_step")
-    # Row stride: rows start on 256-byte boundaries (ld = d rounded up to 64 elements).  With rows
-    # that are only 16-byte aligned every 1 KiB wave access straddles an extra cache line and the
-    # ragged workload loses about 17 % (measured 4.65 vs 5.60 TB/s).
+    # Row stride: see padded_ld.  (With rows that are only 16-byte aligned every 1 KiB wave access
+    # straddles an extra cache line and the ragged workload loses about 17 %: 4.65 vs 5.60 TB/s.)
     if ld is None:
-        ld = (d + 63) // 64 * 64
+        ld = padded_ld(d)
     xb = workloads.device_x0(w, "cuda", ld=ld)
     mb = torch.zeros_like(xb)
     gb = torch.zeros_like(xb)
@@ -241,8 +248,8 @@ def bench_xprev(P, workloads, name, steps, warmup):
 
 def bench_blocked(P, workloads, name, algo, steps, warmup, bw=8192, calibration_copy=False):
     """The same n x d step on arrays in the blocked layout (blocks of bw columns, each a row-major
-    n x bw matrix): the n rows a workgroup touches lie within n*bw*4 bytes and share address
-    translations, instead of being d*4 bytes apart."""
+    n x bw matrix): the n rows a workgroup touches lie within n*bw*4 bytes instead of being d*4 bytes
+    apart."""
     import numpy as np
     import torch
 
@@ -310,7 +317,7 @@ def bench_g16(P, workloads, name, steps, warmup, dtype_name="bfloat16"):
     d = workloads.generate.dim(w)
     topo = P.topology_build(w.topo, w.n)
     gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
-    ld = (d + 63) // 64 * 64
+    ld = padded_ld(d)
     xb = workloads.device_x0(w, "cuda", ld=ld)
     mb = torch.zeros_like(xb)
     g32 = torch.zeros_like(xb)
@@ -340,7 +347,7 @@ def bench_multi(P, workloads, name, steps, warmup):
     offsets = np.asarray(offsets, dtype=np.int64)
     topo = P.topology_build(w.topo, w.n)
     gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
-    ld = (d + 63) // 64 * 64
+    ld = padded_ld(d)
     x = workloads.device_x0(w, "cuda", ld=ld)
     m = torch.zeros_like(x)
     g = torch.zeros_like(x)
@@ -437,7 +444,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=10,
+                    help="untimed launches before the timed ones (the step time settles after about eight launches)")
     ap.add_argument("--workload", default="c3_exp32",
                     choices=["c3_exp32", "c4_ring16_ragged", "c5_onepeer64_lsq"])
     ap.add_argument("--algo", default="decentlam", choices=["decentlam", "dmsgd"])
@@ -553,18 +561,21 @@ def main():
             b2 = BYTES_PER_ELEMENT * w2.n * d2
             extras[f"{algo}_step_{name}"] = {"kernel_ms": round(k2, 4), "GBps": round(b2 / (k2 * 1e-3) / 1e9, 1),
                                              "frac_of_hbm_peak": round(b2 / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        # row-major with the rows padded to 128 MiB (ld = 2^25 elements): the row stride alone moves the
-        # row-major figure between 2.8 and 3.5 ms (address hashing); 2^25 was the best of a dozen tried
-        _, _, _, _, _, k3 = bench_step(P, workloads, "c3_exp32", "decentlam", args.steps, args.warmup, ld=1 << 25)
-        extras["decentlam_step_c3_exp32_ld_2pow25"] = {
-            "kernel_ms": round(k3, 4), "GBps": round(bytes_per_step / (k3 * 1e-3) / 1e9, 1),
-            "frac_of_hbm_peak": round(bytes_per_step / (k3 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        w3 = workloads.get("c3_exp32")
+        d3 = workloads.generate.dim(w3)
+        b3 = BYTES_PER_ELEMENT * w3.n * d3
+        # c3 with no padding at all (ld = d = 3125 x 32 KiB: odd rows start in the upper half of a
+        # 64 KiB unit, so only every other row can write whole address pairs)
+        _, _, _, _, _, k4 = bench_step(P, workloads, "c3_exp32", "decentlam", args.steps, args.warmup, ld=d3)
+        extras["decentlam_step_c3_exp32_ld_equals_d"] = {
+            "kernel_ms": round(k4, 4), "GBps": round(b3 / (k4 * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(b3 / (k4 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         extras["decentlam_step_xprev_c3_exp32"] = bench_xprev(P, workloads, "c3_exp32", args.steps, args.warmup)
         blk = bench_blocked(P, workloads, "c3_exp32", "decentlam", args.steps, args.warmup)
         extras["decentlam_step_blocked_c3_exp32"] = blk
         if (args.workload, args.algo) == ("c3_exp32", "decentlam"):
             # the same workload through decentlam_step_blocked (arrays stored in blocks of 8192 columns):
-            # same arithmetic, same bytes, no address-translation misses
+            # same arithmetic, same bytes
             out["roofline_blocked_layout"] = {
                 "bound": "hbm", "achieved": blk["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": blk["frac_of_hbm_peak"], "traffic": MEASURED_TRAFFIC_BYTES.get(("c3_exp32", "decentlam_blocked")),

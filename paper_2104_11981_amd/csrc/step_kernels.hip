@@ -34,6 +34,8 @@ using namespace step;
 
 // Widest access for which the fp64 tile of n rows takes 64 KiB of LDS, so that two workgroups
 // share a CU (VEC * n <= 128); beyond n = 128 the 4-byte variant uses up to 128 KiB.
+constexpr int64_t kSplitMinColumns = 1 << 20;   // below this a launch keeps plain tiles
+
 int widest_vec_for(int32_t n, Algo algo) {
     if (algo == ALGO_DA_DMSGD) n *= 2;   // two tiles
     if (n <= 32) return 4;
@@ -69,9 +71,10 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
     const int64_t body = ((d - head) / vec) * vec;
     const int64_t tail = d - head - body;
 
-    auto run = [&](int v, int64_t c0, int64_t cols) {
+    auto run = [&](int v, int64_t c0, int64_t cols, uint32_t split_tiles = 0) {
         if (cols <= 0) return static_cast<int>(DL_OK);
         StepCall s;
+        s.split_tiles = split_tiles;
         s.x = x + c0;
         s.m = m ? m + c0 : nullptr;
         s.g = static_cast<const char*>(g.p) + static_cast<size_t>(c0) * gbytes;
@@ -96,7 +99,20 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
             default: return launch_method<ALGO_DECENTLAM_XPREV>(v, g.format, norms != nullptr, s);
         }
     };
-    if (int rc = run(vec, head, body)) return rc;   // aligned body first: it is the bulk
+    // Large single problems with 16-byte lanes: split tiles (see split_column) from the first column at
+    // which the written array is 64 KiB-aligned, whole 64 KiB units only; what precedes is a launch
+    // of its own, what follows rides along as ordinary tiles of the same launch.  (The per-tensor sums
+    // need tiles that are column ranges.)
+    if (vec == 4 && batches == 1 && !norms && body >= kSplitMinColumns) {
+        const float* written = algo == ALGO_DECENTLAM_XPREV ? m : x;
+        const uintptr_t at = reinterpret_cast<uintptr_t>(written + head) % (4u * kSplitUnit);
+        const int64_t pre = at ? static_cast<int64_t>((4u * kSplitUnit - at) / 4) : 0;
+        const int64_t units = (body - pre) / kSplitUnit;
+        if (int rc = run(vec, head + pre, body - pre, static_cast<uint32_t>(units * kSplitTilesPerUnit))) return rc;
+        if (int rc = run(vec, head, pre)) return rc;
+    } else if (int rc = run(vec, head, body)) {   // aligned body first: it is the bulk
+        return rc;
+    }
     if (int rc = run(1, 0, head)) return rc;        // columns are independent, so the peeled
     if (int rc = run(1, head + body, tail)) return rc;  // head and tail are separate launches
     return DL_OK;

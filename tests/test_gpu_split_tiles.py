@@ -1,0 +1,90 @@
+"""GPU parity of the large-launch column order of the row-major step.
+
+From 2^20 columns on, a row-major launch with 16-byte lanes maps its tiles to two 512-byte segments
+32 KiB apart inside 64 KiB-aligned units of the written array (what precedes the first aligned column
+is a launch of its own, what follows the last whole unit rides along as ordinary tiles).  Every
+column must still be updated exactly once: a column left out keeps its old value, a column taken
+twice gets the update twice, and either fails the comparison with the oracle, which is made on every
+element.  Bases are placed at chosen distances from a 64 KiB boundary so that all three parts occur.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+UNIT = 16384   # columns per 64 KiB
+
+
+@pytest.fixture(scope="module")
+def P():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2104_11981_amd as pkg
+
+    return pkg
+
+
+def check_elementwise(gpu, ref, what):
+    err = np.abs(gpu.astype(np.float64) - ref)
+    tol = 1e-5 * (1.0 + np.abs(ref))
+    bad = err > tol
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} elements outside 1e-5*(1+|ref|), first at {np.argwhere(bad)[0]}"
+
+
+def placed(n, d, ld, skew, fill):
+    """n x d view with row stride ld whose first element lies `skew` elements past a 64 KiB boundary."""
+    buf = torch.full((n * ld + 2 * UNIT,), fill, dtype=torch.float32, device="cuda")
+    first = (-(buf.data_ptr() // 4)) % UNIT + skew
+    return buf, buf[first:first + n * ld].view(n, ld)[:, :d]
+
+
+CASES = [
+    # kind, n, d, ld - d, skew of x, m, g (elements past a 64 KiB boundary)
+    (0, 4, (1 << 20) + 2 * UNIT + 300, 0, (0, 0, 0)),               # aligned; ld not a multiple of a unit
+    (0, 4, (1 << 20) + 5 * UNIT, 3 * UNIT, (0, 0, 0)),              # whole units only, aligned rows
+    (1, 32, (1 << 20) + 77 * 4, 8188 - 77 * 4 + 4, (4, 4, 4)),      # 16 bytes past the boundary: a launch of 16380 columns first
+    (0, 16, (1 << 20) + UNIT + 1031, 1, (9000, 9000, 9000)),        # odd stride: narrow lanes, no split tiles at all
+    (2, 8, (1 << 20) + 3 * UNIT + 8, 8, (8, 4, 12)),                # arrays placed differently (the written x decides)
+    (1, 32, (1 << 20) + 40, UNIT - 40, (3, 3, 3)),                  # three elements off 16-byte alignment: head columns, then the rest
+]
+
+
+@pytest.mark.parametrize("algo", ["decentlam", "dmsgd", "dsgd", "xprev", "awc_dmsgd"])
+@pytest.mark.parametrize("kind,n,d,pad,skew", CASES)
+def test_large_row_major_launch_matches_oracle(P, oracle, algo, kind, n, d, pad, skew):
+    gamma, beta = float(np.float32(0.05)), float(np.float32(0.9))
+    topo = P.topology_build(kind, n)
+    otopo = oracle.topology(kind, n)
+    rng = np.random.default_rng(n * 7 + d)
+    x0, m0, g0 = (rng.standard_normal((n, d)).astype(np.float32) for _ in range(3))
+    ld = d + pad
+    SENT = 4242.0
+    (bx, x), (bm, m), (bg, g) = (placed(n, d, ld, s, SENT) for s in skew)
+    for view, a in ((x, x0), (m, m0), (g, g0)):
+        view.copy_(torch.from_numpy(a).cuda())
+    k = 1
+    if algo == "dsgd":
+        P.dsgd_step(x, g, topo, gamma, k)
+        xr = oracle.dsgd_step(x0, g0, otopo, gamma, k)
+        mr = m0.astype(np.float64)
+    elif algo == "xprev":
+        # state (x^k, x^{k-1}) = (x0, m0); the result lands in the x_prev buffer, x is only read
+        P.decentlam_step_xprev(x, m, g, topo, gamma, beta, k)
+        mr = oracle.decentlam_xprev_step(x0, m0, g0, otopo, gamma, beta, k)
+        xr = x0.astype(np.float64)
+    else:
+        getattr(P, algo + "_step")(x, m, g, topo, gamma, beta, k)
+        xr, mr = oracle.STEP[algo](x0, m0, g0, otopo, gamma, beta, k)
+    torch.cuda.synchronize()
+    check_elementwise(x.cpu().numpy(), xr, algo + " x")
+    check_elementwise(m.cpu().numpy(), mr, algo + " m")
+    np.testing.assert_array_equal(g.cpu().numpy(), g0)
+    for buf, view in ((bx, x), (bm, m), (bg, g)):   # nothing outside the views was written
+        full = buf.cpu().numpy()
+        inside = np.zeros(full.shape, dtype=bool)
+        first = (view.data_ptr() - buf.data_ptr()) // 4
+        for i in range(n):
+            inside[first + i * ld:first + i * ld + d] = True
+        assert np.all(full[~inside] == SENT)
