@@ -93,25 +93,26 @@ int pack_phase(const char* fn, int32_t n, const int32_t* row_ptr, const int32_t*
             return set_error(DL_ETOPO, "%s: phase %d row %d sums to %.9g, not 1", fn, p, i, sum);
     }
     out->row_ptr[n] = static_cast<uint16_t>(nnz);
-    // second pass: encode
-    if (few_values) {
-        out->palette = 1;
-        for (int v = 0; v < n_values; ++v) out->pal.value[v] = values[v];
+    // second pass: encode; the direct form while it fits (one load per entry in the kernel, where the
+    // palette needs a second, dependent one)
+    if (nnz <= DL_MAX_NNZ) {
+        out->palette = 0;
         for (int64_t q = 0; q < nnz; ++q) {
-            out->pal.col[q] = static_cast<uint8_t>(col_idx[base + q]);
-            int v = 0;
-            while (values[v] != w[base + q]) ++v;
-            out->pal.widx[q] = static_cast<uint8_t>(v);
+            out->direct.col[q] = static_cast<uint8_t>(col_idx[base + q]);
+            out->direct.w[q] = w[base + q];
         }
         return DL_OK;
     }
-    if (nnz > DL_MAX_NNZ)
+    if (!few_values)
         return set_error(DL_ETOPO, "%s: phase %d has %lld entries with more than %d distinct weights, "
                          "limit DL_MAX_NNZ = %d", fn, p, static_cast<long long>(nnz), kMaxWeightValues, DL_MAX_NNZ);
-    out->palette = 0;
+    out->palette = 1;
+    for (int v = 0; v < n_values; ++v) out->pal.value[v] = values[v];
     for (int64_t q = 0; q < nnz; ++q) {
-        out->direct.col[q] = static_cast<uint8_t>(col_idx[base + q]);
-        out->direct.w[q] = w[base + q];
+        out->pal.col[q] = static_cast<uint8_t>(col_idx[base + q]);
+        int v = 0;
+        while (values[v] != w[base + q]) ++v;
+        out->pal.widx[q] = static_cast<uint8_t>(v);
     }
     return DL_OK;
 }

@@ -154,37 +154,75 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
         if constexpr (ALGO != ALGO_DSGD) m += b * batch.stride;
         g += b * batch.stride_g;
     }
-    int64_t c = static_cast<int64_t>(tile) * TC + lane * VEC;
+    // First column of the tile (uniform) and the lane's offset inside it; see split_column.
+    int64_t tile_col = static_cast<int64_t>(tile) * TC;
+    int lane_col = lane * VEC;
     if constexpr (VEC == 4) {
-        if (tile < batch.split_tiles) c = split_column(tile, lane);   // uniform over the workgroup
+        if (tile < batch.split_tiles) {   // uniform over the workgroup
+            tile_col = split_column(tile, 0);
+            lane_col = static_cast<int>(split_column(0, lane));
+        }
     }
+    const int64_t c = tile_col + lane_col;
     const bool live = c < d;  // d is a multiple of VEC for this launch
 
-    // ---- phase 1: stream rows in
+    // Neighbour list: kernel arguments -> LDS table, one entry per thread and round.  In the direct
+    // form the first round's two loads go out here, ahead of the rows, and are used once the rows
+    // are on their way.
+    const uint32_t last_pair = reinterpret_cast<const uint32_t*>(topo.row_ptr)[n >> 1];   // uniform: a scalar load
+    const int nnz = (n & 1) ? last_pair >> 16 : last_pair & 0xffffu;
+    const bool direct = topo.palette == 0;   // uniform over the grid
+    const int e_mine = threadIdx.x;
+    // (no branch around these two loads, or they would be waited for at its end; in the palette form
+    // they read bytes of the other encoding, which nobody uses)
+    const int e_safe = e_mine < nnz && e_mine < DL_MAX_NNZ ? e_mine : 0;
+    const unsigned col_mine = topo.direct.col[e_safe];
+    const float w_mine = topo.direct.w[e_safe];
+    // ---- phase 1: stream rows in.  Every load is issued before anything waits for one: rows and
+    // lanes beyond the problem read the tile's first column of row 0 instead (in bounds, never used),
+    // so that no load sits inside a branch, and the row bases are uniform (scalar address
+    // arithmetic, one vector register of offsets for all loads).
     float xr[RPT][VEC], mr[RPT][VEC], gr[RPT][VEC];
     // NORMS: sums of squares that are complete before the barrier (g; the new m of DmSGD), reduced
     // over the wave right away and kept as scalars so that they cost no vector registers later
     double early[RPT][2];
+    const int safe_col = live ? lane_col : 0;
 #pragma unroll
     for (int r = 0; r < RPT; ++r) {
         const int i = wave + WAVES * r;
-        if (i < n && live) {
-            const int64_t at = static_cast<int64_t>(i) * ld + c;
-            load_vec<VEC>(x + at, xr[r]);
-            load_grad<VEC, GF>(g + static_cast<int64_t>(i) * ldg + c, gr[r]);
-            if constexpr (ALGO != ALGO_DSGD) load_vec<VEC>(m + at, mr[r]);
-        }
+        const int64_t row = i < n ? i : 0;   // uniform
+        load_vec<VEC>(x + (row * ld + tile_col) + safe_col, xr[r]);
+        load_grad<VEC, GF>(g + (row * ldg + tile_col) + safe_col, gr[r]);
+        if constexpr (ALGO != ALGO_DSGD) load_vec<VEC>(m + (row * ld + tile_col) + safe_col, mr[r]);
     }
-    // neighbour list: kernel arguments -> LDS table (one entry per thread and round)
-    const int nnz = topo.row_ptr[n];
-    for (int e = threadIdx.x; e < nnz; e += 64 * WAVES) {
+    // This wave's slices of the neighbour list (uniform, hence scalar loads): fetched now, used
+    // after the barrier, where a vector load from the kernel arguments would first wait for the
+    // stores of the row before it (loads and stores share one in-order counter).
+    int e_begin[RPT], e_end[RPT];
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) {
+        const int i = wave + WAVES * r;
+        const int row = i < n ? i : 0;
+        const uint32_t* pairs = reinterpret_cast<const uint32_t*>(topo.row_ptr);   // two offsets per word
+        const uint32_t lo = pairs[row >> 1], hi = pairs[(row + 1) >> 1];
+        e_begin[r] = (row & 1) ? lo >> 16 : lo & 0xffffu;
+        e_end[r] = (row & 1) ? hi & 0xffffu : hi >> 16;
+    }
+    if (direct && e_mine < nnz) {
         Neighbour t;
-        if (topo.palette) {  // uniform over the grid
-            t.w = static_cast<double>(topo.pal.value[topo.pal.widx[e]]);
-            t.offset = static_cast<int>(topo.pal.col[e]) * TC;
-        } else {
+        t.w = static_cast<double>(w_mine);
+        t.offset = static_cast<int>(col_mine) * TC;
+        t.unused = 0;
+        table[e_mine] = t;
+    }
+    for (int e = direct ? e_mine + 64 * WAVES : e_mine; e < nnz; e += 64 * WAVES) {   // later rounds; palette form
+        Neighbour t;
+        if (direct) {
             t.w = static_cast<double>(topo.direct.w[e]);
             t.offset = static_cast<int>(topo.direct.col[e]) * TC;
+        } else {
+            t.w = static_cast<double>(topo.pal.value[topo.pal.widx[e]]);
+            t.offset = static_cast<int>(topo.pal.col[e]) * TC;
         }
         t.unused = 0;
         table[e] = t;
@@ -194,7 +232,7 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
     for (int r = 0; r < RPT; ++r) {
         const int i = wave + WAVES * r;
         double sq_g = 0.0, sq_m = 0.0;   // this lane's share (NORMS)
-        if (i < n && live) {
+        if (i < n) {   // uniform; lanes beyond the problem work on the stand-in column and store nothing
             double* slot = lds + i * TC + lane;
             if constexpr (NORMS) {
 #pragma unroll
@@ -236,6 +274,7 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
             }
         }
         if constexpr (NORMS) {
+            if (!live) sq_g = sq_m = 0.0;
             if (i < n) {   // wave-uniform: all 64 lanes take part
                 if constexpr (ALGO == ALGO_DMSGD) {
                     const double both = wave_sum2(sq_g, sq_m, lane);   // lane 0: g, lane 1: m
@@ -247,6 +286,10 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
             }
         }
     }
+    // Every load has returned on every path from here on: said explicitly, or the compiler, unsure
+    // about paths that skipped a row, makes the second row's stores wait for the first row's
+    // (loads and stores share one in-order counter).
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), nothing else
     __syncthreads();
     // Odd waves start their second phase a little later (see stagger_units).
     constexpr int kStagger = stagger_units<VEC, RPT, WAVES, ALGO, GF, NORMS>();
@@ -260,12 +303,12 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
     for (int r = 0; r < RPT; ++r) {
         const int i = wave + WAVES * r;
         double sq_m = 0.0, sq_x = 0.0;   // this lane's share (NORMS)
-        if (i < n && live) {
+        if (i < n) {
             double z[VEC];
 #pragma unroll
             for (int v = 0; v < VEC; ++v) z[v] = 0.0;
-            int e = topo.row_ptr[i];
-            const int e1 = topo.row_ptr[i + 1];
+            int e = e_begin[r];
+            const int e1 = e_end[r];
             // groups of 4 (2 for 16-byte lanes: eight fp64 values in flight keep the kernel at
             // 64 VGPRs, i.e. two 1024-thread workgroups per CU), then 2, then 1
             if constexpr (VEC < 4) {
@@ -279,7 +322,7 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
             }
             for (; e < e1; ++e) gather<VEC, 1>(table + e, tile_at_lane, z);
 
-            const int64_t at = static_cast<int64_t>(i) * ld + c;
+            const int64_t at = (static_cast<int64_t>(i) * ld + tile_col) + lane_col;   // uniform base + lane offset
             float xo[VEC];
             if constexpr (ALGO == ALGO_DECENTLAM) {
                 float mo[VEC];
@@ -295,7 +338,7 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
                         sq_m = __builtin_fma(mv, mv, sq_m);
                     }
                 }
-                store_vec<VEC>(m + at, mo);
+                if (live) store_vec<VEC>(m + at, mo);
             } else if constexpr (ALGO == ALGO_DECENTLAM_XPREV) {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
@@ -310,26 +353,28 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
                     mo[v] = static_cast<float>(m_new);
                     xo[v] = static_cast<float>(z[v] - gamma * m_new);
                 }
-                store_vec<VEC>(m + at, mo);
+                if (live) store_vec<VEC>(m + at, mo);
             } else if constexpr (ALGO == ALGO_DA_DMSGD) {
                 double zm[VEC];   // second partial average, over the momentum tile
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) zm[v] = 0.0;
                 const double* m_tile_at_lane = tile_at_lane + n * TC;
-                for (int q = topo.row_ptr[i]; q < e1; ++q) gather<VEC, 1>(table + q, m_tile_at_lane, zm);
+                for (int q = e_begin[r]; q < e1; ++q) gather<VEC, 1>(table + q, m_tile_at_lane, zm);
                 float mo[VEC];
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
                     mo[v] = static_cast<float>(zm[v]);
                     xo[v] = static_cast<float>(z[v]);
                 }
-                store_vec<VEC>(m + at, mo);
+                if (live) store_vec<VEC>(m + at, mo);
             } else {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) xo[v] = static_cast<float>(z[v]);
-                if constexpr (ALGO == ALGO_DMSGD) store_vec<VEC>(m + at, mr[r]);
+                if constexpr (ALGO == ALGO_DMSGD) {
+                    if (live) store_vec<VEC>(m + at, mr[r]);
+                }
             }
-            store_vec<VEC>((ALGO == ALGO_DECENTLAM_XPREV ? m : x) + at, xo);
+            if (live) store_vec<VEC>((ALGO == ALGO_DECENTLAM_XPREV ? m : x) + at, xo);
             if constexpr (NORMS) {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
@@ -339,8 +384,9 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
             }
         }
         // per-tile sums of squares: one record of 3 doubles (g, new m, new x) per row and tile;
-        // lanes beyond the launch contributed zeros
+        // lanes beyond the launch contribute zeros
         if constexpr (NORMS) {
+            if (!live) sq_m = sq_x = 0.0;
             if (i < n) {
                 double* rec = na.partial + ((na.tile0 + blockIdx.x) * n + i) * 3;
                 if constexpr (ALGO == ALGO_DMSGD) {
