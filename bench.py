@@ -227,10 +227,11 @@ def bench_xprev(P, workloads, name, steps, warmup):
     d = workloads.generate.dim(w)
     topo = P.topology_build(w.topo, w.n)
     gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
-    bufs = [workloads.device_x0(w, "cuda")]
-    bufs.append(bufs[0].clone())
-    g = torch.empty_like(bufs[0])
-    workloads.device_grad(w, 0, g)
+    full = [workloads.device_x0(w, "cuda", ld=padded_ld(d))]
+    full.append(full[0].clone())
+    gb = torch.zeros_like(full[0])
+    workloads.device_grad(w, 0, gb)
+    bufs, g = [b[:, :d] for b in full], gb[:, :d]
     torch.cuda.synchronize()
 
     def step(k):
@@ -238,7 +239,7 @@ def bench_xprev(P, workloads, name, steps, warmup):
 
     _, kern_ms = time_launches(step, steps, warmup)
     nbytes = 16 * w.n * d
-    del bufs, g
+    del bufs, g, full, gb
     torch.cuda.empty_cache()
     return {"kernel_ms": round(kern_ms, 4), "bytes_per_node_element": 16,
             "GBps": round(nbytes / (kern_ms * 1e-3) / 1e9, 1),

@@ -107,6 +107,32 @@ __device__ __forceinline__ double wave_sum2(double a, double b, int lane) {
     v += __shfl_xor(v, 32, 64);
     return v;
 }
+// The same sums over each half of the wave (lanes 0-31, lanes 32-63): the last exchange is left out.
+__device__ __forceinline__ double half_sum(double v) {
+    v += dpp_f64<0xB1>(v);
+    v += dpp_f64<0x4E>(v);
+    v += dpp_f64<0x141>(v);
+    v += dpp_f64<0x140>(v);
+    v += __shfl_xor(v, 16, 64);
+    return v;
+}
+__device__ __forceinline__ double half_sum2(double a, double b, int lane) {
+    a += dpp_f64<0xB1>(a);
+    b += dpp_f64<0xB1>(b);
+    double v = (lane & 1) ? b : a;
+    v += dpp_f64<0x4E>(v);
+    v += dpp_f64<0x124>(v);
+    v += dpp_f64<0x128>(v);
+    v += __shfl_xor(v, 16, 64);
+    return v;
+}
+template <int LANE>
+__device__ __forceinline__ double lane_f64(double v) {   // the value of one lane as a scalar
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<int>(b), LANE);
+    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<int>(b >> 32), LANE);
+    return __builtin_bit_cast(double, (static_cast<uint64_t>(hi) << 32) | lo);
+}
 __device__ __forceinline__ double uniform_f64(double v) {   // lane 0's value as a scalar
     const uint64_t b = __builtin_bit_cast(uint64_t, v);
     const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<int>(b));

@@ -51,15 +51,17 @@ inline size_t grad_elem_bytes(int format) { return format == DL_GRAD_F32 ? 4 : 2
 
 // Per-tensor sums of squares fused into a step.  Tensor t is the column range
 // [offsets[t], offsets[t + 1]) of the caller's arrays.  Every workgroup of a step launch owns one
-// tile of columns and writes one record of n x 3 doubles (sums of squares of g, new m, new x over
-// the tile) with plain stores.  A final pass adds, for every tensor, the records of the tiles that
-// lie wholly inside it and sums the remaining edge columns directly from the arrays.
-constexpr int kMaxNormGrids = 3;   // aligned body, peeled head, peeled tail
+// tile of columns and writes records of n x 3 doubles (sums of squares of g, new m, new x) with
+// plain stores: one per tile, or with 16-byte lanes one per half tile, so that a record always
+// covers one range of `tc` columns and is numbered by it, whatever the column order of the launch.
+// A final pass adds, for every tensor, the records of the ranges that lie wholly inside it and sums
+// the remaining edge columns directly from the arrays.
+constexpr int kMaxNormGrids = 4;   // aligned body (in two launches when it starts off a 64 KiB boundary), peeled head, peeled tail
 struct NormGrid {
     int64_t col0;    // first column of the launch, relative to the first column of the step
     int64_t cols;    // columns covered by the launch
     int64_t tile0;   // index of the launch's first record in `partial`
-    int32_t tc;      // columns per tile
+    int32_t tc;      // columns per record (a tile; half a tile with 16-byte lanes)
 };
 struct NormPlan {
     const int64_t* offsets;   // host, num_tensors + 1; offsets[0] is the first column of the step

@@ -185,7 +185,10 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
     float xr[RPT][VEC], mr[RPT][VEC], gr[RPT][VEC];
     // NORMS: sums of squares that are complete before the barrier (g; the new m of DmSGD), reduced
     // over the wave right away and kept as scalars so that they cost no vector registers later
-    double early[RPT][2];
+    // With 16-byte lanes the sums are kept per half of the tile (lanes 0-31 and 32-63: 128 columns each,
+    // contiguous also in a split tile), so a record always covers one 128-column range.
+    constexpr int H = (NORMS && VEC == 4) ? 2 : 1;
+    double early[RPT][H][2];
     const int safe_col = live ? lane_col : 0;
 #pragma unroll
     for (int r = 0; r < RPT; ++r) {
@@ -277,11 +280,18 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
             if (!live) sq_g = sq_m = 0.0;
             if (i < n) {   // wave-uniform: all 64 lanes take part
                 if constexpr (ALGO == ALGO_DMSGD) {
-                    const double both = wave_sum2(sq_g, sq_m, lane);   // lane 0: g, lane 1: m
-                    early[r][0] = uniform_f64(both);
-                    early[r][1] = uniform_f64(dpp_f64<0xB1>(both));
+                    const double both = H == 2 ? half_sum2(sq_g, sq_m, lane) : wave_sum2(sq_g, sq_m, lane);   // even lanes: g, odd: m
+                    const double other = dpp_f64<0xB1>(both);
+                    early[r][0][0] = uniform_f64(both);
+                    early[r][0][1] = uniform_f64(other);
+                    if constexpr (H == 2) {
+                        early[r][1][0] = lane_f64<32>(both);
+                        early[r][1][1] = lane_f64<32>(other);
+                    }
                 } else {
-                    early[r][0] = uniform_f64(wave_sum(sq_g));
+                    const double sg = H == 2 ? half_sum(sq_g) : wave_sum(sq_g);
+                    early[r][0][0] = uniform_f64(sg);
+                    if constexpr (H == 2) early[r][1][0] = lane_f64<32>(sg);
                 }
             }
         }
@@ -383,18 +393,28 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
                 }
             }
         }
-        // per-tile sums of squares: one record of 3 doubles (g, new m, new x) per row and tile;
-        // lanes beyond the launch contribute zeros
+        // sums of squares: one record of 3 doubles (g, new m, new x) per row and tile, with 16-byte
+        // lanes per row and half tile; records are numbered by the columns they cover (column / 128
+        // of the launch, or tile index); lanes beyond the launch contribute zeros
         if constexpr (NORMS) {
             if (!live) sq_m = sq_x = 0.0;
             if (i < n) {
-                double* rec = na.partial + ((na.tile0 + blockIdx.x) * n + i) * 3;
+                int64_t record = blockIdx.x;
+                if constexpr (H == 2) {
+                    record = batch.tiles ? 2 * static_cast<int64_t>(blockIdx.x) : tile_col / 128;
+                    if (lane >= 32) record += lane_col >= kSplitDistance ? kSplitDistance / 128 : 1;
+                }
+                double* rec = na.partial + ((na.tile0 + record) * n + i) * 3;
+                const bool upper = H == 2 && lane >= 32;
+                const int hl = H == 2 ? lane & 31 : lane;
+                const double e0 = upper ? early[r][H - 1][0] : early[r][0][0];
                 if constexpr (ALGO == ALGO_DMSGD) {
-                    const double sx = wave_sum(sq_x);
-                    if (lane < 3) rec[lane] = lane == 0 ? early[r][0] : (lane == 1 ? early[r][1] : sx);
+                    const double e1 = upper ? early[r][H - 1][1] : early[r][0][1];
+                    const double sx = H == 2 ? half_sum(sq_x) : wave_sum(sq_x);
+                    if (hl < 3) rec[hl] = hl == 0 ? e0 : (hl == 1 ? e1 : sx);
                 } else {
-                    const double mx = wave_sum2(sq_m, sq_x, lane);   // lane 0: m, lane 1: x
-                    if (lane < 3) rec[(lane + 1) % 3] = lane == 2 ? early[r][0] : mx;
+                    const double mx = H == 2 ? half_sum2(sq_m, sq_x, lane) : wave_sum2(sq_m, sq_x, lane);   // even lanes: m, odd: x
+                    if (hl < 3) rec[(hl + 1) % 3] = hl == 2 ? e0 : mx;
                 }
             }
         }

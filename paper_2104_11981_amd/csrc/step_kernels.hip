@@ -83,12 +83,14 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
         s.na = NormArgs{nullptr, 0};
         s.batches = batches; s.batch_stride = batch_stride; s.batch_stride_g = batch_stride_g;
         if (norms) {
-            const int tc = 64 * v;
+            // records: one per tile, with 16-byte lanes one per half tile (128 columns)
+            const int tile_cols = 64 * v;
+            const int tc = v == 4 ? 128 : tile_cols;
             if (norms->grids >= kMaxNormGrids) return set_error(DL_EINVAL, "step: too many launches for the per-tensor sums");
             NormGrid& gr = norms->grid[norms->grids++];
             gr.col0 = norms->col_base + c0; gr.cols = cols * batches; gr.tile0 = norms->tiles_used; gr.tc = tc;
             s.na = NormArgs{norms->partial, gr.tile0};
-            norms->tiles_used += (cols + tc - 1) / tc * batches;
+            norms->tiles_used += (cols + tile_cols - 1) / tile_cols * (tile_cols / tc) * batches;
         }
         switch (algo) {
             case ALGO_DECENTLAM: return launch_method<ALGO_DECENTLAM>(v, g.format, norms != nullptr, s);
@@ -103,7 +105,7 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
     // which the written array is 64 KiB-aligned, whole 64 KiB units only; what precedes is a launch
     // of its own, what follows rides along as ordinary tiles of the same launch.  (The per-tensor sums
     // need tiles that are column ranges.)
-    if (vec == 4 && batches == 1 && !norms && body >= kSplitMinColumns) {
+    if (vec == 4 && batches == 1 && body >= kSplitMinColumns) {
         const float* written = algo == ALGO_DECENTLAM_XPREV ? m : x;
         const uintptr_t at = reinterpret_cast<uintptr_t>(written + head) % (4u * kSplitUnit);
         const int64_t pre = at ? static_cast<int64_t>((4u * kSplitUnit - at) / 4) : 0;
