@@ -32,7 +32,7 @@ BYTES_PER_ELEMENT = 20         # read x, m, g + write x, m, fp32
 # HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by what
 # the same counter reads for a plain device copy of known size; profiles/*_hbm_traffic_pmc.txt),
 # keyed by (workload, algo); None where not measured.
-MEASURED_TRAFFIC_BYTES = {("c3_exp32", "decentlam"): 16_383_753_870,
+MEASURED_TRAFFIC_BYTES = {("c3_exp32", "decentlam"): 16_383_750_981,
                           ("c3_exp32", "decentlam_blocked"): 16_383_742_345,
                           ("c5_onepeer64_lsq", "local_grad_lsq"): 4_342_500_000}
 

@@ -132,7 +132,7 @@ constexpr int stagger_units() {
 //        (mh = beta m + g; x <- W (x - gamma mh); m <- W mh: two tiles, h and mh, both gathered)
 // GF     dl_grad_format of g;  NORMS: accumulate the per-tensor sums of squares
 template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
-__global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8) ? 8 : 1) void k_step(float* __restrict__ x, float* __restrict__ m,
+__global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, float* __restrict__ m,
                                                       const typename GradElem<GF>::type* __restrict__ g,
                                                       int64_t d, int64_t ld, int64_t ldg,
                                                       double gamma, double inv_gamma, double beta,
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(64 * WAVES, (NORMS && WAVES == 16 && VEC * RPT == 8
                     gather<VEC, 2>(table + e, tile_at_lane, z);
                     e += 2;
                 }
-            } else if constexpr (!(NORMS && RPT >= 2)) {   // (with the sums: one at a time, to fit 64 VGPRs)
+            } else {
                 for (; e + 2 <= e1; e += 2) gather<VEC, 2>(table + e, tile_at_lane, z);
             }
             for (; e < e1; ++e) gather<VEC, 1>(table + e, tile_at_lane, z);
