@@ -105,12 +105,12 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
 
 // After the barrier all waves of a workgroup gather, compute and store at the same moment, and the
 // memory system sees the workgroup's 64 KiB of stores as one burst.  Letting the odd-numbered waves
-// (SIMDs 1 and 3) begin that phase 32-48 x 64 cycles later measured 4-8 % faster wherever the kernel
-// is bound by the mix of reads and writes: 16-byte lanes up to 32 nodes, every form that moves 14 B
-// per node-element or more.  Measured neutral or harmful, hence off: DSGD (12 B), 64 nodes and
-// more, the 16-wave single-row shape with less than 20 B, the variants with per-tensor sums.
-// A hand-over through a second barrier (odd waves wait for the even ones) was tried instead of the
-// fixed pause: better for DecentLaM at 32 nodes, worse everywhere else.
+// (SIMDs 1 and 3) begin that phase 32-48 x 64 cycles later measured 4-8 % faster while the kernel
+// still stalled on vector loads after the barrier; since it does not, the pause is worth about 1 %
+// (2.50 against 2.52 ms on the 32-node headline workload, both layouts) and is kept where it was
+// measured: 16-byte lanes up to 32 nodes, every form that moves 14 B per node-element or more.  Off
+// where it measured neutral or harmful: DSGD (12 B), 64 nodes and more, the 16-wave single-row shape
+// with less than 20 B, the variants with per-tensor sums.
 template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
 constexpr int stagger_units() {
     if (NORMS || VEC != 4 || ALGO == ALGO_DSGD || ALGO == ALGO_DA_DMSGD) return 0;
@@ -319,8 +319,8 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
             for (int v = 0; v < VEC; ++v) z[v] = 0.0;
             int e = e_begin[r];
             const int e1 = e_end[r];
-            // groups of 4 (2 for 16-byte lanes: eight fp64 values in flight keep the kernel at
-            // 64 VGPRs, i.e. two 1024-thread workgroups per CU), then 2, then 1
+            // groups of 4 (2 for 16-byte lanes: eight fp64 values in flight; the kernel must stay within
+            // 64 VGPRs for two 1024-thread workgroups per CU), then 2, then 1
             if constexpr (VEC < 4) {
                 for (; e + 4 <= e1; e += 4) gather<VEC, 4>(table + e, tile_at_lane, z);
                 if (e + 2 <= e1) {

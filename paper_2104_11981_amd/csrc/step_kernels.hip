@@ -6,12 +6,13 @@
 // TC = 64*VEC columns for ALL n rows:
 //
 //   phase 1  every wave streams whole rows of the tile (row index is wave-uniform):
-//            x_j, g_j, m_j come in with VEC*4-byte non-temporal loads, the local
-//            pre-step (u_j = x_j - gamma g_j for DecentLaM, h_j = x_j - gamma (beta m_j + g_j)
-//            for DmSGD) is evaluated in fp64 and parked in LDS as fp64 (each tile row as VEC
-//            planes of 64 doubles: bank-conflict free); meanwhile the neighbour list of W is
-//            unpacked from the kernel arguments into an LDS table of (fp64 weight, LDS row
-//            offset) pairs;
+//            x_j, g_j, m_j come in with VEC*4-byte non-temporal loads, all issued before anything
+//            waits for one; the local pre-step (u_j = x_j - gamma g_j for DecentLaM,
+//            h_j = x_j - gamma (beta m_j + g_j) for DmSGD) is evaluated in fp64 and parked in LDS
+//            as fp64 (each tile row as VEC planes of 64 doubles: bank-conflict free); meanwhile
+//            the neighbour list of W is unpacked from the kernel arguments into an LDS table of
+//            (fp64 weight, LDS row offset) pairs and every wave fetches the bounds of its rows'
+//            slices of that list with scalar loads;
 //   phase 2  after one barrier (and, for some shapes, a short pause of the odd-numbered waves
 //            that spreads the workgroup's stores), row i gathers its |N_i| neighbour rows from
 //            LDS in list order, finishes the update in fp64 and stores fp32 in place with
@@ -19,7 +20,8 @@
 //
 // HBM traffic is exactly read x, m, g + write x, m = 20 bytes per node-element,
 // independent of the node degree; updating in place is race-free because no
-// other workgroup touches these columns.
+// other workgroup touches these columns.  Which columns a tile owns is free: large row-major
+// launches use "split tiles" (step_impl.hpp), the column order this GPU's write path prefers.
 //
 // The same template serves DSGD, the momentum-free form of DecentLaM, AWC-DmSGD and DA-DmSGD, bf16 or
 // fp16 gradients (widened exactly on load), per-tile sums of squares of g, the new m and the new x
