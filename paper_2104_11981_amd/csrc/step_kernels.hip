@@ -34,14 +34,17 @@ namespace {
 
 using namespace step;
 
-// Widest access for which the fp64 tile of n rows takes 64 KiB of LDS, so that two workgroups
-// share a CU (VEC * n <= 128); beyond n = 128 the 4-byte variant uses up to 128 KiB.
 constexpr int64_t kSplitMinColumns = 1 << 20;   // below this a launch keeps plain tiles
 
+// Widest access by node count.  Up to 32 nodes the fp64 tile of 16-byte lanes takes 64 KiB of LDS and
+// two workgroups share a CU.  Beyond that the wide lanes are kept and the tile grows to 128 KiB, one
+// workgroup per CU: measured better than halving the lanes to keep two (64 nodes: 6.2 against 5.3 TB/s
+// row-major, 6.5 against 6.4 blocked; 128 nodes with 8-byte lanes: 6.4 against 5.5 blocked), because
+// the 16-byte lanes bring full 512-byte segments and their pairing (split tiles) with them.
 int widest_vec_for(int32_t n, Algo algo) {
     if (algo == ALGO_DA_DMSGD) n *= 2;   // two tiles
-    if (n <= 32) return 4;
-    if (n <= 64) return 2;
+    if (n <= 64) return 4;
+    if (n <= 128) return 2;
     return 1;
 }
 
