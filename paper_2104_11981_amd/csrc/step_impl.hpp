@@ -452,11 +452,11 @@ int launch_variant(const StepCall& s) {
 }
 
 // Workgroup shape by node count: as many waves as rows up to 16, then more rows per thread.  The fp64
-// tile (tiles, for DA-DmSGD) may take up to 128 KiB of LDS, see widest_vec_for.
+// tile may take up to 128 KiB of LDS (the two tiles of DA-DmSGD: 64 KiB), see widest_vec_for.
 template <int VEC, int ALGO, int GF, bool NORMS>
 int launch_rows(const StepCall& s) {
 #define DL_SHAPE(MAXN, W, R)                                                             \
-    if constexpr (VEC == 1 || VEC * (MAXN) <= (ALGO == ALGO_DA_DMSGD ? 128 : 256)) {        \
+    if constexpr (VEC == 1 || VEC * (MAXN) <= (ALGO == ALGO_DA_DMSGD ? 64 : 256)) {        \
         if (s.n <= (MAXN)) return launch_variant<VEC, R, W, ALGO, GF, NORMS>(s);         \
     }
     DL_SHAPE(1, 1, 1) DL_SHAPE(2, 2, 1) DL_SHAPE(4, 4, 1) DL_SHAPE(8, 8, 1) DL_SHAPE(16, 16, 1) DL_SHAPE(32, 16, 2)
