@@ -33,6 +33,12 @@ def sample_columns(d, seed, block=64, blocks=48, edge=1024):
     cols = [np.arange(0, min(edge, d)), np.arange(max(0, d - edge), d)]
     for s in rng.integers(0, max(1, d - block), size=blocks):
         cols.append(np.arange(s, s + block))
+    # the seams of the large-launch column order: around multiples of 8192 and 16384 columns, and
+    # where the last whole 64 KiB unit ends and ordinary tiles take over
+    last_unit = d // 16384 * 16384
+    for s in (8192, 16384, 3 * 8192, (d // 2) // 16384 * 16384 + 8192, last_unit - 8192, last_unit):
+        if 128 <= s <= d - 128:
+            cols.append(np.arange(s - 128, s + 128))
     return np.unique(np.concatenate(cols))
 
 
@@ -68,12 +74,17 @@ def run_sampled_trajectory(P, oracle, w, algo, kind, stepper=None, ld=None):
     return x, m
 
 
+@pytest.mark.parametrize("padded", [True, False], ids=["ld_64KiB", "ld_d"])
 @pytest.mark.parametrize("algo", ["decentlam", "dmsgd"])
-def test_workload3_n32_d25_6M_sampled_columns(P, oracle, algo):
-    """The headline configuration: n = 32, static exponential graph, d = 25.6 M, 20 iterations."""
+def test_workload3_n32_d25_6M_sampled_columns(P, oracle, algo, padded):
+    """The headline configuration: n = 32, static exponential graph, d = 25.6 M, 20 iterations, with the
+    row stride the benchmark uses (rows on 64 KiB boundaries) and with ld = d."""
     import workloads
+    from bench import padded_ld
 
-    run_sampled_trajectory(P, oracle, workloads.get("c3_exp32"), algo, 1)
+    w = workloads.get("c3_exp32")
+    d = workloads.generate.dim(w)
+    run_sampled_trajectory(P, oracle, w, algo, 1, ld=padded_ld(d) if padded else d)
 
 
 def test_workload4_ragged_flat_and_ranged_calls(P, oracle):
