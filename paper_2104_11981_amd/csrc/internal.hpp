@@ -19,7 +19,10 @@ constexpr int kMaxWeightValues = DL_MAX_WEIGHT_VALUES;
 struct PhaseArgs {
     int32_t n;
     int32_t palette;                     // 0: direct, 1: palette
-    uint16_t row_ptr[DL_MAX_NODES + 1];  // offsets relative to this phase
+    union {
+        uint16_t row_ptr[DL_MAX_NODES + 1];       // offsets relative to this phase
+        uint32_t row_ptr_pairs[DL_MAX_NODES / 2 + 1];   // the same, two per word: what the kernel's scalar loads fetch
+    };
     union {
         struct {
             uint8_t col[DL_MAX_NNZ];

@@ -8,6 +8,8 @@
 // sum_i (x_i - xbar)^2 = s2 - s1^2 / n without the cancellation of the raw-moment formula.
 // Partial sums go wave shuffle -> LDS -> one slot per workgroup; k_stats_finish adds the
 // slots in a fixed order, so results are reproducible bit for bit.
+#include <type_traits>
+
 #include "internal.hpp"
 
 namespace dl {
@@ -26,14 +28,18 @@ __device__ __forceinline__ double wave_sum(double v) {
 template <int VEC>
 __device__ __forceinline__ void load_cols(const float* __restrict__ p, float (&v)[VEC]) {
     if constexpr (VEC == 4) {
-        const vf4 t = *reinterpret_cast<const vf4*>(p);
+        const vf4 t = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(p));   // streamed once
         v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
     } else {
-        v[0] = *p;
+        v[0] = __builtin_nontemporal_load(p);
     }
 }
 
-template <int VEC>
+// HAS_M, HAS_REF: whether m and ref are given (compile-time, so that no load sits behind a test).
+// Rows are taken kRows at a time: all their loads go out before the first one is used (rows past the
+// last are clamped to it for the load and skipped in the sums).
+constexpr int kRows = 8;
+template <int VEC, bool HAS_M, bool HAS_REF>
 __global__ __launch_bounds__(kThreads) void k_stats(const float* __restrict__ x, const float* __restrict__ m,
                                                      const float* __restrict__ ref, int n, int64_t d,
                                                      int64_t ld, double* __restrict__ slots) {
@@ -45,30 +51,37 @@ __global__ __launch_bounds__(kThreads) void k_stats(const float* __restrict__ x,
          c += static_cast<int64_t>(gridDim.x) * kThreads * VEC) {  // d is a multiple of VEC for this launch
         float pv[VEC], rv[VEC];
         load_cols<VEC>(x + c, pv);
-        if (ref != nullptr) load_cols<VEC>(ref + c, rv);
+        if constexpr (HAS_REF) load_cols<VEC>(ref + c, rv);
         double s1[VEC], s2[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) s1[v] = s2[v] = 0.0;
-#pragma unroll 4
-        for (int i = 0; i < n; ++i) {
-            float xv[VEC];
-            load_cols<VEC>(x + static_cast<int64_t>(i) * ld + c, xv);
+        for (int i0 = 0; i0 < n; i0 += kRows) {
+            float xv[kRows][VEC], mv[kRows][VEC];
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                const double dev = static_cast<double>(xv[v]) - static_cast<double>(pv[v]);
-                s1[v] += dev;
-                s2[v] = __builtin_fma(dev, dev, s2[v]);
-                if (ref != nullptr) {
-                    const double e = static_cast<double>(xv[v]) - static_cast<double>(rv[v]);
-                    acc[2] = __builtin_fma(e, e, acc[2]);
-                }
+            for (int r = 0; r < kRows; ++r) {
+                const int64_t i = i0 + r < n ? i0 + r : n - 1;
+                load_cols<VEC>(x + i * ld + c, xv[r]);
+                if constexpr (HAS_M) load_cols<VEC>(m + i * ld + c, mv[r]);
             }
-            if (m != nullptr) {
-                float mv[VEC];
-                load_cols<VEC>(m + static_cast<int64_t>(i) * ld + c, mv);
 #pragma unroll
-                for (int v = 0; v < VEC; ++v)
-                    acc[4] = __builtin_fma(static_cast<double>(mv[v]), static_cast<double>(mv[v]), acc[4]);
+            for (int r = 0; r < kRows; ++r) {
+                if (i0 + r < n) {   // uniform
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        const double dev = static_cast<double>(xv[r][v]) - static_cast<double>(pv[v]);
+                        s1[v] += dev;
+                        s2[v] = __builtin_fma(dev, dev, s2[v]);
+                        if constexpr (HAS_REF) {
+                            const double e = static_cast<double>(xv[r][v]) - static_cast<double>(rv[v]);
+                            acc[2] = __builtin_fma(e, e, acc[2]);
+                        }
+                    }
+                    if constexpr (HAS_M) {
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v)
+                            acc[4] = __builtin_fma(static_cast<double>(mv[r][v]), static_cast<double>(mv[r][v]), acc[4]);
+                    }
+                }
             }
         }
         const double inv_n = 1.0 / static_cast<double>(n);
@@ -77,7 +90,7 @@ __global__ __launch_bounds__(kThreads) void k_stats(const float* __restrict__ x,
             acc[0] += s2[v] - s1[v] * s1[v] * inv_n;
             const double mean = static_cast<double>(pv[v]) + s1[v] * inv_n;
             acc[1] = __builtin_fma(mean, mean, acc[1]);
-            if (ref != nullptr) acc[3] = __builtin_fma(static_cast<double>(rv[v]), static_cast<double>(rv[v]), acc[3]);
+            if constexpr (HAS_REF) acc[3] = __builtin_fma(static_cast<double>(rv[v]), static_cast<double>(rv[v]), acc[3]);
         }
     }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -136,16 +149,23 @@ int launch_stats(const float* x, const float* m, const float* ref, int32_t n, in
     const int64_t body = vec4 ? (d / 4) * 4 : 0;
     const int64_t tail = d - body;
     const int64_t nb_body = blocks_for(body, 4), nb_tail = blocks_for(tail, 1);
+    auto launch = [&](auto vec_tag, int64_t blocks, const float* xp, const float* mp, const float* rp, int64_t cols,
+                      double* out_slots) {
+        constexpr int V = decltype(vec_tag)::value;
+        const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+        if (mp && rp) hipLaunchKernelGGL((k_stats<V, true, true>), grid, block, 0, stream, xp, mp, rp, n, cols, ld, out_slots);
+        else if (mp) hipLaunchKernelGGL((k_stats<V, true, false>), grid, block, 0, stream, xp, mp, rp, n, cols, ld, out_slots);
+        else if (rp) hipLaunchKernelGGL((k_stats<V, false, true>), grid, block, 0, stream, xp, mp, rp, n, cols, ld, out_slots);
+        else hipLaunchKernelGGL((k_stats<V, false, false>), grid, block, 0, stream, xp, mp, rp, n, cols, ld, out_slots);
+        return check_hip(hipGetLastError(), "stats kernel launch");
+    };
     if (nb_body > 0) {
-        hipLaunchKernelGGL(k_stats<4>, dim3(static_cast<unsigned>(nb_body)), dim3(kThreads), 0, stream, x, m, ref,
-                           n, body, ld, slots);
-        if (int rc = check_hip(hipGetLastError(), "stats kernel launch")) return rc;
+        if (int rc = launch(std::integral_constant<int, 4>(), nb_body, x, m, ref, body, slots)) return rc;
     }
     if (nb_tail > 0) {
-        hipLaunchKernelGGL(k_stats<1>, dim3(static_cast<unsigned>(nb_tail)), dim3(kThreads), 0, stream, x + body,
-                           m ? m + body : nullptr, ref ? ref + body : nullptr, n, tail, ld,
-                           slots + nb_body * kOut);
-        if (int rc = check_hip(hipGetLastError(), "stats kernel launch")) return rc;
+        if (int rc = launch(std::integral_constant<int, 1>(), nb_tail, x + body, m ? m + body : nullptr,
+                            ref ? ref + body : nullptr, tail, slots + nb_body * kOut))
+            return rc;
     }
     hipLaunchKernelGGL(k_stats_finish, dim3(1), dim3(kThreads), 0, stream, slots, nb_body + nb_tail, out);
     return check_hip(hipGetLastError(), "stats finish kernel launch");

@@ -169,7 +169,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
     // Neighbour list: kernel arguments -> LDS table, one entry per thread and round.  In the direct
     // form the first round's two loads go out here, ahead of the rows, and are used once the rows
     // are on their way.
-    const uint32_t last_pair = reinterpret_cast<const uint32_t*>(topo.row_ptr)[n >> 1];   // uniform: a scalar load
+    const uint32_t last_pair = topo.row_ptr_pairs[n >> 1];   // uniform: a scalar load
     const int nnz = (n & 1) ? last_pair >> 16 : last_pair & 0xffffu;
     const bool direct = topo.palette == 0;   // uniform over the grid
     const int e_mine = threadIdx.x;
@@ -206,8 +206,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
     for (int r = 0; r < RPT; ++r) {
         const int i = wave + WAVES * r;
         const int row = i < n ? i : 0;
-        const uint32_t* pairs = reinterpret_cast<const uint32_t*>(topo.row_ptr);   // two offsets per word
-        const uint32_t lo = pairs[row >> 1], hi = pairs[(row + 1) >> 1];
+        const uint32_t lo = topo.row_ptr_pairs[row >> 1], hi = topo.row_ptr_pairs[(row + 1) >> 1];   // two offsets per word
         e_begin[r] = (row & 1) ? lo >> 16 : lo & 0xffffu;
         e_end[r] = (row & 1) ? hi & 0xffffu : hi >> 16;
     }
