@@ -1,0 +1,61 @@
+"""Code-generation properties the step kernel's speed rests on, checked on the compiler's output.
+
+On gfx950 vector loads and stores share one in-order counter (`vmcnt`).  The headline kernel reached the
+rate of a bare stream only once (a) all six row loads of a wave were issued before anything waited for
+one of them and (b) nothing after the barrier waited on that counter: a single vector load there (the
+row offsets of W used to be one) makes the second row's gather wait for the first row's stores.  Both
+are easy to lose to an innocent source change, and no functional test would notice.
+"""
+import os
+import re
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+@pytest.fixture(scope="module")
+def headline_kernel_asm(tmp_path_factory):
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not installed")
+    from paper_2104_11981_amd import build
+
+    out = tmp_path_factory.mktemp("asm") / "step_decentlam.s"
+    flags = [f for f in build.FLAGS if f != "-fPIC"]
+    subprocess.run([HIPCC] + flags + ["-S", "--cuda-device-only", os.path.join(build.CSRC, "step_decentlam.hip"),
+                                      "-o", str(out)], check=True, capture_output=True)
+    text = out.read_text()
+    # k_step<VEC = 4, RPT = 2, WAVES = 16, DecentLaM, fp32 gradients, no per-tensor sums>: the 32-node shape
+    m = re.search(r"^(_ZN[^\n]*k_stepILi4ELi2ELi16ELi0ELi0ELb0E[^\n:]*):[^\n]*\n", text, re.M)
+    assert m, "headline instantiation not found in the assembly"
+    body = text[m.end():text.index(".Lfunc_end", m.end())]
+    return [ln.strip() for ln in body.split("\n") if ln.strip() and not ln.strip().startswith(";")]
+
+
+def test_row_loads_are_issued_before_the_first_wait_on_them(headline_kernel_asm):
+    wide = [k for k, ins in enumerate(headline_kernel_asm) if ins.startswith("global_load_dwordx4")]
+    assert len(wide) == 6, f"expected the six row loads (x, g, m of two rows), found {len(wide)}"
+    waits = [k for k, ins in enumerate(headline_kernel_asm) if ins.startswith("s_waitcnt") and "vmcnt" in ins]
+    assert waits, "no wait on the loads at all?"
+    assert all(k < waits[0] for k in wide[:5]), "a row load is issued only after a wait on an earlier one"
+    # the sixth may sit just inside the block that first uses it, but still before any wait
+    assert wide[5] < waits[0] or not any(wide[4] < w < wide[5] for w in waits)
+
+
+def test_nothing_after_the_barrier_waits_on_vector_memory(headline_kernel_asm):
+    barrier = [k for k, ins in enumerate(headline_kernel_asm) if ins.startswith("s_barrier")]
+    assert len(barrier) == 1
+    after = headline_kernel_asm[barrier[0]:]
+    assert not [ins for ins in after if ins.startswith("s_waitcnt") and "vmcnt" in ins]
+    assert not [ins for ins in after if ins.startswith(("global_load", "buffer_load", "flat_load"))]
+    assert len([ins for ins in after if ins.startswith("global_store_dwordx4")]) == 4   # m and x of two rows
+
+
+def test_headline_kernel_fits_two_workgroups_per_cu(headline_kernel_asm):
+    # 1024 threads per workgroup: two of them share a CU only up to 64 vector registers per lane
+    text = "\n".join(headline_kernel_asm)
+    m = re.search(r"\.amdhsa_next_free_vgpr\s+(\d+)", text)
+    assert m and int(m.group(1)) <= 64
+    assert not re.search(r"scratch_(load|store)", text)
