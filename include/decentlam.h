@@ -139,7 +139,7 @@ int topology_metropolis(int32_t n, const int32_t* row_ptr, const int32_t* col_id
  * 128-byte boundaries (16-byte aligned bases, ld a multiple of 32), and for arrays of a
  * million columns or more on 64 KiB boundaries (64 KiB-aligned bases, ld a multiple of
  * 16384): the step then writes whole 64 KiB-aligned address pairs (A, A + 32 KiB), worth
- * 5-10 % at every node count (measured at n = 32, d = 25.6 M: 2.77 instead of 2.90 ms).
+ * about 10 % at every node count (measured at n = 32, d = 25.6 M: 2.51 instead of 2.80 ms).
  * Errors: DL_EINVAL, DL_ETOPO, DL_EALIAS, DL_EHIP.
  */
 int decentlam_step(float* x, float* m, const float* g,
@@ -184,10 +184,11 @@ int decentlam_step_xprev(const float* x, float* x_prev, const float* g,
  * ceil(d / bw) * n * bw elements at most.  Nothing else changes: same arithmetic, same 20 bytes per
  * node-element.  The layout keeps the n rows a workgroup works on within n * bw * 4 bytes instead of
  * n rows that are d * 4 bytes apart; with row starts 32 KiB apart (bw = 8192) a tile's writes fill
- * whole 64 KiB-aligned address pairs and the call runs about 8 % faster than the row-major one at
- * n >= 16 (measured at n = 32: 6.3-6.4 instead of 5.9 TB/s).  A caller that owns its layout, as a simulation of n nodes on one GPU
- * does, should prefer it.  Let bw be a multiple of 64 and the bases 16-byte aligned for full-width
- * accesses.  Errors as decentlam_step; bw < 1 is DL_EINVAL.
+ * whole 64 KiB-aligned address pairs whatever d is.  Up to 32 nodes it runs at the rate of the
+ * row-major call with 64 KiB-aligned rows (measured at n = 32: 6.5 TB/s both) and 10 % faster than a
+ * row-major call whose rows are not so aligned; at 64 nodes and more it is the faster layout
+ * (n = 128: 6.4 instead of 5.1 TB/s).  Let bw be a multiple of 64 and the bases 16-byte aligned for
+ * full-width accesses.  Errors as decentlam_step; bw < 1 is DL_EINVAL.
  */
 int decentlam_step_blocked(float* x, float* m, const float* g,
                            int32_t n, int64_t d, int64_t bw,
