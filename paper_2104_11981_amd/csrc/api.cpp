@@ -134,25 +134,58 @@ size_t multi_workspace_bytes(int32_t n, int64_t d) {
     return static_cast<size_t>(norm_tiles_bound(d)) * static_cast<size_t>(n) * 3 * sizeof(double);
 }
 
+// Checks shared by every step entry point: scalar arguments and the presence of W.
+int check_step_scalars(const char* fn, Algo algo, int32_t n, int g_format, float gamma, float gamma_prev, float beta,
+                       int64_t k, int32_t period, const int32_t* row_ptr, const int32_t* col_idx, const float* w) {
+    if (algo == ALGO_DECENTLAM_XPREV && (!std::isfinite(gamma_prev) || !(gamma_prev > 0.0f)))
+        return set_error(DL_EINVAL, "%s: gamma_prev = %g must be finite and > 0", fn, static_cast<double>(gamma_prev));
+    if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
+    if (g_format != DL_GRAD_F32 && g_format != DL_GRAD_BF16 && g_format != DL_GRAD_F16)
+        return set_error(DL_EINVAL, "%s: g_format = %d is not a dl_grad_format", fn, g_format);
+    if (!std::isfinite(gamma) || !(gamma > 0.0f))
+        return set_error(DL_EINVAL, "%s: gamma = %g must be finite and > 0", fn, static_cast<double>(gamma));
+    if (!(beta >= 0.0f && beta < 1.0f))
+        return set_error(DL_EINVAL, "%s: beta = %g must lie in [0, 1)", fn, static_cast<double>(beta));
+    if (k < 0) return set_error(DL_EINVAL, "%s: k = %lld, need k >= 0", fn, static_cast<long long>(k));
+    if (period < 1) return set_error(DL_EINVAL, "%s: period = %d, need period >= 1", fn, period);
+    if (!row_ptr || !col_idx || !w)
+        return set_error(DL_EINVAL, "%s: row_ptr, col_idx and w must not be NULL", fn);
+    return DL_OK;
+}
+
+// The tensor table of a multi-tensor call: at least one tensor, offsets that do not decrease.
+int check_offsets(const char* fn, int32_t num_tensors, const int64_t* offsets) {
+    if (num_tensors < 1) return set_error(DL_EINVAL, "%s: num_tensors = %d, need >= 1", fn, num_tensors);
+    if (!offsets) return set_error(DL_EINVAL, "%s: offsets must not be NULL", fn);
+    if (offsets[0] < 0)
+        return set_error(DL_EINVAL, "%s: offsets[0] = %lld < 0", fn, static_cast<long long>(offsets[0]));
+    for (int32_t t = 0; t < num_tensors; ++t)
+        if (offsets[t + 1] < offsets[t]) return set_error(DL_EINVAL, "%s: offsets decrease at tensor %d", fn, t);
+    return DL_OK;
+}
+
+// Workspace and output of the per-tensor sums: present, large enough, 8-byte aligned.
+int check_norms_buffers(const char* fn, int32_t n, int64_t d, const void* workspace, size_t workspace_bytes,
+                        const double* norms) {
+    const size_t need = multi_workspace_bytes(n, d);
+    if (!workspace || workspace_bytes < need)
+        return set_error(DL_ECAP, "%s: workspace of %zu bytes needed, %zu given", fn, need,
+                         workspace ? workspace_bytes : size_t{0});
+    if ((reinterpret_cast<uintptr_t>(workspace) | reinterpret_cast<uintptr_t>(norms)) & 7u)
+        return set_error(DL_EINVAL, "%s: workspace and norms must be 8-byte aligned", fn);
+    return DL_OK;
+}
+
 int step_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int32_t n, int64_t d,
                int64_t ld, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
                int32_t period, float gamma, float beta, int64_t k, void* stream, float gamma_prev = 0.0f,
                const StepExtras& ex = StepExtras()) {
     clear_error();
-    if (algo == ALGO_DECENTLAM_XPREV && (!std::isfinite(gamma_prev) || !(gamma_prev > 0.0f)))
-        return set_error(DL_EINVAL, "%s: gamma_prev = %g must be finite and > 0", fn, static_cast<double>(gamma_prev));
-    if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
-    if (ex.g_format != DL_GRAD_F32 && ex.g_format != DL_GRAD_BF16 && ex.g_format != DL_GRAD_F16)
-        return set_error(DL_EINVAL, "%s: g_format = %d is not a dl_grad_format", fn, ex.g_format);
+    if (int rc = check_step_scalars(fn, algo, n, ex.g_format, gamma, gamma_prev, beta, k, period, row_ptr, col_idx, w))
+        return rc;
     int64_t col0 = 0;
     if (ex.multi) {   // the tensor table fixes the column range
-        if (ex.num_tensors < 1) return set_error(DL_EINVAL, "%s: num_tensors = %d, need >= 1", fn, ex.num_tensors);
-        if (!ex.offsets) return set_error(DL_EINVAL, "%s: offsets must not be NULL", fn);
-        if (ex.offsets[0] < 0) return set_error(DL_EINVAL, "%s: offsets[0] = %lld < 0", fn,
-                                                static_cast<long long>(ex.offsets[0]));
-        for (int32_t t = 0; t < ex.num_tensors; ++t)
-            if (ex.offsets[t + 1] < ex.offsets[t])
-                return set_error(DL_EINVAL, "%s: offsets decrease at tensor %d", fn, t);
+        if (int rc = check_offsets(fn, ex.num_tensors, ex.offsets)) return rc;
         col0 = ex.offsets[0];
         d = ex.offsets[ex.num_tensors] - col0;
         if (ex.offsets[ex.num_tensors] > ld)
@@ -166,14 +199,6 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int
     const int64_t ldg = ex.ldg < 0 ? ld : ex.ldg;
     if (ldg < col0 + d)
         return set_error(DL_EINVAL, "%s: ldg = %lld does not cover the columns", fn, static_cast<long long>(ldg));
-    if (!std::isfinite(gamma) || !(gamma > 0.0f))
-        return set_error(DL_EINVAL, "%s: gamma = %g must be finite and > 0", fn, static_cast<double>(gamma));
-    if (!(beta >= 0.0f && beta < 1.0f))
-        return set_error(DL_EINVAL, "%s: beta = %g must lie in [0, 1)", fn, static_cast<double>(beta));
-    if (k < 0) return set_error(DL_EINVAL, "%s: k = %lld, need k >= 0", fn, static_cast<long long>(k));
-    if (period < 1) return set_error(DL_EINVAL, "%s: period = %d, need period >= 1", fn, period);
-    if (!row_ptr || !col_idx || !w)
-        return set_error(DL_EINVAL, "%s: row_ptr, col_idx and w must not be NULL", fn);
 
     PhaseArgs topo;
     std::memset(&topo, 0, sizeof(topo));
@@ -181,12 +206,7 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int
 
     const bool want_norms = ex.multi && ex.norms != nullptr;
     if (want_norms) {
-        const size_t need = multi_workspace_bytes(n, d);
-        if (!ex.workspace || ex.workspace_bytes < need)
-            return set_error(DL_ECAP, "%s: workspace of %zu bytes needed, %zu given", fn, need,
-                             ex.workspace ? ex.workspace_bytes : size_t{0});
-        if ((reinterpret_cast<uintptr_t>(ex.workspace) | reinterpret_cast<uintptr_t>(ex.norms)) & 7u)
-            return set_error(DL_EINVAL, "%s: workspace and norms must be 8-byte aligned", fn);
+        if (int rc = check_norms_buffers(fn, n, d, ex.workspace, ex.workspace_bytes, ex.norms)) return rc;
     }
     if (d == 0 && !want_norms) return DL_OK;
     const bool uses_m = algo != ALGO_DSGD;
@@ -247,43 +267,22 @@ int blocked_entry(const char* fn, Algo algo, float* x, float* m, const void* g, 
                   float gamma_prev = 0.0f, const StepExtras* multi = nullptr) {
     clear_error();
     if (multi) {   // the tensor table fixes d
-        if (multi->num_tensors < 1)
-            return set_error(DL_EINVAL, "%s: num_tensors = %d, need >= 1", fn, multi->num_tensors);
-        if (!multi->offsets) return set_error(DL_EINVAL, "%s: offsets must not be NULL", fn);
+        if (int rc = check_offsets(fn, multi->num_tensors, multi->offsets)) return rc;
         if (multi->offsets[0] != 0)
             return set_error(DL_EINVAL, "%s: offsets[0] = %lld; in the blocked layout the table starts at column 0",
                              fn, static_cast<long long>(multi->offsets[0]));
-        for (int32_t t = 0; t < multi->num_tensors; ++t)
-            if (multi->offsets[t + 1] < multi->offsets[t])
-                return set_error(DL_EINVAL, "%s: offsets decrease at tensor %d", fn, t);
         d = multi->offsets[multi->num_tensors];
     }
-    if (g_format != DL_GRAD_F32 && g_format != DL_GRAD_BF16 && g_format != DL_GRAD_F16)
-        return set_error(DL_EINVAL, "%s: g_format = %d is not a dl_grad_format", fn, g_format);
-    if (algo == ALGO_DECENTLAM_XPREV && (!std::isfinite(gamma_prev) || !(gamma_prev > 0.0f)))
-        return set_error(DL_EINVAL, "%s: gamma_prev = %g must be finite and > 0", fn, static_cast<double>(gamma_prev));
-    if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
+    if (int rc = check_step_scalars(fn, algo, n, g_format, gamma, gamma_prev, beta, k, period, row_ptr, col_idx, w))
+        return rc;
     if (d < 0) return set_error(DL_EINVAL, "%s: d = %lld, need d >= 0", fn, static_cast<long long>(d));
     if (bw < 1) return set_error(DL_EINVAL, "%s: bw = %lld, need bw >= 1", fn, static_cast<long long>(bw));
-    if (!std::isfinite(gamma) || !(gamma > 0.0f))
-        return set_error(DL_EINVAL, "%s: gamma = %g must be finite and > 0", fn, static_cast<double>(gamma));
-    if (!(beta >= 0.0f && beta < 1.0f))
-        return set_error(DL_EINVAL, "%s: beta = %g must lie in [0, 1)", fn, static_cast<double>(beta));
-    if (k < 0) return set_error(DL_EINVAL, "%s: k = %lld, need k >= 0", fn, static_cast<long long>(k));
-    if (period < 1) return set_error(DL_EINVAL, "%s: period = %d, need period >= 1", fn, period);
-    if (!row_ptr || !col_idx || !w)
-        return set_error(DL_EINVAL, "%s: row_ptr, col_idx and w must not be NULL", fn);
     PhaseArgs topo;
     std::memset(&topo, 0, sizeof(topo));
     if (int rc = pack_phase(fn, n, row_ptr, col_idx, w, static_cast<int32_t>(k % period), &topo)) return rc;
     const bool want_norms = multi && multi->norms != nullptr;
     if (want_norms) {
-        const size_t need = multi_workspace_bytes(n, d);
-        if (!multi->workspace || multi->workspace_bytes < need)
-            return set_error(DL_ECAP, "%s: workspace of %zu bytes needed, %zu given", fn, need,
-                             multi->workspace ? multi->workspace_bytes : size_t{0});
-        if ((reinterpret_cast<uintptr_t>(multi->workspace) | reinterpret_cast<uintptr_t>(multi->norms)) & 7u)
-            return set_error(DL_EINVAL, "%s: workspace and norms must be 8-byte aligned", fn);
+        if (int rc = check_norms_buffers(fn, n, d, multi->workspace, multi->workspace_bytes, multi->norms)) return rc;
         // whole tiles per block and no peeled columns: the tile records then line up with the columns
         if (bw % 256 != 0 || ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m)) & 15u) ||
             (reinterpret_cast<uintptr_t>(g) & (4 * grad_elem_bytes(g_format) - 1)))
