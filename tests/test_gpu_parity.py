@@ -293,7 +293,7 @@ def test_workload2_trajectory_200_steps(P, oracle, name, ring, algo):
 
 # ---------------------------------------------------------------- diagnostics
 @pytest.mark.parametrize("n,d,pad,off", [(8, 1000, 0, 0), (32, 4099, 1, 0), (5, 7, 0, 0), (16, 2048, 4, 1),
-                                         (1, 300, 0, 0), (64, 513, 3, 0)])
+                                         (1, 300, 0, 0), (64, 513, 3, 0), (13, 777, 3, 0), (100, 132, 0, 0)])
 def test_stats_match_oracle(P, oracle, n, d, pad, off):
     rng = np.random.default_rng(n + d)
     x0 = (rng.standard_normal((n, d)) * 0.01 + rng.standard_normal(d) * 5.0).astype(np.float32)  # near consensus
@@ -314,6 +314,15 @@ def test_stats_match_oracle(P, oracle, n, d, pad, off):
     got = out.cpu().numpy()
     np.testing.assert_allclose(got[:2], ref[:2], rtol=1e-10, atol=1e-18)
     assert np.all(got[2:] == 0.0)
+    P.decentlam_stats(x, m, None, out, ws)             # each optional input on its own
+    got = out.cpu().numpy()
+    np.testing.assert_allclose(got[[0, 1, 4]], ref[[0, 1, 4]], rtol=1e-10, atol=1e-18)
+    assert np.all(got[2:4] == 0.0)
+    P.decentlam_stats(x, None, dev(r0), out, ws)
+    got = out.cpu().numpy()
+    np.testing.assert_allclose(got[:4], ref[:4], rtol=1e-10, atol=1e-18)
+    assert got[4] == 0.0
+    P.decentlam_stats(x, None, None, out, ws)
     out2 = torch.empty_like(out)
     P.decentlam_stats(x, None, None, out2, ws)
     assert torch.equal(out, out2)                      # fixed summation order
