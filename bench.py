@@ -247,6 +247,30 @@ def bench_xprev(P, workloads, name, steps, warmup):
             "steps_per_s": round(1e3 / kern_ms, 1)}
 
 
+def bench_stats(P, workloads, name, steps, warmup):
+    """decentlam_stats (consensus distance, mean norm, error against a reference, momentum norm) on the
+    workload's state: one pass over x and m, 8 bytes per node-element plus the reference vector."""
+    import torch
+
+    w = workloads.get(name)
+    d = workloads.generate.dim(w)
+    ld = padded_ld(d)
+    xb = workloads.device_x0(w, "cuda", ld=ld)
+    mb = torch.zeros_like(xb)
+    workloads.device_grad(w, 0, mb)
+    x, m = xb[:, :d], mb[:, :d]
+    ref = torch.zeros(d, dtype=torch.float32, device="cuda")
+    out = torch.empty(5, dtype=torch.float64, device="cuda")
+    ws = torch.empty(P.decentlam_stats_workspace(w.n, d), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    _, kern_ms = time_launches(lambda k: P.decentlam_stats(x, m, ref, out, ws), steps, warmup)
+    nbytes = 8 * w.n * d + 4 * d
+    del x, m, xb, mb, ref
+    torch.cuda.empty_cache()
+    return {"ms_per_call": round(kern_ms, 4), "GBps": round(nbytes / (kern_ms * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(nbytes / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
 def bench_blocked(P, workloads, name, algo, steps, warmup, bw=8192, calibration_copy=False):
     """The same n x d step on arrays in the blocked layout (blocks of bw columns, each a row-major
     n x bw matrix): the n rows a workgroup touches lie within n*bw*4 bytes instead of being d*4 bytes
@@ -590,6 +614,7 @@ def main():
         extras["decentlam_step_g16_bf16_c3_exp32"] = bench_g16(P, workloads, "c3_exp32", args.steps, args.warmup)
         extras["decentlam_step_multi_norms_c4_ring16_ragged"] = bench_multi(P, workloads, "c4_ring16_ragged",
                                                                              args.steps, args.warmup)
+        extras["decentlam_stats_c3_exp32"] = bench_stats(P, workloads, "c3_exp32", args.steps, args.warmup)
         extras["local_grad_lsq_c5"] = bench_lsq(P, workloads, "c5_onepeer64_lsq", args.steps, args.warmup)
         # the small least-squares workloads are cache-resident and latency-bound: microseconds only
         for small in ("c2_onepeer8_b32", "c2_onepeer8_b1024"):
