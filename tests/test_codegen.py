@@ -59,3 +59,51 @@ def test_headline_kernel_fits_two_workgroups_per_cu(headline_kernel_asm):
     m = re.search(r"\.amdhsa_next_free_vgpr\s+(\d+)", text)
     assert m and int(m.group(1)) <= 64
     assert not re.search(r"scratch_(load|store)", text)
+
+
+SPLIT_CHECK = r"""
+#include <cstdio>
+#include <vector>
+#include "step_impl.hpp"
+// Host run of the device function that maps (tile, lane) to columns in a split-tile launch: over
+// `units` whole 64 KiB units every column must be owned exactly once, a tile must consist of two runs
+// of 128 columns that lie 8192 columns apart inside one unit, and tile u + 1 must continue tile u.
+int main() {
+    using namespace dl::step;
+    const int units = 5;
+    std::vector<int> owner(static_cast<size_t>(units) * kSplitUnit, 0);
+    for (unsigned tile = 0; tile < static_cast<unsigned>(units * kSplitTilesPerUnit); ++tile) {
+        const long long first = split_column(tile, 0);
+        if (first != split_column(tile, 0) || first / kSplitUnit != tile / kSplitTilesPerUnit) return 1;
+        for (int lane = 0; lane < 64; ++lane) {
+            const long long c = split_column(tile, lane);
+            const long long expect = first + (lane >> 5) * kSplitDistance + (lane & 31) * 4;
+            if (c != expect) return 2;
+            if (c != split_column(tile, 0) + split_column(0, lane)) return 3;   // the kernel adds the two parts
+            for (int v = 0; v < 4; ++v) {
+                if (c + v < 0 || c + v >= static_cast<long long>(owner.size())) return 4;
+                owner[c + v] += 1;
+            }
+        }
+        if (tile % kSplitTilesPerUnit && split_column(tile, 0) != split_column(tile - 1, 0) + kSplitSegment) return 5;
+    }
+    for (int n : owner) if (n != 1) return 6;
+    if (kSplitSegment * 4 != 512 || kSplitDistance * 4 != 32768 || kSplitUnit * 4 != 65536) return 7;
+    std::puts("ok");
+    return 0;
+}
+"""
+
+
+def test_split_tile_column_map_owns_every_column_once(tmp_path):
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not installed")
+    from paper_2104_11981_amd import build
+
+    src = tmp_path / "split_check.hip"
+    src.write_text(SPLIT_CHECK)
+    exe = tmp_path / "split_check"
+    subprocess.run([HIPCC, "--cuda-host-only", "-O1", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", build.CSRC,
+                    str(src), "-o", str(exe)], check=True, capture_output=True)
+    run = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert run.returncode == 0 and run.stdout.strip() == "ok", f"check {run.returncode} failed"
