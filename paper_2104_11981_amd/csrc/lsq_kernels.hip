@@ -50,25 +50,30 @@ int row_splits(int32_t n, int32_t b, int64_t d) {
     return static_cast<int>(s);
 }
 
-// rows == nullptr: all b rows (bs == b); otherwise bs sampled rows per node
-template <bool VEC4>
+// rows == nullptr: all b rows (bs == b); otherwise bs sampled rows per node.
+// WIDE: a whole workgroup per row instead of one wave (few, long rows: a wave per row would leave
+// most of the GPU idle).
+template <bool VEC4, bool WIDE>
 __global__ __launch_bounds__(kThreads) void k_residual(const float* __restrict__ A,
                                                         const float* __restrict__ y,
                                                         const float* __restrict__ x,
                                                         double* __restrict__ res, int b, int64_t d,
                                                         int64_t ldA, int64_t ld,
                                                         const int32_t* __restrict__ rows, int bs) {
+    __shared__ double part[kThreads / 64];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i = blockIdx.y;
-    const int r = blockIdx.x * (kThreads / 64) + wave;
-    if (r >= bs) return;
+    const int r = WIDE ? blockIdx.x : blockIdx.x * (kThreads / 64) + wave;
+    if (r >= bs) return;   // WIDE: the whole workgroup leaves together
+    const int t = WIDE ? static_cast<int>(threadIdx.x) : lane;   // position in the row's team of threads
+    constexpr int kTeam = WIDE ? kThreads : 64;
     const int pr = rows ? physical_row(rows + static_cast<int64_t>(i) * bs, r, b) : r;
     const float* __restrict__ a = A + (static_cast<int64_t>(i) * b + pr) * ldA;
     const float* __restrict__ xi = x + static_cast<int64_t>(i) * ld;
     double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
     if constexpr (VEC4) {
-        for (int64_t c = lane * 4; c < d; c += 256) {  // d % 4 == 0 here
+        for (int64_t c = t * 4; c < d; c += kTeam * 4) {  // d % 4 == 0 here
             const vf4 av = *reinterpret_cast<const vf4*>(a + c);
             const vf4 xv = *reinterpret_cast<const vf4*>(xi + c);
             acc0 = __builtin_fma(static_cast<double>(av.x), static_cast<double>(xv.x), acc0);
@@ -77,11 +82,19 @@ __global__ __launch_bounds__(kThreads) void k_residual(const float* __restrict__
             acc3 = __builtin_fma(static_cast<double>(av.w), static_cast<double>(xv.w), acc3);
         }
     } else {
-        for (int64_t c = lane; c < d; c += 64)
+        for (int64_t c = t; c < d; c += kTeam)
             acc0 = __builtin_fma(static_cast<double>(a[c]), static_cast<double>(xi[c]), acc0);
     }
-    const double dot = wave_sum((acc0 + acc1) + (acc2 + acc3));
-    if (lane == 0) res[static_cast<int64_t>(i) * bs + r] = dot - static_cast<double>(y[static_cast<int64_t>(i) * b + pr]);
+    double dot = wave_sum((acc0 + acc1) + (acc2 + acc3));
+    if constexpr (WIDE) {
+        if (lane == 0) part[wave] = dot;
+        __syncthreads();
+        dot = (part[0] + part[1]) + (part[2] + part[3]);
+        if (threadIdx.x != 0) return;
+    } else {
+        if (lane != 0) return;
+    }
+    res[static_cast<int64_t>(i) * bs + r] = dot - static_cast<double>(y[static_cast<int64_t>(i) * b + pr]);
 }
 
 template <bool VEC4>
@@ -367,11 +380,17 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
         return check_hip(hipGetLastError(), "finish kernel launch");
     }
 
-    const dim3 grid_r(static_cast<unsigned>((bs + 3) / 4), static_cast<unsigned>(n));
-    if (vec4)
-        hipLaunchKernelGGL(k_residual<true>, grid_r, block, 0, stream, A, y, x, res, b, d, ldA, ld, rows, bs);
+    // few long rows: a workgroup per row (a wave per row would occupy n * bs / 4 workgroups only)
+    const bool wide = static_cast<int64_t>(n) * bs <= 4096 && d >= 4096;
+    const dim3 grid_r(static_cast<unsigned>(wide ? bs : (bs + 3) / 4), static_cast<unsigned>(n));
+    if (vec4 && wide)
+        hipLaunchKernelGGL((k_residual<true, true>), grid_r, block, 0, stream, A, y, x, res, b, d, ldA, ld, rows, bs);
+    else if (vec4)
+        hipLaunchKernelGGL((k_residual<true, false>), grid_r, block, 0, stream, A, y, x, res, b, d, ldA, ld, rows, bs);
+    else if (wide)
+        hipLaunchKernelGGL((k_residual<false, true>), grid_r, block, 0, stream, A, y, x, res, b, d, ldA, ld, rows, bs);
     else
-        hipLaunchKernelGGL(k_residual<false>, grid_r, block, 0, stream, A, y, x, res, b, d, ldA, ld, rows, bs);
+        hipLaunchKernelGGL((k_residual<false, false>), grid_r, block, 0, stream, A, y, x, res, b, d, ldA, ld, rows, bs);
     if (int rc = check_hip(hipGetLastError(), "residual kernel launch")) return rc;
 
     if (d > 0) {
