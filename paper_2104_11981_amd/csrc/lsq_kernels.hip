@@ -73,6 +73,7 @@ __global__ __launch_bounds__(kThreads) void k_residual(const float* __restrict__
     const float* __restrict__ xi = x + static_cast<int64_t>(i) * ld;
     double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
     if constexpr (VEC4) {
+#pragma unroll 4
         for (int64_t c = t * 4; c < d; c += kTeam * 4) {  // d % 4 == 0 here
             const vf4 av = *reinterpret_cast<const vf4*>(a + c);
             const vf4 xv = *reinterpret_cast<const vf4*>(xi + c);
