@@ -12,6 +12,10 @@
 // issued before the current tile's reduction.  Each workgroup owns a block of rows of one node
 // and leaves a partial gradient; k_finish_fused adds the partials in fixed order.
 //
+// Small problems (bs * d <= 4096 elements per node, any alignment): k_small, one launch,
+// one workgroup per node with A_i, x_i and the residuals in LDS; such sizes are bound by launch
+// latency, and this is one launch instead of two or three.
+//
 // Two sweeps (any shape and alignment):
 //   k_residual   one wave per row r of A_i: res[i][r] = A_i[r,:] . x_i - y_i[r]
 //                (lane-strided 16-byte loads, fp64 accumulators, wavefront-shuffle reduction)
@@ -318,6 +322,66 @@ __global__ __launch_bounds__(kThreads) void k_finish_fused(const double* __restr
     }
 }
 
+// ---------------------------------------------------------------- small problems
+constexpr int kSmallElements = 4096;   // floats of A_i kept in LDS; beyond, one workgroup per node is too little parallelism
+constexpr int kSmallD = 2048;
+constexpr int kSmallRows = 1024;
+
+bool small_problem(int32_t bs, int64_t d) {
+    return d >= 1 && d <= kSmallD && bs <= kSmallRows && static_cast<int64_t>(bs) * d <= kSmallElements;
+}
+size_t small_lds_bytes(int32_t bs, int64_t d) {
+    return static_cast<size_t>(bs) * sizeof(double) + (static_cast<size_t>(bs) * d + d) * sizeof(float);
+}
+
+// One workgroup per node.  LDS: res[bs] (fp64), then A_i as bs x d floats, then x_i.  Residuals: a
+// wave per row, lanes strided over the columns, fixed-order wave sum.  Gradient: a thread per column,
+// rows in order.  Everything in a fixed order: same inputs, same bits.
+__global__ __launch_bounds__(kThreads) void k_small(const float* __restrict__ A, const float* __restrict__ y,
+                                                     const float* __restrict__ x, float* __restrict__ g,
+                                                     float* __restrict__ loss, int b, int d, int64_t ldA,
+                                                     int64_t ld, const int32_t* __restrict__ rows, int bs,
+                                                     double scale) {
+    extern __shared__ double small_lds[];
+    double* res = small_lds;
+    float* As = reinterpret_cast<float*>(small_lds + bs);
+    float* xs = As + static_cast<size_t>(bs) * d;
+    const int i = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int32_t* __restrict__ rows_i = rows ? rows + static_cast<int64_t>(i) * bs : nullptr;
+    const float* __restrict__ a_node = A + static_cast<int64_t>(i) * b * ldA;
+    for (int c = threadIdx.x; c < d; c += kThreads) xs[c] = x[static_cast<int64_t>(i) * ld + c];
+    for (int r = wave; r < bs; r += kThreads / 64) {   // a wave copies a row: coalesced along the columns
+        const int pr = rows_i ? physical_row(rows_i, r, b) : r;
+        const float* __restrict__ a_row = a_node + static_cast<int64_t>(pr) * ldA;
+        for (int c = lane; c < d; c += 64) As[r * d + c] = a_row[c];
+    }
+    __syncthreads();
+    for (int r = wave; r < bs; r += kThreads / 64) {
+        double acc = 0.0;
+        for (int c = lane; c < d; c += 64)
+            acc = __builtin_fma(static_cast<double>(As[r * d + c]), static_cast<double>(xs[c]), acc);
+        const double dot = wave_sum(acc);
+        if (lane == 0) {
+            const int pr = rows_i ? physical_row(rows_i, r, b) : r;
+            res[r] = dot - static_cast<double>(y[static_cast<int64_t>(i) * b + pr]);
+        }
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < d; c += kThreads) {
+        double acc = 0.0;
+        for (int r = 0; r < bs; ++r) acc = __builtin_fma(static_cast<double>(As[r * d + c]), res[r], acc);
+        g[static_cast<int64_t>(i) * ld + c] = static_cast<float>(scale * acc);
+    }
+    if (loss != nullptr && wave == 0) {   // one wave, fixed order
+        double sq = 0.0;
+        for (int r = lane; r < bs; r += 64) sq = __builtin_fma(res[r], res[r], sq);
+        sq = wave_sum(sq);
+        if (lane == 0) loss[i] = static_cast<float>(0.5 * scale * sq);
+    }
+}
+
 // Row blocks per node for the single sweep: about two workgroups per CU in total, all resident
 // at once (measured best on 256 CUs: 512 workgroups; more, shorter ones lose up to 15 %), but at
 // least one double tile of rows each.
@@ -362,6 +426,18 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
     if (n > 65535 || splits > 65535) return set_error(DL_EINVAL, "local_grad_lsq: n too large for the launch grid");
 
     const dim3 block(kThreads);
+    if (small_problem(bs, d)) {
+        const size_t lds = small_lds_bytes(bs, d);
+        if (lds > 48 * 1024) {
+            if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(k_small),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)),
+                                   "hipFuncSetAttribute(max dynamic LDS)"))
+                return rc;
+        }
+        hipLaunchKernelGGL(k_small, dim3(static_cast<unsigned>(n)), block, lds, stream, A, y, x, g, loss, b,
+                           static_cast<int>(d), ldA, ld, rows, bs, static_cast<double>(scale));
+        return check_hip(hipGetLastError(), "small gradient kernel launch");
+    }
     if (vec4 && d > 0 && d <= kMaxFusedD) {
         const int cpt = fused_cpt(d);
         const int fs = fused_splits(n, bs, fused_rows(cpt));
