@@ -158,11 +158,13 @@ def time_launches(fn, steps, warmup):
 
 
 def padded_ld(d):
-    """Row stride the library's header recommends: rows start on 64 KiB boundaries when the arrays are
-    large (the step then writes whole 64 KiB-aligned address pairs, see split tiles in step_impl.hpp;
-    c3: 25 608 192 instead of 25 600 000 elements, +0.03 %), on 256-byte boundaries otherwise."""
-    unit = 16384 if d >= (1 << 20) else 64
-    return (d + unit - 1) // unit * unit
+    """Row stride the library recommends (paper_2104_11981_amd.recommended_ld): rows start on 64 KiB
+    boundaries when the arrays are large (the step then writes whole 64 KiB-aligned address pairs, see
+    split tiles in step_impl.hpp; c3: 25 608 192 instead of 25 600 000 elements, +0.03 %), on 256-byte
+    boundaries otherwise."""
+    from paper_2104_11981_amd import recommended_ld
+
+    return recommended_ld(d)
 
 
 def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False, detail=None, ld=None):

@@ -15,7 +15,7 @@ _BINDING_NAMES = (
     "EXPORTS", "LIB_PATH", "DecentLamError", "Topology",
     "decentlam_stats", "decentlam_stats_workspace", "decentlam_step", "decentlam_step_xprev",
     "dmsgd_step", "dsgd_step", "awc_dmsgd_step", "da_dmsgd_step", "decentlam_step_blocked",
-    "dmsgd_step_blocked", "to_blocked", "from_blocked", "decentlam_step_ex", "dmsgd_step_ex",
+    "dmsgd_step_blocked", "to_blocked", "from_blocked", "recommended_ld", "empty_rows", "decentlam_step_ex", "dmsgd_step_ex",
     "decentlam_step_xprev_ex", "decentlam_step_multi_ex", "dmsgd_step_multi_ex", "Layout", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
     "dmsgd_step_multi", "decentlam_step_multi_workspace", "last_error", "local_grad_lsq", "local_grad_lsq_workspace",
     "make_topology", "topology_build", "topology_metropolis",

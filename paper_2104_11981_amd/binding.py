@@ -231,6 +231,32 @@ def dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, s
     _step(_lib.dmsgd_step, x, m, g, topo, gamma, beta, k, stream)
 
 
+ROW_ALIGN_ELEMENTS = 16384   # 64 KiB of fp32: the row alignment the step kernel's large launches want
+
+
+def recommended_ld(d: int) -> int:
+    """Row stride (in elements) the header recommends for an n x d fp32 array: rows on 64 KiB boundaries
+    from a million columns on, on 256-byte boundaries below."""
+    unit = ROW_ALIGN_ELEMENTS if d >= (1 << 20) else 64
+    return (d + unit - 1) // unit * unit
+
+
+def empty_rows(n: int, d: int, device="cuda", dtype=None, fill=None):
+    """An n x d view (row-major, rows recommended_ld(d) apart, first row on a 64 KiB boundary) of a fresh
+    allocation: the layout in which the row-major step calls run fastest.  `fill`: initial value of the
+    view (None: uninitialised).  Memory handling only; no arithmetic of the method."""
+    dtype = torch.float32 if dtype is None else dtype
+    ld = recommended_ld(d)
+    item = torch.empty((), dtype=dtype).element_size()
+    slack = 65536 // item
+    buf = torch.empty(n * ld + slack, dtype=dtype, device=device)
+    first = (-(buf.data_ptr() // item)) % slack if buf.data_ptr() % item == 0 else 0
+    view = buf[first:first + n * ld].view(n, ld)[:, :d]
+    if fill is not None:
+        view.fill_(fill)
+    return view
+
+
 def to_blocked(a, bw: int, fill: float = 0.0):
     """Logical n x d tensor -> blocked layout tensor of shape (ceil(d / bw), n, bw) (a copy; padding = fill)."""
     n, d = a.shape

@@ -358,3 +358,18 @@ def test_general_step_argument_validation():
     assert f(0.1) == P.DL_OK and f(0.0) == P.DL_EINVAL
     layout.bw = 64
     assert f(0.1) == P.DL_OK and f(-1.0) == P.DL_EINVAL and "gamma_prev" in P.last_error()
+
+
+def test_recommended_row_layout_helpers():
+    """recommended_ld / empty_rows: rows on 64 KiB boundaries for large arrays, 256 bytes for small ones."""
+    import torch
+    import paper_2104_11981_amd as P
+
+    assert P.recommended_ld(25_600_000) == 25_608_192 and P.recommended_ld(25_608_192) == 25_608_192
+    assert P.recommended_ld(1 << 20) == 1 << 20 and P.recommended_ld((1 << 20) + 1) == (1 << 20) + 16384
+    assert P.recommended_ld(1000) == 1024 and P.recommended_ld(64) == 64 and P.recommended_ld(1) == 64
+    v = P.empty_rows(3, (1 << 20) + 5, device="cpu", fill=2.0)
+    assert tuple(v.shape) == (3, (1 << 20) + 5) and v.stride() == ((1 << 20) + 16384, 1)
+    assert v.data_ptr() % 65536 == 0 and float(v.sum()) == 2.0 * 3 * ((1 << 20) + 5)
+    h = P.empty_rows(2, 100, device="cpu", dtype=torch.bfloat16)
+    assert h.stride() == (128, 1) and h.data_ptr() % 65536 == 0
