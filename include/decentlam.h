@@ -259,8 +259,8 @@ int dmsgd_step_multi_ex(float* x, float* m, const void* g,
  *                  m_i <- beta m_i + g_i ;  x_i <- sum_{j in N_i} w_ij x_j - gamma m_i
  *   DA-DmSGD   (Algorithm 1 with an additional partial average over the momentum):
  *                  mh_i = beta m_i + g_i ;  x_i <- sum_j w_ij (x_j - gamma mh_j) ;  m_i <- sum_j w_ij mh_j
- * Arguments, conventions and errors as dmsgd_step; 20 bytes per node-element.  da_dmsgd_step keeps
- * two n-row tiles on chip and therefore takes n <= 128 (DL_ETOPO beyond what fits).
+ * Arguments, conventions and errors as dmsgd_step; 20 bytes per node-element (da_dmsgd_step uses
+ * its on-chip tile twice, for x - gamma mh and then for mh).
  */
 int awc_dmsgd_step(float* x, float* m, const float* g,
                    int32_t n, int64_t d, int64_t ld,

@@ -129,7 +129,7 @@ constexpr int stagger_units() {
 //        holds x_prev on entry and x_next on exit, x is only read, and `beta` carries
 //        beta' = beta * gamma / gamma_prev: 16 bytes per node-element, one written array;
 //        ALGO_AWC_DMSGD (m <- beta m + g; x <- W x - gamma m: the tile holds x) and ALGO_DA_DMSGD
-//        (mh = beta m + g; x <- W (x - gamma mh); m <- W mh: two tiles, h and mh, both gathered)
+//        (mh = beta m + g; x <- W (x - gamma mh); m <- W mh: the tile holds h, then mh, each gathered)
 // GF     dl_grad_format of g;  NORMS: accumulate the per-tensor sums of squares
 template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
 __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, float* __restrict__ m,
@@ -141,8 +141,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
     constexpr int TC = 64 * VEC;
     extern __shared__ double lds[];  // tile [n][TC] of u_j (DecentLaM) or h_j (DmSGD), then the table
     const int n = topo.n;
-    constexpr int TILES = ALGO == ALGO_DA_DMSGD ? 2 : 1;   // DA-DmSGD parks mh_j in a second tile
-    Neighbour* table = reinterpret_cast<Neighbour*>(lds + TILES * n * TC);
+    Neighbour* table = reinterpret_cast<Neighbour*>(lds + n * TC);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -248,10 +247,9 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                 for (int v = 0; v < VEC; ++v) slot[lds_col(v)] = static_cast<double>(xr[r][v]);
             } else if constexpr (ALGO == ALGO_DA_DMSGD) {
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) {
+                for (int v = 0; v < VEC; ++v) {   // h_j now; mh_j takes the tile over later
                     const double mh = beta * static_cast<double>(mr[r][v]) + static_cast<double>(gr[r][v]);
                     slot[lds_col(v)] = static_cast<double>(xr[r][v]) - gamma * mh;
-                    slot[n * TC + lds_col(v)] = mh;
                 }
             } else if constexpr (ALGO != ALGO_DMSGD) {
 #pragma unroll
@@ -363,20 +361,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                     xo[v] = static_cast<float>(z[v] - gamma * m_new);
                 }
                 if (live) store_vec<VEC>(m + at, mo);
-            } else if constexpr (ALGO == ALGO_DA_DMSGD) {
-                double zm[VEC];   // second partial average, over the momentum tile
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) zm[v] = 0.0;
-                const double* m_tile_at_lane = tile_at_lane + n * TC;
-                for (int q = e_begin[r]; q < e1; ++q) gather<VEC, 1>(table + q, m_tile_at_lane, zm);
-                float mo[VEC];
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    mo[v] = static_cast<float>(zm[v]);
-                    xo[v] = static_cast<float>(z[v]);
-                }
-                if (live) store_vec<VEC>(m + at, mo);
-            } else {
+            } else {   // DSGD, DmSGD; DA-DmSGD: x is done, its momentum follows below
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) xo[v] = static_cast<float>(z[v]);
                 if constexpr (ALGO == ALGO_DMSGD) {
@@ -418,6 +403,39 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
             }
         }
     }
+    // DA-DmSGD, second partial average: the same tile is used again for mh_j = beta m_j + g_j (recomputed
+    // from the registers), so that the fp64 tile stays at 64 KiB and two workgroups share a CU.
+    if constexpr (ALGO == ALGO_DA_DMSGD) {
+        __syncthreads();   // every wave has finished gathering h
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) {
+            const int i = wave + WAVES * r;
+            if (i < n) {
+                double* slot = lds + i * TC + lane;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+                    slot[lds_col(v)] = beta * static_cast<double>(mr[r][v]) + static_cast<double>(gr[r][v]);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) {
+            const int i = wave + WAVES * r;
+            if (i < n) {
+                double zm[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) zm[v] = 0.0;
+                int e = e_begin[r];
+                const int e1 = e_end[r];
+                for (; e + 2 <= e1; e += 2) gather<VEC, 2>(table + e, tile_at_lane, zm);
+                for (; e < e1; ++e) gather<VEC, 1>(table + e, tile_at_lane, zm);
+                float mo[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) mo[v] = static_cast<float>(zm[v]);
+                if (live) store_vec<VEC>(m + ((static_cast<int64_t>(i) * ld + tile_col) + lane_col), mo);
+            }
+        }
+    }
 }
 
 size_t lds_bytes_for(int32_t n, int vec, int nnz, int tiles) {
@@ -427,7 +445,7 @@ size_t lds_bytes_for(int32_t n, int vec, int nnz, int tiles) {
 template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
 int launch_variant(const StepCall& s) {
     constexpr int TC = 64 * VEC;
-    const size_t lds_bytes = lds_bytes_for(s.n, VEC, s.topo->row_ptr[s.n], ALGO == ALGO_DA_DMSGD ? 2 : 1);
+    const size_t lds_bytes = lds_bytes_for(s.n, VEC, s.topo->row_ptr[s.n], 1);
     auto kernel = k_step<VEC, RPT, WAVES, ALGO, GF, NORMS>;
     if (lds_bytes > 160 * 1024)
         return set_error(DL_ETOPO, "step: n = %d with %d entries needs %zu bytes of LDS, a CU has 163840", s.n,
@@ -451,11 +469,11 @@ int launch_variant(const StepCall& s) {
 }
 
 // Workgroup shape by node count: as many waves as rows up to 16, then more rows per thread.  The fp64
-// tile may take up to 128 KiB of LDS (the two tiles of DA-DmSGD: 64 KiB), see widest_vec_for.
+// tile may take up to 128 KiB of LDS, see widest_vec_for.
 template <int VEC, int ALGO, int GF, bool NORMS>
 int launch_rows(const StepCall& s) {
 #define DL_SHAPE(MAXN, W, R)                                                             \
-    if constexpr (VEC == 1 || VEC * (MAXN) <= (ALGO == ALGO_DA_DMSGD ? 64 : 256)) {        \
+    if constexpr (VEC == 1 || VEC * (MAXN) <= 256) {                                     \
         if (s.n <= (MAXN)) return launch_variant<VEC, R, W, ALGO, GF, NORMS>(s);         \
     }
     DL_SHAPE(1, 1, 1) DL_SHAPE(2, 2, 1) DL_SHAPE(4, 4, 1) DL_SHAPE(8, 8, 1) DL_SHAPE(16, 16, 1) DL_SHAPE(32, 16, 2)

@@ -41,9 +41,7 @@ constexpr int64_t kSplitMinColumns = 1 << 20;   // below this a launch keeps pla
 // workgroup per CU: measured better than halving the lanes to keep two (64 nodes: 6.2 against 5.3 TB/s
 // row-major, 6.5 against 6.4 blocked; 128 nodes with 8-byte lanes: 6.4 against 5.5 blocked), because
 // the 16-byte lanes bring full 512-byte segments and their pairing (split tiles) with them.
-int widest_vec_for(int32_t n, Algo algo) {
-    if (algo == ALGO_DA_DMSGD)   // two tiles, kept within 64 KiB together (at 32 nodes: 3.13 ms so, 3.57 ms with 128 KiB)
-        return n <= 16 ? 4 : n <= 32 ? 2 : 1;
+int widest_vec_for(int32_t n, Algo /*algo*/) {
     if (n <= 64) return 4;
     if (n <= 128) return 2;
     return 1;

@@ -58,15 +58,22 @@ def test_sibling_step_matches_oracle_every_iteration(P, oracle, algo, kind, n, d
         assert np.all(full[:, :off] == SENT) and np.all(full[:, off + d:] == SENT)
 
 
-def test_da_dmsgd_rejects_more_rows_than_fit_on_chip(P):
-    n, d = 256, 64
+def test_siblings_at_the_maximum_node_count(P, oracle):
+    """n = DL_MAX_NODES: both methods run with one fp64 tile of 256 rows (DA-DmSGD uses it twice)."""
+    n, d = 256, 70
     topo = P.topology_build(P.DL_TOPO_RING, n)
-    x = torch.zeros((n, d), device="cuda")
-    with pytest.raises(P.DecentLamError) as e:
-        P.da_dmsgd_step(x, torch.zeros_like(x), torch.zeros_like(x), topo, 0.1, 0.9, 0)
-    assert e.value.status == P.DL_ETOPO and "LDS" in str(e.value)
-    P.awc_dmsgd_step(x, torch.zeros_like(x), torch.zeros_like(x), topo, 0.1, 0.9, 0)   # one tile: fine
-    torch.cuda.synchronize()
+    otopo = oracle.topology(P.DL_TOPO_RING, n)
+    rng = np.random.default_rng(256)
+    x0, m0, g0 = (rng.standard_normal((n, d)).astype(np.float32) for _ in range(3))
+    gamma, beta = float(np.float32(0.1)), float(np.float32(0.9))
+    for algo in ("awc_dmsgd", "da_dmsgd"):
+        x, m, g = (torch.from_numpy(a).cuda() for a in (x0, m0, g0))
+        getattr(P, algo + "_step")(x, m, g, topo, gamma, beta, 0)
+        torch.cuda.synchronize()
+        xr, mr = oracle.STEP[algo](x0, m0, g0, otopo, gamma, beta, 0)
+        for got, ref, what in ((x, xr, "x"), (m, mr, "m")):
+            err = np.abs(got.cpu().numpy().astype(np.float64) - ref)
+            assert (err <= 1e-5 * (1.0 + np.abs(ref))).all(), f"{algo} {what}"
 
 
 @pytest.mark.parametrize("algo", ["awc_dmsgd", "da_dmsgd"])
