@@ -98,3 +98,45 @@ def test_random_combinations_match_oracle(P, oracle, method):
     rng = np.random.default_rng(2104_11981 + METHODS.index(method))
     for _ in range(40):
         one_case(P, oracle, rng, method)
+
+
+def test_random_gradient_shapes_match_oracle(P, oracle):
+    """local_grad_lsq / local_grad_lsq_rows on seeded random shapes: tiny problems (one launch), the
+    single sweep, the two-sweep path with a wave or a workgroup per row, odd strides, sampled rows."""
+    rng = np.random.default_rng(2104_11981 + 99)
+    for case in range(60):
+        n = int(rng.integers(1, 12))
+        b = int(rng.choice([1, 2, 5, 17, 50, 64, 200, 300]))
+        d = int(rng.choice([1, 7, 30, 64, 130, 1000, 1024, 2500, 4100, 8192, 8200, 9001]))
+        if n * b * d > 6_000_000:
+            b = max(1, 6_000_000 // (n * d))
+        pad_a, pad = int(rng.choice([0, 0, 1, 3, 4])), int(rng.choice([0, 0, 2, 4]))
+        scale = float(np.float32(rng.choice([1.0, 0.5, 1.0 / b])))
+        sampled = rng.random() < 0.4
+        what = f"case {case}: n={n} b={b} d={d} padA={pad_a} pad={pad} scale={scale:g} sampled={sampled}"
+        A0 = rng.standard_normal((n, b, d)).astype(np.float32)
+        y0 = rng.standard_normal((n, b)).astype(np.float32)
+        x0 = rng.standard_normal((n, d)).astype(np.float32)
+        Ab = torch.full((n, b, d + pad_a), 7.0, device="cuda")
+        A = Ab[:, :, :d]
+        A.copy_(torch.from_numpy(A0).cuda())
+        xb = torch.full((n, d + pad), 7.0, device="cuda")
+        gb = torch.full((n, d + pad), 7.0, device="cuda")
+        x, g = xb[:, :d], gb[:, :d]
+        x.copy_(torch.from_numpy(x0).cuda())
+        y = torch.from_numpy(y0).cuda()
+        loss = torch.empty(n, device="cuda")
+        if sampled:
+            bs = int(rng.integers(1, 2 * b + 1))
+            rows0 = rng.integers(0, b, size=(n, bs)).astype(np.int32)
+            ws = torch.empty(P.local_grad_lsq_workspace(n, bs, d), dtype=torch.uint8, device="cuda")
+            P.local_grad_lsq(A, y, x, g, loss, scale, ws, rows=torch.from_numpy(rows0).cuda())
+            gr, lr = oracle.lsq_grad_rows(A0, y0, x0, rows0, scale)
+        else:
+            ws = torch.empty(P.local_grad_lsq_workspace(n, b, d), dtype=torch.uint8, device="cuda")
+            P.local_grad_lsq(A, y, x, g, loss, scale, ws)
+            gr, lr = oracle.lsq_grad(A0, y0, x0, scale)
+        torch.cuda.synchronize()
+        check(g.cpu().numpy(), gr, what + ": g")
+        check(loss.cpu().numpy(), lr, what + ": loss")
+        assert np.all(gb.cpu().numpy()[:, d:] == 7.0), what + ": padding written"
