@@ -197,7 +197,16 @@ def make_topology(n: int, row_ptr, col_idx, w, period: int = 1) -> Topology:
                     np.ascontiguousarray(col_idx, np.int32), np.ascontiguousarray(w, np.float32))
 
 
+_raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+_raw_device = getattr(torch._C, "_cuda_getDevice", None)
+
+
 def _stream() -> int:
+    """Handle of torch's current stream on the current device.  The small workloads are bound by the
+    host's call rate, and torch.cuda.current_stream() alone costs about 3 us: the two C accessors
+    behind it are used directly where this torch has them."""
+    if _raw_stream is not None and _raw_device is not None:
+        return _raw_stream(_raw_device())
     return torch.cuda.current_stream().cuda_stream
 
 
