@@ -140,3 +140,33 @@ def test_random_gradient_shapes_match_oracle(P, oracle):
         check(g.cpu().numpy(), gr, what + ": g")
         check(loss.cpu().numpy(), lr, what + ": loss")
         assert np.all(gb.cpu().numpy()[:, d:] == 7.0), what + ": padding written"
+
+
+SCALES = [   # magnitude of x, g, m; gamma
+    (1e7, 1.0, 1e9, 1e-3),      # large state, small learning rate: ulp(x)/gamma would swamp m in fp32 arithmetic
+    (1e30, 1e20, 1e30, 1e-4),   # near the top of the fp32 range
+    (1.0, 1e6, 0.0, 1e-6),      # tiny learning rate, first iteration
+    (1e-20, 1e-20, 1e-20, 0.1),
+    (1e-38, 1e-38, 1e-38, 0.5),  # subnormal fp32 inputs
+]
+
+
+@pytest.mark.parametrize("xs,gs,ms,gamma", SCALES)
+@pytest.mark.parametrize("algo", ["decentlam", "dmsgd"])
+def test_tolerance_holds_in_every_scale_regime(P, oracle, algo, xs, gs, ms, gamma):
+    """|gpu - ref| <= 1e-5 (1 + |ref|) whatever the magnitudes: the kernel evaluates in fp64 and rounds
+    once, so its error is one fp32 rounding of the oracle's value (err / tol <= 2^-24 / 1e-5 = 0.006)."""
+    n, d = 32, 3000
+    topo = P.topology_build(1, n)
+    otopo = oracle.topology(1, n)
+    rng = np.random.default_rng(int(-np.log10(gamma)) + 17)
+    x0, m0, g0 = ((rng.standard_normal((n, d)) * s).astype(np.float32) for s in (xs, ms, gs))
+    g32, beta = float(np.float32(gamma)), float(np.float32(0.9))
+    x, m, g = (torch.from_numpy(a).cuda() for a in (x0, m0, g0))
+    getattr(P, algo + "_step")(x, m, g, topo, g32, beta, 1)
+    xr, mr = oracle.STEP[algo](x0, m0, g0, otopo, g32, beta, 1)
+    for got, ref, what in ((x, xr, "x"), (m, mr, "m")):
+        assert np.isfinite(ref.astype(np.float32)).all()
+        err = np.abs(got.cpu().numpy().astype(np.float64) - ref)
+        ratio = (err / (1e-5 * (1.0 + np.abs(ref)))).max()
+        assert ratio <= 0.0061, f"{algo} {what}: worst err/tol {ratio:.4f}"
