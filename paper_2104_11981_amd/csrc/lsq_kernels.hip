@@ -5,7 +5,7 @@
 // The bound is HBM, and the kernels are organised around streaming A with wide
 // coalesced loads; products are exact in fp64 (two fp32 factors) and sums are fp64.
 //
-// Single sweep (rows 16-byte aligned, d <= 8192): k_fused keeps a tile of R rows of A_i in
+// Single sweep (rows 16-byte aligned, d <= 16384; 256 threads up to d = 8192, 512 beyond): k_fused keeps a tile of R rows of A_i in
 // registers, split by columns over the 256 threads of a workgroup; the R residuals are reduced
 // with wavefront shuffles plus one LDS hop, then the same registers feed the transposed
 // product, so A is read from HBM exactly once (4*b*d bytes per node).  The next tile's loads are
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(kThreads) void k_finish(const double* __restrict__ 
 
 
 // ---------------------------------------------------------------- single sweep
-// CPT  16-byte column chunks per thread (thread t owns columns 4t + 1024q .. +3, q < CPT)
+// CPT  16-byte column chunks per thread (thread t owns columns 4t + 4 THREADS q .. +3, q < CPT)
 // R    rows of A per register tile
 template <int CPT, int R>
 struct Tile {
@@ -194,7 +194,7 @@ __device__ __forceinline__ void load_tile(Tile<CPT, R>& t, const float* __restri
     }
 }
 
-template <int CPT, int R>
+template <int CPT, int R, int WAVES>
 __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float (&xs)[CPT][4],
                                              double (&acc)[CPT][4], double& sq, double (*red)[R],
                                              const float* __restrict__ yi, int r, int r1, int lane, int wave,
@@ -230,7 +230,11 @@ __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float 
         double res = 0.0;
         if (r + rr < r1) {  // uniform over the workgroup
             const int pr = rows_i ? physical_row(rows_i, r + rr, b) : r + rr;
-            res = ((red[0][rr] + red[1][rr]) + (red[2][rr] + red[3][rr])) - static_cast<double>(yi[pr]);
+            double dot = 0.0;   // the waves' shares in a fixed order
+#pragma unroll
+            for (int w4 = 0; w4 < WAVES; w4 += 4)
+                dot += (red[w4][rr] + red[w4 + 1][rr]) + (red[w4 + 2][rr] + red[w4 + 3][rr]);
+            res = dot - static_cast<double>(yi[pr]);
         }
         sq = __builtin_fma(res, res, sq);
 #pragma unroll
@@ -243,13 +247,16 @@ __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float 
     }
 }
 
-template <int CPT, int R, bool PF>
-__global__ __launch_bounds__(kThreads, (PF || CPT >= 8) ? 2 : 4) void k_fused(const float* __restrict__ A, const float* __restrict__ y,
+// THREADS: 256 up to d = 8192; 512 threads (same columns per thread, more threads) carry the single
+// sweep to d = 16384
+template <int CPT, int R, bool PF, int THREADS>
+__global__ __launch_bounds__(THREADS, THREADS > 256 ? 1 : ((PF || CPT >= 8) ? 2 : 4)) void k_fused(const float* __restrict__ A, const float* __restrict__ y,
                                                      const float* __restrict__ x, double* __restrict__ partial,
                                                      double* __restrict__ sq_partial, int b, int64_t d,
                                                      int64_t ldA, int64_t ld, int splits,
                                                      const int32_t* __restrict__ rows, int bs) {
-    __shared__ double red[2][kThreads / 64][R];  // two buffers: one barrier per tile is enough
+    constexpr int WAVES = THREADS / 64;
+    __shared__ double red[2][WAVES][R];  // two buffers: one barrier per tile is enough
     const int i = blockIdx.y, s = blockIdx.x;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -262,7 +269,7 @@ __global__ __launch_bounds__(kThreads, (PF || CPT >= 8) ? 2 : 4) void k_fused(co
     double acc[CPT][4];
 #pragma unroll
     for (int q = 0; q < CPT; ++q) {
-        const int c = 4 * static_cast<int>(threadIdx.x) + 1024 * q;
+        const int c = 4 * static_cast<int>(threadIdx.x) + 4 * THREADS * q;
         const bool inside = c < d;
         col[q] = inside ? c : static_cast<int>(d) - 4;
         const vf4 xv = *reinterpret_cast<const vf4*>(x + static_cast<int64_t>(i) * ld + col[q]);
@@ -279,23 +286,23 @@ __global__ __launch_bounds__(kThreads, (PF || CPT >= 8) ? 2 : 4) void k_fused(co
         load_tile<CPT, R>(t0, a_node, ldA, r0, r1 - 1, col, rows_i, b);
         for (int r = r0; r < r1; r += 2 * R) {
             load_tile<CPT, R>(t1, a_node, ldA, r + R, r1 - 1, col, rows_i, b);
-            consume_tile<CPT, R>(t0, xs, acc, sq, red[0], yi, r, r1, lane, wave, rows_i, b);
+            consume_tile<CPT, R, WAVES>(t0, xs, acc, sq, red[0], yi, r, r1, lane, wave, rows_i, b);
             load_tile<CPT, R>(t0, a_node, ldA, r + 2 * R, r1 - 1, col, rows_i, b);
-            consume_tile<CPT, R>(t1, xs, acc, sq, red[1], yi, r + R, r1, lane, wave, rows_i, b);
+            consume_tile<CPT, R, WAVES>(t1, xs, acc, sq, red[1], yi, r + R, r1, lane, wave, rows_i, b);
         }
     } else {
         Tile<CPT, R> t0;
         int buf = 0;
         for (int r = r0; r < r1; r += R, buf ^= 1) {
             load_tile<CPT, R>(t0, a_node, ldA, r, r1 - 1, col, rows_i, b);
-            consume_tile<CPT, R>(t0, xs, acc, sq, red[buf], yi, r, r1, lane, wave, rows_i, b);
+            consume_tile<CPT, R, WAVES>(t0, xs, acc, sq, red[buf], yi, r, r1, lane, wave, rows_i, b);
         }
     }
 
     double* out = partial + (static_cast<int64_t>(i) * splits + s) * d;
 #pragma unroll
     for (int q = 0; q < CPT; ++q) {
-        const int c = 4 * static_cast<int>(threadIdx.x) + 1024 * q;
+        const int c = 4 * static_cast<int>(threadIdx.x) + 4 * THREADS * q;
         if (c < d) {
             out[c + 0] = acc[q][0]; out[c + 1] = acc[q][1]; out[c + 2] = acc[q][2]; out[c + 3] = acc[q][3];
         }
@@ -397,7 +404,7 @@ int fused_splits(int32_t n, int32_t b, int rows_per_iteration) {
 // rows consumed per loop iteration (two register tiles of R rows, or one without prefetch)
 int fused_rows(int cpt) { return cpt == 1 ? 8 : cpt == 2 ? 4 : cpt == 4 ? 2 : 1; }
 int fused_cpt(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : 8; }
-constexpr int kMaxFusedD = 8192;
+constexpr int kMaxFusedD = 16384;   // 512 threads x 8 chunks of 4 columns (1024 threads would spill: 128 registers each)
 
 }  // namespace
 
@@ -445,10 +452,15 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
         double* fpartial = sq_partial + ((static_cast<size_t>(n) * fs + 1) & ~size_t{1});
         const dim3 grid(static_cast<unsigned>(fs), static_cast<unsigned>(n));
         switch (cpt) {
-            case 1: hipLaunchKernelGGL((k_fused<1, 4, true>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
-            case 2: hipLaunchKernelGGL((k_fused<2, 2, true>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
-            case 4: hipLaunchKernelGGL((k_fused<4, 1, true>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
-            default: hipLaunchKernelGGL((k_fused<8, 1, false>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
+            case 1: hipLaunchKernelGGL((k_fused<1, 4, true, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
+            case 2: hipLaunchKernelGGL((k_fused<2, 2, true, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
+            case 4: hipLaunchKernelGGL((k_fused<4, 1, true, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
+            default:
+                if (d <= 8192)
+                    hipLaunchKernelGGL((k_fused<8, 1, false, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+                else
+                    hipLaunchKernelGGL((k_fused<8, 1, false, 512>), grid, dim3(512), 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+                break;
         }
         if (int rc = check_hip(hipGetLastError(), "fused gradient kernel launch")) return rc;
         const dim3 grid_ff(static_cast<unsigned>((d + kThreads - 1) / kThreads), static_cast<unsigned>(n));
