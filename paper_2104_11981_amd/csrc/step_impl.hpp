@@ -68,12 +68,18 @@ int launch_method(int vec, int format, bool norms, const StepCall& s);
 #ifdef DL_STEP_KERNEL_IMPL
 namespace {
 
-// Position of a lane's v-th column inside a row of the LDS tile, in doubles: a row is kept as VEC
-// planes of 64 doubles (column v of every lane), so that every LDS access of a wave touches 64
-// consecutive doubles and is free of bank conflicts.  With the lane's VEC columns side by side
-// (32-byte groups per lane) 71 % of the LDS cycles were bank conflicts (measured) and the kernel was
-// LDS-bound at 2.6 ms on the headline workload whatever the traffic.
-__device__ __forceinline__ constexpr int lds_col(int v) { return v * 64; }
+// Position of a lane's v-th column inside a row of the LDS tile, in doubles, relative to the lane's
+// base (lane * 2 with two or more columns per lane, else lane): a row is kept as VEC / 2 planes of 64
+// pairs of doubles (columns 2p and 2p + 1 of every lane side by side), so that a lane reads and writes
+// 16 bytes at a time (ds_read_b128 / ds_write_b128) and a wave's access is 1 KiB of consecutive
+// addresses: free of bank conflicts.  With a lane's VEC columns all side by side (32-byte groups per
+// lane) 71 % of the LDS cycles were bank conflicts (measured) and the kernel was LDS-bound at 2.6 ms on
+// the headline workload whatever the traffic.  Planes of single doubles (8-byte accesses) are equally
+// conflict-free but issue twice the instructions: from about ten neighbours per row on, where the LDS
+// reads start to show, the 16-byte form measured 2-15 % faster (32 nodes, 10 / 16 / 32 entries per row:
+// 2.57 / 2.78 / 3.53 ms against 2.62 / 2.91 / 4.14).
+__device__ __forceinline__ constexpr int lds_col(int v) { return (v >> 1) * 128 + (v & 1); }
+typedef double vd2 __attribute__((ext_vector_type(2)));
 
 // One neighbour in the LDS table.
 struct alignas(16) Neighbour {
@@ -93,8 +99,16 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
     double u[K][VEC];
 #pragma unroll
     for (int t = 0; t < K; ++t) {
+        if constexpr (VEC >= 2) {
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) u[t][v] = tile_at_lane[nb[t].offset + lds_col(v)];
+            for (int v = 0; v < VEC; v += 2) {
+                const vd2 pair = *reinterpret_cast<const vd2*>(tile_at_lane + nb[t].offset + lds_col(v));
+                u[t][v] = pair.x;
+                u[t][v + 1] = pair.y;
+            }
+        } else {
+            u[t][0] = tile_at_lane[nb[t].offset];
+        }
     }
 #pragma unroll
     for (int t = 0; t < K; ++t) {   // list order, one fused multiply-add per term
@@ -139,7 +153,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                                                       const BatchArgs batch, const NormArgs na,
                                                       const PhaseArgs topo) {
     constexpr int TC = 64 * VEC;
-    extern __shared__ double lds[];  // tile [n][TC] of u_j (DecentLaM) or h_j (DmSGD), then the table
+    extern __shared__ __attribute__((aligned(16))) double lds[];  // tile [n][TC] of u_j (DecentLaM) or h_j (DmSGD), then the table
     const int n = topo.n;
     Neighbour* table = reinterpret_cast<Neighbour*>(lds + n * TC);
 
@@ -234,7 +248,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
         const int i = wave + WAVES * r;
         double sq_g = 0.0, sq_m = 0.0;   // this lane's share (NORMS)
         if (i < n) {   // uniform; lanes beyond the problem work on the stand-in column and store nothing
-            double* slot = lds + i * TC + lane;
+            double* slot = lds + i * TC + lane * (VEC >= 2 ? 2 : 1);
             if constexpr (NORMS) {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
@@ -305,7 +319,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
     }
 
     // ---- phase 2: gather-mix from LDS, finish the update, store in place
-    const double* tile_at_lane = lds + lane;
+    const double* tile_at_lane = lds + lane * (VEC >= 2 ? 2 : 1);
 #pragma unroll
     for (int r = 0; r < RPT; ++r) {
         const int i = wave + WAVES * r;
@@ -411,7 +425,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
         for (int r = 0; r < RPT; ++r) {
             const int i = wave + WAVES * r;
             if (i < n) {
-                double* slot = lds + i * TC + lane;
+                double* slot = lds + i * TC + lane * (VEC >= 2 ? 2 : 1);
 #pragma unroll
                 for (int v = 0; v < VEC; ++v)
                     slot[lds_col(v)] = beta * static_cast<double>(mr[r][v]) + static_cast<double>(gr[r][v]);

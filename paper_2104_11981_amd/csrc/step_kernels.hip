@@ -9,7 +9,8 @@
 //            x_j, g_j, m_j come in with VEC*4-byte non-temporal loads, all issued before anything
 //            waits for one; the local pre-step (u_j = x_j - gamma g_j for DecentLaM,
 //            h_j = x_j - gamma (beta m_j + g_j) for DmSGD) is evaluated in fp64 and parked in LDS
-//            as fp64 (each tile row as VEC planes of 64 doubles: bank-conflict free); meanwhile
+//            as fp64 (each tile row as planes of 64 pairs of doubles: 16-byte accesses, no bank
+//            conflicts); meanwhile
 //            the neighbour list of W is unpacked from the kernel arguments into an LDS table of
 //            (fp64 weight, LDS row offset) pairs and every wave fetches the bounds of its rows'
 //            slices of that list with scalar loads;
