@@ -167,13 +167,21 @@ def padded_ld(d):
     return recommended_ld(d)
 
 
-def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False, detail=None, ld=None):
+def all_to_all(P, n):
+    """Every node averages all n with equal weights: the densest W there is."""
+    import numpy as np
+
+    return P.make_topology(n, np.arange(0, n * n + 1, n), np.tile(np.arange(n), n), np.full(n * n, 1.0 / n, np.float32))
+
+
+def bench_step(P, workloads, name, algo, steps, warmup, calibration_copy=False, detail=None, ld=None, topo=None):
     import numpy as np
     import torch
 
     w = workloads.get(name)
     d = workloads.generate.dim(w)
-    topo = P.topology_build(w.topo, w.n)
+    if topo is None:
+        topo = P.topology_build(w.topo, w.n)
     gamma, beta = float(np.float32(w.gamma)), float(np.float32(w.beta))
     step = getattr(P, algo + "_step")
     # Row stride: see padded_ld.  (With rows that are only 16-byte aligned every 1 KiB wave access
@@ -597,6 +605,14 @@ def main():
         extras["decentlam_step_c3_exp32_ld_equals_d"] = {
             "kernel_ms": round(k4, 4), "GBps": round(b3 / (k4 * 1e-3) / 1e9, 1),
             "frac_of_hbm_peak": round(b3 / (k4 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        # c3's arrays under all-to-all averaging (1024 entries): the mixing runs as an fp64 product on
+        # the matrix cores, 2 n^2 d flops per step beside the same 20 B per node-element
+        _, _, _, _, _, k5 = bench_step(P, workloads, "c3_exp32", "decentlam", args.steps, args.warmup,
+                                       topo=all_to_all(P, w3.n))
+        extras["decentlam_step_c3_all_to_all32"] = {
+            "kernel_ms": round(k5, 4), "GBps": round(b3 / (k5 * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(b3 / (k5 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "mix_fp64_mfma_TFLOPps": round(2.0 * w3.n * w3.n * d3 / (k5 * 1e-3) / 1e12, 2)}
         extras["decentlam_step_xprev_c3_exp32"] = bench_xprev(P, workloads, "c3_exp32", args.steps, args.warmup)
         blk = bench_blocked(P, workloads, "c3_exp32", "decentlam", args.steps, args.warmup)
         extras["decentlam_step_blocked_c3_exp32"] = blk

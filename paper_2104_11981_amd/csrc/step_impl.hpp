@@ -117,6 +117,41 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
     }
 }
 
+// Dense W (17-32 nodes, most pairs neighbours): the mixing of a tile is the fp64 contraction
+// Z[32 x TC] = W[32 x 32] * U[32 x TC], and it runs on the matrix cores (v_mfma_f64_16x16x4_f64)
+// instead of |N_i| LDS gathers per row.  Wave w owns the 16 positions [16 w, 16 w + 16) of every
+// tile row: for each of the eight groups of four rows it reads its 4 x 16 block of U as the B
+// operand (lane l: row l / 16 of the group, position l % 16), multiplies it with the two 16 x 4
+// blocks of W kept in LDS in operand order (lane l: row l % 16, column l / 16 of the block) and, when
+// all products are in, writes its 32 x 16 block of Z over U: it alone read those positions, so no
+// barrier separates the two.  The result registers of the instruction hold rows l / 16 + 4 r
+// (r = 0..3) of column l % 16 (layout checked on the device).  Tile rows are kDensePad doubles longer than
+// the tile is wide so that the four rows of an operand read fall into different LDS banks.
+// Sums run in the instruction's order, not in list order: fp64 rounding differs in the last bits, far
+// inside the fp32 rounding of the result.  A zero weight multiplies its node's value like any other,
+// so a non-finite value in one node's column reaches every node of that column, neighbour or not.
+constexpr int kDensePad = 16;
+constexpr int kDenseRows = 32;   // rows of the padded problem: two 16-row blocks, eight groups of four
+typedef double vd4 __attribute__((ext_vector_type(4)));
+template <int STRIDE>
+__device__ __forceinline__ void mix_dense(double* __restrict__ tile, const double* __restrict__ w_operands, int wave,
+                                          int lane) {
+    double* mine = tile + (lane >> 4) * STRIDE + 16 * wave + (lane & 15);
+    const double* a_at = w_operands + lane;
+    vd4 lo = {0.0, 0.0, 0.0, 0.0}, hi = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int s = 0; s < kDenseRows / 4; ++s) {   // all eight groups, whatever n: rows from n on hold zeros
+        const double b = mine[4 * s * STRIDE];
+        lo = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[s * 64], b, lo, 0, 0, 0);
+        hi = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[(kDenseRows / 4 + s) * 64], b, hi, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        mine[4 * r * STRIDE] = lo[r];
+        mine[(16 + 4 * r) * STRIDE] = hi[r];
+    }
+}
+
 // After the barrier all waves of a workgroup gather, compute and store at the same moment, and the
 // memory system sees the workgroup's 64 KiB of stores as one burst.  Letting the odd-numbered waves
 // (SIMDs 1 and 3) begin that phase 32-48 x 64 cycles later measured 4-8 % faster while the kernel
@@ -125,9 +160,9 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
 // measured: 16-byte lanes up to 32 nodes, every form that moves 14 B per node-element or more.  Off
 // where it measured neutral or harmful: DSGD (12 B), 64 nodes and more, the 16-wave single-row shape
 // with less than 20 B, the variants with per-tensor sums.
-template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
+template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS, bool DENSE>
 constexpr int stagger_units() {
-    if (NORMS || VEC != 4 || ALGO == ALGO_DSGD || ALGO == ALGO_DA_DMSGD) return 0;
+    if (DENSE || NORMS || VEC != 4 || ALGO == ALGO_DSGD || ALGO == ALGO_DA_DMSGD) return 0;
     const bool twenty_bytes = ALGO != ALGO_DECENTLAM_XPREV && GF == DL_GRAD_F32;
     if (RPT == 2 && WAVES == 16) return twenty_bytes ? 48 : 32;
     if (RPT == 1 && WAVES == 16) return twenty_bytes ? 32 : 0;
@@ -145,7 +180,8 @@ constexpr int stagger_units() {
 //        ALGO_AWC_DMSGD (m <- beta m + g; x <- W x - gamma m: the tile holds x) and ALGO_DA_DMSGD
 //        (mh = beta m + g; x <- W (x - gamma mh); m <- W mh: the tile holds h, then mh, each gathered)
 // GF     dl_grad_format of g;  NORMS: accumulate the per-tensor sums of squares
-template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
+// DENSE  mix on the matrix cores (see mix_dense): 16-byte lanes, 17-32 nodes
+template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS, bool DENSE = false>
 __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, float* __restrict__ m,
                                                       const typename GradElem<GF>::type* __restrict__ g,
                                                       int64_t d, int64_t ld, int64_t ldg,
@@ -153,9 +189,13 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                                                       const BatchArgs batch, const NormArgs na,
                                                       const PhaseArgs topo) {
     constexpr int TC = 64 * VEC;
-    extern __shared__ __attribute__((aligned(16))) double lds[];  // tile [n][TC] of u_j (DecentLaM) or h_j (DmSGD), then the table
+    static_assert(!DENSE || (VEC == 4 && RPT == 2 && WAVES == 16), "dense mixing: one shape");
+    constexpr int STRIDE = DENSE ? TC + kDensePad : TC;   // doubles from one tile row to the next
+    // tile [n][TC] of u_j (DecentLaM) or h_j (DmSGD), then the table; DENSE: [32][STRIDE], then W as operands
+    extern __shared__ __attribute__((aligned(16))) double lds[];
     const int n = topo.n;
     Neighbour* table = reinterpret_cast<Neighbour*>(lds + n * TC);
+    double* w_operands = lds + kDenseRows * STRIDE;   // DENSE: [2 row blocks][8 row groups][64 lanes]
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -188,9 +228,12 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
     const int e_mine = threadIdx.x;
     // (no branch around these two loads, or they would be waited for at its end; in the palette form
     // they read bytes of the other encoding, which nobody uses)
-    const int e_safe = e_mine < nnz && e_mine < DL_MAX_NNZ ? e_mine : 0;
+    const int e_safe = !DENSE && e_mine < nnz && e_mine < DL_MAX_NNZ ? e_mine : 0;
     const unsigned col_mine = topo.direct.col[e_safe];
     const float w_mine = topo.direct.w[e_safe];
+    // DENSE: lane l of a wave takes entry l of each of the wave's rows; the palette rides along, one
+    // value per lane
+    const float palette_mine = topo.pal.value[DENSE ? lane : 0];
     // ---- phase 1: stream rows in.  Every load is issued before anything waits for one: rows and
     // lanes beyond the problem read the tile's first column of row 0 instead (in bounds, never used),
     // so that no load sits inside a branch, and the row bases are uniform (scalar address
@@ -223,14 +266,28 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
         e_begin[r] = (row & 1) ? lo >> 16 : lo & 0xffffu;
         e_end[r] = (row & 1) ? hi & 0xffffu : hi >> 16;
     }
-    if (direct && e_mine < nnz) {
+    // DENSE: a wave writes rows i and i + 16 of W into the operand array, zeros first, then its
+    // entries (LDS writes of one wave land in program order).
+    unsigned dense_col[RPT], dense_widx[RPT];
+    float dense_w[RPT];
+    if constexpr (DENSE) {
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) {
+            const int e = e_begin[r] + lane;
+            const int e_row = e < e_end[r] ? e : 0;   // both encodings keep their columns in the same bytes
+            dense_col[r] = topo.pal.col[e_row];
+            dense_widx[r] = topo.pal.widx[e_row];
+            dense_w[r] = topo.direct.w[direct ? e_row : 0];
+        }
+    }
+    if (!DENSE && direct && e_mine < nnz) {
         Neighbour t;
         t.w = static_cast<double>(w_mine);
         t.offset = static_cast<int>(col_mine) * TC;
         t.unused = 0;
         table[e_mine] = t;
     }
-    for (int e = direct ? e_mine + 64 * WAVES : e_mine; e < nnz; e += 64 * WAVES) {   // later rounds; palette form
+    for (int e = DENSE ? nnz : (direct ? e_mine + 64 * WAVES : e_mine); e < nnz; e += 64 * WAVES) {   // later rounds; palette form
         Neighbour t;
         if (direct) {
             t.w = static_cast<double>(topo.direct.w[e]);
@@ -247,8 +304,23 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
     for (int r = 0; r < RPT; ++r) {
         const int i = wave + WAVES * r;
         double sq_g = 0.0, sq_m = 0.0;   // this lane's share (NORMS)
+        if constexpr (DENSE) {
+            // row i of W in operand order: element (i, k) is lane (i % 16) + 16 (k % 4) of block [i / 16][k / 4]
+            double* w_row = w_operands + (i >> 4) * (kDenseRows / 4) * 64 + (i & 15);
+            if (lane < kDenseRows) w_row[(lane >> 2) * 64 + (lane & 3) * 16] = 0.0;
+            const float from_palette = __shfl(palette_mine, static_cast<int>(dense_widx[r] & 63u));
+            if (i < n && e_begin[r] + lane < e_end[r]) {
+                const unsigned k = dense_col[r];
+                w_row[(k >> 2) * 64 + (k & 3) * 16] = static_cast<double>(direct ? dense_w[r] : from_palette);
+            }
+            if (i >= n) {   // uniform: a row of the padding, all zeros
+                double* pad = lds + i * STRIDE + lane * 2;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) pad[lds_col(v)] = 0.0;
+            }
+        }
         if (i < n) {   // uniform; lanes beyond the problem work on the stand-in column and store nothing
-            double* slot = lds + i * TC + lane * (VEC >= 2 ? 2 : 1);
+            double* slot = lds + i * STRIDE + lane * (VEC >= 2 ? 2 : 1);
             if constexpr (NORMS) {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
@@ -313,13 +385,17 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), nothing else
     __syncthreads();
     // Odd waves start their second phase a little later (see stagger_units).
-    constexpr int kStagger = stagger_units<VEC, RPT, WAVES, ALGO, GF, NORMS>();
+    constexpr int kStagger = stagger_units<VEC, RPT, WAVES, ALGO, GF, NORMS, DENSE>();
     if constexpr (kStagger > 0) {
         if (wave & 1) __builtin_amdgcn_s_sleep(kStagger);
     }
 
     // ---- phase 2: gather-mix from LDS, finish the update, store in place
     const double* tile_at_lane = lds + lane * (VEC >= 2 ? 2 : 1);
+    if constexpr (DENSE) {
+        mix_dense<STRIDE>(lds, w_operands, wave, lane);
+        __syncthreads();   // the tile now holds Z = W U
+    }
 #pragma unroll
     for (int r = 0; r < RPT; ++r) {
         const int i = wave + WAVES * r;
@@ -332,7 +408,15 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
             const int e1 = e_end[r];
             // groups of 4 (2 for 16-byte lanes: eight fp64 values in flight; the kernel must stay within
             // 64 VGPRs for two 1024-thread workgroups per CU), then 2, then 1
-            if constexpr (VEC < 4) {
+            if constexpr (DENSE) {
+#pragma unroll
+                for (int v = 0; v < VEC; v += 2) {
+                    const vd2 pair = *reinterpret_cast<const vd2*>(tile_at_lane + i * STRIDE + lds_col(v));
+                    z[v] = pair.x;
+                    z[v + 1] = pair.y;
+                }
+                e = e1;
+            } else if constexpr (VEC < 4) {
                 for (; e + 4 <= e1; e += 4) gather<VEC, 4>(table + e, tile_at_lane, z);
                 if (e + 2 <= e1) {
                     gather<VEC, 2>(table + e, tile_at_lane, z);
@@ -425,13 +509,21 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
         for (int r = 0; r < RPT; ++r) {
             const int i = wave + WAVES * r;
             if (i < n) {
-                double* slot = lds + i * TC + lane * (VEC >= 2 ? 2 : 1);
+                double* slot = lds + i * STRIDE + lane * (VEC >= 2 ? 2 : 1);
 #pragma unroll
                 for (int v = 0; v < VEC; ++v)
                     slot[lds_col(v)] = beta * static_cast<double>(mr[r][v]) + static_cast<double>(gr[r][v]);
+            } else if constexpr (DENSE) {   // a row of the padding: zeros again
+                double* pad = lds + i * STRIDE + lane * 2;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) pad[lds_col(v)] = 0.0;
             }
         }
         __syncthreads();
+        if constexpr (DENSE) {
+            mix_dense<STRIDE>(lds, w_operands, wave, lane);
+            __syncthreads();
+        }
 #pragma unroll
         for (int r = 0; r < RPT; ++r) {
             const int i = wave + WAVES * r;
@@ -441,6 +533,15 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                 for (int v = 0; v < VEC; ++v) zm[v] = 0.0;
                 int e = e_begin[r];
                 const int e1 = e_end[r];
+                if constexpr (DENSE) {
+#pragma unroll
+                    for (int v = 0; v < VEC; v += 2) {
+                        const vd2 pair = *reinterpret_cast<const vd2*>(tile_at_lane + i * STRIDE + lds_col(v));
+                        zm[v] = pair.x;
+                        zm[v + 1] = pair.y;
+                    }
+                    e = e1;
+                }
                 for (; e + 2 <= e1; e += 2) gather<VEC, 2>(table + e, tile_at_lane, zm);
                 for (; e < e1; ++e) gather<VEC, 1>(table + e, tile_at_lane, zm);
                 float mo[VEC];
@@ -456,11 +557,12 @@ size_t lds_bytes_for(int32_t n, int vec, int nnz, int tiles) {
     return static_cast<size_t>(tiles) * n * 64 * vec * sizeof(double) + static_cast<size_t>(nnz) * sizeof(Neighbour);
 }
 
-template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS>
+template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS, bool DENSE = false>
 int launch_variant(const StepCall& s) {
     constexpr int TC = 64 * VEC;
-    const size_t lds_bytes = lds_bytes_for(s.n, VEC, s.topo->row_ptr[s.n], 1);
-    auto kernel = k_step<VEC, RPT, WAVES, ALGO, GF, NORMS>;
+    const size_t lds_bytes = DENSE ? (static_cast<size_t>(kDenseRows) * (TC + kDensePad) + kDenseRows * kDenseRows) * sizeof(double)
+                                   : lds_bytes_for(s.n, VEC, s.topo->row_ptr[s.n], 1);
+    auto kernel = k_step<VEC, RPT, WAVES, ALGO, GF, NORMS, DENSE>;
     if (lds_bytes > 160 * 1024)
         return set_error(DL_ETOPO, "step: n = %d with %d entries needs %zu bytes of LDS, a CU has 163840", s.n,
                          static_cast<int>(s.topo->row_ptr[s.n]), lds_bytes);
@@ -484,8 +586,18 @@ int launch_variant(const StepCall& s) {
 
 // Workgroup shape by node count: as many waves as rows up to 16, then more rows per thread.  The fp64
 // tile may take up to 128 KiB of LDS, see widest_vec_for.
+// From this many entries per row on, 17-32 nodes with 16-byte lanes mix on the matrix cores
+// (mix_dense) instead of gathering.  Measured on 32 nodes and 25.6 M columns, DecentLaM: the product
+// takes 2.67-2.70 ms whatever the graph; gathering takes 2.58 / 2.62 / 2.65 / 2.68 / 2.75 / 3.48 ms at
+// 11 / 12 / 13 / 14 / 16 / 32 entries per row.
+constexpr int kDenseMinDegree = 14;
+
 template <int VEC, int ALGO, int GF, bool NORMS>
 int launch_rows(const StepCall& s) {
+    if constexpr (VEC == 4) {
+        if (s.n > 16 && s.n <= kDenseRows && s.topo->row_ptr[s.n] >= kDenseMinDegree * s.n)
+            return launch_variant<4, 2, 16, ALGO, GF, NORMS, true>(s);
+    }
 #define DL_SHAPE(MAXN, W, R)                                                             \
     if constexpr (VEC == 1 || VEC * (MAXN) <= 256) {                                     \
         if (s.n <= (MAXN)) return launch_variant<VEC, R, W, ALGO, GF, NORMS>(s);         \

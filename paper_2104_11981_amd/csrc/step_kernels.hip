@@ -24,6 +24,9 @@
 // other workgroup touches these columns.  Which columns a tile owns is free: large row-major
 // launches use "split tiles" (step_impl.hpp), the column order this GPU's write path prefers.
 //
+// Dense graphs on 17-32 nodes take a different phase 2: the tile is multiplied by W on the matrix cores
+// (fp64 MFMA; mix_dense in step_impl.hpp), a second barrier, and every row reads its sum with one access.
+//
 // The same template serves DSGD, the momentum-free form of DecentLaM, AWC-DmSGD and DA-DmSGD, bf16 or
 // fp16 gradients (widened exactly on load), per-tile sums of squares of g, the new m and the new x
 // (per-tensor norms are finished in norms_kernels.hip), and launches over "batches" (the blocks of the

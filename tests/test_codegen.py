@@ -17,7 +17,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
 @pytest.fixture(scope="module")
-def headline_kernel_asm(tmp_path_factory):
+def decentlam_asm(tmp_path_factory):
     if not os.path.exists(HIPCC):
         pytest.skip("hipcc not installed")
     from paper_2104_11981_amd import build
@@ -26,12 +26,26 @@ def headline_kernel_asm(tmp_path_factory):
     flags = [f for f in build.FLAGS if f != "-fPIC"]
     subprocess.run([HIPCC] + flags + ["-S", "--cuda-device-only", os.path.join(build.CSRC, "step_decentlam.hip"),
                                       "-o", str(out)], check=True, capture_output=True)
-    text = out.read_text()
-    # k_step<VEC = 4, RPT = 2, WAVES = 16, DecentLaM, fp32 gradients, no per-tensor sums>: the 32-node shape
-    m = re.search(r"^(_ZN[^\n]*k_stepILi4ELi2ELi16ELi0ELi0ELb0E[^\n:]*):[^\n]*\n", text, re.M)
-    assert m, "headline instantiation not found in the assembly"
+    return out.read_text()
+
+
+def instantiation(text, args):
+    m = re.search(r"^(_ZN[^\n]*k_stepI" + args + r"E[^\n:]*):[^\n]*\n", text, re.M)
+    assert m, "instantiation not found in the assembly"
     body = text[m.end():text.index(".Lfunc_end", m.end())]
     return [ln.strip() for ln in body.split("\n") if ln.strip() and not ln.strip().startswith(";")]
+
+
+@pytest.fixture(scope="module")
+def headline_kernel_asm(decentlam_asm):
+    # k_step<VEC = 4, RPT = 2, WAVES = 16, DecentLaM, fp32 gradients, no per-tensor sums, gathers>: the 32-node shape
+    return instantiation(decentlam_asm, "Li4ELi2ELi16ELi0ELi0ELb0ELb0")
+
+
+@pytest.fixture(scope="module")
+def dense_kernel_asm(decentlam_asm):
+    # the same with the mixing on the matrix cores
+    return instantiation(decentlam_asm, "Li4ELi2ELi16ELi0ELi0ELb0ELb1")
 
 
 def test_row_loads_are_issued_before_the_first_wait_on_them(headline_kernel_asm):
@@ -56,6 +70,27 @@ def test_nothing_after_the_barrier_waits_on_vector_memory(headline_kernel_asm):
 def test_headline_kernel_fits_two_workgroups_per_cu(headline_kernel_asm):
     # 1024 threads per workgroup: two of them share a CU only up to 64 vector registers per lane
     text = "\n".join(headline_kernel_asm)
+    m = re.search(r"\.amdhsa_next_free_vgpr\s+(\d+)", text)
+    assert m and int(m.group(1)) <= 64
+    assert not re.search(r"scratch_(load|store)", text)
+
+
+def test_dense_kernel_multiplies_on_the_matrix_cores(dense_kernel_asm):
+    """32 x 32 times 32 x 16 per wave in fp64: sixteen 16x16x4 products, between two barriers; the
+    operands are read ahead (no wait for every single one); stores after the second barrier wait for
+    no vector load; registers allow two workgroups per CU."""
+    ins = dense_kernel_asm
+    barrier = [k for k, i in enumerate(ins) if i.startswith("s_barrier")]
+    assert len(barrier) == 2
+    mfma = [k for k, i in enumerate(ins) if i.startswith("v_mfma_f64_16x16x4")]
+    assert len(mfma) == 16 and barrier[0] < mfma[0] and mfma[-1] < barrier[1]
+    between = ins[barrier[0]:barrier[1]]
+    assert len([i for i in between if i.startswith("s_waitcnt") and "lgkmcnt" in i]) <= 8
+    after = ins[barrier[0]:]
+    assert not [i for i in after if i.startswith("s_waitcnt") and "vmcnt" in i]
+    assert not [i for i in after if i.startswith(("global_load", "buffer_load", "flat_load"))]
+    assert len([i for i in after if i.startswith("global_store_dwordx4")]) == 4
+    text = "\n".join(ins)
     m = re.search(r"\.amdhsa_next_free_vgpr\s+(\d+)", text)
     assert m and int(m.group(1)) <= 64
     assert not re.search(r"scratch_(load|store)", text)
