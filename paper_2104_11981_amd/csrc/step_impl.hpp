@@ -117,7 +117,7 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
     }
 }
 
-// Dense W (17-32 nodes, most pairs neighbours): the mixing of a tile is the fp64 contraction
+// Dense W (up to 32 nodes, most pairs neighbours; see mixes_on_matrix_cores): the mixing of a tile is the fp64 contraction
 // Z[32 x TC] = W[32 x 32] * U[32 x TC], and it runs on the matrix cores (v_mfma_f64_16x16x4_f64)
 // instead of |N_i| LDS gathers per row.  Wave w owns the 16 positions [16 w, 16 w + 16) of every
 // tile row: for each of the eight groups of four rows it reads its 4 x 16 block of U as the B
@@ -134,16 +134,18 @@ constexpr int kDensePad = 16;
 constexpr int kDenseRows = 32;   // rows of the padded problem: two 16-row blocks, eight groups of four
 typedef double vd4 __attribute__((ext_vector_type(4)));
 template <int STRIDE>
-__device__ __forceinline__ void mix_dense(double* __restrict__ tile, const double* __restrict__ w_operands, int wave,
+__device__ __forceinline__ void mix_dense(double* __restrict__ tile, const double* __restrict__ w_operands, int n, int wave,
                                           int lane) {
     double* mine = tile + (lane >> 4) * STRIDE + 16 * wave + (lane & 15);
     const double* a_at = w_operands + lane;
     vd4 lo = {0.0, 0.0, 0.0, 0.0}, hi = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-    for (int s = 0; s < kDenseRows / 4; ++s) {   // all eight groups, whatever n: rows from n on hold zeros
-        const double b = mine[4 * s * STRIDE];
-        lo = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[s * 64], b, lo, 0, 0, 0);
-        hi = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[(kDenseRows / 4 + s) * 64], b, hi, 0, 0, 0);
+    for (int s = 0; s < kDenseRows / 4; ++s) {
+        if (4 * s < n) {   // uniform; rows from n on hold zeros, whole groups of them are skipped
+            const double b = mine[4 * s * STRIDE];
+            lo = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[s * 64], b, lo, 0, 0, 0);
+            hi = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[(kDenseRows / 4 + s) * 64], b, hi, 0, 0, 0);
+        }
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -180,7 +182,7 @@ constexpr int stagger_units() {
 //        ALGO_AWC_DMSGD (m <- beta m + g; x <- W x - gamma m: the tile holds x) and ALGO_DA_DMSGD
 //        (mh = beta m + g; x <- W (x - gamma mh); m <- W mh: the tile holds h, then mh, each gathered)
 // GF     dl_grad_format of g;  NORMS: accumulate the per-tensor sums of squares
-// DENSE  mix on the matrix cores (see mix_dense): 16-byte lanes, 17-32 nodes
+// DENSE  mix on the matrix cores (see mix_dense): 16-byte lanes, 17-32 nodes (used from 23 on)
 template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS, bool DENSE = false>
 __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, float* __restrict__ m,
                                                       const typename GradElem<GF>::type* __restrict__ g,
@@ -393,7 +395,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
     // ---- phase 2: gather-mix from LDS, finish the update, store in place
     const double* tile_at_lane = lds + lane * (VEC >= 2 ? 2 : 1);
     if constexpr (DENSE) {
-        mix_dense<STRIDE>(lds, w_operands, wave, lane);
+        mix_dense<STRIDE>(lds, w_operands, n, wave, lane);
         __syncthreads();   // the tile now holds Z = W U
     }
 #pragma unroll
@@ -521,7 +523,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
         }
         __syncthreads();
         if constexpr (DENSE) {
-            mix_dense<STRIDE>(lds, w_operands, wave, lane);
+            mix_dense<STRIDE>(lds, w_operands, n, wave, lane);
             __syncthreads();
         }
 #pragma unroll
@@ -586,16 +588,19 @@ int launch_variant(const StepCall& s) {
 
 // Workgroup shape by node count: as many waves as rows up to 16, then more rows per thread.  The fp64
 // tile may take up to 128 KiB of LDS, see widest_vec_for.
-// From this many entries per row on, 17-32 nodes with 16-byte lanes mix on the matrix cores
-// (mix_dense) instead of gathering.  Measured on 32 nodes and 25.6 M columns, DecentLaM: the product
-// takes 2.67-2.70 ms whatever the graph; gathering takes 2.58 / 2.62 / 2.65 / 2.68 / 2.75 / 3.48 ms at
-// 11 / 12 / 13 / 14 / 16 / 32 entries per row.
-constexpr int kDenseMinDegree = 14;
+// Where the matrix cores (mix_dense) beat the gather, measured with DecentLaM on c3-sized arrays
+// (n x d = 819 M elements) and circulant graphs: the product costs the same at any density but more
+// per byte the fewer rows a tile has (32 / 28 / 24 / 20 nodes: 2.70 / 2.95 / 3.22 / 3.32 ms), the
+// gather grows with the entries per row (32 nodes: 2.61 / 2.74 / 2.93 / 3.50 ms at 13 / 14 / 20 / 32;
+// 28 nodes: 2.89 / 3.00 / 3.53 at 16 / 18 / 28; 24 nodes: 3.22 / 3.34 / 3.46 at 20 / 22 / 24; 20 nodes:
+// 3.21 at 20).  The two cross at about 46 - n entries per row: 14 at 32 nodes, 18 at 28, 22 at 24,
+// never below 23 nodes.
+inline bool mixes_on_matrix_cores(int n, int nnz) { return n > 16 && n <= kDenseRows && nnz >= (46 - n) * n; }
 
 template <int VEC, int ALGO, int GF, bool NORMS>
 int launch_rows(const StepCall& s) {
     if constexpr (VEC == 4) {
-        if (s.n > 16 && s.n <= kDenseRows && s.topo->row_ptr[s.n] >= kDenseMinDegree * s.n)
+        if (mixes_on_matrix_cores(s.n, s.topo->row_ptr[s.n]))
             return launch_variant<4, 2, 16, ALGO, GF, NORMS, true>(s);
     }
 #define DL_SHAPE(MAXN, W, R)                                                             \
