@@ -489,6 +489,9 @@ def main():
                          "blocked: the *_step_blocked calls on the same problem stored in blocks of "
                          "--block-columns columns")
     ap.add_argument("--block-columns", type=int, default=8192)
+    ap.add_argument("--all-to-all", action="store_true",
+                    help="row-major line only: replace the workload's graph by all-to-all averaging with equal "
+                         "weights (the mixing then runs on the matrix cores; a side measurement, not the metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the side measurements (DmSGD, ragged workload, least-squares gradient)")
@@ -560,8 +563,9 @@ def main():
         }), flush=True)
         return
     detail = None if args.no_extras else {}
-    w, d, ld, topo, wall_ms, kern_ms = bench_step(P, workloads, args.workload, args.algo, args.steps,
-                                                  args.warmup, args.calibration_copy, detail)
+    w, d, ld, topo, wall_ms, kern_ms = bench_step(
+        P, workloads, args.workload, args.algo, args.steps, args.warmup, args.calibration_copy, detail,
+        topo=all_to_all(P, workloads.get(args.workload).n) if args.all_to_all else None)
     kind = w.topo
     bytes_per_step = BYTES_PER_ELEMENT * w.n * d
     value = bytes_per_step / (wall_ms * 1e-3) / 1e9
@@ -569,23 +573,25 @@ def main():
 
     out = {
         "metric": "DecentLaM step: achieved HBM GB/s & steps/s at n=32 nodes x d=25.6M fp32"
-        if (args.workload, args.algo) == ("c3_exp32", "decentlam")
-        else f"{args.algo} step: achieved HBM GB/s & steps/s ({w.name})",
+        if (args.workload, args.algo, args.all_to_all) == ("c3_exp32", "decentlam", False)
+        else f"{args.algo} step: achieved HBM GB/s & steps/s ({w.name}{', all-to-all graph' if args.all_to_all else ''})",
         "value": round(value, 2), "unit": "GB/s",
         "steps_per_s": round(1e3 / wall_ms, 2),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(wall_ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": w.name, "algo": args.algo, "n": w.n, "d": d, "ld": ld,
-                   "topology": {0: "ring", 1: "exp_static", 2: "exp_onepeer"}[kind],
+                   "topology": "all_to_all" if args.all_to_all else {0: "ring", 1: "exp_static", 2: "exp_onepeer"}[kind],
                    "deg": int(topo.row_ptr[1] - topo.row_ptr[0]), "gamma": w.gamma, "beta": w.beta,
                    "storage": "fp32", "bytes_per_node_element": BYTES_PER_ELEMENT},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.algo)),
+                     "traffic": None if args.all_to_all else MEASURED_TRAFFIC_BYTES.get((args.workload, args.algo)),
                      "kernel": "k_step", "kernel_ms": round(kern_ms, 4),
                      "algorithmic_bytes_per_launch": bytes_per_step},
     }
+    if args.all_to_all:
+        out["mix_fp64_mfma_TFLOPps"] = round(2.0 * w.n * w.n * d / (kern_ms * 1e-3) / 1e12, 2)
     if not args.no_extras:
         extras = dict(detail)
         for name, algo in (("c3_exp32", "dmsgd"), ("c4_ring16_ragged", "decentlam"), ("c3_exp32", "awc_dmsgd"),

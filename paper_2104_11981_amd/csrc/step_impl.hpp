@@ -122,7 +122,7 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
 // instead of |N_i| LDS gathers per row.  Wave w owns the 16 positions [16 w, 16 w + 16) of every
 // tile row: for each of the eight groups of four rows it reads its 4 x 16 block of U as the B
 // operand (lane l: row l / 16 of the group, position l % 16), multiplies it with the two 16 x 4
-// blocks of W kept in LDS in operand order (lane l: row l % 16, column l / 16 of the block) and, when
+// blocks of W kept in LDS (lane l: row l % 16, column l / 16 of the block; see dense_w_at) and, when
 // all products are in, writes its 32 x 16 block of Z over U: it alone read those positions, so no
 // barrier separates the two.  The result registers of the instruction hold rows l / 16 + 4 r
 // (r = 0..3) of column l % 16 (layout checked on the device).  Tile rows are kDensePad doubles longer than
@@ -132,19 +132,31 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
 // so a non-finite value in one node's column reaches every node of that column, neighbour or not.
 constexpr int kDensePad = 16;
 constexpr int kDenseRows = 32;   // rows of the padded problem: two 16-row blocks, eight groups of four
+// Where element (i, k) of W sits in its LDS array, in doubles: per block of 16 rows, sixteen slabs (one
+// per pair of columns) of 16 rows x 2 columns, two doubles of padding after each.  With the padding
+// both access patterns are free of bank conflicts: a wave that writes one row of W (lane = column)
+// touches 32 different 8-byte banks, and so does a half-wave that reads an A operand (16 rows x
+// 2 columns of one slab).  (Without it the row writes were 16-way conflicts: 42 % of the kernel's LDS
+// cycles, measured.)
+constexpr int kDenseSlab = 2 * 16 + 2;
+constexpr int kDenseBlock = (kDenseRows / 2) * kDenseSlab;
+constexpr int kDenseWDoubles = 2 * kDenseBlock;
+__host__ __device__ constexpr int dense_w_at(int i, int k) {
+    return (i >> 4) * kDenseBlock + (k >> 1) * kDenseSlab + (i & 15) * 2 + (k & 1);
+}
 typedef double vd4 __attribute__((ext_vector_type(4)));
 template <int STRIDE>
 __device__ __forceinline__ void mix_dense(double* __restrict__ tile, const double* __restrict__ w_operands, int n, int wave,
                                           int lane) {
     double* mine = tile + (lane >> 4) * STRIDE + 16 * wave + (lane & 15);
-    const double* a_at = w_operands + lane;
+    const double* a_at = w_operands + dense_w_at(lane & 15, lane >> 4);   // + dense_w_at(16 rb, 4 s) per operand
     vd4 lo = {0.0, 0.0, 0.0, 0.0}, hi = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int s = 0; s < kDenseRows / 4; ++s) {
         if (4 * s < n) {   // uniform; rows from n on hold zeros, whole groups of them are skipped
             const double b = mine[4 * s * STRIDE];
-            lo = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[s * 64], b, lo, 0, 0, 0);
-            hi = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[(kDenseRows / 4 + s) * 64], b, hi, 0, 0, 0);
+            lo = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[dense_w_at(0, 4 * s)], b, lo, 0, 0, 0);
+            hi = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[dense_w_at(16, 4 * s)], b, hi, 0, 0, 0);
         }
     }
 #pragma unroll
@@ -197,7 +209,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
     extern __shared__ __attribute__((aligned(16))) double lds[];
     const int n = topo.n;
     Neighbour* table = reinterpret_cast<Neighbour*>(lds + n * TC);
-    double* w_operands = lds + kDenseRows * STRIDE;   // DENSE: [2 row blocks][8 row groups][64 lanes]
+    double* w_operands = lds + kDenseRows * STRIDE;   // DENSE: W, laid out by dense_w_at
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -307,13 +319,13 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
         const int i = wave + WAVES * r;
         double sq_g = 0.0, sq_m = 0.0;   // this lane's share (NORMS)
         if constexpr (DENSE) {
-            // row i of W in operand order: element (i, k) is lane (i % 16) + 16 (k % 4) of block [i / 16][k / 4]
-            double* w_row = w_operands + (i >> 4) * (kDenseRows / 4) * 64 + (i & 15);
-            if (lane < kDenseRows) w_row[(lane >> 2) * 64 + (lane & 3) * 16] = 0.0;
+            // row i of W: zeros, then the entries of the list
+            double* w_row = w_operands + dense_w_at(i, 0);
+            if (lane < kDenseRows) w_row[dense_w_at(0, lane)] = 0.0;
             const float from_palette = __shfl(palette_mine, static_cast<int>(dense_widx[r] & 63u));
             if (i < n && e_begin[r] + lane < e_end[r]) {
                 const unsigned k = dense_col[r];
-                w_row[(k >> 2) * 64 + (k & 3) * 16] = static_cast<double>(direct ? dense_w[r] : from_palette);
+                w_row[dense_w_at(0, static_cast<int>(k))] = static_cast<double>(direct ? dense_w[r] : from_palette);
             }
             if (i >= n) {   // uniform: a row of the padding, all zeros
                 double* pad = lds + i * STRIDE + lane * 2;
@@ -562,7 +574,7 @@ size_t lds_bytes_for(int32_t n, int vec, int nnz, int tiles) {
 template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS, bool DENSE = false>
 int launch_variant(const StepCall& s) {
     constexpr int TC = 64 * VEC;
-    const size_t lds_bytes = DENSE ? (static_cast<size_t>(kDenseRows) * (TC + kDensePad) + kDenseRows * kDenseRows) * sizeof(double)
+    const size_t lds_bytes = DENSE ? (static_cast<size_t>(kDenseRows) * (TC + kDensePad) + kDenseWDoubles) * sizeof(double)
                                    : lds_bytes_for(s.n, VEC, s.topo->row_ptr[s.n], 1);
     auto kernel = k_step<VEC, RPT, WAVES, ALGO, GF, NORMS, DENSE>;
     if (lds_bytes > 160 * 1024)
