@@ -252,6 +252,7 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int
     plan.offsets = ex.offsets;
     plan.num_tensors = ex.num_tensors;
     plan.partial = static_cast<double*>(ex.workspace);
+    plan.capacity = norm_tiles_bound(d);
     plan.norms = ex.norms;
     if (int rc = launch_step(algo, x, m, ga, n, d, ld, topo, gamma, beta_eff, s, &plan)) return rc;
     return launch_norms_finish(plan, x, m, ga, ld, n, s);
@@ -321,6 +322,7 @@ int blocked_entry(const char* fn, Algo algo, float* x, float* m, const void* g, 
         plan.offsets = multi->offsets;
         plan.num_tensors = multi->num_tensors;
         plan.partial = static_cast<double*>(multi->workspace);
+        plan.capacity = norm_tiles_bound(d);
         plan.norms = multi->norms;
         plan.bw = bw;
         np = &plan;

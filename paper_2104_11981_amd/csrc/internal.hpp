@@ -54,9 +54,11 @@ inline size_t grad_elem_bytes(int format) { return format == DL_GRAD_F32 ? 4 : 2
 
 // Per-tensor sums of squares fused into a step.  Tensor t is the column range
 // [offsets[t], offsets[t + 1]) of the caller's arrays.  Every workgroup of a step launch owns one
-// tile of columns and writes records of n x 3 doubles (sums of squares of g, new m, new x) with
-// plain stores: one per tile, or with 16-byte lanes one per half tile, so that a record always
-// covers one range of `tc` columns and is numbered by it, whatever the column order of the launch.
+// tile of columns and writes, for every node, a record of 3 doubles (sums of squares of g, new m,
+// new x) with plain stores: one per tile, or with 16-byte lanes one per half tile, so that a record
+// always covers one range of `tc` columns and is numbered by it, whatever the column order of the
+// launch.  The records of one node are contiguous (node i's record q sits at (i * capacity + q) * 3),
+// so that the final pass, one workgroup per tensor and node, reads consecutive memory.
 // A final pass adds, for every tensor, the records of the ranges that lie wholly inside it and sums
 // the remaining edge columns directly from the arrays.
 constexpr int kMaxNormGrids = 4;   // aligned body (in two launches when it starts off a 64 KiB boundary), peeled head, peeled tail
@@ -69,7 +71,8 @@ struct NormGrid {
 struct NormPlan {
     const int64_t* offsets;   // host, num_tensors + 1; offsets[0] is the first column of the step
     int32_t num_tensors;
-    double* partial;          // device, room for norm_tiles_bound(d) records of n x 3 doubles
+    double* partial;          // device, room for n x capacity records of 3 doubles
+    int64_t capacity;         // records per node: norm_tiles_bound(d)
     double* norms;            // device, [num_tensors][n][3]
     NormGrid grid[kMaxNormGrids];   // appended to by every launch_step call of one iteration
     int grids;

@@ -41,7 +41,8 @@ __host__ __device__ inline int64_t split_column(uint32_t tile, int lane) {   // 
 // Per-launch arguments of the per-tensor sums (see NormPlan): where the tile records go.
 struct NormArgs {
     double* partial;
-    int64_t tile0;   // record index of this launch's tile 0
+    int64_t tile0;      // record index of this launch's tile 0
+    int64_t capacity;   // records per node: node i's records start at partial + i * capacity * 3
 };
 
 // Everything a launch needs besides its template parameters.
@@ -500,7 +501,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                     record = batch.tiles ? 2 * static_cast<int64_t>(blockIdx.x) : tile_col / 128;
                     if (lane >= 32) record += lane_col >= kSplitDistance ? kSplitDistance / 128 : 1;
                 }
-                double* rec = na.partial + ((na.tile0 + record) * n + i) * 3;
+                double* rec = na.partial + (i * na.capacity + na.tile0 + record) * 3;
                 const bool upper = H == 2 && lane >= 32;
                 const int hl = H == 2 ? lane & 31 : lane;
                 const double e0 = upper ? early[r][H - 1][0] : early[r][0][0];

@@ -88,7 +88,7 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
         s.g = static_cast<const char*>(g.p) + static_cast<size_t>(c0) * gbytes;
         s.n = n; s.d = cols; s.ld = ld; s.ldg = g.ld;
         s.gamma = gamma; s.beta = beta; s.topo = &topo; s.stream = stream;
-        s.na = NormArgs{nullptr, 0};
+        s.na = NormArgs{nullptr, 0, 0};
         s.batches = batches; s.batch_stride = batch_stride; s.batch_stride_g = batch_stride_g;
         if (norms) {
             // records: one per tile, with 16-byte lanes one per half tile (128 columns)
@@ -97,7 +97,7 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
             if (norms->grids >= kMaxNormGrids) return set_error(DL_EINVAL, "step: too many launches for the per-tensor sums");
             NormGrid& gr = norms->grid[norms->grids++];
             gr.col0 = norms->col_base + c0; gr.cols = cols * batches; gr.tile0 = norms->tiles_used; gr.tc = tc;
-            s.na = NormArgs{norms->partial, gr.tile0};
+            s.na = NormArgs{norms->partial, gr.tile0, norms->capacity};
             norms->tiles_used += (cols + tile_cols - 1) / tile_cols * (tile_cols / tc) * batches;
         }
         switch (algo) {
