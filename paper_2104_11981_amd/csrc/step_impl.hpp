@@ -599,8 +599,15 @@ int launch_variant(const StepCall& s) {
     return check_hip(hipGetLastError(), "step kernel launch");
 }
 
-// Workgroup shape by node count: as many waves as rows up to 16, then more rows per thread.  The fp64
-// tile may take up to 128 KiB of LDS, see widest_vec_for.
+// Workgroup shape by node count: as many waves as rows up to 8 nodes, two rows per thread up to 32, then
+// more rows per thread.  The fp64 tile may take up to 128 KiB of LDS, see widest_vec_for.  Measured on
+// arrays of 819 M elements (DecentLaM, ring, 16-byte lanes), TB/s of the 20 B per node-element:
+//   9-16 nodes    8 waves x 2 rows (four workgroups per CU) against 16 x 1 (two, with idle waves below 16
+//                 nodes): 6.1 / 6.3 / 6.5 against 5.5 / 5.9 / 6.05 at 9 / 12 / 16 nodes
+//   17-24 nodes   10 x 2 and 12 x 2 against 16 x 2: 6.2 / 6.4 / 6.3 / 6.5 against 5.65 / 5.8 / 6.0 / 6.0 at
+//                 17 / 20 / 22 / 24 nodes (14 x 2 for 25-28 nodes measured worse than 16 x 2: 14 waves do
+//                 not spread evenly over four SIMDs)
+//   1-8 nodes     two rows per thread (1 x 2, 2 x 2, 4 x 2) measured equal or worse than one (6.4-6.6)
 // Where the matrix cores (mix_dense) beat the gather, measured with DecentLaM on c3-sized arrays
 // (n x d = 819 M elements) and circulant graphs: the product costs the same at any density but more
 // per byte the fewer rows a tile has (32 / 28 / 24 / 20 nodes: 2.70 / 2.95 / 3.22 / 3.32 ms), the
@@ -620,7 +627,7 @@ int launch_rows(const StepCall& s) {
     if constexpr (VEC == 1 || VEC * (MAXN) <= 256) {                                     \
         if (s.n <= (MAXN)) return launch_variant<VEC, R, W, ALGO, GF, NORMS>(s);         \
     }
-    DL_SHAPE(1, 1, 1) DL_SHAPE(2, 2, 1) DL_SHAPE(4, 4, 1) DL_SHAPE(8, 8, 1) DL_SHAPE(16, 16, 1) DL_SHAPE(32, 16, 2)
+    DL_SHAPE(1, 1, 1) DL_SHAPE(2, 2, 1) DL_SHAPE(4, 4, 1) DL_SHAPE(8, 8, 1) DL_SHAPE(16, 8, 2) DL_SHAPE(20, 10, 2) DL_SHAPE(24, 12, 2) DL_SHAPE(32, 16, 2)
     DL_SHAPE(64, 16, 4) DL_SHAPE(128, 16, 8) DL_SHAPE(256, 16, 16)
 #undef DL_SHAPE
     return set_error(DL_ETOPO, "step: n = %d has no kernel variant at vector width %d", s.n, VEC);
