@@ -421,9 +421,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
             for (int v = 0; v < VEC; ++v) z[v] = 0.0;
             int e = e_begin[r];
             const int e1 = e_end[r];
-            // groups of 4 (2 for 16-byte lanes: eight fp64 values in flight; the kernel must stay within
-            // 64 VGPRs for two 1024-thread workgroups per CU), then 2, then 1
-            if constexpr (DENSE) {
+            if constexpr (DENSE) {   // the tile already holds z
 #pragma unroll
                 for (int v = 0; v < VEC; v += 2) {
                     const vd2 pair = *reinterpret_cast<const vd2*>(tile_at_lane + i * STRIDE + lds_col(v));
@@ -431,7 +429,11 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                     z[v + 1] = pair.y;
                 }
                 e = e1;
-            } else if constexpr (VEC < 4) {
+            }
+            // groups of 4 (2 for 16-byte lanes: eight fp64 values in flight; the kernel must stay within
+            // 64 VGPRs for two 1024-thread workgroups per CU; groups of 3 measured the same, of 4 slower),
+            // then 2, then 1
+            else if constexpr (VEC < 4) {
                 for (; e + 4 <= e1; e += 4) gather<VEC, 4>(table + e, tile_at_lane, z);
                 if (e + 2 <= e1) {
                     gather<VEC, 2>(table + e, tile_at_lane, z);
