@@ -61,6 +61,30 @@ struct StepCall {
 };
 
 
+// Dense mixing on the matrix cores (mix_dense below): constants and the two host-checkable functions.
+constexpr int kDensePad = 16;
+constexpr int kDenseRows = 32;   // rows of the padded problem: two 16-row blocks, eight groups of four
+// Where element (i, k) of W sits in its LDS array, in doubles: per block of 16 rows, sixteen slabs (one
+// per pair of columns) of 16 rows x 2 columns, two doubles of padding after each.  With the padding
+// both access patterns are free of bank conflicts: a wave that writes one row of W (lane = column)
+// touches 32 different 8-byte banks, and so does a half-wave that reads an A operand (16 rows x
+// 2 columns of one slab).  (Without it the row writes were 16-way conflicts: 42 % of the kernel's LDS
+// cycles, measured.)
+constexpr int kDenseSlab = 2 * 16 + 2;
+constexpr int kDenseBlock = (kDenseRows / 2) * kDenseSlab;
+constexpr int kDenseWDoubles = 2 * kDenseBlock;
+__host__ __device__ constexpr int dense_w_at(int i, int k) {
+    return (i >> 4) * kDenseBlock + (k >> 1) * kDenseSlab + (i & 15) * 2 + (k & 1);
+}
+// Where the matrix cores (mix_dense) beat the gather, measured with DecentLaM on c3-sized arrays
+// (n x d = 819 M elements) and circulant graphs: the product costs the same at any density but more
+// per byte the fewer rows a tile has (32 / 28 / 24 / 20 nodes: 2.70 / 2.95 / 3.22 / 3.32 ms), the
+// gather grows with the entries per row (32 nodes: 2.61 / 2.74 / 2.93 / 3.50 ms at 13 / 14 / 20 / 32;
+// 28 nodes: 2.89 / 3.00 / 3.53 at 16 / 18 / 28; 24 nodes: 3.22 / 3.34 / 3.46 at 20 / 22 / 24; 20 nodes:
+// 3.21 at 20).  The two cross at about 46 - n entries per row: 14 at 32 nodes, 18 at 28, 22 at 24,
+// never below 23 nodes.
+inline bool mixes_on_matrix_cores(int n, int nnz) { return n > 16 && n <= kDenseRows && nnz >= (46 - n) * n; }
+
 // Launch the kernel of one method for the given vector width, gradient format and sums option
 // (defined in step_<method>.hip).
 template <int ALGO>
@@ -131,20 +155,6 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
 // Sums run in the instruction's order, not in list order: fp64 rounding differs in the last bits, far
 // inside the fp32 rounding of the result.  A zero weight multiplies its node's value like any other,
 // so a non-finite value in one node's column reaches every node of that column, neighbour or not.
-constexpr int kDensePad = 16;
-constexpr int kDenseRows = 32;   // rows of the padded problem: two 16-row blocks, eight groups of four
-// Where element (i, k) of W sits in its LDS array, in doubles: per block of 16 rows, sixteen slabs (one
-// per pair of columns) of 16 rows x 2 columns, two doubles of padding after each.  With the padding
-// both access patterns are free of bank conflicts: a wave that writes one row of W (lane = column)
-// touches 32 different 8-byte banks, and so does a half-wave that reads an A operand (16 rows x
-// 2 columns of one slab).  (Without it the row writes were 16-way conflicts: 42 % of the kernel's LDS
-// cycles, measured.)
-constexpr int kDenseSlab = 2 * 16 + 2;
-constexpr int kDenseBlock = (kDenseRows / 2) * kDenseSlab;
-constexpr int kDenseWDoubles = 2 * kDenseBlock;
-__host__ __device__ constexpr int dense_w_at(int i, int k) {
-    return (i >> 4) * kDenseBlock + (k >> 1) * kDenseSlab + (i & 15) * 2 + (k & 1);
-}
 typedef double vd4 __attribute__((ext_vector_type(4)));
 template <int STRIDE>
 __device__ __forceinline__ void mix_dense(double* __restrict__ tile, const double* __restrict__ w_operands, int n, int wave,
@@ -610,15 +620,6 @@ int launch_variant(const StepCall& s) {
 //                 17 / 20 / 22 / 24 nodes (14 x 2 for 25-28 nodes measured worse than 16 x 2: 14 waves do
 //                 not spread evenly over four SIMDs)
 //   1-8 nodes     two rows per thread (1 x 2, 2 x 2, 4 x 2) measured equal or worse than one (6.4-6.6)
-// Where the matrix cores (mix_dense) beat the gather, measured with DecentLaM on c3-sized arrays
-// (n x d = 819 M elements) and circulant graphs: the product costs the same at any density but more
-// per byte the fewer rows a tile has (32 / 28 / 24 / 20 nodes: 2.70 / 2.95 / 3.22 / 3.32 ms), the
-// gather grows with the entries per row (32 nodes: 2.61 / 2.74 / 2.93 / 3.50 ms at 13 / 14 / 20 / 32;
-// 28 nodes: 2.89 / 3.00 / 3.53 at 16 / 18 / 28; 24 nodes: 3.22 / 3.34 / 3.46 at 20 / 22 / 24; 20 nodes:
-// 3.21 at 20).  The two cross at about 46 - n entries per row: 14 at 32 nodes, 18 at 28, 22 at 24,
-// never below 23 nodes.
-inline bool mixes_on_matrix_cores(int n, int nnz) { return n > 16 && n <= kDenseRows && nnz >= (46 - n) * n; }
-
 template <int VEC, int ALGO, int GF, bool NORMS>
 int launch_rows(const StepCall& s) {
     if constexpr (VEC == 4) {

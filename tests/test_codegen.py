@@ -141,3 +141,64 @@ def test_split_tile_column_map_owns_every_column_once(tmp_path):
                     str(src), "-o", str(exe)], check=True, capture_output=True)
     run = subprocess.run([str(exe)], capture_output=True, text=True)
     assert run.returncode == 0 and run.stdout.strip() == "ok", f"check {run.returncode} failed"
+
+
+DENSE_CHECK = r"""
+#include <cstdio>
+#include <set>
+#include "step_impl.hpp"
+// Host run of the layout of W in LDS for the matrix-core mixing: every element has a slot of its own
+// inside the array; a wave writing one row (lane = column) and a half-wave reading an A operand of the
+// 16x16x4 instruction (lane l: row l % 16, column l / 16 of the 16 x 4 block) touch 32 different
+// 8-byte banks; the kernel's way of composing an operand address from a per-lane and a per-block part
+// gives the same slot.  And the switch-over rule: 46 - n entries per row, nothing below 23 nodes.
+int main() {
+    using namespace dl::step;
+    std::set<int> seen;
+    for (int i = 0; i < kDenseRows; ++i)
+        for (int k = 0; k < kDenseRows; ++k) {
+            const int at = dense_w_at(i, k);
+            if (at < 0 || at >= kDenseWDoubles || !seen.insert(at).second) return 1;
+        }
+    for (int i = 0; i < kDenseRows; ++i) {   // row write
+        std::set<int> banks;
+        for (int k = 0; k < kDenseRows; ++k) banks.insert(dense_w_at(i, k) % 32);
+        if (banks.size() != 32) return 2;
+        for (int k = 0; k < kDenseRows; ++k)
+            if (dense_w_at(i, k) != dense_w_at(i, 0) + dense_w_at(0, k)) return 3;
+    }
+    for (int rb = 0; rb < 2; ++rb)
+        for (int s = 0; s < kDenseRows / 4; ++s)
+            for (int half = 0; half < 2; ++half) {   // operand read, 32 lanes at a time
+                std::set<int> banks;
+                for (int lane = 32 * half; lane < 32 * half + 32; ++lane) {
+                    const int at = dense_w_at(16 * rb + (lane & 15), 4 * s + (lane >> 4));
+                    if (at != dense_w_at(lane & 15, lane >> 4) + dense_w_at(16 * rb, 4 * s)) return 4;
+                    banks.insert(at % 32);
+                }
+                if (banks.size() != 32) return 5;
+            }
+    for (int n = 1; n <= 40; ++n)
+        for (int per_row = 1; per_row <= n; ++per_row) {
+            const bool want = n >= 23 && n <= 32 && per_row >= 46 - n;
+            if (mixes_on_matrix_cores(n, per_row * n) != want) return 6;
+        }
+    std::puts("ok");
+    return 0;
+}
+"""
+
+
+def test_dense_weight_layout_is_conflict_free_and_rule_is_as_documented(tmp_path):
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not installed")
+    from paper_2104_11981_amd import build
+
+    src = tmp_path / "dense_check.hip"
+    src.write_text(DENSE_CHECK)
+    exe = tmp_path / "dense_check"
+    subprocess.run([HIPCC, "--cuda-host-only", "-O1", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", build.CSRC,
+                    str(src), "-o", str(exe)], check=True, capture_output=True)
+    run = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert run.returncode == 0 and run.stdout.strip() == "ok", f"check {run.returncode} failed"
+
