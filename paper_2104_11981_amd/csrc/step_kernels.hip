@@ -79,10 +79,11 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
     const int64_t body = ((d - head) / vec) * vec;
     const int64_t tail = d - head - body;
 
-    auto run = [&](int v, int64_t c0, int64_t cols, uint32_t split_tiles = 0) {
+    auto run = [&](int v, int64_t c0, int64_t cols, uint32_t split_tiles = 0, bool by_xcd = false) {
         if (cols <= 0) return static_cast<int>(DL_OK);
         StepCall s;
         s.split_tiles = split_tiles;
+        s.by_xcd = by_xcd;
         s.x = x + c0;
         s.m = m ? m + c0 : nullptr;
         s.g = static_cast<const char*>(g.p) + static_cast<size_t>(c0) * gbytes;
@@ -112,8 +113,12 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
     // Large single problems with 16-byte lanes: split tiles (see split_column) from the first column at
     // which the written array is 64 KiB-aligned, whole 64 KiB units only; what precedes is a launch
     // of its own, what follows rides along as ordinary tiles of the same launch.  (The per-tensor sums
-    // need tiles that are column ranges.)
-    if (vec == 4 && batches == 1 && body >= kSplitMinColumns) {
+    // need tiles that are column ranges.)  Rows that start at different offsets inside a 128-byte line
+    // cannot be paired up; their launch goes out in the per-XCD order instead (step_impl.hpp).
+    const bool large = vec == 4 && batches == 1 && body >= kSplitMinColumns;
+    if (large && ld % 32 != 0) {
+        if (int rc = run(vec, head, body, 0, true)) return rc;
+    } else if (large) {
         const float* written = algo == ALGO_DECENTLAM_XPREV ? m : x;
         const uintptr_t at = reinterpret_cast<uintptr_t>(written + head) % (4u * kSplitUnit);
         const int64_t pre = at ? static_cast<int64_t>((4u * kSplitUnit - at) / 4) : 0;

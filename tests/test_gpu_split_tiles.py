@@ -1,4 +1,4 @@
-"""GPU parity of the large-launch column order of the row-major step.
+"""GPU parity of the large-launch column orders of the row-major step.
 
 From 2^20 columns on, a row-major launch with 16-byte lanes maps its tiles to two 512-byte segments
 32 KiB apart inside 64 KiB-aligned units of the written array (what precedes the first aligned column
@@ -6,6 +6,8 @@ is a launch of its own, what follows the last whole unit rides along as ordinary
 column must still be updated exactly once: a column left out keeps its old value, a column taken
 twice gets the update twice, and either fails the comparison with the oracle, which is made on every
 element.  Bases are placed at chosen distances from a 64 KiB boundary so that all three parts occur.
+Row strides that are not a multiple of 32 elements take the other large-launch order (tiles handed out
+XCD by XCD), checked the same way, also with the per-tensor sums riding along.
 """
 import numpy as np
 import pytest
@@ -48,6 +50,12 @@ CASES = [
     (0, 16, (1 << 20) + UNIT + 1031, 1, (9000, 9000, 9000)),        # odd stride: narrow lanes, no split tiles at all
     (2, 8, (1 << 20) + 3 * UNIT + 8, 8, (8, 4, 12)),                # arrays placed differently (the written x decides)
     (1, 32, (1 << 20) + 40, UNIT - 40, (3, 3, 3)),                  # three elements off 16-byte alignment: head columns, then the rest
+    # rows that start at different offsets inside a 128-byte line (ld not a multiple of 32): one piece per
+    # row and tile, every XCD's workgroups on a contiguous share of the tiles; tile counts 8q + 2, + 6, + 0, + 7
+    (0, 4, (1 << 20) + 260, 4, (0, 0, 0)),
+    (2, 8, (1 << 20) + 1284, 4, (0, 0, 0)),
+    (0, 4, (1 << 20) + 1796, 12, (0, 4, 8)),
+    (1, 16, (1 << 20) + 1540, 20, (4, 4, 4)),
 ]
 
 
@@ -88,3 +96,29 @@ def test_large_row_major_launch_matches_oracle(P, oracle, algo, kind, n, d, pad,
         for i in range(n):
             inside[first + i * ld:first + i * ld + d] = True
         assert np.all(full[~inside] == SENT)
+
+
+@pytest.mark.parametrize("n,d,pad", [(4, (1 << 20) + 1284, 4), (8, (1 << 20) + 3 * UNIT + 8, 8), (4, (1 << 20) + 2 * UNIT, 0)])
+def test_large_launch_with_per_tensor_sums(P, oracle, n, d, pad):
+    """The multi-tensor call over one large launch in either order: state and sums against the oracle."""
+    gamma, beta = float(np.float32(0.05)), float(np.float32(0.9))
+    topo, otopo = P.topology_build(0, n), oracle.topology(0, n)
+    rng = np.random.default_rng(d + n)
+    x0, m0, g0 = (rng.standard_normal((n, d)).astype(np.float32) for _ in range(3))
+    ld = d + pad
+    bufs = [torch.zeros((n, ld), device="cuda") for _ in range(3)]
+    for b, a in zip(bufs, (x0, m0, g0)):
+        b[:, :d].copy_(torch.from_numpy(a).cuda())
+    T = 9
+    offsets = np.concatenate([[0], np.sort(rng.integers(0, d + 1, size=T - 1)), [d]]).astype(np.int64)
+    norms = torch.full((T, n, 3), -1.0, dtype=torch.float64, device="cuda")
+    ws = torch.empty(P.decentlam_step_multi_workspace(n, d, T) + 256, dtype=torch.uint8, device="cuda")
+    ws = ws[(-ws.data_ptr()) % 256:]
+    P.decentlam_step_multi(bufs[0], bufs[1], bufs[2], offsets, topo, gamma, beta, 2, norms=norms, workspace=ws)
+    torch.cuda.synchronize()
+    xr, mr = oracle.STEP["decentlam"](x0, m0, g0, otopo, gamma, beta, 2)
+    check_elementwise(bufs[0][:, :d].cpu().numpy(), xr, "x")
+    check_elementwise(bufs[1][:, :d].cpu().numpy(), mr, "m")
+    want = oracle.tensor_sumsq(g0, mr.astype(np.float32), xr.astype(np.float32), offsets)
+    np.testing.assert_allclose(norms.cpu().numpy(), want, rtol=3e-6, atol=1e-30)
+
