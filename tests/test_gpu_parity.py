@@ -482,6 +482,52 @@ def test_iteration_is_capturable_in_a_hip_graph(P):
         torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("graph", ["exp_sym", "all_to_all"])
+def test_large_lds_kernels_are_capturable(P, graph):
+    """The 32-node kernels ask for more than 48 KiB of dynamic LDS, which takes a function-attribute
+    call before the launch, also while a stream is being captured; the all-to-all graph takes the
+    matrix-core form of the kernel.  Three replays of two captured iterations against eager execution."""
+    n, d = 32, 3000
+    if graph == "exp_sym":
+        topo = P.topology_build(P.DL_TOPO_EXP_SYM, n)
+    else:
+        topo = P.make_topology(n, np.arange(0, n * n + 1, n), np.tile(np.arange(n), n), np.full(n * n, 1.0 / n, np.float32))
+    gamma, beta = float(np.float32(0.05)), float(np.float32(0.9))
+    gen = torch.Generator(device="cuda").manual_seed(77)
+    x0 = torch.randn((n, d), device="cuda", generator=gen)
+    g = torch.randn((n, d), device="cuda", generator=gen)
+
+    def two_steps(x, m):
+        P.decentlam_step(x, m, g, topo, gamma, beta, 0)
+        P.dmsgd_step(x, m, g, topo, gamma, beta, 1)
+
+    xe, me = x0.clone(), torch.zeros_like(x0)
+    eager = []
+    for _ in range(3):
+        two_steps(xe, me)
+        eager.append((xe.clone(), me.clone()))
+    xg, mg = x0.clone(), torch.zeros_like(x0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        two_steps(xg, mg)
+    torch.cuda.current_stream().wait_stream(side)
+    xg.copy_(x0)
+    mg.zero_()
+    graph_obj = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph_obj, stream=side):
+        two_steps(xg, mg)
+    xg.copy_(x0)
+    mg.zero_()
+    scratch = torch.zeros(1000, device="cuda")
+    for r in range(3):
+        graph_obj.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(xg, eager[r][0]) and torch.equal(mg, eager[r][1]), f"replay {r} differs from eager"
+        scratch.add_(1.0)
+        torch.cuda.synchronize()
+
+
 # ---------------------------------------------------------------- momentum-free DecentLaM
 @pytest.mark.parametrize("kind,n,d,pad,off,steps", [(1, 32, 1030, 2, 0, 6), (2, 8, 1000, 0, 0, 7), (0, 16, 2051, 1, 3, 4),
                                                      (3, 64, 517, 3, 0, 4), (4, 12, 515, 1, 0, 4), (0, 100, 333, 0, 0, 3),
