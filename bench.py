@@ -257,6 +257,23 @@ def bench_xprev(P, workloads, name, steps, warmup):
             "steps_per_s": round(1e3 / kern_ms, 1)}
 
 
+def bench_copy(P, workloads, name, steps, warmup):
+    """What this GPU gives a plain device-to-device copy of one n x ld fp32 array of the workload (torch's
+    copy_: reads and writes 4 * n * ld bytes), as context for the roofline fractions."""
+    import torch
+
+    w = workloads.get(name)
+    ld = padded_ld(workloads.generate.dim(w))
+    src = torch.zeros((w.n, ld), dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    _, ms = time_launches(lambda k: dst.copy_(src), steps, warmup)
+    nbytes = 2.0 * 4.0 * w.n * ld
+    del src, dst
+    torch.cuda.empty_cache()
+    return {"ms": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
 def bench_stats(P, workloads, name, steps, warmup):
     """decentlam_stats (consensus distance, mean norm, error against a reference, momentum norm) on the
     workload's state: one pass over x and m, 8 bytes per node-element plus the reference vector."""
@@ -638,6 +655,7 @@ def main():
         extras["decentlam_step_g16_bf16_c3_exp32"] = bench_g16(P, workloads, "c3_exp32", args.steps, args.warmup)
         extras["decentlam_step_multi_norms_c4_ring16_ragged"] = bench_multi(P, workloads, "c4_ring16_ragged",
                                                                              args.steps, args.warmup)
+        extras["plain_device_copy_c3_array"] = bench_copy(P, workloads, "c3_exp32", args.steps, args.warmup)
         extras["decentlam_stats_c3_exp32"] = bench_stats(P, workloads, "c3_exp32", args.steps, args.warmup)
         extras["local_grad_lsq_c5"] = bench_lsq(P, workloads, "c5_onepeer64_lsq", args.steps, args.warmup)
         # the small least-squares workloads are cache-resident and latency-bound: microseconds only
