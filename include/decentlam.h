@@ -70,6 +70,8 @@ typedef enum {
 #define DL_MAX_NNZ 512            /* entries per phase, arbitrary weights                                 */
 #define DL_MAX_NNZ_PALETTE 1536   /* entries per phase when it holds at most DL_MAX_WEIGHT_VALUES distinct */
 #define DL_MAX_WEIGHT_VALUES 64   /* weight values (true of every topology topology_build produces)       */
+#define DL_MAX_NNZ_ROW_WEIGHTS 2816 /* entries per phase when, besides, every row carries one value only   */
+                                  /* (uniform 1/|N_i| rows: the exponential graph up to 256 nodes)        */
 
 /*
  * topology_build -- neighbour lists and weights of the paper's topologies

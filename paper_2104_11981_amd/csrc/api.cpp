@@ -51,14 +51,15 @@ int pack_phase(const char* fn, int32_t n, const int32_t* row_ptr, const int32_t*
     const int64_t nnz = static_cast<int64_t>(rp[n]) - base;
     if (base < 0 || nnz < n)
         return set_error(DL_ETOPO, "%s: phase %d: row_ptr not monotone or a row is empty", fn, p);
-    if (nnz > kMaxNnzPalette)
-        return set_error(DL_ETOPO, "%s: phase %d has %lld entries, limit DL_MAX_NNZ_PALETTE = %d", fn, p,
-                         static_cast<long long>(nnz), kMaxNnzPalette);
+    if (nnz > kMaxNnzRowWeights)
+        return set_error(DL_ETOPO, "%s: phase %d has %lld entries, limit DL_MAX_NNZ_ROW_WEIGHTS = %d", fn, p,
+                         static_cast<long long>(nnz), kMaxNnzRowWeights);
     out->n = n;
     // first pass: validate, and collect the distinct weight values while there are few of them
     float values[kMaxWeightValues];
     int n_values = 0;
     bool few_values = true;
+    bool one_value_per_row = true;
     int32_t last_seen[DL_MAX_NODES];
     for (int32_t j = 0; j < n; ++j) last_seen[j] = -1;
     for (int32_t i = 0; i < n; ++i) {
@@ -80,6 +81,7 @@ int pack_phase(const char* fn, int32_t n, const int32_t* row_ptr, const int32_t*
                 return set_error(DL_ETOPO, "%s: phase %d: w[%d,%d] = %g must be finite and > 0", fn,
                                  p, i, j, static_cast<double>(wij));
             sum += static_cast<double>(wij);
+            if (wij != w[b]) one_value_per_row = false;
             if (few_values) {
                 int v = 0;
                 while (v < n_values && values[v] != wij) ++v;
@@ -106,6 +108,20 @@ int pack_phase(const char* fn, int32_t n, const int32_t* row_ptr, const int32_t*
     if (!few_values)
         return set_error(DL_ETOPO, "%s: phase %d has %lld entries with more than %d distinct weights, "
                          "limit DL_MAX_NNZ = %d", fn, p, static_cast<long long>(nnz), kMaxWeightValues, DL_MAX_NNZ);
+    if (nnz > kMaxNnzPalette) {
+        if (!one_value_per_row)
+            return set_error(DL_ETOPO, "%s: phase %d has %lld entries and rows of mixed weights, limit "
+                             "DL_MAX_NNZ_PALETTE = %d", fn, p, static_cast<long long>(nnz), kMaxNnzPalette);
+        out->palette = 2;
+        for (int v = 0; v < n_values; ++v) out->rows.value[v] = values[v];
+        for (int64_t q = 0; q < nnz; ++q) out->rows.col[q] = static_cast<uint8_t>(col_idx[base + q]);
+        for (int32_t i = 0; i < n; ++i) {
+            int v = 0;
+            while (values[v] != w[rp[i]]) ++v;
+            out->rows.widx[i] = static_cast<uint8_t>(v);
+        }
+        return DL_OK;
+    }
     out->palette = 1;
     for (int v = 0; v < n_values; ++v) out->pal.value[v] = values[v];
     for (int64_t q = 0; q < nnz; ++q) {

@@ -13,12 +13,15 @@ namespace dl {
 // arguments).  Two encodings of the entries:
 //   direct   up to DL_MAX_NNZ entries, each a column index and its fp32 weight;
 //   palette  up to DL_MAX_NNZ_PALETTE entries, each a column index and an index into a table of at
-//            most DL_MAX_WEIGHT_VALUES distinct fp32 weights (every built-in topology has a handful).
+//            most DL_MAX_WEIGHT_VALUES distinct fp32 weights (every built-in topology has a handful);
+//   rows     up to DL_MAX_NNZ_ROW_WEIGHTS entries, each a column index only: every row carries a single
+//            weight value (an index into the same kind of table per row).
 constexpr int kMaxNnzPalette = DL_MAX_NNZ_PALETTE;
+constexpr int kMaxNnzRowWeights = DL_MAX_NNZ_ROW_WEIGHTS;
 constexpr int kMaxWeightValues = DL_MAX_WEIGHT_VALUES;
 struct PhaseArgs {
     int32_t n;
-    int32_t palette;                     // 0: direct, 1: palette
+    int32_t palette;                     // 0: direct, 1: palette, 2: rows
     union {
         uint16_t row_ptr[DL_MAX_NODES + 1];       // offsets relative to this phase
         uint32_t row_ptr_pairs[DL_MAX_NODES / 2 + 1];   // the same, two per word: what the kernel's scalar loads fetch
@@ -33,6 +36,11 @@ struct PhaseArgs {
             uint8_t widx[kMaxNnzPalette];
             float value[kMaxWeightValues];
         } pal;
+        struct {
+            uint8_t col[kMaxNnzRowWeights];
+            uint8_t widx[DL_MAX_NODES];     // per row
+            float value[kMaxWeightValues];
+        } rows;
     };
 };
 static_assert(sizeof(PhaseArgs) <= 4096 - 128, "kernel-argument segment is 4 KiB");

@@ -2,6 +2,8 @@
 // (the instantiations are split over several files only so that they compile in parallel).
 #pragma once
 
+#include <type_traits>
+
 #include "device_util.hpp"
 #include "internal.hpp"
 
@@ -115,19 +117,32 @@ namespace {
 __device__ __forceinline__ constexpr int lds_col(int v) { return (v >> 1) * 128 + (v & 1); }
 typedef double vd2 __attribute__((ext_vector_type(2)));
 
-// One neighbour in the LDS table.
+// One neighbour in the LDS table.  Lanes of 16 bytes (up to 64 nodes) read the 16-byte form with one
+// access; the narrower lanes (65 nodes and more, where the fp64 tile already takes 128 KiB) use the
+// 8-byte form and widen the weight when they use it, so that graphs of up to DL_MAX_NNZ_ROW_WEIGHTS
+// entries still fit the LDS beside the tile.
 struct alignas(16) Neighbour {
     double w;     // w_ij, promoted exactly from fp32
     int offset;   // j * TC: start of row j in the LDS tile, in doubles
     int unused;
+    __device__ __forceinline__ void set(float weight, int at) { w = static_cast<double>(weight); offset = at; unused = 0; }
+    __device__ __forceinline__ double weight() const { return w; }
 };
+struct alignas(8) NeighbourCompact {
+    float w;
+    int offset;
+    __device__ __forceinline__ void set(float weight, int at) { w = weight; offset = at; }
+    __device__ __forceinline__ double weight() const { return static_cast<double>(w); }
+};
+template <int VEC>
+using NeighbourFor = typename std::conditional<VEC == 4, Neighbour, NeighbourCompact>::type;
 
 // z += sum over K consecutive table entries; all K table reads, then all K tile reads, are
 // issued before the first multiply-add so their latencies overlap.
 template <int VEC, int K>
-__device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, const double* __restrict__ tile_at_lane,
-                                       double (&z)[VEC]) {
-    Neighbour nb[K];
+__device__ __forceinline__ void gather(const NeighbourFor<VEC>* __restrict__ entry,
+                                       const double* __restrict__ tile_at_lane, double (&z)[VEC]) {
+    NeighbourFor<VEC> nb[K];
 #pragma unroll
     for (int t = 0; t < K; ++t) nb[t] = entry[t];
     double u[K][VEC];
@@ -147,7 +162,7 @@ __device__ __forceinline__ void gather(const Neighbour* __restrict__ entry, cons
 #pragma unroll
     for (int t = 0; t < K; ++t) {   // list order, one fused multiply-add per term
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) z[v] = __builtin_fma(nb[t].w, u[t][v], z[v]);
+        for (int v = 0; v < VEC; ++v) z[v] = __builtin_fma(nb[t].weight(), u[t][v], z[v]);
     }
 }
 
@@ -228,7 +243,8 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
     // tile [n][TC] of u_j (DecentLaM) or h_j (DmSGD), then the table; DENSE: [32][STRIDE], then W as operands
     extern __shared__ __attribute__((aligned(16))) double lds[];
     const int n = topo.n;
-    Neighbour* table = reinterpret_cast<Neighbour*>(lds + n * TC);
+    using Entry = NeighbourFor<VEC>;
+    Entry* table = reinterpret_cast<Entry*>(lds + n * TC);
     double* w_operands = lds + kDenseRows * STRIDE;   // DENSE: W, laid out by dense_w_at
 
     const int lane = threadIdx.x & 63;
@@ -319,22 +335,29 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
         }
     }
     if (!DENSE && direct && e_mine < nnz) {
-        Neighbour t;
-        t.w = static_cast<double>(w_mine);
-        t.offset = static_cast<int>(col_mine) * TC;
-        t.unused = 0;
+        Entry t;
+        t.set(w_mine, static_cast<int>(col_mine) * TC);
         table[e_mine] = t;
     }
-    for (int e = DENSE ? nnz : (direct ? e_mine + 64 * WAVES : e_mine); e < nnz; e += 64 * WAVES) {   // later rounds; palette form
-        Neighbour t;
-        if (direct) {
-            t.w = static_cast<double>(topo.direct.w[e]);
-            t.offset = static_cast<int>(topo.direct.col[e]) * TC;
-        } else {
-            t.w = static_cast<double>(topo.pal.value[topo.pal.widx[e]]);
-            t.offset = static_cast<int>(topo.pal.col[e]) * TC;
+    if (!DENSE && topo.palette == 2) {   // one weight per row: every wave writes the entries of its rows
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) {
+            const int i = wave + WAVES * r;
+            if (i < n) {
+                const float w_row = topo.rows.value[topo.rows.widx[i]];
+                for (int e = e_begin[r] + lane; e < e_end[r]; e += 64) {
+                    Entry t;
+                    t.set(w_row, static_cast<int>(topo.rows.col[e]) * TC);
+                    table[e] = t;
+                }
+            }
         }
-        t.unused = 0;
+    }
+    const int e_first = (DENSE || topo.palette == 2) ? nnz : (direct ? e_mine + 64 * WAVES : e_mine);
+    for (int e = e_first; e < nnz; e += 64 * WAVES) {   // later rounds of the direct form; palette form
+        Entry t;
+        if (direct) t.set(topo.direct.w[e], static_cast<int>(topo.direct.col[e]) * TC);
+        else t.set(topo.pal.value[topo.pal.widx[e]], static_cast<int>(topo.pal.col[e]) * TC);
         table[e] = t;
     }
     // local pre-step, parked in LDS
@@ -594,7 +617,8 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
 }
 
 size_t lds_bytes_for(int32_t n, int vec, int nnz, int tiles) {
-    return static_cast<size_t>(tiles) * n * 64 * vec * sizeof(double) + static_cast<size_t>(nnz) * sizeof(Neighbour);
+    const size_t entry = vec == 4 ? sizeof(Neighbour) : sizeof(NeighbourCompact);
+    return static_cast<size_t>(tiles) * n * 64 * vec * sizeof(double) + static_cast<size_t>(nnz) * entry;
 }
 
 template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS, bool DENSE = false>

@@ -126,7 +126,14 @@ def test_step_topology_validation():
     dense = _topo(32, [[(j, 1.0 / 32) for j in range(32)] for _ in range(32)])
     assert _call(fn, n=32, topo=dense) == P.DL_OK          # 1024 entries, one weight value: palette encoding
     dense64 = _topo(64, [[(j, 1.0 / 64) for j in range(64)] for _ in range(64)])
-    assert _call(fn, n=64, topo=dense64) == P.DL_ETOPO and "DL_MAX_NNZ_PALETTE" in P.last_error()
+    assert _call(fn, n=64, topo=dense64) == P.DL_ETOPO and "DL_MAX_NNZ_ROW_WEIGHTS" in P.last_error()
+    dense50 = _topo(50, [[(j, 1.0 / 50) for j in range(50)] for _ in range(50)])
+    assert _call(fn, n=50, topo=dense50) == P.DL_OK        # 2500 entries, one weight per row: column indices only
+    mixed = [[(j, 1.0 / 50) for j in range(50)] for _ in range(50)]
+    mixed[7] = [(j, (1.5 if j == 0 else 0.5 if j == 1 else 1.0) / 50) for j in range(50)]
+    assert _call(fn, n=50, topo=_topo(50, mixed)) == P.DL_ETOPO and "mixed weights" in P.last_error()
+    exp256 = P.topology_build(P.DL_TOPO_EXP_STATIC, 256)    # 9 x 256 = 2304 entries, all 1/9
+    assert _call(fn, n=256, topo=exp256) == P.DL_OK
     rng = np.random.default_rng(0)
     rows = []
     for i in range(30):                                     # 900 entries, all weights different

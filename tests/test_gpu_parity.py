@@ -63,6 +63,9 @@ STEP_CASES = [
     (0, 170, 67, 0, 0, 2, 0.1),
     (0, 256, 67, 0, 0, 2, 0.1),       # 768 entries: beyond DL_MAX_NNZ, palette encoding of the weights
     (1, 128, 70, 0, 0, 2, 0.1),       # 1024 entries
+    (1, 256, 70, 0, 0, 2, 0.1),       # exponential graph at DL_MAX_NODES: 2304 entries, one weight per row, column indices only
+    (3, 128, 131, 1, 0, 3, 0.1),      # symmetric exponential graph on 128 nodes: 1920 entries, the same encoding
+    (1, 200, 64, 0, 0, 2, 0.1),       # 1800 entries
     (3, 64, 300, 0, 0, 3, 0.1),       # symmetric exponential graph on 64 nodes, 768 entries
     (1, 7, 129, 0, 0, 3, 0.1),        # n not a power of two
     (0, 1, 70, 0, 0, 3, 0.1),         # single node: W = [1]

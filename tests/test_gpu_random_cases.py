@@ -33,7 +33,7 @@ def check(gpu, ref, what):
 def one_case(P, oracle, rng, method):
     n = int(rng.choice(NODES))
     kind = int(rng.integers(0, 6))
-    if (kind == 1 and n > 128) or (kind == 3 and n > 64):   # more entries per phase than a call takes
+    if kind == 3 and n > 128:   # more entries per phase than a call takes
         kind = 0
     big = rng.random() < 0.06 and n <= 16
     d = int(rng.integers(1 << 20, (1 << 20) + 70000)) if big else int(rng.integers(1, 3000))

@@ -20,7 +20,8 @@ CASES = [
     (2, 64, 517, 3, 0, 7, 0.05),
     (3, 64, 300, 0, 0, 3, 0.1),       # palette-encoded weights
     (0, 100, 333, 0, 0, 2, 0.1),
-    (1, 128, 70, 0, 0, 2, 0.1),       # DA: two 64 KiB tiles + 16 KiB table
+    (1, 128, 70, 0, 0, 2, 0.1),       # 1024 entries
+    (1, 256, 67, 0, 0, 2, 0.1),       # 2304 entries: one weight per row, column indices only
     (4, 12, 515, 1, 0, 4, 0.05),      # irregular degrees
     (5, 9, 64, 0, 0, 6, 0.1),         # a new matching every iteration
     (0, 1, 70, 0, 0, 3, 0.1),
