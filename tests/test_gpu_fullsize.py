@@ -185,6 +185,22 @@ def test_more_than_2_pow_31_elements_per_array(P, oracle):
     assert abs(got[4] - m2) <= 1e-9 * m2
 
 
+def test_stats_over_more_column_blocks_than_workgroups(P, oracle):
+    """decentlam_stats caps its grid (32768 workgroups of 1024 columns with 16-byte lanes); beyond that
+    width every workgroup walks several blocks of columns.  2 x 40 M: against the oracle on the
+    downloaded arrays."""
+    n, d = 2, 40_000_000
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    x = torch.empty((n, d), dtype=torch.float32, device="cuda").normal_(generator=gen)
+    m = torch.empty((n, d), dtype=torch.float32, device="cuda").normal_(generator=gen)
+    ref = torch.empty(d, dtype=torch.float32, device="cuda").normal_(generator=gen)
+    out = torch.empty(5, dtype=torch.float64, device="cuda")
+    ws = torch.empty(P.decentlam_stats_workspace(n, d), dtype=torch.uint8, device="cuda")
+    P.decentlam_stats(x, m, ref, out, ws)
+    want = oracle.stats(x.cpu().numpy(), m.cpu().numpy(), ref.cpu().numpy())
+    np.testing.assert_allclose(out.cpu().numpy(), want, rtol=1e-10)
+
+
 def test_workload3_bf16_gradients_sampled_columns(P, oracle):
     """n = 32, d = 25.6 M with the gradients stored as bfloat16 (decentlam_step_g16), in the
     benchmark's layout.  The oracle gets the values of the same 16-bit patterns on sampled columns."""
