@@ -109,6 +109,7 @@ MULTI_CASES = [
     (0, 4, 0, [300000, 5, 700000, 128, 127, 129, 8192, 16384, 40000, 65539], 0),
     (0, 4, 4, [300000, 5, 700000, 128, 127, 129, 8192, 16384, 40000, 65539], 3),   # 16 bytes past the start: a shorter launch first
     (1, 32, 0, [1 << 20, 1000, 70000], 0),                                         # two rows per thread
+    (0, 4, 0, [(7 * t) % 23 for t in range(1000)], 0),     # more tensors than one final-pass launch takes (440): three launches
 ]
 
 
