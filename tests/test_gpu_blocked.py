@@ -36,6 +36,8 @@ CASES = [
     (0, 100, 700, 128, 0, 2),       # 4-byte accesses
     (4, 12, 999, 320, 1, 3),
     (0, 3, 7, 1, 0, 2),             # one column per block
+    (1, 256, 300, 64, 0, 2),        # exponential graph on 256 nodes: 2304 entries, one weight per row
+    (1, 24, 2100, 1024, 0, 2),      # twelve waves of two rows
 ]
 
 
