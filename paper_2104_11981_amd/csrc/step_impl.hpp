@@ -2,6 +2,7 @@
 // (the instantiations are split over several files only so that they compile in parallel).
 #pragma once
 
+#include <atomic>
 #include <type_traits>
 
 #include "device_util.hpp"
@@ -631,11 +632,19 @@ int launch_variant(const StepCall& s) {
         return set_error(DL_ETOPO, "step: n = %d with %d entries needs %zu bytes of LDS, a CU has 163840", s.n,
                          static_cast<int>(s.topo->row_ptr[s.n]), lds_bytes);
     if (lds_bytes > 48 * 1024) {
-        if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                   static_cast<int>(lds_bytes)),
-                               "hipFuncSetAttribute(max dynamic LDS)"))
-            return rc;
+        // More than 48 KiB of dynamic LDS takes a function attribute: set once per instantiation and
+        // device to the most this chip has (the call costs about 2 us, a fifth of a small step).
+        static std::atomic<uint32_t> configured{0};   // one bit per device ordinal below 32
+        int device = 0;
+        if (int rc = check_hip(hipGetDevice(&device), "hipGetDevice")) return rc;
+        const uint32_t bit = device >= 0 && device < 32 ? 1u << device : 0u;
+        if (!(configured.load(std::memory_order_relaxed) & bit) || bit == 0) {
+            if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024),
+                                   "hipFuncSetAttribute(max dynamic LDS)"))
+                return rc;
+            configured.fetch_or(bit, std::memory_order_relaxed);
+        }
     }
     const int64_t tiles = (s.d + TC - 1) / TC;
     const int64_t blocks = tiles * s.batches;
