@@ -257,6 +257,24 @@ def bench_xprev(P, workloads, name, steps, warmup):
             "steps_per_s": round(1e3 / kern_ms, 1)}
 
 
+def bench_shape(P, n, d, kind, steps, warmup):
+    """decentlam_step on a synthetic n x d state with a built-in graph (values N(0,1), zero momentum)."""
+    import torch
+
+    topo = P.topology_build(kind, n)
+    x, m, g = (P.empty_rows(n, d) for _ in range(3))
+    x.normal_()
+    m.zero_()
+    g.normal_()
+    _, ms = time_launches(lambda k: P.decentlam_step(x, m, g, topo, 0.01, 0.9, k), steps, warmup)
+    nbytes = BYTES_PER_ELEMENT * n * d
+    del x, m, g
+    torch.cuda.empty_cache()
+    return {"n": n, "d": d, "kernel_ms": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "steps_per_s": round(1e3 / ms, 1)}
+
+
 def bench_copy(P, workloads, name, steps, warmup):
     """What this GPU gives a plain device-to-device copy of one n x ld fp32 array of the workload (torch's
     copy_: reads and writes 4 * n * ld bytes), as context for the roofline fractions."""
@@ -655,6 +673,9 @@ def main():
         extras["decentlam_step_g16_bf16_c3_exp32"] = bench_g16(P, workloads, "c3_exp32", args.steps, args.warmup)
         extras["decentlam_step_multi_norms_c4_ring16_ragged"] = bench_multi(P, workloads, "c4_ring16_ragged",
                                                                              args.steps, args.warmup)
+        # the paper's own scale: 8 nodes (its servers), symmetric exponential graph, a ResNet-50-sized vector
+        extras["decentlam_step_8_nodes_sym_exp_25.6M"] = bench_shape(P, 8, 25_600_000, P.DL_TOPO_EXP_SYM,
+                                                                    args.steps, args.warmup)
         extras["plain_device_copy_c3_array"] = bench_copy(P, workloads, "c3_exp32", args.steps, args.warmup)
         extras["decentlam_stats_c3_exp32"] = bench_stats(P, workloads, "c3_exp32", args.steps, args.warmup)
         extras["local_grad_lsq_c5"] = bench_lsq(P, workloads, "c5_onepeer64_lsq", args.steps, args.warmup)
