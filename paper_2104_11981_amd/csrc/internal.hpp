@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <cstdint>
 
 #include "decentlam.h"
@@ -44,6 +45,10 @@ struct PhaseArgs {
     };
 };
 static_assert(sizeof(PhaseArgs) <= 4096 - 128, "kernel-argument segment is 4 KiB");
+static_assert(offsetof(PhaseArgs, pal.value) == offsetof(PhaseArgs, rows.value) &&
+              offsetof(PhaseArgs, pal.col) == offsetof(PhaseArgs, rows.col) &&
+              offsetof(PhaseArgs, direct.col) == offsetof(PhaseArgs, rows.col),
+              "the kernels read the column bytes and the palette of any encoding through one member");
 
 enum Algo { ALGO_DECENTLAM = 0, ALGO_DMSGD = 1, ALGO_DSGD = 2, ALGO_DECENTLAM_XPREV = 3, ALGO_AWC_DMSGD = 4,
             ALGO_DA_DMSGD = 5 };

@@ -75,7 +75,8 @@ struct StepCall {
 
 // Dense mixing on the matrix cores (mix_dense below): constants and the two host-checkable functions.
 constexpr int kDensePad = 16;
-constexpr int kDenseRows = 32;   // rows of the padded problem: two 16-row blocks, eight groups of four
+constexpr int kDenseRows = 32;   // rows of the padded problem: two 16-row blocks, eight groups of four ...
+constexpr int kDenseRowsMax = 48;   // ... or three blocks and twelve groups (33-48 nodes, three rows per thread)
 // Where element (i, k) of W sits in its LDS array, in doubles: per block of 16 rows, sixteen slabs (one
 // per pair of columns) of 16 rows x 2 columns, two doubles of padding after each.  With the padding
 // both access patterns are free of bank conflicts: a wave that writes one row of W (lane = column)
@@ -83,11 +84,11 @@ constexpr int kDenseRows = 32;   // rows of the padded problem: two 16-row block
 // 2 columns of one slab).  (Without it the row writes were 16-way conflicts: 42 % of the kernel's LDS
 // cycles, measured.)
 constexpr int kDenseSlab = 2 * 16 + 2;
-constexpr int kDenseBlock = (kDenseRows / 2) * kDenseSlab;
-constexpr int kDenseWDoubles = 2 * kDenseBlock;
-__host__ __device__ constexpr int dense_w_at(int i, int k) {
-    return (i >> 4) * kDenseBlock + (k >> 1) * kDenseSlab + (i & 15) * 2 + (k & 1);
+__host__ __device__ constexpr int dense_w_doubles(int rows) { return (rows / 16) * (rows / 2) * kDenseSlab; }
+__host__ __device__ constexpr int dense_w_at(int i, int k, int rows = kDenseRows) {
+    return (i >> 4) * (rows / 2) * kDenseSlab + (k >> 1) * kDenseSlab + (i & 15) * 2 + (k & 1);
 }
+constexpr int kDenseWDoubles = dense_w_doubles(kDenseRows);
 // Where the matrix cores (mix_dense) beat the gather, measured with DecentLaM on c3-sized arrays
 // (n x d = 819 M elements) and circulant graphs: the product costs the same at any density but more
 // per byte the fewer rows a tile has (32 / 28 / 24 / 20 nodes: 2.70 / 2.95 / 3.22 / 3.32 ms), the
@@ -95,7 +96,14 @@ __host__ __device__ constexpr int dense_w_at(int i, int k) {
 // 28 nodes: 2.89 / 3.00 / 3.53 at 16 / 18 / 28; 24 nodes: 3.22 / 3.34 / 3.46 at 20 / 22 / 24; 20 nodes:
 // 3.21 at 20).  The two cross at about 46 - n entries per row: 14 at 32 nodes, 18 at 28, 22 at 24,
 // never below 23 nodes.
-inline bool mixes_on_matrix_cores(int n, int nnz) { return n > 16 && n <= kDenseRows && nnz >= (46 - n) * n; }
+// Three row blocks (33-48 nodes, one workgroup per CU), same arrays: the product takes 4.55 / 4.35 / 3.9 ms
+// at 36 / 40 / 48 nodes, the gather 3.8 / 3.7 / 3.5 ms at 23 entries per row, 4.4 / 4.4 / 4.2 at 32 and
+// 4.9 / 5.2 / 5.5 at all-to-all: they cross at about 52 - n / 2 entries per row (28 at 48 nodes, 32 at 40,
+// 34 at 36).
+inline bool mixes_on_matrix_cores(int n, int nnz) {
+    if (n > kDenseRows) return n <= kDenseRowsMax && 2 * nnz >= (104 - n) * n;
+    return n > 16 && nnz >= (46 - n) * n;
+}
 
 // Launch the kernel of one method for the given vector width, gradient format and sums option
 // (defined in step_<method>.hip).
@@ -167,8 +175,9 @@ __device__ __forceinline__ void gather(const NeighbourFor<VEC>* __restrict__ ent
     }
 }
 
-// Dense W (up to 32 nodes, most pairs neighbours; see mixes_on_matrix_cores): the mixing of a tile is the fp64 contraction
-// Z[32 x TC] = W[32 x 32] * U[32 x TC], and it runs on the matrix cores (v_mfma_f64_16x16x4_f64)
+// Dense W (up to 48 nodes, most pairs neighbours; see mixes_on_matrix_cores): the mixing of a tile is the fp64 contraction
+// Z[32 x TC] = W[32 x 32] * U[32 x TC] (48 x 48 for 33-48 nodes: three blocks of 16 rows where this text says
+// two), and it runs on the matrix cores (v_mfma_f64_16x16x4_f64)
 // instead of |N_i| LDS gathers per row.  Wave w owns the 16 positions [16 w, 16 w + 16) of every
 // tile row: for each of the eight groups of four rows it reads its 4 x 16 block of U as the B
 // operand (lane l: row l / 16 of the group, position l % 16), multiplies it with the two 16 x 4
@@ -181,24 +190,28 @@ __device__ __forceinline__ void gather(const NeighbourFor<VEC>* __restrict__ ent
 // inside the fp32 rounding of the result.  A zero weight multiplies its node's value like any other,
 // so a non-finite value in one node's column reaches every node of that column, neighbour or not.
 typedef double vd4 __attribute__((ext_vector_type(4)));
-template <int STRIDE>
+template <int STRIDE, int RB>
 __device__ __forceinline__ void mix_dense(double* __restrict__ tile, const double* __restrict__ w_operands, int n, int wave,
                                           int lane) {
+    constexpr int ROWS = 16 * RB;
     double* mine = tile + (lane >> 4) * STRIDE + 16 * wave + (lane & 15);
-    const double* a_at = w_operands + dense_w_at(lane & 15, lane >> 4);   // + dense_w_at(16 rb, 4 s) per operand
-    vd4 lo = {0.0, 0.0, 0.0, 0.0}, hi = {0.0, 0.0, 0.0, 0.0};
+    const double* a_at = w_operands + dense_w_at(lane & 15, lane >> 4, ROWS);   // + dense_w_at(16 rb, 4 s) per operand
+    vd4 acc[RB];
 #pragma unroll
-    for (int s = 0; s < kDenseRows / 4; ++s) {
+    for (int rb = 0; rb < RB; ++rb) acc[rb] = vd4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int s = 0; s < ROWS / 4; ++s) {
         if (4 * s < n) {   // uniform; rows from n on hold zeros, whole groups of them are skipped
             const double b = mine[4 * s * STRIDE];
-            lo = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[dense_w_at(0, 4 * s)], b, lo, 0, 0, 0);
-            hi = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[dense_w_at(16, 4 * s)], b, hi, 0, 0, 0);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                acc[rb] = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[dense_w_at(16 * rb, 4 * s, ROWS)], b, acc[rb], 0, 0, 0);
         }
     }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        mine[4 * r * STRIDE] = lo[r];
-        mine[(16 + 4 * r) * STRIDE] = hi[r];
+    for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mine[(16 * rb + 4 * r) * STRIDE] = acc[rb][r];
     }
 }
 
@@ -230,7 +243,8 @@ constexpr int stagger_units() {
 //        ALGO_AWC_DMSGD (m <- beta m + g; x <- W x - gamma m: the tile holds x) and ALGO_DA_DMSGD
 //        (mh = beta m + g; x <- W (x - gamma mh); m <- W mh: the tile holds h, then mh, each gathered)
 // GF     dl_grad_format of g;  NORMS: accumulate the per-tensor sums of squares
-// DENSE  mix on the matrix cores (see mix_dense): 16-byte lanes, 17-32 nodes (used from 23 on)
+// DENSE  mix on the matrix cores (see mix_dense): 16-byte lanes, 16 waves with two rows per thread
+//        (17-32 nodes, used from 23 on) or three (33-48 nodes)
 template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS, bool DENSE = false>
 __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, float* __restrict__ m,
                                                       const typename GradElem<GF>::type* __restrict__ g,
@@ -239,14 +253,15 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                                                       const BatchArgs batch, const NormArgs na,
                                                       const PhaseArgs topo) {
     constexpr int TC = 64 * VEC;
-    static_assert(!DENSE || (VEC == 4 && RPT == 2 && WAVES == 16), "dense mixing: one shape");
+    static_assert(!DENSE || (VEC == 4 && (RPT == 2 || RPT == 3) && WAVES == 16), "dense mixing: two shapes");
+    constexpr int DROWS = 16 * RPT;   // DENSE: rows of the padded problem
     constexpr int STRIDE = DENSE ? TC + kDensePad : TC;   // doubles from one tile row to the next
     // tile [n][TC] of u_j (DecentLaM) or h_j (DmSGD), then the table; DENSE: [32][STRIDE], then W as operands
     extern __shared__ __attribute__((aligned(16))) double lds[];
     const int n = topo.n;
     using Entry = NeighbourFor<VEC>;
     Entry* table = reinterpret_cast<Entry*>(lds + n * TC);
-    double* w_operands = lds + kDenseRows * STRIDE;   // DENSE: W, laid out by dense_w_at
+    double* w_operands = lds + DROWS * STRIDE;   // DENSE: W, laid out by dense_w_at
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -329,9 +344,9 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
 #pragma unroll
         for (int r = 0; r < RPT; ++r) {
             const int e = e_begin[r] + lane;
-            const int e_row = e < e_end[r] ? e : 0;   // both encodings keep their columns in the same bytes
-            dense_col[r] = topo.pal.col[e_row];
-            dense_widx[r] = topo.pal.widx[e_row];
+            const int e_row = e < e_end[r] ? e : 0;   // all encodings keep their columns in the same bytes
+            dense_col[r] = topo.rows.col[e_row];
+            dense_widx[r] = topo.pal.widx[topo.palette == 1 ? e_row : 0];
             dense_w[r] = topo.direct.w[direct ? e_row : 0];
         }
     }
@@ -368,12 +383,15 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
         double sq_g = 0.0, sq_m = 0.0;   // this lane's share (NORMS)
         if constexpr (DENSE) {
             // row i of W: zeros, then the entries of the list
-            double* w_row = w_operands + dense_w_at(i, 0);
-            if (lane < kDenseRows) w_row[dense_w_at(0, lane)] = 0.0;
-            const float from_palette = __shfl(palette_mine, static_cast<int>(dense_widx[r] & 63u));
+            double* w_row = w_operands + dense_w_at(i, 0, DROWS);
+            if (lane < DROWS) w_row[dense_w_at(0, lane, DROWS)] = 0.0;
+            // the weight: its own (direct), by the entry's palette index, or by the row's (the palettes of the
+            // two forms sit in the same bytes)
+            const unsigned widx = topo.palette == 2 ? topo.rows.widx[i < n ? i : 0] : dense_widx[r];
+            const float from_palette = __shfl(palette_mine, static_cast<int>(widx & 63u));
             if (i < n && e_begin[r] + lane < e_end[r]) {
                 const unsigned k = dense_col[r];
-                w_row[dense_w_at(0, static_cast<int>(k))] = static_cast<double>(direct ? dense_w[r] : from_palette);
+                w_row[dense_w_at(0, static_cast<int>(k), DROWS)] = static_cast<double>(direct ? dense_w[r] : from_palette);
             }
             if (i >= n) {   // uniform: a row of the padding, all zeros
                 double* pad = lds + i * STRIDE + lane * 2;
@@ -455,7 +473,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
     // ---- phase 2: gather-mix from LDS, finish the update, store in place
     const double* tile_at_lane = lds + lane * (VEC >= 2 ? 2 : 1);
     if constexpr (DENSE) {
-        mix_dense<STRIDE>(lds, w_operands, n, wave, lane);
+        mix_dense<STRIDE, RPT>(lds, w_operands, n, wave, lane);
         __syncthreads();   // the tile now holds Z = W U
     }
 #pragma unroll
@@ -585,7 +603,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
         }
         __syncthreads();
         if constexpr (DENSE) {
-            mix_dense<STRIDE>(lds, w_operands, n, wave, lane);
+            mix_dense<STRIDE, RPT>(lds, w_operands, n, wave, lane);
             __syncthreads();
         }
 #pragma unroll
@@ -625,7 +643,7 @@ size_t lds_bytes_for(int32_t n, int vec, int nnz, int tiles) {
 template <int VEC, int RPT, int WAVES, int ALGO, int GF, bool NORMS, bool DENSE = false>
 int launch_variant(const StepCall& s) {
     constexpr int TC = 64 * VEC;
-    const size_t lds_bytes = DENSE ? (static_cast<size_t>(kDenseRows) * (TC + kDensePad) + kDenseWDoubles) * sizeof(double)
+    const size_t lds_bytes = DENSE ? (static_cast<size_t>(16 * RPT) * (TC + kDensePad) + dense_w_doubles(16 * RPT)) * sizeof(double)
                                    : lds_bytes_for(s.n, VEC, s.topo->row_ptr[s.n], 1);
     auto kernel = k_step<VEC, RPT, WAVES, ALGO, GF, NORMS, DENSE>;
     if (lds_bytes > 160 * 1024)
@@ -671,8 +689,10 @@ int launch_variant(const StepCall& s) {
 template <int VEC, int ALGO, int GF, bool NORMS>
 int launch_rows(const StepCall& s) {
     if constexpr (VEC == 4) {
-        if (mixes_on_matrix_cores(s.n, s.topo->row_ptr[s.n]))
-            return launch_variant<4, 2, 16, ALGO, GF, NORMS, true>(s);
+        if (mixes_on_matrix_cores(s.n, s.topo->row_ptr[s.n])) {
+            if (s.n <= kDenseRows) return launch_variant<4, 2, 16, ALGO, GF, NORMS, true>(s);
+            return launch_variant<4, 3, 16, ALGO, GF, NORMS, true>(s);
+        }
     }
 #define DL_SHAPE(MAXN, W, R)                                                             \
     if constexpr (VEC == 1 || VEC * (MAXN) <= 256) {                                     \

@@ -151,36 +151,46 @@ DENSE_CHECK = r"""
 // inside the array; a wave writing one row (lane = column) and a half-wave reading an A operand of the
 // 16x16x4 instruction (lane l: row l % 16, column l / 16 of the 16 x 4 block) touch 32 different
 // 8-byte banks; the kernel's way of composing an operand address from a per-lane and a per-block part
-// gives the same slot.  And the switch-over rule: 46 - n entries per row, nothing below 23 nodes.
-int main() {
+// gives the same slot.  And the switch-over rule: 46 - n entries per row up to 32 nodes (nothing below 23
+// nodes), 52 - n / 2 entries per row from 33 to 48 nodes.
+int check_layout(int rows) {   // the padded problem has `rows` rows and columns: 32 or 48
     using namespace dl::step;
     std::set<int> seen;
-    for (int i = 0; i < kDenseRows; ++i)
-        for (int k = 0; k < kDenseRows; ++k) {
-            const int at = dense_w_at(i, k);
-            if (at < 0 || at >= kDenseWDoubles || !seen.insert(at).second) return 1;
+    for (int i = 0; i < rows; ++i)
+        for (int k = 0; k < rows; ++k) {
+            const int at = dense_w_at(i, k, rows);
+            if (at < 0 || at >= dense_w_doubles(rows) || !seen.insert(at).second) return 1;
         }
-    for (int i = 0; i < kDenseRows; ++i) {   // row write
-        std::set<int> banks;
-        for (int k = 0; k < kDenseRows; ++k) banks.insert(dense_w_at(i, k) % 32);
-        if (banks.size() != 32) return 2;
-        for (int k = 0; k < kDenseRows; ++k)
-            if (dense_w_at(i, k) != dense_w_at(i, 0) + dense_w_at(0, k)) return 3;
+    for (int i = 0; i < rows; ++i) {   // row write: lanes 0-31, then the rest
+        for (int first = 0; first < rows; first += 32) {
+            std::set<int> banks;
+            const int last = first + 32 < rows ? first + 32 : rows;
+            for (int k = first; k < last; ++k) banks.insert(dense_w_at(i, k, rows) % 32);
+            if (static_cast<int>(banks.size()) != last - first) return 2;
+        }
+        for (int k = 0; k < rows; ++k)
+            if (dense_w_at(i, k, rows) != dense_w_at(i, 0, rows) + dense_w_at(0, k, rows)) return 3;
     }
-    for (int rb = 0; rb < 2; ++rb)
-        for (int s = 0; s < kDenseRows / 4; ++s)
+    for (int rb = 0; rb < rows / 16; ++rb)
+        for (int s = 0; s < rows / 4; ++s)
             for (int half = 0; half < 2; ++half) {   // operand read, 32 lanes at a time
                 std::set<int> banks;
                 for (int lane = 32 * half; lane < 32 * half + 32; ++lane) {
-                    const int at = dense_w_at(16 * rb + (lane & 15), 4 * s + (lane >> 4));
-                    if (at != dense_w_at(lane & 15, lane >> 4) + dense_w_at(16 * rb, 4 * s)) return 4;
+                    const int at = dense_w_at(16 * rb + (lane & 15), 4 * s + (lane >> 4), rows);
+                    if (at != dense_w_at(lane & 15, lane >> 4, rows) + dense_w_at(16 * rb, 4 * s, rows)) return 4;
                     banks.insert(at % 32);
                 }
                 if (banks.size() != 32) return 5;
             }
-    for (int n = 1; n <= 40; ++n)
+    return 0;
+}
+int main() {
+    using namespace dl::step;
+    if (int rc = check_layout(kDenseRows)) return rc;
+    if (int rc = check_layout(kDenseRowsMax)) return 10 + rc;
+    for (int n = 1; n <= 60; ++n)
         for (int per_row = 1; per_row <= n; ++per_row) {
-            const bool want = n >= 23 && n <= 32 && per_row >= 46 - n;
+            const bool want = (n >= 23 && n <= 32 && per_row >= 46 - n) || (n >= 33 && n <= 48 && 2 * per_row >= 104 - n);
             if (mixes_on_matrix_cores(n, per_row * n) != want) return 6;
         }
     std::puts("ok");
