@@ -95,6 +95,18 @@ def test_dense_kernel_multiplies_on_the_matrix_cores(dense_kernel_asm):
     assert not re.search(r"scratch_(load|store)", text)
 
 
+def test_three_block_dense_kernel(decentlam_asm):
+    """33-48 nodes: 48 x 48 times 48 x 16 per wave, thirty-six products; one workgroup per CU, so up to 128
+    registers are fine, scratch is not."""
+    ins = instantiation(decentlam_asm, "Li4ELi3ELi16ELi0ELi0ELb0ELb1")
+    assert len([i for i in ins if i.startswith("v_mfma_f64_16x16x4")]) == 36
+    assert len([i for i in ins if i.startswith("s_barrier")]) == 2
+    text = "\n".join(ins)
+    m = re.search(r"\.amdhsa_next_free_vgpr\s+(\d+)", text)
+    assert m and int(m.group(1)) <= 128
+    assert not re.search(r"scratch_(load|store)", text)
+
+
 SPLIT_CHECK = r"""
 #include <cstdio>
 #include <vector>
