@@ -685,6 +685,8 @@ int launch_variant(const StepCall& s) {
 //                 not spread evenly over four SIMDs)
 //   33-48 nodes   16 x 3 against 16 x 4 (whose fourth row slot loads a stand-in row): 6.1 / 5.9 / 6.05 against
 //                 5.8 / 5.6 / 5.75 at 36 / 40 / 48 nodes
+//   65-96, 129-192 nodes   16 x 6 and 16 x 12 against 16 x 8 and 16 x 16: 5.0 / 5.3 / 4.7 / 4.85 against 4.7 / 5.05 /
+//                 4.3 / 4.5 at 80 / 96 / 160 / 192 nodes
 //   1-8 nodes     two rows per thread (1 x 2, 2 x 2, 4 x 2) measured equal or worse than one (6.4-6.6)
 template <int VEC, int ALGO, int GF, bool NORMS>
 int launch_rows(const StepCall& s) {
@@ -699,7 +701,7 @@ int launch_rows(const StepCall& s) {
         if (s.n <= (MAXN)) return launch_variant<VEC, R, W, ALGO, GF, NORMS>(s);         \
     }
     DL_SHAPE(1, 1, 1) DL_SHAPE(2, 2, 1) DL_SHAPE(4, 4, 1) DL_SHAPE(8, 8, 1) DL_SHAPE(16, 8, 2) DL_SHAPE(20, 10, 2) DL_SHAPE(24, 12, 2) DL_SHAPE(32, 16, 2) DL_SHAPE(48, 16, 3)
-    DL_SHAPE(64, 16, 4) DL_SHAPE(128, 16, 8) DL_SHAPE(256, 16, 16)
+    DL_SHAPE(64, 16, 4) DL_SHAPE(96, 16, 6) DL_SHAPE(128, 16, 8) DL_SHAPE(192, 16, 12) DL_SHAPE(256, 16, 16)
 #undef DL_SHAPE
     return set_error(DL_ETOPO, "step: n = %d has no kernel variant at vector width %d", s.n, VEC);
 }

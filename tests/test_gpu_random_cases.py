@@ -10,7 +10,7 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
-NODES = [1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 20, 21, 24, 25, 31, 32, 33, 40, 48, 49, 64, 65, 100, 128, 200, 256]
+NODES = [1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 20, 21, 24, 25, 31, 32, 33, 40, 48, 49, 64, 65, 96, 100, 128, 160, 200, 256]
 METHODS = ["decentlam", "dmsgd", "dsgd", "xprev", "awc_dmsgd", "da_dmsgd", "multi", "blocked", "g16"]
 SENT = 777.0
 
