@@ -143,7 +143,7 @@ int topology_metropolis(int32_t n, const int32_t* row_ptr, const int32_t* col_id
  * 16384): the step then writes whole 64 KiB-aligned address pairs (A, A + 32 KiB), worth
  * about 10 % at every node count (measured at n = 32, d = 25.6 M: 2.51 instead of 2.80 ms).
  * Dense graphs (23 <= n <= 32 with 46 - n or more entries per row on average: 14 at n = 32, all
- * 23 at n = 23; 33 <= n <= 48 with 52 - n / 2 or more; this holds for every step entry point): the partial averaging runs as an fp64 matrix product on the matrix cores
+ * 23 at n = 23; 33 <= n <= 48 with 38 - n / 4 or more; this holds for every step entry point): the partial averaging runs as an fp64 matrix product on the matrix cores
  * instead of neighbour by neighbour (all-to-all at n = 32, d = 25.6 M: 2.7 instead of 3.5 ms).
  * The sums are then taken in the instruction's order, not list order (differences in the last
  * bits of fp64, before the one rounding to fp32), and absent pairs enter with weight zero: a

@@ -39,7 +39,10 @@ struct PhaseArgs {
         } pal;
         struct {
             uint8_t col[kMaxNnzRowWeights];
-            uint8_t widx[DL_MAX_NODES];     // per row
+            union {
+                uint8_t widx[DL_MAX_NODES];          // per row
+                uint32_t widx_words[DL_MAX_NODES / 4];   // the same, four per word: what the kernel's scalar loads fetch
+            };
             float value[kMaxWeightValues];
         } rows;
     };

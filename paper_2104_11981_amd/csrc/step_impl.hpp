@@ -96,12 +96,12 @@ constexpr int kDenseWDoubles = dense_w_doubles(kDenseRows);
 // 28 nodes: 2.89 / 3.00 / 3.53 at 16 / 18 / 28; 24 nodes: 3.22 / 3.34 / 3.46 at 20 / 22 / 24; 20 nodes:
 // 3.21 at 20).  The two cross at about 46 - n entries per row: 14 at 32 nodes, 18 at 28, 22 at 24,
 // never below 23 nodes.
-// Three row blocks (33-48 nodes, one workgroup per CU), same arrays: the product takes 4.55 / 4.35 / 3.9 ms
-// at 36 / 40 / 48 nodes, the gather 3.8 / 3.7 / 3.5 ms at 23 entries per row, 4.4 / 4.4 / 4.2 at 32 and
-// 4.9 / 5.2 / 5.5 at all-to-all: they cross at about 52 - n / 2 entries per row (28 at 48 nodes, 32 at 40,
-// 34 at 36).
+// Three row blocks (33-48 nodes, one workgroup per CU), same arrays: the product takes 4.25 / 4.0 / 3.6 ms
+// at 36 / 40 / 48 nodes, the gather 3.85 / 3.75 / 3.5 ms at 23 entries per row, 4.2 / 4.1 / 3.9 at 28 and
+// 4.9 / 5.2 / 5.5 at all-to-all: they cross at about 38 - n / 4 entries per row (26 at 48 nodes, 28 at 40,
+// 29 at 36).
 inline bool mixes_on_matrix_cores(int n, int nnz) {
-    if (n > kDenseRows) return n <= kDenseRowsMax && 2 * nnz >= (104 - n) * n;
+    if (n > kDenseRows) return n <= kDenseRowsMax && 4 * nnz >= (152 - n) * n;
     return n > 16 && nnz >= (46 - n) * n;
 }
 
@@ -125,6 +125,13 @@ namespace {
 // 2.57 / 2.78 / 3.53 ms against 2.62 / 2.91 / 4.14).
 __device__ __forceinline__ constexpr int lds_col(int v) { return (v >> 1) * 128 + (v & 1); }
 typedef double vd2 __attribute__((ext_vector_type(2)));
+
+// The palette index of a row in the one-weight-per-row form of the neighbour list, for a uniform row: a
+// word load and a shift, because there are no scalar byte loads and a vector load from the kernel
+// arguments would be waited for together with every row load before it.
+__device__ __forceinline__ unsigned row_palette_index(const PhaseArgs& topo, int row) {
+    return (topo.rows.widx_words[row >> 2] >> (8 * (row & 3))) & 0xffu;
+}
 
 // One neighbour in the LDS table.  Lanes of 16 bytes (up to 64 nodes) read the 16-byte form with one
 // access; the narrower lanes (65 nodes and more, where the fp64 tile already takes 128 KiB) use the
@@ -196,22 +203,24 @@ __device__ __forceinline__ void mix_dense(double* __restrict__ tile, const doubl
     constexpr int ROWS = 16 * RB;
     double* mine = tile + (lane >> 4) * STRIDE + 16 * wave + (lane & 15);
     const double* a_at = w_operands + dense_w_at(lane & 15, lane >> 4, ROWS);   // + dense_w_at(16 rb, 4 s) per operand
-    vd4 acc[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) acc[rb] = vd4{0.0, 0.0, 0.0, 0.0};
+    // one named accumulator per row block (an array of them made the compiler copy all of them after
+    // every step, each copy waiting for its instruction to finish: 2.88 instead of 2.66 ms at 32 nodes)
+    vd4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0}, acc2 = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int s = 0; s < ROWS / 4; ++s) {
         if (4 * s < n) {   // uniform; rows from n on hold zeros, whole groups of them are skipped
             const double b = mine[4 * s * STRIDE];
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-                acc[rb] = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[dense_w_at(16 * rb, 4 * s, ROWS)], b, acc[rb], 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[dense_w_at(0, 4 * s, ROWS)], b, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[dense_w_at(16, 4 * s, ROWS)], b, acc1, 0, 0, 0);
+            if constexpr (RB == 3)
+                acc2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a_at[dense_w_at(32, 4 * s, ROWS)], b, acc2, 0, 0, 0);
         }
     }
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) mine[(16 * rb + 4 * r) * STRIDE] = acc[rb][r];
+    for (int r = 0; r < 4; ++r) {
+        mine[4 * r * STRIDE] = acc0[r];
+        mine[(16 + 4 * r) * STRIDE] = acc1[r];
+        if constexpr (RB == 3) mine[(32 + 4 * r) * STRIDE] = acc2[r];
     }
 }
 
@@ -360,7 +369,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
         for (int r = 0; r < RPT; ++r) {
             const int i = wave + WAVES * r;
             if (i < n) {
-                const float w_row = topo.rows.value[topo.rows.widx[i]];
+                const float w_row = topo.rows.value[row_palette_index(topo, i)];
                 for (int e = e_begin[r] + lane; e < e_end[r]; e += 64) {
                     Entry t;
                     t.set(w_row, static_cast<int>(topo.rows.col[e]) * TC);
@@ -387,7 +396,8 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
             if (lane < DROWS) w_row[dense_w_at(0, lane, DROWS)] = 0.0;
             // the weight: its own (direct), by the entry's palette index, or by the row's (the palettes of the
             // two forms sit in the same bytes)
-            const unsigned widx = topo.palette == 2 ? topo.rows.widx[i < n ? i : 0] : dense_widx[r];
+            unsigned widx = dense_widx[r];
+            if (topo.palette == 2) widx = row_palette_index(topo, i < n ? i : 0);   // uniform
             const float from_palette = __shfl(palette_mine, static_cast<int>(widx & 63u));
             if (i < n && e_begin[r] + lane < e_end[r]) {
                 const unsigned k = dense_col[r];

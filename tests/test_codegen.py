@@ -164,7 +164,7 @@ DENSE_CHECK = r"""
 // 16x16x4 instruction (lane l: row l % 16, column l / 16 of the 16 x 4 block) touch 32 different
 // 8-byte banks; the kernel's way of composing an operand address from a per-lane and a per-block part
 // gives the same slot.  And the switch-over rule: 46 - n entries per row up to 32 nodes (nothing below 23
-// nodes), 52 - n / 2 entries per row from 33 to 48 nodes.
+// nodes), 38 - n / 4 entries per row from 33 to 48 nodes.
 int check_layout(int rows) {   // the padded problem has `rows` rows and columns: 32 or 48
     using namespace dl::step;
     std::set<int> seen;
@@ -202,7 +202,7 @@ int main() {
     if (int rc = check_layout(kDenseRowsMax)) return 10 + rc;
     for (int n = 1; n <= 60; ++n)
         for (int per_row = 1; per_row <= n; ++per_row) {
-            const bool want = (n >= 23 && n <= 32 && per_row >= 46 - n) || (n >= 33 && n <= 48 && 2 * per_row >= 104 - n);
+            const bool want = (n >= 23 && n <= 32 && per_row >= 46 - n) || (n >= 33 && n <= 48 && 4 * per_row >= 152 - n);
             if (mixes_on_matrix_cores(n, per_row * n) != want) return 6;
         }
     std::puts("ok");
