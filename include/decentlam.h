@@ -372,6 +372,30 @@ int local_grad_lsq(const float* A, const float* y, const float* x,
                    float scale, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * local_grad_lsq_static -- local_grad_lsq for callers that cannot allocate or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same
+ * results bit for bit; the partial sums live in an array of DL_STATIC_SCRATCH_BYTES that is part of
+ * the library's device image (every GPU the library runs on holds its own copy until the process
+ * ends).  The call allocates nothing and frees nothing.
+ *   Limit: the partial sums of the kernels this shape and alignment select must fit
+ *   DL_STATIC_SCRATCH_BYTES (32 MiB).  With 16-byte aligned rows and d <= 16384 (one sweep over A)
+ *   that is about n * max(1, 512 / n) * (d + 1) * 8 bytes (n = 64 nodes of 4096 x 4096: 16.8 MB), never
+ *   more than local_grad_lsq_workspace(n, b, d).  Larger problems return DL_ECAP (nothing is launched)
+ *   and belong to local_grad_lsq.
+ *   All calls on one GPU share that GPU's array: calls that may overlap in time (different streams,
+ *   different threads) race on it and must be serialised by the caller.  The array keeps the last
+ *   call's contents; every call writes each partial sum before it reads it, so nothing needs clearing.
+ *   The first call on a device looks the array's address up (this may load the library's device
+ *   code): make it once outside of graph capture.
+ * Arguments and the other errors as local_grad_lsq.
+ */
+#define DL_STATIC_SCRATCH_BYTES (32u << 20)
+int local_grad_lsq_static(const float* A, const float* y, const float* x,
+                          float* g, float* loss,
+                          int32_t n, int32_t b, int64_t d, int64_t ldA, int64_t ld,
+                          float scale, void* stream);
+
+/*
  * local_grad_lsq_rows -- the stochastic (mini-batch) version: node i's sample xi_i (Algorithms 1
  * and 2, "Sample xi_i") is a list of bs row indices into its local data, drawn by the caller:
  *     g_i = scale * sum_{t < bs} a_t (a_t . x_i - y_i[r_t]),  r_t = rows[i*bs + t],  a_t = A_i[r_t, :]

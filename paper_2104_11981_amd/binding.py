@@ -29,11 +29,13 @@ DL_FLAG_ROW_STOCHASTIC, DL_FLAG_COL_STOCHASTIC, DL_FLAG_SYMMETRIC = 1, 2, 4
 DL_MAX_NODES, DL_MAX_NNZ, DL_MAX_NNZ_PALETTE, DL_MAX_WEIGHT_VALUES = 256, 512, 1536, 64
 
 DL_GRAD_F32, DL_GRAD_BF16, DL_GRAD_F16 = 0, 1, 2
+DL_STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decentlam_step", "decentlam_step_xprev",
            "dmsgd_step", "dsgd_step", "awc_dmsgd_step", "da_dmsgd_step", "decentlam_step_blocked",
            "dmsgd_step_blocked", "decentlam_step_ex", "dmsgd_step_ex", "decentlam_step_xprev_ex", "decentlam_step_multi_ex", "dmsgd_step_multi_ex", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
            "dmsgd_step_multi", "decentlam_step_multi_workspace", "local_grad_lsq", "local_grad_lsq_rows",
+           "local_grad_lsq_static",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
 
@@ -111,6 +113,9 @@ def _load() -> ctypes.CDLL:
     lib.local_grad_lsq.restype = ctypes.c_int
     lib.local_grad_lsq.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.local_grad_lsq_static.restype = ctypes.c_int
+    lib.local_grad_lsq_static.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
+                                          ctypes.c_int64, ctypes.c_int64, ctypes.c_float, vp]
     lib.local_grad_lsq_rows.restype = ctypes.c_int
     lib.local_grad_lsq_rows.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                         ctypes.c_int64, ctypes.c_int64, vp, ctypes.c_int32, ctypes.c_float, vp,
@@ -561,6 +566,30 @@ def local_grad_lsq(A, y, x, g, loss=None, scale: float = 1.0, workspace=None, st
         raise TypeError("rows: need a contiguous n x bs int32 device tensor")
     _check(_lib.local_grad_lsq_rows(A.data_ptr(), y.data_ptr(), px, pg, pl, n, b, d, ldA, ld, rows.data_ptr(),
                                     rows.shape[1], scale, workspace.data_ptr(), ws_bytes, st))
+
+
+def local_grad_lsq_static(A, y, x, g, loss=None, scale: float = 1.0, stream=None):
+    """local_grad_lsq without a workspace argument: the partial sums go to the library's own device array
+    (DL_STATIC_SCRATCH_BYTES); no allocation anywhere.  Calls that overlap on one GPU race on that array."""
+    if A.dtype != torch.float32 or A.dim() != 3 or not A.is_cuda or A.stride(2) != 1:
+        raise TypeError("A: need a 3-D float32 device tensor with contiguous last axis")
+    n, b, d = A.shape
+    if b > 1 and n > 1 and A.stride(0) != b * A.stride(1):
+        raise TypeError("A: node stride must be b * row stride")
+    ldA = A.stride(1) if b > 1 else max(A.stride(1), d)
+    if y.dtype != torch.float32 or tuple(y.shape) != (n, b) or not y.is_contiguous() or not y.is_cuda:
+        raise TypeError("y: need a contiguous n x b float32 device tensor")
+    px, nx, dx, ld = _matrix_args(x, "x")
+    pg, ng, dg, ldg = _matrix_args(g, "g")
+    if (nx, dx) != (n, d) or (ng, dg, ldg) != (n, d, ld):
+        raise TypeError("x and g must be n x d with the same row stride")
+    pl = 0
+    if loss is not None:
+        if loss.dtype != torch.float32 or tuple(loss.shape) != (n,) or not loss.is_contiguous() or not loss.is_cuda:
+            raise TypeError("loss: need a contiguous float32 device tensor of n elements")
+        pl = loss.data_ptr()
+    _check(_lib.local_grad_lsq_static(A.data_ptr(), y.data_ptr(), px, pg, pl, n, b, d, ldA, ld, scale,
+                                      _stream() if stream is None else stream))
 
 
 def decentlam_stats_workspace(n: int, d: int) -> int:

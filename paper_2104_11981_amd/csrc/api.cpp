@@ -583,11 +583,12 @@ size_t local_grad_lsq_workspace(int32_t n, int32_t b, int64_t d) {
     return dl::lsq_workspace_bytes(n, b, d);
 }
 
+}  // extern "C"
+
 namespace dl {
-namespace {
 int lsq_entry(const char* fn, const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
               int32_t b, int64_t d, int64_t ldA, int64_t ld, const int32_t* rows, int32_t bs, bool sampled,
-              float scale, void* workspace, size_t workspace_bytes, void* stream) {
+              float scale, void* workspace, size_t workspace_bytes, void* stream, bool exact_need) {
     clear_error();
     if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
     if (b < 1) return set_error(DL_EINVAL, "%s: b = %d, need b >= 1", fn, b);
@@ -606,7 +607,9 @@ int lsq_entry(const char* fn, const float* A, const float* y, const float* x, fl
     if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(y) | reinterpret_cast<uintptr_t>(x) |
          reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(loss) | reinterpret_cast<uintptr_t>(rows)) & 3u)
         return set_error(DL_EINVAL, "%s: arrays must be 4-byte aligned", fn);
-    const size_t need = lsq_workspace_bytes(n, bs, d);
+    // the documented size covers every path; the library's own array is checked against the path taken
+    const size_t need = exact_need ? lsq_workspace_bytes_path(n, bs, d, lsq_path(bs, d, lsq_wide_accesses(A, x, d, ldA, ld)))
+                                   : lsq_workspace_bytes(n, bs, d);
     if (!workspace || workspace_bytes < need)
         return set_error(DL_ECAP, "%s: workspace of %zu bytes needed, %zu given", fn, need,
                          workspace ? workspace_bytes : size_t{0});
@@ -638,8 +641,9 @@ int lsq_entry(const char* fn, const float* A, const float* y, const float* x, fl
     return launch_lsq(A, y, x, g, loss, n, b, d, ldA, ld, sampled ? rows : nullptr, bs, scale, workspace,
                       static_cast<hipStream_t>(stream));
 }
-}  // namespace
 }  // namespace dl
+
+extern "C" {
 
 int local_grad_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
                    int32_t b, int64_t d, int64_t ldA, int64_t ld, float scale, void* workspace,

@@ -115,10 +115,20 @@ int launch_norms_finish(const NormPlan& plan, const float* x, const float* m, Gr
 
 // Least-squares gradient (already validated).
 size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d);
+// What the kernels that launch_lsq picks for this shape and alignment actually use (<= lsq_workspace_bytes).
+bool lsq_wide_accesses(const float* A, const float* x, int64_t d, int64_t ldA, int64_t ld);
+int lsq_path(int32_t bs, int64_t d, bool wide_accesses);
+size_t lsq_workspace_bytes_path(int32_t n, int32_t b, int64_t d, int path);
 // rows == nullptr: full-batch gradient over all b rows; otherwise bs sampled rows per node.
 int launch_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
                int32_t b, int64_t d, int64_t ldA, int64_t ld, const int32_t* rows, int32_t bs, float scale,
                void* workspace, hipStream_t stream);
+
+// The boundary of local_grad_lsq / local_grad_lsq_rows: validates every argument (status codes as the
+// header documents them), then calls launch_lsq.  `fn` names the entry point in error messages.
+int lsq_entry(const char* fn, const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
+              int32_t b, int64_t d, int64_t ldA, int64_t ld, const int32_t* rows, int32_t bs, bool sampled,
+              float scale, void* workspace, size_t workspace_bytes, void* stream, bool exact_need = false);
 
 // Diagnostics (already validated).
 size_t stats_workspace_bytes(int64_t d);

@@ -23,6 +23,8 @@
 //                partial[i][s][c] = sum_{r in split s} A_i[r,c] * res[i][r]
 //   k_finish     g[i][c] = scale * sum_s partial[i][s][c] in fixed order (deterministic),
 //                loss[i] = (scale/2) * sum_r res[i][r]^2
+#include <atomic>
+
 #include "internal.hpp"
 
 namespace dl {
@@ -408,17 +410,34 @@ constexpr int kMaxFusedD = 16384;   // 512 threads x 8 chunks of 4 columns (1024
 
 }  // namespace
 
-size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d) {  // b = rows actually used per node
+bool lsq_wide_accesses(const float* A, const float* x, int64_t d, int64_t ldA, int64_t ld) {
+    return d % 4 == 0 && ldA % 4 == 0 && ld % 4 == 0 &&
+           ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(x)) & 15u) == 0;
+}
+
+// b = rows actually used per node.  path: 0 the two-sweep kernels, 1 the single sweep, 2 the small-problem kernel
+// (launch_lsq picks by shape and alignment), -1 the largest of the three.
+size_t lsq_workspace_bytes_path(int32_t n, int32_t b, int64_t d, int path) {
     // two-sweep layout: res[n*b], partial[n*splits*d]; single-sweep layout: sq[n*splits], partial[n*splits*d]
     const size_t res = static_cast<size_t>(n) * static_cast<size_t>(b);
     const size_t partial = static_cast<size_t>(n) * static_cast<size_t>(row_splits(n, b, d)) * static_cast<size_t>(d);
-    size_t need = (res + partial) * sizeof(double) + 16;
+    const size_t two_sweeps = (res + partial) * sizeof(double) + 16;
+    size_t fused = 0;
     if (d > 0 && d <= kMaxFusedD) {
         const size_t fs = static_cast<size_t>(fused_splits(n, b, fused_rows(fused_cpt(d))));
-        const size_t fused = (static_cast<size_t>(n) * fs * (static_cast<size_t>(d) + 1)) * sizeof(double) + 16;
-        if (fused > need) need = fused;
+        fused = (static_cast<size_t>(n) * fs * (static_cast<size_t>(d) + 1)) * sizeof(double) + 16;
     }
-    return need;
+    if (path == 0) return two_sweeps;
+    if (path == 1) return fused;
+    if (path == 2) return 0;
+    return fused > two_sweeps ? fused : two_sweeps;
+}
+
+size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d) { return lsq_workspace_bytes_path(n, b, d, -1); }
+
+int lsq_path(int32_t bs, int64_t d, bool wide_accesses) {
+    if (small_problem(bs, d)) return 2;
+    return wide_accesses && d > 0 && d <= kMaxFusedD ? 1 : 0;
 }
 
 int launch_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
@@ -428,12 +447,12 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
     double* res = static_cast<double*>(workspace);
     double* partial = res + ((static_cast<size_t>(n) * bs + 1) & ~size_t{1});  // keep 16-byte alignment
     const int splits = row_splits(n, bs, d);
-    const bool vec4 = d % 4 == 0 && ldA % 4 == 0 && ld % 4 == 0 &&
-                      ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(x)) & 15u) == 0;
+    const bool vec4 = lsq_wide_accesses(A, x, d, ldA, ld);
+    const int path = lsq_path(bs, d, vec4);
     if (n > 65535 || splits > 65535) return set_error(DL_EINVAL, "local_grad_lsq: n too large for the launch grid");
 
     const dim3 block(kThreads);
-    if (small_problem(bs, d)) {
+    if (path == 2) {
         const size_t lds = small_lds_bytes(bs, d);
         if (lds > 48 * 1024) {
             if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(k_small),
@@ -445,7 +464,7 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
                            static_cast<int>(d), ldA, ld, rows, bs, static_cast<double>(scale));
         return check_hip(hipGetLastError(), "small gradient kernel launch");
     }
-    if (vec4 && d > 0 && d <= kMaxFusedD) {
+    if (path == 1) {
         const int cpt = fused_cpt(d);
         const int fs = fused_splits(n, bs, fused_rows(cpt));
         double* sq_partial = static_cast<double*>(workspace);
@@ -500,3 +519,54 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
 }
 
 }  // namespace dl
+
+// ---------------------------------------------------------------- local_grad_lsq_static
+// The same gradient for callers that cannot hand over (or allocate) a workspace: the partial sums go
+// to an array that is part of the library's device image.  Every GPU that loads the library holds its
+// own copy at its own address until the process ends; in host code the array's name is only a handle,
+// so the address is asked for once per device and that pointer is what the kernels get.
+namespace dl {
+namespace {
+
+static __device__ __align__(256) unsigned char scratch[DL_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];   // per device ordinal; zero-initialised
+
+// Address of the current device's copy of `scratch` (resolved on the first call on that device).
+int static_scratch(void** out) {
+    int device = 0;
+    if (int rc = check_hip(hipGetDevice(&device), "hipGetDevice")) return rc;
+    if (device < 0 || device >= kMaxDevices)
+        return set_error(DL_EINVAL, "local_grad_lsq_static: device ordinal %d, at most %d devices are supported", device,
+                         kMaxDevices);
+    void* p = g_scratch_ptr[device].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        if (int rc = check_hip(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)")) return rc;
+        if (p == nullptr) return set_error(DL_EHIP, "local_grad_lsq_static: the scratch array has no device address");
+        g_scratch_ptr[device].store(p, std::memory_order_release);   // two threads racing store the same value
+    }
+    *out = p;
+    return DL_OK;
+}
+
+}  // namespace
+}  // namespace dl
+
+extern "C" int local_grad_lsq_static(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
+                                     int32_t b, int64_t d, int64_t ldA, int64_t ld, float scale, void* stream) {
+    using namespace dl;
+    clear_error();
+    // sizes first: a problem beyond the array is refused before anything touches the device
+    if (n >= 1 && b >= 1 && d >= 0) {
+        const size_t need = lsq_workspace_bytes_path(n, b, d, lsq_path(b, d, lsq_wide_accesses(A, x, d, ldA, ld)));
+        if (need > static_cast<size_t>(DL_STATIC_SCRATCH_BYTES))
+            return set_error(DL_ECAP, "local_grad_lsq_static: n = %d, b = %d, d = %lld needs %zu bytes of scratch, the "
+                             "library's array holds DL_STATIC_SCRATCH_BYTES = %zu; use local_grad_lsq with a workspace",
+                             n, b, static_cast<long long>(d), need, static_cast<size_t>(DL_STATIC_SCRATCH_BYTES));
+    }
+    void* ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    return lsq_entry("local_grad_lsq_static", A, y, x, g, loss, n, b, d, ldA, ld, nullptr, b, false, scale, ws,
+                     static_cast<size_t>(DL_STATIC_SCRATCH_BYTES), stream, /*exact_need=*/true);
+}

@@ -185,6 +185,16 @@ def test_lsq_argument_validation():
     assert call(loss=0x40000) == P.DL_EALIAS         # loss inside g
 
 
+def test_lsq_static_refuses_sizes_beyond_its_array():
+    """local_grad_lsq_static checks the size first: nothing touches a device, so fake pointers will do."""
+    fake = ctypes.c_void_p(0x10000)   # 16-byte aligned: the single-sweep kernels would be chosen
+    n, b, d = 64, 4096, 16384         # 64 x 8 row blocks x 16385 doubles = 67 MB of partial sums
+    rc = P.raw.local_grad_lsq_static(fake, fake, fake, fake, None, n, b, d, d, d, 1.0, None)
+    assert rc == P.DL_ECAP and "DL_STATIC_SCRATCH_BYTES" in P.last_error()
+    header = open(os.path.join(ROOT, "include", "decentlam.h")).read()
+    assert re.search(r"#define DL_STATIC_SCRATCH_BYTES \(32u << 20\)", header) and P.DL_STATIC_SCRATCH_BYTES == 32 << 20
+
+
 def test_stats_argument_validation():
     f = P.raw.decentlam_stats
     ws = P.decentlam_stats_workspace(4, 100)
