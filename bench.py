@@ -30,11 +30,21 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 BYTES_PER_ELEMENT = 20         # read x, m, g + write x, m, fp32
 
 # HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by what
-# the same counter reads for a plain device copy of known size; profiles/*_hbm_traffic_pmc.txt),
-# keyed by (workload, algo); None where not measured.
-MEASURED_TRAFFIC_BYTES = {("c3_exp32", "decentlam"): 16_383_750_981,
-                          ("c3_exp32", "decentlam_blocked"): 16_383_742_345,
-                          ("c5_onepeer64_lsq", "local_grad_lsq"): 4_342_500_000}
+# the same counter reads for a plain device copy of known size), keyed by (workload, what); each entry
+# names the summary under profiles/ it was read from, so that a figure can be traced (and seen to be
+# stale when the kernel has changed since).  None where not measured.
+MEASURED_TRAFFIC = {
+    ("c3_exp32", "decentlam"): (16_383_750_981, "profiles/k_step_c3_exp32_hbm_traffic_pmc.txt"),
+    ("c3_exp32", "decentlam_ld_equals_d"): (16_383_890_000,
+                                            "profiles/k_step_chain_c3_exp32_ld_equals_d_kernel_stats_and_hbm_traffic.txt"),
+    ("c3_exp32", "decentlam_blocked"): (16_383_742_345, "profiles/k_step_c3_exp32_layouts_tlb_and_traffic_pmc.txt"),
+    ("c5_onepeer64_lsq", "local_grad_lsq"): (4_342_500_000, "profiles/local_grad_lsq_c5_hbm_traffic_pmc.txt"),
+}
+
+
+def measured_traffic(workload, what):
+    nbytes, source = MEASURED_TRAFFIC.get((workload, what), (None, None))
+    return {"traffic": nbytes, "traffic_profile": source}
 
 
 def ensure_built():
@@ -44,15 +54,14 @@ def ensure_built():
         hip_build.build()
 
 
-def cpu_baseline(w, kind, algo, target_seconds=12.0):
-    """Time the oracle as it stands on a column sample of the same workload."""
+def time_oracle_steps(w, kind, algo, d_s, target_seconds):
+    """Seconds per oracle step on an n x d_s sample of the workload, with the thread count of this process."""
     import numpy as np
 
     import oracle
 
     oracle.build()
     topo = oracle.topology(kind, w.n)
-    d_s = 1_280_000 if w.d >= 1_280_000 else w.d
     rng = np.random.default_rng(0)
     x = rng.standard_normal((w.n, d_s))
     m = np.zeros_like(x)
@@ -68,16 +77,45 @@ def cpu_baseline(w, kind, algo, target_seconds=12.0):
         el = time.perf_counter() - t0
         if el >= target_seconds or steps >= 200:
             break
-    per_step = el / steps
+    return el / steps, steps, oracle.num_threads()
+
+
+def cpu_baseline(w, kind, algo, target_seconds=12.0):
+    """Time the oracle as it stands on a column sample of the same workload: with all the host cores this
+    process may use, and (in a child process, since an OpenMP runtime fixes its thread count at start) with one."""
+    import subprocess
+
+    d_s = 1_280_000 if w.d >= 1_280_000 else w.d
+    per_step, steps, threads = time_oracle_steps(w, kind, algo, d_s, target_seconds)
     gbs = BYTES_PER_ELEMENT * w.n * d_s / per_step / 1e9
-    return {
-        "value": round(gbs, 3), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+    out = {
+        "value": round(gbs, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
         "sample": f"{algo} oracle (fp64 C loops, OpenMP), n={w.n}, same topology, d={d_s} columns "
                   f"({d_s / w.d:.3f} of the workload; cost is linear in d), {steps} steps, "
                   f"{per_step * 1e3:.1f} ms/step; full-size equivalent "
                   f"{1.0 / (per_step * w.d / d_s):.4f} steps/s",
         "steps_per_s_full_size_equiv": 1.0 / (per_step * w.d / d_s),
     }
+    d_1 = min(d_s, 256_000)                                # one thread: a fifth of the sample, about 5 s
+    env = dict(os.environ, OMP_NUM_THREADS="1")
+    child = subprocess.run([sys.executable, os.path.abspath(__file__), "--oracle-one-thread", w.name, algo, str(d_1)],
+                           env=env, capture_output=True, text=True)
+    if child.returncode == 0 and child.stdout.strip():
+        one = json.loads(child.stdout.strip().splitlines()[-1])
+        out["one_thread"] = {
+            "value": round(BYTES_PER_ELEMENT * w.n * d_1 / one["s_per_step"] / 1e9, 3), "unit": "GB/s", "cores": 1,
+            "sample": f"the same oracle with OMP_NUM_THREADS=1 on d={d_1} columns, {one['steps']} steps, "
+                      f"{one['s_per_step'] * 1e3:.1f} ms/step",
+            "steps_per_s_full_size_equiv": 1.0 / (one["s_per_step"] * w.d / d_1)}
+    return out
+
+
+def oracle_one_thread_child(name, algo, d_s):
+    import workloads
+
+    w = workloads.get(name)
+    per_step, steps, threads = time_oracle_steps(w, w.topo, algo, int(d_s), 5.0)
+    print(json.dumps({"s_per_step": per_step, "steps": steps, "threads": threads}), flush=True)
 
 
 def oracle_table_child():
@@ -290,6 +328,32 @@ def bench_copy(P, workloads, name, steps, warmup):
     torch.cuda.empty_cache()
     return {"ms": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
             "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
+def bench_stream(P, workloads, name, steps, warmup, ld=None):
+    """The achievable-bandwidth denominator: bare streams with the step kernel's access pattern
+    (dl_calibration_stream: same tiles, same 16-byte non-temporal accesses, no arithmetic of the method) on
+    arrays of the workload's shape, in the column order of the step's large launches."""
+    import torch
+
+    w = workloads.get(name)
+    d = workloads.generate.dim(w)
+    if ld is None:
+        ld = padded_ld(d)
+    bufs = [torch.zeros((w.n, ld), dtype=torch.float32, device="cuda") for _ in range(3)]
+    bufs[0].normal_()
+    bufs[2].normal_()
+    x, m, g = (b[:, :d] for b in bufs)
+    out = {"ld": ld}
+    for key, kind, nbytes in (("stream_3r2w", 0, 20), ("stream_read", 1, 12), ("stream_write", 2, 8)):
+        cols = P.dl_calibration_stream(kind, True, x, m, g)
+        _, ms = time_launches(lambda k: P.dl_calibration_stream(kind, True, x, m, g), steps, warmup)
+        out[key + "_ms"] = round(ms, 4)
+        out[key + "_GBps"] = round(nbytes * w.n * cols / (ms * 1e-3) / 1e9, 1)
+    out["columns_covered"] = cols
+    del x, m, g, bufs
+    torch.cuda.empty_cache()
+    return out
 
 
 def bench_stats(P, workloads, name, steps, warmup):
@@ -523,6 +587,9 @@ def main():
                     help="rowmajor: decentlam_step / dmsgd_step on n x d arrays with row stride ld (the default); "
                          "blocked: the *_step_blocked calls on the same problem stored in blocks of "
                          "--block-columns columns")
+    ap.add_argument("--ld", default="padded", choices=["padded", "d"],
+                    help="row stride of the row-major line: 'padded' = rows on 64 KiB boundaries (what the header "
+                         "recommends; +0.03 %% of memory on the headline workload), 'd' = no padding at all")
     ap.add_argument("--block-columns", type=int, default=8192)
     ap.add_argument("--all-to-all", action="store_true",
                     help="row-major line only: replace the workload's graph by all-to-all averaging with equal "
@@ -534,10 +601,17 @@ def main():
                     help="after the timed region, run one plain device copy of one n x d array "
                          "(known size: reads and writes 4*n*d bytes) so that a rocprofv3 --pmc run "
                          "of this command can scale FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--streams-only", action="store_true",
+                    help="only the bare calibration streams (dl_calibration_stream) on the workload's shape, with "
+                         "rows padded to 64 KiB boundaries and with ld = d: one JSON line (used for the profiles)")
     ap.add_argument("--oracle-table", action="store_true",
                     help="CPU only: time the oracle on every workload at 1 thread and at all host cores")
     ap.add_argument("--oracle-table-child", action="store_true", help=argparse.SUPPRESS)
+    ap.add_argument("--oracle-one-thread", nargs=3, metavar=("WORKLOAD", "ALGO", "COLUMNS"), help=argparse.SUPPRESS)
     args = ap.parse_args()
+    if args.oracle_one_thread:
+        oracle_one_thread_child(*args.oracle_one_thread)
+        return
     if args.oracle_table_child:
         oracle_table_child()
         return
@@ -560,6 +634,13 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     torch.cuda.set_device(0)
 
+    if args.streams_only:
+        d0 = workloads.generate.dim(workloads.get(args.workload))
+        print(json.dumps({"workload": args.workload, "steps": args.steps, "warmup": args.warmup,
+                          "rows_on_64KiB": bench_stream(P, workloads, args.workload, args.steps, args.warmup),
+                          "ld_equals_d": bench_stream(P, workloads, args.workload, args.steps, args.warmup, ld=d0)}),
+              flush=True)
+        return
     if args.workload == "c5_onepeer64_lsq":
         # side workload: one iteration = local_grad_lsq + decentlam_step; the gradient kernel dominates
         r = bench_lsq(P, workloads, args.workload, args.steps, args.warmup, args.calibration_copy)
@@ -572,7 +653,7 @@ def main():
             "config": {"workload": args.workload, "n": r["n"], "b": r["b"], "d": r["d"]},
             "roofline": {"bound": "hbm", "achieved": r["grad_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": r["grad_frac_of_hbm_peak"],
-                         "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "local_grad_lsq")),
+                         **measured_traffic(args.workload, "local_grad_lsq"),
                          "kernel": "k_fused", "kernel_ms": r["grad_kernel_ms"],
                          "algorithmic_bytes_per_launch": r["grad_algorithmic_bytes"]},
         }), flush=True)
@@ -593,13 +674,14 @@ def main():
                        "block_columns": args.block_columns, "bytes_per_node_element": BYTES_PER_ELEMENT},
             "roofline": {"bound": "hbm", "achieved": r["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": r["frac_of_hbm_peak"],
-                         "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.algo + "_blocked")),
+                         **measured_traffic(args.workload, args.algo + "_blocked"),
                          "kernel": "k_step", "kernel_ms": r["kernel_ms"], "algorithmic_bytes_per_launch": nbytes},
         }), flush=True)
         return
     detail = None if args.no_extras else {}
     w, d, ld, topo, wall_ms, kern_ms = bench_step(
         P, workloads, args.workload, args.algo, args.steps, args.warmup, args.calibration_copy, detail,
+        ld=workloads.generate.dim(workloads.get(args.workload)) if args.ld == "d" else None,
         topo=all_to_all(P, workloads.get(args.workload).n) if args.all_to_all else None)
     kind = w.topo
     bytes_per_step = BYTES_PER_ELEMENT * w.n * d
@@ -616,13 +698,17 @@ def main():
         "ms_per_step": round(wall_ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": w.name, "algo": args.algo, "n": w.n, "d": d, "ld": ld,
+                   "layout": "row-major, ld = d (no padding)" if ld == d else
+                             "row-major, rows padded to 64 KiB boundaries (ld = %d, +%.2f %% of memory)" % (ld, 100.0 * (ld - d) / d),
                    "topology": "all_to_all" if args.all_to_all else {0: "ring", 1: "exp_static", 2: "exp_onepeer"}[kind],
                    "deg": int(topo.row_ptr[1] - topo.row_ptr[0]), "gamma": w.gamma, "beta": w.beta,
                    "storage": "fp32", "bytes_per_node_element": BYTES_PER_ELEMENT},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": None if args.all_to_all else MEASURED_TRAFFIC_BYTES.get((args.workload, args.algo)),
-                     "kernel": "k_step", "kernel_ms": round(kern_ms, 4),
+                     **(measured_traffic(args.workload, args.algo + ("_ld_equals_d" if args.ld == "d" else ""))
+                        if not args.all_to_all else {"traffic": None, "traffic_profile": None}),
+                     "kernel": "k_step_chain" if (args.ld == "d" and args.workload == "c3_exp32" and not args.all_to_all)
+                     else "k_step", "kernel_ms": round(kern_ms, 4),
                      "algorithmic_bytes_per_launch": bytes_per_step},
     }
     if args.all_to_all:
@@ -635,7 +721,8 @@ def main():
                 continue
             w2, d2, _, _, _, k2 = bench_step(P, workloads, name, algo, args.steps, args.warmup)
             b2 = BYTES_PER_ELEMENT * w2.n * d2
-            extras[f"{algo}_step_{name}"] = {"kernel_ms": round(k2, 4), "GBps": round(b2 / (k2 * 1e-3) / 1e9, 1),
+            extras[f"{algo}_step_{name}"] = {"kernel_ms": round(k2, 4), "steps_per_s": round(1e3 / k2, 1),
+                                             "GBps": round(b2 / (k2 * 1e-3) / 1e9, 1),
                                              "frac_of_hbm_peak": round(b2 / (k2 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         w3 = workloads.get("c3_exp32")
         d3 = workloads.generate.dim(w3)
@@ -644,8 +731,17 @@ def main():
         # 64 KiB unit, so only every other row can write whole address pairs)
         _, _, _, _, _, k4 = bench_step(P, workloads, "c3_exp32", "decentlam", args.steps, args.warmup, ld=d3)
         extras["decentlam_step_c3_exp32_ld_equals_d"] = {
-            "kernel_ms": round(k4, 4), "GBps": round(b3 / (k4 * 1e-3) / 1e9, 1),
+            "kernel_ms": round(k4, 4), "steps_per_s": round(1e3 / k4, 1), "GBps": round(b3 / (k4 * 1e-3) / 1e9, 1),
             "frac_of_hbm_peak": round(b3 / (k4 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        if (args.workload, args.algo, args.ld, args.all_to_all) == ("c3_exp32", "decentlam", "padded", False):
+            # the same workload with the row stride the workload states (a contiguous 32 x 25.6 M array): the
+            # headline beside it is measured on rows padded to 64 KiB boundaries, which the header recommends
+            out["roofline_ld_equals_d"] = {
+                "bound": "hbm", "achieved": round(b3 / (k4 * 1e-3) / 1e9, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(b3 / (k4 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                **measured_traffic("c3_exp32", "decentlam_ld_equals_d"), "kernel": "k_step_chain",
+                "kernel_ms": round(k4, 4), "steps_per_s": round(1e3 / k4, 1), "ld": d3,
+                "algorithmic_bytes_per_launch": b3}
         # c3's arrays under all-to-all averaging (1024 entries): the mixing runs as an fp64 product on
         # the matrix cores, 2 n^2 d flops per step beside the same 20 B per node-element
         _, _, _, _, _, k5 = bench_step(P, workloads, "c3_exp32", "decentlam", args.steps, args.warmup,
@@ -662,7 +758,7 @@ def main():
             # same arithmetic, same bytes
             out["roofline_blocked_layout"] = {
                 "bound": "hbm", "achieved": blk["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": blk["frac_of_hbm_peak"], "traffic": MEASURED_TRAFFIC_BYTES.get(("c3_exp32", "decentlam_blocked")),
+                "frac": blk["frac_of_hbm_peak"], **measured_traffic("c3_exp32", "decentlam_blocked"),
                 "kernel": "k_step", "kernel_ms": blk["kernel_ms"], "steps_per_s": blk["steps_per_s"],
                 "algorithmic_bytes_per_launch": bytes_per_step, "entry_point": "decentlam_step_blocked",
                 "block_columns": blk["block_columns"]}
@@ -677,8 +773,28 @@ def main():
         extras["decentlam_step_8_nodes_sym_exp_25.6M"] = bench_shape(P, 8, 25_600_000, P.DL_TOPO_EXP_SYM,
                                                                     args.steps, args.warmup)
         extras["plain_device_copy_c3_array"] = bench_copy(P, workloads, "c3_exp32", args.steps, args.warmup)
+        # what the memory gives bare streams with the step's access pattern on c3-shaped arrays (both row strides)
+        st = bench_stream(P, workloads, "c3_exp32", args.steps, args.warmup)
+        extras["calibration_streams_c3_shape"] = st
+        extras["calibration_streams_c3_shape_ld_equals_d"] = bench_stream(P, workloads, "c3_exp32", args.steps,
+                                                                           args.warmup, ld=d3)
+        if (args.workload, args.ld, args.all_to_all) == ("c3_exp32", "padded", False):
+            out["stream_3r2w_GBps"] = st["stream_3r2w_GBps"]
+            out["stream_read_GBps"] = st["stream_read_GBps"]
+            out["stream_write_GBps"] = st["stream_write_GBps"]
+            out["roofline"]["frac_of_measured_stream"] = round(achieved / st["stream_3r2w_GBps"], 4)
         extras["decentlam_stats_c3_exp32"] = bench_stats(P, workloads, "c3_exp32", args.steps, args.warmup)
-        extras["local_grad_lsq_c5"] = bench_lsq(P, workloads, "c5_onepeer64_lsq", args.steps, args.warmup)
+        c5 = bench_lsq(P, workloads, "c5_onepeer64_lsq", args.steps, args.warmup)
+        extras["local_grad_lsq_c5"] = c5
+        # the two other large workloads under their own names: iterations per second and fraction of the HBM peak
+        c4 = extras.get("decentlam_step_c4_ring16_ragged")
+        if c4:
+            out["c4_ring16_ragged"] = {"steps_per_s": c4["steps_per_s"], "GBps": c4["GBps"], "frac": c4["frac_of_hbm_peak"],
+                                       "what": "decentlam_step, one flat call over the 160 packed tensors, 20 B per node-element"}
+        out["c5_onepeer64_lsq"] = {
+            "steps_per_s": round(1e3 / c5["ms_per_iteration_grad_plus_step"], 1),
+            "grad_GBps": c5["grad_GBps"], "frac": c5["grad_frac_of_hbm_peak"],
+            "what": "local_grad_lsq + decentlam_step per iteration; frac prices the gradient call against 4 n b d bytes"}
         # the small least-squares workloads are cache-resident and latency-bound: microseconds only
         for small in ("c2_onepeer8_b32", "c2_onepeer8_b1024"):
             r2 = bench_lsq(P, workloads, small, 200, 20)

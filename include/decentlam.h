@@ -141,7 +141,10 @@ int topology_metropolis(int32_t n, const int32_t* row_ptr, const int32_t* col_id
  * 128-byte boundaries (16-byte aligned bases, ld a multiple of 32), and for arrays of a
  * million columns or more on 64 KiB boundaries (64 KiB-aligned bases, ld a multiple of
  * 16384): the step then writes whole 64 KiB-aligned address pairs (A, A + 32 KiB), worth
- * about 10 % at every node count (measured at n = 32, d = 25.6 M: 2.51 instead of 2.80 ms).
+ * about 10 % at every node count (measured at n = 32, d = 25.6 M: 2.51 instead of 2.80 ms).  Rows that
+ * alternate between such boundaries and their midpoints (ld an odd multiple of 8192, e.g. a contiguous
+ * 32 x 25.6 M array; 17 to 32 nodes, x, m, g placed alike modulo 64 KiB) are served by a kernel of their
+ * own that loads and stores half of each odd row's accesses one 64 KiB unit ahead / late: 2.64 ms there.
  * Dense graphs (23 <= n <= 32 with 46 - n or more entries per row on average: 14 at n = 32, all
  * 23 at n = 23; 33 <= n <= 48 with 38 - n / 4 or more; this holds for every step entry point): the partial averaging runs as an fp64 matrix product on the matrix cores
  * instead of neighbour by neighbour (all-to-all at n = 32, d = 25.6 M: 2.7 instead of 3.5 ms).
@@ -430,6 +433,23 @@ size_t decentlam_stats_workspace(int32_t n, int64_t d);
 int decentlam_stats(const float* x, const float* m, const float* ref,
                     int32_t n, int64_t d, int64_t ld,
                     double* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * dl_calibration_stream -- no part of the method: a bare stream with the step kernel's access pattern,
+ * which benchmarks use as the achievable-bandwidth denominator beside the published HBM peak.  One
+ * workgroup per 256 columns of all n rows, the loads of x, g, m up front, one barrier, the stores of m and
+ * x; no on-chip tile, no neighbour list.
+ *   kind  0: x <- x + g / 2, m <- m / 2 + g (3 reads + 2 writes, 20 bytes per node-element);
+ *         1: the three reads only (12 bytes); 2: the two writes only (8 bytes; x and m are overwritten).
+ *   split 0: tile t owns columns [256 t, 256 t + 256); 1: the column order of the step's large launches
+ *         (two 512-byte segments 32 KiB apart inside 64 KiB units of 16384 columns).
+ *   x, m, g  device, n x d fp32 with row stride ld, n <= 32, 16-byte aligned, ld a multiple of 4.
+ *   columns_out [out, host] columns actually covered: whole tiles only (d rounded down to a multiple of 256,
+ *         or of 16384 in the split order); the rest is left untouched.
+ * Errors: DL_EINVAL, DL_EHIP.
+ */
+int dl_calibration_stream(int kind, int split, float* x, float* m, const float* g,
+                          int32_t n, int64_t d, int64_t ld, int64_t* columns_out, void* stream);
 
 /* Description of the last failure on the calling thread ("" if none). Never NULL. */
 const char* dl_last_error(void);

@@ -35,7 +35,7 @@ EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decent
            "dmsgd_step", "dsgd_step", "awc_dmsgd_step", "da_dmsgd_step", "decentlam_step_blocked",
            "dmsgd_step_blocked", "decentlam_step_ex", "dmsgd_step_ex", "decentlam_step_xprev_ex", "decentlam_step_multi_ex", "dmsgd_step_multi_ex", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
            "dmsgd_step_multi", "decentlam_step_multi_workspace", "local_grad_lsq", "local_grad_lsq_rows",
-           "local_grad_lsq_static",
+           "local_grad_lsq_static", "dl_calibration_stream",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
 
@@ -125,6 +125,9 @@ def _load() -> ctypes.CDLL:
     lib.decentlam_stats.restype = ctypes.c_int
     lib.decentlam_stats.argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, vp, vp,
                                     ctypes.c_size_t, vp]
+    lib.dl_calibration_stream.restype = ctypes.c_int
+    lib.dl_calibration_stream.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp, vp, ctypes.c_int32, ctypes.c_int64,
+                                          ctypes.c_int64, ctypes.POINTER(ctypes.c_int64), vp]
     lib.dl_last_error.restype = ctypes.c_char_p
     lib.dl_last_error.argtypes = []
     return lib
@@ -590,6 +593,20 @@ def local_grad_lsq_static(A, y, x, g, loss=None, scale: float = 1.0, stream=None
         pl = loss.data_ptr()
     _check(_lib.local_grad_lsq_static(A.data_ptr(), y.data_ptr(), px, pg, pl, n, b, d, ldA, ld, scale,
                                       _stream() if stream is None else stream))
+
+
+def dl_calibration_stream(kind: int, split: bool, x, m, g, stream=None) -> int:
+    """Bare stream with the step kernel's access pattern (kind 0: 3 reads + 2 writes, 1: reads, 2: writes);
+    returns the number of columns it covered.  A benchmark aid, no part of the method."""
+    px, n, d, ld = _matrix_args(x, "x")
+    pm, nm, dm, ldm = _matrix_args(m, "m")
+    pg, ng, dg, ldg = _matrix_args(g, "g")
+    if (nm, dm, ldm) != (n, d, ld) or (ng, dg, ldg) != (n, d, ld):
+        raise TypeError("x, m and g must share shape and row stride")
+    cols = ctypes.c_int64(0)
+    _check(_lib.dl_calibration_stream(kind, 1 if split else 0, px, pm, pg, n, d, ld, ctypes.byref(cols),
+                                      _stream() if stream is None else stream))
+    return cols.value
 
 
 def decentlam_stats_workspace(n: int, d: int) -> int:

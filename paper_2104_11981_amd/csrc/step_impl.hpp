@@ -110,6 +110,13 @@ inline bool mixes_on_matrix_cores(int n, int nnz) {
 template <int ALGO>
 int launch_method(int vec, int format, bool norms, const StepCall& s);
 
+// Chained split tiles for rows that alternate between 64 KiB boundaries and their midpoints (step_chain.hip):
+// whether that kernel serves this method, node count and graph, and its launch over `units` whole 64 KiB
+// units of columns starting at s.x / s.m / s.g (row 0 of each on a 64 KiB boundary, fp32 gradients with the
+// row stride of x), `len` units per workgroup.
+bool chain_serves(int algo, int32_t n, int nnz);
+int launch_chain(int algo, const StepCall& s, uint32_t units, uint32_t len);
+
 #ifdef DL_STEP_KERNEL_IMPL
 namespace {
 

@@ -45,6 +45,12 @@ constexpr int64_t kSplitMinColumns = 1 << 20;   // below this a launch keeps pla
 // workgroup per CU: measured better than halving the lanes to keep two (64 nodes: 6.2 against 5.3 TB/s
 // row-major, 6.5 against 6.4 blocked; 128 nodes with 8-byte lanes: 6.4 against 5.5 blocked), because
 // the 16-byte lanes bring full 512-byte segments and their pairing (split tiles) with them.
+// Longest chain of the chained-tile kernel, in units (the chains get shorter towards the end of a launch).
+// Measured on 32 x 25.6 M, ld = d: 2.70 / 2.67 / 2.68 / 2.71 ms with every chain 2 / 4 / 8 / 16 units long (long
+// chains leave the chip half idle at the end of the launch), 2.63 / 2.65 / 2.65 / 2.66 ms with chains of at
+// most 8 / 16 / 32 / 64 units that shorten towards the end.
+constexpr uint32_t kChainLength = 8;
+
 int widest_vec_for(int32_t n, Algo /*algo*/) {
     if (n <= 64) return 4;
     if (n <= 128) return 2;
@@ -123,7 +129,28 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
         const uintptr_t at = reinterpret_cast<uintptr_t>(written + head) % (4u * kSplitUnit);
         const int64_t pre = at ? static_cast<int64_t>((4u * kSplitUnit - at) / 4) : 0;
         const int64_t units = (body - pre) / kSplitUnit;
-        if (int rc = run(vec, head + pre, body - pre, static_cast<uint32_t>(units * kSplitTilesPerUnit))) return rc;
+        // Rows that alternate between 64 KiB boundaries and their midpoints (ld * 4 an odd multiple of
+        // 32 KiB), all three arrays alike: the whole units go to the chained-tile kernel (step_chain.hip).
+        const auto on_unit = [&](const void* p, size_t elem) {
+            return p && (reinterpret_cast<uintptr_t>(p) + static_cast<size_t>(head + pre) * elem) % (4u * kSplitUnit) == 0;
+        };
+        const bool chained = ld % kSplitUnit == kSplitDistance && units > 0 && !norms && g.format == DL_GRAD_F32 &&
+                             g.ld == ld && on_unit(x, 4) && on_unit(m, 4) && on_unit(g.p, 4) &&
+                             chain_serves(algo, n, topo.row_ptr[n]);
+        if (chained) {
+            StepCall s;
+            s.x = x + head + pre;
+            s.m = m + head + pre;
+            s.g = static_cast<const float*>(g.p) + head + pre;
+            s.n = n; s.d = units * kSplitUnit; s.ld = ld; s.ldg = ld;
+            s.gamma = gamma; s.beta = beta; s.topo = &topo; s.stream = stream;
+            s.na = NormArgs{nullptr, 0, 0};
+            s.batches = 1; s.batch_stride = 0; s.batch_stride_g = 0; s.split_tiles = 0; s.by_xcd = false;
+            if (int rc = launch_chain(algo, s, static_cast<uint32_t>(units), kChainLength)) return rc;
+            if (int rc = run(vec, head + pre + units * kSplitUnit, body - pre - units * kSplitUnit)) return rc;
+        } else if (int rc = run(vec, head + pre, body - pre, static_cast<uint32_t>(units * kSplitTilesPerUnit))) {
+            return rc;
+        }
         if (int rc = run(vec, head, pre)) return rc;
     } else if (int rc = run(vec, head, body)) {   // aligned body first: it is the bulk
         return rc;

@@ -80,11 +80,10 @@ def test_workload3_n32_d25_6M_sampled_columns(P, oracle, algo, padded):
     """The headline configuration: n = 32, static exponential graph, d = 25.6 M, 20 iterations, with the
     row stride the benchmark uses (rows on 64 KiB boundaries) and with ld = d."""
     import workloads
-    from bench import padded_ld
 
     w = workloads.get("c3_exp32")
     d = workloads.generate.dim(w)
-    run_sampled_trajectory(P, oracle, w, algo, 1, ld=padded_ld(d) if padded else d)
+    run_sampled_trajectory(P, oracle, w, algo, 1, ld=P.recommended_ld(d) if padded else d)
 
 
 def test_workload4_ragged_flat_and_ranged_calls(P, oracle):

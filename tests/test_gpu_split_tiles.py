@@ -98,6 +98,31 @@ def test_large_row_major_launch_matches_oracle(P, oracle, algo, kind, n, d, pad,
         assert np.all(full[~inside] == SENT)
 
 
+# Rows that alternate between 64 KiB boundaries and their midpoints (ld an odd multiple of 8192 elements: a
+# contiguous 32 x 25.6 M array is one): the whole units of a launch on 17-32 nodes go to the chained-tile
+# kernel, in which the odd rows load half a wave one unit ahead and store half a wave one unit late.  A value
+# loaded ahead from the wrong place, a result stored late at the wrong place, or a chain end handled wrongly
+# fails the comparison, which covers every element.  Chains shorten towards the end of a launch: 64-67 units
+# make chains of four, two and one unit.
+CHAIN_CASES = [
+    # kind, n, d, ld - d, skew of x, m, g
+    (1, 32, (1 << 20) + 8192, 0, (0, 0, 0)),                          # ld = d: 64 units chained, 8192 columns after them
+    (1, 32, (1 << 20) + 3 * UNIT + 8192, 0, (0, 0, 0)),               # 67 units: one chain of four, then twos and ones
+    (0, 21, (1 << 20) + 3 * UNIT + 400, 8192 - 400, (260, 260, 260)), # off the boundary alike: 16124 columns first
+    (3, 31, (1 << 20) + 2 * UNIT + 12, 8192 - 12 + UNIT, (0, 0, 0)),  # odd node count: the last wave holds one row
+    (1, 17, (1 << 20) + 8192, 0, (8192, 8192, 8192)),                 # all bases half a unit off: half a unit first
+    (1, 32, (1 << 20) + 8192, 0, (0, 8192, 0)),                       # m placed differently: not served, split tiles
+    (4, 24, (1 << 20) + 8192, 0, (0, 0, 0)),                          # irregular degrees (mesh)
+]
+
+
+@pytest.mark.parametrize("algo", ["decentlam", "dmsgd", "awc_dmsgd", "xprev"])
+@pytest.mark.parametrize("kind,n,d,pad,skew", CHAIN_CASES)
+def test_rows_alternating_between_boundaries_and_midpoints(P, oracle, algo, kind, n, d, pad, skew):
+    assert (d + pad) % UNIT == UNIT // 2
+    test_large_row_major_launch_matches_oracle(P, oracle, algo, kind, n, d, pad, skew)
+
+
 @pytest.mark.parametrize("n,d,pad", [(4, (1 << 20) + 1284, 4), (8, (1 << 20) + 3 * UNIT + 8, 8), (4, (1 << 20) + 2 * UNIT, 0)])
 def test_large_launch_with_per_tensor_sums(P, oracle, n, d, pad):
     """The multi-tensor call over one large launch in either order: state and sums against the oracle."""
