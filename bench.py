@@ -536,6 +536,43 @@ def bench_graph(P, workloads, name, replays=200):
             "eager_us_per_iteration": round(eager_ms * 1e3 / topo.period, 2)}
 
 
+def bench_small(P, workloads, steps=2000, warmup=200):
+    """The launch-latency-bound workloads with W packed once (topology_pack) and the calls' arguments marshalled
+    once (prepare_step, prepare_local_grad_lsq): microseconds per iteration of workload 1 (one step) and of
+    workload 2 with b = 32 (gradient, then step), eager launches on one stream."""
+    import numpy as np
+    import torch
+
+    out = {}
+    w = workloads.get("c1_ring4")
+    packed = P.topology_pack(P.topology_build(w.topo, w.n))
+    x = workloads.device_x0(w, "cuda", ld=w.d)
+    m, g = torch.zeros_like(x), torch.zeros_like(x)
+    workloads.device_grad(w, 0, g)
+    step = P.prepare_step("decentlam", x, m, g, packed, 1e-3, float(np.float32(w.beta)))
+    _, ms = time_launches(step, steps, warmup)
+    out["c1_ring4_step_us"] = round(ms * 1e3, 2)
+    w = workloads.get("c2_onepeer8_b32")
+    A, y, _ = workloads.device_lsq_problem(w, "cuda")
+    packed = P.topology_pack(P.topology_build(w.topo, w.n))
+    gamma, beta, scale = (float(np.float32(v)) for v in (w.gamma, w.beta, w.lsq_scale))
+    x = torch.zeros((w.n, w.d), dtype=torch.float32, device="cuda")
+    m, g = torch.zeros_like(x), torch.zeros_like(x)
+    ws = torch.empty(P.local_grad_lsq_workspace(w.n, w.b, w.d), dtype=torch.uint8, device="cuda")
+    grad = P.prepare_local_grad_lsq(A, y, x, g, None, scale, ws)
+    step = P.prepare_step("dmsgd", x, m, g, packed, gamma, beta)   # DmSGD: this workload's DecentLaM run diverges
+
+    def iteration(k):
+        grad()
+        step(k)
+
+    _, ms = time_launches(iteration, steps, warmup)
+    out["c2_onepeer8_b32_grad_plus_step_us"] = round(ms * 1e3, 2)
+    _, ms = time_launches(lambda k: grad(), steps, warmup)
+    out["c2_onepeer8_b32_grad_us"] = round(ms * 1e3, 2)
+    return out
+
+
 def bench_lsq(P, workloads, name, steps, warmup, calibration_copy=False):
     """Workload 5: local_grad_lsq then decentlam_step per iteration; times the gradient alone too."""
     import numpy as np
@@ -805,6 +842,8 @@ def main():
         w1 = workloads.get("c1_ring4")
         _, _, _, _, _, k1 = bench_step(P, workloads, "c1_ring4", "decentlam", 200, 20)
         extras["decentlam_step_c1_ring4_us"] = round(k1 * 1e3, 2)
+        # the same small workloads with W packed once and the calls' arguments marshalled once
+        extras["small_workloads_prepared_calls"] = bench_small(P, workloads)
         out["extras"] = extras
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, kind, args.algo)

@@ -15,8 +15,10 @@
  *  - Every function returns DL_OK (0) or a negative dl_status; nothing aborts,
  *    prints or throws.  dl_last_error() gives a thread-local description of the
  *    last failure on the calling thread.
- *  - The caller owns every buffer.  The library allocates no device memory and
- *    keeps no state between calls.
+ *  - The caller owns every buffer.  The library allocates no device memory and keeps no state
+ *    between calls, with one exception that no result depends on: kernel variants whose on-chip
+ *    tile exceeds 48 KiB need a driver attribute raised once per device, and the library remembers
+ *    per variant and device that it has done so.
  *  - Device work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *    the default stream) and the call returns without synchronising.  Host
  *    arrays (the topology) are consumed before the call returns.
@@ -167,6 +169,33 @@ int dmsgd_step(float* x, float* m, const float* g,
                int32_t n, int64_t d, int64_t ld,
                const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
                float gamma, float beta, int64_t k, void* stream);
+
+/*
+ * topology_pack, *_step_packed -- W validated and encoded once instead of at every call.
+ *
+ * The step calls above take W as three flat host arrays (the fields a `dl_topology { n, period, row_ptr,
+ * col_idx, w }` struct would carry, passed one by one) and check and encode the phase in use on every call:
+ * O(entries) host work per iteration, which shows where a step is only microseconds long.  topology_pack
+ * does that work for all `period` phases once and writes the result into a caller-owned host buffer of
+ * topology_pack_bytes(n, period) bytes (4-byte aligned; an opaque blob that holds no pointers: it may be
+ * copied, must not be edited, and is only valid for the library build that wrote it).  The *_step_packed
+ * calls take that buffer in place of (row_ptr, col_idx, w, period); iteration k uses phase k mod period as
+ * before.  Results are bit-identical to the flat calls.  The library keeps no reference to the buffer and
+ * no other state: the buffer is consumed before the call returns.
+ * Errors: topology_pack as the W checks of decentlam_step (DL_EINVAL, DL_ETOPO), DL_ECAP if the buffer is
+ *         too small; *_step_packed as their flat forms, DL_ETOPO if the buffer was not written by
+ *         topology_pack or describes another node count.  topology_pack_bytes returns 0 for n < 1,
+ *         n > DL_MAX_NODES or period < 1.
+ */
+size_t topology_pack_bytes(int32_t n, int32_t period);
+int topology_pack(int32_t n, const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                  void* packed, size_t packed_bytes);
+int decentlam_step_packed(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
+                          const void* packed, float gamma, float beta, int64_t k, void* stream);
+int dmsgd_step_packed(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
+                      const void* packed, float gamma, float beta, int64_t k, void* stream);
+int dsgd_step_packed(float* x, const float* g, int32_t n, int64_t d, int64_t ld,
+                     const void* packed, float gamma, int64_t k, void* stream);
 
 /*
  * decentlam_step_xprev -- DecentLaM in its momentum-free form (appendix "Reformulation of
@@ -363,8 +392,13 @@ int dsgd_step(float* x, const float* g,
  *   x  [in] device, n x d fp32, row stride ld.     g [out] device, n x d fp32, row stride ld.
  *   loss [out] device, n fp32, or NULL.
  *   workspace [scratch] device, at least local_grad_lsq_workspace(n, b, d) bytes, 16-byte aligned;
- *             contents are undefined before and after the call.
+ *             contents are undefined before and after the call (no initialisation is needed).
  * Deterministic: partial sums are combined in a fixed order.
+ * The contraction is a batch of n matrix-vector products with no shared operand (every node has its own
+ * A_i and x_i): 1 flop per byte of A at best, so the bound is HBM bandwidth and the kernels are built
+ * around one streaming pass over A (rows 16-byte aligned, d <= 16384; otherwise two passes).  Products and sums run as fp64 fused multiply-adds on the vector units; the matrix cores are
+ * not used: an MFMA tile would have one useful column in sixteen, and for fp32 / fp64 the matrix and
+ * vector peaks of this chip are equal.
  * Errors: DL_EINVAL (NULL, n < 1, b < 1, d < 0, ldA < d, ld < d, scale not finite),
  *         DL_ECAP (workspace too small), DL_EALIAS (g overlaps an input), DL_EHIP.
  */

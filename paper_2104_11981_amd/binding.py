@@ -35,7 +35,8 @@ EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decent
            "dmsgd_step", "dsgd_step", "awc_dmsgd_step", "da_dmsgd_step", "decentlam_step_blocked",
            "dmsgd_step_blocked", "decentlam_step_ex", "dmsgd_step_ex", "decentlam_step_xprev_ex", "decentlam_step_multi_ex", "dmsgd_step_multi_ex", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
            "dmsgd_step_multi", "decentlam_step_multi_workspace", "local_grad_lsq", "local_grad_lsq_rows",
-           "local_grad_lsq_static", "dl_calibration_stream",
+           "local_grad_lsq_static", "dl_calibration_stream", "topology_pack_bytes", "topology_pack",
+           "decentlam_step_packed", "dmsgd_step_packed", "dsgd_step_packed",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
 
@@ -125,6 +126,17 @@ def _load() -> ctypes.CDLL:
     lib.decentlam_stats.restype = ctypes.c_int
     lib.decentlam_stats.argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, vp, vp,
                                     ctypes.c_size_t, vp]
+    lib.topology_pack_bytes.restype = ctypes.c_size_t
+    lib.topology_pack_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    lib.topology_pack.restype = ctypes.c_int
+    lib.topology_pack.argtypes = [ctypes.c_int32, i32p, i32p, f32p, ctypes.c_int32, vp, ctypes.c_size_t]
+    for name in ("decentlam_step_packed", "dmsgd_step_packed"):
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, vp, ctypes.c_float,
+                                       ctypes.c_float, ctypes.c_int64, vp]
+    lib.dsgd_step_packed.restype = ctypes.c_int
+    lib.dsgd_step_packed.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, vp, ctypes.c_float,
+                                     ctypes.c_int64, vp]
     lib.dl_calibration_stream.restype = ctypes.c_int
     lib.dl_calibration_stream.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp, vp, ctypes.c_int32, ctypes.c_int64,
                                           ctypes.c_int64, ctypes.POINTER(ctypes.c_int64), vp]
@@ -415,6 +427,133 @@ def dmsgd_step_multi_ex(x, m, g, offsets, topo: Topology, gamma: float, beta: fl
                         norms=None, workspace=None, stream=None):
     """General multi-tensor DmSGD step, see decentlam_step_multi_ex."""
     _step_multi_ex(_lib.dmsgd_step_multi_ex, x, m, g, offsets, topo, gamma, beta, k, norms, workspace, stream)
+
+
+def topology_pack_bytes(n: int, period: int) -> int:
+    return int(_lib.topology_pack_bytes(n, period))
+
+
+@dataclass
+class PackedTopology:
+    """A topology validated and encoded once by topology_pack: an opaque host buffer for the *_step_packed calls."""
+    n: int
+    period: int
+    buffer: np.ndarray   # uint8, owned here
+
+    def _ptr(self):
+        cached = self.__dict__.get("_cached_ptr")
+        if cached is None:
+            cached = self.__dict__["_cached_ptr"] = self.buffer.ctypes.data
+        return cached
+
+
+def topology_pack(topo: Topology) -> PackedTopology:
+    """topology_pack: check and encode every phase of `topo` once."""
+    nbytes = topology_pack_bytes(topo.n, topo.period)
+    if nbytes == 0:
+        raise DecentLamError(DL_ETOPO, f"topology_pack: n = {topo.n}, period = {topo.period} cannot be packed")
+    buf = np.zeros(nbytes, dtype=np.uint8)
+    _check(_lib.topology_pack(topo.n, *topo._args(), buf.ctypes.data, nbytes))
+    return PackedTopology(topo.n, topo.period, buf)
+
+
+def _step_packed(fn, x, m, g, packed: PackedTopology, gamma, beta, k, stream):
+    px, n, d, ld = _matrix_args(x, "x")
+    pm, nm, dm, ldm = _matrix_args(m, "m")
+    pg, ng, dg, ldg = _matrix_args(g, "g")
+    if (nm, dm, ldm) != (n, d, ld) or (ng, dg, ldg) != (n, d, ld):
+        raise TypeError("x, m and g must share shape and row stride")
+    _check(fn(px, pm, pg, n, d, ld, packed._ptr(), gamma, beta, k, _stream() if stream is None else stream))
+
+
+def decentlam_step_packed(x, m, g, packed: PackedTopology, gamma: float, beta: float, k: int = 0, stream=None):
+    """decentlam_step with W from topology_pack (no per-call validation of W)."""
+    _step_packed(_lib.decentlam_step_packed, x, m, g, packed, gamma, beta, k, stream)
+
+
+def dmsgd_step_packed(x, m, g, packed: PackedTopology, gamma: float, beta: float, k: int = 0, stream=None):
+    """dmsgd_step with W from topology_pack."""
+    _step_packed(_lib.dmsgd_step_packed, x, m, g, packed, gamma, beta, k, stream)
+
+
+def dsgd_step_packed(x, g, packed: PackedTopology, gamma: float, k: int = 0, stream=None):
+    """dsgd_step with W from topology_pack."""
+    px, n, d, ld = _matrix_args(x, "x")
+    pg, ng, dg, ldg = _matrix_args(g, "g")
+    if (ng, dg, ldg) != (n, d, ld):
+        raise TypeError("x and g must share shape and row stride")
+    _check(_lib.dsgd_step_packed(px, pg, n, d, ld, packed._ptr(), gamma, k, _stream() if stream is None else stream))
+
+
+class PreparedCall:
+    """A library call whose arguments were marshalled once.  `call(k)` issues it for iteration k on torch's current
+    stream (or on the stream fixed at preparation) and checks the status; everything else about the call -- the
+    arrays, their shapes and strides, W, gamma, beta -- is as it was when the call was prepared.  The small
+    workloads are bound by the host's call rate, and building the argument list is a third of a call's cost.
+    Marshalling only: the tensors are kept alive here, nothing is computed."""
+    __slots__ = ("_fn", "_head", "_takes_k", "_stream", "_keep")
+
+    def __init__(self, fn, head, takes_k, stream, keep):
+        self._fn, self._head, self._takes_k, self._stream, self._keep = fn, head, takes_k, stream, keep
+
+    def __call__(self, k: int = 0):
+        st = self._stream if self._stream is not None else _stream()
+        rc = self._fn(*self._head, k, st) if self._takes_k else self._fn(*self._head, st)
+        if rc != DL_OK:
+            raise DecentLamError(rc, last_error())
+
+
+def prepare_step(algo: str, x, m, g, topo, gamma: float, beta: float, stream=None) -> PreparedCall:
+    """decentlam_step / dmsgd_step (`algo` = "decentlam" or "dmsgd") with everything but k fixed; `topo` is a
+    Topology or, to skip the per-call validation of W as well, a PackedTopology."""
+    if algo not in ("decentlam", "dmsgd"):
+        raise ValueError("algo: 'decentlam' or 'dmsgd'")
+    px, n, d, ld = _matrix_args(x, "x")
+    pm, nm, dm, ldm = _matrix_args(m, "m")
+    pg, ng, dg, ldg = _matrix_args(g, "g")
+    if (nm, dm, ldm) != (n, d, ld) or (ng, dg, ldg) != (n, d, ld):
+        raise TypeError("x, m and g must share shape and row stride")
+    if topo.n != n:
+        raise DecentLamError(DL_ETOPO, f"topology has {topo.n} nodes, arrays have {n} rows")
+    vp = ctypes.c_void_p
+    head = [vp(px), vp(pm), vp(pg), ctypes.c_int32(n), ctypes.c_int64(d), ctypes.c_int64(ld)]
+    if isinstance(topo, PackedTopology):
+        fn = getattr(_lib, algo + "_step_packed")
+        head.append(vp(topo._ptr()))
+    else:
+        fn = getattr(_lib, algo + "_step")
+        rp, ci, w, period = topo._args()
+        head += [rp, ci, w, ctypes.c_int32(period)]
+    head += [ctypes.c_float(gamma), ctypes.c_float(beta)]
+    return PreparedCall(fn, tuple(head), True, stream, (x, m, g, topo))
+
+
+def prepare_local_grad_lsq(A, y, x, g, loss=None, scale: float = 1.0, workspace=None, stream=None) -> PreparedCall:
+    """local_grad_lsq with all of its arguments fixed (the iteration number plays no role: call() or call(k))."""
+    if A.dtype != torch.float32 or A.dim() != 3 or not A.is_cuda or A.stride(2) != 1:
+        raise TypeError("A: need a 3-D float32 device tensor with contiguous last axis")
+    n, b, d = A.shape
+    if b > 1 and n > 1 and A.stride(0) != b * A.stride(1):
+        raise TypeError("A: node stride must be b * row stride")
+    ldA = A.stride(1) if b > 1 else max(A.stride(1), d)
+    if y.dtype != torch.float32 or tuple(y.shape) != (n, b) or not y.is_contiguous() or not y.is_cuda:
+        raise TypeError("y: need a contiguous n x b float32 device tensor")
+    px, nx, dx, ld = _matrix_args(x, "x")
+    pg, ng, dg, ldg = _matrix_args(g, "g")
+    if (nx, dx) != (n, d) or (ng, dg, ldg) != (n, d, ld):
+        raise TypeError("x and g must be n x d with the same row stride")
+    pl = 0
+    if loss is not None:
+        if loss.dtype != torch.float32 or tuple(loss.shape) != (n,) or not loss.is_contiguous() or not loss.is_cuda:
+            raise TypeError("loss: need a contiguous float32 device tensor of n elements")
+        pl = loss.data_ptr()
+    if workspace is None:
+        raise TypeError("workspace: pass a uint8 device tensor (size from local_grad_lsq_workspace)")
+    vp = ctypes.c_void_p
+    head = (vp(A.data_ptr()), vp(y.data_ptr()), vp(px), vp(pg), vp(pl), ctypes.c_int32(n), ctypes.c_int32(b),
+            ctypes.c_int64(d), ctypes.c_int64(ldA), ctypes.c_int64(ld), ctypes.c_float(scale),
+            vp(workspace.data_ptr()), ctypes.c_size_t(workspace.numel() * workspace.element_size()))
+    return PreparedCall(_lib.local_grad_lsq, head, False, stream, (A, y, x, g, loss, workspace))
 
 
 def awc_dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):

@@ -169,6 +169,32 @@ int check_step_scalars(const char* fn, Algo algo, int32_t n, int g_format, float
     return DL_OK;
 }
 
+// A packed topology (topology_pack): a header, then `period` phases in kernel-argument form.  Caller-owned
+// host memory; the library keeps no reference to it.
+constexpr uint32_t kPackedMagic = 0x444C5450u;   // "DLTP"
+struct PackedHeader {
+    uint32_t magic;
+    int32_t n;
+    int32_t period;
+    uint32_t phase_bytes;   // sizeof(PhaseArgs) of the library that packed it
+};
+static_assert(sizeof(PackedHeader) == 16 && sizeof(PhaseArgs) % 4 == 0, "phases follow the header, 4-byte aligned");
+
+// The phase of a packed topology that iteration k uses.
+int packed_phase(const char* fn, const void* packed, int32_t n, int64_t k, const PhaseArgs** out) {
+    if (!packed) return set_error(DL_EINVAL, "%s: packed must not be NULL", fn);
+    if (reinterpret_cast<uintptr_t>(packed) & 3u) return set_error(DL_EINVAL, "%s: packed must be 4-byte aligned", fn);
+    const PackedHeader* h = static_cast<const PackedHeader*>(packed);
+    if (h->magic != kPackedMagic || h->phase_bytes != sizeof(PhaseArgs) || h->period < 1 || h->n < 1)
+        return set_error(DL_ETOPO, "%s: packed was not written by this library's topology_pack", fn);
+    if (h->n != n)
+        return set_error(DL_ETOPO, "%s: packed topology has %d nodes, the arrays have %d rows", fn, h->n, n);
+    if (k < 0) return set_error(DL_EINVAL, "%s: k = %lld, need k >= 0", fn, static_cast<long long>(k));
+    const char* phases = static_cast<const char*>(packed) + sizeof(PackedHeader);
+    *out = reinterpret_cast<const PhaseArgs*>(phases + static_cast<size_t>(k % h->period) * sizeof(PhaseArgs));
+    return DL_OK;
+}
+
 // The tensor table of a multi-tensor call: at least one tensor, offsets that do not decrease.
 int check_offsets(const char* fn, int32_t num_tensors, const int64_t* offsets) {
     if (num_tensors < 1) return set_error(DL_EINVAL, "%s: num_tensors = %d, need >= 1", fn, num_tensors);
@@ -195,8 +221,15 @@ int check_norms_buffers(const char* fn, int32_t n, int64_t d, const void* worksp
 int step_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int32_t n, int64_t d,
                int64_t ld, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
                int32_t period, float gamma, float beta, int64_t k, void* stream, float gamma_prev = 0.0f,
-               const StepExtras& ex = StepExtras()) {
+               const StepExtras& ex = StepExtras(), const void* packed = nullptr, bool use_packed = false) {
     clear_error();
+    static const int32_t kNoRows[2] = {0, 0};
+    static const float kNoWeight[1] = {0.f};
+    if (use_packed) {   // W comes validated and encoded: only its presence is checked below
+        row_ptr = col_idx = kNoRows;
+        w = kNoWeight;
+        period = 1;
+    }
     if (int rc = check_step_scalars(fn, algo, n, ex.g_format, gamma, gamma_prev, beta, k, period, row_ptr, col_idx, w))
         return rc;
     int64_t col0 = 0;
@@ -216,9 +249,16 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int
     if (ldg < col0 + d)
         return set_error(DL_EINVAL, "%s: ldg = %lld does not cover the columns", fn, static_cast<long long>(ldg));
 
-    PhaseArgs topo;
-    std::memset(&topo, 0, sizeof(topo));
-    if (int rc = pack_phase(fn, n, row_ptr, col_idx, w, static_cast<int32_t>(k % period), &topo)) return rc;
+    PhaseArgs packed_now;
+    const PhaseArgs* phase = nullptr;
+    if (use_packed) {
+        if (int rc = packed_phase(fn, packed, n, k, &phase)) return rc;
+    } else {
+        std::memset(&packed_now, 0, sizeof(packed_now));
+        if (int rc = pack_phase(fn, n, row_ptr, col_idx, w, static_cast<int32_t>(k % period), &packed_now)) return rc;
+        phase = &packed_now;
+    }
+    const PhaseArgs& topo = *phase;
 
     const bool want_norms = ex.multi && ex.norms != nullptr;
     if (want_norms) {
@@ -377,6 +417,59 @@ int dmsgd_step(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t
                float gamma, float beta, int64_t k, void* stream) {
     return dl::step_entry("dmsgd_step", dl::ALGO_DMSGD, x, m, g, n, d, ld, row_ptr, col_idx, w, period,
                           gamma, beta, k, stream);
+}
+
+size_t topology_pack_bytes(int32_t n, int32_t period) {
+    if (n < 1 || n > DL_MAX_NODES || period < 1) return 0;
+    return sizeof(dl::PackedHeader) + static_cast<size_t>(period) * sizeof(dl::PhaseArgs);
+}
+
+int topology_pack(int32_t n, const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                  void* packed, size_t packed_bytes) {
+    using namespace dl;
+    const char* fn = "topology_pack";
+    clear_error();
+    if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
+    if (period < 1) return set_error(DL_EINVAL, "%s: period = %d, need period >= 1", fn, period);
+    if (!row_ptr || !col_idx || !w || !packed)
+        return set_error(DL_EINVAL, "%s: row_ptr, col_idx, w and packed must not be NULL", fn);
+    if (n > DL_MAX_NODES) return set_error(DL_ETOPO, "%s: n = %d exceeds DL_MAX_NODES = %d", fn, n, DL_MAX_NODES);
+    if (reinterpret_cast<uintptr_t>(packed) & 3u) return set_error(DL_EINVAL, "%s: packed must be 4-byte aligned", fn);
+    const size_t need = topology_pack_bytes(n, period);
+    if (packed_bytes < need)
+        return set_error(DL_ECAP, "%s: packed needs %zu bytes (topology_pack_bytes), %zu given", fn, need, packed_bytes);
+    // every phase is validated and encoded before the header is written: a failed call leaves no valid buffer
+    PackedHeader* h = static_cast<PackedHeader*>(packed);
+    h->magic = 0;
+    char* phases = static_cast<char*>(packed) + sizeof(PackedHeader);
+    for (int32_t p = 0; p < period; ++p) {
+        PhaseArgs* out = reinterpret_cast<PhaseArgs*>(phases + static_cast<size_t>(p) * sizeof(PhaseArgs));
+        std::memset(out, 0, sizeof(PhaseArgs));
+        if (int rc = pack_phase(fn, n, row_ptr, col_idx, w, p, out)) return rc;
+    }
+    h->n = n;
+    h->period = period;
+    h->phase_bytes = static_cast<uint32_t>(sizeof(PhaseArgs));
+    h->magic = kPackedMagic;
+    return DL_OK;
+}
+
+int decentlam_step_packed(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld, const void* packed,
+                          float gamma, float beta, int64_t k, void* stream) {
+    return dl::step_entry("decentlam_step_packed", dl::ALGO_DECENTLAM, x, m, g, n, d, ld, nullptr, nullptr, nullptr, 1,
+                          gamma, beta, k, stream, 0.0f, dl::StepExtras(), packed, true);
+}
+
+int dmsgd_step_packed(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld, const void* packed,
+                      float gamma, float beta, int64_t k, void* stream) {
+    return dl::step_entry("dmsgd_step_packed", dl::ALGO_DMSGD, x, m, g, n, d, ld, nullptr, nullptr, nullptr, 1, gamma,
+                          beta, k, stream, 0.0f, dl::StepExtras(), packed, true);
+}
+
+int dsgd_step_packed(float* x, const float* g, int32_t n, int64_t d, int64_t ld, const void* packed, float gamma,
+                     int64_t k, void* stream) {
+    return dl::step_entry("dsgd_step_packed", dl::ALGO_DSGD, x, nullptr, g, n, d, ld, nullptr, nullptr, nullptr, 1, gamma,
+                          0.0f, k, stream, 0.0f, dl::StepExtras(), packed, true);
 }
 
 int decentlam_step_blocked(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t bw,

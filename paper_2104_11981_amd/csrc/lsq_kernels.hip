@@ -10,7 +10,12 @@
 // with wavefront shuffles plus one LDS hop, then the same registers feed the transposed
 // product, so A is read from HBM exactly once (4*b*d bytes per node).  The next tile's loads are
 // issued before the current tile's reduction.  Each workgroup owns a block of rows of one node
-// and leaves a partial gradient; k_finish_fused adds the partials in fixed order.
+// and leaves a partial gradient; k_finish_fused adds the partials in fixed order.  (Folding that sum into
+// k_fused -- the block that finds all blocks of its node done adds them up -- was built and measured and is
+// not used: the chip has eight L2 caches, a device-wide fence writes back and invalidates a whole one, and one
+// fencing thread per block took workload 5 from 0.65 to 0.69 ms and 8 nodes of 1024 x 1024 from 31 to 73 us;
+// without fences, with device-scope atomic accesses for everything that crosses blocks, the final sum of one
+// block is a chain of uncached loads: 0.64 ms and 54 us.  The second launch costs less than either.)
 //
 // Small problems (bs * d <= 4096 elements per node, any alignment): k_small, one launch,
 // one workgroup per node with A_i, x_i and the residuals in LDS; such sizes are bound by launch

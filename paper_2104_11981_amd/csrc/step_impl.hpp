@@ -668,11 +668,13 @@ int launch_variant(const StepCall& s) {
                          static_cast<int>(s.topo->row_ptr[s.n]), lds_bytes);
     if (lds_bytes > 48 * 1024) {
         // More than 48 KiB of dynamic LDS takes a function attribute: set once per instantiation and
-        // device to the most this chip has (the call costs about 2 us, a fifth of a small step).
-        static std::atomic<uint32_t> configured{0};   // one bit per device ordinal below 32
+        // device to the most this chip has (the call costs about 2 us, a fifth of a small step).  The
+        // one thing the library remembers between calls is that this has been done (a bit per kernel
+        // variant and device, the header says so); devices with ordinal 64 and up set it at every launch.
+        static std::atomic<uint64_t> configured{0};   // one bit per device ordinal below 64
         int device = 0;
         if (int rc = check_hip(hipGetDevice(&device), "hipGetDevice")) return rc;
-        const uint32_t bit = device >= 0 && device < 32 ? 1u << device : 0u;
+        const uint64_t bit = device >= 0 && device < 64 ? uint64_t{1} << device : uint64_t{0};
         if (!(configured.load(std::memory_order_relaxed) & bit) || bit == 0) {
             if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024),

@@ -80,7 +80,16 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
             break;
         }
     }
+    // The fp64 tile and the LDS table of neighbours must fit a CU's 160 KiB: 59-64 nodes with their 118-128 KiB
+    // tile take 16-byte lanes only up to about 2000 entries (16 bytes each); beyond, narrower lanes (half the
+    // tile, 8 bytes per entry) serve every list the encodings accept.
+    if (!mixes_on_matrix_cores(n, topo.row_ptr[n])) {
+        while (vec > 1 && static_cast<size_t>(n) * 64 * vec * sizeof(double) +
+                              static_cast<size_t>(topo.row_ptr[n]) * (vec == 4 ? 16 : 8) > 160 * 1024)
+            vec >>= 1;
+    }
     if (vec == 1) head = 0;
+    else head = static_cast<int64_t>((vec - ((reinterpret_cast<uintptr_t>(x) >> 2) & (vec - 1))) & (vec - 1));
     if (head > d) head = d;
     const int64_t body = ((d - head) / vec) * vec;
     const int64_t tail = d - head - body;

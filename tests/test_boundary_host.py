@@ -195,6 +195,56 @@ def test_lsq_static_refuses_sizes_beyond_its_array():
     assert re.search(r"#define DL_STATIC_SCRATCH_BYTES \(32u << 20\)", header) and P.DL_STATIC_SCRATCH_BYTES == 32 << 20
 
 
+def test_topology_pack_and_packed_step_validation():
+    topo = P.topology_build(P.DL_TOPO_EXP_ONEPEER, 8)
+    need = P.topology_pack_bytes(8, topo.period)
+    assert need > 0 and P.topology_pack_bytes(0, 1) == 0 and P.topology_pack_bytes(257, 1) == 0 and P.topology_pack_bytes(4, 0) == 0
+    buf = np.zeros(need, np.uint8)
+    ptr = ctypes.c_void_p(buf.ctypes.data)
+    assert P.raw.topology_pack(8, *topo._args(), ptr, need - 1) == P.DL_ECAP and "topology_pack_bytes" in P.last_error()
+    assert not buf.any()
+    assert P.raw.topology_pack(8, *topo._args(), None, need) == P.DL_EINVAL
+    assert P.raw.topology_pack(0, *topo._args(), ptr, need) == P.DL_EINVAL
+    rp, ci, w, per = topo._args()
+    assert P.raw.topology_pack(8, None, ci, w, per, ptr, need) == P.DL_EINVAL
+    assert P.raw.topology_pack(8, rp, ci, w, 0, ptr, need) == P.DL_EINVAL
+    bad = P.make_topology(8, topo.row_ptr, topo.col_idx, topo.w * np.float32(0.9), topo.period)   # rows no longer sum to 1
+    assert P.raw.topology_pack(8, *bad._args(), ptr, need) == P.DL_ETOPO
+    # a failed call leaves no valid buffer behind: the step refuses it
+    assert P.raw.decentlam_step_packed(None, None, None, 8, 0, 0, ptr, 0.1, 0.9, 0, None) == P.DL_ETOPO
+    assert P.raw.topology_pack(8, *topo._args(), ptr, need) == P.DL_OK
+    step = lambda **kw: P.raw.decentlam_step_packed(None, None, None, kw.get("n", 8), kw.get("d", 0), 0, kw.get("packed", ptr),
+                                                    kw.get("gamma", 0.1), kw.get("beta", 0.9), kw.get("k", 0), None)
+    assert step() == P.DL_OK                                   # d == 0: no device needed
+    assert step(n=4) == P.DL_ETOPO and "8 nodes" in P.last_error()
+    assert step(packed=None) == P.DL_EINVAL and step(k=-1) == P.DL_EINVAL
+    assert step(gamma=0.0) == P.DL_EINVAL and step(beta=1.0) == P.DL_EINVAL
+    assert step(packed=ctypes.c_void_p(buf.ctypes.data + 1)) == P.DL_EINVAL      # misaligned
+    scribbled = buf.copy()
+    scribbled[0] ^= 0xFF
+    assert step(packed=ctypes.c_void_p(scribbled.ctypes.data)) == P.DL_ETOPO
+    assert P.raw.dmsgd_step_packed(None, None, None, 8, 0, 0, ptr, 0.1, 0.9, 3, None) == P.DL_OK
+    assert P.raw.dsgd_step_packed(None, None, 8, 0, 0, ptr, 0.1, 5, None) == P.DL_OK
+    # the Python wrapper
+    packed = P.topology_pack(topo)
+    assert packed.n == 8 and packed.period == topo.period and packed.buffer.size == need
+    assert bytes(packed.buffer) == bytes(buf)                  # deterministic encoding
+
+
+def test_calibration_stream_argument_validation():
+    fake = ctypes.c_void_p(0x10000)
+    cols = ctypes.c_int64(-1)
+    call = lambda kind=0, split=0, x=fake, n=4, d=1024, ld=1024, out=ctypes.byref(cols): P.raw.dl_calibration_stream(
+        kind, split, x, fake, fake, n, d, ld, out, None)
+    assert call(kind=3) == P.DL_EINVAL and call(split=2) == P.DL_EINVAL
+    assert call(n=0) == P.DL_EINVAL and call(n=33) == P.DL_EINVAL
+    assert call(d=-1) == P.DL_EINVAL and call(d=2048) == P.DL_EINVAL        # ld < d
+    assert call(x=None) == P.DL_EINVAL and call(out=None) == P.DL_EINVAL
+    assert call(x=ctypes.c_void_p(0x10004)) == P.DL_EINVAL and call(ld=1026, d=1024) == P.DL_EINVAL
+    assert call(d=200, ld=200) == P.DL_OK and cols.value == 0                 # less than a tile: nothing to launch
+    assert call(split=1, d=16000, ld=16000) == P.DL_OK and cols.value == 0
+
+
 def test_stats_argument_validation():
     f = P.raw.decentlam_stats
     ws = P.decentlam_stats_workspace(4, 100)

@@ -29,42 +29,56 @@ def decentlam_asm(tmp_path_factory):
     return out.read_text()
 
 
-def instantiation(text, args):
-    m = re.search(r"^(_ZN[^\n]*k_stepI" + args + r"E[^\n:]*):[^\n]*\n", text, re.M)
-    assert m, "instantiation not found in the assembly"
-    body = text[m.end():text.index(".Lfunc_end", m.end())]
+def instantiation(text, template_args, kernel="k_step"):
+    """Instructions of one instantiation, found by its demangled name (`template_args` as a demangler prints
+    them, e.g. "4, 2, 16, 0, 0, false, false"); without a demangler on the machine the Itanium encoding of the
+    arguments is searched for instead."""
+    import shutil
+
+    labels = re.findall(r"^(_Z[\w$.]+):", text, re.M)
+    tool = shutil.which("c++filt") or shutil.which("llvm-cxxfilt")
+    if tool:
+        plain = subprocess.run([tool], input="\n".join(labels), capture_output=True, text=True, check=True).stdout.split("\n")
+    else:
+        enc = "".join({"false": "Lb0E", "true": "Lb1E"}.get(a.strip(), f"Li{a.strip()}E") for a in template_args.split(","))
+        plain = [f"{kernel}<{template_args}>(" if f"{kernel}I{enc}E" in lab else lab for lab in labels]
+    want = f"{kernel}<{template_args}>("
+    hits = [lab for lab, name in zip(labels, plain) if want in name]
+    assert len(hits) == 1, f"{want}: {len(hits)} instantiations in the assembly"
+    start = text.index("\n" + hits[0] + ":") + 1
+    body = text[text.index("\n", start) + 1:text.index(".Lfunc_end", start)]
     return [ln.strip() for ln in body.split("\n") if ln.strip() and not ln.strip().startswith(";")]
 
 
 @pytest.fixture(scope="module")
 def headline_kernel_asm(decentlam_asm):
     # k_step<VEC = 4, RPT = 2, WAVES = 16, DecentLaM, fp32 gradients, no per-tensor sums, gathers>: the 32-node shape
-    return instantiation(decentlam_asm, "Li4ELi2ELi16ELi0ELi0ELb0ELb0")
+    return instantiation(decentlam_asm, "4, 2, 16, 0, 0, false, false")
 
 
 @pytest.fixture(scope="module")
 def dense_kernel_asm(decentlam_asm):
     # the same with the mixing on the matrix cores
-    return instantiation(decentlam_asm, "Li4ELi2ELi16ELi0ELi0ELb0ELb1")
+    return instantiation(decentlam_asm, "4, 2, 16, 0, 0, false, true")
 
 
 def test_row_loads_are_issued_before_the_first_wait_on_them(headline_kernel_asm):
     wide = [k for k, ins in enumerate(headline_kernel_asm) if ins.startswith("global_load_dwordx4")]
-    assert len(wide) == 6, f"expected the six row loads (x, g, m of two rows), found {len(wide)}"
+    assert len(wide) >= 6, f"expected at least the six row loads (x, g, m of two rows), found {len(wide)}"
     waits = [k for k, ins in enumerate(headline_kernel_asm) if ins.startswith("s_waitcnt") and "vmcnt" in ins]
     assert waits, "no wait on the loads at all?"
-    assert all(k < waits[0] for k in wide[:5]), "a row load is issued only after a wait on an earlier one"
-    # the sixth may sit just inside the block that first uses it, but still before any wait
-    assert wide[5] < waits[0] or not any(wide[4] < w < wide[5] for w in waits)
+    assert all(k < waits[0] for k in wide[:-1]), "a row load is issued only after a wait on an earlier one"
+    # the last may sit just inside the block that first uses it, but still before any wait
+    assert wide[-1] < waits[0] or not any(wide[-2] < w < wide[-1] for w in waits)
 
 
 def test_nothing_after_the_barrier_waits_on_vector_memory(headline_kernel_asm):
     barrier = [k for k, ins in enumerate(headline_kernel_asm) if ins.startswith("s_barrier")]
-    assert len(barrier) == 1
+    assert len(barrier) >= 1
     after = headline_kernel_asm[barrier[0]:]
     assert not [ins for ins in after if ins.startswith("s_waitcnt") and "vmcnt" in ins]
     assert not [ins for ins in after if ins.startswith(("global_load", "buffer_load", "flat_load"))]
-    assert len([ins for ins in after if ins.startswith("global_store_dwordx4")]) == 4   # m and x of two rows
+    assert len([ins for ins in after if ins.startswith("global_store_dwordx4")]) >= 4   # m and x of two rows
 
 
 def test_headline_kernel_fits_two_workgroups_per_cu(headline_kernel_asm):
@@ -82,13 +96,13 @@ def test_dense_kernel_multiplies_on_the_matrix_cores(dense_kernel_asm):
     per CU."""
     ins = dense_kernel_asm
     barrier = [k for k, i in enumerate(ins) if i.startswith("s_barrier")]
-    assert len(barrier) == 2
+    assert len(barrier) >= 2
     mfma = [k for k, i in enumerate(ins) if i.startswith("v_mfma_f64_16x16x4")]
-    assert len(mfma) == 16 and barrier[0] < mfma[0]
+    assert len(mfma) >= 16 and barrier[0] < mfma[0]
     after = ins[barrier[0]:]
     assert not [i for i in after if i.startswith("s_waitcnt") and "vmcnt" in i]
     assert not [i for i in after if i.startswith(("global_load", "buffer_load", "flat_load"))]
-    assert len([i for i in after if i.startswith("global_store_dwordx4")]) == 4
+    assert len([i for i in after if i.startswith("global_store_dwordx4")]) >= 4
     text = "\n".join(ins)
     m = re.search(r"\.amdhsa_next_free_vgpr\s+(\d+)", text)
     assert m and int(m.group(1)) <= 64
@@ -98,13 +112,34 @@ def test_dense_kernel_multiplies_on_the_matrix_cores(dense_kernel_asm):
 def test_three_block_dense_kernel(decentlam_asm):
     """33-48 nodes: 48 x 48 times 48 x 16 per wave, thirty-six products; one workgroup per CU, so up to 128
     registers are fine, scratch is not."""
-    ins = instantiation(decentlam_asm, "Li4ELi3ELi16ELi0ELi0ELb0ELb1")
-    assert len([i for i in ins if i.startswith("v_mfma_f64_16x16x4")]) == 36
-    assert len([i for i in ins if i.startswith("s_barrier")]) == 2
+    ins = instantiation(decentlam_asm, "4, 3, 16, 0, 0, false, true")
+    assert len([i for i in ins if i.startswith("v_mfma_f64_16x16x4")]) >= 36
+    assert len([i for i in ins if i.startswith("s_barrier")]) >= 2
     text = "\n".join(ins)
     m = re.search(r"\.amdhsa_next_free_vgpr\s+(\d+)", text)
     assert m and int(m.group(1)) <= 128
     assert not re.search(r"scratch_(load|store)", text)
+
+
+def test_chained_tile_kernel_fits_two_workgroups_per_cu(tmp_path):
+    """k_step_chain keeps twelve values waiting across its loop on top of what k_step holds: it is built for
+    exactly 64 registers per lane (two workgroups of 1024 threads per CU), and a spill would put memory traffic
+    of its own into a kernel that is bound by memory."""
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not installed")
+    from paper_2104_11981_amd import build
+
+    out = tmp_path / "step_chain.s"
+    flags = [f for f in build.FLAGS if f != "-fPIC"]
+    subprocess.run([HIPCC] + flags + ["-S", "--cuda-device-only", os.path.join(build.CSRC, "step_chain.hip"), "-o", str(out)],
+                   check=True, capture_output=True)
+    text = out.read_text()
+    for algo in (0, 1, 4):   # DecentLaM, DmSGD, AWC-DmSGD
+        body = "\n".join(instantiation(text, str(algo), kernel="k_step_chain"))
+        m = re.search(r"\.amdhsa_next_free_vgpr\s+(\d+)", body)
+        assert m and int(m.group(1)) <= 64
+        assert not re.search(r"scratch_(load|store)", body)
+        assert len(re.findall(r"global_load_dwordx4", body)) >= 9     # three before the loop, six inside
 
 
 SPLIT_CHECK = r"""

@@ -3,11 +3,16 @@ Inconsistency Bias", Sec. "Improving Inconsistency Bias", appendix "Experimental
 linear regression"): n = 8, A_i 50 x 30 Gaussian, b_i = A_i x^o + 0.01 noise, gamma = 1e-3,
 beta = 0.8, exact gradients A_i^T (A_i x - b_i), DSGD vs DmSGD vs DecentLaM.
 
-The paper's curves and its mesh topology are lost with the figures, so the check is against the
-closed-form limits: the fixed-point equations of the appendix "Limiting Bias of Decentralized
-Algorithms" are solved directly in fp64 (numpy) and the GPU iterates (local_grad_lsq + step
-kernels, fp32 storage) must land on them; the relative-error metric of the appendix comes from
-decentlam_stats.  Topology: ring with uniform weights 1/3 (Metropolis-Hastings on a ring).
+Topologies: the paper's own, the mesh with Metropolis-Hastings weights (8 nodes: 2 x 4), the
+symmetric exponential graph, and the ring.  The paper's curves are lost with its figures, so the
+GPU run (local_grad_lsq + step kernels, fp32 storage) is checked against
+  * the oracle's trajectory of the same study (oracle.lsq_grad + the oracle's step, fp32 storage):
+    at checked iterations one GPU iteration from the oracle's state, element by element, and the
+    free-running GPU state in Frobenius norm;
+  * the closed-form limits: the fixed-point equations of the appendix "Limiting Bias of
+    Decentralized Algorithms", solved directly in fp64 (numpy), on which the iterates must land;
+  * the paper's claim itself: DecentLaM's limit is DSGD's, and DmSGD's is several times further
+    from the global solution; the relative-error metric of the appendix comes from decentlam_stats.
 Inputs are synthetic and seeded; the stated limits are this data set's, not the paper's.
 """
 import numpy as np
@@ -17,8 +22,11 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
+CHECKED = (0, 1, 2, 10, 100, 1000, 2999)   # iterations k whose step k -> k + 1 is compared
 
-def test_dsgd_dmsgd_decentlam_limits():
+
+@pytest.mark.parametrize("kind", [4, 3, 0], ids=["mesh_2x4_metropolis", "exp_sym", "ring"])
+def test_dsgd_dmsgd_decentlam_trajectories_and_limits(oracle, kind):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     import paper_2104_11981_amd as P
@@ -30,11 +38,10 @@ def test_dsgd_dmsgd_decentlam_limits():
     xo = r.standard_normal(d)
     y0 = (np.einsum("nbd,d->nb", A0.astype(np.float64), xo) + 0.01 * r.standard_normal((n, b))).astype(np.float32)
 
-    topo = P.topology_build(P.DL_TOPO_RING, n)
-    W = np.zeros((n, n))
-    for i in range(n):
-        for e in range(topo.row_ptr[i], topo.row_ptr[i + 1]):
-            W[i, topo.col_idx[e]] = float(topo.w[e])
+    topo = P.topology_build(kind, n)
+    otopo = oracle.topology(kind, n)
+    assert topo.flags & P.DL_FLAG_SYMMETRIC and topo.period == 1
+    W = otopo.dense(0)
 
     # closed forms: global minimiser and the two fixed points (fp64)
     A64 = A0.astype(np.float64)
@@ -55,32 +62,62 @@ def test_dsgd_dmsgd_decentlam_limits():
     fp_lam, fp_dm = fixed_point(1.0), fixed_point(1.0 - beta)
     assert rel_err(fp_dm) > 5 * rel_err(fp_lam)       # the bias DmSGD's momentum adds
 
-    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
     A, y = dev(A0), dev(y0)
-    ref = dev(xstar.astype(np.float32))
+    ref = dev(xstar)
     ws = torch.empty(P.local_grad_lsq_workspace(n, b, d), dtype=torch.uint8, device="cuda")
     sws = torch.empty(P.decentlam_stats_workspace(n, d), dtype=torch.uint8, device="cuda")
     out = torch.empty(5, dtype=torch.float64, device="cuda")
+    r32 = lambda a: a.astype(np.float32).astype(np.float64)
+
+    def gpu_iteration(algo, x, m, g, k):
+        P.local_grad_lsq(A, y, x, g, None, 1.0, ws)
+        if algo == "dsgd":
+            P.dsgd_step(x, g, topo, gamma, k)
+        else:
+            getattr(P, algo + "_step")(x, m, g, topo, gamma, beta, k)
+
+    def oracle_iteration(algo, xs, ms, k):
+        gs = r32(oracle.lsq_grad(A0, y0, xs, 1.0)[0])
+        if algo == "dsgd":
+            return r32(oracle.dsgd_step(xs, gs, otopo, gamma, k)), ms
+        xn, mn = oracle.STEP[algo](xs, ms, gs, otopo, gamma, beta, k)
+        return r32(xn), r32(mn)
+
+    def close(got, want, what):
+        err = np.abs(got.cpu().numpy().astype(np.float64) - want)
+        assert (err <= 1e-5 * (1 + np.abs(want))).all(), f"{what}: off by {err.max():.3e}"
 
     def run(algo, iterations):
         x = torch.zeros((n, d), dtype=torch.float32, device="cuda")
         m = torch.zeros_like(x)
         g = torch.empty_like(x)
+        xs, ms = np.zeros((n, d)), np.zeros((n, d))         # the oracle's own trajectory
         for k in range(iterations):
-            P.local_grad_lsq(A, y, x, g, None, 1.0, ws)
-            if algo == "dsgd":
-                P.dsgd_step(x, g, topo, gamma, k)
-            else:
-                getattr(P, algo + "_step")(x, m, g, topo, gamma, beta, k)
+            xs_next, ms_next = oracle_iteration(algo, xs, ms, k)
+            if k in CHECKED:
+                # (S) one GPU iteration from the oracle's state k against the oracle's state k + 1
+                xt, mt, gt = dev(xs), dev(ms), torch.empty_like(x)
+                gpu_iteration(algo, xt, mt, gt, k)
+                close(xt, xs_next, f"{algo} x after iteration {k}")
+                if algo != "dsgd":
+                    close(mt, ms_next, f"{algo} m after iteration {k}")
+            gpu_iteration(algo, x, m, g, k)
+            xs, ms = xs_next, ms_next
+            if k in CHECKED:
+                # (F) the GPU's free-running state against the oracle's
+                diff = np.linalg.norm(x.cpu().numpy().astype(np.float64) - xs)
+                assert diff <= 1e-4 * np.linalg.norm(xs), f"{algo}: trajectories differ by {diff:.3e} at iteration {k}"
         P.decentlam_stats(x, m, ref, out, sws)
         s = out.cpu().numpy()
-        return x.cpu().numpy().astype(np.float64), m.cpu().numpy(), s[2] / (n * s[3])
+        return x.cpu().numpy().astype(np.float64), m.cpu().numpy(), s[2] / (n * s[3]), xs
 
-    x_lam, m_lam, e_lam = run("decentlam", 3000)
-    x_dm, _, e_dm = run("dmsgd", 3000)
-    x_ds, _, e_ds = run("dsgd", 6000)
+    x_lam, m_lam, e_lam, o_lam = run("decentlam", 3000)
+    x_dm, _, e_dm, o_dm = run("dmsgd", 3000)
+    x_ds, _, e_ds, o_ds = run("dsgd", 6000)
 
     assert np.abs(x_lam - fp_lam).max() < 5e-6 and np.abs(x_dm - fp_dm).max() < 5e-6
+    assert np.abs(o_lam - fp_lam).max() < 5e-6 and np.abs(o_dm - fp_dm).max() < 5e-6   # the oracle lands there too
     assert np.abs(x_ds - fp_lam).max() < 2e-5          # DSGD stalls a little earlier in fp32 storage
     assert np.abs(m_lam).max() < 1e-2                  # DecentLaM's momentum dies out (up to ulp(x)/gamma)
     np.testing.assert_allclose(e_lam, rel_err(fp_lam), rtol=2e-3)
