@@ -134,11 +134,10 @@ def test_step_topology_validation():
     assert _call(fn, n=50, topo=_topo(50, mixed)) == P.DL_ETOPO and "mixed weights" in P.last_error()
     exp256 = P.topology_build(P.DL_TOPO_EXP_STATIC, 256)    # 9 x 256 = 2304 entries, all 1/9
     assert _call(fn, n=256, topo=exp256) == P.DL_OK
-    # a graph that fits the kernel arguments but not the LDS beside the tile: refused before any launch
+    # a graph that fits the kernel arguments but not the LDS beside a tile of 16-byte lanes: accepted (it runs
+    # with narrower lanes; tests/test_gpu_limits.py launches it)
     wide = _topo(64, [[((i + t) % 64, 1.0 / 40) for t in range(40)] for i in range(64)])   # 2560 entries
     assert _call(fn, n=64, topo=wide) == P.DL_OK            # d == 0: nothing to launch
-    assert _call(fn, n=64, d=8, ld=8, topo=wide, x=1 << 20, m=2 << 20, g=3 << 20) == P.DL_ETOPO
-    assert "LDS" in P.last_error()
     rng = np.random.default_rng(0)
     rows = []
     for i in range(30):                                     # 900 entries, all weights different
