@@ -198,6 +198,39 @@ int dsgd_step_packed(float* x, const float* g, int32_t n, int64_t d, int64_t ld,
                      const void* packed, float gamma, int64_t k, void* stream);
 
 /*
+ * topology_pack_device, *_step_dev -- graphs beyond the limits above: up to DL_MAX_NODES_DEVICE nodes,
+ * neighbour lists of any length with arbitrary weights (eq. (2) asks nothing more of W than its sparsity
+ * pattern and weights).  The lists live in DEVICE memory: topology_pack_device validates all phases on the host
+ * (the W rules of decentlam_step) and copies them, encoded, into a caller-owned device buffer of
+ * topology_device_bytes(n, period, total entries over all phases) bytes, 8-byte aligned.  It is a set-up call:
+ * the copy is synchronous (do not call it under graph capture).  It fills a small host descriptor that the
+ * *_step_dev calls take; the descriptor holds the device pointer and must not outlive the buffer.
+ * The step is the same in-place, single-pass, fp64-in-registers update (20 bytes per node-element), on a kernel
+ * built for reach rather than speed: its tile narrows as n grows (64 columns up to 256 nodes, 32 up to 512, 16
+ * up to 1024), so rows are touched 256, 128 or 64 bytes at a time.  Graphs that fit the ordinary calls should
+ * use them.  fp32 gradients, row-major arrays; decentlam, dmsgd and dsgd.
+ * Errors: DL_EINVAL, DL_ETOPO (also: n > DL_MAX_NODES_DEVICE, descriptor not written by topology_pack_device or
+ *         for another node count), DL_ECAP (device buffer too small), DL_EALIAS, DL_EHIP.
+ */
+#define DL_MAX_NODES_DEVICE 1024
+typedef struct {
+    uint32_t magic;          /* set by topology_pack_device */
+    int32_t n, period;
+    int32_t reserved;
+    const void* device;      /* the caller's device buffer */
+    uint64_t device_bytes;   /* bytes of it in use */
+} dl_device_topology;
+size_t topology_device_bytes(int32_t n, int32_t period, int64_t nnz_total);
+int topology_pack_device(int32_t n, const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                         void* device_buffer, size_t device_bytes, dl_device_topology* out);
+int decentlam_step_dev(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
+                       const dl_device_topology* W, float gamma, float beta, int64_t k, void* stream);
+int dmsgd_step_dev(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld,
+                   const dl_device_topology* W, float gamma, float beta, int64_t k, void* stream);
+int dsgd_step_dev(float* x, const float* g, int32_t n, int64_t d, int64_t ld,
+                  const dl_device_topology* W, float gamma, int64_t k, void* stream);
+
+/*
  * decentlam_step_xprev -- DecentLaM in its momentum-free form (appendix "Reformulation of
  * DecentLaM"): with m^k = (x^{k-1} - x^k) / gamma_{k-1} eliminated,
  *     x^{k+1} = W (x^k - gamma_k g^k) + beta (gamma_k / gamma_{k-1}) (x^k - x^{k-1}).

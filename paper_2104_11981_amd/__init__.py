@@ -21,7 +21,8 @@ _BINDING_NAMES = (
     "local_grad_lsq_static", "DL_STATIC_SCRATCH_BYTES", "dl_calibration_stream",
     "make_topology", "topology_build", "topology_metropolis", "topology_pack", "topology_pack_bytes", "PackedTopology",
     "decentlam_step_packed", "dmsgd_step_packed", "dsgd_step_packed", "PreparedCall", "prepare_step",
-    "prepare_local_grad_lsq",
+    "prepare_local_grad_lsq", "topology_device_bytes", "topology_pack_device", "DeviceTopology", "DeviceTopologyStruct",
+    "decentlam_step_dev", "dmsgd_step_dev", "dsgd_step_dev", "DL_MAX_NODES_DEVICE",
 )
 __all__ = list(_BINDING_NAMES) + ["raw"]
 

@@ -30,19 +30,27 @@ DL_MAX_NODES, DL_MAX_NNZ, DL_MAX_NNZ_PALETTE, DL_MAX_WEIGHT_VALUES = 256, 512, 1
 
 DL_GRAD_F32, DL_GRAD_BF16, DL_GRAD_F16 = 0, 1, 2
 DL_STATIC_SCRATCH_BYTES = 32 << 20
+DL_MAX_NODES_DEVICE = 1024
 
 EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decentlam_step", "decentlam_step_xprev",
            "dmsgd_step", "dsgd_step", "awc_dmsgd_step", "da_dmsgd_step", "decentlam_step_blocked",
            "dmsgd_step_blocked", "decentlam_step_ex", "dmsgd_step_ex", "decentlam_step_xprev_ex", "decentlam_step_multi_ex", "dmsgd_step_multi_ex", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
            "dmsgd_step_multi", "decentlam_step_multi_workspace", "local_grad_lsq", "local_grad_lsq_rows",
            "local_grad_lsq_static", "dl_calibration_stream", "topology_pack_bytes", "topology_pack",
-           "decentlam_step_packed", "dmsgd_step_packed", "dsgd_step_packed",
+           "decentlam_step_packed", "dmsgd_step_packed", "dsgd_step_packed", "topology_device_bytes",
+           "topology_pack_device", "decentlam_step_dev", "dmsgd_step_dev", "dsgd_step_dev",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
 
 class Layout(ctypes.Structure):
     """dl_layout of include/decentlam.h."""
     _fields_ = [("g_format", ctypes.c_int32), ("ld", ctypes.c_int64), ("ldg", ctypes.c_int64), ("bw", ctypes.c_int64)]
+
+
+class DeviceTopologyStruct(ctypes.Structure):
+    """dl_device_topology of include/decentlam.h."""
+    _fields_ = [("magic", ctypes.c_uint32), ("n", ctypes.c_int32), ("period", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("device", ctypes.c_void_p), ("device_bytes", ctypes.c_uint64)]
 
 
 class DecentLamError(RuntimeError):
@@ -137,6 +145,18 @@ def _load() -> ctypes.CDLL:
     lib.dsgd_step_packed.restype = ctypes.c_int
     lib.dsgd_step_packed.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, vp, ctypes.c_float,
                                      ctypes.c_int64, vp]
+    dtp = ctypes.POINTER(DeviceTopologyStruct)
+    lib.topology_device_bytes.restype = ctypes.c_size_t
+    lib.topology_device_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64]
+    lib.topology_pack_device.restype = ctypes.c_int
+    lib.topology_pack_device.argtypes = [ctypes.c_int32, i32p, i32p, f32p, ctypes.c_int32, vp, ctypes.c_size_t, dtp]
+    for name in ("decentlam_step_dev", "dmsgd_step_dev"):
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, dtp, ctypes.c_float,
+                                       ctypes.c_float, ctypes.c_int64, vp]
+    lib.dsgd_step_dev.restype = ctypes.c_int
+    lib.dsgd_step_dev.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, dtp, ctypes.c_float,
+                                  ctypes.c_int64, vp]
     lib.dl_calibration_stream.restype = ctypes.c_int
     lib.dl_calibration_stream.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp, vp, ctypes.c_int32, ctypes.c_int64,
                                           ctypes.c_int64, ctypes.POINTER(ctypes.c_int64), vp]
@@ -483,6 +503,60 @@ def dsgd_step_packed(x, g, packed: PackedTopology, gamma: float, k: int = 0, str
     if (ng, dg, ldg) != (n, d, ld):
         raise TypeError("x and g must share shape and row stride")
     _check(_lib.dsgd_step_packed(px, pg, n, d, ld, packed._ptr(), gamma, k, _stream() if stream is None else stream))
+
+
+def topology_device_bytes(n: int, period: int, nnz_total: int) -> int:
+    return int(_lib.topology_device_bytes(n, period, nnz_total))
+
+
+@dataclass
+class DeviceTopology:
+    """A topology held in device memory by topology_pack_device, for the *_step_dev calls (up to 1024 nodes, lists
+    of any length).  `buffer` is the caller-owned device buffer (a uint8 tensor, kept alive here), `desc` the host
+    descriptor the C calls take."""
+    n: int
+    period: int
+    buffer: "torch.Tensor"
+    desc: DeviceTopologyStruct
+
+
+def topology_pack_device(topo: Topology, device="cuda") -> DeviceTopology:
+    """topology_pack_device: validate every phase and copy the lists into a fresh device buffer (synchronous)."""
+    nbytes = topology_device_bytes(topo.n, topo.period, int(topo.col_idx.size))
+    if nbytes == 0:
+        raise DecentLamError(DL_ETOPO, f"topology_pack_device: n = {topo.n}, period = {topo.period} cannot be packed")
+    buf = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    desc = DeviceTopologyStruct()
+    _check(_lib.topology_pack_device(topo.n, *topo._args(), buf.data_ptr(), nbytes, ctypes.byref(desc)))
+    return DeviceTopology(topo.n, topo.period, buf, desc)
+
+
+def _step_dev(fn, x, m, g, W: DeviceTopology, gamma, beta, k, stream):
+    px, n, d, ld = _matrix_args(x, "x")
+    pm, nm, dm, ldm = _matrix_args(m, "m")
+    pg, ng, dg, ldg = _matrix_args(g, "g")
+    if (nm, dm, ldm) != (n, d, ld) or (ng, dg, ldg) != (n, d, ld):
+        raise TypeError("x, m and g must share shape and row stride")
+    _check(fn(px, pm, pg, n, d, ld, ctypes.byref(W.desc), gamma, beta, k, _stream() if stream is None else stream))
+
+
+def decentlam_step_dev(x, m, g, W: DeviceTopology, gamma: float, beta: float, k: int = 0, stream=None):
+    """decentlam_step with the neighbour lists in device memory (graphs beyond the ordinary calls' limits)."""
+    _step_dev(_lib.decentlam_step_dev, x, m, g, W, gamma, beta, k, stream)
+
+
+def dmsgd_step_dev(x, m, g, W: DeviceTopology, gamma: float, beta: float, k: int = 0, stream=None):
+    """dmsgd_step with the neighbour lists in device memory."""
+    _step_dev(_lib.dmsgd_step_dev, x, m, g, W, gamma, beta, k, stream)
+
+
+def dsgd_step_dev(x, g, W: DeviceTopology, gamma: float, k: int = 0, stream=None):
+    """dsgd_step with the neighbour lists in device memory."""
+    px, n, d, ld = _matrix_args(x, "x")
+    pg, ng, dg, ldg = _matrix_args(g, "g")
+    if (ng, dg, ldg) != (n, d, ld):
+        raise TypeError("x and g must share shape and row stride")
+    _check(_lib.dsgd_step_dev(px, pg, n, d, ld, ctypes.byref(W.desc), gamma, k, _stream() if stream is None else stream))
 
 
 class PreparedCall:

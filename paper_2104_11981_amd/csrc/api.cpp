@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "internal.hpp"
 
@@ -40,6 +41,39 @@ Span span_of(const void* p, int64_t rows, int64_t cols, int64_t ld, int64_t elem
     return {lo, lo + static_cast<uintptr_t>(((rows - 1) * ld + cols) * elem_bytes)};
 }
 bool overlap(Span a, Span b) { return a.lo < b.hi && b.lo < a.hi; }
+
+// Validate phase `p` of the caller's CSR (the rules of the header: rows non-empty, indices in range, no duplicate
+// in a row, weights finite and positive, row sums 1 within 1e-6) for up to `max_n` nodes.
+int validate_phase(const char* fn, int32_t n, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
+                   int32_t p, int32_t max_n, int64_t* nnz_out) {
+    if (n > max_n) return set_error(DL_ETOPO, "%s: n = %d exceeds the limit of %d nodes", fn, n, max_n);
+    const int32_t* rp = row_ptr + static_cast<int64_t>(p) * (n + 1);
+    const int64_t base = rp[0];
+    const int64_t nnz = static_cast<int64_t>(rp[n]) - base;
+    if (base < 0 || nnz < n) return set_error(DL_ETOPO, "%s: phase %d: row_ptr not monotone or a row is empty", fn, p);
+    std::vector<int32_t> last_seen(static_cast<size_t>(n), -1);
+    for (int32_t i = 0; i < n; ++i) {
+        const int64_t b = rp[i], e = rp[i + 1];
+        if (e <= b) return set_error(DL_ETOPO, "%s: phase %d row %d is empty or row_ptr decreases", fn, p, i);
+        double sum = 0.0;
+        for (int64_t q = b; q < e; ++q) {
+            const int32_t j = col_idx[q];
+            const float wij = w[q];
+            if (j < 0 || j >= n)
+                return set_error(DL_ETOPO, "%s: phase %d row %d: neighbour index %d outside [0, %d)", fn, p, i, j, n);
+            if (last_seen[j] == i) return set_error(DL_ETOPO, "%s: phase %d row %d lists neighbour %d twice", fn, p, i, j);
+            last_seen[j] = i;
+            if (!std::isfinite(wij) || !(wij > 0.0f))
+                return set_error(DL_ETOPO, "%s: phase %d: w[%d,%d] = %g must be finite and > 0", fn, p, i, j,
+                                 static_cast<double>(wij));
+            sum += static_cast<double>(wij);
+        }
+        if (std::fabs(sum - 1.0) > 1e-6)
+            return set_error(DL_ETOPO, "%s: phase %d row %d sums to %.9g, not 1", fn, p, i, sum);
+    }
+    *nnz_out = nnz;
+    return DL_OK;
+}
 
 // Validate phase `p` of the caller's CSR and copy it into kernel-argument form.
 int pack_phase(const char* fn, int32_t n, const int32_t* row_ptr, const int32_t* col_idx,
@@ -221,11 +255,12 @@ int check_norms_buffers(const char* fn, int32_t n, int64_t d, const void* worksp
 int step_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int32_t n, int64_t d,
                int64_t ld, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
                int32_t period, float gamma, float beta, int64_t k, void* stream, float gamma_prev = 0.0f,
-               const StepExtras& ex = StepExtras(), const void* packed = nullptr, bool use_packed = false) {
+               const StepExtras& ex = StepExtras(), const void* packed = nullptr, bool use_packed = false,
+               const dl_device_topology* device_topo = nullptr, bool use_device = false) {
     clear_error();
     static const int32_t kNoRows[2] = {0, 0};
     static const float kNoWeight[1] = {0.f};
-    if (use_packed) {   // W comes validated and encoded: only its presence is checked below
+    if (use_packed || use_device) {   // W comes validated and encoded: only its presence is checked below
         row_ptr = col_idx = kNoRows;
         w = kNoWeight;
         period = 1;
@@ -251,7 +286,15 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int
 
     PhaseArgs packed_now;
     const PhaseArgs* phase = nullptr;
-    if (use_packed) {
+    if (use_device) {
+        if (!device_topo) return set_error(DL_EINVAL, "%s: W must not be NULL", fn);
+        if (device_topo->magic != kDeviceTopoMagic || !device_topo->device || device_topo->period < 1)
+            return set_error(DL_ETOPO, "%s: W was not written by topology_pack_device", fn);
+        if (device_topo->n != n)
+            return set_error(DL_ETOPO, "%s: W has %d nodes, the arrays have %d rows", fn, device_topo->n, n);
+        std::memset(&packed_now, 0, sizeof(packed_now));   // not used by this path
+        phase = &packed_now;
+    } else if (use_packed) {
         if (int rc = packed_phase(fn, packed, n, k, &phase)) return rc;
     } else {
         std::memset(&packed_now, 0, sizeof(packed_now));
@@ -294,6 +337,14 @@ int step_entry(const char* fn, Algo algo, float* x, float* m, const void* g, int
         beta_eff = beta_eff * static_cast<double>(gamma) / static_cast<double>(gamma_prev);
     const GradArg ga{g, ex.g_format, ldg};
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (use_device) {
+        const Span st = {reinterpret_cast<uintptr_t>(device_topo->device),
+                         reinterpret_cast<uintptr_t>(device_topo->device) + static_cast<uintptr_t>(device_topo->device_bytes)};
+        if (overlap(st, sx) || (uses_m && overlap(st, sm)))
+            return set_error(DL_EALIAS, "%s: W's device buffer overlaps x or m", fn);
+        return launch_step_wide(algo, x, m, static_cast<const float*>(g), n, d, ld, gamma, beta_eff, device_topo->device,
+                                static_cast<int32_t>(k % device_topo->period), s);
+    }
     if (!want_norms) return launch_step(algo, x, m, ga, n, d, ld, topo, gamma, beta_eff, s);
 
     const size_t need = multi_workspace_bytes(n, d);
@@ -470,6 +521,78 @@ int dsgd_step_packed(float* x, const float* g, int32_t n, int64_t d, int64_t ld,
                      int64_t k, void* stream) {
     return dl::step_entry("dsgd_step_packed", dl::ALGO_DSGD, x, nullptr, g, n, d, ld, nullptr, nullptr, nullptr, 1, gamma,
                           0.0f, k, stream, 0.0f, dl::StepExtras(), packed, true);
+}
+
+size_t topology_device_bytes(int32_t n, int32_t period, int64_t nnz_total) {
+    if (n < 1 || n > DL_MAX_NODES_DEVICE || period < 1 || nnz_total < 0) return 0;
+    const size_t words = static_cast<size_t>(dl::kDeviceTopoHeaderWords) + ((static_cast<size_t>(period) + 1) & ~size_t{1}) +
+                         static_cast<size_t>(period) * dl::device_topo_row_ptr_words(n) + 2 * static_cast<size_t>(nnz_total);
+    return words * 4;
+}
+
+int topology_pack_device(int32_t n, const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                         void* device_buffer, size_t device_bytes, dl_device_topology* out) {
+    using namespace dl;
+    const char* fn = "topology_pack_device";
+    clear_error();
+    if (n < 1) return set_error(DL_EINVAL, "%s: n = %d, need n >= 1", fn, n);
+    if (period < 1) return set_error(DL_EINVAL, "%s: period = %d, need period >= 1", fn, period);
+    if (!row_ptr || !col_idx || !w || !device_buffer || !out)
+        return set_error(DL_EINVAL, "%s: row_ptr, col_idx, w, device_buffer and out must not be NULL", fn);
+    if (reinterpret_cast<uintptr_t>(device_buffer) & 7u) return set_error(DL_EINVAL, "%s: device_buffer must be 8-byte aligned", fn);
+    out->magic = 0;
+    int64_t total = 0;
+    for (int32_t p = 0; p < period; ++p) {
+        int64_t nnz = 0;
+        if (int rc = validate_phase(fn, n, row_ptr, col_idx, w, p, DL_MAX_NODES_DEVICE, &nnz)) return rc;
+        total += nnz;
+    }
+    const size_t need = topology_device_bytes(n, period, total);
+    if (device_bytes < need)
+        return set_error(DL_ECAP, "%s: device_buffer needs %zu bytes (topology_device_bytes), %zu given", fn, need, device_bytes);
+    std::vector<uint32_t> img(need / 4, 0u);
+    img[0] = kDeviceTopoMagic;
+    img[1] = static_cast<uint32_t>(n);
+    img[2] = static_cast<uint32_t>(period);
+    size_t at = static_cast<size_t>(kDeviceTopoHeaderWords) + ((static_cast<size_t>(period) + 1) & ~size_t{1});
+    for (int32_t p = 0; p < period; ++p) {
+        const int32_t* rp = row_ptr + static_cast<int64_t>(p) * (n + 1);
+        img[kDeviceTopoHeaderWords + p] = static_cast<uint32_t>(at);
+        for (int32_t i = 0; i <= n; ++i) img[at + i] = static_cast<uint32_t>(rp[i] - rp[0]);
+        at += device_topo_row_ptr_words(n);
+        for (int64_t q = rp[0]; q < rp[n]; ++q) {
+            img[at++] = static_cast<uint32_t>(col_idx[q]);
+            uint32_t bits;
+            std::memcpy(&bits, &w[q], 4);
+            img[at++] = bits;
+        }
+    }
+    // a set-up call: the copy is synchronous, so the host image may go when the call returns
+    if (int rc = check_hip(hipMemcpy(device_buffer, img.data(), need, hipMemcpyHostToDevice), "hipMemcpy(topology)")) return rc;
+    out->n = n;
+    out->period = period;
+    out->device = device_buffer;
+    out->device_bytes = need;
+    out->magic = kDeviceTopoMagic;
+    return DL_OK;
+}
+
+int decentlam_step_dev(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld, const dl_device_topology* W,
+                       float gamma, float beta, int64_t k, void* stream) {
+    return dl::step_entry("decentlam_step_dev", dl::ALGO_DECENTLAM, x, m, g, n, d, ld, nullptr, nullptr, nullptr, 1, gamma,
+                          beta, k, stream, 0.0f, dl::StepExtras(), nullptr, false, W, true);
+}
+
+int dmsgd_step_dev(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld, const dl_device_topology* W,
+                   float gamma, float beta, int64_t k, void* stream) {
+    return dl::step_entry("dmsgd_step_dev", dl::ALGO_DMSGD, x, m, g, n, d, ld, nullptr, nullptr, nullptr, 1, gamma, beta, k,
+                          stream, 0.0f, dl::StepExtras(), nullptr, false, W, true);
+}
+
+int dsgd_step_dev(float* x, const float* g, int32_t n, int64_t d, int64_t ld, const dl_device_topology* W, float gamma,
+                  int64_t k, void* stream) {
+    return dl::step_entry("dsgd_step_dev", dl::ALGO_DSGD, x, nullptr, g, n, d, ld, nullptr, nullptr, nullptr, 1, gamma, 0.0f,
+                          k, stream, 0.0f, dl::StepExtras(), nullptr, false, W, true);
 }
 
 int decentlam_step_blocked(float* x, float* m, const float* g, int32_t n, int64_t d, int64_t bw,

@@ -113,6 +113,16 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
 int launch_norms_finish(const NormPlan& plan, const float* x, const float* m, GradArg g, int64_t ld, int32_t n,
                         hipStream_t stream);
 
+// Device-resident topology (topology_pack_device), 32-bit words: header {magic, n, period, 0}, `period` phase
+// offsets (in words from the start of the buffer, each even), then per phase n + 1 row offsets into the phase's
+// entries (padded to an even count) followed by the entries as (column, fp32 weight bits) pairs.
+constexpr uint32_t kDeviceTopoMagic = 0x444C4454u;   // "DLDT"
+constexpr int kDeviceTopoHeaderWords = 4;
+__host__ __device__ constexpr int device_topo_row_ptr_words(int n) { return (n + 2) & ~1; }
+// Enqueue one iteration with the lists of phase `phase` read from `device_topology` (already validated).
+int launch_step_wide(Algo algo, float* x, float* m, const float* g, int32_t n, int64_t d, int64_t ld, float gamma,
+                     double beta, const void* device_topology, int32_t phase, hipStream_t stream);
+
 // Least-squares gradient (already validated).
 size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d);
 // What the kernels that launch_lsq picks for this shape and alignment actually use (<= lsq_workspace_bytes).

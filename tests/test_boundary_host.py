@@ -230,6 +230,35 @@ def test_topology_pack_and_packed_step_validation():
     assert bytes(packed.buffer) == bytes(buf)                  # deterministic encoding
 
 
+def test_device_topology_argument_validation():
+    """What topology_pack_device and the *_step_dev calls refuse before any device work."""
+    t = P.topology_build(P.DL_TOPO_EXP_SYM, 512)
+    nnz = int(t.col_idx.size)
+    need = P.topology_device_bytes(512, 1, nnz)
+    assert need == 4 * (4 + 2 + 514 + 2 * nnz)
+    assert P.topology_device_bytes(1025, 1, 10) == 0 and P.topology_device_bytes(0, 1, 1) == 0 and P.topology_device_bytes(4, 0, 1) == 0
+    desc = P.DeviceTopologyStruct()
+    fake = ctypes.c_void_p(0x100000)
+    call = lambda topo=t, n=512, buf=fake, nbytes=need, out=ctypes.byref(desc): P.raw.topology_pack_device(
+        n, *topo._args(), buf, nbytes, out)
+    assert call(nbytes=need - 4) == P.DL_ECAP and "topology_device_bytes" in P.last_error()   # checked before the copy
+    assert call(buf=None) == P.DL_EINVAL and call(out=None) == P.DL_EINVAL and call(n=0) == P.DL_EINVAL
+    assert call(buf=ctypes.c_void_p(0x100004)) == P.DL_EINVAL
+    big = P.make_topology(1025, np.arange(1026), np.arange(1025), np.ones(1025, np.float32))
+    assert call(topo=big, n=1025) == P.DL_ETOPO and "1024" in P.last_error()
+    bad = P.make_topology(512, t.row_ptr, t.col_idx, t.w * np.float32(1.01))
+    assert call(topo=bad) == P.DL_ETOPO and "sums to" in P.last_error()
+    assert desc.magic == 0
+    step = lambda W=ctypes.byref(desc), n=512, d=0: P.raw.decentlam_step_dev(None, None, None, n, d, 0, W, 0.1, 0.9, 0, None)
+    assert step() == P.DL_ETOPO and "topology_pack_device" in P.last_error()     # a descriptor nobody filled in
+    assert step(W=None) == P.DL_EINVAL
+    filled = P.DeviceTopologyStruct(0x444C4454, 512, 1, 0, 0x100000, need)
+    assert step(W=ctypes.byref(filled)) == P.DL_OK                              # d == 0: nothing to launch
+    assert step(W=ctypes.byref(filled), n=256) == P.DL_ETOPO and "512 nodes" in P.last_error()
+    assert P.raw.dmsgd_step_dev(None, None, None, 512, 0, 0, ctypes.byref(filled), 0.1, 1.5, 0, None) == P.DL_EINVAL
+    assert P.raw.dsgd_step_dev(None, None, 512, 0, 0, ctypes.byref(filled), 0.1, -1, None) == P.DL_EINVAL
+
+
 def test_calibration_stream_argument_validation():
     fake = ctypes.c_void_p(0x10000)
     cols = ctypes.c_int64(-1)
