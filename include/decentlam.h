@@ -346,6 +346,34 @@ int da_dmsgd_step(float* x, float* m, const float* g,
                   float gamma, float beta, int64_t k, void* stream);
 
 /*
+ * awc_dmsgd_step_ex, da_dmsgd_step_ex, awc_dmsgd_step_multi_ex, da_dmsgd_step_multi_ex -- the two sibling
+ * methods in the general forms: layout (row-major or blocked) and gradient format (fp32, bf16, fp16) from a
+ * dl_layout as decentlam_step_ex, tensor table and per-tensor sums of squares of g, the new m and the new x as
+ * decentlam_step_multi_ex (for da_dmsgd the new m is the averaged one).  Arguments, conventions and errors as
+ * those calls.
+ */
+int awc_dmsgd_step_ex(float* x, float* m, const void* g,
+                      int32_t n, int64_t d, const dl_layout* layout,
+                      const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                      float gamma, float beta, int64_t k, void* stream);
+int da_dmsgd_step_ex(float* x, float* m, const void* g,
+                     int32_t n, int64_t d, const dl_layout* layout,
+                     const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                     float gamma, float beta, int64_t k, void* stream);
+int awc_dmsgd_step_multi_ex(float* x, float* m, const void* g,
+                            int32_t n, const dl_layout* layout,
+                            int32_t num_tensors, const int64_t* offsets,
+                            double* norms, void* workspace, size_t workspace_bytes,
+                            const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                            float gamma, float beta, int64_t k, void* stream);
+int da_dmsgd_step_multi_ex(float* x, float* m, const void* g,
+                           int32_t n, const dl_layout* layout,
+                           int32_t num_tensors, const int64_t* offsets,
+                           double* norms, void* workspace, size_t workspace_bytes,
+                           const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                           float gamma, float beta, int64_t k, void* stream);
+
+/*
  * decentlam_step_g16, dmsgd_step_g16 -- Algorithm 2 / Algorithm 1 with the gradients held in a
  * 16-bit format, as they come out of a mixed-precision backward pass (the paper trains in mixed
  * precision, Sec. "Experiments", implementation details); x and m stay fp32.  Each g value is

@@ -23,6 +23,7 @@ _BINDING_NAMES = (
     "decentlam_step_packed", "dmsgd_step_packed", "dsgd_step_packed", "PreparedCall", "prepare_step",
     "prepare_local_grad_lsq", "topology_device_bytes", "topology_pack_device", "DeviceTopology", "DeviceTopologyStruct",
     "decentlam_step_dev", "dmsgd_step_dev", "dsgd_step_dev", "DL_MAX_NODES_DEVICE",
+    "awc_dmsgd_step_ex", "da_dmsgd_step_ex", "awc_dmsgd_step_multi_ex", "da_dmsgd_step_multi_ex",
 )
 __all__ = list(_BINDING_NAMES) + ["raw"]
 

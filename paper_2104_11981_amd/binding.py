@@ -39,6 +39,7 @@ EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decent
            "local_grad_lsq_static", "dl_calibration_stream", "topology_pack_bytes", "topology_pack",
            "decentlam_step_packed", "dmsgd_step_packed", "dsgd_step_packed", "topology_device_bytes",
            "topology_pack_device", "decentlam_step_dev", "dmsgd_step_dev", "dsgd_step_dev",
+           "awc_dmsgd_step_ex", "da_dmsgd_step_ex", "awc_dmsgd_step_multi_ex", "da_dmsgd_step_multi_ex",
            "local_grad_lsq_workspace", "decentlam_stats", "decentlam_stats_workspace", "dl_last_error")
 
 
@@ -95,11 +96,11 @@ def _load() -> ctypes.CDLL:
                                        i32p, i32p, f32p, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
                                        ctypes.c_int64, vp]
     layp = ctypes.POINTER(Layout)
-    for name in ("decentlam_step_ex", "dmsgd_step_ex"):
+    for name in ("decentlam_step_ex", "dmsgd_step_ex", "awc_dmsgd_step_ex", "da_dmsgd_step_ex"):
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = [vp, vp, vp, ctypes.c_int32, ctypes.c_int64, layp, i32p, i32p, f32p,
                                        ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_int64, vp]
-    for name in ("decentlam_step_multi_ex", "dmsgd_step_multi_ex"):
+    for name in ("decentlam_step_multi_ex", "dmsgd_step_multi_ex", "awc_dmsgd_step_multi_ex", "da_dmsgd_step_multi_ex"):
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = [vp, vp, vp, ctypes.c_int32, layp, ctypes.c_int32,
                                        ctypes.POINTER(ctypes.c_int64), vp, vp, ctypes.c_size_t, i32p, i32p, f32p,
@@ -389,6 +390,16 @@ def dmsgd_step_ex(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0
     _step_ex(_lib.dmsgd_step_ex, x, m, g, d, topo, gamma, beta, k, stream)
 
 
+def awc_dmsgd_step_ex(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, d=None, stream=None):
+    """General AWC-DmSGD step, see decentlam_step_ex."""
+    _step_ex(_lib.awc_dmsgd_step_ex, x, m, g, d, topo, gamma, beta, k, stream)
+
+
+def da_dmsgd_step_ex(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, d=None, stream=None):
+    """General DA-DmSGD step, see decentlam_step_ex."""
+    _step_ex(_lib.da_dmsgd_step_ex, x, m, g, d, topo, gamma, beta, k, stream)
+
+
 def decentlam_step_xprev_ex(x, x_prev, g, topo: Topology, gamma: float, beta: float, k: int = 0,
                             gamma_prev: float | None = None, d=None, stream=None):
     """General momentum-free DecentLaM step (x_prev is overwritten with x^{k+1}), see decentlam_step_ex."""
@@ -628,6 +639,18 @@ def prepare_local_grad_lsq(A, y, x, g, loss=None, scale: float = 1.0, workspace=
             ctypes.c_int64(d), ctypes.c_int64(ldA), ctypes.c_int64(ld), ctypes.c_float(scale),
             vp(workspace.data_ptr()), ctypes.c_size_t(workspace.numel() * workspace.element_size()))
     return PreparedCall(_lib.local_grad_lsq, head, False, stream, (A, y, x, g, loss, workspace))
+
+
+def awc_dmsgd_step_multi_ex(x, m, g, offsets, topo: Topology, gamma: float, beta: float, k: int = 0,
+                            norms=None, workspace=None, stream=None):
+    """General multi-tensor AWC-DmSGD step, see decentlam_step_multi_ex."""
+    _step_multi_ex(_lib.awc_dmsgd_step_multi_ex, x, m, g, offsets, topo, gamma, beta, k, norms, workspace, stream)
+
+
+def da_dmsgd_step_multi_ex(x, m, g, offsets, topo: Topology, gamma: float, beta: float, k: int = 0,
+                           norms=None, workspace=None, stream=None):
+    """General multi-tensor DA-DmSGD step, see decentlam_step_multi_ex."""
+    _step_multi_ex(_lib.da_dmsgd_step_multi_ex, x, m, g, offsets, topo, gamma, beta, k, norms, workspace, stream)
 
 
 def awc_dmsgd_step(x, m, g, topo: Topology, gamma: float, beta: float, k: int = 0, stream=None):

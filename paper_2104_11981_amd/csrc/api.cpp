@@ -649,6 +649,20 @@ int dmsgd_step_ex(float* x, float* m, const void* g, int32_t n, int64_t d, const
                         0.0f, beta, k, stream);
 }
 
+int awc_dmsgd_step_ex(float* x, float* m, const void* g, int32_t n, int64_t d, const dl_layout* layout,
+                      const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                      float gamma, float beta, int64_t k, void* stream) {
+    return dl::ex_entry("awc_dmsgd_step_ex", dl::ALGO_AWC_DMSGD, x, m, g, n, d, layout, row_ptr, col_idx, w, period, gamma,
+                        0.0f, beta, k, stream);
+}
+
+int da_dmsgd_step_ex(float* x, float* m, const void* g, int32_t n, int64_t d, const dl_layout* layout,
+                     const int32_t* row_ptr, const int32_t* col_idx, const float* w, int32_t period,
+                     float gamma, float beta, int64_t k, void* stream) {
+    return dl::ex_entry("da_dmsgd_step_ex", dl::ALGO_DA_DMSGD, x, m, g, n, d, layout, row_ptr, col_idx, w, period, gamma,
+                        0.0f, beta, k, stream);
+}
+
 int decentlam_step_xprev_ex(const float* x, float* x_prev, const void* g, int32_t n, int64_t d,
                             const dl_layout* layout, const int32_t* row_ptr, const int32_t* col_idx,
                             const float* w, int32_t period, float gamma, float gamma_prev, float beta, int64_t k,
@@ -702,6 +716,22 @@ int dmsgd_step_multi_ex(float* x, float* m, const void* g, int32_t n, const dl_l
                         size_t workspace_bytes, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
                         int32_t period, float gamma, float beta, int64_t k, void* stream) {
     return dl::multi_ex_entry("dmsgd_step_multi_ex", dl::ALGO_DMSGD, x, m, g, n, layout, num_tensors, offsets, norms,
+                              workspace, workspace_bytes, row_ptr, col_idx, w, period, gamma, beta, k, stream);
+}
+
+int awc_dmsgd_step_multi_ex(float* x, float* m, const void* g, int32_t n, const dl_layout* layout,
+                            int32_t num_tensors, const int64_t* offsets, double* norms, void* workspace,
+                            size_t workspace_bytes, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
+                            int32_t period, float gamma, float beta, int64_t k, void* stream) {
+    return dl::multi_ex_entry("awc_dmsgd_step_multi_ex", dl::ALGO_AWC_DMSGD, x, m, g, n, layout, num_tensors, offsets, norms,
+                              workspace, workspace_bytes, row_ptr, col_idx, w, period, gamma, beta, k, stream);
+}
+
+int da_dmsgd_step_multi_ex(float* x, float* m, const void* g, int32_t n, const dl_layout* layout,
+                           int32_t num_tensors, const int64_t* offsets, double* norms, void* workspace,
+                           size_t workspace_bytes, const int32_t* row_ptr, const int32_t* col_idx, const float* w,
+                           int32_t period, float gamma, float beta, int64_t k, void* stream) {
+    return dl::multi_ex_entry("da_dmsgd_step_multi_ex", dl::ALGO_DA_DMSGD, x, m, g, n, layout, num_tensors, offsets, norms,
                               workspace, workspace_bytes, row_ptr, col_idx, w, period, gamma, beta, k, stream);
 }
 

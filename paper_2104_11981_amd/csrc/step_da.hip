@@ -1,0 +1,14 @@
+// Instantiations of the fused step kernel (step_impl.hpp) for: ALGO_DA_DMSGD.
+#define DL_STEP_KERNEL_IMPL
+#include "step_impl.hpp"
+
+namespace dl {
+namespace step {
+
+template <>
+int launch_method<ALGO_DA_DMSGD>(int vec, int format, bool norms, const StepCall& s) {
+    return launch_extras<ALGO_DA_DMSGD>(vec, format, norms, s);
+}
+
+}  // namespace step
+}  // namespace dl

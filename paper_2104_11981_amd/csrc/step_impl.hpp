@@ -556,6 +556,10 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
                     const double m_new = beta * static_cast<double>(mr[r][v]) + static_cast<double>(gr[r][v]);
                     mo[v] = static_cast<float>(m_new);
                     xo[v] = static_cast<float>(z[v] - gamma * m_new);
+                    if constexpr (NORMS) {
+                        const double mv = static_cast<double>(mo[v]);
+                        sq_m = __builtin_fma(mv, mv, sq_m);
+                    }
                 }
                 if (live) store_vec<VEC>(m + at, mo);
             } else {   // DSGD, DmSGD; DA-DmSGD: x is done, its momentum follows below
@@ -647,6 +651,19 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) mo[v] = static_cast<float>(zm[v]);
                 if (live) store_vec<VEC>(m + ((static_cast<int64_t>(i) * ld + tile_col) + lane_col), mo);
+                if constexpr (NORMS) {   // the record's second slot, left at zero by the first gather: the sum of the new m
+                    double sq = 0.0;
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) sq = __builtin_fma(static_cast<double>(mo[v]), static_cast<double>(mo[v]), sq);
+                    if (!live) sq = 0.0;
+                    const double sm = H == 2 ? half_sum(sq) : wave_sum(sq);
+                    int64_t record = blockIdx.x;
+                    if constexpr (H == 2) {
+                        record = batch.tiles ? 2 * static_cast<int64_t>(blockIdx.x) : tile_col / 128;
+                        if (lane >= 32) record += lane_col >= kSplitDistance ? kSplitDistance / 128 : 1;
+                    }
+                    if ((H == 2 ? lane & 31 : lane) == 0) na.partial[(i * na.capacity + na.tile0 + record) * 3 + 1] = sm;
+                }
             }
         }
     }
@@ -735,17 +752,17 @@ int launch_cols(int vec, const StepCall& s) {
     }
 }
 
-// 16-bit gradients exist for DecentLaM (both forms) and DmSGD, per-tensor sums for the (x, m) forms.
+// 16-bit gradients exist for every method but DSGD, per-tensor sums for the methods that keep (x, m).
 template <int ALGO>
 int launch_extras(int vec, int format, bool norms, const StepCall& s) {
-    if constexpr (ALGO == ALGO_DECENTLAM || ALGO == ALGO_DMSGD) {
+    if constexpr (ALGO == ALGO_DECENTLAM || ALGO == ALGO_DMSGD || ALGO == ALGO_AWC_DMSGD || ALGO == ALGO_DA_DMSGD) {
         if (norms) {
             if (format == DL_GRAD_BF16) return launch_cols<ALGO, DL_GRAD_BF16, true>(vec, s);
             if (format == DL_GRAD_F16) return launch_cols<ALGO, DL_GRAD_F16, true>(vec, s);
             return launch_cols<ALGO, DL_GRAD_F32, true>(vec, s);
         }
     }
-    if constexpr (ALGO == ALGO_DECENTLAM || ALGO == ALGO_DMSGD || ALGO == ALGO_DECENTLAM_XPREV) {
+    if constexpr (ALGO != ALGO_DSGD) {
         if (!norms) {
             if (format == DL_GRAD_BF16) return launch_cols<ALGO, DL_GRAD_BF16, false>(vec, s);
             if (format == DL_GRAD_F16) return launch_cols<ALGO, DL_GRAD_F16, false>(vec, s);

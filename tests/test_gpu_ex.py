@@ -1,6 +1,6 @@
 """GPU parity of the general step calls (`*_step_ex`): every combination of layout (row-major,
-blocked) and gradient format (fp32, bf16, fp16) for DecentLaM, DmSGD and the momentum-free DecentLaM,
-against the oracle; and bit for bit against the special-case calls where one exists."""
+blocked) and gradient format (fp32, bf16, fp16) for DecentLaM, DmSGD, the momentum-free DecentLaM,
+AWC-DmSGD and DA-DmSGD, against the oracle; and bit for bit against the special-case calls where one exists."""
 import numpy as np
 import pytest
 
@@ -36,7 +36,7 @@ CASES = [
 
 
 @pytest.mark.parametrize("fmt", ["f32", "bf16", "f16"])
-@pytest.mark.parametrize("algo", ["decentlam", "dmsgd", "decentlam_xprev"])
+@pytest.mark.parametrize("algo", ["decentlam", "dmsgd", "decentlam_xprev", "awc_dmsgd", "da_dmsgd"])
 @pytest.mark.parametrize("kind,n,d,bw,steps", CASES)
 def test_general_step_matches_oracle(P, oracle, fmt, algo, kind, n, d, bw, steps):
     gamma, beta = float(np.float32(0.05)), float(np.float32(0.9))
@@ -198,7 +198,7 @@ MULTI_EX_CASES = [
 
 
 @pytest.mark.parametrize("fmt", ["f32", "bf16"])
-@pytest.mark.parametrize("algo", ["decentlam", "dmsgd"])
+@pytest.mark.parametrize("algo", ["decentlam", "dmsgd", "awc_dmsgd", "da_dmsgd"])
 @pytest.mark.parametrize("n,bw,sizes", MULTI_EX_CASES)
 def test_general_multi_tensor_call_matches_oracle(P, oracle, fmt, algo, n, bw, sizes):
     gamma, beta = float(np.float32(0.05)), float(np.float32(0.9))
