@@ -142,6 +142,25 @@ def test_chained_tile_kernel_fits_two_workgroups_per_cu(tmp_path):
         assert len(re.findall(r"global_load_dwordx4", body)) >= 9     # three before the loop, six inside
 
 
+def test_two_pass_kernels_keep_every_input_in_registers(tmp_path):
+    """k_step_tall holds all twelve values per row of up to eight rows per thread (96 registers) across two LDS passes;
+    a workgroup of 1024 threads has 128 registers per lane.  A spill would wait for a load the moment it is issued."""
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not installed")
+    from paper_2104_11981_amd import build
+
+    out = tmp_path / "step_tall.s"
+    flags = [f for f in build.FLAGS if f != "-fPIC"]
+    subprocess.run([HIPCC] + flags + ["-S", "--cuda-device-only", os.path.join(build.CSRC, "step_tall.hip"), "-o", str(out)],
+                   check=True, capture_output=True)
+    text = out.read_text()
+    assert len(re.findall(r"^\s*\.amdhsa_kernel\s+\S*k_step_tall", text, re.M)) == 20   # five methods x four shapes
+    assert not re.search(r"scratch_(load|store)", text)
+    counts = [int(v) for v in re.findall(r"\.vgpr_count:\s+(\d+)", text)]
+    spills = [int(v) for v in re.findall(r"\.vgpr_spill_count:\s+(\d+)", text)]
+    assert len(counts) == 20 and max(counts) <= 128 and not any(spills)
+
+
 SPLIT_CHECK = r"""
 #include <cstdio>
 #include <vector>

@@ -123,6 +123,29 @@ def test_rows_alternating_between_boundaries_and_midpoints(P, oracle, algo, kind
     test_large_row_major_launch_matches_oracle(P, oracle, algo, kind, n, d, pad, skew)
 
 
+# 65-128 nodes with rows on 64 KiB boundaries: the whole units of a large launch go to the kernel that uses its LDS
+# tile twice per tile of 256 columns (columns 0-1 of every lane, then 2-3); what precedes the first boundary of the
+# written array and what follows the last whole unit are launches of the ordinary kernel.  A result of the first pass
+# lost while it waits in registers, a second pass that reads the first pass's tile, or a seam between the launches
+# fails the comparison, which covers every element.
+ALL_TALL = ("decentlam", "dmsgd", "dsgd", "xprev", "awc_dmsgd")
+TALL_CASES = [
+    # kind, n, d, ld - d, skew of x, m, g, methods
+    (0, 128, (1 << 20) + UNIT + 300, UNIT - 300, (0, 0, 0), ALL_TALL),    # eight rows per thread; 300 columns after the units
+    (1, 96, (1 << 20) + 2 * UNIT, 0, (4, 4, 4), ALL_TALL),                # six rows per thread; 16380 columns before the units
+    (3, 72, (1 << 20) + UNIT + 12, UNIT - 12, (0, 8192, 4096), ("decentlam", "xprev")),   # m, g placed differently; five rows per thread, 72-79 absent
+    (4, 100, (1 << 20) + 200, UNIT - 200, (3, 3, 3), ("decentlam", "dmsgd")),   # irregular degrees; seven rows per thread; off 16-byte alignment alike
+    (1, 65, (1 << 20) + 4, UNIT - 4, (0, 0, 0), ("dmsgd", "awc_dmsgd")),   # the smallest node count served
+    (0, 128, (1 << 20) + 8, UNIT - 8, (1, 2, 3), ("decentlam",)),         # misaligned differently: not served, narrow lanes
+]
+
+
+@pytest.mark.parametrize("kind,n,d,pad,skew,algo", [c[:5] + (a,) for c in TALL_CASES for a in c[5]])
+def test_tall_tiles_in_two_passes(P, oracle, algo, kind, n, d, pad, skew):
+    assert (d + pad) % UNIT == 0 and 64 < n <= 128
+    test_large_row_major_launch_matches_oracle(P, oracle, algo, kind, n, d, pad, skew)
+
+
 @pytest.mark.parametrize("n,d,pad", [(4, (1 << 20) + 1284, 4), (8, (1 << 20) + 3 * UNIT + 8, 8), (4, (1 << 20) + 2 * UNIT, 0)])
 def test_large_launch_with_per_tensor_sums(P, oracle, n, d, pad):
     """The multi-tensor call over one large launch in either order: state and sums against the oracle."""
