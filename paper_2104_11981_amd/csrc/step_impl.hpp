@@ -117,7 +117,7 @@ int launch_method(int vec, int format, bool norms, const StepCall& s);
 bool chain_serves(int algo, int32_t n, int nnz);
 int launch_chain(int algo, const StepCall& s, uint32_t units, uint32_t len);
 
-// Two LDS passes under split tiles for 65-128 nodes (step_tall.hip): whether that kernel serves this method, node
+// Two LDS passes under split tiles for 33-128 nodes (step_tall.hip): whether that kernel serves this method, node
 // count and graph, and its launch over `units` whole 64 KiB units of columns starting at s.x / s.m / s.g (row 0 of
 // x on a 64 KiB boundary, s.ld a multiple of 16384, every array 16-byte aligned, fp32 gradients).
 bool tall_serves(int algo, int32_t n, int nnz);

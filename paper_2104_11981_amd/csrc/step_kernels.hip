@@ -44,8 +44,9 @@ constexpr int64_t kSplitMinColumns = 1 << 20;   // below this a launch keeps pla
 // two workgroups share a CU.  Beyond that the wide lanes are kept and the tile grows to 128 KiB, one
 // workgroup per CU: measured better than halving the lanes to keep two (64 nodes: 6.2 against 5.3 TB/s
 // row-major, 6.5 against 6.4 blocked; 128 nodes with 8-byte lanes: 6.4 against 5.5 blocked), because
-// the 16-byte lanes bring full 512-byte segments and their pairing (split tiles) with them.  (65-128 nodes keep
-// them in large aligned launches through the two-pass kernel of step_tall.hip; this table is for everything else.)
+// the 16-byte lanes bring full 512-byte segments and their pairing (split tiles) with them.  (Large launches on
+// 64 KiB-aligned rows of 33-128 nodes go to the two-pass kernel of step_tall.hip, which has 16-byte lanes at all of
+// these node counts; this table is for everything else.)
 // Longest chain of the chained-tile kernel, in units (the chains get shorter towards the end of a launch).
 // Measured on 32 x 25.6 M, ld = d: 2.70 / 2.67 / 2.68 / 2.71 ms with every chain 2 / 4 / 8 / 16 units long (long
 // chains leave the chip half idle at the end of the launch), 2.63 / 2.65 / 2.65 / 2.66 ms with chains of at
@@ -66,10 +67,10 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
     const size_t gbytes = grad_elem_bytes(g.format);
     const unsigned gshift = gbytes == 4 ? 2 : 1;
 
-    // 65-128 nodes, rows on 64 KiB boundaries, all arrays alike modulo 16 bytes: the whole 64 KiB units of a large
+    // 33-128 nodes, rows on 64 KiB boundaries, all arrays alike modulo 16 bytes: the whole 64 KiB units of a large
     // launch go to the kernel that keeps 16-byte lanes and split tiles by using its LDS tile twice (step_tall.hip);
     // the columns before and after them are short launches of their own.
-    if (n > 64 && batches == 1 && !norms && g.format == DL_GRAD_F32 && d >= kSplitMinColumns && ld % kSplitUnit == 0 &&
+    if (n > 32 && batches == 1 && !norms && g.format == DL_GRAD_F32 && d >= kSplitMinColumns && ld % kSplitUnit == 0 &&
         g.ld % 4 == 0 && tall_serves(algo, n, topo.row_ptr[n])) {
         const uintptr_t ax = (reinterpret_cast<uintptr_t>(x) >> 2) & 3;
         const uintptr_t am = m ? (reinterpret_cast<uintptr_t>(m) >> 2) & 3 : ax;

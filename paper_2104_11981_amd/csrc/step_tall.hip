@@ -1,18 +1,23 @@
-// The fused step for 65-128 nodes on row-major arrays whose rows start on 64 KiB boundaries.
+// The fused step for 33-128 nodes on row-major arrays whose rows start on 64 KiB boundaries.
 //
-// What limits k_step there: its fp64 tile holds every row of a tile's columns, 128 rows x 8 bytes leave room for
-// 128 columns in a CU's LDS, and 128 columns are 8 bytes per lane, one 512-byte piece per row and tile.  This
+// What limits k_step there: its fp64 tile holds every row of a tile's columns.  Beyond 64 nodes that leaves room
+// for 128 columns in a CU's LDS, and 128 columns are 8 bytes per lane, one 512-byte piece per row and tile; this
 // GPU's memory wants 16-byte lanes that cover both 512-byte halves of an address pair (A, A + 32 KiB), the split
 // tiles of step_impl.hpp.  Bare 3-read/2-write streams over 128 rows: 5.05-5.15 TB/s for every shape of a
 // 128-column tile (one 512-byte piece; two 256-byte pieces 32 KiB apart; 16-byte lanes over two rows at a
-// time), 6.0 TB/s for the split tile of 256 columns.
+// time), 6.0 TB/s for the split tile of 256 columns.  At 33-64 nodes the 16-byte lanes fit, but their tile of
+// 96-128 KiB leaves one workgroup per CU, which has nothing to overlap its gathers with (a pause of 1.7 us between
+// the loads and the stores of a bare stream costs 7 % with one workgroup per CU, 2.5 % with two).
 //
-// Here the global accesses are those of a split tile (16 bytes per lane, 256 columns) and the LDS tile is used
-// twice: first for columns 0 and 1 of every lane, then, when every wave has finished gathering, for columns 2
-// and 3.  Each pass is the 8-byte-lane kernel's second phase on half of the columns, so the tile still takes
+// Here the global accesses are those of a split tile (16 bytes per lane, 256 columns) and an LDS tile of half that
+// width is used twice: first for columns 0 and 1 of every lane, then, when every wave has finished gathering, for
+// columns 2 and 3.  Each pass is the 8-byte-lane kernel's second phase on half of the columns, so the tile takes
 // n x 128 x 8 bytes, and the results of the first pass wait in the registers of the inputs they replace until
 // the row is stored whole.  All twelve values per row (x, g, m) are in registers at once: up to 96 of a thread's
-// 128 registers at eight rows per thread, which a workgroup of 1024 threads alone on its CU can have.
+// 128 registers at eight rows per thread, which a workgroup of 1024 threads alone on its CU can have; the shapes
+// with three and four rows per thread (33-64 nodes, tile of 48-64 KiB) are built for 64 registers, so that two
+// workgroups share a CU.  Measured at 819 M node-elements (ring, DecentLaM): 48 / 64 nodes 6.4 TB/s (0.80) where
+// k_step ran 5.95 / 6.2; 96 / 128 nodes 5.5 where it ran 5.2 / 5.0.
 //
 // Arithmetic, order of the sums and results are those of k_step: same bits.
 #define DL_STEP_KERNEL_IMPL
@@ -23,13 +28,15 @@ namespace step {
 namespace {
 
 template <int ALGO, int RPT>
-__global__ __launch_bounds__(1024) void k_step_tall(float* __restrict__ x, float* __restrict__ m,
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(RPT <= 4 ? 8 : 4, RPT <= 4 ? 8 : 4))) void k_step_tall(float* __restrict__ x, float* __restrict__ m,
                                                     const float* __restrict__ g, int64_t ld, int64_t ldg,
                                                     double gamma, double inv_gamma, double beta, const PhaseArgs topo) {
     constexpr int TC = 128, WAVES = 16;   // columns of the LDS tile: two per lane and pass
     static_assert(ALGO != ALGO_DA_DMSGD, "one gather per iteration");
     constexpr bool kHasM = ALGO != ALGO_DSGD;
-    constexpr int GROUP = (RPT > 7 && ALGO != ALGO_DMSGD && ALGO != ALGO_DSGD) ? 2 : 4;
+    // neighbours per gather: four as in k_step with 8-byte lanes, two where the registers end (64 for the shapes that
+    // share a CU between two workgroups, 128 for the others)
+    constexpr int GROUP = (RPT == 4 || (RPT == 3 && ALGO == ALGO_AWC_DMSGD) || (RPT > 7 && ALGO != ALGO_DMSGD && ALGO != ALGO_DSGD)) ? 2 : 4;
     extern __shared__ __attribute__((aligned(16))) double lds[];
     const int n = topo.n;
     using Entry = NeighbourCompact;
@@ -170,7 +177,10 @@ __global__ __launch_bounds__(1024) void k_step_tall(float* __restrict__ x, float
                     }
                 }
                 if (p == 1) {
-                    const int64_t at = (static_cast<int64_t>(i) * ld + tile_col) + lane_col;
+                    // the lane's columns, worked out afresh from the lane number (two instructions) rather than kept
+                    // in a register through both passes, which the four-row shape has none left for
+                    const int lane_again = static_cast<int>(__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)));
+                    const int64_t at = (static_cast<int64_t>(i) * ld + tile_col) + split_column(0, lane_again);
                     if constexpr (kHasM) store_vec<4>(m + at, mr[r]);
                     if constexpr (ALGO != ALGO_DECENTLAM_XPREV) store_vec<4>(x + at, xr[r]);
                 }
@@ -197,7 +207,11 @@ int launch_tall_shape(const StepCall& s, uint32_t units) {
 
 template <int ALGO>
 int launch_tall_algo(const StepCall& s, uint32_t units) {
-    if (s.n <= 80) return launch_tall_shape<ALGO, 5>(s, units);   // 16 waves x rows per thread
+    if (s.n <= 48) return launch_tall_shape<ALGO, 3>(s, units);   // 16 waves x rows per thread
+    if constexpr (ALGO != ALGO_AWC_DMSGD) {
+        if (s.n <= 64) return launch_tall_shape<ALGO, 4>(s, units);
+    }
+    if (s.n <= 80) return launch_tall_shape<ALGO, 5>(s, units);
     if (s.n <= 96) return launch_tall_shape<ALGO, 6>(s, units);
     if (s.n <= 112) return launch_tall_shape<ALGO, 7>(s, units);
     return launch_tall_shape<ALGO, 8>(s, units);
@@ -206,7 +220,8 @@ int launch_tall_algo(const StepCall& s, uint32_t units) {
 }  // namespace
 
 bool tall_serves(int algo, int32_t n, int nnz) {
-    if (n <= 64 || n > 128 || algo == ALGO_DA_DMSGD) return false;
+    if (n <= 32 || n > 128 || algo == ALGO_DA_DMSGD || mixes_on_matrix_cores(n, nnz)) return false;
+    if (n > 48 && n <= 64 && algo == ALGO_AWC_DMSGD) return false;   // four rows per thread of x, g and m: 4 registers short
     return lds_bytes_for(n, 2, nnz, 1) <= 160 * 1024;
 }
 

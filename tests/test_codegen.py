@@ -144,7 +144,8 @@ def test_chained_tile_kernel_fits_two_workgroups_per_cu(tmp_path):
 
 def test_two_pass_kernels_keep_every_input_in_registers(tmp_path):
     """k_step_tall holds all twelve values per row of up to eight rows per thread (96 registers) across two LDS passes;
-    a workgroup of 1024 threads has 128 registers per lane.  A spill would wait for a load the moment it is issued."""
+    a workgroup of 1024 threads has 128 registers per lane, and the shapes with three and four rows per thread are
+    built for 64, so that two workgroups share a CU.  A spill would wait for a load the moment it is issued."""
     if not os.path.exists(HIPCC):
         pytest.skip("hipcc not installed")
     from paper_2104_11981_amd import build
@@ -154,11 +155,13 @@ def test_two_pass_kernels_keep_every_input_in_registers(tmp_path):
     subprocess.run([HIPCC] + flags + ["-S", "--cuda-device-only", os.path.join(build.CSRC, "step_tall.hip"), "-o", str(out)],
                    check=True, capture_output=True)
     text = out.read_text()
-    assert len(re.findall(r"^\s*\.amdhsa_kernel\s+\S*k_step_tall", text, re.M)) == 20   # five methods x four shapes
+    kernels = len(re.findall(r"^\s*\.amdhsa_kernel\s+\S*k_step_tall", text, re.M))
+    assert kernels >= 29   # five methods x six shapes, less AWC-DmSGD with four rows
     assert not re.search(r"scratch_(load|store)", text)
     counts = [int(v) for v in re.findall(r"\.vgpr_count:\s+(\d+)", text)]
     spills = [int(v) for v in re.findall(r"\.vgpr_spill_count:\s+(\d+)", text)]
-    assert len(counts) == 20 and max(counts) <= 128 and not any(spills)
+    assert len(counts) == kernels and max(counts) <= 128 and not any(spills)
+    assert sum(c <= 64 for c in counts) >= 9   # the three- and four-row shapes
 
 
 SPLIT_CHECK = r"""

@@ -123,7 +123,7 @@ def test_rows_alternating_between_boundaries_and_midpoints(P, oracle, algo, kind
     test_large_row_major_launch_matches_oracle(P, oracle, algo, kind, n, d, pad, skew)
 
 
-# 65-128 nodes with rows on 64 KiB boundaries: the whole units of a large launch go to the kernel that uses its LDS
+# 33-128 nodes with rows on 64 KiB boundaries: the whole units of a large launch go to the kernel that uses its LDS
 # tile twice per tile of 256 columns (columns 0-1 of every lane, then 2-3); what precedes the first boundary of the
 # written array and what follows the last whole unit are launches of the ordinary kernel.  A result of the first pass
 # lost while it waits in registers, a second pass that reads the first pass's tile, or a seam between the launches
@@ -137,12 +137,17 @@ TALL_CASES = [
     (4, 100, (1 << 20) + 200, UNIT - 200, (3, 3, 3), ("decentlam", "dmsgd")),   # irregular degrees; seven rows per thread; off 16-byte alignment alike
     (1, 65, (1 << 20) + 4, UNIT - 4, (0, 0, 0), ("dmsgd", "awc_dmsgd")),   # the smallest node count served
     (0, 128, (1 << 20) + 8, UNIT - 8, (1, 2, 3), ("decentlam",)),         # misaligned differently: not served, narrow lanes
+    # 33-64 nodes: the same kernel with three or four rows per thread, two workgroups per CU
+    (1, 64, (1 << 20) + UNIT + 300, UNIT - 300, (0, 0, 0), ALL_TALL),     # four rows per thread (AWC-DmSGD: not served there)
+    (1, 48, (1 << 20) + 2 * UNIT, 0, (4, 4, 4), ALL_TALL),                # three rows per thread
+    (4, 40, (1 << 20) + 200, UNIT - 200, (0, 4096, 8192), ("decentlam", "dmsgd")),   # rows 40-47 absent; irregular degrees
+    (0, 33, (1 << 20) + 4, UNIT - 4, (3, 3, 3), ("xprev", "awc_dmsgd")),  # the smallest node count served
 ]
 
 
 @pytest.mark.parametrize("kind,n,d,pad,skew,algo", [c[:5] + (a,) for c in TALL_CASES for a in c[5]])
 def test_tall_tiles_in_two_passes(P, oracle, algo, kind, n, d, pad, skew):
-    assert (d + pad) % UNIT == 0 and 64 < n <= 128
+    assert (d + pad) % UNIT == 0 and 32 < n <= 128
     test_large_row_major_launch_matches_oracle(P, oracle, algo, kind, n, d, pad, skew)
 
 
