@@ -146,21 +146,48 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const float* __restrict_
     for (int v = 0; v < V; ++v) out[v] = acc[v];
 }
 
+// Sum of the `splits` partial gradients of one node for 64 consecutive columns per workgroup: wave w adds the
+// w-th quarter of the partials for its lane's column, eight loads in flight at a time, and wave 0 adds the four
+// quarters; every sum in a fixed order.  (One thread per column adding all partials one after the other was a
+// chain of dependent loads in a grid of d / 256 workgroups per node: 18 us of the 31 us that 8 nodes of
+// 1024 x 1024 took, more than the sweep over A itself.)
+constexpr int kFinishColumns = 64;
+__device__ __forceinline__ void finish_columns(const double* __restrict__ partial_i, float* __restrict__ g_i,
+                                               int64_t d, int splits, double scale, double (&quarter)[4][kFinishColumns]) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t c = static_cast<int64_t>(blockIdx.x) * kFinishColumns + lane;
+    const int per = (splits + 3) / 4;
+    const int s0 = w * per < splits ? w * per : splits, s1 = s0 + per < splits ? s0 + per : splits;
+    double acc = 0.0;
+    if (c < d) {
+        const double* p = partial_i + c;
+        int s = s0;
+        for (; s + 8 <= s1; s += 8) {
+            double v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = p[static_cast<int64_t>(s + k) * d];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc += v[k];
+        }
+        for (; s < s1; ++s) acc += p[static_cast<int64_t>(s) * d];
+    }
+    quarter[w][lane] = acc;
+    __syncthreads();
+    if (w == 0 && c < d) g_i[c] = static_cast<float>(scale * (((quarter[0][lane] + quarter[1][lane]) + quarter[2][lane]) + quarter[3][lane]));
+}
+
 __global__ __launch_bounds__(kThreads) void k_finish(const double* __restrict__ partial,
                                                       const double* __restrict__ res,
                                                       float* __restrict__ g, float* __restrict__ loss,
                                                       int b, int64_t d, int64_t ld, int splits,
                                                       double scale) {
     __shared__ double red[kThreads];
+    static_assert(kThreads == 4 * kFinishColumns, "four waves per workgroup");
     const int i = blockIdx.y;
-    const int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (c < d) {
-        const double* p = partial + static_cast<int64_t>(i) * splits * d + c;
-        double acc = 0.0;
-        for (int s = 0; s < splits; ++s) acc += p[static_cast<int64_t>(s) * d];
-        g[static_cast<int64_t>(i) * ld + c] = static_cast<float>(scale * acc);
-    }
+    finish_columns(partial + static_cast<int64_t>(i) * splits * d, g + static_cast<int64_t>(i) * ld, d, splits, scale,
+                   *reinterpret_cast<double (*)[4][kFinishColumns]>(red));
     if (loss != nullptr && blockIdx.x == 0) {  // whole workgroup takes this branch together
+        __syncthreads();   // the column sums are out of `red`
         const double* ri = res + static_cast<int64_t>(i) * b;
         double sq = 0.0;
         for (int r = threadIdx.x; r < b; r += kThreads) sq = __builtin_fma(ri[r], ri[r], sq);
@@ -321,18 +348,14 @@ __global__ __launch_bounds__(kThreads) void k_finish_fused(const double* __restr
                                                             const double* __restrict__ sq_partial,
                                                             float* __restrict__ g, float* __restrict__ loss,
                                                             int64_t d, int64_t ld, int splits, double scale) {
+    __shared__ double quarter[4][kFinishColumns];
     const int i = blockIdx.y;
-    const int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (c < d) {
-        const double* p = partial + static_cast<int64_t>(i) * splits * d + c;
-        double acc = 0.0;
-        for (int s = 0; s < splits; ++s) acc += p[static_cast<int64_t>(s) * d];
-        g[static_cast<int64_t>(i) * ld + c] = static_cast<float>(scale * acc);
-    }
-    if (loss != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
+    finish_columns(partial + static_cast<int64_t>(i) * splits * d, g + static_cast<int64_t>(i) * ld, d, splits, scale, quarter);
+    if (loss != nullptr && blockIdx.x == 0 && threadIdx.x < 64) {   // one wave: lane-strided, then the fixed-order wave sum
         double sq = 0.0;
-        for (int s = 0; s < splits; ++s) sq += sq_partial[static_cast<int64_t>(i) * splits + s];
-        loss[i] = static_cast<float>(0.5 * scale * sq);
+        for (int s = threadIdx.x; s < splits; s += 64) sq += sq_partial[static_cast<int64_t>(i) * splits + s];
+        sq = wave_sum(sq);
+        if (threadIdx.x == 0) loss[i] = static_cast<float>(0.5 * scale * sq);
     }
 }
 
@@ -487,7 +510,7 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
                 break;
         }
         if (int rc = check_hip(hipGetLastError(), "fused gradient kernel launch")) return rc;
-        const dim3 grid_ff(static_cast<unsigned>((d + kThreads - 1) / kThreads), static_cast<unsigned>(n));
+        const dim3 grid_ff(static_cast<unsigned>((d + kFinishColumns - 1) / kFinishColumns), static_cast<unsigned>(n));
         hipLaunchKernelGGL(k_finish_fused, grid_ff, block, 0, stream, fpartial, sq_partial, g, loss, d, ld, fs,
                            static_cast<double>(scale));
         return check_hip(hipGetLastError(), "finish kernel launch");
@@ -517,7 +540,7 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
         if (int rc = check_hip(hipGetLastError(), "transpose kernel launch")) return rc;
     }
 
-    const dim3 grid_f(static_cast<unsigned>(d > 0 ? (d + kThreads - 1) / kThreads : 1), static_cast<unsigned>(n));
+    const dim3 grid_f(static_cast<unsigned>(d > 0 ? (d + kFinishColumns - 1) / kFinishColumns : 1), static_cast<unsigned>(n));
     hipLaunchKernelGGL(k_finish, grid_f, block, 0, stream, partial, res, g, loss, bs, d, ld, splits,
                        static_cast<double>(scale));
     return check_hip(hipGetLastError(), "finish kernel launch");
