@@ -300,6 +300,9 @@ def bench_xprev(P, workloads, name, steps, warmup):
             "steps_per_s": round(1e3 / kern_ms, 1)}
 
 
+HEADLINE_ELEMENTS = 32 * 25_600_000
+
+
 def bench_shape(P, n, d, kind, steps, warmup):
     """decentlam_step on a synthetic n x d state with a built-in graph (values N(0,1), zero momentum)."""
     import torch
@@ -646,6 +649,10 @@ def main():
     ap.add_argument("--streams-only", action="store_true",
                     help="only the bare calibration streams (dl_calibration_stream) on the workload's shape, with "
                          "rows padded to 64 KiB boundaries and with ld = d: one JSON line (used for the profiles)")
+    ap.add_argument("--node-counts", default=None, metavar="N1,N2,...",
+                    help="only decentlam_step at these node counts on arrays of the headline size (819.2 M node-elements, "
+                         "rows on 64 KiB boundaries), ring and static exponential graph: one JSON line (used for the "
+                         "profiles)")
     ap.add_argument("--oracle-table", action="store_true",
                     help="CPU only: time the oracle on every workload at 1 thread and at all host cores")
     ap.add_argument("--oracle-table-child", action="store_true", help=argparse.SUPPRESS)
@@ -676,6 +683,14 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     torch.cuda.set_device(0)
 
+    if args.node_counts:
+        out = {}
+        for n in (int(v) for v in args.node_counts.split(",")):
+            for kind, name in ((P.DL_TOPO_RING, "ring"), (P.DL_TOPO_EXP_STATIC, "exp_static")):
+                out[f"n{n}_{name}"] = bench_shape(P, n, HEADLINE_ELEMENTS // n, kind, args.steps, args.warmup)
+        print(json.dumps({"what": "decentlam_step by node count, 819.2 M node-elements, rows on 64 KiB boundaries",
+                          "steps": args.steps, "warmup": args.warmup, **out}), flush=True)
+        return
     if args.streams_only:
         d0 = workloads.generate.dim(workloads.get(args.workload))
         print(json.dumps({"workload": args.workload, "steps": args.steps, "warmup": args.warmup,
@@ -812,6 +827,10 @@ def main():
         extras["decentlam_step_multi_norms_c4_ring16_ragged"] = bench_multi(P, workloads, "c4_ring16_ragged",
                                                                              args.steps, args.warmup)
         # the paper's own scale: 8 nodes (its servers), symmetric exponential graph, a ResNet-50-sized vector
+        # other node counts on arrays of the headline size (the kernel and its workgroup shape change with n)
+        extras["decentlam_step_by_node_count_exp_static"] = {
+            f"n{n}": bench_shape(P, n, HEADLINE_ELEMENTS // n, P.DL_TOPO_EXP_STATIC, args.steps, args.warmup)
+            for n in (16, 48, 64, 128)}
         extras["decentlam_step_8_nodes_sym_exp_25.6M"] = bench_shape(P, 8, 25_600_000, P.DL_TOPO_EXP_SYM,
                                                                     args.steps, args.warmup)
         extras["plain_device_copy_c3_array"] = bench_copy(P, workloads, "c3_exp32", args.steps, args.warmup)
