@@ -15,8 +15,8 @@
 // n x 128 x 8 bytes, and the results of the first pass wait in the registers of the inputs they replace until
 // the row is stored whole.  All twelve values per row (x, g, m) are in registers at once: up to 96 of a thread's
 // 128 registers at eight rows per thread, which a workgroup of 1024 threads alone on its CU can have; the shapes
-// with three and four rows per thread (33-64 nodes, tile of 48-64 KiB) are built for 64 registers, so that two
-// workgroups share a CU.  Measured at 819 M node-elements (ring, DecentLaM): 48 / 64 nodes 6.4 TB/s (0.80) where
+// with three and four rows per thread (33-64 nodes, 10 to 16 waves, tile of at most 64 KiB) are built for 64
+// registers, so that two or three workgroups share a CU.  Measured at 819 M node-elements (ring, DecentLaM): 48 / 64 nodes 6.4 TB/s (0.80) where
 // k_step ran 5.95 / 6.2; 96 / 128 nodes 5.5 where it ran 5.2 / 5.0.
 //
 // Arithmetic, order of the sums and results are those of k_step: same bits.
@@ -27,11 +27,11 @@ namespace dl {
 namespace step {
 namespace {
 
-template <int ALGO, int RPT>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(RPT <= 4 ? 8 : 4, RPT <= 4 ? 8 : 4))) void k_step_tall(float* __restrict__ x, float* __restrict__ m,
+template <int ALGO, int RPT, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(RPT <= 4 ? 8 : 4, RPT <= 4 ? 8 : 4))) void k_step_tall(float* __restrict__ x, float* __restrict__ m,
                                                     const float* __restrict__ g, int64_t ld, int64_t ldg,
                                                     double gamma, double inv_gamma, double beta, const PhaseArgs topo) {
-    constexpr int TC = 128, WAVES = 16;   // columns of the LDS tile: two per lane and pass
+    constexpr int TC = 128;   // columns of the LDS tile: two per lane and pass
     static_assert(ALGO != ALGO_DA_DMSGD, "one gather per iteration");
     constexpr bool kHasM = ALGO != ALGO_DSGD;
     // neighbours per gather: four as in k_step with 8-byte lanes, two where the registers end (64 for the shapes that
@@ -189,26 +189,33 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(RPT <= 4 ?
     }
 }
 
-template <int ALGO, int RPT>
+template <int ALGO, int RPT, int WAVES = 16>
 int launch_tall_shape(const StepCall& s, uint32_t units) {
     const size_t lds_bytes = lds_bytes_for(s.n, 2, s.topo->row_ptr[s.n], 1);
     if (lds_bytes > 160 * 1024) return set_error(DL_ETOPO, "step: the two-pass kernel's tile does not fit");
-    auto kernel = k_step_tall<ALGO, RPT>;
+    auto kernel = k_step_tall<ALGO, RPT, WAVES>;
     if (lds_bytes > 48 * 1024) {
         if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024),
                                "hipFuncSetAttribute(max dynamic LDS)"))
             return rc;
     }
-    hipLaunchKernelGGL(kernel, dim3(units * kSplitTilesPerUnit), dim3(1024), lds_bytes, s.stream, s.x, s.m,
+    hipLaunchKernelGGL(kernel, dim3(units * kSplitTilesPerUnit), dim3(64 * WAVES), lds_bytes, s.stream, s.x, s.m,
                        static_cast<const float*>(s.g), s.ld, s.ldg, s.gamma, 1.0 / s.gamma, s.beta, *s.topo);
     return check_hip(hipGetLastError(), "step kernel launch (two-pass tiles)");
 }
 
 template <int ALGO>
 int launch_tall_algo(const StepCall& s, uint32_t units) {
-    if (s.n <= 48) return launch_tall_shape<ALGO, 3>(s, units);   // 16 waves x rows per thread
+    // waves x rows per thread.  Up to 64 nodes a shape without empty row slots is worth 2-4 % (36 / 40 / 56 nodes:
+    // 6.5 / 6.45 / 6.3 TB/s with 12 x 3 / 10 x 4 / 14 x 4 against 6.2 / 6.25 / 6.2 with 16 x 3 / 16 x 3 / 16 x 4)
+    if (s.n <= 36) return launch_tall_shape<ALGO, 3, 12>(s, units);
     if constexpr (ALGO != ALGO_AWC_DMSGD) {
+        if (s.n <= 40) return launch_tall_shape<ALGO, 4, 10>(s, units);
+    }
+    if (s.n <= 48) return launch_tall_shape<ALGO, 3>(s, units);
+    if constexpr (ALGO != ALGO_AWC_DMSGD) {
+        if (s.n <= 56) return launch_tall_shape<ALGO, 4, 14>(s, units);
         if (s.n <= 64) return launch_tall_shape<ALGO, 4>(s, units);
     }
     if (s.n <= 80) return launch_tall_shape<ALGO, 5>(s, units);

@@ -140,8 +140,9 @@ TALL_CASES = [
     # 33-64 nodes: the same kernel with three or four rows per thread, two workgroups per CU
     (1, 64, (1 << 20) + UNIT + 300, UNIT - 300, (0, 0, 0), ALL_TALL),     # four rows per thread (AWC-DmSGD: not served there)
     (1, 48, (1 << 20) + 2 * UNIT, 0, (4, 4, 4), ALL_TALL),                # three rows per thread
-    (4, 40, (1 << 20) + 200, UNIT - 200, (0, 4096, 8192), ("decentlam", "dmsgd")),   # rows 40-47 absent; irregular degrees
-    (0, 33, (1 << 20) + 4, UNIT - 4, (3, 3, 3), ("xprev", "awc_dmsgd")),  # the smallest node count served
+    (4, 40, (1 << 20) + 200, UNIT - 200, (0, 4096, 8192), ("decentlam", "dmsgd", "awc_dmsgd")),   # 10 waves x 4 rows (AWC: 16 x 3); irregular degrees
+    (0, 33, (1 << 20) + 4, UNIT - 4, (3, 3, 3), ("xprev", "awc_dmsgd")),  # the smallest node count served: 12 waves x 3 rows, rows 33-35 absent
+    (2, 56, (1 << 20) + 2 * UNIT, 0, (0, 0, 0), ("decentlam", "dsgd")),   # 14 waves x 4 rows; one peer per iteration
 ]
 
 
