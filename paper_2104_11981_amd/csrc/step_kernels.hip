@@ -69,8 +69,11 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
 
     // 33-128 nodes, rows on 64 KiB boundaries, all arrays alike modulo 16 bytes: the whole 64 KiB units of a large
     // launch go to the kernel that keeps 16-byte lanes and split tiles by using its LDS tile twice (step_tall.hip);
-    // the columns before and after them are short launches of their own.
-    if (n > 32 && batches == 1 && !norms && g.format == DL_GRAD_F32 && d >= kSplitMinColumns && ld % kSplitUnit == 0 &&
+    // the columns before and after them are short launches of their own.  Up to 64 nodes that kernel's second
+    // workgroup per CU is worth more than the alignment: rows on any 512-byte boundary take it too (48 / 64 nodes,
+    // rows alternating between 64 KiB boundaries and their midpoints: 6.15 / 6.0 TB/s against 5.7 with k_step; rows
+    // on other 512-byte boundaries 6.1 / 5.8 against 5.7; at 96 and 128 nodes the comparison went either way).
+    if (n > 32 && batches == 1 && !norms && g.format == DL_GRAD_F32 && d >= kSplitMinColumns && ld % (n <= 64 ? kSplitSegment : kSplitUnit) == 0 &&
         g.ld % 4 == 0 && tall_serves(algo, n, topo.row_ptr[n])) {
         const uintptr_t ax = (reinterpret_cast<uintptr_t>(x) >> 2) & 3;
         const uintptr_t am = m ? (reinterpret_cast<uintptr_t>(m) >> 2) & 3 : ax;

@@ -152,6 +152,18 @@ def test_tall_tiles_in_two_passes(P, oracle, algo, kind, n, d, pad, skew):
     test_large_row_major_launch_matches_oracle(P, oracle, algo, kind, n, d, pad, skew)
 
 
+# Up to 64 nodes the same kernel also takes rows that start on other 512-byte boundaries (its column order is then
+# relative to row 0 of the written array; the other rows' pieces are 512 bytes at some other phase of their units).
+@pytest.mark.parametrize("kind,n,d,pad,skew,algo", [
+    (1, 48, (1 << 20) + 8192, 0, (0, 0, 0), "decentlam"),              # ld = d, rows alternate between boundaries and midpoints
+    (1, 64, (1 << 20) + 8192 + 77, 128 - 77, (4, 4, 4), "dmsgd"),      # rows 512 bytes further on each, 16380 columns first
+    (0, 36, (1 << 20) + 3 * 128, 0, (0, 128, 256), "xprev"),           # m, g placed differently
+])
+def test_tall_tiles_on_rows_off_the_64_kib_boundaries(P, oracle, algo, kind, n, d, pad, skew):
+    assert (d + pad) % 128 == 0 and (d + pad) % UNIT != 0 and 32 < n <= 64
+    test_large_row_major_launch_matches_oracle(P, oracle, algo, kind, n, d, pad, skew)
+
+
 @pytest.mark.parametrize("n,d,pad", [(4, (1 << 20) + 1284, 4), (8, (1 << 20) + 3 * UNIT + 8, 8), (4, (1 << 20) + 2 * UNIT, 0)])
 def test_large_launch_with_per_tensor_sums(P, oracle, n, d, pad):
     """The multi-tensor call over one large launch in either order: state and sums against the oracle."""
