@@ -188,3 +188,48 @@ def test_large_launch_with_per_tensor_sums(P, oracle, n, d, pad):
     want = oracle.tensor_sumsq(g0, mr.astype(np.float32), xr.astype(np.float32), offsets)
     np.testing.assert_allclose(norms.cpu().numpy(), want, rtol=3e-6, atol=1e-30)
 
+
+
+@pytest.mark.parametrize("n,d,ld", [(48, (1 << 20) + 3 * UNIT + 300, (1 << 20) + 4 * UNIT),      # two-pass kernel + ordinary launches around it
+                                    (32, (1 << 20) + 8192, (1 << 20) + 8192)])                   # chained tiles + an ordinary launch
+def test_large_launches_made_of_several_kernels_are_capturable(P, n, d, ld):
+    """A large call on these layouts is two or three kernel launches, some of which set a function attribute first;
+    all of it must be recordable into a HIP graph.  Three replays of two captured iterations against eager execution,
+    with the program's own work and synchronisations between the replays."""
+    topo = P.topology_build(P.DL_TOPO_EXP_STATIC, n)
+    gamma, beta = float(np.float32(0.05)), float(np.float32(0.9))
+    gen = torch.Generator(device="cuda").manual_seed(n)
+    skew = 4                                                  # 16 bytes past a 64 KiB boundary: columns before the units too
+    bufs = [placed(n, d, ld, skew, 0.0) for _ in range(5)]    # eager x, m; graph x, m; g
+    (_, xe), (_, me), (_, xg), (_, mg), (_, g) = bufs
+    x0 = torch.randn((n, d), device="cuda", generator=gen)
+    g.copy_(torch.randn((n, d), device="cuda", generator=gen))
+
+    def two_steps(x, m):
+        P.decentlam_step(x, m, g, topo, gamma, beta, 0)
+        P.dmsgd_step(x, m, g, topo, gamma, beta, 1)
+
+    xe.copy_(x0)
+    eager = []
+    for _ in range(3):
+        two_steps(xe, me)
+        eager.append((xe.clone(), me.clone()))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):          # warm-up on the capture stream, then restore the state
+        two_steps(xg, mg)
+    torch.cuda.current_stream().wait_stream(side)
+    xg.copy_(x0)
+    mg.zero_()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        two_steps(xg, mg)
+    xg.copy_(x0)
+    mg.zero_()
+    scratch = torch.zeros(1000, device="cuda")
+    for r in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(xg, eager[r][0]) and torch.equal(mg, eager[r][1]), f"replay {r} differs from eager"
+        scratch.add_(1.0)
+        torch.cuda.synchronize()
