@@ -419,12 +419,17 @@ __global__ __launch_bounds__(kThreads) void k_small(const float* __restrict__ A,
     }
 }
 
-// Row blocks per node for the single sweep: about two workgroups per CU in total, all resident
-// at once (measured best on 256 CUs: 512 workgroups; more, shorter ones lose up to 15 %), but at
-// least one double tile of rows each.
-int fused_splits(int32_t n, int32_t b, int rows_per_iteration) {
-    int64_t s = (512 + n / 2) / n;
-    const int64_t most = (b + rows_per_iteration - 1) / rows_per_iteration;
+// Row blocks per node for the single sweep: as many workgroups as are resident at once -- two per CU, 512 (one per
+// CU, 256, for the 512-thread kernel beyond d = 8192); more, shorter ones lose up to 15 % -- but at least one double
+// tile and at least eight rows each: every workgroup writes a partial gradient of d doubles, which the final pass
+// reads again, as much traffic as four rows of A each way.  Measured, workgroups in total 128 / 256 / 512 / 1024:
+// 8 nodes of 1024 x 1024: 26.7 / 16.5 / 14.8 / 17.4 us; 8 nodes of 256 x 4096: 17.0 / 14.8 / 21.0 / 24.7 us;
+// 64 nodes of 4096 x 4096: 1312 / 747 / 624 / 691 us; 16 nodes of 1024 x 16384: 292 / 185 / 201 / 231 us.
+int fused_splits(int32_t n, int32_t b, int64_t d, int rows_per_iteration) {
+    const int64_t resident = d > 8192 ? 256 : 512;
+    int64_t s = (resident + n / 2) / n;
+    const int64_t rows_each = rows_per_iteration > 8 ? rows_per_iteration : 8;
+    const int64_t most = (b + rows_each - 1) / rows_each;
     if (s > most) s = most;
     if (s > 256) s = 256;
     if (s < 1) s = 1;
@@ -452,7 +457,7 @@ size_t lsq_workspace_bytes_path(int32_t n, int32_t b, int64_t d, int path) {
     const size_t two_sweeps = (res + partial) * sizeof(double) + 16;
     size_t fused = 0;
     if (d > 0 && d <= kMaxFusedD) {
-        const size_t fs = static_cast<size_t>(fused_splits(n, b, fused_rows(fused_cpt(d))));
+        const size_t fs = static_cast<size_t>(fused_splits(n, b, d, fused_rows(fused_cpt(d))));
         fused = (static_cast<size_t>(n) * fs * (static_cast<size_t>(d) + 1)) * sizeof(double) + 16;
     }
     if (path == 0) return two_sweeps;
@@ -494,7 +499,7 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
     }
     if (path == 1) {
         const int cpt = fused_cpt(d);
-        const int fs = fused_splits(n, bs, fused_rows(cpt));
+        const int fs = fused_splits(n, bs, d, fused_rows(cpt));
         double* sq_partial = static_cast<double*>(workspace);
         double* fpartial = sq_partial + ((static_cast<size_t>(n) * fs + 1) & ~size_t{1});
         const dim3 grid(static_cast<unsigned>(fs), static_cast<unsigned>(n));
