@@ -5,7 +5,7 @@
 // The bound is HBM, and the kernels are organised around streaming A with wide
 // coalesced loads; products are exact in fp64 (two fp32 factors) and sums are fp64.
 //
-// Single sweep (rows 16-byte aligned, d <= 16384; 256 threads up to d = 8192, 512 beyond): k_fused keeps a tile of R rows of A_i in
+// Single sweep (rows 16-byte aligned, d <= 16384; 256 threads up to d = 8192, 1024 beyond): k_fused keeps a tile of R rows of A_i in
 // registers, split by columns over the 256 threads of a workgroup; the R residuals are reduced
 // with wavefront shuffles plus one LDS hop, then the same registers feed the transposed
 // product, so A is read from HBM exactly once (4*b*d bytes per node).  The next tile's loads are
@@ -281,10 +281,13 @@ __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float 
     }
 }
 
-// THREADS: 256 up to d = 8192; 512 threads (same columns per thread, more threads) carry the single
-// sweep to d = 16384
+// THREADS: 256 up to d = 8192; 1024 threads with four column chunks each carry the single sweep to d = 16384
+// (one workgroup per CU within 128 registers, no prefetch; 512 threads with eight chunks each measured 2-3 % slower:
+// 16 nodes of 1024 x 16384 5.75 against 5.94 TB/s, 8 nodes of 4096 x 16384 6.31 against 6.44; up to d = 8192, 512
+// threads with four chunks, with or without prefetch, are slower than 256 with eight: 64 nodes of 1024 x 6144
+// 5.6-5.8 against 6.2 TB/s)
 template <int CPT, int R, bool PF, int THREADS>
-__global__ __launch_bounds__(THREADS, THREADS > 256 ? 1 : ((PF || CPT >= 8) ? 2 : 4)) void k_fused(const float* __restrict__ A, const float* __restrict__ y,
+__global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 : 4)) void k_fused(const float* __restrict__ A, const float* __restrict__ y,
                                                      const float* __restrict__ x, double* __restrict__ partial,
                                                      double* __restrict__ sq_partial, int b, int64_t d,
                                                      int64_t ldA, int64_t ld, int splits,
@@ -420,7 +423,7 @@ __global__ __launch_bounds__(kThreads) void k_small(const float* __restrict__ A,
 }
 
 // Row blocks per node for the single sweep: as many workgroups as are resident at once -- two per CU, 512 (one per
-// CU, 256, for the 512-thread kernel beyond d = 8192); more, shorter ones lose up to 15 % -- but at least one double
+// CU, 256, for the 1024-thread kernel beyond d = 8192); more, shorter ones lose up to 15 % -- but at least one double
 // tile and at least eight rows each: every workgroup writes a partial gradient of d doubles, which the final pass
 // reads again, as much traffic as four rows of A each way.  Measured, workgroups in total 128 / 256 / 512 / 1024:
 // 8 nodes of 1024 x 1024: 26.7 / 16.5 / 14.8 / 17.4 us; 8 nodes of 256 x 4096: 17.0 / 14.8 / 21.0 / 24.7 us;
@@ -439,7 +442,7 @@ int fused_splits(int32_t n, int32_t b, int64_t d, int rows_per_iteration) {
 // rows consumed per loop iteration (two register tiles of R rows, or one without prefetch)
 int fused_rows(int cpt) { return cpt == 1 ? 8 : cpt == 2 ? 4 : cpt == 4 ? 2 : 1; }
 int fused_cpt(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : 8; }
-constexpr int kMaxFusedD = 16384;   // 512 threads x 8 chunks of 4 columns (1024 threads would spill: 128 registers each)
+constexpr int kMaxFusedD = 16384;   // 1024 threads x 4 chunks of 4 columns
 
 }  // namespace
 
@@ -511,7 +514,7 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
                 if (d <= 8192)
                     hipLaunchKernelGGL((k_fused<8, 1, false, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
                 else
-                    hipLaunchKernelGGL((k_fused<8, 1, false, 512>), grid, dim3(512), 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+                    hipLaunchKernelGGL((k_fused<4, 1, false, 1024>), grid, dim3(1024), 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
                 break;
         }
         if (int rc = check_hip(hipGetLastError(), "fused gradient kernel launch")) return rc;

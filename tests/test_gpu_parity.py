@@ -198,8 +198,9 @@ LSQ_CASES = [
     (2, 77, 132, 0, 4, 1.0),             # single sweep with most threads idle (d < 1024)
     (3, 1000, 1500, 4, 0, 0.001),        # single sweep, 2 chunks per thread, ragged row blocks
     (2, 45, 5000, 0, 0, 1.0),            # single sweep, 8 chunks per thread
-    (1, 9, 8200, 0, 0, 1.0),             # 8192 < d <= 16384: single sweep with 512 threads
+    (1, 9, 8200, 0, 0, 1.0),             # 8192 < d <= 16384: single sweep with 1024 threads, 4 chunks each
     (2, 37, 16384, 0, 0, 0.25),          # the widest single sweep
+    (3, 40, 12292, 4, 0, 1.0),           # 1024 threads, last chunk of most threads past d, padded rows
     (1, 9, 16388, 0, 0, 1.0),            # d > 16384: two sweeps with 16-byte loads, a workgroup per row
     (2, 7, 4099, 1, 3, 1.0),             # few long rows, odd strides: a workgroup per row, 4-byte loads
     (3, 2000, 8196, 0, 0, 1.0),          # many long rows: a wave per row
