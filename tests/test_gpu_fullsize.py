@@ -86,6 +86,35 @@ def test_workload3_n32_d25_6M_sampled_columns(P, oracle, algo, padded):
     run_sampled_trajectory(P, oracle, w, algo, 1, ld=P.recommended_ld(d) if padded else d)
 
 
+@pytest.mark.parametrize("n", [48, 64, 128])
+def test_headline_size_at_other_node_counts_sampled_columns(P, oracle, n):
+    """The benchmark's side measurement `decentlam_step_by_node_count`: 819.2 M node-elements on n nodes, static
+    exponential graph, rows on 64 KiB boundaries (empty_rows): from 33 nodes on these launches take the kernel
+    that uses its LDS tile twice per 256 columns.  Five iterations, the oracle on sampled columns incl. the seams."""
+    d = 32 * 25_600_000 // n
+    topo = P.topology_build(P.DL_TOPO_EXP_STATIC, n)
+    otopo = oracle.topology(1, n)
+    gamma, beta = float(np.float32(0.01)), float(np.float32(0.9))
+    gen = torch.Generator(device="cuda").manual_seed(1000 + n)
+    x, m, g = (P.empty_rows(n, d) for _ in range(3))
+    x.normal_(generator=gen)
+    m.zero_()
+    cols = sample_columns(d, seed=n)
+    cols_t = torch.from_numpy(cols).cuda()
+    xs = x.index_select(1, cols_t).cpu().numpy().astype(np.float64)
+    ms = np.zeros_like(xs)
+    for k in range(5):
+        g.normal_(generator=gen)
+        gs = g.index_select(1, cols_t).cpu().numpy().astype(np.float64)
+        P.decentlam_step(x, m, g, topo, gamma, beta, k)
+        xs, ms = oracle.STEP["decentlam"](xs, ms, gs, otopo, gamma, beta, k)
+        xs = xs.astype(np.float32).astype(np.float64)
+        ms = ms.astype(np.float32).astype(np.float64)
+        check_elementwise(x.index_select(1, cols_t).cpu().numpy(), xs, f"n = {n}: x, iteration {k}")
+        check_elementwise(m.index_select(1, cols_t).cpu().numpy(), ms, f"n = {n}: m, iteration {k}")
+    assert torch.isfinite(x).all() and torch.isfinite(m).all()
+
+
 def test_workload4_ragged_flat_and_ranged_calls(P, oracle):
     """n = 16 ring over 160 packed tensors (sizes not multiples of 4): one flat call per iteration
     against the oracle on sampled columns; then the same run as 160 per-tensor ranged calls
