@@ -119,7 +119,9 @@ int launch_chain(int algo, const StepCall& s, uint32_t units, uint32_t len);
 
 // Two LDS passes under split tiles for 33-128 nodes (step_tall.hip): whether that kernel serves this method, node
 // count and graph, and its launch over `units` whole 64 KiB units of columns starting at s.x / s.m / s.g (row 0 of
-// x on a 64 KiB boundary, s.ld a multiple of 16384, every array 16-byte aligned, fp32 gradients).
+// x on a 64 KiB boundary, s.ld a multiple of 128, every array 16-byte aligned, fp32 gradients); or, with
+// s.batch_stride != 0 (blocked layout), over s.batches sub-problems of s.d columns each (s.d a multiple of 256,
+// `units` unused).
 bool tall_serves(int algo, int32_t n, int nnz);
 int launch_tall(int algo, const StepCall& s, uint32_t units);
 

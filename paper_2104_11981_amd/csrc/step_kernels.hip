@@ -103,6 +103,24 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
         }
     }
 
+    // The blocked layout on 33-40 and 49-56 nodes (blocks of whole 256-column tiles, everything 16-byte aligned, a
+    // launch of 4096 tiles and more): the same kernel in its shapes of 10 to 14 waves, two or three workgroups per CU
+    // where k_step has one whose gathers nothing overlaps.  Ring / exponential graph, TB/s: 36 nodes 6.4 / 6.4 against
+    // 6.25 / 6.25, 40 nodes 6.25 / 6.3 against 6.2 / 5.8, 56 nodes 6.3 / 6.3 against 6.4 / 6.05; with the 16-wave
+    // shapes (48, 64 nodes) 6.4 / 6.05 either way, so those stay with k_step.
+    if (n > 32 && (n <= 40 || (n > 48 && n <= 56)) && batch_stride != 0 && !norms && g.format == DL_GRAD_F32 && d % 256 == 0 && ld == d && g.ld == d &&
+        batch_stride % 4 == 0 && batch_stride_g == batch_stride && batches * (d / 256) >= kSplitMinColumns / 256 &&
+        ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(g.p)) & 15u) == 0 &&
+        tall_serves(algo, n, topo.row_ptr[n])) {
+        StepCall s;
+        s.x = x; s.m = m; s.g = g.p;
+        s.n = n; s.d = d; s.ld = ld; s.ldg = g.ld;
+        s.gamma = gamma; s.beta = beta; s.topo = &topo; s.stream = stream;
+        s.na = NormArgs{nullptr, 0, 0};
+        s.batches = batches; s.batch_stride = batch_stride; s.batch_stride_g = batch_stride_g; s.split_tiles = 0; s.by_xcd = false;
+        return launch_tall(algo, s, 0);
+    }
+
     // Pick the widest access all three arrays can share: same misalignment (in elements)
     // modulo the vector width and row strides that preserve it.
     int vec = widest_vec_for(n, algo);

@@ -30,7 +30,8 @@ namespace {
 template <int ALGO, int RPT, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(RPT <= 4 ? 8 : 4, RPT <= 4 ? 8 : 4))) void k_step_tall(float* __restrict__ x, float* __restrict__ m,
                                                     const float* __restrict__ g, int64_t ld, int64_t ldg,
-                                                    double gamma, double inv_gamma, double beta, const PhaseArgs topo) {
+                                                    double gamma, double inv_gamma, double beta,
+                                                    uint32_t batch_tiles, int64_t batch_stride, const PhaseArgs topo) {
     constexpr int TC = 128;   // columns of the LDS tile: two per lane and pass
     static_assert(ALGO != ALGO_DA_DMSGD, "one gather per iteration");
     constexpr bool kHasM = ALGO != ALGO_DSGD;
@@ -43,8 +44,18 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(RPT 
     Entry* table = reinterpret_cast<Entry*>(lds + n * TC);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t tile_col = split_column(blockIdx.x, 0);
-    const int lane_col = static_cast<int>(split_column(0, lane));
+    // Which columns: a split tile of a single row-major problem, or (batch_tiles != 0: the blocked layout) tile
+    // blockIdx.x % batch_tiles, 256 consecutive columns, of sub-problem blockIdx.x / batch_tiles; all uniform.
+    int64_t tile_col = split_column(blockIdx.x, 0);
+    int lane_col = static_cast<int>(split_column(0, lane));
+    if (batch_tiles) {
+        const uint32_t sub = blockIdx.x / batch_tiles;
+        x += sub * batch_stride;
+        if constexpr (kHasM) m += sub * batch_stride;
+        g += sub * batch_stride;
+        tile_col = static_cast<int64_t>(blockIdx.x - sub * batch_tiles) * 256;
+        lane_col = lane * 4;
+    }
 
     // ---- all loads of the tile, what the first pre-step needs first: the rest may still be on its way while the
     // first pass runs (loads return in order)
@@ -180,7 +191,8 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(RPT 
                     // the lane's columns, worked out afresh from the lane number (two instructions) rather than kept
                     // in a register through both passes, which the four-row shape has none left for
                     const int lane_again = static_cast<int>(__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)));
-                    const int64_t at = (static_cast<int64_t>(i) * ld + tile_col) + split_column(0, lane_again);
+                    const int64_t at = (static_cast<int64_t>(i) * ld + tile_col) +
+                                       (batch_tiles ? static_cast<int64_t>(lane_again) * 4 : split_column(0, lane_again));
                     if constexpr (kHasM) store_vec<4>(m + at, mr[r]);
                     if constexpr (ALGO != ALGO_DECENTLAM_XPREV) store_vec<4>(x + at, xr[r]);
                 }
@@ -190,7 +202,7 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(RPT 
 }
 
 template <int ALGO, int RPT, int WAVES = 16>
-int launch_tall_shape(const StepCall& s, uint32_t units) {
+int launch_tall_shape(const StepCall& s, uint32_t tiles, uint32_t batch_tiles) {
     const size_t lds_bytes = lds_bytes_for(s.n, 2, s.topo->row_ptr[s.n], 1);
     if (lds_bytes > 160 * 1024) return set_error(DL_ETOPO, "step: the two-pass kernel's tile does not fit");
     auto kernel = k_step_tall<ALGO, RPT, WAVES>;
@@ -200,28 +212,29 @@ int launch_tall_shape(const StepCall& s, uint32_t units) {
                                "hipFuncSetAttribute(max dynamic LDS)"))
             return rc;
     }
-    hipLaunchKernelGGL(kernel, dim3(units * kSplitTilesPerUnit), dim3(64 * WAVES), lds_bytes, s.stream, s.x, s.m,
-                       static_cast<const float*>(s.g), s.ld, s.ldg, s.gamma, 1.0 / s.gamma, s.beta, *s.topo);
+    hipLaunchKernelGGL(kernel, dim3(tiles), dim3(64 * WAVES), lds_bytes, s.stream, s.x, s.m,
+                       static_cast<const float*>(s.g), s.ld, s.ldg, s.gamma, 1.0 / s.gamma, s.beta, batch_tiles,
+                       s.batch_stride, *s.topo);
     return check_hip(hipGetLastError(), "step kernel launch (two-pass tiles)");
 }
 
 template <int ALGO>
-int launch_tall_algo(const StepCall& s, uint32_t units) {
+int launch_tall_algo(const StepCall& s, uint32_t tiles, uint32_t batch_tiles) {
     // waves x rows per thread.  Up to 64 nodes a shape without empty row slots is worth 2-4 % (36 / 40 / 56 nodes:
     // 6.5 / 6.45 / 6.3 TB/s with 12 x 3 / 10 x 4 / 14 x 4 against 6.2 / 6.25 / 6.2 with 16 x 3 / 16 x 3 / 16 x 4)
-    if (s.n <= 36) return launch_tall_shape<ALGO, 3, 12>(s, units);
+    if (s.n <= 36) return launch_tall_shape<ALGO, 3, 12>(s, tiles, batch_tiles);
     if constexpr (ALGO != ALGO_AWC_DMSGD) {
-        if (s.n <= 40) return launch_tall_shape<ALGO, 4, 10>(s, units);
+        if (s.n <= 40) return launch_tall_shape<ALGO, 4, 10>(s, tiles, batch_tiles);
     }
-    if (s.n <= 48) return launch_tall_shape<ALGO, 3>(s, units);
+    if (s.n <= 48) return launch_tall_shape<ALGO, 3>(s, tiles, batch_tiles);
     if constexpr (ALGO != ALGO_AWC_DMSGD) {
-        if (s.n <= 56) return launch_tall_shape<ALGO, 4, 14>(s, units);
-        if (s.n <= 64) return launch_tall_shape<ALGO, 4>(s, units);
+        if (s.n <= 56) return launch_tall_shape<ALGO, 4, 14>(s, tiles, batch_tiles);
+        if (s.n <= 64) return launch_tall_shape<ALGO, 4>(s, tiles, batch_tiles);
     }
-    if (s.n <= 80) return launch_tall_shape<ALGO, 5>(s, units);
-    if (s.n <= 96) return launch_tall_shape<ALGO, 6>(s, units);
-    if (s.n <= 112) return launch_tall_shape<ALGO, 7>(s, units);
-    return launch_tall_shape<ALGO, 8>(s, units);
+    if (s.n <= 80) return launch_tall_shape<ALGO, 5>(s, tiles, batch_tiles);
+    if (s.n <= 96) return launch_tall_shape<ALGO, 6>(s, tiles, batch_tiles);
+    if (s.n <= 112) return launch_tall_shape<ALGO, 7>(s, tiles, batch_tiles);
+    return launch_tall_shape<ALGO, 8>(s, tiles, batch_tiles);
 }
 
 }  // namespace
@@ -233,13 +246,23 @@ bool tall_serves(int algo, int32_t n, int nnz) {
 }
 
 int launch_tall(int algo, const StepCall& s, uint32_t units) {
-    if (units > 0x7fffffffu / kSplitTilesPerUnit) return set_error(DL_EINVAL, "step: d too large for one launch");
+    uint32_t tiles, batch_tiles = 0;
+    if (s.batches > 1 || s.batch_stride != 0) {   // blocked layout: s.d columns per sub-problem, whole tiles only
+        const int64_t per = s.d / 256, all = per * s.batches;
+        if (s.d % 256 != 0 || per < 1 || all > 0x7fffffffLL || s.batch_stride_g != s.batch_stride)
+            return set_error(DL_EINVAL, "step: the two-pass kernel takes blocks of whole 256-column tiles");
+        tiles = static_cast<uint32_t>(all);
+        batch_tiles = static_cast<uint32_t>(per);
+    } else {
+        if (units > 0x7fffffffu / kSplitTilesPerUnit) return set_error(DL_EINVAL, "step: d too large for one launch");
+        tiles = units * kSplitTilesPerUnit;
+    }
     switch (algo) {
-        case ALGO_DECENTLAM: return launch_tall_algo<ALGO_DECENTLAM>(s, units);
-        case ALGO_DMSGD: return launch_tall_algo<ALGO_DMSGD>(s, units);
-        case ALGO_DSGD: return launch_tall_algo<ALGO_DSGD>(s, units);
-        case ALGO_AWC_DMSGD: return launch_tall_algo<ALGO_AWC_DMSGD>(s, units);
-        case ALGO_DECENTLAM_XPREV: return launch_tall_algo<ALGO_DECENTLAM_XPREV>(s, units);
+        case ALGO_DECENTLAM: return launch_tall_algo<ALGO_DECENTLAM>(s, tiles, batch_tiles);
+        case ALGO_DMSGD: return launch_tall_algo<ALGO_DMSGD>(s, tiles, batch_tiles);
+        case ALGO_DSGD: return launch_tall_algo<ALGO_DSGD>(s, tiles, batch_tiles);
+        case ALGO_AWC_DMSGD: return launch_tall_algo<ALGO_AWC_DMSGD>(s, tiles, batch_tiles);
+        case ALGO_DECENTLAM_XPREV: return launch_tall_algo<ALGO_DECENTLAM_XPREV>(s, tiles, batch_tiles);
         default: return set_error(DL_EINVAL, "step: this method has no two-pass kernel");
     }
 }

@@ -38,6 +38,12 @@ CASES = [
     (0, 3, 7, 1, 0, 2),             # one column per block
     (1, 256, 300, 64, 0, 2),        # exponential graph on 256 nodes: 2304 entries, one weight per row
     (1, 24, 2100, 1024, 0, 2),      # twelve waves of two rows
+    # launches of 4096 tiles and more on 33-40 and 49-56 nodes: the kernel that uses its LDS tile twice per tile
+    (1, 40, (1 << 20) + 3 * 2048 + 100, 2048, 0, 2),    # 515 blocks of 8 tiles + a narrow last block; 10 waves x 4 rows
+    (0, 36, (1 << 20) + 8192, 8192, 0, 2),              # 129 blocks of 32 tiles; 12 waves x 3 rows
+    (4, 56, (1 << 20) + 512, 1024, 0, 2),               # irregular degrees; 14 waves x 4 rows; half a block at the end
+    (1, 40, (1 << 20) + 2048, 2048, 4, 1),              # base 16 bytes past an aligned address: still served
+    (1, 40, (1 << 20) + 2048, 2048, 1, 1),              # misaligned base: not served, the ordinary kernel
 ]
 
 
