@@ -251,10 +251,8 @@ int launch_chain_algo(const StepCall& s, uint32_t units, uint32_t len) {
     if (lds_bytes > 80 * 1024) return set_error(DL_ETOPO, "step: the chain kernel's tile does not fit");
     auto kernel = k_step_chain<ALGO>;
     if (lds_bytes > 48 * 1024) {
-        if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024),
-                               "hipFuncSetAttribute(max dynamic LDS)"))
-            return rc;
+        static std::atomic<uint64_t> configured{0};   // per instantiation; see allow_large_lds
+        if (int rc = allow_large_lds(reinterpret_cast<const void*>(kernel), configured)) return rc;
     }
     // chains of `len` units while at least 16 chains of that length remain, then half as long, and so on
     ChainArgs chain{};

@@ -677,6 +677,23 @@ __global__ __launch_bounds__(64 * WAVES) void k_step(float* __restrict__ x, floa
     }
 }
 
+// More than 48 KiB of dynamic LDS takes a function attribute: set once per kernel instantiation and device to the
+// most this chip has (the call costs about 2 us, a fifth of a small step).  The one thing the library remembers
+// between calls is that this has been done (a bit per kernel variant and device, the header says so: `configured`
+// is a static of the calling instantiation); devices with ordinal 64 and up set it at every launch.
+inline int allow_large_lds(const void* kernel, std::atomic<uint64_t>& configured) {
+    int device = 0;
+    if (int rc = check_hip(hipGetDevice(&device), "hipGetDevice")) return rc;
+    const uint64_t bit = device >= 0 && device < 64 ? uint64_t{1} << device : uint64_t{0};
+    if (!(configured.load(std::memory_order_relaxed) & bit) || bit == 0) {
+        if (int rc = check_hip(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024),
+                               "hipFuncSetAttribute(max dynamic LDS)"))
+            return rc;
+        configured.fetch_or(bit, std::memory_order_relaxed);
+    }
+    return DL_OK;
+}
+
 size_t lds_bytes_for(int32_t n, int vec, int nnz, int tiles) {
     const size_t entry = vec == 4 ? sizeof(Neighbour) : sizeof(NeighbourCompact);
     return static_cast<size_t>(tiles) * n * 64 * vec * sizeof(double) + static_cast<size_t>(nnz) * entry;
@@ -692,21 +709,8 @@ int launch_variant(const StepCall& s) {
         return set_error(DL_ETOPO, "step: n = %d with %d entries needs %zu bytes of LDS, a CU has 163840", s.n,
                          static_cast<int>(s.topo->row_ptr[s.n]), lds_bytes);
     if (lds_bytes > 48 * 1024) {
-        // More than 48 KiB of dynamic LDS takes a function attribute: set once per instantiation and
-        // device to the most this chip has (the call costs about 2 us, a fifth of a small step).  The
-        // one thing the library remembers between calls is that this has been done (a bit per kernel
-        // variant and device, the header says so); devices with ordinal 64 and up set it at every launch.
         static std::atomic<uint64_t> configured{0};   // one bit per device ordinal below 64
-        int device = 0;
-        if (int rc = check_hip(hipGetDevice(&device), "hipGetDevice")) return rc;
-        const uint64_t bit = device >= 0 && device < 64 ? uint64_t{1} << device : uint64_t{0};
-        if (!(configured.load(std::memory_order_relaxed) & bit) || bit == 0) {
-            if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024),
-                                   "hipFuncSetAttribute(max dynamic LDS)"))
-                return rc;
-            configured.fetch_or(bit, std::memory_order_relaxed);
-        }
+        if (int rc = allow_large_lds(reinterpret_cast<const void*>(kernel), configured)) return rc;
     }
     const int64_t tiles = (s.d + TC - 1) / TC;
     const int64_t blocks = tiles * s.batches;

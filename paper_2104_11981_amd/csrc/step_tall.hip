@@ -207,10 +207,8 @@ int launch_tall_shape(const StepCall& s, uint32_t tiles, uint32_t batch_tiles) {
     if (lds_bytes > 160 * 1024) return set_error(DL_ETOPO, "step: the two-pass kernel's tile does not fit");
     auto kernel = k_step_tall<ALGO, RPT, WAVES>;
     if (lds_bytes > 48 * 1024) {
-        if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024),
-                               "hipFuncSetAttribute(max dynamic LDS)"))
-            return rc;
+        static std::atomic<uint64_t> configured{0};   // per instantiation; see allow_large_lds
+        if (int rc = allow_large_lds(reinterpret_cast<const void*>(kernel), configured)) return rc;
     }
     hipLaunchKernelGGL(kernel, dim3(tiles), dim3(64 * WAVES), lds_bytes, s.stream, s.x, s.m,
                        static_cast<const float*>(s.g), s.ld, s.ldg, s.gamma, 1.0 / s.gamma, s.beta, batch_tiles,
