@@ -148,8 +148,9 @@ int topology_metropolis(int32_t n, const int32_t* row_ptr, const int32_t* col_id
  * 32 x 25.6 M array; 17 to 32 nodes, x, m, g placed alike modulo 64 KiB) are served by a kernel of their
  * own that loads and stores half of each odd row's accesses one 64 KiB unit ahead / late: 2.64 ms there.
  * On 33 to 128 nodes the 64 KiB alignment also selects a kernel that uses an on-chip tile of half the width
- * twice per 256 columns: 6.2-6.4 instead of 5.9-6.2 TB/s up to 64 nodes (two workgroups per CU instead of
- * one), 5.4-5.7 instead of 5.0-5.2 beyond (16-byte instead of 8-byte accesses).
+ * twice per 256 columns: 6.3-6.5 instead of 5.9-6.2 TB/s up to 64 nodes (two workgroups per CU instead of
+ * one; there rows on any 512-byte boundary select it, at 5.8-6.2 TB/s), 5.4-5.7 instead of 5.0-5.2 beyond
+ * (16-byte instead of 8-byte accesses).
  * Dense graphs (23 <= n <= 32 with 46 - n or more entries per row on average: 14 at n = 32, all
  * 23 at n = 23; 33 <= n <= 48 with 38 - n / 4 or more; this holds for every step entry point): the partial averaging runs as an fp64 matrix product on the matrix cores
  * instead of neighbour by neighbour (all-to-all at n = 32, d = 25.6 M: 2.7 instead of 3.5 ms).
