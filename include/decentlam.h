@@ -461,7 +461,7 @@ int dsgd_step(float* x, const float* g,
  * Deterministic: partial sums are combined in a fixed order.
  * The contraction is a batch of n matrix-vector products with no shared operand (every node has its own
  * A_i and x_i): 1 flop per byte of A at best, so the bound is HBM bandwidth and the kernels are built
- * around one streaming pass over A (rows 16-byte aligned, d <= 16384; otherwise two passes).  Products and sums run as fp64 fused multiply-adds on the vector units; the matrix cores are
+ * around one streaming pass over A (rows 16-byte aligned, d <= 32768; otherwise two passes).  Products and sums run as fp64 fused multiply-adds on the vector units; the matrix cores are
  * not used: an MFMA tile would have one useful column in sixteen, and for fp32 / fp64 the matrix and
  * vector peaks of this chip are equal.
  * Errors: DL_EINVAL (NULL, n < 1, b < 1, d < 0, ldA < d, ld < d, scale not finite),
@@ -480,7 +480,7 @@ int local_grad_lsq(const float* A, const float* y, const float* x,
  * the library's device image (every GPU the library runs on holds its own copy until the process
  * ends).  The call allocates nothing and frees nothing.
  *   Limit: the partial sums of the kernels this shape and alignment select must fit
- *   DL_STATIC_SCRATCH_BYTES (32 MiB).  With 16-byte aligned rows and d <= 16384 (one sweep over A)
+ *   DL_STATIC_SCRATCH_BYTES (32 MiB).  With 16-byte aligned rows and d <= 32768 (one sweep over A)
  *   that is about n * max(1, 512 / n) * (d + 1) * 8 bytes (n = 64 nodes of 4096 x 4096: 16.8 MB), never
  *   more than local_grad_lsq_workspace(n, b, d).  Larger problems return DL_ECAP (nothing is launched)
  *   and belong to local_grad_lsq.

@@ -5,7 +5,7 @@
 // The bound is HBM, and the kernels are organised around streaming A with wide
 // coalesced loads; products are exact in fp64 (two fp32 factors) and sums are fp64.
 //
-// Single sweep (rows 16-byte aligned, d <= 16384; 256 threads up to d = 8192, 1024 beyond): k_fused keeps a tile of R rows of A_i in
+// Single sweep (rows 16-byte aligned, d <= 32768; 256 threads up to d = 8192, 1024 beyond): k_fused keeps a tile of R rows of A_i in
 // registers, split by columns over the 256 threads of a workgroup; the R residuals are reduced
 // with wavefront shuffles plus one LDS hop, then the same registers feed the transposed
 // product, so A is read from HBM exactly once (4*b*d bytes per node).  The next tile's loads are
@@ -228,8 +228,9 @@ __device__ __forceinline__ void load_tile(Tile<CPT, R>& t, const float* __restri
     }
 }
 
-template <int CPT, int R, int WAVES>
-__device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float (&xs)[CPT][4],
+// XL: the thread's chunks of x_i wait in LDS (xl[q * 64 * WAVES], written by this thread) instead of in registers
+template <int CPT, int R, int WAVES, bool XL = false>
+__device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float (&xs)[CPT][4], const vf4* xl,
                                              double (&acc)[CPT][4], double& sq, double (*red)[R],
                                              const float* __restrict__ yi, int r, int r1, int lane, int wave,
                                              const int32_t* __restrict__ rows_i, int b) {
@@ -239,10 +240,16 @@ __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float 
         double s0 = 0.0, s1 = 0.0;
 #pragma unroll
         for (int q = 0; q < CPT; ++q) {
-            s0 = __builtin_fma(static_cast<double>(t.a[rr][q].x), static_cast<double>(xs[q][0]), s0);
-            s1 = __builtin_fma(static_cast<double>(t.a[rr][q].y), static_cast<double>(xs[q][1]), s1);
-            s0 = __builtin_fma(static_cast<double>(t.a[rr][q].z), static_cast<double>(xs[q][2]), s0);
-            s1 = __builtin_fma(static_cast<double>(t.a[rr][q].w), static_cast<double>(xs[q][3]), s1);
+            vf4 xv;
+            if constexpr (XL) {
+                xv = xl[q * 64 * WAVES];
+            } else {
+                xv.x = xs[q][0]; xv.y = xs[q][1]; xv.z = xs[q][2]; xv.w = xs[q][3];
+            }
+            s0 = __builtin_fma(static_cast<double>(t.a[rr][q].x), static_cast<double>(xv.x), s0);
+            s1 = __builtin_fma(static_cast<double>(t.a[rr][q].y), static_cast<double>(xv.y), s1);
+            s0 = __builtin_fma(static_cast<double>(t.a[rr][q].z), static_cast<double>(xv.z), s0);
+            s1 = __builtin_fma(static_cast<double>(t.a[rr][q].w), static_cast<double>(xv.w), s1);
         }
         p[rr] = wave_sum(s0 + s1);
     }
@@ -281,12 +288,14 @@ __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float 
     }
 }
 
-// THREADS: 256 up to d = 8192; 1024 threads with four column chunks each carry the single sweep to d = 16384
+// THREADS: 256 up to d = 8192; 1024 threads with four column chunks each carry the single sweep to d = 16384, with
+// eight chunks each and x_i in LDS (XL) to d = 32768 (8 nodes of 2048 x 32768: 0.36 ms, 0.74 of the HBM peak, where
+// the two sweeps take 0.83 ms)
 // (one workgroup per CU within 128 registers, no prefetch; 512 threads with eight chunks each measured 2-3 % slower:
 // 16 nodes of 1024 x 16384 5.75 against 5.94 TB/s, 8 nodes of 4096 x 16384 6.31 against 6.44; up to d = 8192, 512
 // threads with four chunks, with or without prefetch, are slower than 256 with eight: 64 nodes of 1024 x 6144
 // 5.6-5.8 against 6.2 TB/s)
-template <int CPT, int R, bool PF, int THREADS>
+template <int CPT, int R, bool PF, int THREADS, bool XL = false>
 __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 : 4)) void k_fused(const float* __restrict__ A, const float* __restrict__ y,
                                                      const float* __restrict__ x, double* __restrict__ partial,
                                                      double* __restrict__ sq_partial, int b, int64_t d,
@@ -301,6 +310,8 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
     const int r1 = static_cast<int>(static_cast<int64_t>(bs) * (s + 1) / splits);  // r1 > r0: splits <= bs
     const int32_t* __restrict__ rows_i = rows ? rows + static_cast<int64_t>(i) * bs : nullptr;
 
+    extern __shared__ vf4 x_chunks[];   // XL: CPT * THREADS chunks of x_i, each read only by the thread that wrote it
+    const vf4* xl = x_chunks + threadIdx.x;
     int col[CPT];
     float xs[CPT][4];
     double acc[CPT][4];
@@ -310,8 +321,12 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
         const bool inside = c < d;
         col[q] = inside ? c : static_cast<int>(d) - 4;
         const vf4 xv = *reinterpret_cast<const vf4*>(x + static_cast<int64_t>(i) * ld + col[q]);
-        xs[q][0] = inside ? xv.x : 0.f; xs[q][1] = inside ? xv.y : 0.f;
-        xs[q][2] = inside ? xv.z : 0.f; xs[q][3] = inside ? xv.w : 0.f;
+        if constexpr (XL) {
+            x_chunks[q * THREADS + threadIdx.x] = inside ? xv : vf4{0.f, 0.f, 0.f, 0.f};
+        } else {
+            xs[q][0] = inside ? xv.x : 0.f; xs[q][1] = inside ? xv.y : 0.f;
+            xs[q][2] = inside ? xv.z : 0.f; xs[q][3] = inside ? xv.w : 0.f;
+        }
         acc[q][0] = acc[q][1] = acc[q][2] = acc[q][3] = 0.0;
     }
     double sq = 0.0;
@@ -323,16 +338,25 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
         load_tile<CPT, R>(t0, a_node, ldA, r0, r1 - 1, col, rows_i, b);
         for (int r = r0; r < r1; r += 2 * R) {
             load_tile<CPT, R>(t1, a_node, ldA, r + R, r1 - 1, col, rows_i, b);
-            consume_tile<CPT, R, WAVES>(t0, xs, acc, sq, red[0], yi, r, r1, lane, wave, rows_i, b);
+            consume_tile<CPT, R, WAVES, XL>(t0, xs, xl, acc, sq, red[0], yi, r, r1, lane, wave, rows_i, b);
             load_tile<CPT, R>(t0, a_node, ldA, r + 2 * R, r1 - 1, col, rows_i, b);
-            consume_tile<CPT, R, WAVES>(t1, xs, acc, sq, red[1], yi, r + R, r1, lane, wave, rows_i, b);
+            consume_tile<CPT, R, WAVES, XL>(t1, xs, xl, acc, sq, red[1], yi, r + R, r1, lane, wave, rows_i, b);
         }
     } else {
         Tile<CPT, R> t0;
         int buf = 0;
         for (int r = r0; r < r1; r += R, buf ^= 1) {
+            if constexpr (XL) {   // the column offsets are worked out per row here: eight registers the kernel lacks
+                int c0 = 4 * static_cast<int>(threadIdx.x);
+                asm volatile("" : "+v"(c0));
+#pragma unroll
+                for (int q = 0; q < CPT; ++q) {
+                    const int c = c0 + 4 * THREADS * q;
+                    col[q] = c < static_cast<int>(d) ? c : static_cast<int>(d) - 4;
+                }
+            }
             load_tile<CPT, R>(t0, a_node, ldA, r, r1 - 1, col, rows_i, b);
-            consume_tile<CPT, R, WAVES>(t0, xs, acc, sq, red[buf], yi, r, r1, lane, wave, rows_i, b);
+            consume_tile<CPT, R, WAVES, XL>(t0, xs, xl, acc, sq, red[buf], yi, r, r1, lane, wave, rows_i, b);
         }
     }
 
@@ -442,7 +466,7 @@ int fused_splits(int32_t n, int32_t b, int64_t d, int rows_per_iteration) {
 // rows consumed per loop iteration (two register tiles of R rows, or one without prefetch)
 int fused_rows(int cpt) { return cpt == 1 ? 8 : cpt == 2 ? 4 : cpt == 4 ? 2 : 1; }
 int fused_cpt(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : 8; }
-constexpr int kMaxFusedD = 16384;   // 1024 threads x 4 chunks of 4 columns
+constexpr int kMaxFusedD = 32768;   // 1024 threads x 8 chunks of 4 columns (from 16385 on with x_i in LDS)
 
 }  // namespace
 
@@ -513,8 +537,25 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
             default:
                 if (d <= 8192)
                     hipLaunchKernelGGL((k_fused<8, 1, false, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
-                else
+                else if (d <= 16384)
                     hipLaunchKernelGGL((k_fused<4, 1, false, 1024>), grid, dim3(1024), 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+                else {
+                    // eight chunks per thread: a row of A (32 registers) and the accumulators (64) fill the thread's 128
+                    // registers, so its 128 bytes of x_i wait in LDS (128 KiB per workgroup, one workgroup per CU)
+                    auto wide = k_fused<8, 1, false, 1024, true>;
+                    static std::atomic<uint64_t> configured{0};   // one bit per device ordinal below 64
+                    int device = 0;
+                    if (int rc = check_hip(hipGetDevice(&device), "hipGetDevice")) return rc;
+                    const uint64_t bit = device >= 0 && device < 64 ? uint64_t{1} << device : uint64_t{0};
+                    if (!(configured.load(std::memory_order_relaxed) & bit) || bit == 0) {
+                        if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(wide),
+                                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024),
+                                               "hipFuncSetAttribute(max dynamic LDS)"))
+                            return rc;
+                        configured.fetch_or(bit, std::memory_order_relaxed);
+                    }
+                    hipLaunchKernelGGL(wide, grid, dim3(1024), 128 * 1024, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+                }
                 break;
         }
         if (int rc = check_hip(hipGetLastError(), "fused gradient kernel launch")) return rc;

@@ -199,9 +199,12 @@ LSQ_CASES = [
     (3, 1000, 1500, 4, 0, 0.001),        # single sweep, 2 chunks per thread, ragged row blocks
     (2, 45, 5000, 0, 0, 1.0),            # single sweep, 8 chunks per thread
     (1, 9, 8200, 0, 0, 1.0),             # 8192 < d <= 16384: single sweep with 1024 threads, 4 chunks each
-    (2, 37, 16384, 0, 0, 0.25),          # the widest single sweep
+    (2, 37, 16384, 0, 0, 0.25),          # the widest with x_i in registers
     (3, 40, 12292, 4, 0, 1.0),           # 1024 threads, last chunk of most threads past d, padded rows
-    (1, 9, 16388, 0, 0, 1.0),            # d > 16384: two sweeps with 16-byte loads, a workgroup per row
+    (1, 9, 16388, 0, 0, 1.0),            # 16384 < d <= 32768: single sweep, 8 chunks per thread, x_i in LDS
+    (2, 20, 32768, 0, 0, 0.5),           # the widest single sweep
+    (3, 33, 20484, 4, 4, 1.0),           # ... with padded rows and most of the last chunks past d
+    (1, 9, 32772, 0, 0, 1.0),            # d > 32768: two sweeps with 16-byte loads, a workgroup per row
     (2, 7, 4099, 1, 3, 1.0),             # few long rows, odd strides: a workgroup per row, 4-byte loads
     (3, 2000, 8196, 0, 0, 1.0),          # many long rows: a wave per row
     (70, 2, 64, 0, 0, 1.0),              # more nodes than rows
