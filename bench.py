@@ -581,6 +581,23 @@ def bench_small(P, workloads, steps=2000, warmup=200):
     return out
 
 
+def bench_lsq_shape(P, n, b, d, steps, warmup):
+    """local_grad_lsq on synthetic N(0,1) data of the given shape: time per call, rate of the 4 n b d bytes of A."""
+    import torch
+
+    A = torch.randn((n, b, d), device="cuda")
+    y = torch.randn((n, b), device="cuda")
+    x = torch.randn((n, d), device="cuda")
+    g = torch.empty_like(x)
+    ws = torch.empty(P.local_grad_lsq_workspace(n, b, d), dtype=torch.uint8, device="cuda")
+    _, ms = time_launches(lambda k: P.local_grad_lsq(A, y, x, g, None, 1.0, ws), steps, warmup)
+    nbytes = 4 * n * b * d
+    del A, y, x, g, ws
+    torch.cuda.empty_cache()
+    return {"ms_per_call": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
 def bench_lsq(P, workloads, name, steps, warmup, calibration_copy=False):
     """Workload 5: local_grad_lsq then decentlam_step per iteration; times the gradient alone too."""
     import numpy as np
@@ -847,6 +864,10 @@ def main():
         extras["decentlam_stats_c3_exp32"] = bench_stats(P, workloads, "c3_exp32", args.steps, args.warmup)
         c5 = bench_lsq(P, workloads, "c5_onepeer64_lsq", args.steps, args.warmup)
         extras["local_grad_lsq_c5"] = c5
+        # rows too wide for the register-resident x_i (16384 < d <= 32768: the sweep's widest form) and beyond (two sweeps)
+        extras["local_grad_lsq_wide_rows"] = {
+            f"n{n}_b{b}_d{d}": bench_lsq_shape(P, n, b, d, args.steps, args.warmup)
+            for n, b, d in ((8, 2048, 32768), (8, 1024, 65536))}
         # the two other large workloads under their own names: iterations per second and fraction of the HBM peak
         c4 = extras.get("decentlam_step_c4_ring16_ragged")
         if c4:
