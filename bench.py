@@ -705,6 +705,12 @@ def main():
         for n in (int(v) for v in args.node_counts.split(",")):
             for kind, name in ((P.DL_TOPO_RING, "ring"), (P.DL_TOPO_EXP_STATIC, "exp_static")):
                 out[f"n{n}_{name}"] = bench_shape(P, n, HEADLINE_ELEMENTS // n, kind, args.steps, args.warmup)
+        if args.calibration_copy:   # one plain device copy of 819.2 M floats: what the counters read for a known size
+            a = torch.empty(HEADLINE_ELEMENTS, dtype=torch.float32, device="cuda").normal_()
+            b = torch.empty_like(a)
+            b.copy_(a)
+            torch.cuda.synchronize()
+            del a, b
         print(json.dumps({"what": "decentlam_step by node count, 819.2 M node-elements, rows on 64 KiB boundaries",
                           "steps": args.steps, "warmup": args.warmup, **out}), flush=True)
         return
