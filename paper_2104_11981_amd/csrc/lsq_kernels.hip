@@ -361,9 +361,11 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
     }
 
     double* out = partial + (static_cast<int64_t>(i) * splits + s) * d;
+    int c_first = 4 * static_cast<int>(threadIdx.x);
+    if constexpr (XL) asm volatile("" : "+v"(c_first));   // worked out again here, not carried through the loop
 #pragma unroll
     for (int q = 0; q < CPT; ++q) {
-        const int c = 4 * static_cast<int>(threadIdx.x) + 4 * THREADS * q;
+        const int c = c_first + 4 * THREADS * q;
         if (c < d) {
             out[c + 0] = acc[q][0]; out[c + 1] = acc[q][1]; out[c + 2] = acc[q][2]; out[c + 3] = acc[q][3];
         }

@@ -164,6 +164,24 @@ def test_two_pass_kernels_keep_every_input_in_registers(tmp_path):
     assert sum(c <= 64 for c in counts) >= 22   # the three- and four-row shapes
 
 
+def test_gradient_sweep_kernels_do_not_spill(tmp_path):
+    """k_fused keeps a row tile of A, its fp64 accumulators and (up to d = 16384) its chunks of x_i in registers; the
+    widest form (d <= 32768, 1024 threads) fills all 128 registers of a lane and keeps x_i in LDS instead.  None of
+    the forms may spill: a spilled tile register would wait for its load the moment it is issued."""
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not installed")
+    from paper_2104_11981_amd import build
+
+    out = tmp_path / "lsq_kernels.s"
+    flags = [f for f in build.FLAGS if f != "-fPIC"]
+    subprocess.run([HIPCC] + flags + ["-S", "--cuda-device-only", os.path.join(build.CSRC, "lsq_kernels.hip"), "-o", str(out)],
+                   check=True, capture_output=True)
+    text = out.read_text()
+    assert len(re.findall(r"^\s*\.amdhsa_kernel\s+\S*k_fused", text, re.M)) >= 6
+    assert not re.search(r"scratch_(load|store)", text)
+    assert not any(int(v) for v in re.findall(r"\.vgpr_spill_count:\s+(\d+)", text))
+
+
 SPLIT_CHECK = r"""
 #include <cstdio>
 #include <vector>
