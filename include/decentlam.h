@@ -461,7 +461,11 @@ int dsgd_step(float* x, const float* g,
  * Deterministic: partial sums are combined in a fixed order.
  * The contraction is a batch of n matrix-vector products with no shared operand (every node has its own
  * A_i and x_i): 1 flop per byte of A at best, so the bound is HBM bandwidth and the kernels are built
- * around one streaming pass over A (rows 16-byte aligned, d <= 32768; otherwise two passes).  Products and sums run as fp64 fused multiply-adds on the vector units; the matrix cores are
+ * around one streaming pass over A.  That pass needs d a multiple of 4, d <= 32768, ldA and ld multiples of 4 and
+ * 16-byte aligned A and x (64 nodes of 4096 x 4096: 0.62 ms, 0.86 of the HBM peak); anything else takes two passes
+ * over A at a third of that rate (d = 4095: 1.9 ms), so pad d itself, not only the strides, where that is possible
+ * (a zero column of A with a zero in x changes nothing).
+ * Products and sums run as fp64 fused multiply-adds on the vector units; the matrix cores are
  * not used: an MFMA tile would have one useful column in sixteen, and for fp32 / fp64 the matrix and
  * vector peaks of this chip are equal.
  * Errors: DL_EINVAL (NULL, n < 1, b < 1, d < 0, ldA < d, ld < d, scale not finite),
