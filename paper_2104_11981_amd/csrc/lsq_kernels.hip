@@ -5,7 +5,8 @@
 // The bound is HBM, and the kernels are organised around streaming A with wide
 // coalesced loads; products are exact in fp64 (two fp32 factors) and sums are fp64.
 //
-// Single sweep (rows 16-byte aligned, d <= 32768; 256 threads up to d = 8192, 1024 beyond): k_fused keeps a tile of R rows of A_i in
+// Single sweep (rows of A and x on 16-byte boundaries, d <= 32768, d a multiple of 4 from 8193 on; 256 threads up
+// to d = 8192, 1024 beyond): k_fused keeps a tile of R rows of A_i in
 // registers, split by columns over the 256 threads of a workgroup; the R residuals are reduced
 // with wavefront shuffles plus one LDS hop, then the same registers feed the transposed
 // product, so A is read from HBM exactly once (4*b*d bytes per node).  The next tile's loads are
@@ -203,20 +204,29 @@ __global__ __launch_bounds__(kThreads) void k_finish(const double* __restrict__ 
 
 
 // ---------------------------------------------------------------- single sweep
+// A value that is the same in every lane, moved to a scalar register (it then costs no vector register).
+__device__ __forceinline__ float uniform_f32(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, v)));
+}
+
 // CPT  16-byte column chunks per thread (thread t owns columns 4t + 4 THREADS q .. +3, q < CPT)
 // R    rows of A per register tile
 template <int CPT, int R>
 struct Tile {
     vf4 a[R][CPT];
+    float tl[R][3];   // TAIL: the row's last d % 4 elements (uniform over the workgroup), zeros after them
 };
 
 // Loads never need a predicate: rows past the block's end are clamped to its last row (their
 // residual is forced to zero below) and column chunks past d are clamped to the last chunk
 // (their x is zero and their accumulators are never stored).
-template <int CPT, int R>
+// TAIL (d not a multiple of 4): the 16-byte chunks cover the first dm = d - d % 4 columns and the last dt = d % 4
+// elements of a row are read one by one from an address that is the same for the whole workgroup, so that no access
+// reaches past column d of any row.
+template <int CPT, int R, bool TAIL = false>
 __device__ __forceinline__ void load_tile(Tile<CPT, R>& t, const float* __restrict__ a_node, int64_t ldA,
                                           int r, int r_last, const int (&col)[CPT],
-                                          const int32_t* __restrict__ rows_i, int b) {
+                                          const int32_t* __restrict__ rows_i, int b, int64_t dm = 0, int dt = 0) {
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
         int row = (r + rr < r_last) ? r + rr : r_last;
@@ -225,15 +235,23 @@ __device__ __forceinline__ void load_tile(Tile<CPT, R>& t, const float* __restri
 #pragma unroll
         for (int q = 0; q < CPT; ++q)
             t.a[rr][q] = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(a_row + col[q]));
+        if constexpr (TAIL) {
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                const float v = a_row[dm + (k < dt ? k : 0)];
+                t.tl[rr][k] = k < dt ? uniform_f32(v) : 0.f;
+            }
+        }
     }
 }
 
 // XL: the thread's chunks of x_i wait in LDS (xl[q * 64 * WAVES], written by this thread) instead of in registers
-template <int CPT, int R, int WAVES, bool XL = false>
+template <int CPT, int R, int WAVES, bool XL = false, bool TAIL = false>
 __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float (&xs)[CPT][4], const vf4* xl,
                                              double (&acc)[CPT][4], double& sq, double (*red)[R],
                                              const float* __restrict__ yi, int r, int r1, int lane, int wave,
-                                             const int32_t* __restrict__ rows_i, int b) {
+                                             const int32_t* __restrict__ rows_i, int b, const float (&xt)[3],
+                                             double (&acc_tail)[3]) {
     double p[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
@@ -275,9 +293,17 @@ __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float 
 #pragma unroll
             for (int w4 = 0; w4 < WAVES; w4 += 4)
                 dot += (red[w4][rr] + red[w4 + 1][rr]) + (red[w4 + 2][rr] + red[w4 + 3][rr]);
+            if constexpr (TAIL) {   // the last d % 4 columns: the same values in every thread
+#pragma unroll
+                for (int k = 0; k < 3; ++k) dot = __builtin_fma(static_cast<double>(t.tl[rr][k]), static_cast<double>(xt[k]), dot);
+            }
             res = dot - static_cast<double>(yi[pr]);
         }
         sq = __builtin_fma(res, res, sq);
+        if constexpr (TAIL) {
+#pragma unroll
+            for (int k = 0; k < 3; ++k) acc_tail[k] = __builtin_fma(static_cast<double>(t.tl[rr][k]), res, acc_tail[k]);
+        }
 #pragma unroll
         for (int q = 0; q < CPT; ++q) {
             acc[q][0] = __builtin_fma(static_cast<double>(u.a[rr][q].x), res, acc[q][0]);
@@ -295,7 +321,7 @@ __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float 
 // 16 nodes of 1024 x 16384 5.75 against 5.94 TB/s, 8 nodes of 4096 x 16384 6.31 against 6.44; up to d = 8192, 512
 // threads with four chunks, with or without prefetch, are slower than 256 with eight: 64 nodes of 1024 x 6144
 // 5.6-5.8 against 6.2 TB/s)
-template <int CPT, int R, bool PF, int THREADS, bool XL = false>
+template <int CPT, int R, bool PF, int THREADS, bool XL = false, bool TAIL = false>
 __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 : 4)) void k_fused(const float* __restrict__ A, const float* __restrict__ y,
                                                      const float* __restrict__ x, double* __restrict__ partial,
                                                      double* __restrict__ sq_partial, int b, int64_t d,
@@ -312,14 +338,26 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
 
     extern __shared__ vf4 x_chunks[];   // XL: CPT * THREADS chunks of x_i, each read only by the thread that wrote it
     const vf4* xl = x_chunks + threadIdx.x;
+    // TAIL: the chunks cover the first dm columns (dm >= 4), the remaining dt = d % 4 are handled element by element
+    const int64_t dm = TAIL ? (d & ~int64_t{3}) : d;
+    const int dt = static_cast<int>(d - dm);
+    float xt[3] = {0.f, 0.f, 0.f};
+    double acc_tail[3] = {0.0, 0.0, 0.0};
+    if constexpr (TAIL) {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            const float v = x[static_cast<int64_t>(i) * ld + dm + (k < dt ? k : 0)];
+            xt[k] = k < dt ? uniform_f32(v) : 0.f;
+        }
+    }
     int col[CPT];
     float xs[CPT][4];
     double acc[CPT][4];
 #pragma unroll
     for (int q = 0; q < CPT; ++q) {
         const int c = 4 * static_cast<int>(threadIdx.x) + 4 * THREADS * q;
-        const bool inside = c < d;
-        col[q] = inside ? c : static_cast<int>(d) - 4;
+        const bool inside = c < dm;
+        col[q] = inside ? c : static_cast<int>(dm) - 4;
         const vf4 xv = *reinterpret_cast<const vf4*>(x + static_cast<int64_t>(i) * ld + col[q]);
         if constexpr (XL) {
             x_chunks[q * THREADS + threadIdx.x] = inside ? xv : vf4{0.f, 0.f, 0.f, 0.f};
@@ -335,12 +373,12 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
 
     if constexpr (PF) {
         Tile<CPT, R> t0, t1;
-        load_tile<CPT, R>(t0, a_node, ldA, r0, r1 - 1, col, rows_i, b);
+        load_tile<CPT, R, TAIL>(t0, a_node, ldA, r0, r1 - 1, col, rows_i, b, dm, dt);
         for (int r = r0; r < r1; r += 2 * R) {
-            load_tile<CPT, R>(t1, a_node, ldA, r + R, r1 - 1, col, rows_i, b);
-            consume_tile<CPT, R, WAVES, XL>(t0, xs, xl, acc, sq, red[0], yi, r, r1, lane, wave, rows_i, b);
-            load_tile<CPT, R>(t0, a_node, ldA, r + 2 * R, r1 - 1, col, rows_i, b);
-            consume_tile<CPT, R, WAVES, XL>(t1, xs, xl, acc, sq, red[1], yi, r + R, r1, lane, wave, rows_i, b);
+            load_tile<CPT, R, TAIL>(t1, a_node, ldA, r + R, r1 - 1, col, rows_i, b, dm, dt);
+            consume_tile<CPT, R, WAVES, XL, TAIL>(t0, xs, xl, acc, sq, red[0], yi, r, r1, lane, wave, rows_i, b, xt, acc_tail);
+            load_tile<CPT, R, TAIL>(t0, a_node, ldA, r + 2 * R, r1 - 1, col, rows_i, b, dm, dt);
+            consume_tile<CPT, R, WAVES, XL, TAIL>(t1, xs, xl, acc, sq, red[1], yi, r + R, r1, lane, wave, rows_i, b, xt, acc_tail);
         }
     } else {
         Tile<CPT, R> t0;
@@ -352,11 +390,11 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
 #pragma unroll
                 for (int q = 0; q < CPT; ++q) {
                     const int c = c0 + 4 * THREADS * q;
-                    col[q] = c < static_cast<int>(d) ? c : static_cast<int>(d) - 4;
+                    col[q] = c < static_cast<int>(dm) ? c : static_cast<int>(dm) - 4;
                 }
             }
-            load_tile<CPT, R>(t0, a_node, ldA, r, r1 - 1, col, rows_i, b);
-            consume_tile<CPT, R, WAVES, XL>(t0, xs, xl, acc, sq, red[buf], yi, r, r1, lane, wave, rows_i, b);
+            load_tile<CPT, R, TAIL>(t0, a_node, ldA, r, r1 - 1, col, rows_i, b, dm, dt);
+            consume_tile<CPT, R, WAVES, XL, TAIL>(t0, xs, xl, acc, sq, red[buf], yi, r, r1, lane, wave, rows_i, b, xt, acc_tail);
         }
     }
 
@@ -366,8 +404,15 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
 #pragma unroll
     for (int q = 0; q < CPT; ++q) {
         const int c = c_first + 4 * THREADS * q;
-        if (c < d) {
+        if (c < dm) {
             out[c + 0] = acc[q][0]; out[c + 1] = acc[q][1]; out[c + 2] = acc[q][2]; out[c + 3] = acc[q][3];
+        }
+    }
+    if constexpr (TAIL) {
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int k = 0; k < 3; ++k)
+                if (k < dt) out[dm + k] = acc_tail[k];
         }
     }
     if (threadIdx.x == 0) sq_partial[static_cast<int64_t>(i) * splits + s] = sq;
@@ -468,12 +513,51 @@ int fused_splits(int32_t n, int32_t b, int64_t d, int rows_per_iteration) {
 // rows consumed per loop iteration (two register tiles of R rows, or one without prefetch)
 int fused_rows(int cpt) { return cpt == 1 ? 8 : cpt == 2 ? 4 : cpt == 4 ? 2 : 1; }
 int fused_cpt(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : 8; }
+constexpr int kMaxFusedTailD = 8192;   // d % 4 != 0: the 256-thread forms only
 constexpr int kMaxFusedD = 32768;   // 1024 threads x 8 chunks of 4 columns (from 16385 on with x_i in LDS)
+
+// The single sweep's kernel by columns per row (TAIL: d is not a multiple of 4).
+template <bool TAIL>
+int launch_fused(int cpt, dim3 grid, hipStream_t stream, const float* A, const float* y, const float* x, double* fpartial,
+                 double* sq_partial, int32_t b, int64_t d, int64_t ldA, int64_t ld, int fs, const int32_t* rows, int32_t bs) {
+    const dim3 block(kThreads);
+    switch (cpt) {
+        case 1: hipLaunchKernelGGL((k_fused<1, 4, true, 256, false, TAIL>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
+        case 2: hipLaunchKernelGGL((k_fused<2, 2, true, 256, false, TAIL>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
+        case 4: hipLaunchKernelGGL((k_fused<4, 1, true, 256, false, TAIL>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
+        default:
+            if (d <= 8192)
+                hipLaunchKernelGGL((k_fused<8, 1, false, 256, false, TAIL>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+            else if constexpr (TAIL)   // the 1024-thread forms have no registers for the tail columns (lsq_path sends such d elsewhere)
+                return set_error(DL_EINVAL, "local_grad_lsq: no single-sweep kernel for this d");
+            else if (d <= 16384)
+                hipLaunchKernelGGL((k_fused<4, 1, false, 1024, false, TAIL>), grid, dim3(1024), 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+            else {
+                // eight chunks per thread: a row of A (32 registers) and the accumulators (64) fill the thread's 128
+                // registers, so its 128 bytes of x_i wait in LDS (128 KiB per workgroup, one workgroup per CU)
+                auto wide = k_fused<8, 1, false, 1024, true, TAIL>;
+                static std::atomic<uint64_t> configured{0};   // one bit per device ordinal below 64
+                int device = 0;
+                if (int rc = check_hip(hipGetDevice(&device), "hipGetDevice")) return rc;
+                const uint64_t bit = device >= 0 && device < 64 ? uint64_t{1} << device : uint64_t{0};
+                if (!(configured.load(std::memory_order_relaxed) & bit) || bit == 0) {
+                    if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(wide),
+                                                               hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024),
+                                           "hipFuncSetAttribute(max dynamic LDS)"))
+                        return rc;
+                    configured.fetch_or(bit, std::memory_order_relaxed);
+                }
+                hipLaunchKernelGGL(wide, grid, dim3(1024), 128 * 1024, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+            }
+            break;
+    }
+    return check_hip(hipGetLastError(), "fused gradient kernel launch");
+}
 
 }  // namespace
 
 bool lsq_wide_accesses(const float* A, const float* x, int64_t d, int64_t ldA, int64_t ld) {
-    return d % 4 == 0 && ldA % 4 == 0 && ld % 4 == 0 &&
+    return ldA % 4 == 0 && ld % 4 == 0 &&
            ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(x)) & 15u) == 0;
 }
 
@@ -497,9 +581,12 @@ size_t lsq_workspace_bytes_path(int32_t n, int32_t b, int64_t d, int path) {
 
 size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d) { return lsq_workspace_bytes_path(n, b, d, -1); }
 
+// wide_accesses: rows of A and x on 16-byte boundaries (lsq_wide_accesses).  The single sweep also takes a d that is
+// not a multiple of 4 (its last d % 4 columns element by element), from d = 8 to 8192.
 int lsq_path(int32_t bs, int64_t d, bool wide_accesses) {
     if (small_problem(bs, d)) return 2;
-    return wide_accesses && d > 0 && d <= kMaxFusedD ? 1 : 0;
+    if (!wide_accesses || d <= 0 || d > kMaxFusedD) return 0;
+    return d % 4 == 0 || (d >= 8 && d <= kMaxFusedTailD) ? 1 : 0;
 }
 
 int launch_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
@@ -509,8 +596,9 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
     double* res = static_cast<double*>(workspace);
     double* partial = res + ((static_cast<size_t>(n) * bs + 1) & ~size_t{1});  // keep 16-byte alignment
     const int splits = row_splits(n, bs, d);
-    const bool vec4 = lsq_wide_accesses(A, x, d, ldA, ld);
-    const int path = lsq_path(bs, d, vec4);
+    const bool aligned_rows = lsq_wide_accesses(A, x, d, ldA, ld);
+    const bool vec4 = aligned_rows && d % 4 == 0;   // the two sweeps' 16-byte loads need whole chunks
+    const int path = lsq_path(bs, d, aligned_rows);
     if (n > 65535 || splits > 65535) return set_error(DL_EINVAL, "local_grad_lsq: n too large for the launch grid");
 
     const dim3 block(kThreads);
@@ -532,35 +620,9 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
         double* sq_partial = static_cast<double*>(workspace);
         double* fpartial = sq_partial + ((static_cast<size_t>(n) * fs + 1) & ~size_t{1});
         const dim3 grid(static_cast<unsigned>(fs), static_cast<unsigned>(n));
-        switch (cpt) {
-            case 1: hipLaunchKernelGGL((k_fused<1, 4, true, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
-            case 2: hipLaunchKernelGGL((k_fused<2, 2, true, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
-            case 4: hipLaunchKernelGGL((k_fused<4, 1, true, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
-            default:
-                if (d <= 8192)
-                    hipLaunchKernelGGL((k_fused<8, 1, false, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
-                else if (d <= 16384)
-                    hipLaunchKernelGGL((k_fused<4, 1, false, 1024>), grid, dim3(1024), 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
-                else {
-                    // eight chunks per thread: a row of A (32 registers) and the accumulators (64) fill the thread's 128
-                    // registers, so its 128 bytes of x_i wait in LDS (128 KiB per workgroup, one workgroup per CU)
-                    auto wide = k_fused<8, 1, false, 1024, true>;
-                    static std::atomic<uint64_t> configured{0};   // one bit per device ordinal below 64
-                    int device = 0;
-                    if (int rc = check_hip(hipGetDevice(&device), "hipGetDevice")) return rc;
-                    const uint64_t bit = device >= 0 && device < 64 ? uint64_t{1} << device : uint64_t{0};
-                    if (!(configured.load(std::memory_order_relaxed) & bit) || bit == 0) {
-                        if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(wide),
-                                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024),
-                                               "hipFuncSetAttribute(max dynamic LDS)"))
-                            return rc;
-                        configured.fetch_or(bit, std::memory_order_relaxed);
-                    }
-                    hipLaunchKernelGGL(wide, grid, dim3(1024), 128 * 1024, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
-                }
-                break;
-        }
-        if (int rc = check_hip(hipGetLastError(), "fused gradient kernel launch")) return rc;
+        if (int rc = d % 4 == 0 ? launch_fused<false>(cpt, grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs)
+                                : launch_fused<true>(cpt, grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs))
+            return rc;
         const dim3 grid_ff(static_cast<unsigned>((d + kFinishColumns - 1) / kFinishColumns), static_cast<unsigned>(n));
         hipLaunchKernelGGL(k_finish_fused, grid_ff, block, 0, stream, fpartial, sq_partial, g, loss, d, ld, fs,
                            static_cast<double>(scale));

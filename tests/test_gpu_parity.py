@@ -208,6 +208,13 @@ LSQ_CASES = [
     (2, 7, 4099, 1, 3, 1.0),             # few long rows, odd strides: a workgroup per row, 4-byte loads
     (3, 2000, 8196, 0, 0, 1.0),          # many long rows: a wave per row
     (70, 2, 64, 0, 0, 1.0),              # more nodes than rows
+    # d not a multiple of 4 with rows on 16-byte boundaries: single sweep, the last d % 4 columns element by element
+    (3, 100, 1030, 2, 2, 1.0),           # two tail columns, 2 chunks per thread
+    (2, 300, 4099, 1, 1, 0.5),           # three tail columns, 8 chunks per thread
+    (1, 64, 8191, 1, 1, 1.0),            # the widest such d
+    (4, 70, 257, 3, 3, 1.0),             # one tail column
+    (1, 2000, 9, 3, 3, 1.0),             # two chunks and a tail column in all
+    (2, 40, 8197, 3, 3, 1.0),            # beyond 8192 such d take the two sweeps with 4-byte loads
 ]
 
 
