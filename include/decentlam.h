@@ -462,7 +462,7 @@ int dsgd_step(float* x, const float* g,
  * The contraction is a batch of n matrix-vector products with no shared operand (every node has its own
  * A_i and x_i): 1 flop per byte of A at best, so the bound is HBM bandwidth and the kernels are built
  * around one streaming pass over A.  That pass needs rows on 16-byte boundaries (ldA and ld multiples of 4, A and x
- * 16-byte aligned) and d <= 32768, d a multiple of 4 from 8193 on (64 nodes of 4096 x 4096: 0.62 ms, 0.86 of the HBM
+ * 16-byte aligned) and d <= 32768 (64 nodes of 4096 x 4096: 0.62 ms, 0.86 of the HBM
  * peak; 4096 x 4095 with ldA = 4096: 0.63 ms); anything else takes two passes over A at a third of that rate
  * (4096 x 4095 with ldA = 4095: 1.9 ms), so pad the row strides where that is possible.  No access reaches past
  * column d of a row in either case.

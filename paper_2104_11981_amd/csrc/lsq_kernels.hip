@@ -5,8 +5,8 @@
 // The bound is HBM, and the kernels are organised around streaming A with wide
 // coalesced loads; products are exact in fp64 (two fp32 factors) and sums are fp64.
 //
-// Single sweep (rows of A and x on 16-byte boundaries, d <= 32768, d a multiple of 4 from 8193 on; 256 threads up
-// to d = 8192, 1024 beyond): k_fused keeps a tile of R rows of A_i in
+// Single sweep (rows of A and x on 16-byte boundaries, d <= 32768; 256 threads up to d = 8192, 1024 beyond):
+// k_fused keeps a tile of R rows of A_i in
 // registers, split by columns over the 256 threads of a workgroup; the R residuals are reduced
 // with wavefront shuffles plus one LDS hop, then the same registers feed the transposed
 // product, so A is read from HBM exactly once (4*b*d bytes per node).  The next tile's loads are
@@ -251,7 +251,7 @@ __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float 
                                              double (&acc)[CPT][4], double& sq, double (*red)[R],
                                              const float* __restrict__ yi, int r, int r1, int lane, int wave,
                                              const int32_t* __restrict__ rows_i, int b, const float (&xt)[3],
-                                             double (&acc_tail)[3]) {
+                                             double (&acc_tail)[3], double* tail_sums) {
     double p[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
@@ -295,14 +295,24 @@ __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float 
                 dot += (red[w4][rr] + red[w4 + 1][rr]) + (red[w4 + 2][rr] + red[w4 + 3][rr]);
             if constexpr (TAIL) {   // the last d % 4 columns: the same values in every thread
 #pragma unroll
-                for (int k = 0; k < 3; ++k) dot = __builtin_fma(static_cast<double>(t.tl[rr][k]), static_cast<double>(xt[k]), dot);
+                for (int k = 0; k < 3; ++k) {
+                    float xk = xt[k];
+                    asm volatile("" : "+s"(xk));   // widened here, row by row: three doubles kept across the loop are registers the wide forms lack
+                    dot = __builtin_fma(static_cast<double>(t.tl[rr][k]), static_cast<double>(xk), dot);
+                }
             }
             res = dot - static_cast<double>(yi[pr]);
         }
         sq = __builtin_fma(res, res, sq);
         if constexpr (TAIL) {
 #pragma unroll
-            for (int k = 0; k < 3; ++k) acc_tail[k] = __builtin_fma(static_cast<double>(t.tl[rr][k]), res, acc_tail[k]);
+            for (int k = 0; k < 3; ++k) {
+                if constexpr (WAVES > 4) {   // the 1024-thread forms have no registers to spare: thread 0 keeps the sums in LDS
+                    if (threadIdx.x == 0) tail_sums[k] = __builtin_fma(static_cast<double>(t.tl[rr][k]), res, tail_sums[k]);
+                } else {
+                    acc_tail[k] = __builtin_fma(static_cast<double>(t.tl[rr][k]), res, acc_tail[k]);
+                }
+            }
         }
 #pragma unroll
         for (int q = 0; q < CPT; ++q) {
@@ -343,6 +353,8 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
     const int dt = static_cast<int>(d - dm);
     float xt[3] = {0.f, 0.f, 0.f};
     double acc_tail[3] = {0.0, 0.0, 0.0};
+    __shared__ double tail_sums[3];   // TAIL with 1024 threads: thread 0's sums (nobody else touches them)
+    if (TAIL && WAVES > 4 && threadIdx.x == 0) tail_sums[0] = tail_sums[1] = tail_sums[2] = 0.0;
     if constexpr (TAIL) {
 #pragma unroll
         for (int k = 0; k < 3; ++k) {
@@ -376,9 +388,9 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
         load_tile<CPT, R, TAIL>(t0, a_node, ldA, r0, r1 - 1, col, rows_i, b, dm, dt);
         for (int r = r0; r < r1; r += 2 * R) {
             load_tile<CPT, R, TAIL>(t1, a_node, ldA, r + R, r1 - 1, col, rows_i, b, dm, dt);
-            consume_tile<CPT, R, WAVES, XL, TAIL>(t0, xs, xl, acc, sq, red[0], yi, r, r1, lane, wave, rows_i, b, xt, acc_tail);
+            consume_tile<CPT, R, WAVES, XL, TAIL>(t0, xs, xl, acc, sq, red[0], yi, r, r1, lane, wave, rows_i, b, xt, acc_tail, tail_sums);
             load_tile<CPT, R, TAIL>(t0, a_node, ldA, r + 2 * R, r1 - 1, col, rows_i, b, dm, dt);
-            consume_tile<CPT, R, WAVES, XL, TAIL>(t1, xs, xl, acc, sq, red[1], yi, r + R, r1, lane, wave, rows_i, b, xt, acc_tail);
+            consume_tile<CPT, R, WAVES, XL, TAIL>(t1, xs, xl, acc, sq, red[1], yi, r + R, r1, lane, wave, rows_i, b, xt, acc_tail, tail_sums);
         }
     } else {
         Tile<CPT, R> t0;
@@ -394,13 +406,13 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
                 }
             }
             load_tile<CPT, R, TAIL>(t0, a_node, ldA, r, r1 - 1, col, rows_i, b, dm, dt);
-            consume_tile<CPT, R, WAVES, XL, TAIL>(t0, xs, xl, acc, sq, red[buf], yi, r, r1, lane, wave, rows_i, b, xt, acc_tail);
+            consume_tile<CPT, R, WAVES, XL, TAIL>(t0, xs, xl, acc, sq, red[buf], yi, r, r1, lane, wave, rows_i, b, xt, acc_tail, tail_sums);
         }
     }
 
     double* out = partial + (static_cast<int64_t>(i) * splits + s) * d;
     int c_first = 4 * static_cast<int>(threadIdx.x);
-    if constexpr (XL) asm volatile("" : "+v"(c_first));   // worked out again here, not carried through the loop
+    if constexpr (THREADS > 256) asm volatile("" : "+v"(c_first));   // worked out again here, not carried through the loop
 #pragma unroll
     for (int q = 0; q < CPT; ++q) {
         const int c = c_first + 4 * THREADS * q;
@@ -412,7 +424,7 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
         if (threadIdx.x == 0) {
 #pragma unroll
             for (int k = 0; k < 3; ++k)
-                if (k < dt) out[dm + k] = acc_tail[k];
+                if (k < dt) out[dm + k] = WAVES > 4 ? tail_sums[k] : acc_tail[k];
         }
     }
     if (threadIdx.x == 0) sq_partial[static_cast<int64_t>(i) * splits + s] = sq;
@@ -513,7 +525,6 @@ int fused_splits(int32_t n, int32_t b, int64_t d, int rows_per_iteration) {
 // rows consumed per loop iteration (two register tiles of R rows, or one without prefetch)
 int fused_rows(int cpt) { return cpt == 1 ? 8 : cpt == 2 ? 4 : cpt == 4 ? 2 : 1; }
 int fused_cpt(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : 8; }
-constexpr int kMaxFusedTailD = 8192;   // d % 4 != 0: the 256-thread forms only
 constexpr int kMaxFusedD = 32768;   // 1024 threads x 8 chunks of 4 columns (from 16385 on with x_i in LDS)
 
 // The single sweep's kernel by columns per row (TAIL: d is not a multiple of 4).
@@ -528,8 +539,6 @@ int launch_fused(int cpt, dim3 grid, hipStream_t stream, const float* A, const f
         default:
             if (d <= 8192)
                 hipLaunchKernelGGL((k_fused<8, 1, false, 256, false, TAIL>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
-            else if constexpr (TAIL)   // the 1024-thread forms have no registers for the tail columns (lsq_path sends such d elsewhere)
-                return set_error(DL_EINVAL, "local_grad_lsq: no single-sweep kernel for this d");
             else if (d <= 16384)
                 hipLaunchKernelGGL((k_fused<4, 1, false, 1024, false, TAIL>), grid, dim3(1024), 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
             else {
@@ -582,11 +591,11 @@ size_t lsq_workspace_bytes_path(int32_t n, int32_t b, int64_t d, int path) {
 size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d) { return lsq_workspace_bytes_path(n, b, d, -1); }
 
 // wide_accesses: rows of A and x on 16-byte boundaries (lsq_wide_accesses).  The single sweep also takes a d that is
-// not a multiple of 4 (its last d % 4 columns element by element), from d = 8 to 8192.
+// not a multiple of 4 (its last d % 4 columns element by element), from d = 8 on.
 int lsq_path(int32_t bs, int64_t d, bool wide_accesses) {
     if (small_problem(bs, d)) return 2;
     if (!wide_accesses || d <= 0 || d > kMaxFusedD) return 0;
-    return d % 4 == 0 || (d >= 8 && d <= kMaxFusedTailD) ? 1 : 0;
+    return d % 4 == 0 || d >= 8 ? 1 : 0;
 }
 
 int launch_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,

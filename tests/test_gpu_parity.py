@@ -211,10 +211,13 @@ LSQ_CASES = [
     # d not a multiple of 4 with rows on 16-byte boundaries: single sweep, the last d % 4 columns element by element
     (3, 100, 1030, 2, 2, 1.0),           # two tail columns, 2 chunks per thread
     (2, 300, 4099, 1, 1, 0.5),           # three tail columns, 8 chunks per thread
-    (1, 64, 8191, 1, 1, 1.0),            # the widest such d
+    (1, 64, 8191, 1, 1, 1.0),            # the widest with 256 threads
     (4, 70, 257, 3, 3, 1.0),             # one tail column
     (1, 2000, 9, 3, 3, 1.0),             # two chunks and a tail column in all
-    (2, 40, 8197, 3, 3, 1.0),            # beyond 8192 such d take the two sweeps with 4-byte loads
+    (2, 40, 8197, 3, 3, 1.0),            # 1024 threads: the tail sums kept in LDS by thread 0
+    (2, 21, 20001, 3, 3, 1.0),           # ... with x_i in LDS as well
+    (1, 12, 32767, 1, 1, 1.0),           # the widest such d
+    (1, 12, 32769, 3, 3, 1.0),           # beyond: two sweeps with 4-byte loads
 ]
 
 
