@@ -427,7 +427,10 @@ def test_decentlam_stays_bounded_on_symmetric_graphs(P):
 # ---------------------------------------------------------------- mini-batch gradient
 @pytest.mark.parametrize("n,b,d,bs,pad", [(8, 1024, 1024, 64, 0), (3, 40, 132, 7, 0), (2, 50, 33, 20, 1),
                                           (4, 300, 2500, 33, 0), (2, 100, 5000, 9, 0), (1, 5, 8200, 5, 0),
-                                          (5, 64, 1500, 200, 0)])
+                                          (5, 64, 1500, 200, 0),
+                                          (2, 30, 16388, 11, 0),      # 1024 threads, x_i in LDS
+                                          (3, 60, 1030, 25, 2),       # d % 4 = 2 with rows on 16-byte boundaries: tail columns
+                                          (1, 20, 20001, 9, 3)])      # both
 def test_local_grad_lsq_rows_matches_oracle(P, oracle, n, b, d, bs, pad):
     rng = np.random.default_rng(n * 1000 + bs)
     A0 = rng.standard_normal((n, b, d)).astype(np.float32)
