@@ -461,11 +461,12 @@ int dsgd_step(float* x, const float* g,
  * Deterministic: partial sums are combined in a fixed order.
  * The contraction is a batch of n matrix-vector products with no shared operand (every node has its own
  * A_i and x_i): 1 flop per byte of A at best, so the bound is HBM bandwidth and the kernels are built
- * around one streaming pass over A.  That pass needs rows on 16-byte boundaries (ldA and ld multiples of 4, A and x
- * 16-byte aligned) and d <= 32768 (64 nodes of 4096 x 4096: 0.62 ms, 0.86 of the HBM
- * peak; 4096 x 4095 with ldA = 4096: 0.63 ms); anything else takes two passes over A at a third of that rate
- * (4096 x 4095 with ldA = 4095: 1.9 ms), so pad the row strides where that is possible.  No access reaches past
- * column d of a row in either case.
+ * around one streaming pass over A.  That pass is fastest with the rows of A on 16-byte boundaries (ldA a multiple
+ * of 4, A 16-byte aligned; x and g may lie anywhere) and d <= 32768 (64 nodes of 4096 x 4096: 0.62 ms, 0.86 of the
+ * HBM peak; 4096 x 4095 with ldA = 4096: 0.63 ms).  Rows of A on 8-byte boundaries only (8 nodes of 4096 x 7850,
+ * contiguous: 0.19 ms, 0.67) or on none (4096 x 4095 with ldA = 4095: 1.05 ms, 0.51) are still read once, with
+ * narrower accesses, up to d = 16384, so pad ldA where that is possible.  Wider rows than these limits take two
+ * passes over A at 0.3-0.35 of the peak.  No access reaches past column d of a row in any case.
  * Products and sums run as fp64 fused multiply-adds on the vector units; the matrix cores are
  * not used: an MFMA tile would have one useful column in sixteen, and for fp32 / fp64 the matrix and
  * vector peaks of this chip are equal.
@@ -485,7 +486,7 @@ int local_grad_lsq(const float* A, const float* y, const float* x,
  * the library's device image (every GPU the library runs on holds its own copy until the process
  * ends).  The call allocates nothing and frees nothing.
  *   Limit: the partial sums of the kernels this shape and alignment select must fit
- *   DL_STATIC_SCRATCH_BYTES (32 MiB).  With rows on 16-byte boundaries and d <= 32768 (one sweep over A)
+ *   DL_STATIC_SCRATCH_BYTES (32 MiB).  With one sweep over A (see local_grad_lsq)
  *   that is about n * max(1, 512 / n) * (d + 1) * 8 bytes (n = 64 nodes of 4096 x 4096: 16.8 MB), never
  *   more than local_grad_lsq_workspace(n, b, d).  Larger problems return DL_ECAP (nothing is launched)
  *   and belong to local_grad_lsq.

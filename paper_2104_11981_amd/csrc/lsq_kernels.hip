@@ -5,7 +5,8 @@
 // The bound is HBM, and the kernels are organised around streaming A with wide
 // coalesced loads; products are exact in fp64 (two fp32 factors) and sums are fp64.
 //
-// Single sweep (rows of A and x on 16-byte boundaries, d <= 32768; 256 threads up to d = 8192, 1024 beyond):
+// Single sweep (rows of A on 16-byte boundaries, d <= 32768; 256 threads up to d = 8192, 1024 beyond; rows of A
+// on other boundaries: k_fused_narrow below, d <= 16384):
 // k_fused keeps a tile of R rows of A_i in
 // registers, split by columns over the 256 threads of a workgroup; the R residuals are reduced
 // with wavefront shuffles plus one LDS hop, then the same registers feed the transposed
@@ -365,12 +366,15 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
     int col[CPT];
     float xs[CPT][4];
     double acc[CPT][4];
+    // x_i is read once per workgroup: its rows need not be on 16-byte boundaries, only A's
+    const bool x_wide = ((reinterpret_cast<uintptr_t>(x) & 15u) | (static_cast<uint64_t>(ld) & 3u)) == 0;
 #pragma unroll
     for (int q = 0; q < CPT; ++q) {
         const int c = 4 * static_cast<int>(threadIdx.x) + 4 * THREADS * q;
         const bool inside = c < dm;
         col[q] = inside ? c : static_cast<int>(dm) - 4;
-        const vf4 xv = *reinterpret_cast<const vf4*>(x + static_cast<int64_t>(i) * ld + col[q]);
+        const float* xp = x + static_cast<int64_t>(i) * ld + col[q];
+        const vf4 xv = x_wide ? *reinterpret_cast<const vf4*>(xp) : vf4{xp[0], xp[1], xp[2], xp[3]};
         if constexpr (XL) {
             x_chunks[q * THREADS + threadIdx.x] = inside ? xv : vf4{0.f, 0.f, 0.f, 0.f};
         } else {
@@ -427,6 +431,138 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
                 if (k < dt) out[dm + k] = WAVES > 4 ? tail_sums[k] : acc_tail[k];
         }
     }
+    if (threadIdx.x == 0) sq_partial[static_cast<int64_t>(i) * splits + s] = sq;
+}
+
+// The single sweep for rows of A that are not on 16-byte boundaries (ldA not a multiple of 4, or a base that is
+// not 16-byte aligned): the same structure as k_fused with 8-byte (V = 2: rows on 8-byte boundaries) or 4-byte
+// (V = 1: any rows) accesses, K columns per thread in K / V chunks, R rows per tile, no prefetch.  A is still read
+// once; what the narrow accesses cost is rate (8 nodes of 4096 x 7850, contiguous: 0.19 ms, 0.67 of the HBM peak,
+// against 0.17 ms with ldA = 7852 in k_fused and 0.49 ms in two sweeps; 64 nodes of 4096 x 4095 with ldA = 4095:
+// 1.05 ms, 0.51, against 1.93 ms), not a second pass.  V = 2 with an odd d: thread 0 takes the last column by itself.
+template <int V, int K, int R, int THREADS>
+__global__ __launch_bounds__(THREADS) void k_fused_narrow(const float* __restrict__ A, const float* __restrict__ y,
+                                                           const float* __restrict__ x, double* __restrict__ partial,
+                                                           double* __restrict__ sq_partial, int b, int64_t d,
+                                                           int64_t ldA, int64_t ld, int splits,
+                                                           const int32_t* __restrict__ rows, int bs) {
+    constexpr int CPT = K / V, WAVES = THREADS / 64;
+    typedef float vfv __attribute__((ext_vector_type(V)));
+    __shared__ double red[2][WAVES][R];
+    const int i = blockIdx.y, s = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r0 = static_cast<int>(static_cast<int64_t>(bs) * s / splits);
+    const int r1 = static_cast<int>(static_cast<int64_t>(bs) * (s + 1) / splits);
+    const int32_t* __restrict__ rows_i = rows ? rows + static_cast<int64_t>(i) * bs : nullptr;
+    const int dm = static_cast<int>(d - d % V);            // columns covered by whole chunks
+    const bool tail = V == 2 && dm < d && threadIdx.x == 0;   // one more column, thread 0's
+
+    // chunk q of this thread: columns column_of(q) .. + V - 1, clamped to the last whole chunk (whose x is zero here and
+    // whose sums are never stored); worked out where it is used rather than kept: CPT registers the wide forms lack
+    const int last_chunk = dm >= V ? dm - V : 0;
+    const auto column_of = [&](int q) {
+        int c0 = V * static_cast<int>(threadIdx.x);
+        asm volatile("" : "+v"(c0));
+        const int c = c0 + V * THREADS * q;
+        return c < dm ? c : last_chunk;
+    };
+    float xs[CPT][V];
+    double acc[CPT][V];
+    const float* __restrict__ xi = x + static_cast<int64_t>(i) * ld;
+#pragma unroll
+    for (int q = 0; q < CPT; ++q) {
+        const int c = V * static_cast<int>(threadIdx.x) + V * THREADS * q;
+        const bool inside = c < dm;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const float xv = dm >= V ? xi[(inside ? c : last_chunk) + v] : 0.f;
+            xs[q][v] = inside ? xv : 0.f;
+            acc[q][v] = 0.0;
+        }
+    }
+    const float x_tail = tail ? xi[dm] : 0.f;
+    double acc_tail = 0.0, sq = 0.0;
+    const float* __restrict__ a_node = A + static_cast<int64_t>(i) * b * ldA;
+    const float* __restrict__ yi = y + static_cast<int64_t>(i) * b;
+
+    int buf = 0;
+    for (int r = r0; r < r1; r += R, buf ^= 1) {
+        float a[R][CPT][V], a_tail[R];
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+            int row = (r + rr < r1 - 1) ? r + rr : r1 - 1;
+            if (rows_i) row = physical_row(rows_i, row, b);
+            const float* __restrict__ a_row = a_node + static_cast<int64_t>(row) * ldA;
+#pragma unroll
+            for (int q = 0; q < CPT; ++q) {
+                if (dm >= V) {   // uniform
+                    const vfv t = __builtin_nontemporal_load(reinterpret_cast<const vfv*>(a_row + column_of(q)));
+#pragma unroll
+                    for (int v = 0; v < V; ++v) a[rr][q][v] = t[v];
+                } else {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) a[rr][q][v] = 0.f;
+                }
+            }
+            a_tail[rr] = tail ? a_row[dm] : 0.f;
+        }
+        double p[R];
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+            double s0 = 0.0;
+#pragma unroll
+            for (int q = 0; q < CPT; ++q) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) s0 = __builtin_fma(static_cast<double>(a[rr][q][v]), static_cast<double>(xs[q][v]), s0);
+            }
+            s0 = __builtin_fma(static_cast<double>(a_tail[rr]), static_cast<double>(x_tail), s0);   // zero but in thread 0
+            p[rr] = wave_sum(s0);
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr) red[buf][wave][rr] = p[rr];
+        }
+        __syncthreads();
+        // the transposed product widens the tile again: keeping the first product's fp64 copies alive across the
+        // barrier would double the tile's registers
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+#pragma unroll
+            for (int q = 0; q < CPT; ++q) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) asm volatile("" : "+v"(a[rr][q][v]));
+            }
+        }
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+            double res = 0.0;
+            if (r + rr < r1) {   // uniform over the workgroup
+                const int pr = rows_i ? physical_row(rows_i, r + rr, b) : r + rr;
+                double dot = 0.0;   // the waves' shares in a fixed order
+#pragma unroll
+                for (int w = 0; w < WAVES; ++w) dot += red[buf][w][rr];
+                res = dot - static_cast<double>(yi[pr]);
+            }
+            sq = __builtin_fma(res, res, sq);
+#pragma unroll
+            for (int q = 0; q < CPT; ++q) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[q][v] = __builtin_fma(static_cast<double>(a[rr][q][v]), res, acc[q][v]);
+            }
+            acc_tail = __builtin_fma(static_cast<double>(a_tail[rr]), res, acc_tail);
+        }
+    }
+    double* out = partial + (static_cast<int64_t>(i) * splits + s) * d;
+#pragma unroll
+    for (int q = 0; q < CPT; ++q) {
+        const int c = V * static_cast<int>(threadIdx.x) + V * THREADS * q;
+        if (c < dm) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) out[c + v] = acc[q][v];
+        }
+    }
+    if (tail) out[dm] = acc_tail;
     if (threadIdx.x == 0) sq_partial[static_cast<int64_t>(i) * splits + s] = sq;
 }
 
@@ -525,6 +661,7 @@ int fused_splits(int32_t n, int32_t b, int64_t d, int rows_per_iteration) {
 // rows consumed per loop iteration (two register tiles of R rows, or one without prefetch)
 int fused_rows(int cpt) { return cpt == 1 ? 8 : cpt == 2 ? 4 : cpt == 4 ? 2 : 1; }
 int fused_cpt(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : 8; }
+constexpr int kMaxNarrowD = 16384;  // rows off the 16-byte boundaries: 1024 threads x 16 columns
 constexpr int kMaxFusedD = 32768;   // 1024 threads x 8 chunks of 4 columns (from 16385 on with x_i in LDS)
 
 // The single sweep's kernel by columns per row (TAIL: d is not a multiple of 4).
@@ -563,11 +700,30 @@ int launch_fused(int cpt, dim3 grid, hipStream_t stream, const float* A, const f
     return check_hip(hipGetLastError(), "fused gradient kernel launch");
 }
 
+// The single sweep with narrow accesses, by columns per row (V = 2: rows on 8-byte boundaries, V = 1: any).
+template <int V>
+int launch_fused_narrow(dim3 grid, hipStream_t stream, const float* A, const float* y, const float* x, double* fpartial,
+                        double* sq_partial, int32_t b, int64_t d, int64_t ldA, int64_t ld, int fs, const int32_t* rows,
+                        int32_t bs) {
+    const dim3 block(kThreads);
+    if (d <= 1024)
+        hipLaunchKernelGGL((k_fused_narrow<V, 4, 4, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+    else if (d <= 2048)
+        hipLaunchKernelGGL((k_fused_narrow<V, 8, 2, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+    else if (d <= 4096)
+        hipLaunchKernelGGL((k_fused_narrow<V, 16, 1, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+    else if (d <= 8192)
+        hipLaunchKernelGGL((k_fused_narrow<V, 32, 1, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+    else
+        hipLaunchKernelGGL((k_fused_narrow<V, 16, 1, 1024>), grid, dim3(1024), 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+    return check_hip(hipGetLastError(), "fused gradient kernel launch (narrow accesses)");
+}
+
 }  // namespace
 
 bool lsq_wide_accesses(const float* A, const float* x, int64_t d, int64_t ldA, int64_t ld) {
-    return ldA % 4 == 0 && ld % 4 == 0 &&
-           ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(x)) & 15u) == 0;
+    (void)x; (void)d; (void)ld;   // the single sweep reads x_i once per workgroup, at whatever alignment it has
+    return ldA % 4 == 0 && (reinterpret_cast<uintptr_t>(A) & 15u) == 0;
 }
 
 // b = rows actually used per node.  path: 0 the two-sweep kernels, 1 the single sweep, 2 the small-problem kernel
@@ -590,11 +746,14 @@ size_t lsq_workspace_bytes_path(int32_t n, int32_t b, int64_t d, int path) {
 
 size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d) { return lsq_workspace_bytes_path(n, b, d, -1); }
 
-// wide_accesses: rows of A and x on 16-byte boundaries (lsq_wide_accesses).  The single sweep also takes a d that is
-// not a multiple of 4 (its last d % 4 columns element by element), from d = 8 on.
+// wide_accesses: rows of A on 16-byte boundaries (lsq_wide_accesses).  The single sweep also takes a d that is
+// not a multiple of 4 (its last d % 4 columns element by element), from d = 8 on, and, up to d = 16384 and with
+// narrower accesses, rows that are not on such boundaries.
 int lsq_path(int32_t bs, int64_t d, bool wide_accesses) {
     if (small_problem(bs, d)) return 2;
-    if (!wide_accesses || d <= 0 || d > kMaxFusedD) return 0;
+    if (d <= 0) return 0;
+    if (!wide_accesses) return d <= kMaxNarrowD ? 1 : 0;   // narrow accesses, same workspace layout
+    if (d > kMaxFusedD) return 0;
     return d % 4 == 0 || d >= 8 ? 1 : 0;
 }
 
@@ -606,7 +765,8 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
     double* partial = res + ((static_cast<size_t>(n) * bs + 1) & ~size_t{1});  // keep 16-byte alignment
     const int splits = row_splits(n, bs, d);
     const bool aligned_rows = lsq_wide_accesses(A, x, d, ldA, ld);
-    const bool vec4 = aligned_rows && d % 4 == 0;   // the two sweeps' 16-byte loads need whole chunks
+    // the two sweeps' 16-byte loads need whole chunks, of x_i too
+    const bool vec4 = aligned_rows && d % 4 == 0 && ld % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
     const int path = lsq_path(bs, d, aligned_rows);
     if (n > 65535 || splits > 65535) return set_error(DL_EINVAL, "local_grad_lsq: n too large for the launch grid");
 
@@ -629,9 +789,16 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
         double* sq_partial = static_cast<double*>(workspace);
         double* fpartial = sq_partial + ((static_cast<size_t>(n) * fs + 1) & ~size_t{1});
         const dim3 grid(static_cast<unsigned>(fs), static_cast<unsigned>(n));
-        if (int rc = d % 4 == 0 ? launch_fused<false>(cpt, grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs)
-                                : launch_fused<true>(cpt, grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs))
-            return rc;
+        int rc;
+        if (!aligned_rows) {
+            const bool even = ldA % 2 == 0 && (reinterpret_cast<uintptr_t>(A) & 7u) == 0;
+            rc = even ? launch_fused_narrow<2>(grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs)
+                      : launch_fused_narrow<1>(grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+        } else {
+            rc = d % 4 == 0 ? launch_fused<false>(cpt, grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs)
+                            : launch_fused<true>(cpt, grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+        }
+        if (rc) return rc;
         const dim3 grid_ff(static_cast<unsigned>((d + kFinishColumns - 1) / kFinishColumns), static_cast<unsigned>(n));
         hipLaunchKernelGGL(k_finish_fused, grid_ff, block, 0, stream, fpartial, sq_partial, g, loss, d, ld, fs,
                            static_cast<double>(scale));

@@ -218,6 +218,15 @@ LSQ_CASES = [
     (2, 21, 20001, 3, 3, 1.0),           # ... with x_i in LDS as well
     (1, 12, 32767, 1, 1, 1.0),           # the widest such d
     (1, 12, 32769, 3, 3, 1.0),           # beyond: two sweeps with 4-byte loads
+    # rows that are not on 16-byte boundaries: single sweep with 8-byte (even ldA) or 4-byte accesses, up to d = 16384
+    (2, 300, 7850, 0, 0, 1.0),           # contiguous, even d: 8-byte accesses, 32 columns per thread
+    (2, 100, 4095, 0, 0, 1.0),           # odd stride: 4-byte accesses, 16 columns per thread
+    (3, 50, 1001, 0, 0, 0.5),            # 4 columns per thread, 4 rows per tile, ragged row blocks
+    (2, 64, 2047, 1, 0, 1.0),            # 8-byte accesses with an odd d: thread 0 takes the last column
+    (2, 40, 12290, 0, 0, 1.0),           # 1024 threads, 8-byte accesses
+    (1, 30, 16383, 0, 0, 1.0),           # 1024 threads, 4-byte accesses, the widest
+    (1, 30, 16385, 0, 0, 1.0),           # beyond: two sweeps
+    (5, 3, 1500, 2, 1, 1.0),             # fewer rows than a tile holds
 ]
 
 
@@ -246,6 +255,35 @@ def test_local_grad_lsq_matches_oracle(P, oracle, n, b, d, padA, pad, scale):
     g2 = torch.zeros_like(gb)[:, :d]
     P.local_grad_lsq(A, dev(y0), x, g2, None, scale, ws)
     assert torch.equal(g2, g)
+
+
+@pytest.mark.parametrize("n,b,d,ldA,offA,offx,offg", [(2, 40, 3000, 3000, 1, 0, 0),     # 4-byte aligned A only
+                                                      (2, 40, 3000, 3000, 2, 1, 3),     # 8-byte aligned A, odd x, g
+                                                      (3, 25, 1021, 1024, 3, 2, 1),     # aligned stride, odd base
+                                                      (2, 20, 9001, 9004, 4, 1, 2),     # aligned A, x and g are not
+                                                      (1, 10, 20001, 20002, 1, 1, 1)])  # two sweeps
+def test_local_grad_lsq_on_views_off_the_16_byte_grid(P, oracle, n, b, d, ldA, offA, offx, offg):
+    """Any 4-byte aligned base is accepted for A, x and g; the kernels pick narrower accesses."""
+    rng = np.random.default_rng(5 * d + offA)
+    A0 = rng.standard_normal((n, b, d)).astype(np.float32)
+    y0 = rng.standard_normal((n, b)).astype(np.float32)
+    x0 = rng.standard_normal((n, d)).astype(np.float32)
+    Abuf = torch.full((offA + n * b * ldA,), 7.0, dtype=torch.float32, device="cuda")
+    A = Abuf[offA:].view(n, b, ldA)[:, :, :d]
+    A.copy_(dev(A0))
+    ld = d + 5
+    xbuf = torch.full((offx + n * ld,), 7.0, dtype=torch.float32, device="cuda")
+    gbuf = torch.full((offg + n * ld,), 7.0, dtype=torch.float32, device="cuda")
+    x, g = xbuf[offx:].view(n, ld)[:, :d], gbuf[offg:].view(n, ld)[:, :d]
+    x.copy_(dev(x0))
+    loss = torch.empty(n, dtype=torch.float32, device="cuda")
+    ws = torch.empty(P.local_grad_lsq_workspace(n, b, d), dtype=torch.uint8, device="cuda")
+    P.local_grad_lsq(A, dev(y0), x, g, loss, 1.0, ws)
+    gr, lr = oracle.lsq_grad(A0, y0, x0, 1.0)
+    check_elementwise(g.cpu().numpy(), gr, "g")
+    check_elementwise(loss.cpu().numpy(), lr, "loss")
+    whole = gbuf.cpu().numpy()
+    assert np.all(whole[:offg] == 7.0) and np.all(whole[offg:].reshape(n, ld)[:, d:] == 7.0)
 
 
 @pytest.mark.parametrize("name,ring", [("c2_onepeer8_b32", False), ("c2_onepeer8_b1024", False),
@@ -430,7 +468,8 @@ def test_decentlam_stays_bounded_on_symmetric_graphs(P):
                                           (5, 64, 1500, 200, 0),
                                           (2, 30, 16388, 11, 0),      # 1024 threads, x_i in LDS
                                           (3, 60, 1030, 25, 2),       # d % 4 = 2 with rows on 16-byte boundaries: tail columns
-                                          (1, 20, 20001, 9, 3)])      # both
+                                          (1, 20, 20001, 9, 3),       # both
+                                          (2, 80, 3001, 17, 0)])      # rows off the 16-byte boundaries: 4-byte accesses
 def test_local_grad_lsq_rows_matches_oracle(P, oracle, n, b, d, bs, pad):
     rng = np.random.default_rng(n * 1000 + bs)
     A0 = rng.standard_normal((n, b, d)).astype(np.float32)

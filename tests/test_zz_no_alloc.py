@@ -43,10 +43,11 @@ def _run_both(A0, y0, x0, scale):
     return out
 
 
-# first call, then a smaller one: a single-sweep shape and then the small-problem kernel; a two-sweep
-# shape (rows not 16-byte aligned) and then a narrower single sweep
+# first call, then a smaller one: a single-sweep shape and then the small-problem kernel; the single sweep
+# with 4-byte accesses (rows not 16-byte aligned) and then a narrower one with 16-byte accesses; a two-sweep
+# shape (such rows, more than 16384 columns) and then a single sweep
 @pytest.mark.parametrize("shapes", [((8, 96, 1024), (3, 20, 100)), ((5, 33, 1001), (4, 16, 512)),
-                                    ((64, 256, 4096), (8, 32, 1024))])
+                                    ((2, 20, 16387), (2, 12, 2048)), ((64, 256, 4096), (8, 32, 1024))])
 def test_static_scratch_call_matches_workspace_call_twice_in_a_row(oracle, shapes):
     rng = np.random.default_rng(11981)
     for n, b, d in shapes:
