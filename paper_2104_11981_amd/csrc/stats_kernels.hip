@@ -3,7 +3,8 @@
 // setting for linear regression" is out[2] / (n * out[3])), and ||m||_F^2.
 //
 // HBM-bound, one pass: a thread owns VEC columns and walks down the n rows (a wave reads
-// 64*VEC contiguous columns of one row per access).  Per column it keeps shifted sums around
+// 64*VEC contiguous columns of one row per access; in large calls two runs of 128 columns 32 KiB
+// apart, see SPLIT below).  Per column it keeps shifted sums around
 // the first row's value p: s1 = sum_i (x_i - p), s2 = sum_i (x_i - p)^2, so that
 // sum_i (x_i - xbar)^2 = s2 - s1^2 / n without the cancellation of the raw-moment formula.
 // Partial sums go wave shuffle -> LDS -> one slot per workgroup; k_stats_finish adds the
@@ -11,14 +12,18 @@
 #include <type_traits>
 
 #include "internal.hpp"
+#include "step_impl.hpp"
 
 namespace dl {
 namespace {
 
 constexpr int kThreads = 256;
 constexpr int kOut = 5;
+constexpr int64_t kSplitMinColumns = 1 << 20;   // below this a call keeps the plain order (as the step kernel does)
 constexpr int64_t kMaxBlocks = 32768;          // workgroups per launch (see blocks_for)
-constexpr int64_t kSlotPitch = 2 * kMaxBlocks;  // partial sums in the workspace: [output][slot], body launch then tail launch
+// partial sums in the workspace: [output][slot]; the launches of one call follow one another: the body in the
+// split order (or all of it in plain order), up to two short plain launches around it, the tail
+constexpr int64_t kSlotPitch = 2 * kMaxBlocks + 64;
 typedef float vf4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ double wave_sum(double v) {
@@ -38,35 +43,42 @@ __device__ __forceinline__ void load_cols(const float* __restrict__ p, float (&v
 }
 
 // HAS_M, HAS_REF: whether m and ref are given (compile-time, so that no load sits behind a test).
-// Rows are taken kRows at a time: all their loads go out before the first one is used (rows past the
+// Rows are taken ROWS at a time: all their loads go out before the first one is used (rows past the
 // last are clamped to it for the load and skipped in the sums).
-constexpr int kRows = 8;
-template <int VEC, bool HAS_M, bool HAS_REF>
-__global__ __launch_bounds__(kThreads) void k_stats(const float* __restrict__ x, const float* __restrict__ m,
+// SPLIT (VEC = 4, d a multiple of 16384, x + c on 64 KiB boundaries for c = 0 in every row that matters): a wave's
+// 256 columns are the two 512-byte segments 32 KiB apart of the step kernel's split tiles (step::split_column)
+// instead of one run of 1 KiB: the order in which this GPU's memory streams at the same rate on every machine.
+//
+// Two shapes: 256 threads with 8 rows in flight, and for the launches over a million columns and more 1024 threads
+// with 4 (the same bytes in flight per CU, a quarter of the workgroups and partial sums: 0.975 against 0.99 ms on
+// 32 x 25.6 M).
+template <int VEC, bool HAS_M, bool HAS_REF, bool SPLIT, int THREADS, int ROWS>
+__global__ __launch_bounds__(THREADS) void k_stats(const float* __restrict__ x, const float* __restrict__ m,
                                                      const float* __restrict__ ref, int n, int64_t d,
                                                      int64_t ld, double* __restrict__ slots) {
-    __shared__ double red[kThreads / 64][kOut];
+    __shared__ double red[THREADS / 64][kOut];
     double acc[kOut] = {0.0, 0.0, 0.0, 0.0, 0.0};
-    // a workgroup walks over every gridDim.x-th block of kThreads * VEC columns: the number of
+    // a workgroup walks over every gridDim.x-th block of THREADS * VEC columns: the number of
     // partial-sum slots stays small whatever d is, and the mapping is fixed, so sums are reproducible
-    for (int64_t c = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * VEC; c < d;
-         c += static_cast<int64_t>(gridDim.x) * kThreads * VEC) {  // d is a multiple of VEC for this launch
+    for (int64_t c0 = (static_cast<int64_t>(blockIdx.x) * THREADS + threadIdx.x) * VEC; c0 < d;
+         c0 += static_cast<int64_t>(gridDim.x) * THREADS * VEC) {  // d is a multiple of VEC for this launch
+        const int64_t c = SPLIT ? step::split_column(static_cast<uint32_t>(c0 >> 8), static_cast<int>(threadIdx.x & 63)) : c0;
         float pv[VEC], rv[VEC];
         load_cols<VEC>(x + c, pv);
         if constexpr (HAS_REF) load_cols<VEC>(ref + c, rv);
         double s1[VEC], s2[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) s1[v] = s2[v] = 0.0;
-        for (int i0 = 0; i0 < n; i0 += kRows) {
-            float xv[kRows][VEC], mv[kRows][VEC];
+        for (int i0 = 0; i0 < n; i0 += ROWS) {
+            float xv[ROWS][VEC], mv[ROWS][VEC];
 #pragma unroll
-            for (int r = 0; r < kRows; ++r) {
+            for (int r = 0; r < ROWS; ++r) {
                 const int64_t i = i0 + r < n ? i0 + r : n - 1;
                 load_cols<VEC>(x + i * ld + c, xv[r]);
                 if constexpr (HAS_M) load_cols<VEC>(m + i * ld + c, mv[r]);
             }
 #pragma unroll
-            for (int r = 0; r < kRows; ++r) {
+            for (int r = 0; r < ROWS; ++r) {
                 if (i0 + r < n) {   // uniform
 #pragma unroll
                     for (int v = 0; v < VEC; ++v) {
@@ -104,7 +116,10 @@ __global__ __launch_bounds__(kThreads) void k_stats(const float* __restrict__ x,
     __syncthreads();
     if (threadIdx.x < kOut) {
         const int q = threadIdx.x;
-        slots[q * kSlotPitch + blockIdx.x] = (red[0][q] + red[1][q]) + (red[2][q] + red[3][q]);   // one array per output
+        double total = 0.0;
+#pragma unroll
+        for (int w = 0; w < THREADS / 64; w += 4) total += (red[w][q] + red[w + 1][q]) + (red[w + 2][q] + red[w + 3][q]);
+        slots[q * kSlotPitch + blockIdx.x] = total;   // one array per output
     }
 }
 
@@ -139,8 +154,8 @@ __global__ __launch_bounds__(kFinishThreads) void k_stats_finish(const double* _
 // Many more workgroups than fit the chip at once, each with one block of columns while d allows: with
 // 8192 workgroups of three or four blocks each (25.6 M columns) the last of them ran on a nearly empty
 // chip and the kernel took 1.07 instead of 1.01 ms.
-int64_t blocks_for(int64_t cols, int vec) {
-    const int64_t blocks = (cols + static_cast<int64_t>(kThreads) * vec - 1) / (static_cast<int64_t>(kThreads) * vec);
+int64_t blocks_for(int64_t cols, int vec, int threads) {
+    const int64_t blocks = (cols + static_cast<int64_t>(threads) * vec - 1) / (static_cast<int64_t>(threads) * vec);
     return blocks < kMaxBlocks ? blocks : kMaxBlocks;
 }
 
@@ -158,26 +173,57 @@ int launch_stats(const float* x, const float* m, const float* ref, int32_t n, in
                                           reinterpret_cast<uintptr_t>(ref)) & 15u) == 0;
     const int64_t body = vec4 ? (d / 4) * 4 : 0;
     const int64_t tail = d - body;
-    const int64_t nb_body = blocks_for(body, 4), nb_tail = blocks_for(tail, 1);
-    auto launch = [&](auto vec_tag, int64_t blocks, const float* xp, const float* mp, const float* rp, int64_t cols,
-                      double* out_slots) {
+    int64_t used = 0;   // slots handed out so far
+    // columns [first, first + cols) in one launch; split: in the split order (cols a multiple of 16384)
+    auto launch = [&](auto vec_tag, auto split_tag, int64_t first, int64_t cols) {
         constexpr int V = decltype(vec_tag)::value;
-        const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
-        if (mp && rp) hipLaunchKernelGGL((k_stats<V, true, true>), grid, block, 0, stream, xp, mp, rp, n, cols, ld, out_slots);
-        else if (mp) hipLaunchKernelGGL((k_stats<V, true, false>), grid, block, 0, stream, xp, mp, rp, n, cols, ld, out_slots);
-        else if (rp) hipLaunchKernelGGL((k_stats<V, false, true>), grid, block, 0, stream, xp, mp, rp, n, cols, ld, out_slots);
-        else hipLaunchKernelGGL((k_stats<V, false, false>), grid, block, 0, stream, xp, mp, rp, n, cols, ld, out_slots);
+        constexpr bool S = decltype(split_tag)::value;
+        const bool big = V == 4 && (S || cols >= kSplitMinColumns);   // every split launch is a big one
+        const int64_t blocks = blocks_for(cols, V, big ? 1024 : kThreads);
+        if (blocks == 0) return 0;
+        const float* xp = x + first;
+        const float* mp = m ? m + first : nullptr;
+        const float* rp = ref ? ref + first : nullptr;
+        double* out_slots = slots + used;
+        used += blocks;
+        const dim3 grid(static_cast<unsigned>(blocks));
+        auto go = [&](auto has_m, auto has_ref) {
+            constexpr bool M = decltype(has_m)::value, R = decltype(has_ref)::value;
+            if constexpr (V == 4) {
+                if (big) {
+                    hipLaunchKernelGGL((k_stats<4, M, R, S, 1024, 4>), grid, dim3(1024), 0, stream, xp, mp, rp, n, cols, ld, out_slots);
+                    return;
+                }
+            }
+            if constexpr (!S)   // the split order is for the big launches only
+                hipLaunchKernelGGL((k_stats<V, M, R, false, kThreads, 8>), grid, dim3(kThreads), 0, stream, xp, mp, rp, n, cols, ld, out_slots);
+        };
+        if (mp && rp) go(std::true_type(), std::true_type());
+        else if (mp) go(std::true_type(), std::false_type());
+        else if (rp) go(std::false_type(), std::true_type());
+        else go(std::false_type(), std::false_type());
         return check_hip(hipGetLastError(), "stats kernel launch");
     };
-    if (nb_body > 0) {
-        if (int rc = launch(std::integral_constant<int, 4>(), nb_body, x, m, ref, body, slots)) return rc;
+    const std::integral_constant<int, 4> wide;
+    const std::integral_constant<int, 1> narrow;
+    // Large states whose rows share their offset inside a 128-byte line: the whole 64 KiB units of x go out in
+    // the split order (the bulk, first), the columns before and after them in plain order.
+    int64_t pre = 0, units = 0;
+    if (body >= kSplitMinColumns && ld % 32 == 0) {
+        const uintptr_t at = reinterpret_cast<uintptr_t>(x) % (4u * step::kSplitUnit);
+        pre = at ? static_cast<int64_t>((4u * step::kSplitUnit - at) / 4) : 0;
+        units = (body - pre) / step::kSplitUnit;
     }
-    if (nb_tail > 0) {
-        if (int rc = launch(std::integral_constant<int, 1>(), nb_tail, x + body, m ? m + body : nullptr,
-                            ref ? ref + body : nullptr, tail, slots + nb_body))
-            return rc;
+    if (units > 0) {
+        const int64_t mid = units * step::kSplitUnit;
+        if (int rc = launch(wide, std::true_type(), pre, mid)) return rc;
+        if (int rc = launch(wide, std::false_type(), 0, pre)) return rc;
+        if (int rc = launch(wide, std::false_type(), pre + mid, body - pre - mid)) return rc;
+    } else if (int rc = launch(wide, std::false_type(), 0, body)) {
+        return rc;
     }
-    hipLaunchKernelGGL(k_stats_finish, dim3(kOut), dim3(kFinishThreads), 0, stream, slots, nb_body + nb_tail, out);
+    if (int rc = launch(narrow, std::false_type(), body, tail)) return rc;
+    hipLaunchKernelGGL(k_stats_finish, dim3(kOut), dim3(kFinishThreads), 0, stream, slots, used, out);
     return check_hip(hipGetLastError(), "stats finish kernel launch");
 }
 

@@ -352,7 +352,10 @@ def test_workload2_trajectory_200_steps(P, oracle, name, ring, algo):
 
 # ---------------------------------------------------------------- diagnostics
 @pytest.mark.parametrize("n,d,pad,off", [(8, 1000, 0, 0), (32, 4099, 1, 0), (5, 7, 0, 0), (16, 2048, 4, 1),
-                                         (1, 300, 0, 0), (64, 513, 3, 0), (13, 777, 3, 0), (100, 132, 0, 0)])
+                                         (1, 300, 0, 0), (64, 513, 3, 0), (13, 777, 3, 0), (100, 132, 0, 0),
+                                         # large states: whole 64 KiB units in the split order, plain launches
+                                         # before and after them, a tail of three columns
+                                         (3, 2**20 + 40003, 25, 4), (2, 2**20 + 16384, 0, 0), (2, 2**20, 28, 4)])
 def test_stats_match_oracle(P, oracle, n, d, pad, off):
     rng = np.random.default_rng(n + d)
     x0 = (rng.standard_normal((n, d)) * 0.01 + rng.standard_normal(d) * 5.0).astype(np.float32)  # near consensus
