@@ -874,6 +874,10 @@ def main():
         extras["local_grad_lsq_wide_rows"] = {
             f"n{n}_b{b}_d{d}": bench_lsq_shape(P, n, b, d, args.steps, args.warmup)
             for n, b, d in ((8, 2048, 32768), (8, 1024, 65536))}
+        # short rows: a wave per row (or per two rows)
+        extras["local_grad_lsq_short_rows"] = {
+            f"n{n}_b{b}_d{d}": bench_lsq_shape(P, n, b, d, args.steps, args.warmup)
+            for n, b, d in ((64, 4096, 1024), (64, 32768, 128))}
         # contiguous A whose rows are not on 16-byte boundaries: on 8-byte ones (even d) and on none (odd d)
         extras["local_grad_lsq_rows_off_16_byte_boundaries"] = {
             f"n{n}_b{b}_d{d}": bench_lsq_shape(P, n, b, d, args.steps, args.warmup)

@@ -465,7 +465,8 @@ int dsgd_step(float* x, const float* g,
  * of 4, A 16-byte aligned; x and g may lie anywhere) and d <= 32768 (64 nodes of 4096 x 4096: 0.62 ms, 0.86 of the
  * HBM peak; 4096 x 4095 with ldA = 4096: 0.63 ms).  Rows of A on 8-byte boundaries only (8 nodes of 4096 x 7850,
  * contiguous: 0.19 ms, 0.67) or on none (4096 x 4095 with ldA = 4095: 1.05 ms, 0.51) are still read once, with
- * narrower accesses, up to d = 16384, so pad ldA where that is possible.  Wider rows than these limits take two
+ * narrower accesses, up to d = 16384, so pad ldA where that is possible.  Rows of up to 1024 columns are handled a
+ * wave per row (64 nodes of 32768 x 128: 0.78 of the peak, of 4096 x 1024: 0.85), at any alignment.  Wider rows than these limits take two
  * passes over A at 0.3-0.35 of the peak.  No access reaches past column d of a row in any case.
  * Products and sums run as fp64 fused multiply-adds on the vector units; the matrix cores are
  * not used: an MFMA tile would have one useful column in sixteen, and for fp32 / fp64 the matrix and
@@ -487,7 +488,8 @@ int local_grad_lsq(const float* A, const float* y, const float* x,
  * ends).  The call allocates nothing and frees nothing.
  *   Limit: the partial sums of the kernels this shape and alignment select must fit
  *   DL_STATIC_SCRATCH_BYTES (32 MiB).  With one sweep over A (see local_grad_lsq)
- *   that is about n * max(1, 512 / n) * (d + 1) * 8 bytes (n = 64 nodes of 4096 x 4096: 16.8 MB), never
+ *   that is about n * max(1, 512 / n) * (d + 1) * 8 bytes (n = 64 nodes of 4096 x 4096: 16.8 MB; up to d = 256,
+ *   where 2048 takes the place of 512, at most 4.2 MB), never
  *   more than local_grad_lsq_workspace(n, b, d).  Larger problems return DL_ECAP (nothing is launched)
  *   and belong to local_grad_lsq.
  *   All calls on one GPU share that GPU's array: calls that may overlap in time (different streams,

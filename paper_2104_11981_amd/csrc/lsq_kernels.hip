@@ -5,8 +5,9 @@
 // The bound is HBM, and the kernels are organised around streaming A with wide
 // coalesced loads; products are exact in fp64 (two fp32 factors) and sums are fp64.
 //
-// Single sweep (rows of A on 16-byte boundaries, d <= 32768; 256 threads up to d = 8192, 1024 beyond; rows of A
-// on other boundaries: k_fused_narrow below, d <= 16384):
+// Single sweep (rows of A on 16-byte boundaries, 1024 < d <= 32768; 256 threads up to d = 8192, 1024 beyond; rows of
+// A on other boundaries: k_fused_narrow below, d <= 16384; rows of up to 1024 columns: k_fused_rows below, a wave
+// per row):
 // k_fused keeps a tile of R rows of A_i in
 // registers, split by columns over the 256 threads of a workgroup; the R residuals are reduced
 // with wavefront shuffles plus one LDS hop, then the same registers feed the transposed
@@ -434,6 +435,112 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
     if (threadIdx.x == 0) sq_partial[static_cast<int64_t>(i) * splits + s] = sq;
 }
 
+// The single sweep for short rows (d <= 1024): a wave owns whole rows, so a row's residual is a sum over lanes -- no
+// LDS hop and no barrier inside the loop, which is what holds k_fused back on short rows (one barrier per 4 rows of
+// 4 KiB at d = 1024, and a workgroup of 256 threads with most of its lanes idle below that).  L lanes share a row
+// (64: the wave reads one row per access with CPW chunks per lane; 8, 16, 32: one chunk per lane and 64 / L
+// consecutive rows per access), R accesses are in flight per lane.  A chunk is V columns: 4 (rows of A on 16-byte
+// boundaries, d a multiple of 4), 2 (rows on 8-byte boundaries, d even) or 1 (anything).  The four waves of a
+// workgroup take consecutive groups of rows, so that a contiguous A is read in contiguous pieces, and add their sums
+// up through LDS once, at the end of the row block.
+template <int V, int CPW, int L, int R>
+__global__ __launch_bounds__(256) void k_fused_rows(const float* __restrict__ A, const float* __restrict__ y,
+                                                    const float* __restrict__ x, double* __restrict__ partial,
+                                                    double* __restrict__ sq_partial, int b, int64_t d,
+                                                    int64_t ldA, int64_t ld, int splits,
+                                                    const int32_t* __restrict__ rows, int bs) {
+    static_assert(L == 64 || CPW == 1, "several chunks per lane only when a row fills the wave");
+    typedef float vfv __attribute__((ext_vector_type(V)));
+    constexpr int G = 64 / L;       // rows per wave-wide access
+    constexpr int STEP = 4 * G;     // rows per workgroup-wide access
+    constexpr int COLS = V * L * CPW;
+    __shared__ double sums[STEP][COLS];
+    __shared__ double sq_wave[4];
+    const int i = blockIdx.y, s = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int sub = lane & (L - 1), slot = wave * G + lane / L;
+    const int r0 = static_cast<int>(static_cast<int64_t>(bs) * s / splits);
+    const int r1 = static_cast<int>(static_cast<int64_t>(bs) * (s + 1) / splits);
+    const int32_t* __restrict__ rows_i = rows ? rows + static_cast<int64_t>(i) * bs : nullptr;
+
+    // chunk q of this lane: columns V (sub + q L) .. + V - 1; chunks past d read column 0 with x = 0, never stored
+    int col[CPW];
+    float xs[CPW][V];
+    double acc[CPW][V];
+#pragma unroll
+    for (int q = 0; q < CPW; ++q) {
+        const int c = V * (sub + q * L);
+        const bool inside = c < d;   // d is a multiple of V
+        col[q] = inside ? c : 0;
+        const float* xp = x + static_cast<int64_t>(i) * ld + col[q];   // x_i is read once: element by element
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            xs[q][v] = inside ? xp[v] : 0.f;
+            acc[q][v] = 0.0;
+        }
+    }
+    double sq = 0.0;
+    const float* __restrict__ a_node = A + static_cast<int64_t>(i) * b * ldA;
+    const float* __restrict__ yi = y + static_cast<int64_t>(i) * b;
+
+    for (int r = r0; r < r1; r += STEP * R) {
+        vfv a[R][CPW];
+        float yv[R];
+        // all loads first; rows past the block's end read its last row and count for nothing
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const int row = r + j * STEP + slot;
+            int pr = row < r1 ? row : r1 - 1;
+            if (rows_i) pr = physical_row(rows_i, pr, b);
+            const float* __restrict__ a_row = a_node + static_cast<int64_t>(pr) * ldA;
+#pragma unroll
+            for (int q = 0; q < CPW; ++q) a[j][q] = __builtin_nontemporal_load(reinterpret_cast<const vfv*>(a_row + col[q]));
+            yv[j] = yi[pr];
+        }
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+            for (int q = 0; q < CPW; ++q) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    double& sv = ((q * V + v) & 1) ? s1 : s0;
+                    sv = __builtin_fma(static_cast<double>(a[j][q][v]), static_cast<double>(xs[q][v]), sv);
+                }
+            }
+            double dot = s0 + s1;
+#pragma unroll
+            for (int off = L / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off, 64);   // every lane of the row has the sum
+            const double res = r + j * STEP + slot < r1 ? dot - static_cast<double>(yv[j]) : 0.0;
+            if (sub == 0) sq = __builtin_fma(res, res, sq);
+#pragma unroll
+            for (int q = 0; q < CPW; ++q) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[q][v] = __builtin_fma(static_cast<double>(a[j][q][v]), res, acc[q][v]);
+            }
+        }
+    }
+
+    // the STEP row slots of the workgroup hold sums over disjoint rows for the same columns: add them in slot order
+#pragma unroll
+    for (int q = 0; q < CPW; ++q) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) sums[slot][V * (sub + q * L) + v] = acc[q][v];
+    }
+    sq = wave_sum(sq);
+    if (lane == 0) sq_wave[wave] = sq;
+    __syncthreads();
+    double* out = partial + (static_cast<int64_t>(i) * splits + s) * d;
+    for (int c = threadIdx.x; c < d; c += 256) {
+        double total = 0.0;
+#pragma unroll
+        for (int k = 0; k < STEP; ++k) total += sums[k][c];
+        out[c] = total;
+    }
+    if (threadIdx.x == 0) sq_partial[static_cast<int64_t>(i) * splits + s] = (sq_wave[0] + sq_wave[1]) + (sq_wave[2] + sq_wave[3]);
+}
+
 // The single sweep for rows of A that are not on 16-byte boundaries (ldA not a multiple of 4, or a base that is
 // not 16-byte aligned): the same structure as k_fused with 8-byte (V = 2: rows on 8-byte boundaries) or 4-byte
 // (V = 1: any rows) accesses, K columns per thread in K / V chunks, R rows per tile, no prefetch.  A is still read
@@ -647,8 +754,12 @@ __global__ __launch_bounds__(kThreads) void k_small(const float* __restrict__ A,
 // reads again, as much traffic as four rows of A each way.  Measured, workgroups in total 128 / 256 / 512 / 1024:
 // 8 nodes of 1024 x 1024: 26.7 / 16.5 / 14.8 / 17.4 us; 8 nodes of 256 x 4096: 17.0 / 14.8 / 21.0 / 24.7 us;
 // 64 nodes of 4096 x 4096: 1312 / 747 / 624 / 691 us; 16 nodes of 1024 x 16384: 292 / 185 / 201 / 231 us.
+// Short rows (k_fused_rows) have fewer bytes in flight per workgroup and want more of them: 64 nodes of
+// 32768 x 128 with 512 / 1024 / 2048 / 4096 workgroups 224 / 175 / 173 / 175 us, of 16384 x 256 216 / 172 / 170 / 179,
+// 4 nodes of 100000 x 300 115 / 86 / 86 / 86, but 64 nodes of 8192 x 512 165 / 166 / 172 / 183 and of 4096 x 1024
+// 158 / 182 / 182 / 194.
 int fused_splits(int32_t n, int32_t b, int64_t d, int rows_per_iteration) {
-    const int64_t resident = d > 8192 ? 256 : 512;
+    const int64_t resident = d > 8192 ? 256 : d > 384 ? 512 : d > 256 ? 1024 : 2048;
     int64_t s = (resident + n / 2) / n;
     const int64_t rows_each = rows_per_iteration > 8 ? rows_per_iteration : 8;
     const int64_t most = (b + rows_each - 1) / rows_each;
@@ -658,11 +769,38 @@ int fused_splits(int32_t n, int32_t b, int64_t d, int rows_per_iteration) {
     return static_cast<int>(s);
 }
 
-// rows consumed per loop iteration (two register tiles of R rows, or one without prefetch)
-int fused_rows(int cpt) { return cpt == 1 ? 8 : cpt == 2 ? 4 : cpt == 4 ? 2 : 1; }
-int fused_cpt(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : 8; }
+// rows consumed per loop iteration: by a workgroup of k_fused_rows in its 16-byte shapes up to d = 1024, then two
+// register tiles of R rows, or one without prefetch
+int fused_rows(int64_t d) {
+    return d <= 32 ? 256 : d <= 64 ? 128 : d <= 128 ? 64 : d <= 256 ? 32 : d <= 512 ? 16 : d <= 1024 ? 8 : d <= 2048 ? 4 : d <= 4096 ? 2 : 1;
+}
+int fused_cpt(int64_t d) { return d <= 2048 ? 2 : d <= 4096 ? 4 : 8; }   // beyond the short rows
 constexpr int kMaxNarrowD = 16384;  // rows off the 16-byte boundaries: 1024 threads x 16 columns
 constexpr int kMaxFusedD = 32768;   // 1024 threads x 8 chunks of 4 columns (from 16385 on with x_i in LDS)
+
+// Short rows: a wave per row (or per 2, 4, 8 rows); V columns per access and lane.
+constexpr int kMaxRowsKernelD = 1024;
+template <int V>
+int launch_fused_rows(dim3 grid, hipStream_t stream, const float* A, const float* y, const float* x, double* fpartial,
+                      double* sq_partial, int32_t b, int64_t d, int64_t ldA, int64_t ld, int fs, const int32_t* rows,
+                      int32_t bs) {
+    const dim3 block(256);
+    const int64_t chunks = (d + V - 1) / V;
+#define DL_ROWS_KERNEL(CPW, L, R) \
+    hipLaunchKernelGGL((k_fused_rows<V, CPW, L, R>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs)
+    if (chunks <= 8) DL_ROWS_KERNEL(1, 8, 8);
+    else if (chunks <= 16) DL_ROWS_KERNEL(1, 16, 8);
+    else if (chunks <= 32) DL_ROWS_KERNEL(1, 32, 8);
+    else if (chunks <= 64) DL_ROWS_KERNEL(1, 64, 8);
+    else if (chunks <= 128) DL_ROWS_KERNEL(2, 64, 4);
+    else if (chunks <= 256) DL_ROWS_KERNEL(4, 64, 2);
+    else if constexpr (V < 4) {
+        if (chunks <= 512) DL_ROWS_KERNEL(8, 64, 1);
+        else if constexpr (V < 2) DL_ROWS_KERNEL(16, 64, 1);
+    }
+#undef DL_ROWS_KERNEL
+    return check_hip(hipGetLastError(), "fused gradient kernel launch (short rows)");
+}
 
 // The single sweep's kernel by columns per row (TAIL: d is not a multiple of 4).
 template <bool TAIL>
@@ -670,7 +808,6 @@ int launch_fused(int cpt, dim3 grid, hipStream_t stream, const float* A, const f
                  double* sq_partial, int32_t b, int64_t d, int64_t ldA, int64_t ld, int fs, const int32_t* rows, int32_t bs) {
     const dim3 block(kThreads);
     switch (cpt) {
-        case 1: hipLaunchKernelGGL((k_fused<1, 4, true, 256, false, TAIL>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
         case 2: hipLaunchKernelGGL((k_fused<2, 2, true, 256, false, TAIL>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
         case 4: hipLaunchKernelGGL((k_fused<4, 1, true, 256, false, TAIL>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
         default:
@@ -706,9 +843,7 @@ int launch_fused_narrow(dim3 grid, hipStream_t stream, const float* A, const flo
                         double* sq_partial, int32_t b, int64_t d, int64_t ldA, int64_t ld, int fs, const int32_t* rows,
                         int32_t bs) {
     const dim3 block(kThreads);
-    if (d <= 1024)
-        hipLaunchKernelGGL((k_fused_narrow<V, 4, 4, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
-    else if (d <= 2048)
+    if (d <= 2048)   // (up to 1024: k_fused_rows)
         hipLaunchKernelGGL((k_fused_narrow<V, 8, 2, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
     else if (d <= 4096)
         hipLaunchKernelGGL((k_fused_narrow<V, 16, 1, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
@@ -735,7 +870,7 @@ size_t lsq_workspace_bytes_path(int32_t n, int32_t b, int64_t d, int path) {
     const size_t two_sweeps = (res + partial) * sizeof(double) + 16;
     size_t fused = 0;
     if (d > 0 && d <= kMaxFusedD) {
-        const size_t fs = static_cast<size_t>(fused_splits(n, b, d, fused_rows(fused_cpt(d))));
+        const size_t fs = static_cast<size_t>(fused_splits(n, b, d, fused_rows(d)));
         fused = (static_cast<size_t>(n) * fs * (static_cast<size_t>(d) + 1)) * sizeof(double) + 16;
     }
     if (path == 0) return two_sweeps;
@@ -752,9 +887,9 @@ size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d) { return lsq_workspa
 int lsq_path(int32_t bs, int64_t d, bool wide_accesses) {
     if (small_problem(bs, d)) return 2;
     if (d <= 0) return 0;
+    if (d <= kMaxRowsKernelD) return 1;                     // a wave per row, any alignment
     if (!wide_accesses) return d <= kMaxNarrowD ? 1 : 0;   // narrow accesses, same workspace layout
-    if (d > kMaxFusedD) return 0;
-    return d % 4 == 0 || d >= 8 ? 1 : 0;
+    return d <= kMaxFusedD ? 1 : 0;
 }
 
 int launch_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
@@ -785,13 +920,20 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
     }
     if (path == 1) {
         const int cpt = fused_cpt(d);
-        const int fs = fused_splits(n, bs, d, fused_rows(cpt));
+        const int fs = fused_splits(n, bs, d, fused_rows(d));
         double* sq_partial = static_cast<double*>(workspace);
         double* fpartial = sq_partial + ((static_cast<size_t>(n) * fs + 1) & ~size_t{1});
         const dim3 grid(static_cast<unsigned>(fs), static_cast<unsigned>(n));
         int rc;
-        if (!aligned_rows) {
-            const bool even = ldA % 2 == 0 && (reinterpret_cast<uintptr_t>(A) & 7u) == 0;
+        const bool even = ldA % 2 == 0 && (reinterpret_cast<uintptr_t>(A) & 7u) == 0;
+        if (d <= kMaxRowsKernelD) {
+            if (aligned_rows && d % 4 == 0)
+                rc = launch_fused_rows<4>(grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+            else if (even && d % 2 == 0)
+                rc = launch_fused_rows<2>(grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+            else
+                rc = launch_fused_rows<1>(grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+        } else if (!aligned_rows) {
             rc = even ? launch_fused_narrow<2>(grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs)
                       : launch_fused_narrow<1>(grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
         } else {

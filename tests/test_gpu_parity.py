@@ -227,6 +227,24 @@ LSQ_CASES = [
     (1, 30, 16383, 0, 0, 1.0),           # 1024 threads, 4-byte accesses, the widest
     (1, 30, 16385, 0, 0, 1.0),           # beyond: two sweeps
     (5, 3, 1500, 2, 1, 1.0),             # fewer rows than a tile holds
+    # short rows (d <= 1024): a wave per row, or per 2, 4, 8 rows; 16-, 8- or 4-byte accesses by alignment
+    (3, 1000, 8, 0, 0, 1.0),             # 16-byte accesses: 8 lanes per row (6 of them idle), 32 rows per access
+    (2, 700, 32, 0, 0, 0.5),             # 8 lanes per row, all busy
+    (3, 333, 64, 4, 0, 1.0),             # 16 lanes per row
+    (2, 300, 100, 0, 0, 1.0),            # 32 lanes per row, 25 busy
+    (2, 260, 256, 0, 4, 1.0),            # a wave per row
+    (3, 77, 300, 0, 0, 1.0),             # two chunks per lane
+    (2, 130, 1000, 0, 1, 1.0),           # four chunks per lane; x and g off the 16-byte grid
+    (2, 600, 30, 0, 0, 1.0),             # 8-byte accesses (even ldA, even d): 16 lanes per row
+    (2, 90, 1022, 0, 0, 1.0),            # 8-byte accesses, eight chunks per lane
+    (2, 210, 250, 0, 0, 1.0),            # 8-byte accesses, two chunks per lane
+    (2, 500, 31, 0, 0, 1.0),             # 4-byte accesses: 32 lanes per row
+    (3, 400, 7, 0, 0, 1.0),              # 4-byte accesses: 8 lanes per row
+    (2, 100, 129, 0, 0, 1.0),            # 4-byte accesses, four chunks per lane
+    (2, 90, 1023, 0, 0, 1.0),            # 4-byte accesses, sixteen chunks per lane
+    (2, 120, 514, 1, 0, 1.0),            # odd ldA with an even d: 4-byte accesses
+    (1, 5000, 1, 0, 0, 1.0),             # one column
+    (2, 40, 1024, 0, 0, 1.0),            # the widest short row; row blocks shorter than a workgroup's access
 ]
 
 
@@ -472,7 +490,11 @@ def test_decentlam_stays_bounded_on_symmetric_graphs(P):
                                           (2, 30, 16388, 11, 0),      # 1024 threads, x_i in LDS
                                           (3, 60, 1030, 25, 2),       # d % 4 = 2 with rows on 16-byte boundaries: tail columns
                                           (1, 20, 20001, 9, 3),       # both
-                                          (2, 80, 3001, 17, 0)])      # rows off the 16-byte boundaries: 4-byte accesses
+                                          (2, 80, 3001, 17, 0),       # rows off the 16-byte boundaries: 4-byte accesses
+                                          (3, 900, 48, 100, 0),       # short rows: 16 lanes per row, ragged row groups
+                                          (2, 500, 200, 37, 0),       # a wave per row
+                                          (2, 300, 30, 50, 0),        # 8-byte accesses
+                                          (2, 200, 999, 13, 0)])      # 4-byte accesses, sixteen chunks per lane
 def test_local_grad_lsq_rows_matches_oracle(P, oracle, n, b, d, bs, pad):
     rng = np.random.default_rng(n * 1000 + bs)
     A0 = rng.standard_normal((n, b, d)).astype(np.float32)
