@@ -764,7 +764,8 @@ int fused_splits(int32_t n, int32_t b, int64_t d, int rows_per_iteration) {
     const int64_t rows_each = rows_per_iteration > 8 ? rows_per_iteration : 8;
     const int64_t most = (b + rows_each - 1) / rows_each;
     if (s > most) s = most;
-    if (s > 256) s = 256;
+    const int64_t cap = d > 4096 ? 256 : 512;   // the final pass adds a node's partials a quarter per wave, one after the other
+    if (s > cap) s = cap;
     if (s < 1) s = 1;
     return static_cast<int>(s);
 }
