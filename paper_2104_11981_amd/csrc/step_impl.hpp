@@ -122,8 +122,8 @@ int launch_chain(int algo, const StepCall& s, uint32_t units, uint32_t len);
 // x on a 64 KiB boundary, s.ld a multiple of 128, every array 16-byte aligned, fp32 gradients); or, with
 // s.batch_stride != 0 (blocked layout), over s.batches sub-problems of s.d columns each (s.d a multiple of 256,
 // `units` unused).
-bool tall_serves(int algo, int32_t n, int nnz);
-int launch_tall(int algo, const StepCall& s, uint32_t units);
+bool tall_serves(int algo, int32_t n, int nnz, int gformat);
+int launch_tall(int algo, const StepCall& s, uint32_t units, int gformat);
 
 #ifdef DL_STEP_KERNEL_IMPL
 namespace {

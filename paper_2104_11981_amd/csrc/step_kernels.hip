@@ -73,11 +73,11 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
     // workgroup per CU is worth more than the alignment: rows on any 512-byte boundary take it too (48 / 64 nodes,
     // rows alternating between 64 KiB boundaries and their midpoints: 6.15 / 6.0 TB/s against 5.7 with k_step; rows
     // on other 512-byte boundaries 6.1 / 5.8 against 5.7; at 96 and 128 nodes the comparison went either way).
-    if (n > 32 && batches == 1 && !norms && g.format == DL_GRAD_F32 && d >= kSplitMinColumns && ld % (n <= 64 ? kSplitSegment : kSplitUnit) == 0 &&
-        g.ld % 4 == 0 && tall_serves(algo, n, topo.row_ptr[n])) {
+    if (n > 32 && batches == 1 && !norms && d >= kSplitMinColumns && ld % (n <= 64 ? kSplitSegment : kSplitUnit) == 0 &&
+        g.ld % 4 == 0 && tall_serves(algo, n, topo.row_ptr[n], g.format)) {
         const uintptr_t ax = (reinterpret_cast<uintptr_t>(x) >> 2) & 3;
         const uintptr_t am = m ? (reinterpret_cast<uintptr_t>(m) >> 2) & 3 : ax;
-        const uintptr_t ag = (reinterpret_cast<uintptr_t>(g.p) >> 2) & 3;
+        const uintptr_t ag = (reinterpret_cast<uintptr_t>(g.p) >> gshift) & 3;
         const float* written = algo == ALGO_DECENTLAM_XPREV ? m : x;
         const int64_t first = static_cast<int64_t>((kSplitUnit - ((reinterpret_cast<uintptr_t>(written) >> 2) % kSplitUnit)) % kSplitUnit);
         const int64_t units = first <= d ? (d - first) / kSplitUnit : 0;
@@ -85,15 +85,15 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
             StepCall s;
             s.x = x + first;
             s.m = m ? m + first : nullptr;
-            s.g = static_cast<const float*>(g.p) + first;
+            s.g = static_cast<const char*>(g.p) + static_cast<size_t>(first) * gbytes;
             s.n = n; s.d = units * kSplitUnit; s.ld = ld; s.ldg = g.ld;
             s.gamma = gamma; s.beta = beta; s.topo = &topo; s.stream = stream;
             s.na = NormArgs{nullptr, 0, 0};
             s.batches = 1; s.batch_stride = 0; s.batch_stride_g = 0; s.split_tiles = 0; s.by_xcd = false;
-            if (int rc = launch_tall(algo, s, static_cast<uint32_t>(units))) return rc;
+            if (int rc = launch_tall(algo, s, static_cast<uint32_t>(units), g.format)) return rc;
             const int64_t after = first + units * kSplitUnit;   // fewer than kSplitUnit columns on either side
             GradArg g_after = g;
-            g_after.p = static_cast<const float*>(g.p) + after;
+            g_after.p = static_cast<const char*>(g.p) + static_cast<size_t>(after) * gbytes;
             if (first > 0) {
                 if (int rc = launch_step(algo, x, m, g, n, first, ld, topo, gamma_f, beta, stream, nullptr, 1, 0, 0)) return rc;
             }
@@ -108,17 +108,17 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
     // where k_step has one whose gathers nothing overlaps.  Ring / exponential graph, TB/s: 36 nodes 6.4 / 6.4 against
     // 6.25 / 6.25, 40 nodes 6.25 / 6.3 against 6.2 / 5.8, 56 nodes 6.3 / 6.3 against 6.4 / 6.05; with the 16-wave
     // shapes (48, 64 nodes) 6.4 / 6.05 either way, so those stay with k_step.
-    if (n > 32 && (n <= 40 || (n > 48 && n <= 56)) && batch_stride != 0 && !norms && g.format == DL_GRAD_F32 && d % 256 == 0 && ld == d && g.ld == d &&
+    if (n > 32 && (n <= 40 || (n > 48 && n <= 56)) && batch_stride != 0 && !norms && d % 256 == 0 && ld == d && g.ld == d &&
         batch_stride % 4 == 0 && batch_stride_g == batch_stride && batches * (d / 256) >= kSplitMinColumns / 256 &&
-        ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(g.p)) & 15u) == 0 &&
-        tall_serves(algo, n, topo.row_ptr[n])) {
+        ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(m)) & 15u) == 0 &&
+        (reinterpret_cast<uintptr_t>(g.p) & (4 * gbytes - 1)) == 0 && tall_serves(algo, n, topo.row_ptr[n], g.format)) {
         StepCall s;
         s.x = x; s.m = m; s.g = g.p;
         s.n = n; s.d = d; s.ld = ld; s.ldg = g.ld;
         s.gamma = gamma; s.beta = beta; s.topo = &topo; s.stream = stream;
         s.na = NormArgs{nullptr, 0, 0};
         s.batches = batches; s.batch_stride = batch_stride; s.batch_stride_g = batch_stride_g; s.split_tiles = 0; s.by_xcd = false;
-        return launch_tall(algo, s, 0);
+        return launch_tall(algo, s, 0, g.format);
     }
 
     // Pick the widest access all three arrays can share: same misalignment (in elements)

@@ -27,9 +27,10 @@ namespace dl {
 namespace step {
 namespace {
 
-template <int ALGO, int RPT, int WAVES>
+// GF: gradient format (fp32, or bf16 / fp16 widened on load: 8 bytes per lane)
+template <int ALGO, int RPT, int WAVES, int GF>
 __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(RPT <= 4 ? 8 : 4, RPT <= 4 ? 8 : 4))) void k_step_tall(float* __restrict__ x, float* __restrict__ m,
-                                                    const float* __restrict__ g, int64_t ld, int64_t ldg,
+                                                    const typename GradElem<GF>::type* __restrict__ g, int64_t ld, int64_t ldg,
                                                     double gamma, double inv_gamma, double beta,
                                                     uint32_t batch_tiles, int64_t batch_stride, const PhaseArgs topo) {
     constexpr int TC = 128;   // columns of the LDS tile: two per lane and pass
@@ -66,14 +67,14 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(RPT 
         const int i = wave + WAVES * r;
         const int64_t row = i < n ? i : 0;   // uniform; rows beyond the problem read row 0 and store nothing
         load_vec<4>(x + (row * ld + tile_col) + lane_col, xr[r]);
-        if constexpr (kEarlyG) load_vec<4>(g + (row * ldg + tile_col) + lane_col, gr[r]);
+        if constexpr (kEarlyG) load_grad<4, GF>(g + (row * ldg + tile_col) + lane_col, gr[r]);
         if constexpr (kHasM && kEarlyM) load_vec<4>(m + (row * ld + tile_col) + lane_col, mr[r]);
     }
 #pragma unroll
     for (int r = 0; r < RPT; ++r) {
         const int i = wave + WAVES * r;
         const int64_t row = i < n ? i : 0;
-        if constexpr (!kEarlyG) load_vec<4>(g + (row * ldg + tile_col) + lane_col, gr[r]);
+        if constexpr (!kEarlyG) load_grad<4, GF>(g + (row * ldg + tile_col) + lane_col, gr[r]);
         if constexpr (kHasM && !kEarlyM) load_vec<4>(m + (row * ld + tile_col) + lane_col, mr[r]);
     }
 
@@ -201,49 +202,51 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(RPT 
     }
 }
 
-template <int ALGO, int RPT, int WAVES = 16>
+template <int ALGO, int GF, int RPT, int WAVES = 16>
 int launch_tall_shape(const StepCall& s, uint32_t tiles, uint32_t batch_tiles) {
     const size_t lds_bytes = lds_bytes_for(s.n, 2, s.topo->row_ptr[s.n], 1);
     if (lds_bytes > 160 * 1024) return set_error(DL_ETOPO, "step: the two-pass kernel's tile does not fit");
-    auto kernel = k_step_tall<ALGO, RPT, WAVES>;
+    auto kernel = k_step_tall<ALGO, RPT, WAVES, GF>;
     if (lds_bytes > 48 * 1024) {
         static std::atomic<uint64_t> configured{0};   // per instantiation; see allow_large_lds
         if (int rc = allow_large_lds(reinterpret_cast<const void*>(kernel), configured)) return rc;
     }
     hipLaunchKernelGGL(kernel, dim3(tiles), dim3(64 * WAVES), lds_bytes, s.stream, s.x, s.m,
-                       static_cast<const float*>(s.g), s.ld, s.ldg, s.gamma, 1.0 / s.gamma, s.beta, batch_tiles,
+                       static_cast<const typename GradElem<GF>::type*>(s.g), s.ld, s.ldg, s.gamma, 1.0 / s.gamma, s.beta, batch_tiles,
                        s.batch_stride, *s.topo);
     return check_hip(hipGetLastError(), "step kernel launch (two-pass tiles)");
 }
 
-template <int ALGO>
+template <int ALGO, int GF = DL_GRAD_F32>
 int launch_tall_algo(const StepCall& s, uint32_t tiles, uint32_t batch_tiles) {
     // waves x rows per thread.  Up to 64 nodes a shape without empty row slots is worth 2-4 % (36 / 40 / 56 nodes:
     // 6.5 / 6.45 / 6.3 TB/s with 12 x 3 / 10 x 4 / 14 x 4 against 6.2 / 6.25 / 6.2 with 16 x 3 / 16 x 3 / 16 x 4)
-    if (s.n <= 36) return launch_tall_shape<ALGO, 3, 12>(s, tiles, batch_tiles);
+    if (s.n <= 36) return launch_tall_shape<ALGO, GF, 3, 12>(s, tiles, batch_tiles);
     if constexpr (ALGO != ALGO_AWC_DMSGD) {
-        if (s.n <= 40) return launch_tall_shape<ALGO, 4, 10>(s, tiles, batch_tiles);
+        if (s.n <= 40) return launch_tall_shape<ALGO, GF, 4, 10>(s, tiles, batch_tiles);
     }
-    if (s.n <= 48) return launch_tall_shape<ALGO, 3>(s, tiles, batch_tiles);
+    if (s.n <= 48) return launch_tall_shape<ALGO, GF, 3>(s, tiles, batch_tiles);
     if constexpr (ALGO != ALGO_AWC_DMSGD) {
-        if (s.n <= 56) return launch_tall_shape<ALGO, 4, 14>(s, tiles, batch_tiles);
-        if (s.n <= 64) return launch_tall_shape<ALGO, 4>(s, tiles, batch_tiles);
+        if (s.n <= 56) return launch_tall_shape<ALGO, GF, 4, 14>(s, tiles, batch_tiles);
+        if (s.n <= 64) return launch_tall_shape<ALGO, GF, 4>(s, tiles, batch_tiles);
     }
-    if (s.n <= 80) return launch_tall_shape<ALGO, 5>(s, tiles, batch_tiles);
-    if (s.n <= 96) return launch_tall_shape<ALGO, 6>(s, tiles, batch_tiles);
-    if (s.n <= 112) return launch_tall_shape<ALGO, 7>(s, tiles, batch_tiles);
-    return launch_tall_shape<ALGO, 8>(s, tiles, batch_tiles);
+    if (s.n <= 80) return launch_tall_shape<ALGO, GF, 5>(s, tiles, batch_tiles);
+    if (s.n <= 96) return launch_tall_shape<ALGO, GF, 6>(s, tiles, batch_tiles);
+    if (s.n <= 112) return launch_tall_shape<ALGO, GF, 7>(s, tiles, batch_tiles);
+    return launch_tall_shape<ALGO, GF, 8>(s, tiles, batch_tiles);
 }
 
 }  // namespace
 
-bool tall_serves(int algo, int32_t n, int nnz) {
+bool tall_serves(int algo, int32_t n, int nnz, int gformat) {
     if (n <= 32 || n > 128 || algo == ALGO_DA_DMSGD || mixes_on_matrix_cores(n, nnz)) return false;
+    // 16-bit gradients: the methods that have entry points of their own for them
+    if (gformat != DL_GRAD_F32 && algo != ALGO_DECENTLAM && algo != ALGO_DMSGD && algo != ALGO_DECENTLAM_XPREV) return false;
     if (n > 48 && n <= 64 && algo == ALGO_AWC_DMSGD) return false;   // four rows per thread of x, g and m: 4 registers short
     return lds_bytes_for(n, 2, nnz, 1) <= 160 * 1024;
 }
 
-int launch_tall(int algo, const StepCall& s, uint32_t units) {
+int launch_tall(int algo, const StepCall& s, uint32_t units, int gformat) {
     uint32_t tiles, batch_tiles = 0;
     if (s.batches > 1 || s.batch_stride != 0) {   // blocked layout: s.d columns per sub-problem, whole tiles only
         const int64_t per = s.d / 256, all = per * s.batches;
@@ -254,6 +257,21 @@ int launch_tall(int algo, const StepCall& s, uint32_t units) {
     } else {
         if (units > 0x7fffffffu / kSplitTilesPerUnit) return set_error(DL_EINVAL, "step: d too large for one launch");
         tiles = units * kSplitTilesPerUnit;
+    }
+    if (gformat != DL_GRAD_F32) {
+        const bool bf = gformat == DL_GRAD_BF16;
+        switch (algo) {
+            case ALGO_DECENTLAM:
+                return bf ? launch_tall_algo<ALGO_DECENTLAM, DL_GRAD_BF16>(s, tiles, batch_tiles)
+                          : launch_tall_algo<ALGO_DECENTLAM, DL_GRAD_F16>(s, tiles, batch_tiles);
+            case ALGO_DMSGD:
+                return bf ? launch_tall_algo<ALGO_DMSGD, DL_GRAD_BF16>(s, tiles, batch_tiles)
+                          : launch_tall_algo<ALGO_DMSGD, DL_GRAD_F16>(s, tiles, batch_tiles);
+            case ALGO_DECENTLAM_XPREV:
+                return bf ? launch_tall_algo<ALGO_DECENTLAM_XPREV, DL_GRAD_BF16>(s, tiles, batch_tiles)
+                          : launch_tall_algo<ALGO_DECENTLAM_XPREV, DL_GRAD_F16>(s, tiles, batch_tiles);
+            default: return set_error(DL_EINVAL, "step: this method has no two-pass kernel for 16-bit gradients");
+        }
     }
     switch (algo) {
         case ALGO_DECENTLAM: return launch_tall_algo<ALGO_DECENTLAM>(s, tiles, batch_tiles);

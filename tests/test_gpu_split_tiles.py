@@ -164,6 +164,55 @@ def test_tall_tiles_on_rows_off_the_64_kib_boundaries(P, oracle, algo, kind, n, 
     test_large_row_major_launch_matches_oracle(P, oracle, algo, kind, n, d, pad, skew)
 
 
+# The same kernel with bf16 / fp16 gradients (8 bytes per lane, widened on load): DecentLaM, DmSGD and the
+# momentum-free form.  g has its own stride and its own place; it is served when its misalignment in elements equals
+# that of x and m.
+@pytest.mark.parametrize("fmt,algo,kind,n,d,pad,skew,skew_g,padg", [
+    ("bf16", "decentlam", 1, 40, (1 << 20) + UNIT + 300, UNIT - 300, 0, 0, 4),      # 10 waves x 4 rows; g with another stride
+    ("f16", "dmsgd", 0, 64, (1 << 20) + 2 * UNIT, 0, 4, 4, 0),                      # 16380 columns first
+    ("bf16", "xprev", 1, 100, (1 << 20) + 200, UNIT - 200, 0, 8, 8),                # seven rows per thread; g placed elsewhere
+    ("f16", "decentlam", 4, 36, (1 << 20) + 3 * 128, 0, 0, 0, 0),                   # rows on other 512-byte boundaries
+    ("bf16", "dmsgd", 1, 128, (1 << 20) + 8, UNIT - 8, 0, 2, 0),                    # g misaligned differently: not served
+])
+def test_tall_tiles_with_16_bit_gradients(P, oracle, fmt, algo, kind, n, d, pad, skew, skew_g, padg):
+    dtype = {"bf16": torch.bfloat16, "f16": torch.float16}[fmt]
+    gamma, beta = float(np.float32(0.05)), float(np.float32(0.9))
+    topo, otopo = P.topology_build(kind, n), oracle.topology(kind, n)
+    rng = np.random.default_rng(n * 13 + d)
+    x0, m0 = (rng.standard_normal((n, d)).astype(np.float32) for _ in range(2))
+    g16 = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).to(dtype)
+    bits = g16.view(torch.int16).numpy().view(np.uint16).copy()
+    g0 = oracle.widen16(bits, fmt)
+    ld, ldg = d + pad, d + pad + padg
+    SENT = 4242.0
+    (bx, x), (bm, m) = (placed(n, d, ld, skew, SENT) for _ in range(2))
+    bg = torch.full((n * ldg + 2 * UNIT,), 7.0, dtype=dtype, device="cuda")
+    first_g = (-(bg.data_ptr() // 2)) % UNIT + skew_g
+    g = bg[first_g:first_g + n * ldg].view(n, ldg)[:, :d]
+    x.copy_(torch.from_numpy(x0).cuda())
+    m.copy_(torch.from_numpy(m0).cuda())
+    g.copy_(g16.cuda())
+    k = 1
+    if algo == "xprev":
+        P.decentlam_step_xprev_ex(x, m, g, topo, gamma, beta, k)
+        mr = oracle.decentlam_xprev_step(x0, m0, g0, otopo, gamma, beta, k)
+        xr = x0.astype(np.float64)
+    else:
+        getattr(P, algo + "_step_g16")(x, m, g, topo, gamma, beta, k)
+        xr, mr = oracle.STEP[algo](x0, m0, g0, otopo, gamma, beta, k)
+    torch.cuda.synchronize()
+    check_elementwise(x.cpu().numpy(), xr, algo + " x")
+    check_elementwise(m.cpu().numpy(), mr, algo + " m")
+    np.testing.assert_array_equal(g.cpu().view(torch.int16).numpy().view(np.uint16), bits)
+    for buf, view in ((bx, x), (bm, m)):   # nothing outside the views was written
+        full = buf.cpu().numpy()
+        inside = np.zeros(full.shape, dtype=bool)
+        first = (view.data_ptr() - buf.data_ptr()) // 4
+        for i in range(n):
+            inside[first + i * ld:first + i * ld + d] = True
+        assert np.all(full[~inside] == SENT)
+
+
 @pytest.mark.parametrize("n,d,pad", [(4, (1 << 20) + 1284, 4), (8, (1 << 20) + 3 * UNIT + 8, 8), (4, (1 << 20) + 2 * UNIT, 0)])
 def test_large_launch_with_per_tensor_sums(P, oracle, n, d, pad):
     """The multi-tensor call over one large launch in either order: state and sums against the oracle."""
