@@ -140,10 +140,12 @@ int topology_metropolis(int32_t n, const int32_t* row_ptr, const int32_t* col_id
  *   The caller zeroes m before iteration 0 (Algorithm 2, initialisation).
  * d == 0 is a successful no-op.  Any alignment and any ld >= d are accepted
  * (unaligned heads/tails fall back to narrower loads); for full speed let rows start on
- * 128-byte boundaries (16-byte aligned bases, ld a multiple of 32), and for arrays of a
- * million columns or more on 64 KiB boundaries (64 KiB-aligned bases, ld a multiple of
+ * 128-byte boundaries (16-byte aligned bases, ld a multiple of 32), and for arrays of
+ * 65536 columns or more on 64 KiB boundaries (64 KiB-aligned bases, ld a multiple of
  * 16384): the step then writes whole 64 KiB-aligned address pairs (A, A + 32 KiB), worth
- * about 10 % at every node count (measured at n = 32, d = 25.6 M: 2.51 instead of 2.80 ms).  Rows that
+ * about 10 % at every node count (measured at n = 32, d = 25.6 M: 2.51 instead of 2.80 ms).  Avoid an ld that
+ * is a multiple of 127 or 129 times 16384: the rows of a column then fall on the same memory channels
+ * (32 nodes x 1 M columns: 161 instead of 110 us with ld = 129 * 16384; 2 to 6 % at 25 M columns).  Rows that
  * alternate between such boundaries and their midpoints (ld an odd multiple of 8192, e.g. a contiguous
  * 32 x 25.6 M array; 17 to 32 nodes, x, m, g placed alike modulo 64 KiB) are served by a kernel of their
  * own that loads and stores half of each odd row's accesses one 64 KiB unit ahead / late: 2.64 ms there.

@@ -286,9 +286,15 @@ ROW_ALIGN_ELEMENTS = 16384   # 64 KiB of fp32: the row alignment the step kernel
 
 def recommended_ld(d: int) -> int:
     """Row stride (in elements) the header recommends for an n x d fp32 array: rows on 64 KiB boundaries
-    from a million columns on, on 256-byte boundaries below."""
-    unit = ROW_ALIGN_ELEMENTS if d >= (1 << 20) else 64
-    return (d + unit - 1) // unit * unit
+    from 65536 columns on (but never a multiple of 127 or 129 times 64 KiB, nor 4 MiB exactly: with such
+    strides the rows of a column fall on the same memory channels; measured on 32 nodes x 1 M columns: 0.49
+    and 0.64-0.69 of the HBM peak against 0.71-0.80 with one 64 KiB unit more), on 256-byte boundaries below."""
+    if d < (1 << 16):
+        return (d + 63) // 64 * 64
+    units = (d + ROW_ALIGN_ELEMENTS - 1) // ROW_ALIGN_ELEMENTS
+    while units % 127 == 0 or units % 129 == 0 or units == 64:
+        units += 1
+    return units * ROW_ALIGN_ELEMENTS
 
 
 def empty_rows(n: int, d: int, device="cuda", dtype=None, fill=None):

@@ -38,7 +38,11 @@ namespace {
 
 using namespace step;
 
-constexpr int64_t kSplitMinColumns = 1 << 20;   // below this a launch keeps plain tiles
+// Below this a launch keeps plain tiles.  Measured with rows on 64 KiB boundaries, exponential graph, split tiles from
+// 2^16 instead of 2^20 columns on: 32 nodes x 262144 / 524288 columns 0.66 / 0.71 -> 0.71 / 0.74 of the HBM peak, 48 nodes
+// x 131072 / 524288 0.64 / 0.69 -> 0.73 / 0.74, 64 nodes x 131072 / 524288 0.59 / 0.67 -> 0.70 / 0.76.
+constexpr int64_t kSplitMinColumns = 1 << 16;
+constexpr int64_t kChainMinColumns = 1 << 20;   // the chained-tile kernel walks runs of units: long rows only
 
 // Widest access by node count.  Up to 32 nodes the fp64 tile of 16-byte lanes takes 64 KiB of LDS and
 // two workgroups share a CU.  Beyond that the wide lanes are kept and the tile grows to 128 KiB, one
@@ -199,7 +203,7 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
         const auto on_unit = [&](const void* p, size_t elem) {
             return p && (reinterpret_cast<uintptr_t>(p) + static_cast<size_t>(head + pre) * elem) % (4u * kSplitUnit) == 0;
         };
-        const bool chained = ld % kSplitUnit == kSplitDistance && units > 0 && !norms && g.format == DL_GRAD_F32 &&
+        const bool chained = ld % kSplitUnit == kSplitDistance && units > 0 && body >= kChainMinColumns && !norms && g.format == DL_GRAD_F32 &&
                              g.ld == ld && on_unit(x, 4) && on_unit(m, 4) && on_unit(g.p, 4) &&
                              chain_serves(algo, n, topo.row_ptr[n]);
         if (chained) {

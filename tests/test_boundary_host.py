@@ -477,8 +477,13 @@ def test_recommended_row_layout_helpers():
     import paper_2104_11981_amd as P
 
     assert P.recommended_ld(25_600_000) == 25_608_192 and P.recommended_ld(25_608_192) == 25_608_192
-    assert P.recommended_ld(1 << 20) == 1 << 20 and P.recommended_ld((1 << 20) + 1) == (1 << 20) + 16384
+    assert P.recommended_ld(1 << 20) == (1 << 20) + 16384 and P.recommended_ld((1 << 20) + 1) == (1 << 20) + 16384
+    assert P.recommended_ld(1 << 21) == 1 << 21
     assert P.recommended_ld(1000) == 1024 and P.recommended_ld(64) == 64 and P.recommended_ld(1) == 64
+    assert P.recommended_ld(65535) == 65536 and P.recommended_ld(65537) == 5 * 16384
+    # strides of 127 or 129 times 64 KiB (and their multiples) put the rows of a column on the same channels
+    assert P.recommended_ld(127 * 16384) == 128 * 16384 and P.recommended_ld(129 * 16384 - 5) == 130 * 16384
+    assert P.recommended_ld(2 * 129 * 16384) == (2 * 129 + 1) * 16384
     v = P.empty_rows(3, (1 << 20) + 5, device="cpu", fill=2.0)
     assert tuple(v.shape) == (3, (1 << 20) + 5) and v.stride() == ((1 << 20) + 16384, 1)
     assert v.data_ptr() % 65536 == 0 and float(v.sum()) == 2.0 * 3 * ((1 << 20) + 5)

@@ -1,6 +1,6 @@
 """GPU parity of the large-launch column orders of the row-major step.
 
-From 2^20 columns on, a row-major launch with 16-byte lanes maps its tiles to two 512-byte segments
+From 2^16 columns on, a row-major launch with 16-byte lanes maps its tiles to two 512-byte segments
 32 KiB apart inside 64 KiB-aligned units of the written array (what precedes the first aligned column
 is a launch of its own, what follows the last whole unit rides along as ordinary tiles).  Every
 column must still be updated exactly once: a column left out keeps its old value, a column taken
@@ -56,6 +56,12 @@ CASES = [
     (2, 8, (1 << 20) + 1284, 4, (0, 0, 0)),
     (0, 4, (1 << 20) + 1796, 12, (0, 4, 8)),
     (1, 16, (1 << 20) + 1540, 20, (4, 4, 4)),
+    # the shortest launches that take these orders (65536 columns), and one just below
+    (1, 32, (1 << 16) + UNIT + 300, UNIT - 300, (4, 4, 4)),
+    (0, 8, 1 << 16, 0, (0, 0, 0)),
+    (1, 16, (1 << 16) + 260, 4, (0, 0, 0)),
+    (1, 32, (1 << 16) - 4, 4, (0, 0, 0)),
+    (1, 24, (1 << 16) + 8192, 0, (0, 0, 0)),                        # rows alternating between boundaries and midpoints, too short for chained tiles
 ]
 
 
@@ -143,6 +149,8 @@ TALL_CASES = [
     (4, 40, (1 << 20) + 200, UNIT - 200, (0, 4096, 8192), ("decentlam", "dmsgd", "awc_dmsgd")),   # 10 waves x 4 rows (AWC: 16 x 3); irregular degrees
     (0, 33, (1 << 20) + 4, UNIT - 4, (3, 3, 3), ("xprev", "awc_dmsgd")),  # the smallest node count served: 12 waves x 3 rows, rows 33-35 absent
     (2, 56, (1 << 20) + 2 * UNIT, 0, (0, 0, 0), ("decentlam", "dsgd")),   # 14 waves x 4 rows; one peer per iteration
+    (1, 48, (1 << 16) + 2 * UNIT, 0, (0, 0, 0), ("decentlam", "dmsgd")),  # the shortest launch served, six units
+    (1, 128, (1 << 16) + 300, UNIT - 300, (4, 4, 4), ("decentlam",)),     # four units between two ordinary launches
 ]
 
 
