@@ -416,7 +416,9 @@ int dmsgd_step_g16(float* x, float* m, const void* g, int32_t g_format,
  *   norms     [out]    device, num_tensors x n x 3 doubles, or NULL for none:
  *                      norms[(t*n + i)*3 + 0] = sum of g_i^2 over tensor t (the values as loaded),
  *                      ... + 1 = sum of the new m_i^2, ... + 2 = sum of the new x_i^2 (the stored
- *                      fp32 values, squared and added in fp64).  Deterministic: same inputs, same bits.
+ *                      fp32 values, squared and added in fp64).  Deterministic: same inputs, same bits
+ *                      (from 2^20 columns on: for arrays at the same addresses modulo 64 KiB, which
+ *                      decide where the tiles of the launch begin and with them the order of the sums).
  *   workspace [scratch] device, 8-byte aligned, at least
  *                      decentlam_step_multi_workspace(n, offsets[num_tensors] - offsets[0], num_tensors)
  *                      bytes; needed only when norms != NULL (per-tile partial sums).

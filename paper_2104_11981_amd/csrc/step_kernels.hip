@@ -190,7 +190,9 @@ int launch_step(Algo algo, float* x, float* m, GradArg g, int32_t n, int64_t d, 
     // of its own, what follows rides along as ordinary tiles of the same launch.  (The per-tensor sums
     // need tiles that are column ranges.)  Rows that start at different offsets inside a 128-byte line
     // cannot be paired up; their launch goes out in the per-XCD order instead (step_impl.hpp).
-    const bool large = vec == 4 && batches == 1 && body >= kSplitMinColumns;
+    // (with per-tensor sums only from 2^20 columns on: where the tiles start decides the order of those sums, and below
+    // that it does not depend on where the arrays lie)
+    const bool large = vec == 4 && batches == 1 && body >= (norms ? kChainMinColumns : kSplitMinColumns);
     if (large && ld % 32 != 0) {
         if (int rc = run(vec, head, body, 0, true)) return rc;
     } else if (large) {
