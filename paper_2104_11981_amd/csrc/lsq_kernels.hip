@@ -217,7 +217,21 @@ template <int CPT, int R>
 struct Tile {
     vf4 a[R][CPT];
     float tl[R][3];   // TAIL: the row's last d % 4 elements (uniform over the workgroup), zeros after them
+    float y[R];       // the rows' entries of y_i (uniform): fetched with the tile, not after the barrier that follows it
 };
+
+// The physical rows of a tile (uniform): rows past the block's end are clamped to its last row, sampled rows are looked
+// up.  Called one tile ahead of the loads that use the result, so that the look-up is not waited for when the loads
+// should go out (with the look-up inside load_tile a sampled sweep ran at 0.65 of the HBM peak where the plain one
+// runs at 0.85).
+template <int R>
+__device__ __forceinline__ void tile_rows(int (&prow)[R], int r, int r_last, const int32_t* __restrict__ rows_i, int b) {
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        const int row = (r + rr < r_last) ? r + rr : r_last;
+        prow[rr] = rows_i ? physical_row(rows_i, row, b) : row;
+    }
+}
 
 // Loads never need a predicate: rows past the block's end are clamped to its last row (their
 // residual is forced to zero below) and column chunks past d are clamped to the last chunk
@@ -227,13 +241,13 @@ struct Tile {
 // reaches past column d of any row.
 template <int CPT, int R, bool TAIL = false>
 __device__ __forceinline__ void load_tile(Tile<CPT, R>& t, const float* __restrict__ a_node, int64_t ldA,
-                                          int r, int r_last, const int (&col)[CPT],
-                                          const int32_t* __restrict__ rows_i, int b, int64_t dm = 0, int dt = 0) {
+                                          const int (&prow)[R], const int (&col)[CPT],
+                                          const float* __restrict__ yi, int64_t dm = 0, int dt = 0) {
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
-        int row = (r + rr < r_last) ? r + rr : r_last;
-        if (rows_i) row = physical_row(rows_i, row, b);
+        const int row = prow[rr];
         const float* __restrict__ a_row = a_node + static_cast<int64_t>(row) * ldA;
+        t.y[rr] = yi[row];
 #pragma unroll
         for (int q = 0; q < CPT; ++q)
             t.a[rr][q] = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(a_row + col[q]));
@@ -251,8 +265,7 @@ __device__ __forceinline__ void load_tile(Tile<CPT, R>& t, const float* __restri
 template <int CPT, int R, int WAVES, bool XL = false, bool TAIL = false>
 __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float (&xs)[CPT][4], const vf4* xl,
                                              double (&acc)[CPT][4], double& sq, double (*red)[R],
-                                             const float* __restrict__ yi, int r, int r1, int lane, int wave,
-                                             const int32_t* __restrict__ rows_i, int b, const float (&xt)[3],
+                                             int r, int r1, int lane, int wave, const float (&xt)[3],
                                              double (&acc_tail)[3], double* tail_sums) {
     double p[R];
 #pragma unroll
@@ -290,7 +303,6 @@ __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float 
     for (int rr = 0; rr < R; ++rr) {
         double res = 0.0;
         if (r + rr < r1) {  // uniform over the workgroup
-            const int pr = rows_i ? physical_row(rows_i, r + rr, b) : r + rr;
             double dot = 0.0;   // the waves' shares in a fixed order
 #pragma unroll
             for (int w4 = 0; w4 < WAVES; w4 += 4)
@@ -303,7 +315,7 @@ __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float 
                     dot = __builtin_fma(static_cast<double>(t.tl[rr][k]), static_cast<double>(xk), dot);
                 }
             }
-            res = dot - static_cast<double>(yi[pr]);
+            res = dot - static_cast<double>(t.y[rr]);
         }
         sq = __builtin_fma(res, res, sq);
         if constexpr (TAIL) {
@@ -390,16 +402,23 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
 
     if constexpr (PF) {
         Tile<CPT, R> t0, t1;
-        load_tile<CPT, R, TAIL>(t0, a_node, ldA, r0, r1 - 1, col, rows_i, b, dm, dt);
+        int p0[R], p1[R];   // physical rows of the tile that is loaded next into t0 / t1
+        tile_rows<R>(p0, r0, r1 - 1, rows_i, b);
+        load_tile<CPT, R, TAIL>(t0, a_node, ldA, p0, col, yi, dm, dt);
+        tile_rows<R>(p1, r0 + R, r1 - 1, rows_i, b);
         for (int r = r0; r < r1; r += 2 * R) {
-            load_tile<CPT, R, TAIL>(t1, a_node, ldA, r + R, r1 - 1, col, rows_i, b, dm, dt);
-            consume_tile<CPT, R, WAVES, XL, TAIL>(t0, xs, xl, acc, sq, red[0], yi, r, r1, lane, wave, rows_i, b, xt, acc_tail, tail_sums);
-            load_tile<CPT, R, TAIL>(t0, a_node, ldA, r + 2 * R, r1 - 1, col, rows_i, b, dm, dt);
-            consume_tile<CPT, R, WAVES, XL, TAIL>(t1, xs, xl, acc, sq, red[1], yi, r + R, r1, lane, wave, rows_i, b, xt, acc_tail, tail_sums);
+            load_tile<CPT, R, TAIL>(t1, a_node, ldA, p1, col, yi, dm, dt);
+            tile_rows<R>(p0, r + 2 * R, r1 - 1, rows_i, b);
+            consume_tile<CPT, R, WAVES, XL, TAIL>(t0, xs, xl, acc, sq, red[0], r, r1, lane, wave, xt, acc_tail, tail_sums);
+            load_tile<CPT, R, TAIL>(t0, a_node, ldA, p0, col, yi, dm, dt);
+            tile_rows<R>(p1, r + 3 * R, r1 - 1, rows_i, b);
+            consume_tile<CPT, R, WAVES, XL, TAIL>(t1, xs, xl, acc, sq, red[1], r + R, r1, lane, wave, xt, acc_tail, tail_sums);
         }
     } else {
         Tile<CPT, R> t0;
         int buf = 0;
+        int p0[R];   // physical rows of the next tile
+        tile_rows<R>(p0, r0, r1 - 1, rows_i, b);
         for (int r = r0; r < r1; r += R, buf ^= 1) {
             if constexpr (XL) {   // the column offsets are worked out per row here: eight registers the kernel lacks
                 int c0 = 4 * static_cast<int>(threadIdx.x);
@@ -410,8 +429,10 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
                     col[q] = c < static_cast<int>(dm) ? c : static_cast<int>(dm) - 4;
                 }
             }
-            load_tile<CPT, R, TAIL>(t0, a_node, ldA, r, r1 - 1, col, rows_i, b, dm, dt);
-            consume_tile<CPT, R, WAVES, XL, TAIL>(t0, xs, xl, acc, sq, red[buf], yi, r, r1, lane, wave, rows_i, b, xt, acc_tail, tail_sums);
+            if constexpr (XL) tile_rows<R>(p0, r, r1 - 1, rows_i, b);   // (no register to carry a row number through the tile)
+            load_tile<CPT, R, TAIL>(t0, a_node, ldA, p0, col, yi, dm, dt);
+            if constexpr (!XL) tile_rows<R>(p0, r + R, r1 - 1, rows_i, b);
+            consume_tile<CPT, R, WAVES, XL, TAIL>(t0, xs, xl, acc, sq, red[buf], r, r1, lane, wave, xt, acc_tail, tail_sums);
         }
     }
 
@@ -484,20 +505,30 @@ __global__ __launch_bounds__(256) void k_fused_rows(const float* __restrict__ A,
     const float* __restrict__ a_node = A + static_cast<int64_t>(i) * b * ldA;
     const float* __restrict__ yi = y + static_cast<int64_t>(i) * b;
 
-    for (int r = r0; r < r1; r += STEP * R) {
-        vfv a[R][CPW];
-        float yv[R];
-        // all loads first; rows past the block's end read its last row and count for nothing
+    // the lane's physical rows of an iteration: rows past the block's end read its last row and count for nothing;
+    // sampled rows are looked up one iteration ahead, so that the loads of A never wait for the look-up
+    int pr[R];
+    const auto rows_of = [&](int r) {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             const int row = r + j * STEP + slot;
-            int pr = row < r1 ? row : r1 - 1;
-            if (rows_i) pr = physical_row(rows_i, pr, b);
-            const float* __restrict__ a_row = a_node + static_cast<int64_t>(pr) * ldA;
+            pr[j] = row < r1 ? row : r1 - 1;
+            if (rows_i) pr[j] = physical_row(rows_i, pr[j], b);
+        }
+    };
+    rows_of(r0);
+    for (int r = r0; r < r1; r += STEP * R) {
+        vfv a[R][CPW];
+        float yv[R];
+        // all loads first
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const float* __restrict__ a_row = a_node + static_cast<int64_t>(pr[j]) * ldA;
 #pragma unroll
             for (int q = 0; q < CPW; ++q) a[j][q] = __builtin_nontemporal_load(reinterpret_cast<const vfv*>(a_row + col[q]));
-            yv[j] = yi[pr];
+            yv[j] = yi[pr[j]];
         }
+        rows_of(r + STEP * R);
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             double s0 = 0.0, s1 = 0.0;
