@@ -21,8 +21,8 @@ constexpr int kThreads = 256;
 constexpr int kOut = 5;
 constexpr int64_t kSplitMinColumns = 1 << 20;   // below this a call keeps the plain order (as the step kernel does)
 constexpr int64_t kMaxBlocks = 32768;          // workgroups per launch (see blocks_for)
-// partial sums in the workspace: [output][slot]; the launches of one call follow one another: the body in the
-// split order (or all of it in plain order), up to two short plain launches around it, the tail
+// partial sums in the workspace: [output][slot]; the launches of one call follow one another: the body (in the
+// split order or not), a short plain launch for what precedes the first 64 KiB unit, the tail
 constexpr int64_t kSlotPitch = 2 * kMaxBlocks + 64;
 typedef float vf4 __attribute__((ext_vector_type(4)));
 
@@ -45,7 +45,7 @@ __device__ __forceinline__ void load_cols(const float* __restrict__ p, float (&v
 // HAS_M, HAS_REF: whether m and ref are given (compile-time, so that no load sits behind a test).
 // Rows are taken ROWS at a time: all their loads go out before the first one is used (rows past the
 // last are clamped to it for the load and skipped in the sums).
-// SPLIT (VEC = 4, d a multiple of 16384, x + c on 64 KiB boundaries for c = 0 in every row that matters): a wave's
+// SPLIT (VEC = 4, the first split_cols columns, a multiple of 16384, with x on a 64 KiB boundary): a wave's
 // 256 columns are the two 512-byte segments 32 KiB apart of the step kernel's split tiles (step::split_column)
 // instead of one run of 1 KiB: the order in which this GPU's memory streams at the same rate on every machine.
 //
@@ -55,14 +55,15 @@ __device__ __forceinline__ void load_cols(const float* __restrict__ p, float (&v
 template <int VEC, bool HAS_M, bool HAS_REF, bool SPLIT, int THREADS, int ROWS>
 __global__ __launch_bounds__(THREADS) void k_stats(const float* __restrict__ x, const float* __restrict__ m,
                                                      const float* __restrict__ ref, int n, int64_t d,
-                                                     int64_t ld, double* __restrict__ slots) {
+                                                     int64_t ld, double* __restrict__ slots, int64_t split_cols) {
     __shared__ double red[THREADS / 64][kOut];
     double acc[kOut] = {0.0, 0.0, 0.0, 0.0, 0.0};
     // a workgroup walks over every gridDim.x-th block of THREADS * VEC columns: the number of
     // partial-sum slots stays small whatever d is, and the mapping is fixed, so sums are reproducible
     for (int64_t c0 = (static_cast<int64_t>(blockIdx.x) * THREADS + threadIdx.x) * VEC; c0 < d;
          c0 += static_cast<int64_t>(gridDim.x) * THREADS * VEC) {  // d is a multiple of VEC for this launch
-        const int64_t c = SPLIT ? step::split_column(static_cast<uint32_t>(c0 >> 8), static_cast<int>(threadIdx.x & 63)) : c0;
+        // SPLIT: the first split_cols columns (whole 64 KiB units) in the split order, the rest as they come
+        const int64_t c = SPLIT && c0 < split_cols ? step::split_column(static_cast<uint32_t>(c0 >> 8), static_cast<int>(threadIdx.x & 63)) : c0;
         float pv[VEC], rv[VEC];
         load_cols<VEC>(x + c, pv);
         if constexpr (HAS_REF) load_cols<VEC>(ref + c, rv);
@@ -180,8 +181,9 @@ int launch_stats(const float* x, const float* m, const float* ref, int32_t n, in
     const int64_t body = vec4 ? (d / 4) * 4 : 0;
     const int64_t tail = d - body;
     int64_t used = 0;   // slots handed out so far
-    // columns [first, first + cols) in one launch; split: in the split order (cols a multiple of 16384)
-    auto launch = [&](auto vec_tag, auto split_tag, int64_t first, int64_t cols) {
+    // columns [first, first + cols) in one launch; split: the first split_cols of them (a multiple of 16384) in the
+    // split order
+    auto launch = [&](auto vec_tag, auto split_tag, int64_t first, int64_t cols, int64_t split_cols) {
         constexpr int V = decltype(vec_tag)::value;
         constexpr bool S = decltype(split_tag)::value;
         const bool big = V == 4 && (S || cols >= kSplitMinColumns);   // every split launch is a big one
@@ -197,12 +199,12 @@ int launch_stats(const float* x, const float* m, const float* ref, int32_t n, in
             constexpr bool M = decltype(has_m)::value, R = decltype(has_ref)::value;
             if constexpr (V == 4) {
                 if (big) {
-                    hipLaunchKernelGGL((k_stats<4, M, R, S, 1024, 4>), grid, dim3(1024), 0, stream, xp, mp, rp, n, cols, ld, out_slots);
+                    hipLaunchKernelGGL((k_stats<4, M, R, S, 1024, 4>), grid, dim3(1024), 0, stream, xp, mp, rp, n, cols, ld, out_slots, split_cols);
                     return;
                 }
             }
             if constexpr (!S)   // the split order is for the big launches only
-                hipLaunchKernelGGL((k_stats<V, M, R, false, kThreads, 8>), grid, dim3(kThreads), 0, stream, xp, mp, rp, n, cols, ld, out_slots);
+                hipLaunchKernelGGL((k_stats<V, M, R, false, kThreads, 8>), grid, dim3(kThreads), 0, stream, xp, mp, rp, n, cols, ld, out_slots, split_cols);
         };
         if (mp && rp) go(std::true_type(), std::true_type());
         else if (mp) go(std::true_type(), std::false_type());
@@ -213,7 +215,9 @@ int launch_stats(const float* x, const float* m, const float* ref, int32_t n, in
     const std::integral_constant<int, 4> wide;
     const std::integral_constant<int, 1> narrow;
     // Large states whose rows share their offset inside a 128-byte line: the whole 64 KiB units of x go out in
-    // the split order (the bulk, first), the columns before and after them in plain order.
+    // the split order and the columns after them ride along in plain order (a launch of their own, eight
+    // workgroups, took 11 us after the 1.04 ms of the units on 32 x 25.6 M); the columns before the first unit
+    // are a launch of their own.
     int64_t pre = 0, units = 0;
     if (body >= kSplitMinColumns && ld % 32 == 0) {
         const uintptr_t at = reinterpret_cast<uintptr_t>(x) % (4u * step::kSplitUnit);
@@ -221,14 +225,12 @@ int launch_stats(const float* x, const float* m, const float* ref, int32_t n, in
         units = (body - pre) / step::kSplitUnit;
     }
     if (units > 0) {
-        const int64_t mid = units * step::kSplitUnit;
-        if (int rc = launch(wide, std::true_type(), pre, mid)) return rc;
-        if (int rc = launch(wide, std::false_type(), 0, pre)) return rc;
-        if (int rc = launch(wide, std::false_type(), pre + mid, body - pre - mid)) return rc;
-    } else if (int rc = launch(wide, std::false_type(), 0, body)) {
+        if (int rc = launch(wide, std::true_type(), pre, body - pre, units * step::kSplitUnit)) return rc;
+        if (int rc = launch(wide, std::false_type(), 0, pre, 0)) return rc;
+    } else if (int rc = launch(wide, std::false_type(), 0, body, 0)) {
         return rc;
     }
-    if (int rc = launch(narrow, std::false_type(), body, tail)) return rc;
+    if (int rc = launch(narrow, std::false_type(), body, tail, 0)) return rc;
     hipLaunchKernelGGL(k_stats_finish, dim3(kOut), dim3(kFinishThreads), 0, stream, slots, used, out);
     return check_hip(hipGetLastError(), "stats finish kernel launch");
 }
