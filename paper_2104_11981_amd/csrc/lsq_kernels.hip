@@ -806,7 +806,7 @@ int fused_splits(int32_t n, int32_t b, int64_t d, int rows_per_iteration) {
 int fused_rows(int64_t d) {
     return d <= 32 ? 256 : d <= 64 ? 128 : d <= 128 ? 64 : d <= 256 ? 32 : d <= 512 ? 16 : d <= 1024 ? 8 : d <= 2048 ? 4 : d <= 4096 ? 2 : 1;
 }
-int fused_cpt(int64_t d) { return d <= 2048 ? 2 : d <= 4096 ? 4 : 8; }   // beyond the short rows
+int fused_cpt(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : 8; }   // (1: a handful of rows of 513-1024 columns)
 constexpr int kMaxNarrowD = 16384;  // rows off the 16-byte boundaries: 1024 threads x 16 columns
 constexpr int kMaxFusedD = 32768;   // 1024 threads x 8 chunks of 4 columns (from 16385 on with x_i in LDS)
 
@@ -840,6 +840,10 @@ int launch_fused(int cpt, dim3 grid, hipStream_t stream, const float* A, const f
                  double* sq_partial, int32_t b, int64_t d, int64_t ldA, int64_t ld, int fs, const int32_t* rows, int32_t bs) {
     const dim3 block(kThreads);
     switch (cpt) {
+        case 1:   // a handful of rows per node, see launch_lsq
+            if constexpr (!TAIL)
+                hipLaunchKernelGGL((k_fused<1, 4, true, 256, false, false>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+            break;
         case 2: hipLaunchKernelGGL((k_fused<2, 2, true, 256, false, TAIL>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
         case 4: hipLaunchKernelGGL((k_fused<4, 1, true, 256, false, TAIL>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
         default:
@@ -958,7 +962,10 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
         const dim3 grid(static_cast<unsigned>(fs), static_cast<unsigned>(n));
         int rc;
         const bool even = ldA % 2 == 0 && (reinterpret_cast<uintptr_t>(A) & 7u) == 0;
-        if (d <= kMaxRowsKernelD) {
+        // (up to 64 rows per node of 513-1024 columns on 16-byte boundaries keep k_fused with one chunk per thread: such
+        // calls are bound by latency, and its 5.5 us against 6.2 are 5 % of the small least-squares workload's iteration)
+        const bool few_rows = bs <= 64 && d > 512 && aligned_rows && d % 4 == 0;
+        if (d <= kMaxRowsKernelD && !few_rows) {
             if (aligned_rows && d % 4 == 0)
                 rc = launch_fused_rows<4>(grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
             else if (even && d % 2 == 0)
