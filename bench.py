@@ -581,17 +581,23 @@ def bench_small(P, workloads, steps=2000, warmup=200):
     return out
 
 
-def bench_lsq_shape(P, n, b, d, steps, warmup):
-    """local_grad_lsq on synthetic N(0,1) data of the given shape: time per call, rate of the 4 n b d bytes of A."""
+def bench_lsq_shape(P, n, b, d, steps, warmup, sampled=0):
+    """local_grad_lsq on synthetic N(0,1) data of the given shape: time per call, rate of the 4 n b d bytes of A.
+    sampled > 0: the mini-batch form over that many of the b rows per node, drawn at random without replacement
+    (seeded); the rate is then that of the rows read."""
     import torch
 
     A = torch.randn((n, b, d), device="cuda")
     y = torch.randn((n, b), device="cuda")
     x = torch.randn((n, d), device="cuda")
     g = torch.empty_like(x)
-    ws = torch.empty(P.local_grad_lsq_workspace(n, b, d), dtype=torch.uint8, device="cuda")
-    _, ms = time_launches(lambda k: P.local_grad_lsq(A, y, x, g, None, 1.0, ws), steps, warmup)
-    nbytes = 4 * n * b * d
+    rows = None
+    if sampled:
+        gen = torch.Generator(device="cuda").manual_seed(11981)
+        rows = torch.stack([torch.randperm(b, device="cuda", generator=gen)[:sampled] for _ in range(n)]).to(torch.int32).contiguous()
+    ws = torch.empty(P.local_grad_lsq_workspace(n, sampled or b, d), dtype=torch.uint8, device="cuda")
+    _, ms = time_launches(lambda k: P.local_grad_lsq(A, y, x, g, None, 1.0, ws, rows=rows), steps, warmup)
+    nbytes = 4 * n * (sampled or b) * d
     del A, y, x, g, ws
     torch.cuda.empty_cache()
     return {"ms_per_call": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
@@ -878,6 +884,10 @@ def main():
         extras["local_grad_lsq_short_rows"] = {
             f"n{n}_b{b}_d{d}": bench_lsq_shape(P, n, b, d, args.steps, args.warmup)
             for n, b, d in ((64, 4096, 1024), (64, 32768, 128))}
+        # the mini-batch form: rows drawn at random from each node's 4096
+        extras["local_grad_lsq_sampled_rows"] = {
+            f"n64_b4096_d4096_bs{bs}": bench_lsq_shape(P, 64, 4096, 4096, args.steps, args.warmup, sampled=bs)
+            for bs in (1024, 4096)}
         # contiguous A whose rows are not on 16-byte boundaries: on 8-byte ones (even d) and on none (odd d)
         extras["local_grad_lsq_rows_off_16_byte_boundaries"] = {
             f"n{n}_b{b}_d{d}": bench_lsq_shape(P, n, b, d, args.steps, args.warmup)

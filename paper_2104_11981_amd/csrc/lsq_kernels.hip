@@ -233,6 +233,46 @@ __device__ __forceinline__ void tile_rows(int (&prow)[R], int r, int r_last, con
     }
 }
 
+// The same with the look-ups of 128 consecutive logical rows kept in two registers per lane (lane j: rows base + j and
+// base + 64 + j), fetched by vector loads 64 rows or more ahead of their use and handed out with readlane: a scalar
+// look-up per tile shares its counter with the tile's LDS traffic, and waiting for one means waiting for the other
+// (64 nodes, 4096 sampled rows of 4096 columns: see launch_lsq).  Requests must come in non-decreasing row order and
+// advance by less than 64 rows at a time; the forms with 1024 threads have no registers for this and look up row by row.
+struct RowWindow {
+    const int32_t* rows_i;
+    int b, r_last, base;
+    int lo, hi;
+    __device__ __forceinline__ int fetch(int first) const {
+        const int row = first + static_cast<int>(threadIdx.x & 63);
+        return physical_row(rows_i, row < r_last ? row : r_last, b);
+    }
+    __device__ __forceinline__ void init(const int32_t* __restrict__ rows, int b_, int r0, int r_last_) {
+        rows_i = rows; b = b_; r_last = r_last_; base = r0;
+        lo = hi = 0;
+        if (rows_i) {
+            lo = fetch(r0);
+            hi = fetch(r0 + 64);
+        }
+    }
+    template <int R>
+    __device__ __forceinline__ void tile(int (&prow)[R], int r) {
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+            const int row = (r + rr < r_last) ? r + rr : r_last;   // uniform
+            if (rows_i) {
+                if (row - base >= 64) {   // uniform; the window moves on by 64 rows, the next 64 look-ups go out
+                    base += 64;
+                    lo = hi;
+                    hi = fetch(base + 64);
+                }
+                prow[rr] = __builtin_amdgcn_readlane(lo, row - base);
+            } else {
+                prow[rr] = row;
+            }
+        }
+    }
+};
+
 // Loads never need a predicate: rows past the block's end are clamped to its last row (their
 // residual is forced to zero below) and column chunks past d are clamped to the last chunk
 // (their x is zero and their accumulators are never stored).
@@ -403,22 +443,31 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
     if constexpr (PF) {
         Tile<CPT, R> t0, t1;
         int p0[R], p1[R];   // physical rows of the tile that is loaded next into t0 / t1
-        tile_rows<R>(p0, r0, r1 - 1, rows_i, b);
+        RowWindow win;
+        win.init(rows_i, b, r0, r1 - 1);
+        win.tile<R>(p0, r0);
         load_tile<CPT, R, TAIL>(t0, a_node, ldA, p0, col, yi, dm, dt);
-        tile_rows<R>(p1, r0 + R, r1 - 1, rows_i, b);
+        win.tile<R>(p1, r0 + R);
         for (int r = r0; r < r1; r += 2 * R) {
             load_tile<CPT, R, TAIL>(t1, a_node, ldA, p1, col, yi, dm, dt);
-            tile_rows<R>(p0, r + 2 * R, r1 - 1, rows_i, b);
+            win.tile<R>(p0, r + 2 * R);
             consume_tile<CPT, R, WAVES, XL, TAIL>(t0, xs, xl, acc, sq, red[0], r, r1, lane, wave, xt, acc_tail, tail_sums);
             load_tile<CPT, R, TAIL>(t0, a_node, ldA, p0, col, yi, dm, dt);
-            tile_rows<R>(p1, r + 3 * R, r1 - 1, rows_i, b);
+            win.tile<R>(p1, r + 3 * R);
             consume_tile<CPT, R, WAVES, XL, TAIL>(t1, xs, xl, acc, sq, red[1], r + R, r1, lane, wave, xt, acc_tail, tail_sums);
         }
     } else {
         Tile<CPT, R> t0;
         int buf = 0;
         int p0[R];   // physical rows of the next tile
-        tile_rows<R>(p0, r0, r1 - 1, rows_i, b);
+        constexpr bool kWindow = THREADS == 256;   // see RowWindow
+        RowWindow win;
+        if constexpr (kWindow) {
+            win.init(rows_i, b, r0, r1 - 1);
+            win.tile<R>(p0, r0);
+        } else {
+            tile_rows<R>(p0, r0, r1 - 1, rows_i, b);
+        }
         for (int r = r0; r < r1; r += R, buf ^= 1) {
             if constexpr (XL) {   // the column offsets are worked out per row here: eight registers the kernel lacks
                 int c0 = 4 * static_cast<int>(threadIdx.x);
@@ -431,7 +480,8 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
             }
             if constexpr (XL) tile_rows<R>(p0, r, r1 - 1, rows_i, b);   // (no register to carry a row number through the tile)
             load_tile<CPT, R, TAIL>(t0, a_node, ldA, p0, col, yi, dm, dt);
-            if constexpr (!XL) tile_rows<R>(p0, r + R, r1 - 1, rows_i, b);
+            if constexpr (kWindow) win.tile<R>(p0, r + R);
+            else if constexpr (!XL) tile_rows<R>(p0, r + R, r1 - 1, rows_i, b);
             consume_tile<CPT, R, WAVES, XL, TAIL>(t0, xs, xl, acc, sq, red[buf], r, r1, lane, wave, xt, acc_tail, tail_sums);
         }
     }

@@ -494,7 +494,12 @@ def test_decentlam_stays_bounded_on_symmetric_graphs(P):
                                           (3, 900, 48, 100, 0),       # short rows: 16 lanes per row, ragged row groups
                                           (2, 500, 200, 37, 0),       # a wave per row
                                           (2, 300, 30, 50, 0),        # 8-byte accesses
-                                          (2, 200, 999, 13, 0)])      # 4-byte accesses, sixteen chunks per lane
+                                          (2, 200, 999, 13, 0),       # 4-byte accesses, sixteen chunks per lane
+                                          # more than 128 sampled rows per workgroup: the look-ups wait in registers, 64 at a time
+                                          (40, 700, 1100, 3000, 0),   # two chunks per thread, two rows per tile
+                                          (40, 300, 4100, 2600, 4),   # eight chunks per thread, no prefetch
+                                          (64, 200, 2052, 1500, 0),   # four chunks per thread
+                                          (40, 500, 1030, 2000, 2)])  # d not a multiple of 4
 def test_local_grad_lsq_rows_matches_oracle(P, oracle, n, b, d, bs, pad):
     rng = np.random.default_rng(n * 1000 + bs)
     A0 = rng.standard_normal((n, b, d)).astype(np.float32)
