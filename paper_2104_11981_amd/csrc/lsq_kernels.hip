@@ -237,7 +237,7 @@ __device__ __forceinline__ void tile_rows(int (&prow)[R], int r, int r_last, con
 // base + 64 + j), fetched by vector loads 64 rows or more ahead of their use and handed out with readlane: a scalar
 // look-up per tile shares its counter with the tile's LDS traffic, and waiting for one means waiting for the other
 // (64 nodes, 4096 sampled rows of 4096 columns: see launch_lsq).  Requests must come in non-decreasing row order and
-// advance by less than 64 rows at a time; the forms with 1024 threads have no registers for this and look up row by row.
+// advance by less than 64 rows at a time; the form with x_i in LDS has no registers for this and looks up row by row.
 struct RowWindow {
     const int32_t* rows_i;
     int b, r_last, base;
@@ -460,7 +460,7 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 
         Tile<CPT, R> t0;
         int buf = 0;
         int p0[R];   // physical rows of the next tile
-        constexpr bool kWindow = THREADS == 256;   // see RowWindow
+        constexpr bool kWindow = !XL;   // see RowWindow; the form with x_i in LDS has no register left for it
         RowWindow win;
         if constexpr (kWindow) {
             win.init(rows_i, b, r0, r1 - 1);
