@@ -470,7 +470,9 @@ int dsgd_step(float* x, const float* g,
  * HBM peak; 4096 x 4095 with ldA = 4096: 0.63 ms).  Rows of A on 8-byte boundaries only (8 nodes of 4096 x 7850,
  * contiguous: 0.19 ms, 0.67) or on none (4096 x 4095 with ldA = 4095: 1.05 ms, 0.51) are still read once, with
  * narrower accesses, up to d = 16384, so pad ldA where that is possible.  Rows of up to 1024 columns are handled a
- * wave per row (64 nodes of 32768 x 128: 0.78 of the peak, of 4096 x 1024: 0.85), at any alignment.  Wider rows than these limits take two
+ * wave per row (64 nodes of 32768 x 128: 0.78 of the peak, of 4096 x 1024: 0.85), at any alignment.  Between the
+ * sizes named here the rate moves between 0.7 and 0.85 with how well d fills the kernel's shape (steps of 256
+ * columns up to 2560, of 1024 up to 8192, of 4096 beyond; lowest, 0.56-0.6, just above 8192).  Wider rows than these limits take two
  * passes over A at 0.3-0.35 of the peak.  No access reaches past column d of a row in any case.
  * Products and sums run as fp64 fused multiply-adds on the vector units; the matrix cores are
  * not used: an MFMA tile would have one useful column in sixteen, and for fp32 / fp64 the matrix and

@@ -386,7 +386,7 @@ __device__ __forceinline__ void consume_tile(const Tile<CPT, R>& t, const float 
 // threads with four chunks, with or without prefetch, are slower than 256 with eight: 64 nodes of 1024 x 6144
 // 5.6-5.8 against 6.2 TB/s)
 template <int CPT, int R, bool PF, int THREADS, bool XL = false, bool TAIL = false>
-__global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : ((PF || CPT >= 8) ? 2 : 4)) void k_fused(const float* __restrict__ A, const float* __restrict__ y,
+__global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : 2) void k_fused(const float* __restrict__ A, const float* __restrict__ y,
                                                      const float* __restrict__ x, double* __restrict__ partial,
                                                      double* __restrict__ sq_partial, int b, int64_t d,
                                                      int64_t ldA, int64_t ld, int splits,
@@ -524,7 +524,8 @@ __global__ __launch_bounds__(256) void k_fused_rows(const float* __restrict__ A,
     typedef float vfv __attribute__((ext_vector_type(V)));
     constexpr int G = 64 / L;       // rows per wave-wide access
     constexpr int STEP = 4 * G;     // rows per workgroup-wide access
-    constexpr int COLS = V * L * CPW;
+    constexpr int QG = CPW < 4 ? CPW : 4;   // chunks per lane that pass through LDS together at the end
+    constexpr int COLS = V * L * QG;
     __shared__ double sums[STEP][COLS];
     __shared__ double sq_wave[4];
     const int i = blockIdx.y, s = blockIdx.x;
@@ -603,21 +604,27 @@ __global__ __launch_bounds__(256) void k_fused_rows(const float* __restrict__ A,
         }
     }
 
-    // the STEP row slots of the workgroup hold sums over disjoint rows for the same columns: add them in slot order
-#pragma unroll
-    for (int q = 0; q < CPW; ++q) {
-#pragma unroll
-        for (int v = 0; v < V; ++v) sums[slot][V * (sub + q * L) + v] = acc[q][v];
-    }
+    // the STEP row slots of the workgroup hold sums over disjoint rows for the same columns: add them in slot order,
+    // up to four chunks per lane (COLS columns) at a time
     sq = wave_sum(sq);
     if (lane == 0) sq_wave[wave] = sq;
-    __syncthreads();
     double* out = partial + (static_cast<int64_t>(i) * splits + s) * d;
-    for (int c = threadIdx.x; c < d; c += 256) {
-        double total = 0.0;
 #pragma unroll
-        for (int k = 0; k < STEP; ++k) total += sums[k][c];
-        out[c] = total;
+    for (int q0 = 0; q0 < CPW; q0 += QG) {
+        if (q0 > 0) __syncthreads();   // the previous group has been read
+#pragma unroll
+        for (int q = q0; q < q0 + QG && q < CPW; ++q) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) sums[slot][V * (sub + (q - q0) * L) + v] = acc[q][v];
+        }
+        __syncthreads();
+        const int first = V * L * q0;   // first column of the group
+        for (int c = threadIdx.x; c < COLS && first + c < d; c += 256) {
+            double total = 0.0;
+#pragma unroll
+            for (int k = 0; k < STEP; ++k) total += sums[k][c];
+            out[first + c] = total;
+        }
     }
     if (threadIdx.x == 0) sq_partial[static_cast<int64_t>(i) * splits + s] = (sq_wave[0] + sq_wave[1]) + (sq_wave[2] + sq_wave[3]);
 }
@@ -856,12 +863,20 @@ int fused_splits(int32_t n, int32_t b, int64_t d, int rows_per_iteration) {
 int fused_rows(int64_t d) {
     return d <= 32 ? 256 : d <= 64 ? 128 : d <= 128 ? 64 : d <= 256 ? 32 : d <= 512 ? 16 : d <= 1024 ? 8 : d <= 2048 ? 4 : d <= 4096 ? 2 : 1;
 }
-int fused_cpt(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : 8; }   // (1: a handful of rows of 513-1024 columns)
 constexpr int kMaxNarrowD = 16384;  // rows off the 16-byte boundaries: 1024 threads x 16 columns
 constexpr int kMaxFusedD = 32768;   // 1024 threads x 8 chunks of 4 columns (from 16385 on with x_i in LDS)
 
 // Short rows: a wave per row (or per 2, 4, 8 rows); V columns per access and lane.
-constexpr int kMaxRowsKernelD = 1024;
+constexpr int kMaxRowsKernelD = 1024;   // any alignment
+// With rows on 16-byte boundaries and d a multiple of 4 the wave-per-row kernel also beats k_fused where k_fused's
+// shapes fit badly, its steps being 256 columns where k_fused's are 1024 (16 nodes, 256 M elements of A, fraction
+// of the HBM peak, k_fused_rows / k_fused): d = 1028 0.85 / 0.42, 1540 0.82 / 0.72, 1792 0.80, 1900 - / 0.69,
+// 2000 - / 0.80, 2048 0.79 / 0.82, 2052 0.76 / 0.61, 2560 0.77 / 0.65, 2564 - / 0.83, 2600 0.68 / -, 3000 0.73 / 0.83
+// (k_fused with three chunks per thread from 2561 on).
+bool rows_kernel_serves(int64_t d, bool aligned_rows) {
+    if (d <= kMaxRowsKernelD) return true;
+    return aligned_rows && d % 4 == 0 && (d <= 1960 || (d > 2048 && d <= 2560));
+}
 template <int V>
 int launch_fused_rows(dim3 grid, hipStream_t stream, const float* A, const float* y, const float* x, double* fpartial,
                       double* sq_partial, int32_t b, int64_t d, int64_t ldA, int64_t ld, int fs, const int32_t* rows,
@@ -875,8 +890,15 @@ int launch_fused_rows(dim3 grid, hipStream_t stream, const float* A, const float
     else if (chunks <= 32) DL_ROWS_KERNEL(1, 32, 8);
     else if (chunks <= 64) DL_ROWS_KERNEL(1, 64, 8);
     else if (chunks <= 128) DL_ROWS_KERNEL(2, 64, 4);
+    else if (chunks <= 192) DL_ROWS_KERNEL(3, 64, 2);
     else if (chunks <= 256) DL_ROWS_KERNEL(4, 64, 2);
-    else if constexpr (V < 4) {
+    else if constexpr (V == 4) {   // 1025-1960 and 2049-2560 columns on 16-byte boundaries, see rows_kernel_serves
+        if (chunks <= 320) DL_ROWS_KERNEL(5, 64, 1);
+        else if (chunks <= 384) DL_ROWS_KERNEL(6, 64, 1);
+        else if (chunks <= 448) DL_ROWS_KERNEL(7, 64, 1);
+        else if (chunks <= 512) DL_ROWS_KERNEL(8, 64, 1);
+        else DL_ROWS_KERNEL(10, 64, 1);
+    } else {
         if (chunks <= 512) DL_ROWS_KERNEL(8, 64, 1);
         else if constexpr (V < 2) DL_ROWS_KERNEL(16, 64, 1);
     }
@@ -885,41 +907,50 @@ int launch_fused_rows(dim3 grid, hipStream_t stream, const float* A, const float
 }
 
 // The single sweep's kernel by columns per row (TAIL: d is not a multiple of 4).
+// One chunk column of 1024 (256 threads) or 4096 (1024 threads) columns more per shape: a shape made for twice the
+// columns loads, and throws away, up to as much again as it uses (16 nodes, 256 M elements of A: d = 2500 / 5000 /
+// 10000 / 20000 ran at 0.64 / 0.65 / 0.59 / 0.64 of the HBM peak with the shapes of 4096 / 8192 / 16384 / 32768 columns).
 template <bool TAIL>
-int launch_fused(int cpt, dim3 grid, hipStream_t stream, const float* A, const float* y, const float* x, double* fpartial,
+int launch_fused(dim3 grid, hipStream_t stream, const float* A, const float* y, const float* x, double* fpartial,
                  double* sq_partial, int32_t b, int64_t d, int64_t ldA, int64_t ld, int fs, const int32_t* rows, int32_t bs) {
-    const dim3 block(kThreads);
-    switch (cpt) {
-        case 1:   // a handful of rows per node, see launch_lsq
-            if constexpr (!TAIL)
-                hipLaunchKernelGGL((k_fused<1, 4, true, 256, false, false>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
-            break;
-        case 2: hipLaunchKernelGGL((k_fused<2, 2, true, 256, false, TAIL>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
-        case 4: hipLaunchKernelGGL((k_fused<4, 1, true, 256, false, TAIL>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs); break;
-        default:
-            if (d <= 8192)
-                hipLaunchKernelGGL((k_fused<8, 1, false, 256, false, TAIL>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
-            else if (d <= 16384)
-                hipLaunchKernelGGL((k_fused<4, 1, false, 1024, false, TAIL>), grid, dim3(1024), 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
-            else {
-                // eight chunks per thread: a row of A (32 registers) and the accumulators (64) fill the thread's 128
-                // registers, so its 128 bytes of x_i wait in LDS (128 KiB per workgroup, one workgroup per CU)
-                auto wide = k_fused<8, 1, false, 1024, true, TAIL>;
-                static std::atomic<uint64_t> configured{0};   // one bit per device ordinal below 64
-                int device = 0;
-                if (int rc = check_hip(hipGetDevice(&device), "hipGetDevice")) return rc;
-                const uint64_t bit = device >= 0 && device < 64 ? uint64_t{1} << device : uint64_t{0};
-                if (!(configured.load(std::memory_order_relaxed) & bit) || bit == 0) {
-                    if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(wide),
-                                                               hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024),
-                                           "hipFuncSetAttribute(max dynamic LDS)"))
-                        return rc;
-                    configured.fetch_or(bit, std::memory_order_relaxed);
-                }
-                hipLaunchKernelGGL(wide, grid, dim3(1024), 128 * 1024, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
-            }
-            break;
+#define DL_FUSED(CPT, R, PF, THREADS) \
+    hipLaunchKernelGGL((k_fused<CPT, R, PF, THREADS, false, TAIL>), grid, dim3(THREADS), 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs)
+    // more than 16384 columns: eight chunks per thread would be a row of A (32 registers) and the accumulators (64)
+    // filling the thread's 128 registers, so its chunks of x_i wait in LDS (16 KiB per chunk column, one workgroup per CU)
+    auto wide = [&](auto chunks) -> int {
+        constexpr int CPT = decltype(chunks)::value;
+        auto kernel = k_fused<CPT, 1, false, 1024, true, TAIL>;
+        static std::atomic<uint64_t> configured{0};   // per instantiation: one bit per device ordinal below 64
+        int device = 0;
+        if (int rc = check_hip(hipGetDevice(&device), "hipGetDevice")) return rc;
+        const uint64_t bit = device >= 0 && device < 64 ? uint64_t{1} << device : uint64_t{0};
+        if (!(configured.load(std::memory_order_relaxed) & bit) || bit == 0) {
+            if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, CPT * 16 * 1024),
+                                   "hipFuncSetAttribute(max dynamic LDS)"))
+                return rc;
+            configured.fetch_or(bit, std::memory_order_relaxed);
+        }
+        hipLaunchKernelGGL(kernel, grid, dim3(1024), CPT * 16 * 1024, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+        return 0;
+    };
+    if (d <= 1024) {   // a handful of rows per node, see launch_lsq
+        if constexpr (!TAIL) DL_FUSED(1, 4, true, 256);
     }
+    else if (d <= 2048) DL_FUSED(2, 2, true, 256);
+    else if (d <= 3072) DL_FUSED(3, 1, true, 256);
+    else if (d <= 4096) DL_FUSED(4, 1, true, 256);
+    else if (d <= 5120) DL_FUSED(5, 1, true, 256);
+    else if (d <= 6144) DL_FUSED(6, 1, false, 256);   // (with prefetch: 0.76-0.78 against 0.82)
+    else if (d <= 7168) DL_FUSED(7, 1, false, 256);
+    else if (d <= 8192) DL_FUSED(8, 1, false, 256);
+    else if (d <= 12288) DL_FUSED(3, 1, false, 1024);   // (with prefetch it does not fit 128 registers)
+    else if (d <= 16384) DL_FUSED(4, 1, false, 1024);
+    else if (d <= 20480) { if (int rc = wide(std::integral_constant<int, 5>())) return rc; }
+    else if (d <= 24576) { if (int rc = wide(std::integral_constant<int, 6>())) return rc; }
+    else if (d <= 28672) { if (int rc = wide(std::integral_constant<int, 7>())) return rc; }
+    else { if (int rc = wide(std::integral_constant<int, 8>())) return rc; }
+#undef DL_FUSED
     return check_hip(hipGetLastError(), "fused gradient kernel launch");
 }
 
@@ -1005,7 +1036,6 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
         return check_hip(hipGetLastError(), "small gradient kernel launch");
     }
     if (path == 1) {
-        const int cpt = fused_cpt(d);
         const int fs = fused_splits(n, bs, d, fused_rows(d));
         double* sq_partial = static_cast<double*>(workspace);
         double* fpartial = sq_partial + ((static_cast<size_t>(n) * fs + 1) & ~size_t{1});
@@ -1015,7 +1045,7 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
         // (up to 64 rows per node of 513-1024 columns on 16-byte boundaries keep k_fused with one chunk per thread: such
         // calls are bound by latency, and its 5.5 us against 6.2 are 5 % of the small least-squares workload's iteration)
         const bool few_rows = bs <= 64 && d > 512 && aligned_rows && d % 4 == 0;
-        if (d <= kMaxRowsKernelD && !few_rows) {
+        if (rows_kernel_serves(d, aligned_rows) && !few_rows) {
             if (aligned_rows && d % 4 == 0)
                 rc = launch_fused_rows<4>(grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
             else if (even && d % 2 == 0)
@@ -1026,8 +1056,8 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
             rc = even ? launch_fused_narrow<2>(grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs)
                       : launch_fused_narrow<1>(grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
         } else {
-            rc = d % 4 == 0 ? launch_fused<false>(cpt, grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs)
-                            : launch_fused<true>(cpt, grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+            rc = d % 4 == 0 ? launch_fused<false>(grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs)
+                            : launch_fused<true>(grid, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
         }
         if (rc) return rc;
         const dim3 grid_ff(static_cast<unsigned>((d + kFinishColumns - 1) / kFinishColumns), static_cast<unsigned>(n));

@@ -245,6 +245,23 @@ LSQ_CASES = [
     (2, 120, 514, 1, 0, 1.0),            # odd ldA with an even d: 4-byte accesses
     (1, 5000, 1, 0, 0, 1.0),             # one column
     (2, 40, 1024, 0, 0, 1.0),            # the widest short row; row blocks shorter than a workgroup's access
+    # shapes between the powers of two: one chunk column more per shape
+    (2, 70, 600, 0, 0, 1.0),             # a wave per row, three chunks per lane
+    (2, 70, 1100, 0, 0, 1.0),            # five
+    (2, 70, 1500, 4, 0, 1.0),            # six
+    (3, 70, 1700, 0, 0, 1.0),            # seven
+    (2, 70, 2300, 0, 0, 1.0),            # ten; the sums pass through LDS in three groups
+    (2, 30, 2800, 0, 0, 1.0),            # a workgroup per row tile, three chunks per thread
+    (2, 30, 2802, 2, 0, 1.0),            # the same with two tail columns
+    (2, 20, 4500, 0, 0, 1.0),            # five chunks per thread
+    (2, 20, 5501, 3, 0, 1.0),            # six, one tail column
+    (2, 20, 6800, 0, 4, 1.0),            # seven
+    (2, 16, 10000, 0, 0, 1.0),           # 1024 threads, three chunks each
+    (1, 12, 10001, 3, 0, 1.0),           # the same with a tail column
+    (1, 12, 24000, 0, 0, 1.0),           # x_i in LDS, six chunks per thread
+    (1, 10, 26000, 0, 0, 1.0),           # seven
+    (1, 10, 27002, 2, 0, 1.0),           # seven, two tail columns
+    (2, 10, 18000, 0, 0, 1.0),           # five
 ]
 
 
