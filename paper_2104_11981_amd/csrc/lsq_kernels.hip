@@ -944,7 +944,7 @@ int launch_fused(dim3 grid, hipStream_t stream, const float* A, const float* y, 
     else if (d <= 6144) DL_FUSED(6, 1, false, 256);   // (with prefetch: 0.76-0.78 against 0.82)
     else if (d <= 7168) DL_FUSED(7, 1, false, 256);
     else if (d <= 8192) DL_FUSED(8, 1, false, 256);
-    else if (d <= 12288) DL_FUSED(3, 1, false, 1024);   // (with prefetch it does not fit 128 registers)
+    else if (d <= 12288) DL_FUSED(3, 1, false, 1024);   // (with prefetch, or as five or six chunks of 512 threads, it does not fit 128 registers)
     else if (d <= 16384) DL_FUSED(4, 1, false, 1024);
     else if (d <= 20480) { if (int rc = wide(std::integral_constant<int, 5>())) return rc; }
     else if (d <= 24576) { if (int rc = wide(std::integral_constant<int, 6>())) return rc; }
