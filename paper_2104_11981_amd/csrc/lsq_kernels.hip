@@ -873,9 +873,12 @@ constexpr int kMaxRowsKernelD = 1024;   // any alignment
 // of the HBM peak, k_fused_rows / k_fused): d = 1028 0.85 / 0.42, 1540 0.82 / 0.72, 1792 0.80, 1900 - / 0.69,
 // 2000 - / 0.80, 2048 0.79 / 0.82, 2052 0.76 / 0.61, 2560 0.77 / 0.65, 2564 - / 0.83, 2600 0.68 / -, 3000 0.73 / 0.83
 // (k_fused with three chunks per thread from 2561 on).
+// Rows off the 16-byte boundaries, or a d that is not a multiple of 4 with aligned rows above 1024: a wave per row up to
+// 2048 columns (k_fused_narrow there, with its barrier per tile of a few short rows: 0.31-0.62 of the peak).
 bool rows_kernel_serves(int64_t d, bool aligned_rows) {
     if (d <= kMaxRowsKernelD) return true;
-    return aligned_rows && d % 4 == 0 && (d <= 1960 || (d > 2048 && d <= 2560));
+    if (!aligned_rows) return d <= 3072;
+    return d % 4 == 0 && (d <= 1960 || (d > 2048 && d <= 2560));
 }
 template <int V>
 int launch_fused_rows(dim3 grid, hipStream_t stream, const float* A, const float* y, const float* x, double* fpartial,
@@ -898,9 +901,20 @@ int launch_fused_rows(dim3 grid, hipStream_t stream, const float* A, const float
         else if (chunks <= 448) DL_ROWS_KERNEL(7, 64, 1);
         else if (chunks <= 512) DL_ROWS_KERNEL(8, 64, 1);
         else DL_ROWS_KERNEL(10, 64, 1);
-    } else {
+    } else if constexpr (V == 2) {   // rows on 8-byte boundaries: up to 2048 columns
         if (chunks <= 512) DL_ROWS_KERNEL(8, 64, 1);
-        else if constexpr (V < 2) DL_ROWS_KERNEL(16, 64, 1);
+        else if (chunks <= 640) DL_ROWS_KERNEL(10, 64, 1);
+        else if (chunks <= 768) DL_ROWS_KERNEL(12, 64, 1);
+        else if (chunks <= 1024) DL_ROWS_KERNEL(16, 64, 1);
+        else if (chunks <= 1280) DL_ROWS_KERNEL(20, 64, 1);
+        else DL_ROWS_KERNEL(24, 64, 1);
+    } else {                         // any rows: up to 2048 columns
+        if (chunks <= 512) DL_ROWS_KERNEL(8, 64, 1);
+        else if (chunks <= 1024) DL_ROWS_KERNEL(16, 64, 1);
+        else if (chunks <= 1536) DL_ROWS_KERNEL(24, 64, 1);
+        else if (chunks <= 2048) DL_ROWS_KERNEL(32, 64, 1);
+        else if (chunks <= 2560) DL_ROWS_KERNEL(40, 64, 1);
+        else DL_ROWS_KERNEL(48, 64, 1);
     }
 #undef DL_ROWS_KERNEL
     return check_hip(hipGetLastError(), "fused gradient kernel launch (short rows)");
@@ -959,15 +973,20 @@ template <int V>
 int launch_fused_narrow(dim3 grid, hipStream_t stream, const float* A, const float* y, const float* x, double* fpartial,
                         double* sq_partial, int32_t b, int64_t d, int64_t ldA, int64_t ld, int fs, const int32_t* rows,
                         int32_t bs) {
-    const dim3 block(kThreads);
-    if (d <= 2048)   // (up to 1024: k_fused_rows)
-        hipLaunchKernelGGL((k_fused_narrow<V, 8, 2, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
-    else if (d <= 4096)
-        hipLaunchKernelGGL((k_fused_narrow<V, 16, 1, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
-    else if (d <= 8192)
-        hipLaunchKernelGGL((k_fused_narrow<V, 32, 1, 256>), grid, block, 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
-    else
-        hipLaunchKernelGGL((k_fused_narrow<V, 16, 1, 1024>), grid, dim3(1024), 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs);
+#define DL_NARROW(K, R, THREADS) \
+    hipLaunchKernelGGL((k_fused_narrow<V, K, R, THREADS>), grid, dim3(THREADS), 0, stream, A, y, x, fpartial, sq_partial, b, d, ldA, ld, fs, rows, bs)
+    // K columns per thread: a shape per 512 or 1024 columns (256 threads), per 4096 beyond 8192; two or four rows per
+    // tile where the columns are few (2502 columns, 8-byte accesses: 0.43 / 0.50 / 0.61 of the peak with 1 / 2 / 4)
+    if (d <= 2560) DL_NARROW(10, 4, 256);   // (up to 2048: k_fused_rows)
+    else if (d <= 3072) DL_NARROW(12, 4, 256);
+    else if (d <= 4096) DL_NARROW(16, 2, 256);
+    else if (d <= 5120) DL_NARROW(20, 2, 256);
+    else if (d <= 6144) DL_NARROW(24, 2, 256);
+    else if (d <= 7168) DL_NARROW(28, 1, 256);
+    else if (d <= 8192) DL_NARROW(32, 1, 256);
+    else if (d <= 12288) DL_NARROW(12, 1, 1024);
+    else DL_NARROW(16, 1, 1024);
+#undef DL_NARROW
     return check_hip(hipGetLastError(), "fused gradient kernel launch (narrow accesses)");
 }
 

@@ -262,6 +262,22 @@ LSQ_CASES = [
     (1, 10, 26000, 0, 0, 1.0),           # seven
     (1, 10, 27002, 2, 0, 1.0),           # seven, two tail columns
     (2, 10, 18000, 0, 0, 1.0),           # five
+    # the same for rows off the 16-byte boundaries
+    (2, 30, 2502, 0, 0, 1.0),            # 8-byte accesses, 12 columns per thread
+    (2, 30, 2999, 0, 0, 1.0),            # 4-byte accesses, 12 columns per thread
+    (2, 20, 5001, 1, 0, 1.0),            # 8-byte accesses with an odd d, 20 columns per thread
+    (2, 20, 6002, 0, 0, 1.0),            # 24 columns per thread
+    (2, 20, 6999, 0, 0, 1.0),            # 4-byte accesses, 28 columns per thread
+    (1, 16, 11001, 0, 0, 1.0),           # 1024 threads, 12 columns each
+    # a wave per row up to 3072 columns off the 16-byte boundaries
+    (2, 60, 1026, 0, 0, 1.0),            # 8-byte accesses, ten chunks per lane
+    (2, 50, 1402, 0, 0, 1.0),            # twelve
+    (2, 50, 1802, 0, 0, 1.0),            # sixteen
+    (2, 40, 3002, 0, 0, 1.0),            # twenty-four
+    (2, 50, 1501, 0, 0, 1.0),            # 4-byte accesses, 24 chunks per lane
+    (2, 50, 2047, 0, 0, 1.0),            # 32
+    (2, 40, 2301, 0, 0, 1.0),            # 40
+    (2, 30, 3071, 1, 0, 1.0),            # 8-byte accesses and an odd d: 4-byte accesses, 48 chunks per lane
 ]
 
 
