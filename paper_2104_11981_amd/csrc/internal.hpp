@@ -127,7 +127,7 @@ int launch_step_wide(Algo algo, float* x, float* m, const float* g, int32_t n, i
 size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d);
 // What the kernels that launch_lsq picks for this shape and alignment actually use (<= lsq_workspace_bytes).
 bool lsq_wide_accesses(const float* A, const float* x, int64_t d, int64_t ldA, int64_t ld);
-int lsq_path(int32_t bs, int64_t d, bool wide_accesses);
+int lsq_path(int32_t bs, int64_t d, bool wide_accesses, bool sampled = false);
 size_t lsq_workspace_bytes_path(int32_t n, int32_t b, int64_t d, int path);
 // rows == nullptr: full-batch gradient over all b rows; otherwise bs sampled rows per node.
 int launch_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,

@@ -20,6 +20,10 @@
 // without fences, with device-scope atomic accesses for everything that crosses blocks, the final sum of one
 // block is a chain of uncached loads: 0.64 ms and 54 us.  The second launch costs less than either.)
 //
+// Single sweep for wider rows (32768 < d <= 131072, d a multiple of 4, rows of A on 16-byte boundaries, all rows of a
+// node): k_fused_split, the columns of a row block split over waves that exchange one number per wave and row
+// through device memory; see there.
+//
 // Small problems (bs * d <= 4096 elements per node, any alignment): k_small, one launch,
 // one workgroup per node with A_i, x_i and the residuals in LDS; such sizes are bound by launch
 // latency, and this is one launch instead of two or three.
@@ -761,6 +765,187 @@ __global__ __launch_bounds__(THREADS) void k_fused_narrow(const float* __restric
     if (threadIdx.x == 0) sq_partial[static_cast<int64_t>(i) * splits + s] = sq;
 }
 
+// ---------------------------------------------------------------- single sweep, rows wider than a workgroup's registers
+// Beyond 32768 columns one workgroup cannot hold a row's accumulators (d fp64 sums), so the columns of a row block are
+// split over several waves, each with its own 2048 columns, its accumulators and no shared memory, and what crosses
+// waves is one number per wave and row: the wave's share of the row's dot product.  Every wave writes its share to
+// its slot of the row (an 8-byte device-scope atomic store, the value is the message), reads the row's slots of all
+// waves (one device-scope atomic load per lane), adds them with the fixed-order wave sum -- the same bits in every wave --
+// and multiplies its tile by that residual.  No fence anywhere: a device-wide fence writes back a whole L2, eight of
+// which this chip has.  A slot that has not been written yet holds kSlotEmpty, a NaN whose low mantissa bits no sum
+// of products of fp32 numbers can have (k_fill_slots writes it before every call).  A row's share is published
+// L iterations before it is collected and its loads are issued LA iterations before that.
+// Measured (fraction of the HBM peak for 4 n b d bytes; the two sweeps: 0.33-0.35): 8 nodes of 1024 x 65536 0.73, 4 of
+// 1024 x 131072 0.73, 4 of 1024 x 98304 0.70, 8 of 2048 x 49152 0.68, 64 of 128 x 65536 0.67, 8 of 1024 x 57344 0.64,
+// 16 of 1024 x 36864 0.53-0.66 (it moved with where the arrays lay), 2 of 4096 x 100000 0.56.  Tried without gain:
+// L = 2 (four tiles of eight chunks do not fit 256 registers; with six or seven chunks per lane they do and shapes
+// that are whole multiples of 1536 or 1792 columns gain 0.03-0.06, but 65536 columns fall to 0.55), the slots read at
+// the top of the iteration (with L = 1 the others' shares are not there yet and the second read costs more than the
+// first saved), one wave per workgroup (0.57-0.71), the rows read through buffer descriptors (same rates).
+// The waves of a row block wait for one another, so all of them must be on the chip together: the launch never has
+// more workgroups than the chip holds at once (launch_fused_split checks the occupancy the runtime reports), and
+// every wait is bounded: a wave that polls kSplitPolls times in vain raises `failed`, stops waiting for the rest of
+// its rows and runs to its end; k_poison_failed then turns that call's g and loss into NaN.
+constexpr int kSplitCPT = 8;                          // 16-byte chunks per lane
+constexpr int kSplitWaveCols = 64 * 4 * kSplitCPT;    // columns per wave: 2048
+constexpr int kSplitWaves = 4;                        // waves per workgroup (they share nothing; neighbours in a row, they read a contiguous piece of it)
+constexpr int kSplitResident = 512;                   // workgroups per launch at most: 256 CUs x 2
+constexpr int64_t kMaxSplitD = 64 * static_cast<int64_t>(kSplitWaveCols);   // 64 slots per row: one load per lane
+constexpr unsigned long long kSlotEmpty = 0x7ff8dec0de5107e1ull;
+constexpr int kSplitPolls = 1 << 21;
+
+__device__ __forceinline__ unsigned long long slot_load(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ __launch_bounds__(kThreads) void k_fill_slots(unsigned long long* __restrict__ slots, int64_t count,
+                                                        unsigned* __restrict__ failed) {
+    for (int64_t k = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; k < count;
+         k += static_cast<int64_t>(gridDim.x) * kThreads)
+        slots[k] = kSlotEmpty;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *failed = 0u;
+}
+
+struct SplitTile {
+    vf4 a[kSplitCPT];
+    float y;
+};
+
+template <int L, int LA>
+__global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float* __restrict__ A, const float* __restrict__ y,
+                                                                    const float* __restrict__ x, double* __restrict__ partial,
+                                                                    double* __restrict__ sq_partial,
+                                                                    unsigned long long* __restrict__ slots,
+                                                                    unsigned* __restrict__ failed, int b, int64_t d,
+                                                                    int64_t ldA, int64_t ld, int splits, int nslots, int node0) {
+    constexpr int NB = L + LA + 1;   // register tiles in rotation
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int gw = static_cast<int>(blockIdx.x) * kSplitWaves + wave;   // this wave's slot; its columns start at 2048 gw
+    if (gw >= nslots) return;   // whole waves only; nothing in this kernel is shared within a workgroup
+    const int s = blockIdx.y, i = node0 + static_cast<int>(blockIdx.z);
+    const int r0 = static_cast<int>(static_cast<int64_t>(b) * s / splits);
+    const int r1 = static_cast<int>(static_cast<int64_t>(b) * (s + 1) / splits);   // r1 > r0: splits <= b
+
+    // a thread's chunks of x_i wait in LDS (xl[256 q], written and read by this thread alone), not in 32 registers
+    __shared__ vf4 x_chunks[kSplitCPT * 64 * kSplitWaves];
+    vf4* xl = x_chunks + threadIdx.x;
+    int col[kSplitCPT];   // chunks past column d are clamped to the last one: their x is zero and their sums are never stored
+    double acc[kSplitCPT][4];
+    const bool x_wide = ((reinterpret_cast<uintptr_t>(x) & 15u) | (static_cast<uint64_t>(ld) & 3u)) == 0;
+#pragma unroll
+    for (int q = 0; q < kSplitCPT; ++q) {
+        const int64_t c = static_cast<int64_t>(gw) * kSplitWaveCols + 256 * q + 4 * lane;
+        const bool inside = c < d;   // d is a multiple of 4: chunks are inside or outside as a whole
+        col[q] = static_cast<int>(inside ? c : d - 4);
+        const float* xp = x + static_cast<int64_t>(i) * ld + col[q];
+        const vf4 xv = x_wide ? *reinterpret_cast<const vf4*>(xp) : vf4{xp[0], xp[1], xp[2], xp[3]};
+        xl[64 * kSplitWaves * q] = inside ? xv : vf4{0.f, 0.f, 0.f, 0.f};
+        acc[q][0] = acc[q][1] = acc[q][2] = acc[q][3] = 0.0;
+    }
+    const float* __restrict__ a_node = A + static_cast<int64_t>(i) * b * ldA;
+    const float* __restrict__ yi = y + static_cast<int64_t>(i) * b;
+    unsigned long long* slots_i = slots + static_cast<int64_t>(i) * b * nslots;
+
+    auto load = [&](SplitTile& t, int r) {   // rows past the block's end read its last row again (never used)
+        const int row = r < r1 ? r : r1 - 1;
+        const float* __restrict__ a_row = a_node + static_cast<int64_t>(row) * ldA;
+        t.y = yi[row];
+#pragma unroll
+        for (int q = 0; q < kSplitCPT; ++q)
+            t.a[q] = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(a_row + col[q]));
+    };
+    auto publish = [&](const SplitTile& t, int r) {   // this wave's share of row r's dot product
+        if (r >= r1) return;   // uniform
+        double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+        for (int q = 0; q < kSplitCPT; ++q) {
+            const vf4 xv = xl[64 * kSplitWaves * q];
+            s0 = __builtin_fma(static_cast<double>(t.a[q].x), static_cast<double>(xv.x), s0);
+            s1 = __builtin_fma(static_cast<double>(t.a[q].y), static_cast<double>(xv.y), s1);
+            s0 = __builtin_fma(static_cast<double>(t.a[q].z), static_cast<double>(xv.z), s0);
+            s1 = __builtin_fma(static_cast<double>(t.a[q].w), static_cast<double>(xv.w), s1);
+        }
+        const double p = wave_sum(s0 + s1);
+        unsigned long long bits = __builtin_bit_cast(unsigned long long, p);
+        if (bits == kSlotEmpty) bits ^= 1ull;   // (cannot happen with fp32 inputs; the mark stays unique anyway)
+        if (lane == 0)
+            __hip_atomic_store(slots_i + static_cast<int64_t>(r) * nslots + gw, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    bool gave_up = false;   // uniform
+    double sq = 0.0;
+    // The row's slots, lane by lane (lanes beyond the last slot read slot 0 and count for nothing).
+    auto peek = [&](int r) -> unsigned long long {
+        const int row = r < r1 ? r : r1 - 1;
+        return slot_load(slots_i + static_cast<int64_t>(row) * nslots + (lane < nslots ? lane : 0));
+    };
+    auto consume = [&](const SplitTile& t, int r, unsigned long long bits) {
+        if (r >= r1) return;   // uniform
+        const unsigned long long* mine = slots_i + static_cast<int64_t>(r) * nslots + (lane < nslots ? lane : 0);
+        if (!gave_up) {
+            int polls = 0;
+            while (__builtin_amdgcn_ballot_w64(bits == kSlotEmpty) != 0ull) {   // until every wave of the block has published
+                if (++polls > kSplitPolls) {
+                    gave_up = true;
+                    if (lane == 0) __hip_atomic_store(failed, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+                bits = slot_load(mine);
+            }
+        }
+        const double share = lane < nslots ? __builtin_bit_cast(double, bits) : 0.0;
+        const double res = wave_sum(share) - static_cast<double>(t.y);   // the same bits in every wave of the block
+        sq = __builtin_fma(res, res, sq);
+#pragma unroll
+        for (int q = 0; q < kSplitCPT; ++q) {
+            vf4 a = t.a[q];
+            asm volatile("" : "+v"(a));   // widened here again: fp64 copies kept since publish() would double the tile's footprint
+            acc[q][0] = __builtin_fma(static_cast<double>(a.x), res, acc[q][0]);
+            acc[q][1] = __builtin_fma(static_cast<double>(a.y), res, acc[q][1]);
+            acc[q][2] = __builtin_fma(static_cast<double>(a.z), res, acc[q][2]);
+            acc[q][3] = __builtin_fma(static_cast<double>(a.w), res, acc[q][3]);
+        }
+    };
+
+    SplitTile t[NB];
+    // Row rho waits in t[(rho - r0) % NB]: rows r0 .. r0 + L + LA - 1 on their way, the first L of them published.
+#pragma unroll
+    for (int k = 0; k < L + LA; ++k) load(t[k], r0 + k);
+#pragma unroll
+    for (int k = 0; k < L; ++k) publish(t[k], r0 + k);
+    for (int r = r0; r < r1; r += NB) {
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {   // row r + k waits in t[k]
+            load(t[(k + L + LA) % NB], r + k + L + LA);
+            publish(t[(k + L) % NB], r + k + L);
+            consume(t[k], r + k, peek(r + k));
+        }
+    }
+
+    // (partial and sq_partial belong to this launch: its first node is their node 0)
+    double* out = partial + (static_cast<int64_t>(blockIdx.z) * splits + s) * d;
+#pragma unroll
+    for (int q = 0; q < kSplitCPT; ++q) {
+        const int64_t c = static_cast<int64_t>(gw) * kSplitWaveCols + 256 * q + 4 * lane;
+        if (c < d) {
+            out[c + 0] = acc[q][0]; out[c + 1] = acc[q][1]; out[c + 2] = acc[q][2]; out[c + 3] = acc[q][3];
+        }
+    }
+    if (gw == 0 && lane == 0) sq_partial[static_cast<int64_t>(blockIdx.z) * splits + s] = sq;
+}
+
+// After the final sums of a k_fused_split call: a wave that gave up waiting has used an incomplete residual.
+__global__ __launch_bounds__(kThreads) void k_poison_failed(const unsigned* __restrict__ failed, float* __restrict__ g,
+                                                           float* __restrict__ loss, int64_t d, int64_t ld) {
+    if (*failed == 0u) return;
+    const int i = blockIdx.y;
+    const float nan = __builtin_nanf("");
+    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < d; c += static_cast<int64_t>(gridDim.x) * kThreads)
+        g[static_cast<int64_t>(i) * ld + c] = nan;
+    if (loss != nullptr && blockIdx.x == 0 && threadIdx.x == 0) loss[i] = nan;
+}
+
 __global__ __launch_bounds__(kThreads) void k_finish_fused(const double* __restrict__ partial,
                                                             const double* __restrict__ sq_partial,
                                                             float* __restrict__ g, float* __restrict__ loss,
@@ -990,6 +1175,115 @@ int launch_fused_narrow(dim3 grid, hipStream_t stream, const float* A, const flo
     return check_hip(hipGetLastError(), "fused gradient kernel launch (narrow accesses)");
 }
 
+// How a call over rows wider than kMaxFusedD is cut up for k_fused_split: launches of `nodes` nodes with `splits` row
+// blocks each, a wave per 1536 columns of a row block, so that no launch has more than kSplitResident waves.  A pure
+// function of the shape (no device query): the workspace size depends on it.  Few nodes per launch allow more row
+// blocks per node and so fill the chip better where nodes x slots divides the chip badly (8 nodes of 65536 columns,
+// 43 slots: one launch of 8 x 5 blocks uses 1720 of 2048 waves, two launches of 4 x 11 blocks 1892); every launch
+// costs its pipeline's fill and drain and the gap to the next, priced at 24 rows' time.
+struct SplitChunk {
+    int nodes, splits;
+};
+int split_slots(int64_t d) { return static_cast<int>((d + kSplitWaveCols - 1) / kSplitWaveCols); }
+SplitChunk split_chunk(int n_left, int32_t b, int nslots) {
+    const int blocks = kSplitResident / ((nslots + kSplitWaves - 1) / kSplitWaves);   // row blocks per launch: 32 or more up to kMaxSplitD
+    const int most = b >= 32 ? b / 16 : 1;        // a row block has 16 rows or more
+    SplitChunk best{1, 1};
+    int64_t best_cost = INT64_MAX;
+    for (int m = n_left < blocks ? n_left : blocks; m >= 1; --m) {
+        int s = blocks / m;
+        if (s > most) s = most;
+        const int64_t launches = (n_left + m - 1) / m;
+        const int64_t cost = launches * ((b + s - 1) / s + 24);
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = SplitChunk{m, s};
+        }
+    }
+    return best;
+}
+// The plan is made for b rounded down to a power of two, and the workspace holds the largest plan of all such values
+// up to b: its size then never shrinks when b grows (a workspace sized for b rows serves every smaller batch).
+int split_plan_rows(int32_t b) {
+    int q = 1;
+    while (2 * static_cast<int64_t>(q) <= b) q *= 2;
+    return q;
+}
+size_t split_sums_doubles(int32_t n, int32_t plan_rows, int64_t d, int nslots) {
+    size_t doubles = 0;
+    for (int node0 = 0; node0 < n;) {
+        const SplitChunk c = split_chunk(n - node0, plan_rows, nslots);
+        const size_t blocks = static_cast<size_t>(c.nodes) * c.splits;
+        doubles += ((blocks + 1) & ~size_t{1}) + blocks * static_cast<size_t>(d);
+        node0 += c.nodes;
+    }
+    return doubles;
+}
+// bytes: the slots and the failure word, then every launch's sums of squares and partial gradients
+size_t split_workspace_bytes(int32_t n, int32_t b, int64_t d) {
+    const int nslots = split_slots(d);
+    size_t sums = 0;
+    for (int64_t q = 1; q <= b; q *= 2) {
+        const size_t v = split_sums_doubles(n, static_cast<int32_t>(q), d, nslots);
+        if (v > sums) sums = v;
+    }
+    return (static_cast<size_t>(n) * static_cast<size_t>(b) * nslots + 2 + sums) * sizeof(double);
+}
+
+// Workgroups of k_fused_split the current device holds at once (asked once per device); 0 on error.
+template <int L, int LA>
+int split_resident_workgroups() {
+    static std::atomic<int> known[64];
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return 0;
+    if (device >= 0 && device < 64) {
+        const int v = known[device].load(std::memory_order_relaxed);
+        if (v) return v;
+    }
+    int per_cu = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused_split<L, LA>, 64 * kSplitWaves, 0) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
+    const int total = per_cu * cus;
+    if (device >= 0 && device < 64 && total > 0) known[device].store(total, std::memory_order_relaxed);
+    return total;
+}
+
+constexpr int kSplitL = 1, kSplitLA = 1;
+
+// Returns DL_OK after launching, a status on error, or -1 when the device cannot hold a launch at once (the caller
+// then takes the two sweeps).
+int launch_fused_split(hipStream_t stream, const float* A, const float* y, const float* x, float* g, float* loss,
+                       int32_t n, int32_t b, int64_t d, int64_t ldA, int64_t ld, double scale, void* workspace) {
+    const int nslots = split_slots(d);
+    if (split_resident_workgroups<kSplitL, kSplitLA>() < kSplitResident) return -1;
+    unsigned long long* slots = static_cast<unsigned long long*>(workspace);
+    const int64_t slot_count = static_cast<int64_t>(n) * b * nslots;
+    unsigned* failed = reinterpret_cast<unsigned*>(slots + slot_count);
+    double* sums = reinterpret_cast<double*>(slots + slot_count + 2);
+    const int64_t fill_blocks = (slot_count + 4 * kThreads - 1) / (4 * kThreads);
+    hipLaunchKernelGGL(k_fill_slots, dim3(static_cast<unsigned>(fill_blocks < 2048 ? (fill_blocks < 1 ? 1 : fill_blocks) : 2048)),
+                       dim3(kThreads), 0, stream, slots, slot_count, failed);
+    if (int rc = check_hip(hipGetLastError(), "slot fill kernel launch")) return rc;
+    for (int node0 = 0; node0 < n;) {
+        const SplitChunk c = split_chunk(n - node0, split_plan_rows(b), nslots);
+        const size_t blocks = static_cast<size_t>(c.nodes) * c.splits;
+        double* sq_partial = sums;
+        double* fpartial = sums + ((blocks + 1) & ~size_t{1});
+        sums = fpartial + blocks * static_cast<size_t>(d);
+        const dim3 grid(static_cast<unsigned>((nslots + kSplitWaves - 1) / kSplitWaves), static_cast<unsigned>(c.splits), static_cast<unsigned>(c.nodes));
+        hipLaunchKernelGGL((k_fused_split<kSplitL, kSplitLA>), grid, dim3(64 * kSplitWaves), 0, stream, A, y, x, fpartial, sq_partial,
+                           slots, failed, b, d, ldA, ld, c.splits, nslots, node0);
+        if (int rc = check_hip(hipGetLastError(), "fused gradient kernel launch (columns split over waves)")) return rc;
+        const dim3 grid_ff(static_cast<unsigned>((d + kFinishColumns - 1) / kFinishColumns), static_cast<unsigned>(c.nodes));
+        hipLaunchKernelGGL(k_finish_fused, grid_ff, dim3(kThreads), 0, stream, fpartial, sq_partial, g + static_cast<int64_t>(node0) * ld,
+                           loss ? loss + node0 : nullptr, d, ld, c.splits, scale);
+        if (int rc = check_hip(hipGetLastError(), "finish kernel launch")) return rc;
+        node0 += c.nodes;
+    }
+    hipLaunchKernelGGL(k_poison_failed, dim3(64, static_cast<unsigned>(n)), dim3(kThreads), 0, stream, failed, g, loss, d, ld);
+    return check_hip(hipGetLastError(), "failure check kernel launch");
+}
+
 }  // namespace
 
 bool lsq_wide_accesses(const float* A, const float* x, int64_t d, int64_t ldA, int64_t ld) {
@@ -997,8 +1291,8 @@ bool lsq_wide_accesses(const float* A, const float* x, int64_t d, int64_t ldA, i
     return ldA % 4 == 0 && (reinterpret_cast<uintptr_t>(A) & 15u) == 0;
 }
 
-// b = rows actually used per node.  path: 0 the two-sweep kernels, 1 the single sweep, 2 the small-problem kernel
-// (launch_lsq picks by shape and alignment), -1 the largest of the three.
+// b = rows actually used per node.  path: 0 the two-sweep kernels, 1 the single sweep, 2 the small-problem kernel,
+// 3 the single sweep with a row's columns split over waves (launch_lsq picks by shape and alignment), -1 the largest.
 size_t lsq_workspace_bytes_path(int32_t n, int32_t b, int64_t d, int path) {
     // two-sweep layout: res[n*b], partial[n*splits*d]; single-sweep layout: sq[n*splits], partial[n*splits*d]
     const size_t res = static_cast<size_t>(n) * static_cast<size_t>(b);
@@ -1009,10 +1303,18 @@ size_t lsq_workspace_bytes_path(int32_t n, int32_t b, int64_t d, int path) {
         const size_t fs = static_cast<size_t>(fused_splits(n, b, d, fused_rows(d)));
         fused = (static_cast<size_t>(n) * fs * (static_cast<size_t>(d) + 1)) * sizeof(double) + 16;
     }
+    // the column-split sweep falls back to the two sweeps on a device that cannot hold its launch at once
+    size_t split = 0;
+    if (d > kMaxFusedD && d <= kMaxSplitD && d % 4 == 0) {
+        split = split_workspace_bytes(n, b, d);
+        if (split < two_sweeps) split = two_sweeps;
+    }
     if (path == 0) return two_sweeps;
     if (path == 1) return fused;
     if (path == 2) return 0;
-    return fused > two_sweeps ? fused : two_sweeps;
+    if (path == 3) return split;
+    const size_t most = fused > two_sweeps ? fused : two_sweeps;
+    return split > most ? split : most;
 }
 
 size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d) { return lsq_workspace_bytes_path(n, b, d, -1); }
@@ -1020,12 +1322,13 @@ size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d) { return lsq_workspa
 // wide_accesses: rows of A on 16-byte boundaries (lsq_wide_accesses).  The single sweep also takes a d that is
 // not a multiple of 4 (its last d % 4 columns element by element), from d = 8 on, and, up to d = 16384 and with
 // narrower accesses, rows that are not on such boundaries.
-int lsq_path(int32_t bs, int64_t d, bool wide_accesses) {
+int lsq_path(int32_t bs, int64_t d, bool wide_accesses, bool sampled) {
     if (small_problem(bs, d)) return 2;
     if (d <= 0) return 0;
     if (d <= kMaxRowsKernelD) return 1;                     // a wave per row, any alignment
     if (!wide_accesses) return d <= kMaxNarrowD ? 1 : 0;   // narrow accesses, same workspace layout
-    return d <= kMaxFusedD ? 1 : 0;
+    if (d <= kMaxFusedD) return 1;
+    return (d <= kMaxSplitD && d % 4 == 0 && !sampled) ? 3 : 0;   // columns split over waves (all rows of a node only)
 }
 
 int launch_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
@@ -1038,8 +1341,13 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
     const bool aligned_rows = lsq_wide_accesses(A, x, d, ldA, ld);
     // the two sweeps' 16-byte loads need whole chunks, of x_i too
     const bool vec4 = aligned_rows && d % 4 == 0 && ld % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
-    const int path = lsq_path(bs, d, aligned_rows);
+    int path = lsq_path(bs, d, aligned_rows, rows != nullptr);
     if (n > 65535 || splits > 65535) return set_error(DL_EINVAL, "local_grad_lsq: n too large for the launch grid");
+    if (path == 3) {
+        const int rc = launch_fused_split(stream, A, y, x, g, loss, n, b, d, ldA, ld, static_cast<double>(scale), workspace);
+        if (rc >= 0) return rc;
+        path = 0;   // this device does not hold the launch at once
+    }
 
     const dim3 block(kThreads);
     if (path == 2) {

@@ -204,7 +204,15 @@ LSQ_CASES = [
     (1, 9, 16388, 0, 0, 1.0),            # 16384 < d <= 32768: single sweep, 8 chunks per thread, x_i in LDS
     (2, 20, 32768, 0, 0, 0.5),           # the widest single sweep
     (3, 33, 20484, 4, 4, 1.0),           # ... with padded rows and most of the last chunks past d
-    (1, 9, 32772, 0, 0, 1.0),            # d > 32768: two sweeps with 16-byte loads, a workgroup per row
+    (1, 9, 32772, 0, 0, 1.0),            # d > 32768: columns split over waves, 17 slots, the last wave with 4 columns
+    (2, 40, 40000, 0, 0, 1.0),           # 20 slots, a ragged last wave, two row blocks per node
+    (3, 50, 65536, 0, 0, 0.5),           # 32 slots: eight whole workgroups per row block
+    (2, 33, 131072, 0, 0, 1.0),          # 64 slots: the widest
+    (2, 70, 36868, 4, 4, 1.0),           # padded rows, four row blocks of 17 or 18 rows
+    (2, 30, 50000, 0, 3, 1.0),           # x and g off the 16-byte grid
+    (40, 3, 131072, 0, 0, 1.0),          # more nodes than one launch holds (32 row blocks of 16 workgroups): two launches
+    (1, 12, 131076, 0, 0, 1.0),          # beyond: two sweeps with 16-byte loads, a workgroup per row
+    (1, 9, 32770, 2, 2, 1.0),            # d not a multiple of 4 above 32768: two sweeps
     (2, 7, 4099, 1, 3, 1.0),             # few long rows, odd strides: a workgroup per row, 4-byte loads
     (3, 2000, 8196, 0, 0, 1.0),          # many long rows: a wave per row
     (70, 2, 64, 0, 0, 1.0),              # more nodes than rows
