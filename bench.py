@@ -876,10 +876,11 @@ def main():
         extras["decentlam_stats_c3_exp32"] = bench_stats(P, workloads, "c3_exp32", args.steps, args.warmup)
         c5 = bench_lsq(P, workloads, "c5_onepeer64_lsq", args.steps, args.warmup)
         extras["local_grad_lsq_c5"] = c5
-        # rows too wide for the register-resident x_i (16384 < d <= 32768: the sweep's widest form) and beyond (two sweeps)
+        # rows too wide for the register-resident x_i (16384 < d <= 32768: the widest form of a workgroup per row tile),
+        # wider still (up to 131072: the columns of a row split over waves, still one sweep) and beyond (two sweeps)
         extras["local_grad_lsq_wide_rows"] = {
             f"n{n}_b{b}_d{d}": bench_lsq_shape(P, n, b, d, args.steps, args.warmup)
-            for n, b, d in ((8, 2048, 32768), (8, 1024, 65536))}
+            for n, b, d in ((8, 2048, 32768), (8, 1024, 65536), (4, 1024, 131072), (2, 1024, 262144))}
         # short rows: a wave per row (or per two rows)
         extras["local_grad_lsq_short_rows"] = {
             f"n{n}_b{b}_d{d}": bench_lsq_shape(P, n, b, d, args.steps, args.warmup)
