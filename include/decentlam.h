@@ -507,7 +507,8 @@ int local_grad_lsq(const float* A, const float* y, const float* x,
  *   and belong to local_grad_lsq.
  *   All calls on one GPU share that GPU's array: calls that may overlap in time (different streams,
  *   different threads) race on it and must be serialised by the caller.  The array keeps the last
- *   call's contents; every call writes each partial sum before it reads it, so nothing needs clearing.
+ *   call's contents; every call writes each partial sum before it reads it (and, for rows of more than 32768
+ *   columns, marks the waves' exchange slots empty with a fill kernel of its own first), so nothing needs clearing.
  *   The first call on a device looks the array's address up (this may load the library's device
  *   code): make it once outside of graph capture.
  * Arguments and the other errors as local_grad_lsq.

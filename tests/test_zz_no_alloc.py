@@ -45,9 +45,11 @@ def _run_both(A0, y0, x0, scale):
 
 # first call, then a smaller one: a single-sweep shape and then the small-problem kernel; the single sweep
 # with 4-byte accesses (rows not 16-byte aligned) and then a narrower one with 16-byte accesses; a two-sweep
-# shape (such rows, more than 16384 columns) and then a single sweep
+# shape (such rows, more than 16384 columns) and then a single sweep; rows beyond 32768 columns twice (the waves of
+# the second call must not take the first call's shares of the dot products, still in the array, for their own)
 @pytest.mark.parametrize("shapes", [((8, 96, 1024), (3, 20, 100)), ((5, 33, 1001), (4, 16, 512)),
-                                    ((2, 20, 16387), (2, 12, 2048)), ((64, 256, 4096), (8, 32, 1024))])
+                                    ((2, 20, 16387), (2, 12, 2048)), ((64, 256, 4096), (8, 32, 1024)),
+                                    ((2, 40, 40000), (1, 20, 36000))])
 def test_static_scratch_call_matches_workspace_call_twice_in_a_row(oracle, shapes):
     rng = np.random.default_rng(11981)
     for n, b, d in shapes:
