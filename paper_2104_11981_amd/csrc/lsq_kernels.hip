@@ -794,6 +794,31 @@ constexpr int64_t kMaxSplitD = 64 * static_cast<int64_t>(kSplitWaveCols);   // 6
 constexpr unsigned long long kSlotEmpty = 0x7ff8dec0de5107e1ull;
 constexpr int kSplitPolls = 1 << 21;
 
+// The sum over a wave without the LDS crossbar, the same value in every lane: two butterfly steps inside the quads and
+// two rotations inside the rows of 16 lanes as data-parallel moves, then lane 0 of each row read into scalar
+// registers and added in a fixed order.  (wave_sum's six permutes through LDS and the waits on them are about 600
+// cycles; a row of k_fused_split has two such sums on the path that paces the waves of a row block.)
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+    const unsigned long long bits = __builtin_bit_cast(unsigned long long, v);
+    const int lo = __builtin_amdgcn_update_dpp(0, static_cast<int>(bits), CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, static_cast<int>(bits >> 32), CTRL, 0xf, 0xf, false);
+    return __builtin_bit_cast(double, (static_cast<unsigned long long>(static_cast<unsigned>(hi)) << 32) | static_cast<unsigned>(lo));
+}
+__device__ __forceinline__ double lane_value(double v, int lane) {   // uniform result
+    const unsigned long long bits = __builtin_bit_cast(unsigned long long, v);
+    const unsigned lo = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(bits), lane));
+    const unsigned hi = static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(bits >> 32), lane));
+    return __builtin_bit_cast(double, (static_cast<unsigned long long>(hi) << 32) | lo);
+}
+__device__ __forceinline__ double wave_sum_uniform(double v) {
+    v += dpp_move<0xB1>(v);    // quad_perm [1, 0, 3, 2]: lane ^ 1
+    v += dpp_move<0x4E>(v);    // quad_perm [2, 3, 0, 1]: lane ^ 2
+    v += dpp_move<0x124>(v);   // row_ror 4: the next quad of the row
+    v += dpp_move<0x128>(v);   // row_ror 8: the other half of the row
+    return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
+}
+
 __device__ __forceinline__ unsigned long long slot_load(const unsigned long long* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -866,7 +891,7 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
             s0 = __builtin_fma(static_cast<double>(t.a[q].z), static_cast<double>(xv.z), s0);
             s1 = __builtin_fma(static_cast<double>(t.a[q].w), static_cast<double>(xv.w), s1);
         }
-        const double p = wave_sum(s0 + s1);
+        const double p = wave_sum_uniform(s0 + s1);
         unsigned long long bits = __builtin_bit_cast(unsigned long long, p);
         if (bits == kSlotEmpty) bits ^= 1ull;   // (cannot happen with fp32 inputs; the mark stays unique anyway)
         if (lane == 0)
@@ -895,7 +920,7 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
             }
         }
         const double share = lane < nslots ? __builtin_bit_cast(double, bits) : 0.0;
-        const double res = wave_sum(share) - static_cast<double>(t.y);   // the same bits in every wave of the block
+        const double res = wave_sum_uniform(share) - static_cast<double>(t.y);   // the same bits in every wave of the block
         sq = __builtin_fma(res, res, sq);
 #pragma unroll
         for (int q = 0; q < kSplitCPT; ++q) {
