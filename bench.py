@@ -676,6 +676,9 @@ def main():
                     help="only decentlam_step at these node counts on arrays of the headline size (819.2 M node-elements, "
                          "rows on 64 KiB boundaries), ring and static exponential graph: one JSON line (used for the "
                          "profiles)")
+    ap.add_argument("--lsq-shapes", default=None, metavar="N:B:D,...",
+                    help="only local_grad_lsq on synthetic problems of these shapes (n nodes of b x d): one JSON line "
+                         "(used for the profiles)")
     ap.add_argument("--oracle-table", action="store_true",
                     help="CPU only: time the oracle on every workload at 1 thread and at all host cores")
     ap.add_argument("--oracle-table-child", action="store_true", help=argparse.SUPPRESS)
@@ -719,6 +722,19 @@ def main():
             del a, b
         print(json.dumps({"what": "decentlam_step by node count, 819.2 M node-elements, rows on 64 KiB boundaries",
                           "steps": args.steps, "warmup": args.warmup, **out}), flush=True)
+        return
+    if args.lsq_shapes:
+        out = {}
+        for n, b, d in (tuple(int(v) for v in shape.split(":")) for shape in args.lsq_shapes.split(",")):
+            out[f"n{n}_b{b}_d{d}"] = bench_lsq_shape(P, n, b, d, args.steps, args.warmup)
+        if args.calibration_copy:   # one plain device copy of 2^29 floats: what the counters read for a known size
+            a = torch.empty(1 << 29, dtype=torch.float32, device="cuda").normal_()
+            b = torch.empty_like(a)
+            b.copy_(a)
+            torch.cuda.synchronize()
+            del a, b
+        print(json.dumps({"what": "local_grad_lsq by shape, rate of the 4 n b d bytes of A", "steps": args.steps,
+                          "warmup": args.warmup, **out}), flush=True)
         return
     if args.streams_only:
         d0 = workloads.generate.dim(workloads.get(args.workload))

@@ -18,7 +18,8 @@
  *  - The caller owns every buffer.  The library allocates no device memory and keeps no state
  *    between calls, with one exception that no result depends on: kernel variants whose on-chip
  *    tile exceeds 48 KiB need a driver attribute raised once per device, and the library remembers
- *    per variant and device that it has done so.
+ *    per variant and device that it has done so (likewise how many workgroups of local_grad_lsq's
+ *    widest sweep a device holds at once).  One setting is kept: local_grad_lsq_poll_limit.
  *  - Device work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *    the default stream) and the call returns without synchronising.  Host
  *    arrays (the topology) are consumed before the call returns.
@@ -492,6 +493,15 @@ int local_grad_lsq(const float* A, const float* y, const float* x,
                    float* g, float* loss,
                    int32_t n, int32_t b, int64_t d, int64_t ldA, int64_t ld,
                    float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * local_grad_lsq_poll_limit -- how long the waves of local_grad_lsq's sweep over rows of more than 32768 columns
+ * wait for one another (see local_grad_lsq): the number of polls after which a wave gives up, process-wide, the one
+ * setting the library keeps between calls.  The default, 2097152, is seconds.  polls < 0 restores the default;
+ * 0 makes every wave that finds a share missing give up at once, which is how the tests reach the path that
+ * answers with NaN instead of numbers (every kernel still runs to its end).  Returns the previous value.
+ */
+int local_grad_lsq_poll_limit(int polls);
 
 /*
  * local_grad_lsq_static -- local_grad_lsq for callers that cannot allocate or pass a workspace: code

@@ -18,7 +18,7 @@ _BINDING_NAMES = (
     "dmsgd_step_blocked", "to_blocked", "from_blocked", "recommended_ld", "empty_rows", "decentlam_step_ex", "dmsgd_step_ex",
     "decentlam_step_xprev_ex", "decentlam_step_multi_ex", "dmsgd_step_multi_ex", "Layout", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
     "dmsgd_step_multi", "decentlam_step_multi_workspace", "last_error", "local_grad_lsq", "local_grad_lsq_workspace",
-    "local_grad_lsq_static", "DL_STATIC_SCRATCH_BYTES", "dl_calibration_stream",
+    "local_grad_lsq_static", "local_grad_lsq_poll_limit", "DL_STATIC_SCRATCH_BYTES", "dl_calibration_stream",
     "make_topology", "topology_build", "topology_metropolis", "topology_pack", "topology_pack_bytes", "PackedTopology",
     "decentlam_step_packed", "dmsgd_step_packed", "dsgd_step_packed", "PreparedCall", "prepare_step",
     "prepare_local_grad_lsq", "topology_device_bytes", "topology_pack_device", "DeviceTopology", "DeviceTopologyStruct",

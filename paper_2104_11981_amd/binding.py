@@ -36,7 +36,7 @@ EXPORTS = ("topology_build", "topology_build_ex", "topology_metropolis", "decent
            "dmsgd_step", "dsgd_step", "awc_dmsgd_step", "da_dmsgd_step", "decentlam_step_blocked",
            "dmsgd_step_blocked", "decentlam_step_ex", "dmsgd_step_ex", "decentlam_step_xprev_ex", "decentlam_step_multi_ex", "dmsgd_step_multi_ex", "decentlam_step_g16", "dmsgd_step_g16", "decentlam_step_multi",
            "dmsgd_step_multi", "decentlam_step_multi_workspace", "local_grad_lsq", "local_grad_lsq_rows",
-           "local_grad_lsq_static", "dl_calibration_stream", "topology_pack_bytes", "topology_pack",
+           "local_grad_lsq_static", "local_grad_lsq_poll_limit", "dl_calibration_stream", "topology_pack_bytes", "topology_pack",
            "decentlam_step_packed", "dmsgd_step_packed", "dsgd_step_packed", "topology_device_bytes",
            "topology_pack_device", "decentlam_step_dev", "dmsgd_step_dev", "dsgd_step_dev",
            "awc_dmsgd_step_ex", "da_dmsgd_step_ex", "awc_dmsgd_step_multi_ex", "da_dmsgd_step_multi_ex",
@@ -123,6 +123,8 @@ def _load() -> ctypes.CDLL:
     lib.local_grad_lsq.restype = ctypes.c_int
     lib.local_grad_lsq.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.local_grad_lsq_poll_limit.restype = ctypes.c_int
+    lib.local_grad_lsq_poll_limit.argtypes = [ctypes.c_int]
     lib.local_grad_lsq_static.restype = ctypes.c_int
     lib.local_grad_lsq_static.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                           ctypes.c_int64, ctypes.c_int64, ctypes.c_float, vp]
@@ -811,6 +813,10 @@ def local_grad_lsq(A, y, x, g, loss=None, scale: float = 1.0, workspace=None, st
         raise TypeError("rows: need a contiguous n x bs int32 device tensor")
     _check(_lib.local_grad_lsq_rows(A.data_ptr(), y.data_ptr(), px, pg, pl, n, b, d, ldA, ld, rows.data_ptr(),
                                     rows.shape[1], scale, workspace.data_ptr(), ws_bytes, st))
+
+
+def local_grad_lsq_poll_limit(polls: int) -> int:
+    return int(_lib.local_grad_lsq_poll_limit(int(polls)))
 
 
 def local_grad_lsq_static(A, y, x, g, loss=None, scale: float = 1.0, stream=None):

@@ -891,6 +891,8 @@ int lsq_entry(const char* fn, const float* A, const float* y, const float* x, fl
 
 extern "C" {
 
+int local_grad_lsq_poll_limit(int polls) { return dl::lsq_poll_limit(polls); }
+
 int local_grad_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
                    int32_t b, int64_t d, int64_t ldA, int64_t ld, float scale, void* workspace,
                    size_t workspace_bytes, void* stream) {

@@ -129,6 +129,8 @@ size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d);
 bool lsq_wide_accesses(const float* A, const float* x, int64_t d, int64_t ldA, int64_t ld);
 int lsq_path(int32_t bs, int64_t d, bool wide_accesses, bool sampled = false);
 size_t lsq_workspace_bytes_path(int32_t n, int32_t b, int64_t d, int path);
+// Polls after which a wave of the column-split sweep stops waiting for the others (negative: the default); returns the old value.
+int lsq_poll_limit(int polls);
 // rows == nullptr: full-batch gradient over all b rows; otherwise bs sampled rows per node.
 int launch_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
                int32_t b, int64_t d, int64_t ldA, int64_t ld, const int32_t* rows, int32_t bs, float scale,

@@ -160,7 +160,8 @@ __global__ __launch_bounds__(kThreads) void k_transpose(const float* __restrict_
 // 1024 x 1024 took, more than the sweep over A itself.)
 constexpr int kFinishColumns = 64;
 __device__ __forceinline__ void finish_columns(const double* __restrict__ partial_i, float* __restrict__ g_i,
-                                               int64_t d, int splits, double scale, double (&quarter)[4][kFinishColumns]) {
+                                               int64_t d, int splits, double scale, double (&quarter)[4][kFinishColumns],
+                                               bool poisoned = false) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int64_t c = static_cast<int64_t>(blockIdx.x) * kFinishColumns + lane;
     const int per = (splits + 3) / 4;
@@ -180,7 +181,9 @@ __device__ __forceinline__ void finish_columns(const double* __restrict__ partia
     }
     quarter[w][lane] = acc;
     __syncthreads();
-    if (w == 0 && c < d) g_i[c] = static_cast<float>(scale * (((quarter[0][lane] + quarter[1][lane]) + quarter[2][lane]) + quarter[3][lane]));
+    if (w == 0 && c < d)
+        g_i[c] = poisoned ? __builtin_nanf("")
+                          : static_cast<float>(scale * (((quarter[0][lane] + quarter[1][lane]) + quarter[2][lane]) + quarter[3][lane]));
 }
 
 __global__ __launch_bounds__(kThreads) void k_finish(const double* __restrict__ partial,
@@ -784,15 +787,15 @@ __global__ __launch_bounds__(THREADS) void k_fused_narrow(const float* __restric
 // first saved), one wave per workgroup (0.57-0.71), the rows read through buffer descriptors (same rates).
 // The waves of a row block wait for one another, so all of them must be on the chip together: the launch never has
 // more workgroups than the chip holds at once (launch_fused_split checks the occupancy the runtime reports), and
-// every wait is bounded: a wave that polls kSplitPolls times in vain raises `failed`, stops waiting for the rest of
-// its rows and runs to its end; k_poison_failed then turns that call's g and loss into NaN.
+// every wait is bounded: a wave that polls max_polls times in vain raises `failed`, stops waiting for the rest of
+// its rows and runs to its end; k_finish_fused then writes NaN for g and loss of that launch's nodes.
 constexpr int kSplitCPT = 8;                          // 16-byte chunks per lane
 constexpr int kSplitWaveCols = 64 * 4 * kSplitCPT;    // columns per wave: 2048
 constexpr int kSplitWaves = 4;                        // waves per workgroup (they share nothing; neighbours in a row, they read a contiguous piece of it)
 constexpr int kSplitResident = 512;                   // workgroups per launch at most: 256 CUs x 2
 constexpr int64_t kMaxSplitD = 64 * static_cast<int64_t>(kSplitWaveCols);   // 64 slots per row: one load per lane
 constexpr unsigned long long kSlotEmpty = 0x7ff8dec0de5107e1ull;
-constexpr int kSplitPolls = 1 << 21;
+constexpr int kSplitPolls = 1 << 21;   // seconds; local_grad_lsq_poll_limit sets another number
 
 // The sum over a wave without the LDS crossbar, the same value in every lane: two butterfly steps inside the quads and
 // two rotations inside the rows of 16 lanes as data-parallel moves, then lane 0 of each row read into scalar
@@ -842,7 +845,8 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
                                                                     double* __restrict__ sq_partial,
                                                                     unsigned long long* __restrict__ slots,
                                                                     unsigned* __restrict__ failed, int b, int64_t d,
-                                                                    int64_t ldA, int64_t ld, int splits, int nslots, int node0) {
+                                                                    int64_t ldA, int64_t ld, int splits, int nslots, int node0,
+                                                                    int max_polls) {
     constexpr int NB = L + LA + 1;   // register tiles in rotation
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -910,7 +914,7 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
         if (!gave_up) {
             int polls = 0;
             while (__builtin_amdgcn_ballot_w64(bits == kSlotEmpty) != 0ull) {   // until every wave of the block has published
-                if (++polls > kSplitPolls) {
+                if (++polls > max_polls) {
                     gave_up = true;
                     if (lane == 0) __hip_atomic_store(failed, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     break;
@@ -960,29 +964,22 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
     if (gw == 0 && lane == 0) sq_partial[static_cast<int64_t>(blockIdx.z) * splits + s] = sq;
 }
 
-// After the final sums of a k_fused_split call: a wave that gave up waiting has used an incomplete residual.
-__global__ __launch_bounds__(kThreads) void k_poison_failed(const unsigned* __restrict__ failed, float* __restrict__ g,
-                                                           float* __restrict__ loss, int64_t d, int64_t ld) {
-    if (*failed == 0u) return;
-    const int i = blockIdx.y;
-    const float nan = __builtin_nanf("");
-    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < d; c += static_cast<int64_t>(gridDim.x) * kThreads)
-        g[static_cast<int64_t>(i) * ld + c] = nan;
-    if (loss != nullptr && blockIdx.x == 0 && threadIdx.x == 0) loss[i] = nan;
-}
-
 __global__ __launch_bounds__(kThreads) void k_finish_fused(const double* __restrict__ partial,
                                                             const double* __restrict__ sq_partial,
                                                             float* __restrict__ g, float* __restrict__ loss,
-                                                            int64_t d, int64_t ld, int splits, double scale) {
+                                                            int64_t d, int64_t ld, int splits, double scale,
+                                                            const unsigned* __restrict__ failed) {
     __shared__ double quarter[4][kFinishColumns];
     const int i = blockIdx.y;
-    finish_columns(partial + static_cast<int64_t>(i) * splits * d, g + static_cast<int64_t>(i) * ld, d, splits, scale, quarter);
+    // k_fused_split only: a wave that gave up waiting for the others has used an incomplete residual; the launch's
+    // results (and those of the launches after it in the same call) then read NaN
+    const bool poisoned = failed != nullptr && *failed != 0u;
+    finish_columns(partial + static_cast<int64_t>(i) * splits * d, g + static_cast<int64_t>(i) * ld, d, splits, scale, quarter, poisoned);
     if (loss != nullptr && blockIdx.x == 0 && threadIdx.x < 64) {   // one wave: lane-strided, then the fixed-order wave sum
         double sq = 0.0;
         for (int s = threadIdx.x; s < splits; s += 64) sq += sq_partial[static_cast<int64_t>(i) * splits + s];
         sq = wave_sum(sq);
-        if (threadIdx.x == 0) loss[i] = static_cast<float>(0.5 * scale * sq);
+        if (threadIdx.x == 0) loss[i] = poisoned ? __builtin_nanf("") : static_cast<float>(0.5 * scale * sq);
     }
 }
 
@@ -1274,6 +1271,7 @@ int split_resident_workgroups() {
 }
 
 constexpr int kSplitL = 1, kSplitLA = 1;
+std::atomic<int> g_split_polls{kSplitPolls};
 
 // Returns DL_OK after launching, a status on error, or -1 when the device cannot hold a launch at once (the caller
 // then takes the two sweeps).
@@ -1297,16 +1295,15 @@ int launch_fused_split(hipStream_t stream, const float* A, const float* y, const
         sums = fpartial + blocks * static_cast<size_t>(d);
         const dim3 grid(static_cast<unsigned>((nslots + kSplitWaves - 1) / kSplitWaves), static_cast<unsigned>(c.splits), static_cast<unsigned>(c.nodes));
         hipLaunchKernelGGL((k_fused_split<kSplitL, kSplitLA>), grid, dim3(64 * kSplitWaves), 0, stream, A, y, x, fpartial, sq_partial,
-                           slots, failed, b, d, ldA, ld, c.splits, nslots, node0);
+                           slots, failed, b, d, ldA, ld, c.splits, nslots, node0, g_split_polls.load(std::memory_order_relaxed));
         if (int rc = check_hip(hipGetLastError(), "fused gradient kernel launch (columns split over waves)")) return rc;
         const dim3 grid_ff(static_cast<unsigned>((d + kFinishColumns - 1) / kFinishColumns), static_cast<unsigned>(c.nodes));
         hipLaunchKernelGGL(k_finish_fused, grid_ff, dim3(kThreads), 0, stream, fpartial, sq_partial, g + static_cast<int64_t>(node0) * ld,
-                           loss ? loss + node0 : nullptr, d, ld, c.splits, scale);
+                           loss ? loss + node0 : nullptr, d, ld, c.splits, scale, static_cast<const unsigned*>(failed));
         if (int rc = check_hip(hipGetLastError(), "finish kernel launch")) return rc;
         node0 += c.nodes;
     }
-    hipLaunchKernelGGL(k_poison_failed, dim3(64, static_cast<unsigned>(n)), dim3(kThreads), 0, stream, failed, g, loss, d, ld);
-    return check_hip(hipGetLastError(), "failure check kernel launch");
+    return DL_OK;
 }
 
 }  // namespace
@@ -1343,6 +1340,8 @@ size_t lsq_workspace_bytes_path(int32_t n, int32_t b, int64_t d, int path) {
 }
 
 size_t lsq_workspace_bytes(int32_t n, int32_t b, int64_t d) { return lsq_workspace_bytes_path(n, b, d, -1); }
+
+int lsq_poll_limit(int polls) { return g_split_polls.exchange(polls < 0 ? kSplitPolls : polls, std::memory_order_relaxed); }
 
 // wide_accesses: rows of A on 16-byte boundaries (lsq_wide_accesses).  The single sweep also takes a d that is
 // not a multiple of 4 (its last d % 4 columns element by element), from d = 8 on, and, up to d = 16384 and with
@@ -1414,7 +1413,7 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
         if (rc) return rc;
         const dim3 grid_ff(static_cast<unsigned>((d + kFinishColumns - 1) / kFinishColumns), static_cast<unsigned>(n));
         hipLaunchKernelGGL(k_finish_fused, grid_ff, block, 0, stream, fpartial, sq_partial, g, loss, d, ld, fs,
-                           static_cast<double>(scale));
+                           static_cast<double>(scale), static_cast<const unsigned*>(nullptr));
         return check_hip(hipGetLastError(), "finish kernel launch");
     }
 

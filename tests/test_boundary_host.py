@@ -195,6 +195,14 @@ def test_lsq_workspace_covers_every_smaller_batch():
             assert sizes[0] >= n * d * 8
 
 
+def test_lsq_poll_limit_setting():
+    old = P.raw.local_grad_lsq_poll_limit(7)
+    assert old == 1 << 21
+    assert P.raw.local_grad_lsq_poll_limit(-1) == 7      # negative: back to the default
+    assert P.raw.local_grad_lsq_poll_limit(-5) == 1 << 21
+    assert P.local_grad_lsq_poll_limit(-1) == 1 << 21
+
+
 def test_lsq_static_refuses_sizes_beyond_its_array():
     """local_grad_lsq_static checks the size first: nothing touches a device, so fake pointers will do."""
     fake = ctypes.c_void_p(0x10000)   # 16-byte aligned: the single-sweep kernels would be chosen

@@ -316,6 +316,40 @@ def test_local_grad_lsq_matches_oracle(P, oracle, n, b, d, padA, pad, scale):
     assert torch.equal(g2, g)
 
 
+def test_wide_row_sweep_answers_nan_when_its_waves_stop_waiting(P, oracle):
+    """Rows of more than 32768 columns: the waves of a row block hand one another their shares of each dot product and
+    wait for them, a bounded number of polls.  With the limit at zero a wave that finds a share missing gives up at
+    once; every kernel still runs to its end, and a launch in which any wave gave up must answer NaN for all of its
+    nodes, never numbers computed from an incomplete residual.  With the limit restored the same call is right again."""
+    n, b, d = 3, 64, 40000
+    rng = np.random.default_rng(5)
+    A0 = rng.standard_normal((n, b, d)).astype(np.float32)
+    y0 = rng.standard_normal((n, b)).astype(np.float32)
+    x0 = rng.standard_normal((n, d)).astype(np.float32)
+    A, y, x = dev(A0), dev(y0), dev(x0)
+    g = torch.zeros((n, d), dtype=torch.float32, device="cuda")
+    loss = torch.zeros(n, dtype=torch.float32, device="cuda")
+    ws = torch.empty(P.local_grad_lsq_workspace(n, b, d), dtype=torch.uint8, device="cuda")
+    gr, lr = oracle.lsq_grad(A0, y0, x0, 1.0)
+    old = P.local_grad_lsq_poll_limit(0)
+    try:
+        assert old == 1 << 21
+        for _ in range(3):
+            P.local_grad_lsq(A, y, x, g, loss, 1.0, ws)
+            torch.cuda.synchronize()
+            gh, lh = g.cpu().numpy(), loss.cpu().numpy()
+            if np.isnan(lh).any() or np.isnan(gh).any():
+                assert np.isnan(gh).all() and np.isnan(lh).all()   # one launch holds all three nodes
+            else:                                                   # nobody had to wait: then the numbers are right
+                check_elementwise(gh, gr, "g")
+                check_elementwise(lh, lr, "loss")
+    finally:
+        assert P.local_grad_lsq_poll_limit(-1) == 0
+    P.local_grad_lsq(A, y, x, g, loss, 1.0, ws)
+    check_elementwise(g.cpu().numpy(), gr, "g")
+    check_elementwise(loss.cpu().numpy(), lr, "loss")
+
+
 @pytest.mark.parametrize("n,b,d,ldA,offA,offx,offg", [(2, 40, 3000, 3000, 1, 0, 0),     # 4-byte aligned A only
                                                       (2, 40, 3000, 3000, 2, 1, 3),     # 8-byte aligned A, odd x, g
                                                       (3, 25, 1021, 1024, 3, 2, 1),     # aligned stride, odd base
