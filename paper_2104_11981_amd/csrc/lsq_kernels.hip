@@ -20,8 +20,8 @@
 // without fences, with device-scope atomic accesses for everything that crosses blocks, the final sum of one
 // block is a chain of uncached loads: 0.64 ms and 54 us.  The second launch costs less than either.)
 //
-// Single sweep for wider rows (32768 < d <= 131072, d a multiple of 4, rows of A on 16-byte boundaries, all rows of a
-// node): k_fused_split, the columns of a row block split over waves that exchange one number per wave and row
+// Single sweep for wider rows (32768 < d <= 131072, d a multiple of 4, rows of A on 16-byte boundaries):
+// k_fused_split, the columns of a row block split over waves that exchange one number per wave and row
 // through device memory; see there.
 //
 // Small problems (bs * d <= 4096 elements per node, any alignment): k_small, one launch,
@@ -846,15 +846,17 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
                                                                     unsigned long long* __restrict__ slots,
                                                                     unsigned* __restrict__ failed, int b, int64_t d,
                                                                     int64_t ldA, int64_t ld, int splits, int nslots, int node0,
-                                                                    int max_polls) {
+                                                                    int max_polls, const int32_t* __restrict__ rows, int bs) {
     constexpr int NB = L + LA + 1;   // register tiles in rotation
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int gw = static_cast<int>(blockIdx.x) * kSplitWaves + wave;   // this wave's slot; its columns start at 2048 gw
     if (gw >= nslots) return;   // whole waves only; nothing in this kernel is shared within a workgroup
     const int s = blockIdx.y, i = node0 + static_cast<int>(blockIdx.z);
-    const int r0 = static_cast<int>(static_cast<int64_t>(b) * s / splits);
-    const int r1 = static_cast<int>(static_cast<int64_t>(b) * (s + 1) / splits);   // r1 > r0: splits <= b
+    // bs logical rows per node: all b rows, or (rows != nullptr) the sampled ones, looked up as they come
+    const int r0 = static_cast<int>(static_cast<int64_t>(bs) * s / splits);
+    const int r1 = static_cast<int>(static_cast<int64_t>(bs) * (s + 1) / splits);   // r1 > r0: splits <= bs
+    const int32_t* __restrict__ rows_i = rows ? rows + static_cast<int64_t>(i) * bs : nullptr;
 
     // a thread's chunks of x_i wait in LDS (xl[256 q], written and read by this thread alone), not in 32 registers
     __shared__ vf4 x_chunks[kSplitCPT * 64 * kSplitWaves];
@@ -874,10 +876,14 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
     }
     const float* __restrict__ a_node = A + static_cast<int64_t>(i) * b * ldA;
     const float* __restrict__ yi = y + static_cast<int64_t>(i) * b;
-    unsigned long long* slots_i = slots + static_cast<int64_t>(i) * b * nslots;
+    unsigned long long* slots_i = slots + static_cast<int64_t>(i) * bs * nslots;
 
-    auto load = [&](SplitTile& t, int r) {   // rows past the block's end read its last row again (never used)
-        const int row = r < r1 ? r : r1 - 1;
+    // The physical row of logical row r (uniform), asked for one iteration before the loads that need it.
+    auto physical = [&](int r) -> int {
+        const int row = r < r1 ? r : r1 - 1;   // rows past the block's end read its last row again (never used)
+        return rows_i ? physical_row(rows_i, row, b) : row;
+    };
+    auto load = [&](SplitTile& t, int row) {
         const float* __restrict__ a_row = a_node + static_cast<int64_t>(row) * ldA;
         t.y = yi[row];
 #pragma unroll
@@ -940,13 +946,15 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
     SplitTile t[NB];
     // Row rho waits in t[(rho - r0) % NB]: rows r0 .. r0 + L + LA - 1 on their way, the first L of them published.
 #pragma unroll
-    for (int k = 0; k < L + LA; ++k) load(t[k], r0 + k);
+    for (int k = 0; k < L + LA; ++k) load(t[k], physical(r0 + k));
 #pragma unroll
     for (int k = 0; k < L; ++k) publish(t[k], r0 + k);
+    int prow = physical(r0 + L + LA);
     for (int r = r0; r < r1; r += NB) {
 #pragma unroll
         for (int k = 0; k < NB; ++k) {   // row r + k waits in t[k]
-            load(t[(k + L + LA) % NB], r + k + L + LA);
+            load(t[(k + L + LA) % NB], prow);
+            prow = physical(r + k + L + LA + 1);
             publish(t[(k + L) % NB], r + k + L);
             consume(t[k], r + k, peek(r + k));
         }
@@ -1276,11 +1284,12 @@ std::atomic<int> g_split_polls{kSplitPolls};
 // Returns DL_OK after launching, a status on error, or -1 when the device cannot hold a launch at once (the caller
 // then takes the two sweeps).
 int launch_fused_split(hipStream_t stream, const float* A, const float* y, const float* x, float* g, float* loss,
-                       int32_t n, int32_t b, int64_t d, int64_t ldA, int64_t ld, double scale, void* workspace) {
+                       int32_t n, int32_t b, int64_t d, int64_t ldA, int64_t ld, const int32_t* rows, int32_t bs,
+                       double scale, void* workspace) {
     const int nslots = split_slots(d);
     if (split_resident_workgroups<kSplitL, kSplitLA>() < kSplitResident) return -1;
     unsigned long long* slots = static_cast<unsigned long long*>(workspace);
-    const int64_t slot_count = static_cast<int64_t>(n) * b * nslots;
+    const int64_t slot_count = static_cast<int64_t>(n) * bs * nslots;
     unsigned* failed = reinterpret_cast<unsigned*>(slots + slot_count);
     double* sums = reinterpret_cast<double*>(slots + slot_count + 2);
     const int64_t fill_blocks = (slot_count + 4 * kThreads - 1) / (4 * kThreads);
@@ -1288,14 +1297,14 @@ int launch_fused_split(hipStream_t stream, const float* A, const float* y, const
                        dim3(kThreads), 0, stream, slots, slot_count, failed);
     if (int rc = check_hip(hipGetLastError(), "slot fill kernel launch")) return rc;
     for (int node0 = 0; node0 < n;) {
-        const SplitChunk c = split_chunk(n - node0, split_plan_rows(b), nslots);
+        const SplitChunk c = split_chunk(n - node0, split_plan_rows(bs), nslots);
         const size_t blocks = static_cast<size_t>(c.nodes) * c.splits;
         double* sq_partial = sums;
         double* fpartial = sums + ((blocks + 1) & ~size_t{1});
         sums = fpartial + blocks * static_cast<size_t>(d);
         const dim3 grid(static_cast<unsigned>((nslots + kSplitWaves - 1) / kSplitWaves), static_cast<unsigned>(c.splits), static_cast<unsigned>(c.nodes));
         hipLaunchKernelGGL((k_fused_split<kSplitL, kSplitLA>), grid, dim3(64 * kSplitWaves), 0, stream, A, y, x, fpartial, sq_partial,
-                           slots, failed, b, d, ldA, ld, c.splits, nslots, node0, g_split_polls.load(std::memory_order_relaxed));
+                           slots, failed, b, d, ldA, ld, c.splits, nslots, node0, g_split_polls.load(std::memory_order_relaxed), rows, bs);
         if (int rc = check_hip(hipGetLastError(), "fused gradient kernel launch (columns split over waves)")) return rc;
         const dim3 grid_ff(static_cast<unsigned>((d + kFinishColumns - 1) / kFinishColumns), static_cast<unsigned>(c.nodes));
         hipLaunchKernelGGL(k_finish_fused, grid_ff, dim3(kThreads), 0, stream, fpartial, sq_partial, g + static_cast<int64_t>(node0) * ld,
@@ -1352,7 +1361,8 @@ int lsq_path(int32_t bs, int64_t d, bool wide_accesses, bool sampled) {
     if (d <= kMaxRowsKernelD) return 1;                     // a wave per row, any alignment
     if (!wide_accesses) return d <= kMaxNarrowD ? 1 : 0;   // narrow accesses, same workspace layout
     if (d <= kMaxFusedD) return 1;
-    return (d <= kMaxSplitD && d % 4 == 0 && !sampled) ? 3 : 0;   // columns split over waves (all rows of a node only)
+    (void)sampled;
+    return (d <= kMaxSplitD && d % 4 == 0) ? 3 : 0;   // columns split over waves
 }
 
 int launch_lsq(const float* A, const float* y, const float* x, float* g, float* loss, int32_t n,
@@ -1368,7 +1378,7 @@ int launch_lsq(const float* A, const float* y, const float* x, float* g, float* 
     int path = lsq_path(bs, d, aligned_rows, rows != nullptr);
     if (n > 65535 || splits > 65535) return set_error(DL_EINVAL, "local_grad_lsq: n too large for the launch grid");
     if (path == 3) {
-        const int rc = launch_fused_split(stream, A, y, x, g, loss, n, b, d, ldA, ld, static_cast<double>(scale), workspace);
+        const int rc = launch_fused_split(stream, A, y, x, g, loss, n, b, d, ldA, ld, rows, bs, static_cast<double>(scale), workspace);
         if (rc >= 0) return rc;
         path = 0;   // this device does not hold the launch at once
     }

@@ -575,7 +575,11 @@ def test_decentlam_stays_bounded_on_symmetric_graphs(P):
                                           (40, 300, 4100, 2600, 4),   # eight chunks per thread, no prefetch
                                           (64, 200, 2052, 1500, 0),   # four chunks per thread
                                           (40, 500, 1030, 2000, 2),   # d not a multiple of 4
-                                          (16, 150, 12292, 1200, 0)]) # 1024 threads, four chunks each
+                                          (16, 150, 12292, 1200, 0),  # 1024 threads, four chunks each
+                                          # rows of more than 32768 columns: the columns split over waves
+                                          (2, 60, 40000, 25, 0),      # 20 slots, one row block
+                                          (3, 40, 65536, 100, 4),     # more samples than rows, padded rows, six row blocks
+                                          (1, 30, 32770, 12, 2)])     # d not a multiple of 4 up there: two sweeps
 def test_local_grad_lsq_rows_matches_oracle(P, oracle, n, b, d, bs, pad):
     rng = np.random.default_rng(n * 1000 + bs)
     A0 = rng.standard_normal((n, b, d)).astype(np.float32)
