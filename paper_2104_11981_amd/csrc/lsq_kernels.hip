@@ -780,22 +780,31 @@ __global__ __launch_bounds__(THREADS) void k_fused_narrow(const float* __restric
 // L iterations before it is collected and its loads are issued LA iterations before that.
 // Measured (fraction of the HBM peak for 4 n b d bytes; the two sweeps: 0.33-0.35): 8 nodes of 1024 x 65536 0.73, 4 of
 // 1024 x 131072 0.73, 4 of 1024 x 98304 0.70, 8 of 2048 x 49152 0.68, 64 of 128 x 65536 0.67, 8 of 1024 x 57344 0.64,
-// 16 of 1024 x 36864 0.53-0.66 (it moved with where the arrays lay), 2 of 4096 x 100000 0.56.  Tried without gain:
+// 16 of 1024 x 36864 0.67 (the four-chunk shape, see split_shape), 2 of 4096 x 100000 0.56.  Tried without gain:
 // L = 2 (four tiles of eight chunks do not fit 256 registers; with six or seven chunks per lane they do and shapes
 // that are whole multiples of 1536 or 1792 columns gain 0.03-0.06, but 65536 columns fall to 0.55), the slots read at
 // the top of the iteration (with L = 1 the others' shares are not there yet and the second read costs more than the
-// first saved), one wave per workgroup (0.57-0.71), the rows read through buffer descriptors (same rates), four chunks
-// per lane with three waves per SIMD and L = 2 (shapes that fit 2048-column waves badly gain, 36864 columns 0.55 ->
-// 0.68, 40000 0.57 -> 0.66; those that fit lose, 65536 columns 0.75 -> 0.70, 64 nodes of them 0.69 -> 0.61).
+// first saved), one wave per workgroup (0.57-0.71), the rows read through buffer descriptors (same rates).
 // The waves of a row block wait for one another, so all of them must be on the chip together: the launch never has
 // more workgroups than the chip holds at once (launch_fused_split checks the occupancy the runtime reports), and
 // every wait is bounded: a wave that polls max_polls times in vain raises `failed`, stops waiting for the rest of
 // its rows and runs to its end; k_finish_fused then writes NaN for g and loss of that launch's nodes.
-constexpr int kSplitCPT = 8;                          // 16-byte chunks per lane
-constexpr int kSplitWaveCols = 64 * 4 * kSplitCPT;    // columns per wave: 2048
+// Two shapes.  Eight 16-byte chunks per lane (2048 columns per wave), two waves per SIMD, L = LA = 1: the faster one where
+// a row is whole workgroups of such waves (multiples of 8192 columns) and the only one beyond 65536 columns (64 slots).
+// Four chunks per lane (1024 columns per wave), three waves per SIMD, L = 2: for the other widths up to 65536, where the
+// first leaves waves idle or half empty (36864 columns 0.55 -> 0.68 of the peak, 40000 0.57 -> 0.66; but 65536 columns
+// 0.75 -> 0.70 and 64 nodes of them 0.69 -> 0.61, hence not everywhere).
+struct SplitShape {
+    int cpt;        // 16-byte chunks per lane
+    int resident;   // workgroups per launch at most: 256 CUs x 2, or x 3
+    int wave_cols() const { return 256 * cpt; }
+};
+constexpr int kSplitNarrowMaxD = 64 * 1024;
+SplitShape split_shape(int64_t d) {
+    return (d <= kSplitNarrowMaxD && d % 8192 != 0) ? SplitShape{4, 768} : SplitShape{8, 512};
+}
 constexpr int kSplitWaves = 4;                        // waves per workgroup (they share nothing; neighbours in a row, they read a contiguous piece of it)
-constexpr int kSplitResident = 512;                   // workgroups per launch at most: 256 CUs x 2
-constexpr int64_t kMaxSplitD = 64 * static_cast<int64_t>(kSplitWaveCols);   // 64 slots per row: one load per lane
+constexpr int64_t kMaxSplitD = 64 * 2048;   // 64 slots per row: one load per lane
 constexpr unsigned long long kSlotEmpty = 0x7ff8dec0de5107e1ull;
 constexpr int kSplitPolls = 1 << 21;   // seconds; local_grad_lsq_poll_limit sets another number
 
@@ -836,13 +845,14 @@ __global__ __launch_bounds__(kThreads) void k_fill_slots(unsigned long long* __r
     if (blockIdx.x == 0 && threadIdx.x == 0) *failed = 0u;
 }
 
+template <int CPT>
 struct SplitTile {
-    vf4 a[kSplitCPT];
+    vf4 a[CPT];
     float y;
 };
 
-template <int L, int LA>
-__global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float* __restrict__ A, const float* __restrict__ y,
+template <int CPT, int WPE, int L, int LA>   // chunks per lane, waves per SIMD, iterations ahead: publishing, loads
+__global__ __launch_bounds__(64 * kSplitWaves, WPE) void k_fused_split(const float* __restrict__ A, const float* __restrict__ y,
                                                                     const float* __restrict__ x, double* __restrict__ partial,
                                                                     double* __restrict__ sq_partial,
                                                                     unsigned long long* __restrict__ slots,
@@ -850,6 +860,7 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
                                                                     int64_t ldA, int64_t ld, int splits, int nslots, int node0,
                                                                     int max_polls, const int32_t* __restrict__ rows, int bs) {
     constexpr int NB = L + LA + 1;   // register tiles in rotation
+    constexpr int kWaveCols = 256 * CPT;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int gw = static_cast<int>(blockIdx.x) * kSplitWaves + wave;   // this wave's slot; its columns start at 2048 gw
@@ -861,14 +872,14 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
     const int32_t* __restrict__ rows_i = rows ? rows + static_cast<int64_t>(i) * bs : nullptr;
 
     // a thread's chunks of x_i wait in LDS (xl[256 q], written and read by this thread alone), not in 32 registers
-    __shared__ vf4 x_chunks[kSplitCPT * 64 * kSplitWaves];
+    __shared__ vf4 x_chunks[CPT * 64 * kSplitWaves];
     vf4* xl = x_chunks + threadIdx.x;
-    int col[kSplitCPT];   // chunks past column d are clamped to the last one: their x is zero and their sums are never stored
-    double acc[kSplitCPT][4];
+    int col[CPT];   // chunks past column d are clamped to the last one: their x is zero and their sums are never stored
+    double acc[CPT][4];
     const bool x_wide = ((reinterpret_cast<uintptr_t>(x) & 15u) | (static_cast<uint64_t>(ld) & 3u)) == 0;
 #pragma unroll
-    for (int q = 0; q < kSplitCPT; ++q) {
-        const int64_t c = static_cast<int64_t>(gw) * kSplitWaveCols + 256 * q + 4 * lane;
+    for (int q = 0; q < CPT; ++q) {
+        const int64_t c = static_cast<int64_t>(gw) * kWaveCols + 256 * q + 4 * lane;
         const bool inside = c < d;   // d is a multiple of 4: chunks are inside or outside as a whole
         col[q] = static_cast<int>(inside ? c : d - 4);
         const float* xp = x + static_cast<int64_t>(i) * ld + col[q];
@@ -885,18 +896,18 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
         const int row = r < r1 ? r : r1 - 1;   // rows past the block's end read its last row again (never used)
         return rows_i ? physical_row(rows_i, row, b) : row;
     };
-    auto load = [&](SplitTile& t, int row) {
+    auto load = [&](SplitTile<CPT>& t, int row) {
         const float* __restrict__ a_row = a_node + static_cast<int64_t>(row) * ldA;
         t.y = yi[row];
 #pragma unroll
-        for (int q = 0; q < kSplitCPT; ++q)
+        for (int q = 0; q < CPT; ++q)
             t.a[q] = __builtin_nontemporal_load(reinterpret_cast<const vf4*>(a_row + col[q]));
     };
-    auto publish = [&](const SplitTile& t, int r) {   // this wave's share of row r's dot product
+    auto publish = [&](const SplitTile<CPT>& t, int r) {   // this wave's share of row r's dot product
         if (r >= r1) return;   // uniform
         double s0 = 0.0, s1 = 0.0;
 #pragma unroll
-        for (int q = 0; q < kSplitCPT; ++q) {
+        for (int q = 0; q < CPT; ++q) {
             const vf4 xv = xl[64 * kSplitWaves * q];
             s0 = __builtin_fma(static_cast<double>(t.a[q].x), static_cast<double>(xv.x), s0);
             s1 = __builtin_fma(static_cast<double>(t.a[q].y), static_cast<double>(xv.y), s1);
@@ -916,7 +927,7 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
         const int row = r < r1 ? r : r1 - 1;
         return slot_load(slots_i + static_cast<int64_t>(row) * nslots + (lane < nslots ? lane : 0));
     };
-    auto consume = [&](const SplitTile& t, int r, unsigned long long bits) {
+    auto consume = [&](const SplitTile<CPT>& t, int r, unsigned long long bits) {
         if (r >= r1) return;   // uniform
         const unsigned long long* mine = slots_i + static_cast<int64_t>(r) * nslots + (lane < nslots ? lane : 0);
         if (!gave_up) {
@@ -935,7 +946,7 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
         const double res = wave_sum_uniform(share) - static_cast<double>(t.y);   // the same bits in every wave of the block
         sq = __builtin_fma(res, res, sq);
 #pragma unroll
-        for (int q = 0; q < kSplitCPT; ++q) {
+        for (int q = 0; q < CPT; ++q) {
             vf4 a = t.a[q];
             asm volatile("" : "+v"(a));   // widened here again: fp64 copies kept since publish() would double the tile's footprint
             acc[q][0] = __builtin_fma(static_cast<double>(a.x), res, acc[q][0]);
@@ -945,7 +956,7 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
         }
     };
 
-    SplitTile t[NB];
+    SplitTile<CPT> t[NB];
     // Row rho waits in t[(rho - r0) % NB]: rows r0 .. r0 + L + LA - 1 on their way, the first L of them published.
 #pragma unroll
     for (int k = 0; k < L + LA; ++k) load(t[k], physical(r0 + k));
@@ -965,8 +976,8 @@ __global__ __launch_bounds__(64 * kSplitWaves, 2) void k_fused_split(const float
     // (partial and sq_partial belong to this launch: its first node is their node 0)
     double* out = partial + (static_cast<int64_t>(blockIdx.z) * splits + s) * d;
 #pragma unroll
-    for (int q = 0; q < kSplitCPT; ++q) {
-        const int64_t c = static_cast<int64_t>(gw) * kSplitWaveCols + 256 * q + 4 * lane;
+    for (int q = 0; q < CPT; ++q) {
+        const int64_t c = static_cast<int64_t>(gw) * kWaveCols + 256 * q + 4 * lane;
         if (c < d) {
             out[c + 0] = acc[q][0]; out[c + 1] = acc[q][1]; out[c + 2] = acc[q][2]; out[c + 3] = acc[q][3];
         }
@@ -1208,7 +1219,8 @@ int launch_fused_narrow(dim3 grid, hipStream_t stream, const float* A, const flo
 }
 
 // How a call over rows wider than kMaxFusedD is cut up for k_fused_split: launches of `nodes` nodes with `splits` row
-// blocks each, a wave per 1536 columns of a row block, so that no launch has more than kSplitResident waves.  A pure
+// blocks each, a wave per 2048 or 1024 columns of a row block, so that no launch has more workgroups than the chip
+// holds at once (split_shape).  A pure
 // function of the shape (no device query): the workspace size depends on it.  Few nodes per launch allow more row
 // blocks per node and so fill the chip better where nodes x slots divides the chip badly (8 nodes of 65536 columns,
 // 43 slots: one launch of 8 x 5 blocks uses 1720 of 2048 waves, two launches of 4 x 11 blocks 1892); every launch
@@ -1216,9 +1228,9 @@ int launch_fused_narrow(dim3 grid, hipStream_t stream, const float* A, const flo
 struct SplitChunk {
     int nodes, splits;
 };
-int split_slots(int64_t d) { return static_cast<int>((d + kSplitWaveCols - 1) / kSplitWaveCols); }
-SplitChunk split_chunk(int n_left, int32_t b, int nslots) {
-    const int blocks = kSplitResident / ((nslots + kSplitWaves - 1) / kSplitWaves);   // row blocks per launch: 32 or more up to kMaxSplitD
+int split_slots(int64_t d) { return static_cast<int>((d + split_shape(d).wave_cols() - 1) / split_shape(d).wave_cols()); }
+SplitChunk split_chunk(int n_left, int32_t b, int nslots, int resident) {
+    const int blocks = resident / ((nslots + kSplitWaves - 1) / kSplitWaves);   // row blocks per launch: 32 or more up to kMaxSplitD
     const int most = b >= 32 ? b / 16 : 1;        // a row block has 16 rows or more
     SplitChunk best{1, 1};
     int64_t best_cost = INT64_MAX;
@@ -1242,9 +1254,10 @@ int split_plan_rows(int32_t b) {
     return q;
 }
 size_t split_sums_doubles(int32_t n, int32_t plan_rows, int64_t d, int nslots) {
+    const int resident = split_shape(d).resident;
     size_t doubles = 0;
     for (int node0 = 0; node0 < n;) {
-        const SplitChunk c = split_chunk(n - node0, plan_rows, nslots);
+        const SplitChunk c = split_chunk(n - node0, plan_rows, nslots, resident);
         const size_t blocks = static_cast<size_t>(c.nodes) * c.splits;
         doubles += ((blocks + 1) & ~size_t{1}) + blocks * static_cast<size_t>(d);
         node0 += c.nodes;
@@ -1263,7 +1276,7 @@ size_t split_workspace_bytes(int32_t n, int32_t b, int64_t d) {
 }
 
 // Workgroups of k_fused_split the current device holds at once (asked once per device); 0 on error.
-template <int L, int LA>
+template <int CPT, int WPE, int L, int LA>
 int split_resident_workgroups() {
     static std::atomic<int> known[64];
     int device = 0;
@@ -1273,14 +1286,13 @@ int split_resident_workgroups() {
         if (v) return v;
     }
     int per_cu = 0, cus = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused_split<L, LA>, 64 * kSplitWaves, 0) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused_split<CPT, WPE, L, LA>, 64 * kSplitWaves, 0) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
     const int total = per_cu * cus;
     if (device >= 0 && device < 64 && total > 0) known[device].store(total, std::memory_order_relaxed);
     return total;
 }
 
-constexpr int kSplitL = 1, kSplitLA = 1;
 std::atomic<int> g_split_polls{kSplitPolls};
 
 // Returns DL_OK after launching, a status on error, or -1 when the device cannot hold a launch at once (the caller
@@ -1289,7 +1301,9 @@ int launch_fused_split(hipStream_t stream, const float* A, const float* y, const
                        int32_t n, int32_t b, int64_t d, int64_t ldA, int64_t ld, const int32_t* rows, int32_t bs,
                        double scale, void* workspace) {
     const int nslots = split_slots(d);
-    if (split_resident_workgroups<kSplitL, kSplitLA>() < kSplitResident) return -1;
+    const SplitShape shape = split_shape(d);
+    const bool narrow = shape.cpt == 4;
+    if ((narrow ? split_resident_workgroups<4, 3, 2, 1>() : split_resident_workgroups<8, 2, 1, 1>()) < shape.resident) return -1;
     unsigned long long* slots = static_cast<unsigned long long*>(workspace);
     const int64_t slot_count = static_cast<int64_t>(n) * bs * nslots;
     unsigned* failed = reinterpret_cast<unsigned*>(slots + slot_count);
@@ -1299,14 +1313,19 @@ int launch_fused_split(hipStream_t stream, const float* A, const float* y, const
                        dim3(kThreads), 0, stream, slots, slot_count, failed);
     if (int rc = check_hip(hipGetLastError(), "slot fill kernel launch")) return rc;
     for (int node0 = 0; node0 < n;) {
-        const SplitChunk c = split_chunk(n - node0, split_plan_rows(bs), nslots);
+        const SplitChunk c = split_chunk(n - node0, split_plan_rows(bs), nslots, shape.resident);
         const size_t blocks = static_cast<size_t>(c.nodes) * c.splits;
         double* sq_partial = sums;
         double* fpartial = sums + ((blocks + 1) & ~size_t{1});
         sums = fpartial + blocks * static_cast<size_t>(d);
         const dim3 grid(static_cast<unsigned>((nslots + kSplitWaves - 1) / kSplitWaves), static_cast<unsigned>(c.splits), static_cast<unsigned>(c.nodes));
-        hipLaunchKernelGGL((k_fused_split<kSplitL, kSplitLA>), grid, dim3(64 * kSplitWaves), 0, stream, A, y, x, fpartial, sq_partial,
-                           slots, failed, b, d, ldA, ld, c.splits, nslots, node0, g_split_polls.load(std::memory_order_relaxed), rows, bs);
+        const int polls = g_split_polls.load(std::memory_order_relaxed);
+        if (narrow)
+            hipLaunchKernelGGL((k_fused_split<4, 3, 2, 1>), grid, dim3(64 * kSplitWaves), 0, stream, A, y, x, fpartial, sq_partial,
+                               slots, failed, b, d, ldA, ld, c.splits, nslots, node0, polls, rows, bs);
+        else
+            hipLaunchKernelGGL((k_fused_split<8, 2, 1, 1>), grid, dim3(64 * kSplitWaves), 0, stream, A, y, x, fpartial, sq_partial,
+                               slots, failed, b, d, ldA, ld, c.splits, nslots, node0, polls, rows, bs);
         if (int rc = check_hip(hipGetLastError(), "fused gradient kernel launch (columns split over waves)")) return rc;
         const dim3 grid_ff(static_cast<unsigned>((d + kFinishColumns - 1) / kFinishColumns), static_cast<unsigned>(c.nodes));
         hipLaunchKernelGGL(k_finish_fused, grid_ff, dim3(kThreads), 0, stream, fpartial, sq_partial, g + static_cast<int64_t>(node0) * ld,
