@@ -793,7 +793,8 @@ __global__ __launch_bounds__(THREADS) void k_fused_narrow(const float* __restric
 // a row is whole workgroups of such waves (multiples of 8192 columns) and the only one beyond 65536 columns (64 slots).
 // Four chunks per lane (1024 columns per wave), three waves per SIMD, L = 2: for the other widths up to 65536, where the
 // first leaves waves idle or half empty (36864 columns 0.55 -> 0.68 of the peak, 40000 0.57 -> 0.66; but 65536 columns
-// 0.75 -> 0.70 and 64 nodes of them 0.69 -> 0.61, hence not everywhere).
+// 0.75 -> 0.70 and 64 nodes of them 0.69 -> 0.61, hence not everywhere; beyond 65536 columns, with two slots per lane, it
+// gained nothing: 100000 columns 0.56 either way, 120000 0.53).
 struct SplitShape {
     int cpt;        // 16-byte chunks per lane
     int resident;   // workgroups per launch at most: 256 CUs x 2, or x 3

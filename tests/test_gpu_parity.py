@@ -208,6 +208,8 @@ LSQ_CASES = [
     (2, 40, 40000, 0, 0, 1.0),           # 20 slots, a ragged last wave, two row blocks per node
     (3, 50, 65536, 0, 0, 0.5),           # 32 slots: eight whole workgroups per row block
     (2, 33, 131072, 0, 0, 1.0),          # 64 slots: the widest
+    (2, 33, 100000, 0, 0, 1.0),          # 49 slots, the last with 1696 columns
+    (1, 20, 131068, 4, 0, 1.0),          # 64 slots, the last four columns short
     (2, 70, 36868, 4, 4, 1.0),           # padded rows, four row blocks of 17 or 18 rows
     (2, 30, 50000, 0, 3, 1.0),           # x and g off the 16-byte grid
     (40, 3, 131072, 0, 0, 1.0),          # more nodes than one launch holds (32 row blocks of 16 workgroups): two launches
@@ -579,6 +581,7 @@ def test_decentlam_stays_bounded_on_symmetric_graphs(P):
                                           # rows of more than 32768 columns: the columns split over waves
                                           (2, 60, 40000, 25, 0),      # 20 slots, one row block
                                           (3, 40, 65536, 100, 4),     # more samples than rows, padded rows, six row blocks
+                                          (2, 30, 70000, 20, 0),      # 35 slots of 2048 columns, the last nearly empty
                                           (1, 30, 32770, 12, 2)])     # d not a multiple of 4 up there: two sweeps
 def test_local_grad_lsq_rows_matches_oracle(P, oracle, n, b, d, bs, pad):
     rng = np.random.default_rng(n * 1000 + bs)
