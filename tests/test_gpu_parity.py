@@ -654,6 +654,49 @@ def test_iteration_is_capturable_in_a_hip_graph(P):
         torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("d", [40000, 65536])
+def test_wide_row_gradient_is_capturable(P, d):
+    """Rows of more than 32768 columns: the call marks its exchange slots empty with a kernel of its own (no memset), so
+    it can be captured like the others.  Four replays of a captured gradient + step, each against eager execution, with
+    eager work in between: every replay has to find the slots marked empty again, not filled by the replay before it."""
+    n, b = 3, 48
+    topo = P.topology_build(P.DL_TOPO_RING, n)
+    gamma, beta = float(np.float32(1e-5)), float(np.float32(0.8))
+    gen = torch.Generator(device="cuda").manual_seed(d)
+    A = torch.randn((n, b, d), device="cuda", generator=gen)
+    y = torch.randn((n, b), device="cuda", generator=gen)
+    x0 = torch.randn((n, d), device="cuda", generator=gen)
+    ws = torch.empty(P.local_grad_lsq_workspace(n, b, d), dtype=torch.uint8, device="cuda")
+    scale = float(np.float32(1.0 / b))
+
+    def iteration(x, m, g, loss):
+        P.local_grad_lsq(A, y, x, g, loss, scale, ws)
+        P.decentlam_step(x, m, g, topo, gamma, beta, 0)
+
+    xe, me, ge, le = x0.clone(), torch.zeros_like(x0), torch.zeros_like(x0), torch.zeros(n, device="cuda")
+    eager = []
+    for _ in range(4):
+        iteration(xe, me, ge, le)
+        eager.append((xe.clone(), me.clone(), le.clone()))
+    assert bool(torch.isfinite(xe).all()) and not torch.equal(eager[0][0], eager[3][0])
+
+    xg, mg, gg, lg = x0.clone(), torch.zeros_like(x0), torch.zeros_like(x0), torch.zeros(n, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        iteration(xg, mg, gg, lg)
+    xg.copy_(x0)
+    mg.zero_()
+    scratch = torch.zeros(1000, device="cuda")
+    for r in range(4):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(xg, eager[r][0]) and torch.equal(mg, eager[r][1]) and torch.equal(lg, eager[r][2]), f"replay {r}"
+        scratch.add_(1.0)
+        torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("graph", ["exp_sym", "all_to_all"])
 def test_large_lds_kernels_are_capturable(P, graph):
     """The 32-node kernels ask for more than 48 KiB of dynamic LDS, which takes a function-attribute
