@@ -784,7 +784,11 @@ __global__ __launch_bounds__(THREADS) void k_fused_narrow(const float* __restric
 // L = 2 (four tiles of eight chunks do not fit 256 registers; with six or seven chunks per lane they do and shapes
 // that are whole multiples of 1536 or 1792 columns gain 0.03-0.06, but 65536 columns fall to 0.55), the slots read at
 // the top of the iteration (with L = 1 the others' shares are not there yet and the second read costs more than the
-// first saved), one wave per workgroup (0.57-0.71), the rows read through buffer descriptors (same rates).
+// first saved), one wave per workgroup (0.57-0.71), the rows read through buffer descriptors (same rates).  Not what
+// holds it back: the waiting itself -- with the poll limit at zero (nobody waits, the numbers are then wrong) the same
+// launches run slower, 0.56-0.62 where they run 0.67-0.73: waves that keep pace read a row together, and the memory
+// likes that better than 32 waves each at its own row -- nor the loads in flight (the four-chunk shape with the loads two
+// iterations ahead: 0.63 where one iteration gives 0.67).
 // The waves of a row block wait for one another, so all of them must be on the chip together: the launch never has
 // more workgroups than the chip holds at once (launch_fused_split checks the occupancy the runtime reports), and
 // every wait is bounded: a wave that polls max_polls times in vain raises `failed`, stops waiting for the rest of
