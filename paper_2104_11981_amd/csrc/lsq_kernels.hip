@@ -872,8 +872,12 @@ __global__ __launch_bounds__(64 * kSplitWaves, WPE) void k_fused_split(const flo
     if (gw >= nslots) return;   // whole waves only; nothing in this kernel is shared within a workgroup
     const int s = blockIdx.y, i = node0 + static_cast<int>(blockIdx.z);
     // bs logical rows per node: all b rows, or (rows != nullptr) the sampled ones, looked up as they come
-    const int r0 = static_cast<int>(static_cast<int64_t>(bs) * s / splits);
-    const int r1 = static_cast<int>(static_cast<int64_t>(bs) * (s + 1) / splits);   // r1 > r0: splits <= bs
+    // Row block s takes the logical rows s, s + splits, s + 2 splits, ...: the blocks of a node, which run side by side,
+    // then read neighbouring rows of A_i at any moment, one window that moves through the matrix, instead of `splits`
+    // places far apart.  Below, r counts the block's own rows (0 .. r1 - 1) and logical(r) is the row it stands for.
+    const int r0 = 0;
+    const int r1 = (bs - s + splits - 1) / splits;   // r1 >= 1: splits <= bs
+    auto logical = [&](int r) -> int { return s + r * splits; };
     const int32_t* __restrict__ rows_i = rows ? rows + static_cast<int64_t>(i) * bs : nullptr;
 
     // a thread's chunks of x_i wait in LDS (xl[256 q], written and read by this thread alone), not in 32 registers
@@ -898,7 +902,7 @@ __global__ __launch_bounds__(64 * kSplitWaves, WPE) void k_fused_split(const flo
 
     // The physical row of logical row r (uniform), asked for one iteration before the loads that need it.
     auto physical = [&](int r) -> int {
-        const int row = r < r1 ? r : r1 - 1;   // rows past the block's end read its last row again (never used)
+        const int row = logical(r < r1 ? r : r1 - 1);   // rows past the block's end read its last row again (never used)
         return rows_i ? physical_row(rows_i, row, b) : row;
     };
     auto load = [&](SplitTile<CPT>& t, int row) {
@@ -923,18 +927,18 @@ __global__ __launch_bounds__(64 * kSplitWaves, WPE) void k_fused_split(const flo
         unsigned long long bits = __builtin_bit_cast(unsigned long long, p);
         if (bits == kSlotEmpty) bits ^= 1ull;   // (cannot happen with fp32 inputs; the mark stays unique anyway)
         if (lane == 0)
-            __hip_atomic_store(slots_i + static_cast<int64_t>(r) * nslots + gw, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(slots_i + static_cast<int64_t>(logical(r)) * nslots + gw, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
     bool gave_up = false;   // uniform
     double sq = 0.0;
     // The row's slots, lane by lane (lanes beyond the last slot read slot 0 and count for nothing).
     auto peek = [&](int r) -> unsigned long long {
-        const int row = r < r1 ? r : r1 - 1;
+        const int row = logical(r < r1 ? r : r1 - 1);
         return slot_load(slots_i + static_cast<int64_t>(row) * nslots + (lane < nslots ? lane : 0));
     };
     auto consume = [&](const SplitTile<CPT>& t, int r, unsigned long long bits) {
         if (r >= r1) return;   // uniform
-        const unsigned long long* mine = slots_i + static_cast<int64_t>(r) * nslots + (lane < nslots ? lane : 0);
+        const unsigned long long* mine = slots_i + static_cast<int64_t>(logical(r)) * nslots + (lane < nslots ? lane : 0);
         if (!gave_up) {
             int polls = 0;
             while (__builtin_amdgcn_ballot_w64(bits == kSlotEmpty) != 0ull) {   // until every wave of the block has published
