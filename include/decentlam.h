@@ -477,7 +477,7 @@ int dsgd_step(float* x, const float* g,
  * boundaries: 0.8 up to 2048 columns, 0.65-0.75 up to 8192, 0.5-0.65 up to 16384).  Rows of 32772 to 131072 columns
  * (d a multiple of 4, rows of A on 16-byte boundaries) are still read once: the columns of a block of rows are split
  * over waves of several workgroups, which hand one another their shares of each row's dot product through the workspace
- * (8 nodes of 1024 x 65536: 0.35 ms, 0.78 of the peak; other shapes 0.55-0.73).  Those workgroups wait for one another,
+ * (8 nodes of 1024 x 65536: 0.35 ms, 0.76 of the peak; other shapes 0.6-0.78).  Those workgroups wait for one another,
  * so a launch is sized to what the chip holds at once and every wait is bounded: should the GPU be kept busy by other
  * work for seconds on end, so that they cannot all run together, the call gives up and leaves NaN in all of g and
  * loss instead of hanging.  Wider rows than these limits take two passes over A at 0.3-0.35 of the peak.  No access

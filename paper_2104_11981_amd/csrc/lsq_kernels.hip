@@ -778,9 +778,10 @@ __global__ __launch_bounds__(THREADS) void k_fused_narrow(const float* __restric
 // which this chip has.  A slot that has not been written yet holds kSlotEmpty, a NaN whose low mantissa bits no sum
 // of products of fp32 numbers can have (k_fill_slots writes it before every call).  A row's share is published
 // L iterations before it is collected and its loads are issued LA iterations before that.
-// Measured (fraction of the HBM peak for 4 n b d bytes; the two sweeps: 0.33-0.35): 8 nodes of 1024 x 65536 0.73, 4 of
-// 1024 x 131072 0.73, 4 of 1024 x 98304 0.70, 8 of 2048 x 49152 0.68, 64 of 128 x 65536 0.67, 8 of 1024 x 57344 0.64,
-// 16 of 1024 x 36864 0.67 (the four-chunk shape, see split_shape), 2 of 4096 x 100000 0.56.  Tried without gain:
+// Measured (fraction of the HBM peak for 4 n b d bytes; the two sweeps: 0.33-0.35): 8 nodes of 1024 x 65536 0.76, 8 of
+// 2048 x 49152 0.78, 8 of 1024 x 57344 0.76, 4 of 1024 x 131072 0.75, 4 of 1024 x 98304 0.73, 2 of 4096 x 100000 0.72,
+// 64 of 128 x 65536 0.69, 16 of 1024 x 36864 0.68 (the four-chunk shape, see split_shape), 8 of 1024 x 33000 0.61.
+// Tried without gain:
 // L = 2 (four tiles of eight chunks do not fit 256 registers; with six or seven chunks per lane they do and shapes
 // that are whole multiples of 1536 or 1792 columns gain 0.03-0.06, but 65536 columns fall to 0.55), the slots read at
 // the top of the iteration (with L = 1 the others' shares are not there yet and the second read costs more than the
