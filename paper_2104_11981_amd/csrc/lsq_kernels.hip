@@ -245,15 +245,19 @@ __device__ __forceinline__ void tile_rows(int (&prow)[R], int r, int r_last, con
 // look-up per tile shares its counter with the tile's LDS traffic, and waiting for one means waiting for the other
 // (64 nodes, 4096 sampled rows of 4096 columns: see launch_lsq).  Requests must come in non-decreasing row order and
 // advance by less than 64 rows at a time; the form with x_i in LDS has no registers for this and looks up row by row.
+// off, stride: request r stands for logical row off + r * stride (0, 1: r itself; s, splits: the interleaved rows of row
+// block s, see k_fused).
 struct RowWindow {
     const int32_t* rows_i;
     int b, r_last, base;
     int lo, hi;
+    int off, stride;
     __device__ __forceinline__ int fetch(int first) const {
         const int row = first + static_cast<int>(threadIdx.x & 63);
-        return physical_row(rows_i, row < r_last ? row : r_last, b);
+        return physical_row(rows_i, off + (row < r_last ? row : r_last) * stride, b);
     }
-    __device__ __forceinline__ void init(const int32_t* __restrict__ rows, int b_, int r0, int r_last_) {
+    __device__ __forceinline__ void init(const int32_t* __restrict__ rows, int b_, int r0, int r_last_, int off_ = 0, int stride_ = 1) {
+        off = off_; stride = stride_;
         rows_i = rows; b = b_; r_last = r_last_; base = r0;
         lo = hi = 0;
         if (rows_i) {
@@ -274,7 +278,7 @@ struct RowWindow {
                 }
                 prow[rr] = __builtin_amdgcn_readlane(lo, row - base);
             } else {
-                prow[rr] = row;
+                prow[rr] = off + row * stride;
             }
         }
     }
@@ -403,8 +407,17 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : 2) void k_fused(const 
     const int i = blockIdx.y, s = blockIdx.x;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int r0 = static_cast<int>(static_cast<int64_t>(bs) * s / splits);
-    const int r1 = static_cast<int>(static_cast<int64_t>(bs) * (s + 1) / splits);  // r1 > r0: splits <= bs
+    // The forms with one row per tile and 256 threads (2048 < d <= 8192) give row block s the rows s, s + splits, ...: the
+    // blocks of a node, which run side by side, then read neighbouring rows of A_i, one window that moves through the
+    // matrix, instead of `splits` places far apart (same box, same calls: 32 nodes of 4096 x 6144 0.83 -> 0.89 of the HBM
+    // peak, 16 of 4096 x 8192 0.82 -> 0.85, 64 of 4096 x 4096 0.86 either way; the 1024-thread forms, whose workgroups read
+    // rows of 64-128 KiB, gain nothing).  There r counts the block's own rows and the row window turns it into the row it
+    // stands for.
+    constexpr bool kInterleaved = R == 1 && THREADS == 256;
+    const int r0 = kInterleaved ? 0 : static_cast<int>(static_cast<int64_t>(bs) * s / splits);
+    const int r1 = kInterleaved ? (bs - s + splits - 1) / splits
+                                : static_cast<int>(static_cast<int64_t>(bs) * (s + 1) / splits);  // r1 > r0: splits <= bs
+    const int row_off = kInterleaved ? s : 0, row_stride = kInterleaved ? splits : 1;
     const int32_t* __restrict__ rows_i = rows ? rows + static_cast<int64_t>(i) * bs : nullptr;
 
     extern __shared__ vf4 x_chunks[];   // XL: CPT * THREADS chunks of x_i, each read only by the thread that wrote it
@@ -451,7 +464,7 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : 2) void k_fused(const 
         Tile<CPT, R> t0, t1;
         int p0[R], p1[R];   // physical rows of the tile that is loaded next into t0 / t1
         RowWindow win;
-        win.init(rows_i, b, r0, r1 - 1);
+        win.init(rows_i, b, r0, r1 - 1, row_off, row_stride);
         win.tile<R>(p0, r0);
         load_tile<CPT, R, TAIL>(t0, a_node, ldA, p0, col, yi, dm, dt);
         win.tile<R>(p1, r0 + R);
@@ -470,7 +483,7 @@ __global__ __launch_bounds__(THREADS, THREADS > 256 ? 4 : 2) void k_fused(const 
         constexpr bool kWindow = !XL;   // see RowWindow; the form with x_i in LDS has no register left for it
         RowWindow win;
         if constexpr (kWindow) {
-            win.init(rows_i, b, r0, r1 - 1);
+            win.init(rows_i, b, r0, r1 - 1, row_off, row_stride);
             win.tile<R>(p0, r0);
         } else {
             tile_rows<R>(p0, r0, r1 - 1, rows_i, b);
