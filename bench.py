@@ -893,10 +893,10 @@ def main():
         c5 = bench_lsq(P, workloads, "c5_onepeer64_lsq", args.steps, args.warmup)
         extras["local_grad_lsq_c5"] = c5
         # rows too wide for the register-resident x_i (16384 < d <= 32768: the widest form of a workgroup per row tile),
-        # wider still (up to 131072: the columns of a row split over waves, still one sweep) and beyond (two sweeps)
+        # wider still (up to 262144: the columns of a row split over waves, still one sweep) and beyond (two sweeps)
         extras["local_grad_lsq_wide_rows"] = {
             f"n{n}_b{b}_d{d}": bench_lsq_shape(P, n, b, d, args.steps, args.warmup)
-            for n, b, d in ((8, 2048, 32768), (8, 1024, 65536), (4, 1024, 131072), (2, 1024, 262144))}
+            for n, b, d in ((8, 2048, 32768), (8, 1024, 65536), (4, 1024, 131072), (2, 1024, 262144), (1, 1024, 524288))}
         # short rows: a wave per row (or per two rows)
         extras["local_grad_lsq_short_rows"] = {
             f"n{n}_b{b}_d{d}": bench_lsq_shape(P, n, b, d, args.steps, args.warmup)

@@ -20,7 +20,7 @@
 // without fences, with device-scope atomic accesses for everything that crosses blocks, the final sum of one
 // block is a chain of uncached loads: 0.64 ms and 54 us.  The second launch costs less than either.)
 //
-// Single sweep for wider rows (32768 < d <= 131072, d a multiple of 4, rows of A on 16-byte boundaries):
+// Single sweep for wider rows (32768 < d <= 262144, d a multiple of 4, rows of A on 16-byte boundaries):
 // k_fused_split, the columns of a row block split over waves that exchange one number per wave and row
 // through device memory; see there.
 //
@@ -793,7 +793,8 @@ __global__ __launch_bounds__(THREADS) void k_fused_narrow(const float* __restric
 // L iterations before it is collected and its loads are issued LA iterations before that.
 // Measured (fraction of the HBM peak for 4 n b d bytes; the two sweeps: 0.33-0.35): 8 nodes of 1024 x 65536 0.76, 8 of
 // 2048 x 49152 0.78, 8 of 1024 x 57344 0.76, 4 of 1024 x 131072 0.75, 4 of 1024 x 98304 0.73, 2 of 4096 x 100000 0.72,
-// 64 of 128 x 65536 0.69, 16 of 1024 x 36864 0.68 (the four-chunk shape, see split_shape), 8 of 1024 x 33000 0.61.
+// 64 of 128 x 65536 0.69, 16 of 1024 x 36864 0.68 (the four-chunk shape, see split_shape), 8 of 1024 x 33000 0.61; beyond
+// 131072 columns (two slots per lane, SL = 2) 2 of 1024 x 262144 0.67, 2 of 1024 x 200000 0.59.
 // Tried without gain:
 // L = 2 (four tiles of eight chunks do not fit 256 registers; with six or seven chunks per lane they do and shapes
 // that are whole multiples of 1536 or 1792 columns gain 0.03-0.06, but 65536 columns fall to 0.55), the slots read at
@@ -823,7 +824,7 @@ SplitShape split_shape(int64_t d) {
     return (d <= kSplitNarrowMaxD && d % 8192 != 0) ? SplitShape{4, 768} : SplitShape{8, 512};
 }
 constexpr int kSplitWaves = 4;                        // waves per workgroup (they share nothing; neighbours in a row, they read a contiguous piece of it)
-constexpr int64_t kMaxSplitD = 64 * 2048;   // 64 slots per row: one load per lane
+constexpr int64_t kMaxSplitD = 128 * 2048;   // 128 slots per row: two loads per lane beyond 131072 columns
 constexpr unsigned long long kSlotEmpty = 0x7ff8dec0de5107e1ull;
 constexpr int kSplitPolls = 1 << 21;   // seconds; local_grad_lsq_poll_limit sets another number
 
@@ -870,7 +871,7 @@ struct SplitTile {
     float y;
 };
 
-template <int CPT, int WPE, int L, int LA>   // chunks per lane, waves per SIMD, iterations ahead: publishing, loads
+template <int CPT, int WPE, int L, int LA, int SL>   // chunks per lane, waves per SIMD, iterations ahead: publishing, loads; slots read per lane
 __global__ __launch_bounds__(64 * kSplitWaves, WPE) void k_fused_split(const float* __restrict__ A, const float* __restrict__ y,
                                                                     const float* __restrict__ x, double* __restrict__ partial,
                                                                     double* __restrict__ sq_partial,
@@ -945,27 +946,41 @@ __global__ __launch_bounds__(64 * kSplitWaves, WPE) void k_fused_split(const flo
     };
     bool gave_up = false;   // uniform
     double sq = 0.0;
-    // The row's slots, lane by lane (lanes beyond the last slot read slot 0 and count for nothing).
-    auto peek = [&](int r) -> unsigned long long {
-        const int row = logical(r < r1 ? r : r1 - 1);
-        return slot_load(slots_i + static_cast<int64_t>(row) * nslots + (lane < nslots ? lane : 0));
+    // The row's slots, SL per lane: lane l reads slots l, l + 64, ... (beyond the last slot: slot 0, counting for nothing).
+    struct Slots {
+        unsigned long long v[SL];
     };
-    auto consume = [&](const SplitTile<CPT>& t, int r, unsigned long long bits) {
+    auto peek = [&](int r) -> Slots {
+        const int row = logical(r < r1 ? r : r1 - 1);
+        Slots got;
+#pragma unroll
+        for (int j = 0; j < SL; ++j)
+            got.v[j] = slot_load(slots_i + static_cast<int64_t>(row) * nslots + (lane + 64 * j < nslots ? lane + 64 * j : 0));
+        return got;
+    };
+    auto any_empty = [&](const Slots& got) -> bool {   // uniform
+        bool empty = false;
+#pragma unroll
+        for (int j = 0; j < SL; ++j) empty |= got.v[j] == kSlotEmpty;
+        return __builtin_amdgcn_ballot_w64(empty) != 0ull;
+    };
+    auto consume = [&](const SplitTile<CPT>& t, int r, Slots got) {
         if (r >= r1) return;   // uniform
-        const unsigned long long* mine = slots_i + static_cast<int64_t>(logical(r)) * nslots + (lane < nslots ? lane : 0);
         if (!gave_up) {
             int polls = 0;
-            while (__builtin_amdgcn_ballot_w64(bits == kSlotEmpty) != 0ull) {   // until every wave of the block has published
+            while (any_empty(got)) {   // until every wave of the block has published
                 if (++polls > max_polls) {
                     gave_up = true;
                     if (lane == 0) __hip_atomic_store(failed, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     break;
                 }
                 __builtin_amdgcn_s_sleep(1);
-                bits = slot_load(mine);
+                got = peek(r);
             }
         }
-        const double share = lane < nslots ? __builtin_bit_cast(double, bits) : 0.0;
+        double share = 0.0;   // the lane's slots in ascending order, then the wave sum: one order for every wave
+#pragma unroll
+        for (int j = 0; j < SL; ++j) share += lane + 64 * j < nslots ? __builtin_bit_cast(double, got.v[j]) : 0.0;
         const double res = wave_sum_uniform(share) - static_cast<double>(t.y);   // the same bits in every wave of the block
         sq = __builtin_fma(res, res, sq);
 #pragma unroll
@@ -1299,7 +1314,7 @@ size_t split_workspace_bytes(int32_t n, int32_t b, int64_t d) {
 }
 
 // Workgroups of k_fused_split the current device holds at once (asked once per device); 0 on error.
-template <int CPT, int WPE, int L, int LA>
+template <int CPT, int WPE, int L, int LA, int SL>
 int split_resident_workgroups() {
     static std::atomic<int> known[64];
     int device = 0;
@@ -1309,7 +1324,7 @@ int split_resident_workgroups() {
         if (v) return v;
     }
     int per_cu = 0, cus = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused_split<CPT, WPE, L, LA>, 64 * kSplitWaves, 0) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused_split<CPT, WPE, L, LA, SL>, 64 * kSplitWaves, 0) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
     const int total = per_cu * cus;
     if (device >= 0 && device < 64 && total > 0) known[device].store(total, std::memory_order_relaxed);
@@ -1325,8 +1340,10 @@ int launch_fused_split(hipStream_t stream, const float* A, const float* y, const
                        double scale, void* workspace) {
     const int nslots = split_slots(d);
     const SplitShape shape = split_shape(d);
-    const bool narrow = shape.cpt == 4;
-    if ((narrow ? split_resident_workgroups<4, 3, 2, 1>() : split_resident_workgroups<8, 2, 1, 1>()) < shape.resident) return -1;
+    const bool narrow = shape.cpt == 4, two_slots = nslots > 64;
+    const int resident = narrow ? split_resident_workgroups<4, 3, 2, 1, 1>()
+                         : two_slots ? split_resident_workgroups<8, 2, 1, 1, 2>() : split_resident_workgroups<8, 2, 1, 1, 1>();
+    if (resident < shape.resident) return -1;
     unsigned long long* slots = static_cast<unsigned long long*>(workspace);
     const int64_t slot_count = static_cast<int64_t>(n) * bs * nslots;
     unsigned* failed = reinterpret_cast<unsigned*>(slots + slot_count);
@@ -1344,10 +1361,13 @@ int launch_fused_split(hipStream_t stream, const float* A, const float* y, const
         const dim3 grid(static_cast<unsigned>((nslots + kSplitWaves - 1) / kSplitWaves), static_cast<unsigned>(c.splits), static_cast<unsigned>(c.nodes));
         const int polls = g_split_polls.load(std::memory_order_relaxed);
         if (narrow)
-            hipLaunchKernelGGL((k_fused_split<4, 3, 2, 1>), grid, dim3(64 * kSplitWaves), 0, stream, A, y, x, fpartial, sq_partial,
+            hipLaunchKernelGGL((k_fused_split<4, 3, 2, 1, 1>), grid, dim3(64 * kSplitWaves), 0, stream, A, y, x, fpartial, sq_partial,
+                               slots, failed, b, d, ldA, ld, c.splits, nslots, node0, polls, rows, bs);
+        else if (two_slots)
+            hipLaunchKernelGGL((k_fused_split<8, 2, 1, 1, 2>), grid, dim3(64 * kSplitWaves), 0, stream, A, y, x, fpartial, sq_partial,
                                slots, failed, b, d, ldA, ld, c.splits, nslots, node0, polls, rows, bs);
         else
-            hipLaunchKernelGGL((k_fused_split<8, 2, 1, 1>), grid, dim3(64 * kSplitWaves), 0, stream, A, y, x, fpartial, sq_partial,
+            hipLaunchKernelGGL((k_fused_split<8, 2, 1, 1, 1>), grid, dim3(64 * kSplitWaves), 0, stream, A, y, x, fpartial, sq_partial,
                                slots, failed, b, d, ldA, ld, c.splits, nslots, node0, polls, rows, bs);
         if (int rc = check_hip(hipGetLastError(), "fused gradient kernel launch (columns split over waves)")) return rc;
         const dim3 grid_ff(static_cast<unsigned>((d + kFinishColumns - 1) / kFinishColumns), static_cast<unsigned>(c.nodes));

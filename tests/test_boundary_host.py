@@ -188,7 +188,7 @@ def test_lsq_workspace_covers_every_smaller_batch():
     """local_grad_lsq_rows runs the kernels on bs <= b rows with a workspace sized for b: the size must not shrink
     when b grows, whichever kernels the shape selects (the row-block count of the single sweep depends on b and d),
     and must hold at least the partial gradients of one row block per node."""
-    for d in (4, 1024, 4096, 8192, 8196, 16384, 20480, 32768, 32772, 40000, 65536, 100000, 131072, 131076):
+    for d in (4, 1024, 4096, 8192, 8196, 16384, 20480, 32768, 32772, 40000, 65536, 100000, 131072, 131076, 262144, 262148):
         for n in (1, 8, 64):
             sizes = [P.local_grad_lsq_workspace(n, b, d) for b in (1, 2, 7, 8, 9, 16, 100, 1024, 4096)]
             assert all(a <= b for a, b in zip(sizes, sizes[1:])), (n, d, sizes)

@@ -213,7 +213,10 @@ LSQ_CASES = [
     (2, 70, 36868, 4, 4, 1.0),           # padded rows, four row blocks of 17 or 18 rows
     (2, 30, 50000, 0, 3, 1.0),           # x and g off the 16-byte grid
     (40, 3, 131072, 0, 0, 1.0),          # more nodes than one launch holds (32 row blocks of 16 workgroups): two launches
-    (1, 12, 131076, 0, 0, 1.0),          # beyond: two sweeps with 16-byte loads, a workgroup per row
+    (1, 12, 131076, 0, 0, 1.0),          # 65 slots: two per lane from here on
+    (2, 20, 200000, 0, 0, 1.0),          # 98 slots
+    (1, 12, 262144, 0, 0, 1.0),          # 128 slots: the widest
+    (1, 6, 262148, 0, 0, 1.0),           # beyond: two sweeps with 16-byte loads, a workgroup per row
     (1, 9, 32770, 2, 2, 1.0),            # d not a multiple of 4 above 32768: two sweeps
     (2, 7, 4099, 1, 3, 1.0),             # few long rows, odd strides: a workgroup per row, 4-byte loads
     (3, 2000, 8196, 0, 0, 1.0),          # many long rows: a wave per row
