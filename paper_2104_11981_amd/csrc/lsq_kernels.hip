@@ -790,7 +790,8 @@ __global__ __launch_bounds__(THREADS) void k_fused_narrow(const float* __restric
 // and multiplies its tile by that residual.  No fence anywhere: a device-wide fence writes back a whole L2, eight of
 // which this chip has.  A slot that has not been written yet holds kSlotEmpty, a NaN whose low mantissa bits no sum
 // of products of fp32 numbers can have (k_fill_slots writes it before every call).  A row's share is published
-// L iterations before it is collected and its loads are issued LA iterations before that.
+// L iterations before it is collected and its loads are issued LA iterations before that.  The row blocks of a node take
+// interleaved rows (see the kernel), so that side by side they move one window through A_i.
 // Measured (fraction of the HBM peak for 4 n b d bytes; the two sweeps: 0.33-0.35): 8 nodes of 1024 x 65536 0.76, 8 of
 // 2048 x 49152 0.78, 8 of 1024 x 57344 0.76, 4 of 1024 x 131072 0.75, 4 of 1024 x 98304 0.73, 2 of 4096 x 100000 0.72,
 // 64 of 128 x 65536 0.69, 16 of 1024 x 36864 0.68 (the four-chunk shape, see split_shape), 8 of 1024 x 33000 0.61; beyond
@@ -809,7 +810,8 @@ __global__ __launch_bounds__(THREADS) void k_fused_narrow(const float* __restric
 // every wait is bounded: a wave that polls max_polls times in vain raises `failed`, stops waiting for the rest of
 // its rows and runs to its end; k_finish_fused then writes NaN for g and loss of that launch's nodes.
 // Two shapes.  Eight 16-byte chunks per lane (2048 columns per wave), two waves per SIMD, L = LA = 1: the faster one where
-// a row is whole workgroups of such waves (multiples of 8192 columns) and the only one beyond 65536 columns (64 slots).
+// a row is whole workgroups of such waves (multiples of 8192 columns) and the only one beyond 65536 columns (a lane reads
+// one slot of a row up to 131072 columns, two up to 262144).
 // Four chunks per lane (1024 columns per wave), three waves per SIMD, L = 2: for the other widths up to 65536, where the
 // first leaves waves idle or half empty (36864 columns 0.55 -> 0.68 of the peak, 40000 0.57 -> 0.66; but 65536 columns
 // 0.75 -> 0.70 and 64 nodes of them 0.69 -> 0.61, hence not everywhere; beyond 65536 columns, with two slots per lane, it
