@@ -321,6 +321,32 @@ def test_local_grad_lsq_matches_oracle(P, oracle, n, b, d, padA, pad, scale):
     assert torch.equal(g2, g)
 
 
+def test_wide_row_sweep_repeats_bit_for_bit_on_a_shared_workspace(P):
+    """Two shapes of more than 32768 columns (both kernel shapes) take turns on one workspace, 40 calls each: the exchange
+    slots of a call lie where the other shape's slots and partial sums lay a moment ago, and every call must mark its
+    own slots empty before its waves read them.  Every call's result equals the first one's bit for bit."""
+    shapes = ((3, 40, 65536), (2, 70, 36868))
+    rng = np.random.default_rng(3)
+    data, first = [], []
+    need = max(P.local_grad_lsq_workspace(*s) for s in shapes)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    for n, b, d in shapes:
+        A = dev(rng.standard_normal((n, b, d)).astype(np.float32))
+        y = dev(rng.standard_normal((n, b)).astype(np.float32))
+        x = dev(rng.standard_normal((n, d)).astype(np.float32))
+        data.append((A, y, x))
+    for it in range(40):
+        for k, (A, y, x) in enumerate(data):
+            g = torch.empty_like(x)
+            loss = torch.empty(x.shape[0], dtype=torch.float32, device="cuda")
+            P.local_grad_lsq(A, y, x, g, loss, 0.01, ws)
+            if it == 0:
+                assert bool(torch.isfinite(g).all()) and bool(torch.isfinite(loss).all())
+                first.append((g, loss))
+            else:
+                assert torch.equal(g, first[k][0]) and torch.equal(loss, first[k][1]), f"call {it} of shape {shapes[k]}"
+
+
 def test_wide_row_sweep_answers_nan_when_its_waves_stop_waiting(P, oracle):
     """Rows of more than 32768 columns: the waves of a row block hand one another their shares of each dot product and
     wait for them, a bounded number of polls.  With the limit at zero a wave that finds a share missing gives up at
