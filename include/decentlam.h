@@ -477,10 +477,11 @@ int dsgd_step(float* x, const float* g,
  * boundaries: 0.8 up to 2048 columns, 0.65-0.75 up to 8192, 0.5-0.65 up to 16384).  Rows of 32772 to 262144 columns
  * (d a multiple of 4, rows of A on 16-byte boundaries) are still read once: the columns of a block of rows are split
  * over waves of several workgroups, which hand one another their shares of each row's dot product through the workspace
- * (8 nodes of 1024 x 65536: 0.35 ms, 0.76 of the peak; other shapes 0.6-0.78, beyond 131072 columns 0.6-0.67).  Those workgroups wait for one another,
- * so a launch is sized to what the chip holds at once and every wait is bounded: should the GPU be kept busy by other
- * work for seconds on end, so that they cannot all run together, the call gives up and leaves NaN in all of g and
- * loss instead of hanging.  Wider rows than these limits take two passes over A at 0.3-0.35 of the peak.  No access
+ * (8 nodes of 1024 x 65536: 0.35 ms, 0.76 of the peak; other shapes 0.6-0.78, beyond 131072 columns 0.6-0.67).
+ * Those workgroups wait for one another, so a launch is sized to what the chip holds at once and every wait is
+ * bounded: should the GPU be kept busy by other work for seconds on end, so that they cannot all run together, the
+ * call gives up and leaves NaN in g and loss (of the nodes of the launch concerned and of those after it) instead
+ * of hanging.  Wider rows than these limits take two passes over A at 0.3-0.35 of the peak.  No access
  * reaches past column d of a row in any case.
  * Products and sums run as fp64 fused multiply-adds on the vector units; the matrix cores are
  * not used: an MFMA tile would have one useful column in sixteen, and for fp32 / fp64 the matrix and
