@@ -184,6 +184,31 @@ def test_gradient_sweep_kernels_do_not_spill(tmp_path):
     assert not any(int(v) for v in re.findall(r"\.vgpr_spill_count:\s+(\d+)", text))
 
 
+def test_wide_row_sweep_exchanges_without_fences_or_barriers(tmp_path):
+    """k_fused_split (rows of more than 32768 columns): what crosses waves is one 8-byte word per wave and row, written
+    and read with device-scope atomic accesses (`sc1` on this chip) -- and nothing else: no cache write-back or
+    invalidate (a device-wide fence writes back a whole L2, of which the chip has eight), no workgroup barrier (the
+    waves of a workgroup share nothing), no spill (248-252 registers in the wide shape, under 170 in the narrow one)."""
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not installed")
+    from paper_2104_11981_amd import build
+
+    out = tmp_path / "lsq_kernels.s"
+    flags = [f for f in build.FLAGS if f != "-fPIC"]
+    subprocess.run([HIPCC] + flags + ["-S", "--cuda-device-only", os.path.join(build.CSRC, "lsq_kernels.hip"), "-o", str(out)],
+                   check=True, capture_output=True)
+    text = out.read_text()
+    for args, most_vgprs in (("8, 2, 1, 1, 1", 256), ("8, 2, 1, 1, 2", 256), ("4, 3, 2, 1, 1", 170)):
+        body = instantiation(text, args, kernel="k_fused_split")
+        assert [i for i in body if i.startswith("global_store_dwordx2") and " sc1" in i], args     # a share published
+        assert [i for i in body if i.startswith("global_load_dwordx2") and " sc1" in i], args      # the shares collected
+        assert not [i for i in body if i.startswith(("buffer_wbl2", "buffer_inv", "s_barrier", "scratch_"))], args
+        assert len([i for i in body if i.startswith("global_load_dwordx4")]) >= int(args[0]), args   # the tile: 16-byte loads
+        used = {int(v) for i in body for v in re.findall(r"\bv(\d+)\b", i)} | \
+               {int(hi) for i in body for hi in re.findall(r"\bv\[\d+:(\d+)\]", i)}
+        assert max(used) < most_vgprs, (args, max(used))
+
+
 SPLIT_CHECK = r"""
 #include <cstdio>
 #include <vector>
